@@ -1,0 +1,420 @@
+"""CPU oracle of the ZeroQAT zeroth-order QAT step -- TEST INFRASTRUCTURE ONLY.
+
+Python face of ``zo_oracle.c`` (element-level definitions, fp32 where an integer
+code is decided) plus the model-level forward written with numpy in fp64.  Only
+``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py``
+may import this module.  It imports nothing from the HIP package.
+
+Paper passages followed:
+  * uniform quantizer ................ Background, "Quantization" equation
+  * group-wise / per-token ........... Appendix "Quantization settings"
+  * two-point estimate, q = 1 ........ Eq. (2)
+  * ZO-SGD update .................... Eq. (3)
+  * lightweight variant .............. Section "Lightweight ZeroQAT" (frozen, pre-quantized
+                                       weights; Q and V projections stay trainable)
+The transformer around the quantized linears is not defined by the paper; it is the
+standard pre-norm decoder named by the benchmark configurations (parity unpinned
+beyond the library cross-check in the tests).
+"""
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "zo_oracle.c")
+_LIB = os.path.join(_HERE, "libzo_oracle.so")
+
+CFLAGS = ["-O2", "-std=c11", "-ffp-contract=off", "-mfma", "-mavx2", "-fopenmp", "-fPIC", "-shared"]
+
+
+def build(force=False):
+    """Compile zo_oracle.c with gcc (no-op if the library is newer than the source)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", *CFLAGS, "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = C.CDLL(build())
+
+_u32p = np.ctypeslib.ndpointer(np.uint32, flags="C_CONTIGUOUS")
+_i32p = np.ctypeslib.ndpointer(np.int32, flags="C_CONTIGUOUS")
+_f32p = np.ctypeslib.ndpointer(np.float32, flags="C_CONTIGUOUS")
+_f64p = np.ctypeslib.ndpointer(np.float64, flags="C_CONTIGUOUS")
+
+
+def _opt(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+_lib.zo_or_philox4x32_10.argtypes = [_u32p, _u32p, _u32p]
+_lib.zo_or_philox_words.argtypes = [C.c_uint64, C.c_int32, C.c_int64, _u32p]
+_lib.zo_or_word_to_normals.argtypes = [C.c_uint32, _f32p]
+_lib.zo_or_z.argtypes = [C.c_uint64, C.c_int32, C.c_int64]
+_lib.zo_or_z.restype = C.c_float
+_lib.zo_or_normal.argtypes = [C.c_uint64, C.c_int32, C.c_int64, C.c_int64, _f32p]
+_lib.zo_or_bf16_round_array.argtypes = [_f32p, C.c_int64, _f32p]
+_lib.zo_or_perturb.argtypes = [_f32p, C.c_int64, C.c_uint64, C.c_int32, C.c_float, _f32p]
+_lib.zo_or_quant_group.argtypes = [_f32p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                   C.c_void_p, C.c_void_p]
+_lib.zo_or_fakequant_weight.argtypes = [_f32p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_uint64, C.c_int32,
+                                        C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+_lib.zo_or_fakequant_act.argtypes = [_f32p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+_lib.zo_or_linear.argtypes = [_f32p, _f32p, C.c_void_p, C.c_int, C.c_int, C.c_int, _f64p]
+_lib.zo_or_projected_grad.argtypes = [C.c_float, C.c_float, C.c_float]
+_lib.zo_or_projected_grad.restype = C.c_float
+_lib.zo_or_coeff.argtypes = [C.c_float, C.c_float]
+_lib.zo_or_coeff.restype = C.c_float
+_lib.zo_or_update.argtypes = [_f32p, C.c_int64, C.c_uint64, C.c_int32, C.c_float]
+
+
+# ----------------------------------------------------------------------------
+# element-level definitions (thin wrappers over the C file)
+# ----------------------------------------------------------------------------
+def philox4x32_10(ctr, key):
+    out = np.empty(4, np.uint32)
+    _lib.zo_or_philox4x32_10(np.asarray(ctr, np.uint32), np.asarray(key, np.uint32), out)
+    return out
+
+
+def philox_words(seed, tensor_id, nwords):
+    out = np.empty(nwords, np.uint32)
+    _lib.zo_or_philox_words(seed, tensor_id, nwords, out)
+    return out
+
+
+def word_to_normals(word):
+    out = np.empty(2, np.float32)
+    _lib.zo_or_word_to_normals(int(word), out)
+    return out
+
+
+def z_at(seed, tensor_id, i):
+    return np.float32(_lib.zo_or_z(seed, tensor_id, i))
+
+
+def normal(seed, tensor_id, n, start=0):
+    out = np.empty(n, np.float32)
+    _lib.zo_or_normal(seed, tensor_id, start, n, out)
+    return out
+
+
+def bf16_round(x):
+    x = np.ascontiguousarray(x, np.float32)
+    out = np.empty_like(x)
+    _lib.zo_or_bf16_round_array(x.reshape(-1), x.size, out.reshape(-1))
+    return out
+
+
+def perturb(w, seed, tensor_id, eps_signed):
+    """theta' = fma(eps_signed, z, theta) in fp32 (argument of Q in Eq. 2)."""
+    w = np.ascontiguousarray(w, np.float32)
+    out = np.empty_like(w)
+    _lib.zo_or_perturb(w.reshape(-1), w.size, seed, tensor_id, eps_signed, out.reshape(-1))
+    return out
+
+
+def quant_group(x, bits, sym=False):
+    """One group through the uniform quantizer: (step, zero_point, codes, dequantized)."""
+    x = np.ascontiguousarray(x, np.float32).reshape(-1)
+    step = np.empty(1, np.float32)
+    zp = np.empty(1, np.int32)
+    codes = np.empty(x.size, np.int32)
+    xhat = np.empty(x.size, np.float32)
+    _lib.zo_or_quant_group(x, x.size, bits, int(sym), _opt(step), _opt(zp), _opt(codes), _opt(xhat))
+    return step[0], int(zp[0]), codes, xhat
+
+
+def fakequant_weight(W, bits, group, seed=0, tensor_id=0, eps_signed=0.0, round_bf16=False, want_codes=True):
+    """Q(W + eps_signed*z) per group of `group` consecutive in-features (Eq. 2's Q for a linear).
+
+    Returns dict(codes[N,K] int32, step[N,K/group], zp[N,K/group] int32, what[N,K] fp32)."""
+    W = np.ascontiguousarray(W, np.float32)
+    N, K = W.shape
+    if bits:
+        if group == 0:
+            group = K
+        assert K % group == 0
+    G = K // group if bits else 0
+    codes = np.empty((N, K), np.int32) if (bits and want_codes) else None
+    step = np.empty((N, G), np.float32) if bits else None
+    zp = np.empty((N, G), np.int32) if bits else None
+    what = np.empty((N, K), np.float32)
+    _lib.zo_or_fakequant_weight(W, N, K, bits, group, seed, tensor_id, eps_signed, int(round_bf16),
+                                _opt(codes), _opt(step), _opt(zp), _opt(what))
+    return dict(codes=codes, step=step, zp=zp, what=what)
+
+
+def fakequant_act(X, bits, sym=False, round_bf16=False, want_codes=True):
+    """Per-token quantizer: every row of X[M,K] is one group."""
+    X = np.ascontiguousarray(X, np.float32)
+    M, K = X.shape
+    q = bits < 16
+    codes = np.empty((M, K), np.int32) if (q and want_codes) else None
+    step = np.empty(M, np.float32) if q else None
+    zp = np.empty(M, np.int32) if q else None
+    xhat = np.empty((M, K), np.float32)
+    _lib.zo_or_fakequant_act(X, M, K, bits, int(sym), int(round_bf16), _opt(codes), _opt(step), _opt(zp), _opt(xhat))
+    return dict(codes=codes, step=step, zp=zp, xhat=xhat)
+
+
+def linear(xhat, what, bias=None):
+    """y = x^ w^T + bias with fp64 accumulation (plain triple loop in C)."""
+    xhat = np.ascontiguousarray(xhat, np.float32)
+    what = np.ascontiguousarray(what, np.float32)
+    M, K = xhat.shape
+    N = what.shape[0]
+    y = np.empty((M, N), np.float64)
+    b = None if bias is None else np.ascontiguousarray(bias, np.float32)
+    _lib.zo_or_linear(xhat, what, _opt(b), M, N, K, y)
+    return y
+
+
+def projected_grad(loss_plus, loss_minus, eps):
+    return np.float32(_lib.zo_or_projected_grad(loss_plus, loss_minus, eps))
+
+
+def coeff(lr, g):
+    return np.float32(_lib.zo_or_coeff(lr, g))
+
+
+def update(w, seed, tensor_id, c):
+    """In place: w <- fma(-c, z, w) (Eq. 3)."""
+    assert w.dtype == np.float32 and w.flags.c_contiguous
+    _lib.zo_or_update(w.reshape(-1), w.size, seed, tensor_id, c)
+    return w
+
+
+# ----------------------------------------------------------------------------
+# model-level forward (numpy, fp64 inside every operation)
+# ----------------------------------------------------------------------------
+ARCH_LINEAR, ARCH_LLAMA, ARCH_OPT = 0, 1, 2
+
+
+class Config:
+    """Mirror of the library's configuration record (field meaning identical)."""
+
+    def __init__(self, arch, n_layers=0, d_model=0, n_heads=1, d_ffn=0, vocab=0, max_seq=0,
+                 w_bits=4, w_group=64, a_bits=16, a_sym=0, act_dtype=0, lightweight=0):
+        self.arch, self.n_layers, self.d_model, self.n_heads = arch, n_layers, d_model, n_heads
+        self.d_ffn, self.vocab, self.max_seq = d_ffn, vocab, max_seq
+        self.w_bits, self.w_group, self.a_bits, self.a_sym = w_bits, w_group, a_bits, a_sym
+        self.act_dtype, self.lightweight = act_dtype, lightweight
+
+
+def param_shapes(cfg):
+    """Ordered (name, shape, quantized?) of the trainable tensors; index = tensor id."""
+    d, f, V = cfg.d_model, cfg.d_ffn, cfg.vocab
+    if cfg.arch == ARCH_LINEAR:
+        return [("w", (f, d), True)]
+    out = [("tok_emb", (V, d), False)]
+    if cfg.arch == ARCH_OPT:
+        out.append(("pos_emb", (cfg.max_seq, d), False))
+    for l in range(cfg.n_layers):
+        p = "l%d." % l
+        if cfg.arch == ARCH_LLAMA:
+            out += [(p + "attn_norm", (d,), False), (p + "wq", (d, d), True), (p + "wk", (d, d), True),
+                    (p + "wv", (d, d), True), (p + "wo", (d, d), True), (p + "ffn_norm", (d,), False),
+                    (p + "w_gate", (f, d), True), (p + "w_up", (f, d), True), (p + "w_down", (d, f), True)]
+        else:
+            out += [(p + "ln1_g", (d,), False), (p + "ln1_b", (d,), False),
+                    (p + "wq", (d, d), True), (p + "bq", (d,), False), (p + "wk", (d, d), True), (p + "bk", (d,), False),
+                    (p + "wv", (d, d), True), (p + "bv", (d,), False), (p + "wo", (d, d), True), (p + "bo", (d,), False),
+                    (p + "ln2_g", (d,), False), (p + "ln2_b", (d,), False),
+                    (p + "fc1", (f, d), True), (p + "b1", (f,), False), (p + "fc2", (d, f), True), (p + "b2", (d,), False)]
+    if cfg.arch == ARCH_LLAMA:
+        out += [("final_norm", (d,), False), ("lm_head", (V, d), False)]
+    else:
+        out += [("final_ln_g", (d,), False), ("final_ln_b", (d,), False), ("lm_head", (V, d), False)]
+    return out
+
+
+def _rt(cfg, a):
+    """Round to the storage type of activations (bf16 in bf16 mode, fp32 otherwise)."""
+    a32 = np.asarray(a, np.float64).astype(np.float32)
+    return bf16_round(a32) if cfg.act_dtype == 1 else a32
+
+
+class _Params:
+    """Perturbed view of the parameter list: theta'_i = fma(eps_signed, z, theta_i)."""
+
+    def __init__(self, cfg, params, seed, eps_signed, trainable=None):
+        self.cfg, self.params, self.seed, self.eps = cfg, params, seed, np.float32(eps_signed)
+        self.index = {name: i for i, (name, _, _) in enumerate(param_shapes(cfg))}
+        self.trainable = trainable
+
+    def _eps_for(self, i):
+        if self.trainable is not None and not self.trainable[i]:
+            return np.float32(0.0)
+        return self.eps
+
+    def plain(self, name):
+        """Perturbed, un-quantized fp32 tensor (norm gains, biases, embeddings)."""
+        i = self.index[name]
+        return perturb(self.params[i], self.seed, i, self._eps_for(i))
+
+    def lm_head(self, name):
+        """Perturbed un-quantized matrix, rounded to the GEMM operand type."""
+        i = self.index[name]
+        return fakequant_weight(self.params[i], 0, 0, self.seed, i, self._eps_for(i),
+                                round_bf16=(self.cfg.act_dtype == 1), want_codes=False)["what"]
+
+    def qweight(self, name):
+        """Q(W + eps z) of a quantized linear, de-quantized, in the GEMM operand type."""
+        i = self.index[name]
+        cfg = self.cfg
+        return fakequant_weight(self.params[i], cfg.w_bits, cfg.w_group, self.seed, i, self._eps_for(i),
+                                round_bf16=(cfg.act_dtype == 1), want_codes=False)["what"]
+
+
+def _qlinear(cfg, x, what, bias=None, residual=None, relu=False):
+    """Quantized linear: per-token Q_A on the stored input, then x^ w^T (+bias)(+relu)(+residual)."""
+    xq = fakequant_act(x, cfg.a_bits, cfg.a_sym, round_bf16=(cfg.act_dtype == 1), want_codes=False)["xhat"]
+    y = xq.astype(np.float64) @ what.astype(np.float64).T
+    if bias is not None:
+        y = y + bias.astype(np.float64)
+    if relu:
+        y = np.maximum(y, 0.0)
+    if residual is not None:
+        y = y + residual.astype(np.float64)
+    return _rt(cfg, y)
+
+
+def _rmsnorm(x, g, eps=1e-5):
+    x = x.astype(np.float64)
+    return x / np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + eps) * g.astype(np.float64)
+
+
+def _layernorm(x, g, b, eps=1e-5):
+    x = x.astype(np.float64)
+    mu = x.mean(-1, keepdims=True)
+    var = ((x - mu) ** 2).mean(-1, keepdims=True)
+    return (x - mu) / np.sqrt(var + eps) * g.astype(np.float64) + b.astype(np.float64)
+
+
+def rope_table(S, dh, theta=10000.0):
+    """cos/sin of pos * theta^(-2i/dh), i < dh/2, rounded to fp32 (a constant table of the model)."""
+    i = np.arange(dh // 2, dtype=np.float64)
+    ang = np.arange(S, dtype=np.float64)[:, None] * theta ** (-2.0 * i / dh)[None, :]
+    return np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+
+
+def _rope(x, B, S, H, dh):
+    """Rotate pairs (i, i + dh/2) of every head by the position angle."""
+    cos, sin = rope_table(S, dh)
+    x = x.astype(np.float64).reshape(B, S, H, dh)
+    x1, x2 = x[..., : dh // 2], x[..., dh // 2:]
+    c = cos.astype(np.float64)[None, :, None, :]
+    s = sin.astype(np.float64)[None, :, None, :]
+    return np.concatenate([x1 * c - x2 * s, x2 * c + x1 * s], -1).reshape(B * S, H * dh)
+
+
+def _attention(q, k, v, B, S, H, dh):
+    """Causal softmax attention, scale 1/sqrt(dh), fp64."""
+    q = q.astype(np.float64).reshape(B, S, H, dh).transpose(0, 2, 1, 3)
+    k = k.astype(np.float64).reshape(B, S, H, dh).transpose(0, 2, 1, 3)
+    v = v.astype(np.float64).reshape(B, S, H, dh).transpose(0, 2, 1, 3)
+    s = q @ k.transpose(0, 1, 3, 2) / np.sqrt(dh)
+    mask = np.triu(np.ones((S, S), bool), 1)
+    s = np.where(mask, -np.inf, s)
+    s = s - s.max(-1, keepdims=True)
+    p = np.exp(s)
+    p = p / p.sum(-1, keepdims=True)
+    return (p @ v).transpose(0, 2, 1, 3).reshape(B * S, H * dh)
+
+
+def cross_entropy(logits, ids, B, S):
+    """Mean over the B*(S-1) next-token positions of logsumexp(logits) - logits[target]."""
+    V = logits.shape[-1]
+    lg = logits.astype(np.float64).reshape(B, S, V)[:, :-1, :]
+    tgt = np.asarray(ids).reshape(B, S)[:, 1:]
+    mx = lg.max(-1, keepdims=True)
+    lse = np.log(np.exp(lg - mx).sum(-1)) + mx[..., 0]
+    picked = np.take_along_axis(lg, tgt[..., None], -1)[..., 0]
+    return np.float32((lse - picked).mean())
+
+
+def forward(cfg, params, ids=None, x=None, target=None, seed=0, eps_signed=0.0, trainable=None, trace=None):
+    """One quantized forward at W + eps_signed * z; returns the fp32 loss.
+
+    arch 0: x[M,K] fp32 input, target[M,N]; loss = mean squared error.
+    arch 1/2: ids[B,S]; loss = next-token cross entropy.
+    `trace`, if a dict, receives the stored activations by name."""
+    P = _Params(cfg, params, seed, eps_signed, trainable)
+
+    def keep(name, val):
+        if trace is not None:
+            trace[name] = val
+        return val
+
+    if cfg.arch == ARCH_LINEAR:
+        y = _qlinear(cfg, _rt(cfg, x), P.qweight("w"))
+        keep("y", y)
+        return np.float32(np.mean((y.astype(np.float64) - np.asarray(target, np.float64)) ** 2))
+
+    B, S = np.asarray(ids).shape
+    d, H = cfg.d_model, cfg.n_heads
+    dh = d // H
+    flat = np.asarray(ids).reshape(-1)
+    emb = P.plain("tok_emb")
+    if cfg.arch == ARCH_OPT:
+        pos = P.plain("pos_emb")
+        xres = _rt(cfg, emb[flat].astype(np.float64) + np.tile(pos[:S], (B, 1)).astype(np.float64))
+    else:
+        xres = _rt(cfg, emb[flat])
+    keep("x0", xres)
+    for l in range(cfg.n_layers):
+        p = "l%d." % l
+        if cfg.arch == ARCH_LLAMA:
+            h = _rt(cfg, _rmsnorm(xres, P.plain(p + "attn_norm")))
+            q = _qlinear(cfg, h, P.qweight(p + "wq"))
+            k = _qlinear(cfg, h, P.qweight(p + "wk"))
+            v = _qlinear(cfg, h, P.qweight(p + "wv"))
+            q = _rt(cfg, _rope(q, B, S, H, dh))
+            k = _rt(cfg, _rope(k, B, S, H, dh))
+            a = _rt(cfg, _attention(q, k, v, B, S, H, dh))
+            xres = _qlinear(cfg, a, P.qweight(p + "wo"), residual=xres)
+            keep(p + "attn_out", xres)
+            h = _rt(cfg, _rmsnorm(xres, P.plain(p + "ffn_norm")))
+            gate = _qlinear(cfg, h, P.qweight(p + "w_gate"))
+            up = _qlinear(cfg, h, P.qweight(p + "w_up"))
+            g64 = gate.astype(np.float64)
+            act = _rt(cfg, g64 / (1.0 + np.exp(-g64)) * up.astype(np.float64))
+            xres = _qlinear(cfg, act, P.qweight(p + "w_down"), residual=xres)
+        else:
+            h = _rt(cfg, _layernorm(xres, P.plain(p + "ln1_g"), P.plain(p + "ln1_b")))
+            q = _qlinear(cfg, h, P.qweight(p + "wq"), P.plain(p + "bq"))
+            k = _qlinear(cfg, h, P.qweight(p + "wk"), P.plain(p + "bk"))
+            v = _qlinear(cfg, h, P.qweight(p + "wv"), P.plain(p + "bv"))
+            a = _rt(cfg, _attention(q, k, v, B, S, H, dh))
+            xres = _qlinear(cfg, a, P.qweight(p + "wo"), P.plain(p + "bo"), residual=xres)
+            keep(p + "attn_out", xres)
+            h = _rt(cfg, _layernorm(xres, P.plain(p + "ln2_g"), P.plain(p + "ln2_b")))
+            f = _qlinear(cfg, h, P.qweight(p + "fc1"), P.plain(p + "b1"), relu=True)
+            xres = _qlinear(cfg, f, P.qweight(p + "fc2"), P.plain(p + "b2"), residual=xres)
+        keep(p + "out", xres)
+    if cfg.arch == ARCH_LLAMA:
+        hf = _rt(cfg, _rmsnorm(xres, P.plain("final_norm")))
+    else:
+        hf = _rt(cfg, _layernorm(xres, P.plain("final_ln_g"), P.plain("final_ln_b")))
+    keep("final", hf)
+    logits = hf.astype(np.float64) @ P.lm_head("lm_head").astype(np.float64).T
+    keep("logits", logits)
+    return cross_entropy(logits, ids, B, S)
+
+
+def zo_step(cfg, params, seed, eps, lr, ids=None, x=None, target=None, trainable=None):
+    """One ZO-SGD step (Eq. 2 with q = 1, then Eq. 3), updating `params` in place.
+
+    Returns (L+, L-, g) as fp32."""
+    eps = np.float32(eps)
+    lp = forward(cfg, params, ids, x, target, seed, eps, trainable)
+    lm = forward(cfg, params, ids, x, target, seed, -eps, trainable)
+    g = projected_grad(lp, lm, eps)
+    c = coeff(np.float32(lr), g)
+    for i, w in enumerate(params):
+        if trainable is None or trainable[i]:
+            update(w, seed, i, c)
+    return lp, lm, g
