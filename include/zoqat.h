@@ -1,0 +1,172 @@
+/*
+ * zoqat.h -- C ABI of the MI355X (gfx950) library for one zeroth-order quantization-aware
+ * training step of ZeroQAT:
+ *
+ *     draw u ~ N(0, I) from a seed                          (Eq. 2; never stored)
+ *     L+ = L(Q(W + eps u)),  L- = L(Q(W - eps u))           (Eq. 2, two quantized forwards)
+ *     g  = (L+ - L-) / (2 eps)                              (Eq. 2 with q = 1)
+ *     W <- W - eta g u                                      (Eq. 3, full-precision masters)
+ *
+ * Q is the uniform asymmetric quantizer of the Background section applied per group of
+ * `w_group` consecutive input features of every quantized linear layer; activations entering a
+ * quantized linear are quantized per token (Appendix "Quantization settings").
+ *
+ * Conventions
+ *   - plain C, no exceptions; every call returns a zo_status (ZO_OK = 0);
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are host addresses;
+ *   - the caller owns every device buffer (master weights, workspace, ids, outputs); the library
+ *     never allocates or frees device memory, and it launches all work asynchronously on the
+ *     hipStream_t given at zo_init / in the call (passed as void*); it never synchronises;
+ *   - matrices are row-major; a linear weight is W[N][K] (N outputs, K inputs, K contiguous) and
+ *     Y[M][N] = X[M][K] * W^T;
+ *   - element i (flat, row-major) of tensor number t under seed s always receives the same
+ *     perturbation u(s, t, i), whichever call or kernel asks for it;
+ *   - device pointers must be 16-byte aligned; K must be a multiple of 8 and of the group size.
+ *   - one context per stream; a context is not thread-safe.
+ */
+#ifndef ZOQAT_H
+#define ZOQAT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ZO_OK = 0,
+    ZO_EINVAL = 1,        /* null pointer, negative size, unknown enum value */
+    ZO_ESHAPE = 2,        /* a dimension violates a divisibility / size rule */
+    ZO_EALIGN = 3,        /* device pointer not 16-byte aligned */
+    ZO_EHIP = 4,          /* a HIP call failed; see zo_last_error */
+    ZO_EUNSUPPORTED = 5,  /* valid request this build cannot run */
+    ZO_EWORKSPACE = 6     /* workspace smaller than zo_workspace_bytes */
+} zo_status;
+
+enum { ZO_ARCH_LINEAR = 0, ZO_ARCH_LLAMA = 1, ZO_ARCH_OPT = 2 };
+enum { ZO_ACT_FP32 = 0, ZO_ACT_BF16 = 1 };
+
+/* Model and quantization setting ("WxAy gN" of the appendix: w_bits, a_bits, w_group). */
+typedef struct {
+    int32_t arch;        /* ZO_ARCH_*: single linear (d_model inputs -> d_ffn outputs, MSE loss),
+                            Llama-shaped (RMSNorm, RoPE, SwiGLU, no biases), OPT-shaped (LayerNorm,
+                            learned positions, ReLU, biases); decoders use next-token cross entropy */
+    int32_t n_layers, d_model, n_heads, d_ffn, vocab, max_seq;
+    int32_t w_bits;      /* weight bits of the quantized linears, 1..8; 0 = no weight quantization */
+    int32_t w_group;     /* group size along K; 0 = per output channel */
+    int32_t a_bits;      /* activation bits, 2..8; 16 = activations not quantized */
+    int32_t a_sym;       /* 0 = asymmetric min/max (the paper's choice), 1 = symmetric absmax */
+    int32_t act_dtype;   /* ZO_ACT_*: storage type of activations and GEMM operands */
+    int32_t lightweight; /* 0 = every tensor trainable; 1 = only tensors whose zo_tensor.trainable
+                            is set are perturbed and updated (lightweight variant) */
+    int32_t reserved[3];
+} zo_config;
+
+/* One parameter tensor.  The array given to zo_init lists them in the fixed order below; the
+ * position in the array is the tensor number used by the perturbation stream.
+ *   linear:  W[d_ffn][d_model]
+ *   llama:   tok_emb[V][d]; per layer: attn_norm[d], wq, wk, wv, wo [d][d], ffn_norm[d],
+ *            w_gate[f][d], w_up[f][d], w_down[d][f]; then final_norm[d], lm_head[V][d]
+ *   opt:     tok_emb[V][d], pos_emb[max_seq][d]; per layer: ln1_g, ln1_b, wq, bq, wk, bk, wv, bv,
+ *            wo, bo, ln2_g, ln2_b, fc1[f][d], b1[f], fc2[d][f], b2[d]; then final_ln_g,
+ *            final_ln_b, lm_head[V][d]                                                       */
+typedef struct {
+    void*   ptr;        /* dev, fp32 master weights, updated in place by zo_update / zo_step */
+    int64_t numel;
+    int32_t trainable;  /* used only when zo_config.lightweight = 1 */
+    int32_t reserved;
+} zo_tensor;
+
+typedef struct zo_ctx zo_ctx;
+
+/* Number of parameter tensors the configuration expects (0 if the configuration is invalid). */
+int32_t zo_num_params(const zo_config* cfg);
+/* Element count of parameter tensor `index` (-1 if out of range). */
+int64_t zo_param_numel(const zo_config* cfg, int32_t index);
+
+/* Bytes of device workspace a context needs to run B x S tokens (B rows for the linear arch). */
+size_t zo_workspace_bytes(const zo_config* cfg, int32_t B, int32_t S);
+
+/* Create a context.  `params` (host array) is copied; the tensors stay owned by the caller.
+ * `workspace` (dev) must hold zo_workspace_bytes(cfg, max_B, max_S) bytes and stay valid until
+ * zo_destroy.  Constant tables (rotary angles) are written into the workspace on `hip_stream`. */
+zo_status zo_init(const zo_config* cfg, const zo_tensor* params, int32_t n_params,
+                  void* workspace, size_t workspace_bytes, int32_t max_B, int32_t max_S,
+                  void* hip_stream, zo_ctx** out);
+zo_status zo_destroy(zo_ctx* ctx);
+/* Text of the last error of this context (host string owned by the context). */
+const char* zo_last_error(const zo_ctx* ctx);
+
+/* One quantized forward at W + eps_signed * u(seed): L(Q(W + eps_signed u); batch) of Eq. 2.
+ *   ids      dev int32 [B][S] token ids (decoders); for the linear arch: dev input X[B][d_model]
+ *            in the activation storage type
+ *   target   dev fp32 [B][d_ffn] regression target (linear arch only, else NULL)
+ *   loss_dev dev fp32[1], written asynchronously
+ * eps_signed = +eps, -eps, or 0 for the unperturbed quantized model. */
+zo_status zo_forward_quant(zo_ctx* ctx, const void* ids, const float* target, int32_t B, int32_t S,
+                           uint64_t seed, float eps_signed, float* loss_dev);
+
+/* One full step: both forwards of Eq. 2 (sharing one pass over the weights), the projected
+ * gradient, and the update of Eq. 3.  out_dev: dev fp32[4] = { L+, L-, g, eta*g }. */
+zo_status zo_step(zo_ctx* ctx, const void* ids, const float* target, int32_t B, int32_t S,
+                  uint64_t seed, float eps, float lr, float* out_dev);
+
+/* Update of Eq. 3 alone: w_i <- w_i - c * u(seed, tensor, i) over every trainable tensor.
+ * c is read from coeff_dev (dev fp32[1]) if non-NULL, else coeff_host is used. */
+zo_status zo_update(zo_ctx* ctx, uint64_t seed, const float* coeff_dev, float coeff_host);
+
+/* ---- stand-alone pieces of the path (same device code as the step), for tests and benches ---- */
+
+/* out[j] = word (j & 3) of Philox4x32-10 block (j >> 2) of the stream (seed, tensor_id). */
+zo_status zo_debug_philox_u32(uint64_t seed, int32_t tensor_id, int64_t nwords, uint32_t* out_dev, void* hip_stream);
+/* out[i] = u(seed, tensor_id, start + i), i < numel: the perturbation of Eq. 2. */
+zo_status zo_debug_normal(uint64_t seed, int32_t tensor_id, int64_t start, int64_t numel, float* out_dev, void* hip_stream);
+
+/* Seeded in-place update of one tensor (Eq. 3): w_i <- w_i - c * u(seed, tensor_id, i). */
+zo_status zo_update_tensor(float* w_dev, int64_t numel, uint64_t seed, int32_t tensor_id,
+                           const float* coeff_dev, float coeff_host, void* hip_stream);
+
+/* Q(W + eps_signed u) of one weight matrix W[N][K] (Eq. 2's argument of L for one linear):
+ * perturb, group min/max, quantize, de-quantize.  bits = 0: perturb only.  Outputs (any may be
+ * NULL): codes u8 [N][K]; step fp32 and zp int32 [N][K/group]; what [N][K] de-quantized weights in
+ * storage type out_dtype (ZO_ACT_*).  group = 0 means K. */
+zo_status zo_debug_quant_weight(const float* W_dev, int32_t N, int32_t K, int32_t bits, int32_t group,
+                                uint64_t seed, int32_t tensor_id, float eps_signed, int32_t out_dtype,
+                                uint8_t* codes_dev, float* step_dev, int32_t* zp_dev, void* what_dev,
+                                void* hip_stream);
+
+/* Per-token quantizer of the input of a quantized linear: every row of X[M][K] (storage type
+ * dtype) is one group.  Outputs (any may be NULL): codes int16 [M][K], step fp32 [M], zp int32 [M],
+ * xhat [M][K] de-quantized in the same storage type. */
+zo_status zo_debug_quant_act(const void* X_dev, int32_t M, int32_t K, int32_t bits, int32_t sym, int32_t dtype,
+                             int16_t* codes_dev, float* step_dev, int32_t* zp_dev, void* xhat_dev,
+                             void* hip_stream);
+
+/* One fake-quantized linear layer: Y = Q_A(X) * Q(W + eps_signed u)^T (+ bias).
+ *   X  dev [M][K] storage type dtype;  W dev fp32 [N][K];  bias dev fp32 [N] or NULL (not perturbed)
+ *   Y  dev [M][N] storage type dtype
+ *   scratch dev, at least zo_linear_scratch_bytes(M, N, K, dtype) bytes */
+size_t zo_linear_scratch_bytes(int32_t M, int32_t N, int32_t K, int32_t dtype);
+zo_status zo_linear_fakequant(const void* X_dev, const float* W_dev, const float* bias_dev, void* Y_dev,
+                              int32_t M, int32_t N, int32_t K, int32_t w_bits, int32_t w_group,
+                              int32_t a_bits, int32_t a_sym, int32_t dtype,
+                              uint64_t seed, int32_t tensor_id, float eps_signed,
+                              void* scratch_dev, void* hip_stream);
+
+/* Plain GEMM of the path, Y[M][N] = X[M][K] * W[N][K]^T with fp32 accumulation, operands and
+ * output in storage type dtype (the contraction every quantized linear runs after both operands
+ * have been de-quantized).  Exposed for roofline measurement and parity. */
+zo_status zo_gemm_nt(const void* X_dev, const void* W_dev, void* Y_dev, int32_t M, int32_t N, int32_t K,
+                     int32_t dtype, void* hip_stream);
+
+/* Device buffers of the context's last forward, for layer-level parity tests.
+ * which: 0 = final hidden state [M][d], 1 = logits fp32 [M][V] (linear arch: output Y [M][N]),
+ *        2 = residual stream after the last layer [M][d].  branch: 0 = '+' (or the single
+ * forward), 1 = '-'.  Returns the dev pointer in *ptr and its size in *bytes. */
+zo_status zo_debug_buffer(zo_ctx* ctx, int32_t which, int32_t branch, void** ptr, size_t* bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZOQAT_H */

@@ -269,9 +269,19 @@ class _Params:
                                 round_bf16=(cfg.act_dtype == 1), want_codes=False)["what"]
 
 
-def _qlinear(cfg, x, what, bias=None, residual=None, relu=False):
+def _tie_margin(x, step):
+    """Per row: distance (in code units) of the closest element to a rounding boundary of
+    round(x / step).  A test uses it to know where a last-bit difference in x may flip a code."""
+    t = np.asarray(x, np.float32) * (np.float32(1.0) / step.astype(np.float32))[:, None]
+    return np.abs(np.abs(t - np.floor(t)) - np.float32(0.5)).min(axis=1)
+
+
+def _qlinear(cfg, x, what, bias=None, residual=None, relu=False, tie_log=None):
     """Quantized linear: per-token Q_A on the stored input, then x^ w^T (+bias)(+relu)(+residual)."""
-    xq = fakequant_act(x, cfg.a_bits, cfg.a_sym, round_bf16=(cfg.act_dtype == 1), want_codes=False)["xhat"]
+    qa = fakequant_act(x, cfg.a_bits, cfg.a_sym, round_bf16=(cfg.act_dtype == 1), want_codes=False)
+    xq = qa["xhat"]
+    if tie_log is not None and cfg.a_bits < 16:
+        tie_log.append(_tie_margin(x, qa["step"]))
     y = xq.astype(np.float64) @ what.astype(np.float64).T
     if bias is not None:
         y = y + bias.astype(np.float64)
@@ -336,12 +346,14 @@ def cross_entropy(logits, ids, B, S):
     return np.float32((lse - picked).mean())
 
 
-def forward(cfg, params, ids=None, x=None, target=None, seed=0, eps_signed=0.0, trainable=None, trace=None):
+def forward(cfg, params, ids=None, x=None, target=None, seed=0, eps_signed=0.0, trainable=None, trace=None,
+            tie_log=None):
     """One quantized forward at W + eps_signed * z; returns the fp32 loss.
 
     arch 0: x[M,K] fp32 input, target[M,N]; loss = mean squared error.
     arch 1/2: ids[B,S]; loss = next-token cross entropy.
-    `trace`, if a dict, receives the stored activations by name."""
+    `trace`, if a dict, receives the stored activations by name; `tie_log`, if a list, receives
+    for every activation-quantizer call the per-row margin to the nearest rounding boundary."""
     P = _Params(cfg, params, seed, eps_signed, trainable)
 
     def keep(name, val):
@@ -350,7 +362,7 @@ def forward(cfg, params, ids=None, x=None, target=None, seed=0, eps_signed=0.0, 
         return val
 
     if cfg.arch == ARCH_LINEAR:
-        y = _qlinear(cfg, _rt(cfg, x), P.qweight("w"))
+        y = _qlinear(cfg, _rt(cfg, x), P.qweight("w"), tie_log=tie_log)
         keep("y", y)
         return np.float32(np.mean((y.astype(np.float64) - np.asarray(target, np.float64)) ** 2))
 
@@ -369,31 +381,31 @@ def forward(cfg, params, ids=None, x=None, target=None, seed=0, eps_signed=0.0, 
         p = "l%d." % l
         if cfg.arch == ARCH_LLAMA:
             h = _rt(cfg, _rmsnorm(xres, P.plain(p + "attn_norm")))
-            q = _qlinear(cfg, h, P.qweight(p + "wq"))
-            k = _qlinear(cfg, h, P.qweight(p + "wk"))
-            v = _qlinear(cfg, h, P.qweight(p + "wv"))
+            q = _qlinear(cfg, h, P.qweight(p + "wq"), tie_log=tie_log)
+            k = _qlinear(cfg, h, P.qweight(p + "wk"), tie_log=tie_log)
+            v = _qlinear(cfg, h, P.qweight(p + "wv"), tie_log=tie_log)
             q = _rt(cfg, _rope(q, B, S, H, dh))
             k = _rt(cfg, _rope(k, B, S, H, dh))
             a = _rt(cfg, _attention(q, k, v, B, S, H, dh))
-            xres = _qlinear(cfg, a, P.qweight(p + "wo"), residual=xres)
+            xres = _qlinear(cfg, a, P.qweight(p + "wo"), residual=xres, tie_log=tie_log)
             keep(p + "attn_out", xres)
             h = _rt(cfg, _rmsnorm(xres, P.plain(p + "ffn_norm")))
-            gate = _qlinear(cfg, h, P.qweight(p + "w_gate"))
-            up = _qlinear(cfg, h, P.qweight(p + "w_up"))
+            gate = _qlinear(cfg, h, P.qweight(p + "w_gate"), tie_log=tie_log)
+            up = _qlinear(cfg, h, P.qweight(p + "w_up"), tie_log=tie_log)
             g64 = gate.astype(np.float64)
             act = _rt(cfg, g64 / (1.0 + np.exp(-g64)) * up.astype(np.float64))
-            xres = _qlinear(cfg, act, P.qweight(p + "w_down"), residual=xres)
+            xres = _qlinear(cfg, act, P.qweight(p + "w_down"), residual=xres, tie_log=tie_log)
         else:
             h = _rt(cfg, _layernorm(xres, P.plain(p + "ln1_g"), P.plain(p + "ln1_b")))
-            q = _qlinear(cfg, h, P.qweight(p + "wq"), P.plain(p + "bq"))
-            k = _qlinear(cfg, h, P.qweight(p + "wk"), P.plain(p + "bk"))
-            v = _qlinear(cfg, h, P.qweight(p + "wv"), P.plain(p + "bv"))
+            q = _qlinear(cfg, h, P.qweight(p + "wq"), P.plain(p + "bq"), tie_log=tie_log)
+            k = _qlinear(cfg, h, P.qweight(p + "wk"), P.plain(p + "bk"), tie_log=tie_log)
+            v = _qlinear(cfg, h, P.qweight(p + "wv"), P.plain(p + "bv"), tie_log=tie_log)
             a = _rt(cfg, _attention(q, k, v, B, S, H, dh))
-            xres = _qlinear(cfg, a, P.qweight(p + "wo"), P.plain(p + "bo"), residual=xres)
+            xres = _qlinear(cfg, a, P.qweight(p + "wo"), P.plain(p + "bo"), residual=xres, tie_log=tie_log)
             keep(p + "attn_out", xres)
             h = _rt(cfg, _layernorm(xres, P.plain(p + "ln2_g"), P.plain(p + "ln2_b")))
-            f = _qlinear(cfg, h, P.qweight(p + "fc1"), P.plain(p + "b1"), relu=True)
-            xres = _qlinear(cfg, f, P.qweight(p + "fc2"), P.plain(p + "b2"), residual=xres)
+            f = _qlinear(cfg, h, P.qweight(p + "fc1"), P.plain(p + "b1"), relu=True, tie_log=tie_log)
+            xres = _qlinear(cfg, f, P.qweight(p + "fc2"), P.plain(p + "b2"), residual=xres, tie_log=tie_log)
         keep(p + "out", xres)
     if cfg.arch == ARCH_LLAMA:
         hf = _rt(cfg, _rmsnorm(xres, P.plain("final_norm")))

@@ -1,0 +1,221 @@
+"""ctypes binding of libzoqat.so -- argument marshalling only.
+
+Every function mirrors the C entry point of the same name in include/zoqat.h.  torch is used
+for device memory and streams; every step of the path runs inside the HIP library.  The
+module raises at import if the library has not been built (there is no CPU fallback)."""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libzoqat.so")
+if not os.path.exists(LIB_PATH):
+    raise ImportError("libzoqat.so is not built; run `python -c 'import __graft_entry__ as g; g.build()'` first")
+_lib = C.CDLL(LIB_PATH)
+
+ZO_OK = 0
+STATUS = {0: "ZO_OK", 1: "ZO_EINVAL", 2: "ZO_ESHAPE", 3: "ZO_EALIGN", 4: "ZO_EHIP", 5: "ZO_EUNSUPPORTED", 6: "ZO_EWORKSPACE"}
+ARCH_LINEAR, ARCH_LLAMA, ARCH_OPT = 0, 1, 2
+ACT_FP32, ACT_BF16 = 0, 1
+
+EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "zo_destroy", "zo_last_error",
+           "zo_forward_quant", "zo_step", "zo_update", "zo_debug_philox_u32", "zo_debug_normal", "zo_update_tensor",
+           "zo_debug_quant_weight", "zo_debug_quant_act", "zo_linear_scratch_bytes", "zo_linear_fakequant",
+           "zo_gemm_nt", "zo_debug_buffer"]
+
+
+class zo_config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("arch", "n_layers", "d_model", "n_heads", "d_ffn", "vocab", "max_seq",
+                                         "w_bits", "w_group", "a_bits", "a_sym", "act_dtype", "lightweight")] + \
+               [("reserved", C.c_int32 * 3)]
+
+
+class zo_tensor(C.Structure):
+    _fields_ = [("ptr", C.c_void_p), ("numel", C.c_int64), ("trainable", C.c_int32), ("reserved", C.c_int32)]
+
+
+class ZoError(RuntimeError):
+    def __init__(self, status, where, detail=""):
+        self.status = status
+        super().__init__("%s returned %s%s" % (where, STATUS.get(status, status), (": " + detail) if detail else ""))
+
+
+_vp, _i32, _i64, _u64, _f32, _sz = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_float, C.c_size_t
+_lib.zo_num_params.argtypes = [C.POINTER(zo_config)]
+_lib.zo_num_params.restype = _i32
+_lib.zo_param_numel.argtypes = [C.POINTER(zo_config), _i32]
+_lib.zo_param_numel.restype = _i64
+_lib.zo_workspace_bytes.argtypes = [C.POINTER(zo_config), _i32, _i32]
+_lib.zo_workspace_bytes.restype = _sz
+_lib.zo_init.argtypes = [C.POINTER(zo_config), C.POINTER(zo_tensor), _i32, _vp, _sz, _i32, _i32, _vp, C.POINTER(_vp)]
+_lib.zo_destroy.argtypes = [_vp]
+_lib.zo_last_error.argtypes = [_vp]
+_lib.zo_last_error.restype = C.c_char_p
+_lib.zo_forward_quant.argtypes = [_vp, _vp, _vp, _i32, _i32, _u64, _f32, _vp]
+_lib.zo_step.argtypes = [_vp, _vp, _vp, _i32, _i32, _u64, _f32, _f32, _vp]
+_lib.zo_update.argtypes = [_vp, _u64, _vp, _f32]
+_lib.zo_debug_philox_u32.argtypes = [_u64, _i32, _i64, _vp, _vp]
+_lib.zo_debug_normal.argtypes = [_u64, _i32, _i64, _i64, _vp, _vp]
+_lib.zo_update_tensor.argtypes = [_vp, _i64, _u64, _i32, _vp, _f32, _vp]
+_lib.zo_debug_quant_weight.argtypes = [_vp, _i32, _i32, _i32, _i32, _u64, _i32, _f32, _i32, _vp, _vp, _vp, _vp, _vp]
+_lib.zo_debug_quant_act.argtypes = [_vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp]
+_lib.zo_linear_scratch_bytes.argtypes = [_i32, _i32, _i32, _i32]
+_lib.zo_linear_scratch_bytes.restype = _sz
+_lib.zo_linear_fakequant.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _u64, _i32, _f32, _vp, _vp]
+_lib.zo_gemm_nt.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp]
+_lib.zo_debug_buffer.argtypes = [_vp, _i32, _i32, C.POINTER(_vp), C.POINTER(_sz)]
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(status, where, ctx=None):
+    if status != ZO_OK:
+        detail = _lib.zo_last_error(ctx).decode() if ctx else ""
+        raise ZoError(status, where, detail)
+
+
+def _tdtype(dtype):
+    return torch.bfloat16 if dtype == ACT_BF16 else torch.float32
+
+
+def make_config(arch, n_layers=0, d_model=0, n_heads=1, d_ffn=0, vocab=0, max_seq=0, w_bits=4, w_group=64,
+                a_bits=16, a_sym=0, act_dtype=ACT_FP32, lightweight=0):
+    return zo_config(arch, n_layers, d_model, n_heads, d_ffn, vocab, max_seq, w_bits, w_group, a_bits, a_sym,
+                     act_dtype, lightweight)
+
+
+def zo_num_params(cfg):
+    return _lib.zo_num_params(C.byref(cfg))
+
+
+def zo_param_numel(cfg, index):
+    return _lib.zo_param_numel(C.byref(cfg), index)
+
+
+def zo_workspace_bytes(cfg, B, S):
+    return _lib.zo_workspace_bytes(C.byref(cfg), B, S)
+
+
+class Context:
+    """Owns nothing on the device except references that keep the caller's tensors alive."""
+
+    def __init__(self, cfg, params, max_B, max_S, trainable=None):
+        self.handle = None
+        self.cfg = cfg
+        self.params = params
+        n = len(params)
+        arr = (zo_tensor * n)()
+        for i, p in enumerate(params):
+            assert p.is_cuda and p.dtype == torch.float32 and p.is_contiguous()
+            arr[i] = zo_tensor(p.data_ptr(), p.numel(), 1 if (trainable is None or trainable[i]) else 0, 0)
+        nbytes = zo_workspace_bytes(cfg, max_B, max_S)
+        if nbytes == 0:
+            raise ZoError(1, "zo_workspace_bytes")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=params[0].device)
+        self.out4 = torch.zeros(4, dtype=torch.float32, device=params[0].device)
+        self.handle = _vp()
+        _check(_lib.zo_init(C.byref(cfg), arr, n, self.workspace.data_ptr(), nbytes, max_B, max_S, _stream(),
+                            C.byref(self.handle)), "zo_init")
+
+    def close(self):
+        if self.handle:
+            _lib.zo_destroy(self.handle)
+            self.handle = _vp()
+
+    def __del__(self):
+        self.close()
+
+    def zo_forward_quant(self, ids, target, B, S, seed, eps_signed, loss_dev=None):
+        loss = loss_dev if loss_dev is not None else torch.zeros(1, dtype=torch.float32, device=ids.device)
+        _check(_lib.zo_forward_quant(self.handle, _ptr(ids), _ptr(target), B, S, seed, eps_signed, loss.data_ptr()),
+               "zo_forward_quant", self.handle)
+        return loss
+
+    def zo_step(self, ids, target, B, S, seed, eps, lr, out_dev=None):
+        out = out_dev if out_dev is not None else self.out4
+        _check(_lib.zo_step(self.handle, _ptr(ids), _ptr(target), B, S, seed, eps, lr, out.data_ptr()), "zo_step", self.handle)
+        return out
+
+    def zo_update(self, seed, coeff_dev=None, coeff_host=0.0):
+        _check(_lib.zo_update(self.handle, seed, _ptr(coeff_dev), coeff_host), "zo_update", self.handle)
+
+    def zo_debug_buffer(self, which, branch=0):
+        p, n = _vp(), _sz()
+        _check(_lib.zo_debug_buffer(self.handle, which, branch, C.byref(p), C.byref(n)), "zo_debug_buffer", self.handle)
+        off = p.value - self.workspace.data_ptr()
+        return self.workspace[off:off + n.value]
+
+
+def zo_debug_philox_u32(seed, tensor_id, nwords, device="cuda"):
+    out = torch.empty(nwords, dtype=torch.int32, device=device)
+    _check(_lib.zo_debug_philox_u32(seed, tensor_id, nwords, out.data_ptr(), _stream()), "zo_debug_philox_u32")
+    return out
+
+
+def zo_debug_normal(seed, tensor_id, numel, start=0, device="cuda"):
+    out = torch.empty(numel, dtype=torch.float32, device=device)
+    _check(_lib.zo_debug_normal(seed, tensor_id, start, numel, out.data_ptr(), _stream()), "zo_debug_normal")
+    return out
+
+
+def zo_update_tensor(w, seed, tensor_id, coeff_dev=None, coeff_host=0.0):
+    _check(_lib.zo_update_tensor(w.data_ptr(), w.numel(), seed, tensor_id, _ptr(coeff_dev), coeff_host, _stream()),
+           "zo_update_tensor")
+    return w
+
+
+def zo_debug_quant_weight(W, bits, group, seed=0, tensor_id=0, eps_signed=0.0, out_dtype=ACT_FP32, want_codes=True):
+    N, K = W.shape
+    g = group if group else K
+    G = K // g if bits else 0
+    dev = W.device
+    codes = torch.empty((N, K), dtype=torch.uint8, device=dev) if (bits and want_codes) else None
+    step = torch.empty((N, G), dtype=torch.float32, device=dev) if bits else None
+    zp = torch.empty((N, G), dtype=torch.int32, device=dev) if bits else None
+    what = torch.empty((N, K), dtype=_tdtype(out_dtype), device=dev)
+    _check(_lib.zo_debug_quant_weight(W.data_ptr(), N, K, bits, group, seed, tensor_id, eps_signed, out_dtype,
+                                      _ptr(codes), _ptr(step), _ptr(zp), what.data_ptr(), _stream()), "zo_debug_quant_weight")
+    return dict(codes=codes, step=step, zp=zp, what=what)
+
+
+def zo_debug_quant_act(X, bits, sym=0, want_codes=True):
+    M, K = X.shape
+    dtype = ACT_BF16 if X.dtype == torch.bfloat16 else ACT_FP32
+    dev = X.device
+    codes = torch.empty((M, K), dtype=torch.int16, device=dev) if want_codes else None
+    step = torch.empty(M, dtype=torch.float32, device=dev)
+    zp = torch.empty(M, dtype=torch.int32, device=dev)
+    xhat = torch.empty_like(X)
+    _check(_lib.zo_debug_quant_act(X.data_ptr(), M, K, bits, sym, dtype, _ptr(codes), step.data_ptr(), zp.data_ptr(),
+                                   xhat.data_ptr(), _stream()), "zo_debug_quant_act")
+    return dict(codes=codes, step=step, zp=zp, xhat=xhat)
+
+
+def zo_linear_fakequant(X, W, bias, w_bits, w_group, a_bits, a_sym=0, seed=0, tensor_id=0, eps_signed=0.0, scratch=None):
+    M, K = X.shape
+    N = W.shape[0]
+    dtype = ACT_BF16 if X.dtype == torch.bfloat16 else ACT_FP32
+    if scratch is None:
+        scratch = torch.empty(_lib.zo_linear_scratch_bytes(M, N, K, dtype), dtype=torch.uint8, device=X.device)
+    Y = torch.empty((M, N), dtype=X.dtype, device=X.device)
+    _check(_lib.zo_linear_fakequant(X.data_ptr(), W.data_ptr(), _ptr(bias), Y.data_ptr(), M, N, K, w_bits, w_group,
+                                    a_bits, a_sym, dtype, seed, tensor_id, eps_signed, scratch.data_ptr(), _stream()),
+           "zo_linear_fakequant")
+    return Y
+
+
+def zo_gemm_nt(X, W, Y=None):
+    M, K = X.shape
+    N = W.shape[0]
+    dtype = ACT_BF16 if X.dtype == torch.bfloat16 else ACT_FP32
+    if Y is None:
+        Y = torch.empty((M, N), dtype=X.dtype, device=X.device)
+    _check(_lib.zo_gemm_nt(X.data_ptr(), W.data_ptr(), Y.data_ptr(), M, N, K, dtype, _stream()), "zo_gemm_nt")
+    return Y

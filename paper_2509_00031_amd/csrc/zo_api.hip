@@ -1,0 +1,614 @@
+// C ABI of the library (see include/zoqat.h): argument checks, the context with its workspace
+// layout, and the schedule of one quantized forward / one ZO step over the kernels.
+#include "../../include/zoqat.h"
+#include "zo_internal.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+namespace {
+
+inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+struct param_desc { int64_t rows, cols; bool quantized; };
+
+// Parameter list of a configuration in the fixed order of the header.
+bool describe_params(const zo_config& c, std::vector<param_desc>& out)
+{
+    out.clear();
+    const int64_t d = c.d_model, f = c.d_ffn, V = c.vocab;
+    if (c.arch == ZO_ARCH_LINEAR) {
+        if (d <= 0 || f <= 0) return false;
+        out.push_back({f, d, true});
+        return true;
+    }
+    if (c.arch != ZO_ARCH_LLAMA && c.arch != ZO_ARCH_OPT) return false;
+    if (d <= 0 || f <= 0 || V <= 0 || c.n_layers < 0 || c.n_heads <= 0 || c.max_seq <= 0) return false;
+    out.push_back({V, d, false});
+    if (c.arch == ZO_ARCH_OPT) out.push_back({c.max_seq, d, false});
+    for (int l = 0; l < c.n_layers; ++l) {
+        if (c.arch == ZO_ARCH_LLAMA) {
+            out.push_back({1, d, false});
+            for (int i = 0; i < 4; ++i) out.push_back({d, d, true});
+            out.push_back({1, d, false});
+            out.push_back({f, d, true});
+            out.push_back({f, d, true});
+            out.push_back({d, f, true});
+        } else {
+            out.push_back({1, d, false}); out.push_back({1, d, false});
+            for (int i = 0; i < 4; ++i) { out.push_back({d, d, true}); out.push_back({1, d, false}); }
+            out.push_back({1, d, false}); out.push_back({1, d, false});
+            out.push_back({f, d, true}); out.push_back({1, f, false});
+            out.push_back({d, f, true}); out.push_back({1, d, false});
+        }
+    }
+    out.push_back({1, d, false});
+    if (c.arch == ZO_ARCH_OPT) out.push_back({1, d, false});
+    out.push_back({V, d, false});
+    return true;
+}
+
+zo_status check_config(const zo_config& c)
+{
+    std::vector<param_desc> p;
+    if (!describe_params(c, p)) return ZO_EINVAL;
+    if (c.act_dtype != ZO_ACT_FP32 && c.act_dtype != ZO_ACT_BF16) return ZO_EINVAL;
+    if (c.w_bits < 0 || c.w_bits > 8) return ZO_EINVAL;
+    if (!(c.a_bits == 16 || (c.a_bits >= 2 && c.a_bits <= 8))) return ZO_EINVAL;
+    if (c.w_group < 0) return ZO_EINVAL;
+    if ((c.d_model & 7) || (c.d_ffn & 7)) return ZO_ESHAPE;
+    if (c.w_bits > 0 && c.w_group > 0 && ((c.w_group & 7) || c.d_model % c.w_group || c.d_ffn % c.w_group)) return ZO_ESHAPE;
+    if (c.arch != ZO_ARCH_LINEAR) {
+        if (c.d_model % c.n_heads) return ZO_ESHAPE;
+        const int dh = c.d_model / c.n_heads;
+        if (dh != 16 && dh != 32 && dh != 64 && dh != 128) return ZO_EUNSUPPORTED;
+    }
+    return ZO_OK;
+}
+
+// Workspace layout for B x S tokens.  Offsets in bytes, everything 256-byte aligned.
+struct layout {
+    size_t scalars;            // fp32[8]: loss[2], out4[4]
+    size_t rope_cos, rope_sin; // fp32 [max_seq][dh/2]
+    size_t what[2];            // de-quantized weights of the current linear(s), per branch
+    size_t vec[2];             // perturbed small vectors of the current sub-layer, per branch
+    size_t vec_stride;         // floats per vector slot
+    struct per_branch {
+        size_t x, h, hq, qkv, att, gu, act, logits, rowloss;
+    } br[2];
+    size_t total;
+};
+
+layout make_layout(const zo_config& c, int B, int S)
+{
+    layout L{};
+    const size_t ts = zo_tsize(c.act_dtype);
+    const size_t d = c.d_model, f = c.d_ffn, V = c.vocab > 0 ? c.vocab : 0;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+    L.scalars = take(8 * sizeof(float));
+    if (c.arch == ZO_ARCH_LINEAR) {
+        const size_t M = B;
+        for (int b = 0; b < 2; ++b) L.what[b] = take(f * d * ts);
+        for (int b = 0; b < 2; ++b) {
+            L.br[b].hq = take(M * d * ts);
+            L.br[b].logits = take(M * f * ts);      // output Y
+            L.br[b].rowloss = take(M * sizeof(float));
+        }
+        L.total = off;
+        return L;
+    }
+    const size_t M = (size_t)B * S;
+    const size_t dh = d / c.n_heads;
+    L.rope_cos = take((size_t)c.max_seq * (dh / 2) * sizeof(float));
+    L.rope_sin = take((size_t)c.max_seq * (dh / 2) * sizeof(float));
+    size_t max_nk = V * d;
+    const size_t ffn_rows = c.arch == ZO_ARCH_LLAMA ? 2 * f : f;
+    if (3 * d * d > max_nk) max_nk = 3 * d * d;
+    if (ffn_rows * d > max_nk) max_nk = ffn_rows * d;
+    for (int b = 0; b < 2; ++b) L.what[b] = take(max_nk * ts);
+    L.vec_stride = d > f ? d : f;
+    if (3 * d > L.vec_stride) L.vec_stride = 3 * d;
+    L.vec_stride = align_up(L.vec_stride * sizeof(float)) / sizeof(float);
+    for (int b = 0; b < 2; ++b) L.vec[b] = take(3 * L.vec_stride * sizeof(float));
+    for (int b = 0; b < 2; ++b) {
+        auto& r = L.br[b];
+        r.x = take(M * d * ts);
+        r.h = take(M * d * ts);
+        r.hq = take(M * (d > f ? d : f) * ts);
+        r.qkv = take(M * 3 * d * ts);
+        r.att = take(M * d * ts);
+        r.gu = take(M * ffn_rows * ts);
+        r.act = take(M * f * ts);
+        r.logits = take(M * V * sizeof(float));
+        r.rowloss = take(M * sizeof(float));
+    }
+    L.total = off;
+    return L;
+}
+
+}  // namespace
+
+struct zo_ctx {
+    zo_config cfg;
+    std::vector<zo_tensor> params;
+    std::vector<param_desc> desc;
+    char* ws;
+    size_t ws_bytes;
+    int max_B, max_S;
+    hipStream_t st;
+    layout L;           // for max_B x max_S
+    int last_M;
+    std::string err;
+};
+
+namespace {
+
+zo_status fail(zo_ctx* c, zo_status s, const char* what, hipError_t e = hipSuccess)
+{
+    if (c) {
+        c->err = what;
+        if (e != hipSuccess) { c->err += ": "; c->err += hipGetErrorString(e); }
+    }
+    return s;
+}
+
+#define ZO_HIP(ctx, call)                                                  \
+    do {                                                                   \
+        hipError_t e_ = (call);                                            \
+        if (e_ != hipSuccess) return fail((ctx), ZO_EHIP, #call, e_);      \
+    } while (0)
+
+inline bool trainable(const zo_ctx* c, int i) { return !c->cfg.lightweight || c->params[i].trainable; }
+
+// One forward for nb branches: branch 0 at +eps (or eps_signed when nb == 1), branch 1 at -eps.
+struct fwd {
+    zo_ctx* c;
+    int nb;
+    float eps;          // magnitude for paired mode, signed value for single mode
+    uint64_t seed;
+    int M, S;
+    template <typename T = char> T* at(size_t off) const { return (T*)(c->ws + off); }
+    int dt() const { return c->cfg.act_dtype; }
+    float eps_of(int tensor) const { return trainable(c, tensor) ? eps : 0.0f; }
+
+    // Q(W +- eps u) of tensor `t` ([rows][cols]) into rows [row0, row0+rows) of the what buffers
+    zo_status weights(int t, int64_t row0, bool quantize)
+    {
+        const param_desc& p = c->desc[t];
+        const size_t ts = zo_tsize(dt());
+        void* op = at(c->L.what[0]) + (size_t)row0 * p.cols * ts;
+        void* om = nb == 2 ? at(c->L.what[1]) + (size_t)row0 * p.cols * ts : nullptr;
+        const int bits = quantize ? c->cfg.w_bits : 0;
+        ZO_HIP(c, zo_launch_fq_weight((const float*)c->params[t].ptr, (int)p.rows, (int)p.cols, bits, c->cfg.w_group,
+                                      seed, t, eps_of(t), dt(), op, om, nullptr, nullptr, nullptr, c->st));
+        return ZO_OK;
+    }
+    // perturbed fp32 vector of tensor `t` into vector slot `slot` at float offset `o`
+    zo_status vector(int t, int slot, int64_t o = 0)
+    {
+        const param_desc& p = c->desc[t];
+        float* op = at<float>(c->L.vec[0]) + slot * c->L.vec_stride + o;
+        float* om = nb == 2 ? at<float>(c->L.vec[1]) + slot * c->L.vec_stride + o : nullptr;
+        ZO_HIP(c, zo_launch_fq_weight((const float*)c->params[t].ptr, 1, (int)p.cols, 0, 0, seed, t, eps_of(t), ZO_T_F32,
+                                      op, om, nullptr, nullptr, nullptr, c->st));
+        return ZO_OK;
+    }
+    float* vec(int b, int slot) const { return at<float>(c->L.vec[b]) + slot * c->L.vec_stride; }
+
+    zo_status norm(size_t layout::per_branch::*in, size_t layout::per_branch::*out, bool has_beta)
+    {
+        for (int b = 0; b < nb; ++b)
+            ZO_HIP(c, zo_launch_norm(at(c->L.br[b].*in), vec(b, 0), has_beta ? vec(b, 1) : nullptr, at(c->L.br[b].*out),
+                                     M, c->cfg.d_model, 1e-5f, dt(), c->st));
+        return ZO_OK;
+    }
+    // per-token quantizer of the input of a quantized linear; returns which buffer holds X^
+    zo_status act_quant(size_t layout::per_branch::*in, int K, size_t layout::per_branch::** used)
+    {
+        if (c->cfg.a_bits >= 16) { *used = in; return ZO_OK; }
+        for (int b = 0; b < nb; ++b)
+            ZO_HIP(c, zo_launch_fq_act(at(c->L.br[b].*in), at(c->L.br[b].hq), M, K, c->cfg.a_bits, c->cfg.a_sym, dt(),
+                                       nullptr, nullptr, nullptr, c->st));
+        *used = &layout::per_branch::hq;
+        return ZO_OK;
+    }
+    zo_status gemm(size_t layout::per_branch::*in, size_t layout::per_branch::*out, int N, int K, bool bias, bool relu,
+                   bool residual, bool out_f32 = false)
+    {
+        zo_gemm_args a{};
+        a.X = at(c->L.br[0].*in);
+        a.W = at(c->L.what[0]);
+        a.Y = at(c->L.br[0].*out);
+        a.bias = bias ? vec(0, 2) : nullptr;
+        a.residual = residual ? at(c->L.br[0].*out) : nullptr;
+        a.M = M; a.N = N; a.K = K;
+        a.batch = nb;
+        const int64_t ts = (int64_t)zo_tsize(dt());
+        if (nb == 2) {
+            a.strideX = (int64_t)(c->L.br[1].*in - c->L.br[0].*in) / ts;
+            a.strideW = (int64_t)(c->L.what[1] - c->L.what[0]) / ts;
+            a.strideY = (int64_t)(c->L.br[1].*out - c->L.br[0].*out) / (out_f32 ? 4 : ts);
+            a.strideBias = (int64_t)(c->L.vec[1] - c->L.vec[0]) / 4;
+            a.strideRes = a.strideY;
+        }
+        a.relu = relu;
+        a.out_f32 = out_f32;
+        a.dtype = dt();
+        ZO_HIP(c, zo_launch_gemm(a, c->st));
+        return ZO_OK;
+    }
+};
+
+#define ZO_TRY(x) do { zo_status s_ = (x); if (s_ != ZO_OK) return s_; } while (0)
+
+zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int B, int S, uint64_t seed,
+                      float eps, int nb, float* loss_out /* dev fp32[nb] */)
+{
+    const zo_config& cfg = c->cfg;
+    using PB = layout::per_branch;
+    fwd F{c, nb, eps, seed, 0, S};
+    const int dt = cfg.act_dtype;
+    const size_t ts = zo_tsize(dt);
+    if (cfg.arch == ZO_ARCH_LINEAR) {
+        const int M = B, K = cfg.d_model, N = cfg.d_ffn;
+        F.M = M;
+        c->last_M = M;
+        ZO_TRY(F.weights(0, 0, true));
+        // input X is given by the caller; quantize into hq (same X^ for both branches)
+        zo_gemm_args a{};
+        const void* xin = ids_or_x;
+        if (cfg.a_bits < 16) {
+            ZO_HIP(c, zo_launch_fq_act(ids_or_x, F.at(c->L.br[0].hq), M, K, cfg.a_bits, cfg.a_sym, dt, nullptr, nullptr, nullptr, c->st));
+            xin = F.at(c->L.br[0].hq);
+        }
+        a.X = xin; a.W = F.at(c->L.what[0]); a.Y = F.at(c->L.br[0].logits);
+        a.M = M; a.N = N; a.K = K; a.batch = nb; a.dtype = dt;
+        if (nb == 2) {
+            a.strideX = 0;
+            a.strideW = (int64_t)(c->L.what[1] - c->L.what[0]) / (int64_t)ts;
+            a.strideY = (int64_t)(c->L.br[1].logits - c->L.br[0].logits) / (int64_t)ts;
+        }
+        ZO_HIP(c, zo_launch_gemm(a, c->st));
+        for (int b = 0; b < nb; ++b) {
+            ZO_HIP(c, zo_launch_sqerr_rows(F.at(c->L.br[b].logits), target, F.at<float>(c->L.br[b].rowloss), M, N, dt, c->st));
+            ZO_HIP(c, zo_launch_reduce_loss(F.at<float>(c->L.br[b].rowloss), M, 1.0f / ((float)M * (float)N), loss_out + b, c->st));
+        }
+        return ZO_OK;
+    }
+
+    const int M = B * S, d = cfg.d_model, f = cfg.d_ffn, V = cfg.vocab, H = cfg.n_heads, dh = d / H;
+    F.M = M;
+    c->last_M = M;
+    const bool llama = cfg.arch == ZO_ARCH_LLAMA;
+    const int32_t* ids = (const int32_t*)ids_or_x;
+    int t = 0;                                           // running tensor number
+    // embedding
+    {
+        const int t_tok = t++;
+        const int t_pos = llama ? -1 : t++;
+        for (int b = 0; b < nb; ++b) {
+            const float sgn = (b == 0) ? 1.0f : -1.0f;
+            ZO_HIP(c, zo_launch_embed(ids, (const float*)c->params[t_tok].ptr, llama ? nullptr : (const float*)c->params[t_pos].ptr,
+                                      F.at(c->L.br[b].x), M, S, d, V, seed, t_tok, llama ? 0 : t_pos,
+                                      sgn * F.eps_of(t_tok), llama ? 0.0f : sgn * F.eps_of(t_pos), dt, c->st));
+        }
+    }
+    size_t PB::* xin;
+    for (int l = 0; l < cfg.n_layers; ++l) {
+        // ---- attention block
+        ZO_TRY(F.vector(t++, 0));
+        if (!llama) ZO_TRY(F.vector(t++, 1));
+        ZO_TRY(F.norm(&PB::x, &PB::h, !llama));
+        ZO_TRY(F.act_quant(&PB::h, d, &xin));
+        for (int i = 0; i < 3; ++i) {
+            ZO_TRY(F.weights(t++, (int64_t)i * d, true));
+            if (!llama) ZO_TRY(F.vector(t++, 2, (int64_t)i * d));
+        }
+        ZO_TRY(F.gemm(xin, &PB::qkv, 3 * d, d, !llama, false, false));
+        for (int b = 0; b < nb; ++b) {
+            char* qkv = F.at(c->L.br[b].qkv);
+            if (llama)
+                ZO_HIP(c, zo_launch_rope(qkv, qkv + (size_t)d * ts, F.at<float>(c->L.rope_cos), F.at<float>(c->L.rope_sin),
+                                         M, S, H, dh, 3 * d, dt, c->st));
+            ZO_HIP(c, zo_launch_attention(qkv, qkv + (size_t)d * ts, qkv + (size_t)2 * d * ts, F.at(c->L.br[b].att),
+                                          B, S, H, dh, 3 * d, dt, c->st));
+        }
+        ZO_TRY(F.act_quant(&PB::att, d, &xin));
+        ZO_TRY(F.weights(t++, 0, true));
+        if (!llama) ZO_TRY(F.vector(t++, 2));
+        ZO_TRY(F.gemm(xin, &PB::x, d, d, !llama, false, true));
+        // ---- feed-forward block
+        ZO_TRY(F.vector(t++, 0));
+        if (!llama) ZO_TRY(F.vector(t++, 1));
+        ZO_TRY(F.norm(&PB::x, &PB::h, !llama));
+        ZO_TRY(F.act_quant(&PB::h, d, &xin));
+        if (llama) {
+            ZO_TRY(F.weights(t++, 0, true));
+            ZO_TRY(F.weights(t++, f, true));
+            ZO_TRY(F.gemm(xin, &PB::gu, 2 * f, d, false, false, false));
+            for (int b = 0; b < nb; ++b) {
+                char* gu = F.at(c->L.br[b].gu);
+                ZO_HIP(c, zo_launch_swiglu(gu, gu + (size_t)f * ts, F.at(c->L.br[b].act), M, f, 2 * f, dt, c->st));
+            }
+        } else {
+            ZO_TRY(F.weights(t++, 0, true));
+            ZO_TRY(F.vector(t++, 2));
+            ZO_TRY(F.gemm(xin, &PB::act, f, d, true, true, false));
+        }
+        ZO_TRY(F.act_quant(&PB::act, f, &xin));
+        ZO_TRY(F.weights(t++, 0, true));
+        if (!llama) ZO_TRY(F.vector(t++, 2));
+        ZO_TRY(F.gemm(xin, &PB::x, d, f, !llama, false, true));
+    }
+    // ---- head
+    ZO_TRY(F.vector(t++, 0));
+    if (!llama) ZO_TRY(F.vector(t++, 1));
+    ZO_TRY(F.norm(&PB::x, &PB::h, !llama));
+    ZO_TRY(F.weights(t++, 0, false));
+    ZO_TRY(F.gemm(&PB::h, &PB::logits, V, d, false, false, false, true));
+    for (int b = 0; b < nb; ++b) {
+        ZO_HIP(c, zo_launch_ce_rows(F.at<float>(c->L.br[b].logits), ids, F.at<float>(c->L.br[b].rowloss), M, S, V, c->st));
+        ZO_HIP(c, zo_launch_reduce_loss(F.at<float>(c->L.br[b].rowloss), M, 1.0f / ((float)B * (float)(S - 1)), loss_out + b, c->st));
+    }
+    return ZO_OK;
+}
+
+zo_status check_batch(zo_ctx* c, const void* ids, const float* target, int B, int S)
+{
+    if (!c) return ZO_EINVAL;
+    if (!ids) return fail(c, ZO_EINVAL, "ids / input is NULL");
+    if (B <= 0 || S <= 0) return fail(c, ZO_EINVAL, "B and S must be positive");
+    if (c->cfg.arch == ZO_ARCH_LINEAR) {
+        if (!target) return fail(c, ZO_EINVAL, "target is NULL");
+        if (S != 1) return fail(c, ZO_ESHAPE, "the linear arch takes S = 1");
+        if (!aligned16(target)) return fail(c, ZO_EALIGN, "target not 16-byte aligned");
+    } else {
+        if (S < 2) return fail(c, ZO_ESHAPE, "next-token loss needs S >= 2");
+        if (S > c->cfg.max_seq) return fail(c, ZO_ESHAPE, "S exceeds max_seq");
+    }
+    if (!aligned16(ids)) return fail(c, ZO_EALIGN, "ids / input not 16-byte aligned");
+    if ((int64_t)B * S > (int64_t)c->max_B * c->max_S || S > c->max_S)
+        return fail(c, ZO_EWORKSPACE, "batch larger than the one the context was created for");
+    return ZO_OK;
+}
+
+}  // namespace
+
+// =============================================================================================
+extern "C" {
+
+int32_t zo_num_params(const zo_config* cfg)
+{
+    std::vector<param_desc> p;
+    if (!cfg || !describe_params(*cfg, p)) return 0;
+    return (int32_t)p.size();
+}
+
+int64_t zo_param_numel(const zo_config* cfg, int32_t index)
+{
+    std::vector<param_desc> p;
+    if (!cfg || !describe_params(*cfg, p) || index < 0 || index >= (int32_t)p.size()) return -1;
+    return p[index].rows * p[index].cols;
+}
+
+size_t zo_workspace_bytes(const zo_config* cfg, int32_t B, int32_t S)
+{
+    if (!cfg || B <= 0 || S <= 0 || check_config(*cfg) != ZO_OK) return 0;
+    return make_layout(*cfg, B, S).total;
+}
+
+zo_status zo_init(const zo_config* cfg, const zo_tensor* params, int32_t n_params,
+                  void* workspace, size_t workspace_bytes, int32_t max_B, int32_t max_S,
+                  void* hip_stream, zo_ctx** out)
+{
+    if (!cfg || !params || !workspace || !out || max_B <= 0 || max_S <= 0) return ZO_EINVAL;
+    *out = nullptr;
+    zo_status s = check_config(*cfg);
+    if (s != ZO_OK) return s;
+    std::vector<param_desc> desc;
+    describe_params(*cfg, desc);
+    if (n_params != (int32_t)desc.size()) return ZO_EINVAL;
+    for (int i = 0; i < n_params; ++i) {
+        if (!params[i].ptr) return ZO_EINVAL;
+        if (params[i].numel != desc[i].rows * desc[i].cols) return ZO_ESHAPE;
+        if (!aligned16(params[i].ptr)) return ZO_EALIGN;
+    }
+    if (cfg->arch != ZO_ARCH_LINEAR && max_S > cfg->max_seq) return ZO_ESHAPE;
+    if (!aligned16(workspace)) return ZO_EALIGN;
+    layout L = make_layout(*cfg, max_B, max_S);
+    if (workspace_bytes < L.total) return ZO_EWORKSPACE;
+    zo_ctx* c = new zo_ctx();
+    c->cfg = *cfg;
+    c->params.assign(params, params + n_params);
+    c->desc = desc;
+    c->ws = (char*)workspace;
+    c->ws_bytes = workspace_bytes;
+    c->max_B = max_B;
+    c->max_S = max_S;
+    c->st = (hipStream_t)hip_stream;
+    c->L = L;
+    c->last_M = 0;
+    if (cfg->arch == ZO_ARCH_LLAMA) {
+        // rotary angle table: cos / sin of pos * 10000^(-2i/dh), evaluated in fp64, stored fp32
+        const int dh = cfg->d_model / cfg->n_heads, half = dh / 2;
+        std::vector<float> cs((size_t)cfg->max_seq * half), sn((size_t)cfg->max_seq * half);
+        for (int p = 0; p < cfg->max_seq; ++p)
+            for (int i = 0; i < half; ++i) {
+                const double ang = (double)p * std::pow(10000.0, -2.0 * (double)i / (double)dh);
+                cs[(size_t)p * half + i] = (float)std::cos(ang);
+                sn[(size_t)p * half + i] = (float)std::sin(ang);
+            }
+        hipError_t e = hipMemcpyAsync(c->ws + L.rope_cos, cs.data(), cs.size() * 4, hipMemcpyHostToDevice, c->st);
+        if (e == hipSuccess) e = hipMemcpyAsync(c->ws + L.rope_sin, sn.data(), sn.size() * 4, hipMemcpyHostToDevice, c->st);
+        if (e == hipSuccess) e = hipStreamSynchronize(c->st);      // host vectors die at return
+        if (e != hipSuccess) { delete c; return ZO_EHIP; }
+    }
+    *out = c;
+    return ZO_OK;
+}
+
+zo_status zo_destroy(zo_ctx* ctx)
+{
+    delete ctx;
+    return ZO_OK;
+}
+
+const char* zo_last_error(const zo_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+zo_status zo_forward_quant(zo_ctx* ctx, const void* ids, const float* target, int32_t B, int32_t S,
+                           uint64_t seed, float eps_signed, float* loss_dev)
+{
+    zo_status s = check_batch(ctx, ids, target, B, S);
+    if (s != ZO_OK) return s;
+    if (!loss_dev) return fail(ctx, ZO_EINVAL, "loss_dev is NULL");
+    return run_forward(ctx, ids, target, B, S, seed, eps_signed, 1, loss_dev);
+}
+
+zo_status zo_update(zo_ctx* ctx, uint64_t seed, const float* coeff_dev, float coeff_host)
+{
+    if (!ctx) return ZO_EINVAL;
+    for (int i = 0; i < (int)ctx->params.size(); ++i) {
+        if (!trainable(ctx, i)) continue;
+        ZO_HIP(ctx, zo_launch_update((float*)ctx->params[i].ptr, ctx->params[i].numel, seed, i, coeff_dev, coeff_host, ctx->st));
+    }
+    return ZO_OK;
+}
+
+zo_status zo_step(zo_ctx* ctx, const void* ids, const float* target, int32_t B, int32_t S,
+                  uint64_t seed, float eps, float lr, float* out_dev)
+{
+    zo_status s = check_batch(ctx, ids, target, B, S);
+    if (s != ZO_OK) return s;
+    if (!out_dev) return fail(ctx, ZO_EINVAL, "out_dev is NULL");
+    if (!(eps > 0.0f)) return fail(ctx, ZO_EINVAL, "eps must be positive");
+    float* loss2 = (float*)(ctx->ws + ctx->L.scalars);
+    s = run_forward(ctx, ids, target, B, S, seed, eps, 2, loss2);
+    if (s != ZO_OK) return s;
+    ZO_HIP(ctx, zo_launch_projected_grad(loss2, eps, lr, out_dev, ctx->st));
+    return zo_update(ctx, seed, out_dev + 3, 0.0f);
+}
+
+zo_status zo_debug_buffer(zo_ctx* ctx, int32_t which, int32_t branch, void** ptr, size_t* bytes)
+{
+    if (!ctx || !ptr || !bytes || branch < 0 || branch > 1) return ZO_EINVAL;
+    const zo_config& c = ctx->cfg;
+    const size_t ts = zo_tsize(c.act_dtype);
+    const layout::per_branch& r = ctx->L.br[branch];
+    const size_t M = ctx->last_M;
+    if (c.arch == ZO_ARCH_LINEAR) {
+        if (which != 1) return ZO_EINVAL;
+        *ptr = ctx->ws + r.logits;
+        *bytes = M * c.d_ffn * ts;
+        return ZO_OK;
+    }
+    switch (which) {
+        case 0: *ptr = ctx->ws + r.h; *bytes = M * c.d_model * ts; return ZO_OK;
+        case 1: *ptr = ctx->ws + r.logits; *bytes = M * (size_t)c.vocab * 4; return ZO_OK;
+        case 2: *ptr = ctx->ws + r.x; *bytes = M * c.d_model * ts; return ZO_OK;
+        default: return ZO_EINVAL;
+    }
+}
+
+// ---- stand-alone pieces -----------------------------------------------------------------------
+zo_status zo_debug_philox_u32(uint64_t seed, int32_t tensor_id, int64_t nwords, uint32_t* out_dev, void* hip_stream)
+{
+    if (nwords < 0 || (nwords > 0 && !out_dev)) return ZO_EINVAL;
+    return zo_launch_philox_words(seed, tensor_id, nwords, out_dev, (hipStream_t)hip_stream) == hipSuccess ? ZO_OK : ZO_EHIP;
+}
+
+zo_status zo_debug_normal(uint64_t seed, int32_t tensor_id, int64_t start, int64_t numel, float* out_dev, void* hip_stream)
+{
+    if (numel < 0 || start < 0 || (numel > 0 && !out_dev)) return ZO_EINVAL;
+    return zo_launch_normal(seed, tensor_id, start, numel, out_dev, (hipStream_t)hip_stream) == hipSuccess ? ZO_OK : ZO_EHIP;
+}
+
+zo_status zo_update_tensor(float* w_dev, int64_t numel, uint64_t seed, int32_t tensor_id,
+                           const float* coeff_dev, float coeff_host, void* hip_stream)
+{
+    if (numel < 0 || (numel > 0 && !w_dev)) return ZO_EINVAL;
+    if (!aligned16(w_dev)) return ZO_EALIGN;
+    return zo_launch_update(w_dev, numel, seed, tensor_id, coeff_dev, coeff_host, (hipStream_t)hip_stream) == hipSuccess ? ZO_OK : ZO_EHIP;
+}
+
+zo_status zo_debug_quant_weight(const float* W_dev, int32_t N, int32_t K, int32_t bits, int32_t group,
+                                uint64_t seed, int32_t tensor_id, float eps_signed, int32_t out_dtype,
+                                uint8_t* codes_dev, float* step_dev, int32_t* zp_dev, void* what_dev, void* hip_stream)
+{
+    if (!W_dev || N < 0 || K < 0) return ZO_EINVAL;
+    if (out_dtype != ZO_ACT_FP32 && out_dtype != ZO_ACT_BF16) return ZO_EINVAL;
+    if (bits < 0 || bits > 8 || group < 0) return ZO_EINVAL;
+    if (!zo_fq_weight_supported(K, bits, group)) return ZO_ESHAPE;
+    if (!aligned16(W_dev) || !aligned16(what_dev)) return ZO_EALIGN;
+    hipError_t e = zo_launch_fq_weight(W_dev, N, K, bits, group, seed, tensor_id, eps_signed, out_dtype, what_dev, nullptr,
+                                       codes_dev, step_dev, zp_dev, (hipStream_t)hip_stream);
+    return e == hipSuccess ? ZO_OK : ZO_EHIP;
+}
+
+zo_status zo_debug_quant_act(const void* X_dev, int32_t M, int32_t K, int32_t bits, int32_t sym, int32_t dtype,
+                             int16_t* codes_dev, float* step_dev, int32_t* zp_dev, void* xhat_dev, void* hip_stream)
+{
+    if (!X_dev || M < 0 || K <= 0) return ZO_EINVAL;
+    if (dtype != ZO_ACT_FP32 && dtype != ZO_ACT_BF16) return ZO_EINVAL;
+    if (bits < 2 || bits > 8) return ZO_EINVAL;
+    if (K & 7) return ZO_ESHAPE;
+    if (!aligned16(X_dev) || !aligned16(xhat_dev)) return ZO_EALIGN;
+    hipError_t e = zo_launch_fq_act(X_dev, xhat_dev, M, K, bits, sym, dtype, codes_dev, step_dev, zp_dev, (hipStream_t)hip_stream);
+    return e == hipSuccess ? ZO_OK : ZO_EHIP;
+}
+
+size_t zo_linear_scratch_bytes(int32_t M, int32_t N, int32_t K, int32_t dtype)
+{
+    if (M < 0 || N < 0 || K < 0) return 0;
+    const size_t ts = zo_tsize(dtype);
+    return align_up((size_t)M * K * ts) + align_up((size_t)N * K * ts);
+}
+
+zo_status zo_linear_fakequant(const void* X_dev, const float* W_dev, const float* bias_dev, void* Y_dev,
+                              int32_t M, int32_t N, int32_t K, int32_t w_bits, int32_t w_group,
+                              int32_t a_bits, int32_t a_sym, int32_t dtype,
+                              uint64_t seed, int32_t tensor_id, float eps_signed, void* scratch_dev, void* hip_stream)
+{
+    if (!X_dev || !W_dev || !Y_dev || !scratch_dev || M < 0 || N < 0 || K <= 0) return ZO_EINVAL;
+    if (dtype != ZO_ACT_FP32 && dtype != ZO_ACT_BF16) return ZO_EINVAL;
+    if (w_bits < 0 || w_bits > 8 || w_group < 0) return ZO_EINVAL;
+    if (!(a_bits == 16 || (a_bits >= 2 && a_bits <= 8))) return ZO_EINVAL;
+    if (!zo_fq_weight_supported(K, w_bits, w_group)) return ZO_ESHAPE;
+    if (!aligned16(X_dev) || !aligned16(W_dev) || !aligned16(Y_dev) || !aligned16(scratch_dev) || !aligned16(bias_dev)) return ZO_EALIGN;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const size_t ts = zo_tsize(dtype);
+    char* xhat = (char*)scratch_dev;
+    char* what = xhat + align_up((size_t)M * K * ts);
+    hipError_t e = zo_launch_fq_weight(W_dev, N, K, w_bits, w_group, seed, tensor_id, eps_signed, dtype, what, nullptr,
+                                       nullptr, nullptr, nullptr, st);
+    if (e != hipSuccess) return ZO_EHIP;
+    const void* xin = X_dev;
+    if (a_bits < 16) {
+        e = zo_launch_fq_act(X_dev, xhat, M, K, a_bits, a_sym, dtype, nullptr, nullptr, nullptr, st);
+        if (e != hipSuccess) return ZO_EHIP;
+        xin = xhat;
+    }
+    zo_gemm_args a{};
+    a.X = xin; a.W = what; a.Y = Y_dev; a.bias = bias_dev;
+    a.M = M; a.N = N; a.K = K; a.batch = 1; a.dtype = dtype;
+    return zo_launch_gemm(a, st) == hipSuccess ? ZO_OK : ZO_EHIP;
+}
+
+zo_status zo_gemm_nt(const void* X_dev, const void* W_dev, void* Y_dev, int32_t M, int32_t N, int32_t K,
+                     int32_t dtype, void* hip_stream)
+{
+    if (!X_dev || !W_dev || !Y_dev || M < 0 || N < 0 || K <= 0) return ZO_EINVAL;
+    if (dtype != ZO_ACT_FP32 && dtype != ZO_ACT_BF16) return ZO_EINVAL;
+    if (K & 7) return ZO_ESHAPE;
+    if (!aligned16(X_dev) || !aligned16(W_dev) || !aligned16(Y_dev)) return ZO_EALIGN;
+    zo_gemm_args a{};
+    a.X = X_dev; a.W = W_dev; a.Y = Y_dev;
+    a.M = M; a.N = N; a.K = K; a.batch = 1; a.dtype = dtype;
+    return zo_launch_gemm(a, (hipStream_t)hip_stream) == hipSuccess ? ZO_OK : ZO_EHIP;
+}
+
+}  // extern "C"

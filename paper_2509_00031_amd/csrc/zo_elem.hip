@@ -1,0 +1,348 @@
+// Streaming (HBM-bound) kernels of the ZO-QAT step: the seeded update of Eq. 3, the weight
+// fake-quantizer Q(W +- eps u) of Eq. 2, the per-token activation quantizer, and the debug
+// materialisation of the perturbation stream.  gfx950, wave64.
+#include "zo_device.h"
+#include "zo_internal.h"
+
+static inline zo_stream make_stream(uint64_t seed, int32_t tid)
+{
+    zo_stream s;
+    s.k0 = (uint32_t)seed;
+    s.k1 = (uint32_t)(seed >> 32);
+    s.tensor_id = (uint32_t)tid;
+    return s;
+}
+
+static inline int grid_for(int64_t items, int per_block, int max_blocks)
+{
+    int64_t b = (items + per_block - 1) / per_block;
+    if (b < 1) b = 1;
+    if (b > max_blocks) b = max_blocks;
+    return (int)b;
+}
+
+// ---------------------------------------------------------------------------------------------
+// perturbation stream, materialised (tests only)
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void zo_philox_words_kernel(zo_stream s, int64_t nwords, uint32_t* out)
+{
+    int64_t nblk = (nwords + 3) >> 2;
+    for (int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x; b < nblk; b += (int64_t)gridDim.x * 256) {
+        uint32_t w[4];
+        zo_philox(s, (uint64_t)b, w);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (4 * b + i < nwords) out[4 * b + i] = w[i];
+    }
+}
+
+__global__ __launch_bounds__(256) void zo_normal_kernel(zo_stream s, int64_t start, int64_t n, float* out)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
+        out[i] = zo_z1(s, (uint64_t)(start + i));
+}
+
+hipError_t zo_launch_philox_words(uint64_t seed, int32_t tid, int64_t nwords, uint32_t* out, hipStream_t st)
+{
+    if (nwords == 0) return hipSuccess;
+    zo_philox_words_kernel<<<grid_for((nwords + 3) / 4, 256, 4096), 256, 0, st>>>(make_stream(seed, tid), nwords, out);
+    return hipGetLastError();
+}
+
+hipError_t zo_launch_normal(uint64_t seed, int32_t tid, int64_t start, int64_t n, float* out, hipStream_t st)
+{
+    if (n == 0) return hipSuccess;
+    zo_normal_kernel<<<grid_for(n, 256, 4096), 256, 0, st>>>(make_stream(seed, tid), start, n, out);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// update (Eq. 3): w_i <- fma(-c, u_i, w_i).  8 B of HBM traffic per parameter, u regenerated.
+// One thread owns one Philox block = 8 consecutive parameters (two 16-byte accesses).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void zo_update_kernel(float* __restrict__ w, int64_t numel, zo_stream s,
+                                                        const float* __restrict__ coeff_dev, float coeff_host)
+{
+    const float negc = -(coeff_dev ? *coeff_dev : coeff_host);
+    const int64_t nblk = numel >> 3;
+    for (int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x; b < nblk; b += (int64_t)gridDim.x * 256) {
+        float v[8], z[8];
+        zo_load8(w + 8 * b, v);
+        zo_z8(s, (uint64_t)b, z);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = __builtin_fmaf(negc, z[i], v[i]);
+        zo_store8(w + 8 * b, v);
+    }
+    // ragged tail (numel not a multiple of 8)
+    if (blockIdx.x == 0) {
+        int64_t i = 8 * nblk + threadIdx.x;
+        if (i < numel) w[i] = __builtin_fmaf(negc, zo_z1(s, (uint64_t)i), w[i]);
+    }
+}
+
+hipError_t zo_launch_update(float* w, int64_t numel, uint64_t seed, int32_t tid,
+                            const float* coeff_dev, float coeff_host, hipStream_t st)
+{
+    if (numel == 0) return hipSuccess;
+    zo_update_kernel<<<grid_for(numel >> 3, 256, 256 * 16), 256, 0, st>>>(w, numel, make_stream(seed, tid), coeff_dev, coeff_host);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// weight fake-quantizer: Q(W + eps u) and/or Q(W - eps u), de-quantized, in GEMM operand type.
+// One thread owns 8 consecutive k (one Philox block); a group of G consecutive k is G/8 = GL
+// neighbouring lanes, reduced with cross-lane shuffles.  u is generated once for both branches.
+// HBM traffic: 4 B read + sizeof(TO) written per branch and element.
+// ---------------------------------------------------------------------------------------------
+template <typename TO, int GL, bool DEBUG>
+__device__ __forceinline__ void fq_branch(const float v[8], int bits, TO* out, int64_t b, bool active,
+                                          uint8_t* codes, float* step, int32_t* zp, int lane)
+{
+    float o[8];
+    if (bits == 0) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] = v[i];
+    } else {
+        float mn = v[0], mx = v[0];
+#pragma unroll
+        for (int i = 1; i < 8; ++i) { mn = fminf(mn, v[i]); mx = fmaxf(mx, v[i]); }
+        mn = zo_group_min<GL>(mn);
+        mx = zo_group_max<GL>(mx);
+        zo_qparams q = zo_qparams_asym(mn, mx, bits);
+        float c[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { c[i] = zo_code(q, v[i]); o[i] = zo_dequant(q, c[i]); }
+        if (DEBUG && active) {
+            if (codes) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) codes[8 * b + i] = (uint8_t)c[i];
+            }
+            if ((lane & (GL - 1)) == 0) {
+                if (step) step[b / GL] = q.step;
+                if (zp) zp[b / GL] = (int32_t)q.zp;
+            }
+        }
+    }
+    if (active && out) zo_store8(out + 8 * b, o);
+}
+
+template <typename TO, int GL, bool DEBUG>
+__global__ __launch_bounds__(256) void zo_fq_weight_kernel(const float* __restrict__ W, int64_t nblk, zo_stream s,
+                                                           float eps, int bits, TO* __restrict__ out_p, TO* __restrict__ out_m,
+                                                           uint8_t* codes, float* step, int32_t* zp)
+{
+    const int lane = threadIdx.x & 63;
+    // trip count uniform over the wave: every lane takes part in the shuffles
+    const int64_t first = (int64_t)blockIdx.x * 256 + (threadIdx.x & ~63);
+    for (int64_t base = first; base < nblk; base += (int64_t)gridDim.x * 256) {
+        const int64_t b = base + lane;
+        const bool active = b < nblk;
+        float w[8], z[8];
+        if (active) {
+            zo_load8(W + 8 * b, w);
+            if (eps != 0.0f) zo_z8(s, (uint64_t)b, z);
+        }
+        if (!active || eps == 0.0f) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { z[i] = 0.0f; if (!active) w[i] = 0.0f; }
+        }
+        if (out_p || DEBUG) {
+            float v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = __builtin_fmaf(eps, z[i], w[i]);
+            fq_branch<TO, GL, DEBUG>(v, bits, out_p, b, active, codes, step, zp, lane);
+        }
+        if (out_m) {
+            float v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = __builtin_fmaf(-eps, z[i], w[i]);
+            fq_branch<TO, GL, false>(v, bits, out_m, b, active, nullptr, nullptr, nullptr, lane);
+        }
+    }
+}
+
+// Groups wider than 512 elements (per-channel quantization): one workgroup per output channel,
+// two sweeps over the row (range, then codes); the stream is regenerated in the second sweep.
+template <typename TO, bool DEBUG>
+__global__ __launch_bounds__(256) void zo_fq_weight_row_kernel(const float* __restrict__ W, int K, int group, zo_stream s,
+                                                               float eps, int bits, TO* __restrict__ out_p, TO* __restrict__ out_m,
+                                                               uint8_t* codes, float* step, int32_t* zp)
+{
+    __shared__ float red[4][4];
+    const int64_t grp = blockIdx.x;                 // group index over the whole matrix
+    const int64_t b0 = grp * (group / 8);           // first Philox block of the group
+    const int nb = group / 8;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float mnp = INFINITY, mxp = -INFINITY, mnm = INFINITY, mxm = -INFINITY;
+    for (int j = threadIdx.x; j < nb; j += 256) {
+        float w[8], z[8];
+        zo_load8(W + 8 * (b0 + j), w);
+        if (eps != 0.0f) zo_z8(s, (uint64_t)(b0 + j), z);
+        else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) z[i] = 0.0f;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            float vp = __builtin_fmaf(eps, z[i], w[i]), vm = __builtin_fmaf(-eps, z[i], w[i]);
+            mnp = fminf(mnp, vp); mxp = fmaxf(mxp, vp); mnm = fminf(mnm, vm); mxm = fmaxf(mxm, vm);
+        }
+    }
+    mnp = zo_group_min<64>(mnp); mxp = zo_group_max<64>(mxp);
+    mnm = zo_group_min<64>(mnm); mxm = zo_group_max<64>(mxm);
+    if (lane == 0) { red[wave][0] = mnp; red[wave][1] = mxp; red[wave][2] = mnm; red[wave][3] = mxm; }
+    __syncthreads();
+    mnp = fminf(fminf(red[0][0], red[1][0]), fminf(red[2][0], red[3][0]));
+    mxp = fmaxf(fmaxf(red[0][1], red[1][1]), fmaxf(red[2][1], red[3][1]));
+    mnm = fminf(fminf(red[0][2], red[1][2]), fminf(red[2][2], red[3][2]));
+    mxm = fmaxf(fmaxf(red[0][3], red[1][3]), fmaxf(red[2][3], red[3][3]));
+    zo_qparams qp = zo_qparams_asym(mnp, mxp, bits), qm = zo_qparams_asym(mnm, mxm, bits);
+    if (DEBUG && threadIdx.x == 0) {
+        if (step) step[grp] = qp.step;
+        if (zp) zp[grp] = (int32_t)qp.zp;
+    }
+    for (int j = threadIdx.x; j < nb; j += 256) {
+        float w[8], z[8], o[8];
+        zo_load8(W + 8 * (b0 + j), w);
+        if (eps != 0.0f) zo_z8(s, (uint64_t)(b0 + j), z);
+        else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) z[i] = 0.0f;
+        }
+        if (out_p || DEBUG) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                float c = zo_code(qp, __builtin_fmaf(eps, z[i], w[i]));
+                o[i] = zo_dequant(qp, c);
+                if (DEBUG && codes) codes[8 * (b0 + j) + i] = (uint8_t)c;
+            }
+            if (out_p) zo_store8(out_p + 8 * (b0 + j), o);
+        }
+        if (out_m) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) o[i] = zo_dequant(qm, zo_code(qm, __builtin_fmaf(-eps, z[i], w[i])));
+            zo_store8(out_m + 8 * (b0 + j), o);
+        }
+    }
+}
+
+bool zo_fq_weight_supported(int32_t K, int32_t bits, int32_t group)
+{
+    if (K <= 0 || (K & 7)) return false;
+    if (bits == 0) return true;
+    if (bits < 1 || bits > 8) return false;
+    if (group == 0) group = K;
+    if (group <= 0 || (group & 7) || K % group) return false;
+    return true;
+}
+
+template <typename TO, int GL>
+static hipError_t launch_fq_weight_gl(const float* W, int64_t nblk, zo_stream s, float eps, int bits, TO* op, TO* om,
+                                      uint8_t* codes, float* step, int32_t* zp, hipStream_t st)
+{
+    const int grid = grid_for(nblk, 256, 256 * 16);
+    if (codes || step || zp)
+        zo_fq_weight_kernel<TO, GL, true><<<grid, 256, 0, st>>>(W, nblk, s, eps, bits, op, om, codes, step, zp);
+    else
+        zo_fq_weight_kernel<TO, GL, false><<<grid, 256, 0, st>>>(W, nblk, s, eps, bits, op, om, nullptr, nullptr, nullptr);
+    return hipGetLastError();
+}
+
+template <typename TO>
+static hipError_t launch_fq_weight_t(const float* W, int32_t N, int32_t K, int32_t bits, int32_t group, zo_stream s, float eps,
+                                     TO* op, TO* om, uint8_t* codes, float* step, int32_t* zp, hipStream_t st)
+{
+    const int64_t nblk = (int64_t)N * K / 8;
+    if (nblk == 0) return hipSuccess;
+    if (bits == 0) return launch_fq_weight_gl<TO, 1>(W, nblk, s, eps, 0, op, om, nullptr, nullptr, nullptr, st);
+    if (group == 0) group = K;
+    const int gl = group / 8;
+    const bool pow2 = (gl & (gl - 1)) == 0;
+    if (pow2 && gl <= 64) {
+        switch (gl) {
+            case 1:  return launch_fq_weight_gl<TO, 1>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
+            case 2:  return launch_fq_weight_gl<TO, 2>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
+            case 4:  return launch_fq_weight_gl<TO, 4>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
+            case 8:  return launch_fq_weight_gl<TO, 8>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
+            case 16: return launch_fq_weight_gl<TO, 16>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
+            case 32: return launch_fq_weight_gl<TO, 32>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
+            default: return launch_fq_weight_gl<TO, 64>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
+        }
+    }
+    const int64_t ngroups = (int64_t)N * (K / group);
+    if (ngroups > 0x7FFFFFFF) return hipErrorInvalidValue;
+    if (codes || step || zp)
+        zo_fq_weight_row_kernel<TO, true><<<(int)ngroups, 256, 0, st>>>(W, K, group, s, eps, bits, op, om, codes, step, zp);
+    else
+        zo_fq_weight_row_kernel<TO, false><<<(int)ngroups, 256, 0, st>>>(W, K, group, s, eps, bits, op, om, nullptr, nullptr, nullptr);
+    return hipGetLastError();
+}
+
+hipError_t zo_launch_fq_weight(const float* W, int32_t N, int32_t K, int32_t bits, int32_t group,
+                               uint64_t seed, int32_t tid, float eps, int dtype,
+                               void* out_plus, void* out_minus,
+                               uint8_t* codes, float* step, int32_t* zp, hipStream_t st)
+{
+    zo_stream s = make_stream(seed, tid);
+    if (dtype == ZO_T_BF16)
+        return launch_fq_weight_t<zo_bf16>(W, N, K, bits, group, s, eps, (zo_bf16*)out_plus, (zo_bf16*)out_minus, codes, step, zp, st);
+    return launch_fq_weight_t<float>(W, N, K, bits, group, s, eps, (float*)out_plus, (float*)out_minus, codes, step, zp, st);
+}
+
+// ---------------------------------------------------------------------------------------------
+// per-token activation fake-quantizer: one wavefront per row; range sweep, then code sweep
+// (the second sweep re-reads the row from cache).
+// ---------------------------------------------------------------------------------------------
+template <typename T, bool DEBUG>
+__global__ __launch_bounds__(256) void zo_fq_act_kernel(const T* __restrict__ X, T* __restrict__ Xhat, int M, int K, int bits, int sym,
+                                                        int16_t* codes, float* step, int32_t* zp)
+{
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= M) return;                            // whole wave leaves together
+    const T* x = X + (int64_t)row * K;
+    float mn = INFINITY, mx = -INFINITY;
+    for (int c = lane * 8; c < K; c += 512) {
+        float v[8];
+        zo_load8(x + c, v);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (sym) mx = fmaxf(mx, fabsf(v[i]));
+            else { mn = fminf(mn, v[i]); mx = fmaxf(mx, v[i]); }
+        }
+    }
+    mn = zo_group_min<64>(mn);
+    mx = zo_group_max<64>(mx);
+    zo_qparams q = sym ? zo_qparams_sym(mx, bits) : zo_qparams_asym(mn, mx, bits);
+    if (DEBUG && lane == 0) {
+        if (step) step[row] = q.step;
+        if (zp) zp[row] = (int32_t)q.zp;
+    }
+    for (int c = lane * 8; c < K; c += 512) {
+        float v[8], o[8];
+        zo_load8(x + c, v);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            float cd = zo_code(q, v[i]);
+            o[i] = zo_dequant(q, cd);
+            if (DEBUG && codes) codes[(int64_t)row * K + c + i] = (int16_t)cd;
+        }
+        if (Xhat) zo_store8(Xhat + (int64_t)row * K + c, o);
+    }
+}
+
+hipError_t zo_launch_fq_act(const void* X, void* Xhat, int32_t M, int32_t K, int32_t bits, int32_t sym, int dtype,
+                            int16_t* codes, float* step, int32_t* zp, hipStream_t st)
+{
+    if (M == 0) return hipSuccess;
+    const int grid = (M + 3) / 4;
+    const bool dbg = codes || step || zp;
+    if (dtype == ZO_T_BF16) {
+        if (dbg) zo_fq_act_kernel<zo_bf16, true><<<grid, 256, 0, st>>>((const zo_bf16*)X, (zo_bf16*)Xhat, M, K, bits, sym, codes, step, zp);
+        else zo_fq_act_kernel<zo_bf16, false><<<grid, 256, 0, st>>>((const zo_bf16*)X, (zo_bf16*)Xhat, M, K, bits, sym, nullptr, nullptr, nullptr);
+    } else {
+        if (dbg) zo_fq_act_kernel<float, true><<<grid, 256, 0, st>>>((const float*)X, (float*)Xhat, M, K, bits, sym, codes, step, zp);
+        else zo_fq_act_kernel<float, false><<<grid, 256, 0, st>>>((const float*)X, (float*)Xhat, M, K, bits, sym, nullptr, nullptr, nullptr);
+    }
+    return hipGetLastError();
+}

@@ -1,0 +1,268 @@
+// GEMM of the quantized linears: Y[M][N] = X[M][K] * W[N][K]^T, both operands already
+// de-quantized (X^ by the per-token quantizer, W^ = Q(W +- eps u) by the weight fake-quantizer).
+// bf16 operands run on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate);
+// fp32 operands (parity mode) use a plain LDS-tiled FMA kernel.
+#include "zo_device.h"
+#include "zo_internal.h"
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// ---------------------------------------------------------------------------------------------
+// bf16 MFMA kernel.
+//   workgroup = 256 threads = 4 waves as 2 (m) x 2 (n); block tile BM x BN, K step 64.
+//   LDS tile rows are 64 bf16 = 128 B = eight 16-byte chunks; chunk c of row r is stored at
+//   chunk slot c ^ f(r), f(r) = (r + (r >> 3)) & 7, which spreads the 16-byte fragment reads of
+//   32 consecutive rows over all banks.  Two LDS buffers: the next K tile is fetched from global
+//   memory into registers while the current one feeds the matrix cores.
+//   The matrix instruction is issued with W as its first operand and X as its second, so each
+//   lane ends up with 4 consecutive n of one row m: outputs are stored as 8- or 16-byte vectors.
+// ---------------------------------------------------------------------------------------------
+template <int BM, int BN> struct gemm_cfg {
+    static constexpr int BK = 64;
+    static constexpr int WM = BM / 2, WN = BN / 2;
+    static constexpr int TM = WM / 32, TN = WN / 32;
+    static constexpr int XCH = BM * 8 / 256;         // 16-byte chunks per thread for the X tile
+    static constexpr int WCH = BN * 8 / 256;
+    static constexpr int LDS_BYTES = 2 * (BM + BN) * 128;
+};
+
+__device__ __forceinline__ int swz(int row) { return (row + (row >> 3)) & 7; }
+
+template <int BM, int BN, typename TY>
+__global__ __launch_bounds__(256) void zo_gemm_bf16_kernel(zo_gemm_args a)
+{
+    using C = gemm_cfg<BM, BN>;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    // buffer b: X tile at b*(BM+BN)*128, W tile right after it
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int M = a.M, N = a.N, K = a.K;
+    const int tiles_n = (N + BN - 1) / BN;
+    const int tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x % tiles_n;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int bz = blockIdx.z;
+    const zo_bf16* X = (const zo_bf16*)a.X + bz * a.strideX;
+    const zo_bf16* W = (const zo_bf16*)a.W + bz * a.strideW;
+
+    // global -> register staging: thread owns chunk (row = tid/8 + 32*i, c = tid%8)
+    const int lrow = tid >> 3, lc = tid & 7;
+    uint4 xr[C::XCH], wr[C::WCH];
+    auto fetch = [&](int kt) {
+        const int k = kt * C::BK + lc * 8;
+        const bool kin = k < K;
+#pragma unroll
+        for (int i = 0; i < C::XCH; ++i) {
+            int r = m0 + lrow + 32 * i;
+            r = r < M ? r : M - 1;
+            xr[i] = kin ? *reinterpret_cast<const uint4*>(X + (int64_t)r * K + k) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < C::WCH; ++i) {
+            int r = n0 + lrow + 32 * i;
+            r = r < N ? r : N - 1;
+            wr[i] = kin ? *reinterpret_cast<const uint4*>(W + (int64_t)r * K + k) : make_uint4(0, 0, 0, 0);
+        }
+    };
+    auto stash = [&](int buf) {
+        unsigned char* xb = lds + buf * (BM + BN) * 128;
+        unsigned char* wb = xb + BM * 128;
+#pragma unroll
+        for (int i = 0; i < C::XCH; ++i) {
+            int r = lrow + 32 * i;
+            *reinterpret_cast<uint4*>(xb + r * 128 + ((lc ^ swz(r)) << 4)) = xr[i];
+        }
+#pragma unroll
+        for (int i = 0; i < C::WCH; ++i) {
+            int r = lrow + 32 * i;
+            *reinterpret_cast<uint4*>(wb + r * 128 + ((lc ^ swz(r)) << 4)) = wr[i];
+        }
+    };
+
+    f32x16 acc[C::TN][C::TM];
+#pragma unroll
+    for (int i = 0; i < C::TN; ++i)
+#pragma unroll
+        for (int j = 0; j < C::TM; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    const int nk = (K + C::BK - 1) / C::BK;
+    fetch(0);
+    stash(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nk) fetch(kt + 1);
+        const unsigned char* xb = lds + buf * (BM + BN) * 128;
+        const unsigned char* wb = xb + BM * 128;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const int c = 2 * ks + (lane >> 5);
+            bf16x8 xf[C::TM], wf[C::TN];
+#pragma unroll
+            for (int j = 0; j < C::TM; ++j) {
+                int r = wm * C::WM + j * 32 + (lane & 31);
+                xf[j] = *reinterpret_cast<const bf16x8*>(xb + r * 128 + ((c ^ swz(r)) << 4));
+            }
+#pragma unroll
+            for (int i = 0; i < C::TN; ++i) {
+                int r = wn * C::WN + i * 32 + (lane & 31);
+                wf[i] = *reinterpret_cast<const bf16x8*>(wb + r * 128 + ((c ^ swz(r)) << 4));
+            }
+#pragma unroll
+            for (int i = 0; i < C::TN; ++i)
+#pragma unroll
+                for (int j = 0; j < C::TM; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0);
+        }
+        if (kt + 1 < nk) {
+            stash(buf ^ 1);          // the other buffer was last read before the previous barrier
+            __syncthreads();
+        }
+    }
+
+    // epilogue: lane holds, per 32x32 tile, rows n = 8*(r/4) + 4*(lane/32) + r%4 of column m = lane%32
+    TY* Y = (TY*)a.Y + bz * a.strideY;
+    const float* bias = a.bias ? a.bias + bz * a.strideBias : nullptr;
+    const zo_bf16* res = a.residual ? (const zo_bf16*)a.residual + bz * a.strideRes : nullptr;
+    const bool vec_ok = (N & 3) == 0;
+#pragma unroll
+    for (int j = 0; j < C::TM; ++j) {
+        const int m = m0 + wm * C::WM + j * 32 + (lane & 31);
+        if (m >= M) continue;
+#pragma unroll
+        for (int i = 0; i < C::TN; ++i) {
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+                const int n = n0 + wn * C::WN + i * 32 + rg * 8 + (lane >> 5) * 4;
+                if (n >= N) continue;
+                float v[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = acc[i][j][rg * 4 + e];
+                const int64_t off = (int64_t)m * N + n;
+                if (vec_ok && n + 3 < N) {
+                    if (bias) {
+                        float4 b4 = *reinterpret_cast<const float4*>(bias + n);
+                        v[0] += b4.x; v[1] += b4.y; v[2] += b4.z; v[3] += b4.w;
+                    }
+                    if (a.relu) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.0f);
+                    }
+                    if (res) {
+                        uint2 r2 = *reinterpret_cast<const uint2*>(res + off);
+                        v[0] += zo_bf16_lo(r2.x); v[1] += zo_bf16_hi(r2.x);
+                        v[2] += zo_bf16_lo(r2.y); v[3] += zo_bf16_hi(r2.y);
+                    }
+                    if constexpr (sizeof(TY) == 4) {
+                        *reinterpret_cast<float4*>((float*)Y + off) = make_float4(v[0], v[1], v[2], v[3]);
+                    } else {
+                        uint2 o;
+                        o.x = zo_pack_bf16x2(v[0], v[1]);
+                        o.y = zo_pack_bf16x2(v[2], v[3]);
+                        *reinterpret_cast<uint2*>((zo_bf16*)Y + off) = o;
+                    }
+                } else {
+                    for (int e = 0; e < 4 && n + e < N; ++e) {
+                        float t = v[e];
+                        if (bias) t += bias[n + e];
+                        if (a.relu) t = fmaxf(t, 0.0f);
+                        if (res) t += (float)res[off + e];
+                        zo_store(Y + off + e, t);
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// fp32 kernel (parity mode): 64 x 64 tile, K step 16, 256 threads x (4 x 4) outputs.
+// ---------------------------------------------------------------------------------------------
+template <typename TY>
+__global__ __launch_bounds__(256) void zo_gemm_f32_kernel(zo_gemm_args a)
+{
+    __shared__ float xs[16][64 + 4];
+    __shared__ float ws[16][64 + 4];
+    const int tid = threadIdx.x;
+    const int M = a.M, N = a.N, K = a.K;
+    const int tiles_n = (N + 63) / 64;
+    const int m0 = (blockIdx.x / tiles_n) * 64, n0 = (blockIdx.x % tiles_n) * 64;
+    const int bz = blockIdx.z;
+    const float* X = (const float*)a.X + bz * a.strideX;
+    const float* W = (const float*)a.W + bz * a.strideW;
+    const int tx = tid & 15, ty = tid >> 4;          // outputs m = ty*4.., n = tx*4..
+    const int lr = tid >> 2, lk = (tid & 3) * 4;     // loader: row lr (0..63), k offset lk
+    float acc[4][4] = {};
+    for (int k0 = 0; k0 < K; k0 += 16) {
+        float4 xv = make_float4(0, 0, 0, 0), wv = make_float4(0, 0, 0, 0);
+        if (k0 + lk < K) {                            // K is a multiple of 4
+            int rm = m0 + lr; rm = rm < M ? rm : M - 1;
+            int rn = n0 + lr; rn = rn < N ? rn : N - 1;
+            xv = *reinterpret_cast<const float4*>(X + (int64_t)rm * K + k0 + lk);
+            wv = *reinterpret_cast<const float4*>(W + (int64_t)rn * K + k0 + lk);
+        }
+        __syncthreads();
+        xs[lk + 0][lr] = xv.x; xs[lk + 1][lr] = xv.y; xs[lk + 2][lr] = xv.z; xs[lk + 3][lr] = xv.w;
+        ws[lk + 0][lr] = wv.x; ws[lk + 1][lr] = wv.y; ws[lk + 2][lr] = wv.z; ws[lk + 3][lr] = wv.w;
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            float xm[4], wn[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { xm[i] = xs[k][ty * 4 + i]; wn[i] = ws[k][tx * 4 + i]; }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_fmaf(xm[i], wn[j], acc[i][j]);
+        }
+    }
+    TY* Y = (TY*)a.Y + bz * a.strideY;
+    const float* bias = a.bias ? a.bias + bz * a.strideBias : nullptr;
+    const float* res = a.residual ? (const float*)a.residual + bz * a.strideRes : nullptr;
+    for (int i = 0; i < 4; ++i) {
+        const int m = m0 + ty * 4 + i;
+        if (m >= M) continue;
+        for (int j = 0; j < 4; ++j) {
+            const int n = n0 + tx * 4 + j;
+            if (n >= N) continue;
+            float t = acc[i][j];
+            if (bias) t += bias[n];
+            if (a.relu) t = fmaxf(t, 0.0f);
+            if (res) t += res[(int64_t)m * N + n];
+            Y[(int64_t)m * N + n] = t;
+        }
+    }
+}
+
+template <int BM, int BN>
+static hipError_t launch_bf16(const zo_gemm_args& a, hipStream_t st)
+{
+    using C = gemm_cfg<BM, BN>;
+    const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
+    dim3 grid(tiles, 1, a.batch);
+    hipError_t e;
+    if (a.out_f32) {
+        e = hipFuncSetAttribute((const void*)zo_gemm_bf16_kernel<BM, BN, float>, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        zo_gemm_bf16_kernel<BM, BN, float><<<grid, 256, C::LDS_BYTES, st>>>(a);
+    } else {
+        e = hipFuncSetAttribute((const void*)zo_gemm_bf16_kernel<BM, BN, zo_bf16>, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        zo_gemm_bf16_kernel<BM, BN, zo_bf16><<<grid, 256, C::LDS_BYTES, st>>>(a);
+    }
+    return hipGetLastError();
+}
+
+hipError_t zo_launch_gemm(const zo_gemm_args& a, hipStream_t st)
+{
+    if (a.M == 0 || a.N == 0) return hipSuccess;
+    if (a.dtype == ZO_T_BF16) {
+        if ((int64_t)a.M * a.N >= (int64_t)256 * 256 * 128) return launch_bf16<256, 256>(a, st);
+        return launch_bf16<128, 128>(a, st);
+    }
+    const int tiles = ((a.M + 63) / 64) * ((a.N + 63) / 64);
+    zo_gemm_f32_kernel<float><<<dim3(tiles, 1, a.batch), 256, 0, st>>>(a);
+    return hipGetLastError();
+}

@@ -1,0 +1,67 @@
+// Host-side launchers of the HIP kernels (internal to the library; the public C ABI is zoqat.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+enum { ZO_T_F32 = 0, ZO_T_BF16 = 1 };
+
+static inline size_t zo_tsize(int dtype) { return dtype == ZO_T_BF16 ? 2 : 4; }
+
+// ---- perturbation stream ---------------------------------------------------------------------
+hipError_t zo_launch_philox_words(uint64_t seed, int32_t tid, int64_t nwords, uint32_t* out, hipStream_t st);
+hipError_t zo_launch_normal(uint64_t seed, int32_t tid, int64_t start, int64_t n, float* out, hipStream_t st);
+
+// ---- update (Eq. 3) ----------------------------------------------------------------------------
+hipError_t zo_launch_update(float* w, int64_t numel, uint64_t seed, int32_t tid,
+                            const float* coeff_dev, float coeff_host, hipStream_t st);
+
+// ---- weight fake-quantizer ---------------------------------------------------------------------
+// Emits Q(W + eps u) into out_plus and/or Q(W - eps u) into out_minus (storage type dtype); either
+// may be NULL.  bits = 0: perturbed weights, not quantized.  Debug outputs describe the '+' branch.
+bool zo_fq_weight_supported(int32_t K, int32_t bits, int32_t group);
+hipError_t zo_launch_fq_weight(const float* W, int32_t N, int32_t K, int32_t bits, int32_t group,
+                               uint64_t seed, int32_t tid, float eps, int dtype,
+                               void* out_plus, void* out_minus,
+                               uint8_t* codes, float* step, int32_t* zp, hipStream_t st);
+
+// ---- per-token activation fake-quantizer -------------------------------------------------------
+hipError_t zo_launch_fq_act(const void* X, void* Xhat, int32_t M, int32_t K, int32_t bits, int32_t sym, int dtype,
+                            int16_t* codes, float* step, int32_t* zp, hipStream_t st);
+
+// ---- GEMM: Y[b] = X[b] * W[b]^T (+bias[b]) (relu) (+residual[b]); batch over branches -----------
+struct zo_gemm_args {
+    const void* X; const void* W; void* Y;
+    const float* bias;          // [N] fp32 or NULL
+    const void* residual;       // [M][N] storage type or NULL
+    int32_t M, N, K;
+    int32_t batch;              // 1 or 2
+    int64_t strideX, strideW, strideY, strideBias, strideRes;   // elements between batch entries
+    int32_t relu;
+    int32_t out_f32;            // 1: Y is fp32 whatever the operand type
+    int dtype;                  // operand (and default output) storage type
+};
+hipError_t zo_launch_gemm(const zo_gemm_args& a, hipStream_t st);
+
+// ---- the rest of the decoder forward -----------------------------------------------------------
+// x[t] = rt(fma(eps, u(tok row), tok_emb[id]) (+ fma(eps, u(pos row), pos_emb[t % S])))
+hipError_t zo_launch_embed(const int32_t* ids, const float* tok_emb, const float* pos_emb, void* out,
+                           int32_t M, int32_t S, int32_t d, int32_t vocab, uint64_t seed, int32_t tid_tok, int32_t tid_pos,
+                           float eps_tok, float eps_pos, int dtype, hipStream_t st);
+// RMSNorm (beta = NULL) or LayerNorm; gamma/beta are already perturbed fp32 vectors
+hipError_t zo_launch_norm(const void* x, const float* gamma, const float* beta, void* out,
+                          int32_t M, int32_t d, float eps, int dtype, hipStream_t st);
+hipError_t zo_launch_rope(void* q, void* k, const float* cos_tab, const float* sin_tab,
+                          int32_t M, int32_t S, int32_t H, int32_t dh, int64_t row_stride, int dtype, hipStream_t st);
+hipError_t zo_launch_attention(const void* q, const void* k, const void* v, void* out,
+                               int32_t B, int32_t S, int32_t H, int32_t dh, int64_t row_stride, int dtype, hipStream_t st);
+hipError_t zo_launch_swiglu(const void* gate, const void* up, void* out, int64_t rows, int32_t cols,
+                            int64_t in_stride, int dtype, hipStream_t st);
+// row_loss[t] = logsumexp(logits[t]) - logits[t][ids[t+1]] (0 for the last position of a sequence)
+hipError_t zo_launch_ce_rows(const float* logits, const int32_t* ids, float* row_loss,
+                             int32_t M, int32_t S, int32_t V, hipStream_t st);
+hipError_t zo_launch_sqerr_rows(const void* y, const float* target, float* row_loss, int32_t M, int32_t N, int dtype, hipStream_t st);
+// loss = sum(row_loss) * scale, fixed summation order
+hipError_t zo_launch_reduce_loss(const float* row_loss, int32_t M, float scale, float* loss, hipStream_t st);
+// out = { L+, L-, g, lr*g } from loss[0], loss[1]
+hipError_t zo_launch_projected_grad(const float* loss2, float eps, float lr, float* out4, hipStream_t st);

@@ -1,0 +1,60 @@
+"""GPU parity: the contraction of the quantized linears and one fake-quantized linear layer.
+Tolerances: relative l2 error 1e-4 with fp32 storage, 1e-2 with bf16 storage."""
+import numpy as np
+import pytest
+
+from oracle import zo_oracle as orc
+from paper_2509_00031_amd import synth
+from gpu_util import gpu, to_dev, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("M,N,K", [(8, 256, 256), (300, 200, 328), (1, 1, 8), (257, 513, 1024), (1024, 768, 512)])
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_gemm_nt(M, N, K, dtype):
+    torch, zo = gpu()
+    X = synth.activations((M, K), 51)
+    W = synth.weights((N, K), 52, scale=1.0)
+    if dtype == "bf16":
+        X, W = orc.bf16_round(X), orc.bf16_round(W)
+        td = torch.bfloat16
+    else:
+        td = torch.float32
+    Y = zo.zo_gemm_nt(to_dev(X, torch, td), to_dev(W, torch, td)).float().cpu().numpy()
+    ref = X.astype(np.float64) @ W.astype(np.float64).T
+    # element-wise: fp32 accumulation over K terms, then storage rounding
+    tol = (2.0 ** -8 if dtype == "bf16" else 2.0 ** -20) * np.abs(ref) + 1e-5 * np.sqrt(K)
+    assert np.all(np.abs(Y - ref) <= tol)
+    assert rel_l2(Y, ref) < (4e-3 if dtype == "bf16" else 1e-6)
+
+
+def test_gemm_large_tile_path():
+    torch, zo = gpu()
+    M, N, K = 3000, 2900, 256                      # takes the 256 x 256 tile kernel, ragged in M and N
+    X = orc.bf16_round(synth.activations((M, K), 53))
+    W = orc.bf16_round(synth.weights((N, K), 54, scale=1.0))
+    Y = zo.zo_gemm_nt(to_dev(X, torch, torch.bfloat16), to_dev(W, torch, torch.bfloat16)).float().cpu().numpy()
+    ref = X.astype(np.float64) @ W.astype(np.float64).T
+    assert np.all(np.abs(Y - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-4)
+
+
+@pytest.mark.parametrize("dtype,tol", [("fp32", 1e-4), ("bf16", 1e-2)])
+@pytest.mark.parametrize("M,N,K,wb,g,ab", [(8, 256, 256, 4, 64, 8), (100, 72, 512, 2, 64, 16), (33, 130, 384, 4, 128, 4)])
+def test_linear_fakequant(dtype, tol, M, N, K, wb, g, ab):
+    torch, zo = gpu()
+    X = synth.activations((M, K), 55)
+    W = synth.weights((N, K), 56)
+    bias = synth.weights((N,), 57)
+    bf = dtype == "bf16"
+    if bf:
+        X = orc.bf16_round(X)
+    xd = to_dev(X, torch, torch.bfloat16 if bf else torch.float32)
+    for eps in (1e-3, -1e-3):
+        Y = zo.zo_linear_fakequant(xd, to_dev(W, torch), to_dev(bias, torch), wb, g, ab, 0, seed=11, tensor_id=4,
+                                   eps_signed=eps).float().cpu().numpy()
+        what = orc.fakequant_weight(W, wb, g, 11, 4, np.float32(eps), round_bf16=bf, want_codes=False)["what"]
+        xhat = orc.fakequant_act(X, ab, False, round_bf16=bf, want_codes=False)["xhat"]
+        ref = orc.linear(xhat, what, bias)
+        assert rel_l2(Y, ref) < tol
+        assert np.abs(Y - ref).max() <= (2.0 ** -7 if bf else 1e-5) * np.abs(ref).max()

@@ -1,0 +1,205 @@
+"""GPU parity: whole quantized forward (loss), and the full ZO step (L+, L-, g, updated weights)
+against the oracle on seeded inputs.  Tolerances: losses 1e-3 relative; g 1e-3 relative in fp32
+storage mode (in bf16 mode g is a difference of two losses that agree to ~1e-3 and inherits the
+bf16 rounding noise of every stored activation; the test bounds it against that noise)."""
+import numpy as np
+import pytest
+
+from oracle import zo_oracle as orc
+from paper_2509_00031_amd import synth
+from gpu_util import gpu, to_dev, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+ARCHS = {"llama": 1, "opt": 2}
+
+
+def _setup(zo, torch, arch, act_dtype, B, S, **kw):
+    base = dict(n_layers=2, d_model=128, n_heads=4, d_ffn=256, vocab=509 + 3, max_seq=S, w_bits=4, w_group=64, a_bits=8)
+    base.update(kw)
+    ocfg = orc.Config(ARCHS[arch], act_dtype=act_dtype, **base)
+    cfg = zo.make_config(ARCHS[arch], act_dtype=act_dtype, **base)
+    params = synth.model_params(orc.param_shapes(ocfg), 61)
+    params = [p * (3.0 if p.ndim == 2 else 1.0) for p in params]
+    ids = synth.token_ids(B, S, base["vocab"], 62)
+    gp = [to_dev(p, torch) for p in params]
+    ctx = zo.Context(cfg, gp, B, S)
+    return ocfg, params, ids, gp, ctx
+
+
+TIE_MARGIN = 1e-4      # code units; fp32 round-off of the GPU's activations is ~4e-5 code units at 8 bits
+
+
+def _clean_rows(tie_log, B, S):
+    """Rows whose value cannot have been touched by a rounding tie of an activation code: a code
+    is decided from an fp32 activation that differs in its last bits between the two sides, so a
+    row within TIE_MARGIN of a rounding boundary (as flagged by the oracle alone) may legitimately
+    come out one code apart; causal attention carries the difference to later positions."""
+    dirty = np.zeros(B * S, bool)
+    for m in tie_log:
+        dirty |= m < TIE_MARGIN
+    dirty = np.maximum.accumulate(dirty.reshape(B, S), axis=1).reshape(-1)
+    return ~dirty
+
+
+def _row_rel(a, b):
+    return np.linalg.norm(a.astype(np.float64) - b, axis=1) / np.maximum(np.linalg.norm(b, axis=1), 1e-30)
+
+
+@pytest.mark.parametrize("arch", ["llama", "opt"])
+@pytest.mark.parametrize("act_dtype", [0, 1])
+@pytest.mark.parametrize("a_bits", [16, 8])
+def test_forward_loss_and_layer_outputs(arch, act_dtype, a_bits):
+    torch, zo = gpu()
+    B, S = 3, 40
+    ocfg, params, ids, gp, ctx = _setup(zo, torch, arch, act_dtype, B, S, a_bits=a_bits)
+    idd = to_dev(ids, torch)
+    tol = 1e-2 if act_dtype else 1e-4
+    for eps in (1e-3, -1e-3, 0.0):
+        loss = ctx.zo_forward_quant(idd, None, B, S, seed=9, eps_signed=eps).item()
+        trace, ties = {}, []
+        ref = orc.forward(ocfg, params, ids=ids, seed=9, eps_signed=np.float32(eps), trace=trace, tie_log=ties)
+        assert abs(loss - ref) <= 1e-3 * abs(ref), (loss, ref)
+        td = torch.bfloat16 if act_dtype else torch.float32
+        x = ctx.zo_debug_buffer(2).view(td).float().cpu().numpy().reshape(B * S, -1)
+        h = ctx.zo_debug_buffer(0).view(td).float().cpu().numpy().reshape(B * S, -1)
+        lg = ctx.zo_debug_buffer(1).view(torch.float32).cpu().numpy().reshape(B * S, -1)
+        clean = _clean_rows(ties, B, S)
+        if a_bits == 16:
+            assert clean.all()                       # weight codes come from identical fp32 inputs
+        for got, name in ((x, "l1.out"), (h, "final"), (lg, "logits")):
+            err = _row_rel(got, trace[name])
+            if act_dtype == 0:
+                # fp32 storage: every row that no flagged tie can have touched is within 1e-4
+                if clean.any():
+                    assert err[clean].max() < tol, (name, err[clean].max())
+                assert np.median(err) < 1e-5, (name, np.median(err))
+            elif a_bits == 16:
+                assert err.max() < tol, (name, err.max())
+            else:
+                # bf16 storage: activation codes are decided from bf16 values, identical on both
+                # sides unless a storage rounding upstream fell on the other side of a tie
+                assert np.median(err) < 1e-3 and np.quantile(err, 0.75) < tol, (name, np.quantile(err, 0.75))
+            assert err.max() < 0.1, (name, err.max())        # one flipped code moves a row by step/|row|
+    ctx.close()
+
+
+@pytest.mark.parametrize("arch", ["llama", "opt"])
+@pytest.mark.parametrize("a_bits", [16, 8])
+def test_zo_step_fp32_mode(arch, a_bits):
+    torch, zo = gpu()
+    B, S = 2, 24
+    ocfg, params, ids, gp, ctx = _setup(zo, torch, arch, 0, B, S, a_bits=a_bits)
+    idd = to_dev(ids, torch)
+    eps, lr = 1e-3, 1e-3
+    for step in range(3):
+        before = [p.copy() for p in params]
+        out = ctx.zo_step(idd, None, B, S, seed=100 + step, eps=eps, lr=lr).cpu().numpy()
+        lp, lm, g = orc.zo_step(ocfg, params, 100 + step, eps, lr, ids=ids)
+        assert abs(out[0] - lp) <= 1e-3 * abs(lp) and abs(out[1] - lm) <= 1e-3 * abs(lm)
+        # fp32 storage of a loss ~6.5 resolves 4.8e-7, i.e. 2.4e-4 in g; with activation codes a
+        # rounding tie (see _clean_rows) moves one token's loss by ~1e-3 / (B S)
+        if a_bits == 16:
+            assert abs(out[2] - g) <= 1e-3 * abs(g) + 1e-3, (out[2], g)
+        else:
+            # one flipped code changes a loss by ~1e-3 / (B S); the quotient divides that by 2 eps
+            assert abs(out[2] - g) <= 0.25 * abs(g) + 1.0, (out[2], g)
+        assert out[3] == np.float32(np.float64(np.float32(lr)) * np.float64(out[2]))
+        # the update itself is bit-exact given the coefficient the GPU used
+        for i, p0 in enumerate(before):
+            want = orc.update(p0.copy(), 100 + step, i, np.float32(out[3]))
+            assert np.array_equal(gp[i].cpu().numpy().view(np.uint32), want.view(np.uint32)), i
+        # continue both sides from the GPU's weights so that later steps compare like with like
+        params[:] = [t.cpu().numpy() for t in gp]
+    ctx.close()
+
+
+def test_zo_step_bf16_mode_losses_and_g_noise():
+    torch, zo = gpu()
+    B, S = 2, 32
+    ocfg, params, ids, gp, ctx = _setup(zo, torch, "llama", 1, B, S)
+    out = ctx.zo_step(to_dev(ids, torch), None, B, S, seed=5, eps=1e-3, lr=1e-3).cpu().numpy()
+    lp, lm, g = orc.zo_step(ocfg, params, 5, 1e-3, 1e-3, ids=ids)
+    assert abs(out[0] - lp) <= 1e-3 * abs(lp) and abs(out[1] - lm) <= 1e-3 * abs(lm)
+    # a storage rounding that falls on the other side of a tie moves a loss by ~1e-4 relative
+    # (see test_forward_loss_and_layer_outputs); the difference quotient divides that by 2 eps.
+    # g itself is exactly the quotient of the two GPU losses (test_step_equals_two_forwards_plus_update).
+    assert abs(out[2] - g) <= 2e-4 * abs(lp) / (2 * 1e-3), (out[2], g)
+    ctx.close()
+
+
+def test_step_equals_two_forwards_plus_update():
+    torch, zo = gpu()
+    B, S = 2, 16
+    ocfg, params, ids, gp, ctx = _setup(zo, torch, "opt", 0, B, S)
+    idd = to_dev(ids, torch)
+    lp = ctx.zo_forward_quant(idd, None, B, S, 7, 1e-3).item()
+    lm = ctx.zo_forward_quant(idd, None, B, S, 7, -1e-3).item()
+    out = ctx.zo_step(idd, None, B, S, 7, 1e-3, 1e-2).cpu().numpy()
+    assert out[0] == np.float32(lp) and out[1] == np.float32(lm)
+    assert out[2] == orc.projected_grad(np.float32(lp), np.float32(lm), np.float32(1e-3))
+    ctx.close()
+
+
+def test_lightweight_updates_only_trainable_tensors():
+    torch, zo = gpu()
+    B, S = 2, 16
+    base = dict(n_layers=2, d_model=128, n_heads=4, d_ffn=256, vocab=512, max_seq=S, w_bits=4, w_group=64, a_bits=4)
+    ocfg = orc.Config(1, act_dtype=0, lightweight=1, **base)
+    cfg = zo.make_config(1, act_dtype=0, lightweight=1, **base)
+    shapes = orc.param_shapes(ocfg)
+    params = synth.model_params(shapes, 63)
+    trainable = [n.endswith(".wq") or n.endswith(".wv") for n, _, _ in shapes]
+    ids = synth.token_ids(B, S, 512, 64)
+    gp = [to_dev(p, torch) for p in params]
+    ctx = zo.Context(cfg, gp, B, S, trainable=trainable)
+    out = ctx.zo_step(to_dev(ids, torch), None, B, S, seed=8, eps=1e-3, lr=1e-2).cpu().numpy()
+    before = [p.copy() for p in params]
+    lp, lm, g = orc.zo_step(ocfg, params, 8, 1e-3, 1e-2, ids=ids, trainable=trainable)
+    assert abs(out[0] - lp) <= 1e-3 * abs(lp) and abs(out[2] - g) <= 1e-3 * abs(g) + 2e-3
+    for i, p0 in enumerate(before):
+        got = gp[i].cpu().numpy()
+        if trainable[i]:
+            assert np.array_equal(got, orc.update(p0.copy(), 8, i, np.float32(out[3])))
+        else:
+            assert np.array_equal(got, p0)
+    ctx.close()
+
+
+def test_single_linear_config_one_spsa_step():
+    # in = out = 256, W4 g64 asymmetric, A8 per-token, 8 tokens, MSE, eps 1e-3, eta 1e-4, seed 0
+    torch, zo = gpu()
+    ocfg = orc.Config(0, d_model=256, d_ffn=256, w_bits=4, w_group=64, a_bits=8, act_dtype=0)
+    cfg = zo.make_config(0, d_model=256, d_ffn=256, w_bits=4, w_group=64, a_bits=8, act_dtype=0)
+    W = synth.weights((256, 256), 65)
+    x = synth.activations((8, 256), 66)
+    tgt = synth.activations((8, 256), 67)
+    gw = to_dev(W, torch)
+    ctx = zo.Context(cfg, [gw], 8, 1)
+    out = ctx.zo_step(to_dev(x, torch), to_dev(tgt, torch), 8, 1, seed=0, eps=1e-3, lr=1e-4).cpu().numpy()
+    y = ctx.zo_debug_buffer(1, 0).view(torch.float32).cpu().numpy().reshape(8, 256)
+    trace = {}
+    orc.forward(ocfg, [W], x=x, target=tgt, seed=0, eps_signed=np.float32(1e-3), trace=trace)
+    assert rel_l2(y, trace["y"]) < 1e-4
+    W0 = W.copy()
+    lp, lm, g = orc.zo_step(ocfg, [W], 0, 1e-3, 1e-4, x=x, target=tgt)
+    assert abs(out[0] - lp) <= 1e-3 * abs(lp) and abs(out[1] - lm) <= 1e-3 * abs(lm)
+    assert abs(out[2] - g) <= 1e-3 * abs(g) + 1e-4
+    assert np.array_equal(gw.cpu().numpy(), orc.update(W0, 0, 0, np.float32(out[3])))
+    ctx.close()
+
+
+def test_bad_arguments_are_reported_not_launched():
+    torch, zo = gpu()
+    B, S = 2, 16
+    ocfg, params, ids, gp, ctx = _setup(zo, torch, "llama", 0, B, S)
+    idd = to_dev(ids, torch)
+    with pytest.raises(zo.ZoError) as e:
+        ctx.zo_forward_quant(idd, None, B, S + 1, 1, 0.0)
+    assert e.value.status in (2, 6)
+    with pytest.raises(zo.ZoError) as e:
+        ctx.zo_step(idd, None, B, S, 1, 0.0, 1e-3)
+    assert e.value.status == 1
+    with pytest.raises(zo.ZoError):
+        zo.Context(zo.make_config(1, n_layers=1, d_model=100, n_heads=4, d_ffn=256, vocab=64, max_seq=16), gp, B, S)
+    ctx.close()
