@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of the ZO-QAT step on one MI355X.
+
+A "step" is one zo_step call: both quantized forwards of Eq. 2 at W +- eps u, the projected
+gradient, and the seeded update of Eq. 3, on a batch of synthetic token ids with random-init
+weights of the named shape, all resident in HBM before the timed region.
+
+Prints ONE JSON line (rank 0): ZO steps/s, the roofline of the dominant kernel (the bf16 MFMA
+GEMM of the fake-quantized linears, timed per launch with HIP events on the launch stream inside
+the timed region), the update kernel's HBM rate, and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+WORKLOADS = {
+    # Llama-2-7B shape, W4A8 group 64, 8 x 1024 tokens (the configuration the metric is quoted on)
+    "llama7b_w4a8_g64_8x1024": dict(arch="llama", n_layers=32, d_model=4096, n_heads=32, d_ffn=11008, vocab=32000,
+                                    w_bits=4, w_group=64, a_bits=8, B=8, S=1024),
+    "llama7b_w2a16_g64_8x1024": dict(arch="llama", n_layers=32, d_model=4096, n_heads=32, d_ffn=11008, vocab=32000,
+                                     w_bits=2, w_group=64, a_bits=16, B=8, S=1024),
+    "opt1p3b_w4a8_g128_16x512": dict(arch="opt", n_layers=24, d_model=2048, n_heads=32, d_ffn=8192, vocab=50272,
+                                     w_bits=4, w_group=128, a_bits=8, B=16, S=512),
+    "tiny_w4a16_g64_8x128": dict(arch="llama", n_layers=4, d_model=512, n_heads=8, d_ffn=2048, vocab=4096,
+                                 w_bits=4, w_group=64, a_bits=16, B=8, S=128),
+}
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def gemm_flops_per_step(w):
+    """2*M*N*K over every GEMM launch of one step (both branches): the algorithmic flops."""
+    M, d, f, V, L = w["B"] * w["S"], w["d_model"], w["d_ffn"], w["vocab"], w["n_layers"]
+    ffn = 3 * d * f if w["arch"] == "llama" else 2 * d * f
+    per_fwd = L * (4 * d * d + ffn) + V * d
+    return 2 * 2.0 * M * per_fwd
+
+
+def attention_flops_per_step(w):
+    B, S, d, L = w["B"], w["S"], w["d_model"], w["n_layers"]
+    return 2 * L * B * 2 * 2.0 * d * S * (S + 1) / 2            # QK^T and PV over the causal half
+
+
+def cpu_baseline(w):
+    """The oracle, as it stands, timed on a bounded sample of the workload: one full ZO step of a
+    1-layer model of the same widths and vocabulary on one sequence.  Extrapolated to the full
+    depth and batch by the ratio of GEMM flops (the dominant term of the full workload)."""
+    import numpy as np  # noqa: F401
+    from oracle import zo_oracle as orc
+    from paper_2509_00031_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        blas_threads = 1
+    omp = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    arch = orc.ARCH_LLAMA if w["arch"] == "llama" else orc.ARCH_OPT
+    cfg = orc.Config(arch, n_layers=1, d_model=w["d_model"], n_heads=w["n_heads"], d_ffn=w["d_ffn"], vocab=w["vocab"],
+                     max_seq=w["S"], w_bits=w["w_bits"], w_group=w["w_group"], a_bits=w["a_bits"], act_dtype=1)
+    params = synth.model_params(orc.param_shapes(cfg), 1234)
+    ids = synth.token_ids(1, w["S"], w["vocab"], 5678)
+    t0 = time.perf_counter()
+    orc.zo_step(cfg, params, 0, 1e-3, 1e-6, ids=ids)
+    t_sample = time.perf_counter() - t0
+    sample = dict(w, n_layers=1, B=1)
+    ratio = gemm_flops_per_step(w) / gemm_flops_per_step(sample)
+    est = t_sample * ratio
+    return {"value": 1.0 / est, "unit": "steps/s", "cores": max(blas_threads, omp), "kind": "oracle",
+            "sample": "one oracle zo_step of a 1-layer model of the same widths on 1 of %d sequences of %d tokens took "
+                      "%.1f s; extrapolated by the GEMM-flop ratio full/sample = %.0f to %.0f s per full step"
+                      % (w["B"], w["S"], t_sample, ratio, est)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="llama7b_w4a8_g64_8x1024", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true", help="do not bracket launches with HIP events in the timed region")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs the ZO-QAT step on ONE GPU (seed-synchronous data parallelism across GPUs is a "
+              "design note only); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2509_00031_amd import binding as zo
+
+    w = WORKLOADS[args.workload]
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    arch = zo.ARCH_LLAMA if w["arch"] == "llama" else zo.ARCH_OPT
+    cfg = zo.make_config(arch, n_layers=w["n_layers"], d_model=w["d_model"], n_heads=w["n_heads"], d_ffn=w["d_ffn"],
+                         vocab=w["vocab"], max_seq=w["S"], w_bits=w["w_bits"], w_group=w["w_group"], a_bits=w["a_bits"],
+                         act_dtype=zo.ACT_BF16)
+    n = zo.zo_num_params(cfg)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1234)
+    params = []
+    n_params = 0
+    for i in range(n):
+        numel = zo.zo_param_numel(cfg, i)
+        n_params += numel
+        t = torch.empty(numel, dtype=torch.float32, device=dev)
+        t.normal_(0.0, 0.02, generator=gen)
+        if numel == w["d_model"]:                       # norm gains / small vectors: around one
+            t.add_(1.0)
+        params.append(t)
+    B, S = w["B"], w["S"]
+    ids = torch.randint(0, w["vocab"], (B, S), dtype=torch.int32, device=dev, generator=gen)
+    ctx = zo.Context(cfg, params, B, S)
+    eps, lr = 1e-3, 1e-6
+
+    for i in range(args.warmup):
+        ctx.zo_step(ids, None, B, S, seed=i, eps=eps, lr=lr)
+    torch.cuda.synchronize()
+    if not args.no_profile:
+        ctx.zo_profile_begin()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        out = ctx.zo_step(ids, None, B, S, seed=args.warmup + i, eps=eps, lr=lr)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = None if args.no_profile else ctx.zo_profile_end()
+    losses = out.cpu().tolist()
+
+    ms_per_step = 1e3 * elapsed / args.steps
+    res = {
+        "metric": "ZO steps/sec (2 quantized fwd + update)", "value": args.steps / elapsed, "unit": "steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "tokens_per_step": B * S, "trainable_params": n_params,
+                   "w_bits": w["w_bits"], "w_group": w["w_group"], "a_bits": w["a_bits"], "eps": eps, "lr": lr,
+                   "last_step": {"loss_plus": losses[0], "loss_minus": losses[1], "g": losses[2]}},
+    }
+    gflops = gemm_flops_per_step(w)
+    if prof:
+        gemm_ms, gemm_launches = prof["gemm"]
+        avg_ms = gemm_ms / max(gemm_launches, 1)
+        flops_per_launch = gflops * args.steps / max(gemm_launches, 1)
+        achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12
+        res["roofline"] = {"bound": "mfma", "kernel": "zo_gemm_bf16_kernel", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+                           "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                           "launches": gemm_launches, "avg_launch_ms": avg_ms,
+                           "flops_per_launch": flops_per_launch}
+        res["gemm_tflops"] = achieved
+        upd_ms, upd_groups = prof["update"]
+        upd_gbs = 8.0 * n_params * upd_groups / (upd_ms * 1e-3) / 1e9 if upd_ms > 0 else None
+        res["update_kernel"] = {"bound": "hbm", "achieved": upd_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                "frac": upd_gbs / PEAK_HBM_GBS if upd_gbs else None, "bytes_per_param": 8,
+                                "ms_per_step": upd_ms / max(upd_groups, 1)}
+        res["breakdown_ms_per_step"] = {k: v[0] / args.steps for k, v in prof.items()}
+    res["step_flops"] = gflops + attention_flops_per_step(w)
+    res["step_tflops"] = res["step_flops"] / (ms_per_step * 1e-3) / 1e12
+    ctx.close()
+    del params, ctx
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -116,6 +116,17 @@ zo_status zo_step(zo_ctx* ctx, const void* ids, const float* target, int32_t B, 
  * c is read from coeff_dev (dev fp32[1]) if non-NULL, else coeff_host is used. */
 zo_status zo_update(zo_ctx* ctx, uint64_t seed, const float* coeff_dev, float coeff_host);
 
+/* Per-launch timing of the context's own work with HIP events recorded on its stream (the
+ * stream the kernels run on).  Between zo_profile_begin and zo_profile_end every group of launches
+ * is bracketed by two events.  zo_profile_end synchronises the stream and returns, per category,
+ * the summed elapsed milliseconds and the number of bracketed groups (host arrays of
+ * ZO_PROF_CATEGORIES entries).  A "GEMM" group is exactly one launch of the GEMM kernel (both
+ * branches of Eq. 2 batched in it). */
+enum { ZO_PROF_GEMM = 0, ZO_PROF_WEIGHT_QUANT = 1, ZO_PROF_ACT_QUANT = 2, ZO_PROF_ATTENTION = 3,
+       ZO_PROF_UPDATE = 4, ZO_PROF_OTHER = 5, ZO_PROF_CATEGORIES = 6 };
+zo_status zo_profile_begin(zo_ctx* ctx);
+zo_status zo_profile_end(zo_ctx* ctx, float* ms_host, int32_t* launches_host);
+
 /* ---- stand-alone pieces of the path (same device code as the step), for tests and benches ---- */
 
 /* out[j] = word (j & 3) of Philox4x32-10 block (j >> 2) of the stream (seed, tensor_id). */
@@ -159,6 +170,15 @@ zo_status zo_linear_fakequant(const void* X_dev, const float* W_dev, const float
  * have been de-quantized).  Exposed for roofline measurement and parity. */
 zo_status zo_gemm_nt(const void* X_dev, const void* W_dev, void* Y_dev, int32_t M, int32_t N, int32_t K,
                      int32_t dtype, void* hip_stream);
+
+/* Causal softmax attention of the decoder forward: for every batch b, head h and position s,
+ * out[b,s,h,:] = sum_{j<=s} softmax_j(q[b,s,h,:].k[b,j,h,:] / sqrt(dh)) v[b,j,h,:].
+ * q, k, v: dev, storage type dtype, element (b,s,h,i) at ((b*S + s) * row_stride + h*dh + i)
+ * (row_stride lets them live inside one fused [B*S][3*H*dh] buffer); out: dev [B*S][H*dh].
+ * dh must be 16, 32, 64 or 128 and row_stride a multiple of 8. */
+zo_status zo_attention_causal(const void* q_dev, const void* k_dev, const void* v_dev, void* out_dev,
+                              int32_t B, int32_t S, int32_t H, int32_t dh, int64_t row_stride, int32_t dtype,
+                              void* hip_stream);
 
 /* Device buffers of the context's last forward, for layer-level parity tests.
  * which: 0 = final hidden state [M][d], 1 = logits fp32 [M][V] (linear arch: output Y [M][N]),

@@ -22,7 +22,8 @@ ACT_FP32, ACT_BF16 = 0, 1
 EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "zo_destroy", "zo_last_error",
            "zo_forward_quant", "zo_step", "zo_update", "zo_debug_philox_u32", "zo_debug_normal", "zo_update_tensor",
            "zo_debug_quant_weight", "zo_debug_quant_act", "zo_linear_scratch_bytes", "zo_linear_fakequant",
-           "zo_gemm_nt", "zo_debug_buffer"]
+           "zo_gemm_nt", "zo_debug_buffer", "zo_profile_begin", "zo_profile_end", "zo_attention_causal"]
+PROF_NAMES = ["gemm", "weight_quant", "act_quant", "attention", "update", "other"]
 
 
 class zo_config(C.Structure):
@@ -65,6 +66,9 @@ _lib.zo_linear_scratch_bytes.restype = _sz
 _lib.zo_linear_fakequant.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _u64, _i32, _f32, _vp, _vp]
 _lib.zo_gemm_nt.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp]
 _lib.zo_debug_buffer.argtypes = [_vp, _i32, _i32, C.POINTER(_vp), C.POINTER(_sz)]
+_lib.zo_attention_causal.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i64, _i32, _vp]
+_lib.zo_profile_begin.argtypes = [_vp]
+_lib.zo_profile_end.argtypes = [_vp, C.POINTER(C.c_float), C.POINTER(_i32)]
 
 
 def _ptr(t):
@@ -146,6 +150,16 @@ class Context:
     def zo_update(self, seed, coeff_dev=None, coeff_host=0.0):
         _check(_lib.zo_update(self.handle, seed, _ptr(coeff_dev), coeff_host), "zo_update", self.handle)
 
+    def zo_profile_begin(self):
+        _check(_lib.zo_profile_begin(self.handle), "zo_profile_begin", self.handle)
+
+    def zo_profile_end(self):
+        """Synchronises; returns {category: (milliseconds, launches)}."""
+        ms = (C.c_float * len(PROF_NAMES))()
+        n = (_i32 * len(PROF_NAMES))()
+        _check(_lib.zo_profile_end(self.handle, ms, n), "zo_profile_end", self.handle)
+        return {name: (float(ms[i]), int(n[i])) for i, name in enumerate(PROF_NAMES)}
+
     def zo_debug_buffer(self, which, branch=0):
         p, n = _vp(), _sz()
         _check(_lib.zo_debug_buffer(self.handle, which, branch, C.byref(p), C.byref(n)), "zo_debug_buffer", self.handle)
@@ -219,3 +233,15 @@ def zo_gemm_nt(X, W, Y=None):
         Y = torch.empty((M, N), dtype=X.dtype, device=X.device)
     _check(_lib.zo_gemm_nt(X.data_ptr(), W.data_ptr(), Y.data_ptr(), M, N, K, dtype, _stream()), "zo_gemm_nt")
     return Y
+
+
+def zo_attention_causal(qkv, B, S, H, dh):
+    """qkv: [B*S, 3*H*dh] fused buffer (q | k | v along the last axis); returns [B*S, H*dh]."""
+    dtype = ACT_BF16 if qkv.dtype == torch.bfloat16 else ACT_FP32
+    d = H * dh
+    out = torch.empty((B * S, d), dtype=qkv.dtype, device=qkv.device)
+    es = qkv.element_size()
+    base = qkv.data_ptr()
+    _check(_lib.zo_attention_causal(base, base + d * es, base + 2 * d * es, out.data_ptr(), B, S, H, dh, 3 * d, dtype,
+                                    _stream()), "zo_attention_causal")
+    return out

@@ -144,6 +144,11 @@ struct zo_ctx {
     layout L;           // for max_B x max_S
     int last_M;
     std::string err;
+    // optional per-launch timing (zo_profile_begin / zo_profile_end)
+    bool prof = false;
+    std::vector<hipEvent_t> ev_pool;      // created on demand, reused across sessions
+    size_t ev_used = 0;
+    std::vector<int> ev_cat;              // category of event pair i = events 2i, 2i+1
 };
 
 namespace {
@@ -156,6 +161,29 @@ zo_status fail(zo_ctx* c, zo_status s, const char* what, hipError_t e = hipSucce
     }
     return s;
 }
+
+// Brackets the launches issued during its lifetime with two events on the context's stream.
+struct prof_scope {
+    zo_ctx* c;
+    bool on;
+    prof_scope(zo_ctx* ctx, int cat) : c(ctx), on(ctx && ctx->prof)
+    {
+        if (!on) return;
+        while (c->ev_pool.size() < c->ev_used + 2) {
+            hipEvent_t e;
+            if (hipEventCreate(&e) != hipSuccess) { on = false; return; }
+            c->ev_pool.push_back(e);
+        }
+        c->ev_cat.push_back(cat);
+        (void)hipEventRecord(c->ev_pool[c->ev_used], c->st);
+    }
+    ~prof_scope()
+    {
+        if (!on) return;
+        (void)hipEventRecord(c->ev_pool[c->ev_used + 1], c->st);
+        c->ev_used += 2;
+    }
+};
 
 #define ZO_HIP(ctx, call)                                                  \
     do {                                                                   \
@@ -184,6 +212,7 @@ struct fwd {
         void* op = at(c->L.what[0]) + (size_t)row0 * p.cols * ts;
         void* om = nb == 2 ? at(c->L.what[1]) + (size_t)row0 * p.cols * ts : nullptr;
         const int bits = quantize ? c->cfg.w_bits : 0;
+        prof_scope ps(c, ZO_PROF_WEIGHT_QUANT);
         ZO_HIP(c, zo_launch_fq_weight((const float*)c->params[t].ptr, (int)p.rows, (int)p.cols, bits, c->cfg.w_group,
                                       seed, t, eps_of(t), dt(), op, om, nullptr, nullptr, nullptr, c->st));
         return ZO_OK;
@@ -194,6 +223,7 @@ struct fwd {
         const param_desc& p = c->desc[t];
         float* op = at<float>(c->L.vec[0]) + slot * c->L.vec_stride + o;
         float* om = nb == 2 ? at<float>(c->L.vec[1]) + slot * c->L.vec_stride + o : nullptr;
+        prof_scope ps(c, ZO_PROF_WEIGHT_QUANT);
         ZO_HIP(c, zo_launch_fq_weight((const float*)c->params[t].ptr, 1, (int)p.cols, 0, 0, seed, t, eps_of(t), ZO_T_F32,
                                       op, om, nullptr, nullptr, nullptr, c->st));
         return ZO_OK;
@@ -202,6 +232,7 @@ struct fwd {
 
     zo_status norm(size_t layout::per_branch::*in, size_t layout::per_branch::*out, bool has_beta)
     {
+        prof_scope ps(c, ZO_PROF_OTHER);
         for (int b = 0; b < nb; ++b)
             ZO_HIP(c, zo_launch_norm(at(c->L.br[b].*in), vec(b, 0), has_beta ? vec(b, 1) : nullptr, at(c->L.br[b].*out),
                                      M, c->cfg.d_model, 1e-5f, dt(), c->st));
@@ -211,6 +242,7 @@ struct fwd {
     zo_status act_quant(size_t layout::per_branch::*in, int K, size_t layout::per_branch::** used)
     {
         if (c->cfg.a_bits >= 16) { *used = in; return ZO_OK; }
+        prof_scope ps(c, ZO_PROF_ACT_QUANT);
         for (int b = 0; b < nb; ++b)
             ZO_HIP(c, zo_launch_fq_act(at(c->L.br[b].*in), at(c->L.br[b].hq), M, K, c->cfg.a_bits, c->cfg.a_sym, dt(),
                                        nullptr, nullptr, nullptr, c->st));
@@ -239,6 +271,7 @@ struct fwd {
         a.relu = relu;
         a.out_f32 = out_f32;
         a.dtype = dt();
+        prof_scope ps(c, ZO_PROF_GEMM);
         ZO_HIP(c, zo_launch_gemm(a, c->st));
         return ZO_OK;
     }
@@ -263,6 +296,7 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
         zo_gemm_args a{};
         const void* xin = ids_or_x;
         if (cfg.a_bits < 16) {
+            prof_scope ps(c, ZO_PROF_ACT_QUANT);
             ZO_HIP(c, zo_launch_fq_act(ids_or_x, F.at(c->L.br[0].hq), M, K, cfg.a_bits, cfg.a_sym, dt, nullptr, nullptr, nullptr, c->st));
             xin = F.at(c->L.br[0].hq);
         }
@@ -273,7 +307,11 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
             a.strideW = (int64_t)(c->L.what[1] - c->L.what[0]) / (int64_t)ts;
             a.strideY = (int64_t)(c->L.br[1].logits - c->L.br[0].logits) / (int64_t)ts;
         }
-        ZO_HIP(c, zo_launch_gemm(a, c->st));
+        {
+            prof_scope ps(c, ZO_PROF_GEMM);
+            ZO_HIP(c, zo_launch_gemm(a, c->st));
+        }
+        prof_scope ps(c, ZO_PROF_OTHER);
         for (int b = 0; b < nb; ++b) {
             ZO_HIP(c, zo_launch_sqerr_rows(F.at(c->L.br[b].logits), target, F.at<float>(c->L.br[b].rowloss), M, N, dt, c->st));
             ZO_HIP(c, zo_launch_reduce_loss(F.at<float>(c->L.br[b].rowloss), M, 1.0f / ((float)M * (float)N), loss_out + b, c->st));
@@ -291,6 +329,7 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
     {
         const int t_tok = t++;
         const int t_pos = llama ? -1 : t++;
+        prof_scope ps(c, ZO_PROF_OTHER);
         for (int b = 0; b < nb; ++b) {
             const float sgn = (b == 0) ? 1.0f : -1.0f;
             ZO_HIP(c, zo_launch_embed(ids, (const float*)c->params[t_tok].ptr, llama ? nullptr : (const float*)c->params[t_pos].ptr,
@@ -311,12 +350,17 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
         }
         ZO_TRY(F.gemm(xin, &PB::qkv, 3 * d, d, !llama, false, false));
         for (int b = 0; b < nb; ++b) {
+            prof_scope ps(c, ZO_PROF_ATTENTION);
             char* qkv = F.at(c->L.br[b].qkv);
             if (llama)
                 ZO_HIP(c, zo_launch_rope(qkv, qkv + (size_t)d * ts, F.at<float>(c->L.rope_cos), F.at<float>(c->L.rope_sin),
                                          M, S, H, dh, 3 * d, dt, c->st));
-            ZO_HIP(c, zo_launch_attention(qkv, qkv + (size_t)d * ts, qkv + (size_t)2 * d * ts, F.at(c->L.br[b].att),
-                                          B, S, H, dh, 3 * d, dt, c->st));
+            if (zo_flash_attention_supported(dh, dt))
+                ZO_HIP(c, zo_launch_flash_attention(qkv, qkv + (size_t)d * ts, qkv + (size_t)2 * d * ts, F.at(c->L.br[b].att),
+                                                    B, S, H, dh, 3 * d, c->st));
+            else
+                ZO_HIP(c, zo_launch_attention(qkv, qkv + (size_t)d * ts, qkv + (size_t)2 * d * ts, F.at(c->L.br[b].att),
+                                              B, S, H, dh, 3 * d, dt, c->st));
         }
         ZO_TRY(F.act_quant(&PB::att, d, &xin));
         ZO_TRY(F.weights(t++, 0, true));
@@ -331,6 +375,7 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
             ZO_TRY(F.weights(t++, 0, true));
             ZO_TRY(F.weights(t++, f, true));
             ZO_TRY(F.gemm(xin, &PB::gu, 2 * f, d, false, false, false));
+            prof_scope ps(c, ZO_PROF_OTHER);
             for (int b = 0; b < nb; ++b) {
                 char* gu = F.at(c->L.br[b].gu);
                 ZO_HIP(c, zo_launch_swiglu(gu, gu + (size_t)f * ts, F.at(c->L.br[b].act), M, f, 2 * f, dt, c->st));
@@ -351,6 +396,7 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
     ZO_TRY(F.norm(&PB::x, &PB::h, !llama));
     ZO_TRY(F.weights(t++, 0, false));
     ZO_TRY(F.gemm(&PB::h, &PB::logits, V, d, false, false, false, true));
+    prof_scope ps(c, ZO_PROF_OTHER);
     for (int b = 0; b < nb; ++b) {
         ZO_HIP(c, zo_launch_ce_rows(F.at<float>(c->L.br[b].logits), ids, F.at<float>(c->L.br[b].rowloss), M, S, V, c->st));
         ZO_HIP(c, zo_launch_reduce_loss(F.at<float>(c->L.br[b].rowloss), M, 1.0f / ((float)B * (float)(S - 1)), loss_out + b, c->st));
@@ -454,7 +500,35 @@ zo_status zo_init(const zo_config* cfg, const zo_tensor* params, int32_t n_param
 
 zo_status zo_destroy(zo_ctx* ctx)
 {
+    if (ctx)
+        for (hipEvent_t e : ctx->ev_pool) (void)hipEventDestroy(e);
     delete ctx;
+    return ZO_OK;
+}
+
+zo_status zo_profile_begin(zo_ctx* ctx)
+{
+    if (!ctx) return ZO_EINVAL;
+    ctx->prof = true;
+    ctx->ev_used = 0;
+    ctx->ev_cat.clear();
+    return ZO_OK;
+}
+
+zo_status zo_profile_end(zo_ctx* ctx, float* ms, int32_t* launches)
+{
+    if (!ctx || !ms || !launches) return ZO_EINVAL;
+    ctx->prof = false;
+    for (int i = 0; i < ZO_PROF_CATEGORIES; ++i) { ms[i] = 0.0f; launches[i] = 0; }
+    ZO_HIP(ctx, hipStreamSynchronize(ctx->st));
+    for (size_t i = 0; i < ctx->ev_cat.size(); ++i) {
+        float t = 0.0f;
+        ZO_HIP(ctx, hipEventElapsedTime(&t, ctx->ev_pool[2 * i], ctx->ev_pool[2 * i + 1]));
+        ms[ctx->ev_cat[i]] += t;
+        launches[ctx->ev_cat[i]] += 1;
+    }
+    ctx->ev_used = 0;
+    ctx->ev_cat.clear();
     return ZO_OK;
 }
 
@@ -472,6 +546,7 @@ zo_status zo_forward_quant(zo_ctx* ctx, const void* ids, const float* target, in
 zo_status zo_update(zo_ctx* ctx, uint64_t seed, const float* coeff_dev, float coeff_host)
 {
     if (!ctx) return ZO_EINVAL;
+    prof_scope ps(ctx, ZO_PROF_UPDATE);
     for (int i = 0; i < (int)ctx->params.size(); ++i) {
         if (!trainable(ctx, i)) continue;
         ZO_HIP(ctx, zo_launch_update((float*)ctx->params[i].ptr, ctx->params[i].numel, seed, i, coeff_dev, coeff_host, ctx->st));
@@ -596,6 +671,22 @@ zo_status zo_linear_fakequant(const void* X_dev, const float* W_dev, const float
     a.X = xin; a.W = what; a.Y = Y_dev; a.bias = bias_dev;
     a.M = M; a.N = N; a.K = K; a.batch = 1; a.dtype = dtype;
     return zo_launch_gemm(a, st) == hipSuccess ? ZO_OK : ZO_EHIP;
+}
+
+zo_status zo_attention_causal(const void* q_dev, const void* k_dev, const void* v_dev, void* out_dev,
+                              int32_t B, int32_t S, int32_t H, int32_t dh, int64_t row_stride, int32_t dtype,
+                              void* hip_stream)
+{
+    if (!q_dev || !k_dev || !v_dev || !out_dev || B < 0 || S < 0 || H <= 0) return ZO_EINVAL;
+    if (dtype != ZO_ACT_FP32 && dtype != ZO_ACT_BF16) return ZO_EINVAL;
+    if (dh != 16 && dh != 32 && dh != 64 && dh != 128) return ZO_EUNSUPPORTED;
+    if (row_stride < (int64_t)H * dh || (row_stride & 7)) return ZO_ESHAPE;
+    if (!aligned16(q_dev) || !aligned16(k_dev) || !aligned16(v_dev) || !aligned16(out_dev)) return ZO_EALIGN;
+    hipStream_t st = (hipStream_t)hip_stream;
+    hipError_t e = zo_flash_attention_supported(dh, dtype)
+                       ? zo_launch_flash_attention(q_dev, k_dev, v_dev, out_dev, B, S, H, dh, row_stride, st)
+                       : zo_launch_attention(q_dev, k_dev, v_dev, out_dev, B, S, H, dh, row_stride, dtype, st);
+    return e == hipSuccess ? ZO_OK : ZO_EHIP;
 }
 
 zo_status zo_gemm_nt(const void* X_dev, const void* W_dev, void* Y_dev, int32_t M, int32_t N, int32_t K,

@@ -203,3 +203,23 @@ def test_bad_arguments_are_reported_not_launched():
     with pytest.raises(zo.ZoError):
         zo.Context(zo.make_config(1, n_layers=1, d_model=100, n_heads=4, d_ffn=256, vocab=64, max_seq=16), gp, B, S)
     ctx.close()
+
+
+@pytest.mark.parametrize("heads,S", [(2, 40), (1, 200), (2, 128), (1, 257)])
+def test_matrix_core_attention_path(heads, S):
+    # bf16 storage with head dimension 64 / 128 runs the matrix-core attention kernel; S spans
+    # several key tiles, a ragged last query tile and a ragged last key tile
+    torch, zo = gpu()
+    B = 2
+    ocfg, params, ids, gp, ctx = _setup(zo, torch, "llama", 1, B, S, n_layers=1, n_heads=heads, a_bits=16)
+    idd = to_dev(ids, torch)
+    loss = ctx.zo_forward_quant(idd, None, B, S, seed=4, eps_signed=1e-3).item()
+    trace = {}
+    ref = orc.forward(ocfg, params, ids=ids, seed=4, eps_signed=np.float32(1e-3), trace=trace)
+    assert abs(loss - ref) <= 1e-3 * abs(ref), (loss, ref)
+    x = ctx.zo_debug_buffer(2).view(torch.bfloat16).float().cpu().numpy().reshape(B * S, -1)
+    # the probabilities enter the second product as bf16 operands (see test_gpu_attention.py):
+    # whole-tensor error within the bf16 tolerance, single rows within twice that
+    assert rel_l2(x, trace["l0.out"]) < 1e-2
+    assert _row_rel(x, trace["l0.out"]).max() < 2e-2
+    ctx.close()
