@@ -4,6 +4,7 @@
 // fp32 operands (parity mode) use a plain LDS-tiled FMA kernel.
 #include "zo_device.h"
 #include "zo_internal.h"
+#include <cstdlib>
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -178,6 +179,189 @@ __global__ __launch_bounds__(256) void zo_gemm_bf16_kernel(zo_gemm_args a)
 }
 
 // ---------------------------------------------------------------------------------------------
+// bf16 MFMA kernel, large shapes (K a multiple of 64): 256 x 256 tile, the K tiles are copied
+// global -> LDS by the load unit itself (16 bytes per lane, no staging registers): a wave-level
+// copy fills 1 KB = 8 tile rows, lane L landing in row L/8, chunk slot L%8; the lane therefore
+// fetches global chunk (L%8) ^ f(row) to realise the same swizzle as above.  Two LDS stages
+// (2 x 64 KB): stage s^1 is being filled while stage s feeds the matrix cores.
+// Workgroups are renumbered so that each of the 8 XCDs (blockIdx % 8) works on a contiguous
+// range of tiles, visited in groups of 8 m-tiles, which keeps operand tiles hot in that XCD's L2.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t lds_offset(const void* p)
+{
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+// one wave-level 1 KB copy: lane fetches 16 bytes at base + voff, LDS destination dst + lane*16
+__device__ __forceinline__ void lds_dma16(const void* base, uint32_t voff, uint32_t dst)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2\n" ::"s"(dst), "v"(voff), "s"(base) : "memory");
+}
+
+template <typename TY, int SCHED>
+__global__ __launch_bounds__(256) void zo_gemm_bf16_dma_kernel(zo_gemm_args a)
+{
+    constexpr int BM = 256, BN = 256, STAGE = (BM + BN) * 128;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int M = a.M, N = a.N, K = a.K;
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    // XCD-aware renumbering, then grouped (8 m-tiles) ordering
+    int vid = blockIdx.x;
+    const int nblk = gridDim.x;
+    if ((nblk & 7) == 0) vid = (vid & 7) * (nblk >> 3) + (vid >> 3);
+    const int group_sz = 8 * tiles_n;
+    const int grp = vid / group_sz;
+    const int first_m = grp * 8;
+    const int gm = (tiles_m - first_m) < 8 ? (tiles_m - first_m) : 8;
+    const int tile_m = first_m + (vid % group_sz) % gm;
+    const int tile_n = (vid % group_sz) / gm;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int bz = blockIdx.z;
+    const zo_bf16* X = (const zo_bf16*)a.X + bz * a.strideX;
+    const zo_bf16* W = (const zo_bf16*)a.W + bz * a.strideW;
+
+    // copy plan: 64 row-blocks of 8 rows per stage (32 of X, then 32 of W); wave w owns 16 of them
+    const int lrow = lane >> 3, slot = lane & 7;
+    uint32_t voff[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int rb = wave * 16 + i;                 // 0..63
+        const bool isw = rb >= 32;
+        const int trow = (rb & 31) * 8 + lrow;        // row inside the operand tile
+        int grow = (isw ? n0 : m0) + trow;
+        const int lim = isw ? N : M;
+        grow = grow < lim ? grow : lim - 1;
+        const int c = slot ^ swz(trow);
+        voff[i] = (uint32_t)(((int64_t)grow * K + c * 8) * 2);
+    }
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_offset(lds));
+    auto issue = [&](int stage, int kt) {
+        const zo_bf16* xb = X + kt * 64;
+        const zo_bf16* wb = W + kt * 64;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int rb = wave * 16 + i;
+            const uint32_t dst = lds0 + stage * STAGE + rb * 1024;
+            lds_dma16(rb >= 32 ? (const void*)wb : (const void*)xb, voff[i], dst);
+        }
+    };
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    const int nk = K / 64;
+    issue(0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): own copies have landed
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < nk) issue(cur ^ 1, kt + 1);
+        const unsigned char* xb = lds + cur * STAGE;
+        const unsigned char* wb = xb + BM * 128;
+        bf16x8 xf[2][4], wf[2][4];
+        auto load_frags = [&](int ks, int sel) {
+            const int c = 2 * ks + (lane >> 5);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int r = wm * 128 + j * 32 + (lane & 31);
+                xf[sel][j] = *reinterpret_cast<const bf16x8*>(xb + r * 128 + ((c ^ swz(r)) << 4));
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int r = wn * 128 + i * 32 + (lane & 31);
+                wf[sel][i] = *reinterpret_cast<const bf16x8*>(wb + r * 128 + ((c ^ swz(r)) << 4));
+            }
+        };
+        load_frags(0, 0);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            if (ks < 3) load_frags(ks + 1, (ks + 1) & 1);
+            if (SCHED == 1) __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ks & 1][i], xf[ks & 1][j], acc[i][j], 0, 0, 0);
+            if (SCHED == 1) __builtin_amdgcn_sched_barrier(0);
+            if (SCHED == 2) {
+                // the fragment reads of the next K step ride in the shadow of this step's MFMAs
+                if (ks < 3) {
+#pragma unroll
+                    for (int g = 0; g < 8; ++g) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+                } else {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+                }
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+    }
+
+    TY* Y = (TY*)a.Y + bz * a.strideY;
+    const float* bias = a.bias ? a.bias + bz * a.strideBias : nullptr;
+    const zo_bf16* res = a.residual ? (const zo_bf16*)a.residual + bz * a.strideRes : nullptr;
+    const bool vec_ok = (N & 3) == 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int m = m0 + wm * 128 + j * 32 + (lane & 31);
+        if (m >= M) continue;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+                const int n = n0 + wn * 128 + i * 32 + rg * 8 + (lane >> 5) * 4;
+                if (n >= N) continue;
+                float v[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = acc[i][j][rg * 4 + e];
+                const int64_t off = (int64_t)m * N + n;
+                if (vec_ok && n + 3 < N) {
+                    if (bias) {
+                        float4 b4 = *reinterpret_cast<const float4*>(bias + n);
+                        v[0] += b4.x; v[1] += b4.y; v[2] += b4.z; v[3] += b4.w;
+                    }
+                    if (a.relu) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.0f);
+                    }
+                    if (res) {
+                        uint2 r2 = *reinterpret_cast<const uint2*>(res + off);
+                        v[0] += zo_bf16_lo(r2.x); v[1] += zo_bf16_hi(r2.x);
+                        v[2] += zo_bf16_lo(r2.y); v[3] += zo_bf16_hi(r2.y);
+                    }
+                    if constexpr (sizeof(TY) == 4) {
+                        *reinterpret_cast<float4*>((float*)Y + off) = make_float4(v[0], v[1], v[2], v[3]);
+                    } else {
+                        uint2 o;
+                        o.x = zo_pack_bf16x2(v[0], v[1]);
+                        o.y = zo_pack_bf16x2(v[2], v[3]);
+                        *reinterpret_cast<uint2*>((zo_bf16*)Y + off) = o;
+                    }
+                } else {
+                    for (int e = 0; e < 4 && n + e < N; ++e) {
+                        float t = v[e];
+                        if (bias) t += bias[n + e];
+                        if (a.relu) t = fmaxf(t, 0.0f);
+                        if (res) t += (float)res[off + e];
+                        zo_store(Y + off + e, t);
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // fp32 kernel (parity mode): 64 x 64 tile, K step 16, 256 threads x (4 x 4) outputs.
 // ---------------------------------------------------------------------------------------------
 template <typename TY>
@@ -259,7 +443,31 @@ hipError_t zo_launch_gemm(const zo_gemm_args& a, hipStream_t st)
 {
     if (a.M == 0 || a.N == 0) return hipSuccess;
     if (a.dtype == ZO_T_BF16) {
-        if ((int64_t)a.M * a.N >= (int64_t)256 * 256 * 128) return launch_bf16<256, 256>(a, st);
+        const bool large = (int64_t)a.M * a.N >= (int64_t)256 * 256 * 128;
+        // operand bytes must be addressable with 32-bit offsets from the (batch) base pointers
+        const bool off32 = (int64_t)a.M * a.K * 2 < ((int64_t)1 << 32) && (int64_t)a.N * a.K * 2 < ((int64_t)1 << 32);
+        if (large && (a.K & 63) == 0 && off32) {
+            const int tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
+            const dim3 grid(tiles, 1, a.batch);
+            constexpr int lds_bytes = 2 * 512 * 128;
+            static const int variant = getenv("ZO_GEMM_VARIANT") ? atoi(getenv("ZO_GEMM_VARIANT")) : 2;
+            if (variant < 0) return launch_bf16<256, 256>(a, st);
+#define ZO_DMA_LAUNCH(TY, SC)                                                                                              \
+    do {                                                                                                                   \
+        hipError_t e_ = hipFuncSetAttribute((const void*)zo_gemm_bf16_dma_kernel<TY, SC>,                                  \
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);                        \
+        if (e_ != hipSuccess) return e_;                                                                                   \
+        zo_gemm_bf16_dma_kernel<TY, SC><<<grid, 256, lds_bytes, st>>>(a);                                                  \
+    } while (0)
+            if (a.out_f32) {
+                if (variant == 0) ZO_DMA_LAUNCH(float, 0); else if (variant == 1) ZO_DMA_LAUNCH(float, 1); else ZO_DMA_LAUNCH(float, 2);
+            } else {
+                if (variant == 0) ZO_DMA_LAUNCH(zo_bf16, 0); else if (variant == 1) ZO_DMA_LAUNCH(zo_bf16, 1); else ZO_DMA_LAUNCH(zo_bf16, 2);
+            }
+#undef ZO_DMA_LAUNCH
+            return hipGetLastError();
+        }
+        if (large) return launch_bf16<256, 256>(a, st);
         return launch_bf16<128, 128>(a, st);
     }
     const int tiles = ((a.M + 63) / 64) * ((a.N + 63) / 64);
