@@ -179,11 +179,12 @@ __global__ __launch_bounds__(256) void zo_gemm_bf16_kernel(zo_gemm_args a)
 }
 
 // ---------------------------------------------------------------------------------------------
-// bf16 MFMA kernel, large shapes (K a multiple of 64): 256 x 256 tile, the K tiles are copied
-// global -> LDS by the load unit itself (16 bytes per lane, no staging registers): a wave-level
-// copy fills 1 KB = 8 tile rows, lane L landing in row L/8, chunk slot L%8; the lane therefore
-// fetches global chunk (L%8) ^ f(row) to realise the same swizzle as above.  Two LDS stages
-// (2 x 64 KB): stage s^1 is being filled while stage s feeds the matrix cores.
+// bf16 MFMA kernel, large shapes (K a multiple of BK): 256 x 256 tile, NW waves, ST LDS stages.
+// The K tiles are copied global -> LDS by the load unit itself (16 bytes per lane, no staging
+// registers): one wave-level copy fills 1 KB of a stage = 1024 / (2 BK) tile rows, lane L landing
+// in row L / CPR, chunk slot L % CPR (CPR = 16-byte chunks per row); the lane fetches global chunk
+// slot ^ f(row) to realise the bank swizzle.  ST - 1 K tiles are in flight while one feeds the
+// matrix cores; the wait at the end of a tile only covers the oldest of them.
 // Workgroups are renumbered so that each of the 8 XCDs (blockIdx % 8) works on a contiguous
 // range of tiles, visited in groups of 8 m-tiles, which keeps operand tiles hot in that XCD's L2.
 // ---------------------------------------------------------------------------------------------
@@ -196,14 +197,83 @@ __device__ __forceinline__ void lds_dma16(const void* base, uint32_t voff, uint3
 {
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2\n" ::"s"(dst), "v"(voff), "s"(base) : "memory");
 }
-
-template <typename TY, int SCHED>
-__global__ __launch_bounds__(256) void zo_gemm_bf16_dma_kernel(zo_gemm_args a)
+template <int BK> __device__ __forceinline__ int swz_bk(int row)
 {
-    constexpr int BM = 256, BN = 256, STAGE = (BM + BN) * 128;
+    return BK == 64 ? ((row ^ (row >> 3)) & 7) : (((row >> 1) & 3) ^ ((row >> 3) & 1));
+}
+// s_waitcnt vmcnt(n) only (expcnt / lgkmcnt left at their maxima)
+template <int N> __device__ __forceinline__ void wait_vmcnt()
+{
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+// epilogue of one 32 x 32 accumulator tile: lane holds rows n = nb + 8*(r/4) + r%4 (nb includes
+// the 4*(lane/32) term) of column m
+template <typename TY>
+__device__ __forceinline__ void store_tile(const f32x16& acc, const zo_gemm_args& a, TY* Y, const float* bias,
+                                           const zo_bf16* res, int m, int nb)
+{
+    const int M = a.M, N = a.N;
+    if (m >= M) return;
+    const bool vec_ok = (N & 3) == 0;
+#pragma unroll
+    for (int rg = 0; rg < 4; ++rg) {
+        const int n = nb + rg * 8;
+        if (n >= N) continue;
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = acc[rg * 4 + e];
+        const int64_t off = (int64_t)m * N + n;
+        if (vec_ok && n + 3 < N) {
+            if (bias) {
+                float4 b4 = *reinterpret_cast<const float4*>(bias + n);
+                v[0] += b4.x; v[1] += b4.y; v[2] += b4.z; v[3] += b4.w;
+            }
+            if (a.relu) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.0f);
+            }
+            if (res) {
+                uint2 r2 = *reinterpret_cast<const uint2*>(res + off);
+                v[0] += zo_bf16_lo(r2.x); v[1] += zo_bf16_hi(r2.x);
+                v[2] += zo_bf16_lo(r2.y); v[3] += zo_bf16_hi(r2.y);
+            }
+            if constexpr (sizeof(TY) == 4) {
+                *reinterpret_cast<float4*>((float*)Y + off) = make_float4(v[0], v[1], v[2], v[3]);
+            } else {
+                uint2 o;
+                o.x = zo_pack_bf16x2(v[0], v[1]);
+                o.y = zo_pack_bf16x2(v[2], v[3]);
+                *reinterpret_cast<uint2*>((zo_bf16*)Y + off) = o;
+            }
+        } else {
+            for (int e = 0; e < 4 && n + e < N; ++e) {
+                float t = v[e];
+                if (bias) t += bias[n + e];
+                if (a.relu) t = fmaxf(t, 0.0f);
+                if (res) t += (float)res[off + e];
+                zo_store(Y + off + e, t);
+            }
+        }
+    }
+}
+
+template <typename TY, int NW, int BK, int ST>
+__global__ __launch_bounds__(NW * 64) void zo_gemm_bf16_dma_kernel(zo_gemm_args a)
+{
+    constexpr int BM = 256, BN = 256;
+    constexpr int RB = BK * 2;                       // bytes per tile row
+    constexpr int CPR = RB / 16;                     // 16-byte chunks per row
+    constexpr int STAGE = (BM + BN) * RB;            // bytes per LDS stage
+    constexpr int RPD = 1024 / RB;                   // tile rows per wave-level copy
+    constexpr int DPW = (BM + BN) / RPD / NW;        // copies per wave per stage
+    constexpr int WN_WAVES = NW / 2;                 // waves along n (2 along m)
+    constexpr int WM = 128, WN = BN / WN_WAVES;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int KS = BK / 16;                      // MFMA K steps per stage
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN_WAVES, wn = wave % WN_WAVES;
     const int M = a.M, N = a.N, K = a.K;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     // XCD-aware renumbering, then grouped (8 m-tiles) ordering
@@ -221,144 +291,126 @@ __global__ __launch_bounds__(256) void zo_gemm_bf16_dma_kernel(zo_gemm_args a)
     const zo_bf16* X = (const zo_bf16*)a.X + bz * a.strideX;
     const zo_bf16* W = (const zo_bf16*)a.W + bz * a.strideW;
 
-    // copy plan: 64 row-blocks of 8 rows per stage (32 of X, then 32 of W); wave w owns 16 of them
-    const int lrow = lane >> 3, slot = lane & 7;
-    uint32_t voff[16];
+    // copy plan: (BM + BN) / RPD row-blocks per stage (X rows first, then W rows)
+    const int lrow = lane / CPR, slot = lane % CPR;
+    uint32_t voff[DPW];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int rb = wave * 16 + i;                 // 0..63
-        const bool isw = rb >= 32;
-        const int trow = (rb & 31) * 8 + lrow;        // row inside the operand tile
+    for (int i = 0; i < DPW; ++i) {
+        const int rb = wave * DPW + i;
+        const bool isw = rb >= BM / RPD;
+        const int trow = (isw ? rb - BM / RPD : rb) * RPD + lrow;   // row inside the operand tile
         int grow = (isw ? n0 : m0) + trow;
         const int lim = isw ? N : M;
         grow = grow < lim ? grow : lim - 1;
-        const int c = slot ^ swz(trow);
+        const int c = slot ^ swz_bk<BK>(trow);
         voff[i] = (uint32_t)(((int64_t)grow * K + c * 8) * 2);
     }
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_offset(lds));
     auto issue = [&](int stage, int kt) {
-        const zo_bf16* xb = X + kt * 64;
-        const zo_bf16* wb = W + kt * 64;
+        const zo_bf16* xb = X + kt * BK;
+        const zo_bf16* wb = W + kt * BK;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int rb = wave * 16 + i;
+        for (int i = 0; i < DPW; ++i) {
+            const int rb = wave * DPW + i;
             const uint32_t dst = lds0 + stage * STAGE + rb * 1024;
-            lds_dma16(rb >= 32 ? (const void*)wb : (const void*)xb, voff[i], dst);
+            lds_dma16(rb >= BM / RPD ? (const void*)wb : (const void*)xb, voff[i], dst);
         }
     };
 
-    f32x16 acc[4][4];
+    f32x16 acc[TN][TM];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < TN; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < TM; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    const int nk = K / 64;
-    issue(0, 0);
-    __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): own copies have landed
+    auto issue_one = [&](int stage, int kt, int i) {
+        const int rb = wave * DPW + i;
+        const uint32_t dst = lds0 + stage * STAGE + rb * 1024;
+        lds_dma16(rb >= BM / RPD ? (const void*)(W + kt * BK) : (const void*)(X + kt * BK), voff[i], dst);
+    };
+    // Pipeline.  Stage t % ST holds K tile t.  Before the MFMAs of the LAST K step of tile t (whose
+    // fragments are already in registers) the workgroup synchronises: tile t + 1 has landed for
+    // everybody and stage t % ST is free.  The first fragments of tile t + 1 are read, and the
+    // copies of tile t + ST into the freed stage are issued, while those last MFMAs run, so neither
+    // the barrier nor the LDS latency after it leaves the matrix cores without issued work.
+    // With two stages all copies of a tile are issued in that last K step (they are needed one tile
+    // later); with more stages they are spread over the KS steps that follow the barrier.
+    constexpr int SPAN = ST == 2 ? 1 : KS;            // K steps over which one tile's copies are issued
+    constexpr int Q = DPW / SPAN;                     // copies per K step
+    constexpr int MPQ = TN * TM / Q;                  // MFMAs between two copies
+    static_assert(DPW % SPAN == 0 && (TN * TM) % Q == 0 && KS % 2 == 0, "copy / MFMA interleave");
+    const int nk = K / BK;
+    auto tile_clamped = [&](int t) { return t < nk ? t : nk - 1; };   // past the end: refetch the last tile
+#pragma unroll
+    for (int s0 = 0; s0 < ST - 1; ++s0) issue(s0, tile_clamped(s0));
+#pragma unroll
+    for (int i = 0; i < Q; ++i) issue_one(ST - 1, tile_clamped(ST - 1), i);
+    wait_vmcnt<(ST - 2) * DPW + Q>();                 // tile 0 has landed (copies complete in order)
     __syncthreads();
+    bf16x8 xf[2][TM], wf[2][TN];
+    auto load_frags = [&](int stage, int ks, int sel) {
+        const unsigned char* xb = lds + stage * STAGE;
+        const unsigned char* wb = xb + BM * RB;
+        const int c = 2 * ks + (lane >> 5);
+#pragma unroll
+        for (int j = 0; j < TM; ++j) {
+            const int r = wm * WM + j * 32 + (lane & 31);
+            xf[sel][j] = *reinterpret_cast<const bf16x8*>(xb + r * RB + ((c ^ swz_bk<BK>(r)) << 4));
+        }
+#pragma unroll
+        for (int i = 0; i < TN; ++i) {
+            const int r = wn * WN + i * 32 + (lane & 31);
+            wf[sel][i] = *reinterpret_cast<const bf16x8*>(wb + r * RB + ((c ^ swz_bk<BK>(r)) << 4));
+        }
+    };
+    int cur = 0, prev = ST - 1;                       // stage of tile kt / of tile kt-1 (= kt-1+ST)
+    load_frags(0, 0, 0);
     for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < nk) issue(cur ^ 1, kt + 1);
-        const unsigned char* xb = lds + cur * STAGE;
-        const unsigned char* wb = xb + BM * 128;
-        bf16x8 xf[2][4], wf[2][4];
-        auto load_frags = [&](int ks, int sel) {
-            const int c = 2 * ks + (lane >> 5);
+        const int cur1 = cur + 1 == ST ? 0 : cur + 1;
+        const int t_prev = tile_clamped(kt - 1 + ST), t_cur = tile_clamped(kt + ST);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int r = wm * 128 + j * 32 + (lane & 31);
-                xf[sel][j] = *reinterpret_cast<const bf16x8*>(xb + r * 128 + ((c ^ swz(r)) << 4));
+        for (int ks = 0; ks < KS; ++ks) {
+            const int sel = ks & 1;                   // KS is even: every tile starts at sel 0
+            const bool last = ks + 1 == KS;
+            if (!last) {
+                load_frags(cur, ks + 1, sel ^ 1);
+            } else {
+                __builtin_amdgcn_sched_barrier(0);
+                wait_vmcnt<(ST - 2) * DPW>();         // own copies of tile kt+1 have landed
+                __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): own reads of stage cur have returned
+                __syncthreads();
+                load_frags(cur1, 0, sel ^ 1);
             }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int r = wn * 128 + i * 32 + (lane & 31);
-                wf[sel][i] = *reinterpret_cast<const bf16x8*>(wb + r * 128 + ((c ^ swz(r)) << 4));
-            }
-        };
-        load_frags(0, 0);
+            for (int qq = 0; qq < Q; ++qq) {
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            if (ks < 3) load_frags(ks + 1, (ks + 1) & 1);
-            if (SCHED == 1) __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ks & 1][i], xf[ks & 1][j], acc[i][j], 0, 0, 0);
-            if (SCHED == 1) __builtin_amdgcn_sched_barrier(0);
-            if (SCHED == 2) {
-                // the fragment reads of the next K step ride in the shadow of this step's MFMAs
-                if (ks < 3) {
-#pragma unroll
-                    for (int g = 0; g < 8; ++g) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
-                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
-                    }
-                    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
-                } else {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+                for (int e = 0; e < MPQ; ++e) {
+                    const int idx = qq * MPQ + e, i = idx / TM, j = idx % TM;
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[sel][i], xf[sel][j], acc[i][j], 0, 0, 0);
                 }
+                __builtin_amdgcn_sched_barrier(0);
+                if (last) issue_one(cur, t_cur, qq);                          // stage freed just above
+                else if (SPAN > 1) issue_one(prev, t_prev, Q * (1 + ks) + qq);   // rest of the previous refill
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();
+        prev = cur;
+        cur = cur1;
     }
+    wait_vmcnt<0>();
 
     TY* Y = (TY*)a.Y + bz * a.strideY;
     const float* bias = a.bias ? a.bias + bz * a.strideBias : nullptr;
     const zo_bf16* res = a.residual ? (const zo_bf16*)a.residual + bz * a.strideRes : nullptr;
-    const bool vec_ok = (N & 3) == 0;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int m = m0 + wm * 128 + j * 32 + (lane & 31);
-        if (m >= M) continue;
+    for (int j = 0; j < TM; ++j)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-#pragma unroll
-            for (int rg = 0; rg < 4; ++rg) {
-                const int n = n0 + wn * 128 + i * 32 + rg * 8 + (lane >> 5) * 4;
-                if (n >= N) continue;
-                float v[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = acc[i][j][rg * 4 + e];
-                const int64_t off = (int64_t)m * N + n;
-                if (vec_ok && n + 3 < N) {
-                    if (bias) {
-                        float4 b4 = *reinterpret_cast<const float4*>(bias + n);
-                        v[0] += b4.x; v[1] += b4.y; v[2] += b4.z; v[3] += b4.w;
-                    }
-                    if (a.relu) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.0f);
-                    }
-                    if (res) {
-                        uint2 r2 = *reinterpret_cast<const uint2*>(res + off);
-                        v[0] += zo_bf16_lo(r2.x); v[1] += zo_bf16_hi(r2.x);
-                        v[2] += zo_bf16_lo(r2.y); v[3] += zo_bf16_hi(r2.y);
-                    }
-                    if constexpr (sizeof(TY) == 4) {
-                        *reinterpret_cast<float4*>((float*)Y + off) = make_float4(v[0], v[1], v[2], v[3]);
-                    } else {
-                        uint2 o;
-                        o.x = zo_pack_bf16x2(v[0], v[1]);
-                        o.y = zo_pack_bf16x2(v[2], v[3]);
-                        *reinterpret_cast<uint2*>((zo_bf16*)Y + off) = o;
-                    }
-                } else {
-                    for (int e = 0; e < 4 && n + e < N; ++e) {
-                        float t = v[e];
-                        if (bias) t += bias[n + e];
-                        if (a.relu) t = fmaxf(t, 0.0f);
-                        if (res) t += (float)res[off + e];
-                        zo_store(Y + off + e, t);
-                    }
-                }
-            }
-        }
-    }
+        for (int i = 0; i < TN; ++i)
+            store_tile<TY>(acc[i][j], a, Y, bias, res, m0 + wm * WM + j * 32 + (lane & 31),
+                           n0 + wn * WN + i * 32 + (lane >> 5) * 4);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -449,21 +501,26 @@ hipError_t zo_launch_gemm(const zo_gemm_args& a, hipStream_t st)
         if (large && (a.K & 63) == 0 && off32) {
             const int tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
             const dim3 grid(tiles, 1, a.batch);
-            constexpr int lds_bytes = 2 * 512 * 128;
             static const int variant = getenv("ZO_GEMM_VARIANT") ? atoi(getenv("ZO_GEMM_VARIANT")) : 2;
             if (variant < 0) return launch_bf16<256, 256>(a, st);
-#define ZO_DMA_LAUNCH(TY, SC)                                                                                              \
+#define ZO_DMA_LAUNCH(TY, NW, BK, ST)                                                                                      \
     do {                                                                                                                   \
-        hipError_t e_ = hipFuncSetAttribute((const void*)zo_gemm_bf16_dma_kernel<TY, SC>,                                  \
+        constexpr int lds_bytes = ST * 512 * BK * 2;                                                                       \
+        hipError_t e_ = hipFuncSetAttribute((const void*)zo_gemm_bf16_dma_kernel<TY, NW, BK, ST>,                          \
                                             hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);                        \
         if (e_ != hipSuccess) return e_;                                                                                   \
-        zo_gemm_bf16_dma_kernel<TY, SC><<<grid, 256, lds_bytes, st>>>(a);                                                  \
+        zo_gemm_bf16_dma_kernel<TY, NW, BK, ST><<<grid, NW * 64, lds_bytes, st>>>(a);                                      \
     } while (0)
-            if (a.out_f32) {
-                if (variant == 0) ZO_DMA_LAUNCH(float, 0); else if (variant == 1) ZO_DMA_LAUNCH(float, 1); else ZO_DMA_LAUNCH(float, 2);
-            } else {
-                if (variant == 0) ZO_DMA_LAUNCH(zo_bf16, 0); else if (variant == 1) ZO_DMA_LAUNCH(zo_bf16, 1); else ZO_DMA_LAUNCH(zo_bf16, 2);
-            }
+#define ZO_DMA_VARIANTS(TY)                                                                                                \
+    do {                                                                                                                   \
+        if (variant == 0) ZO_DMA_LAUNCH(TY, 4, 64, 2);                                                                     \
+        else if (variant == 1) ZO_DMA_LAUNCH(TY, 4, 32, 4);                                                                \
+        else if (variant == 2) ZO_DMA_LAUNCH(TY, 8, 64, 2);                                                                \
+        else if (variant == 3) ZO_DMA_LAUNCH(TY, 8, 32, 4);                                                                \
+        else ZO_DMA_LAUNCH(TY, 8, 32, 3);                                                                                  \
+    } while (0)
+            if (a.out_f32) ZO_DMA_VARIANTS(float); else ZO_DMA_VARIANTS(zo_bf16);
+#undef ZO_DMA_VARIANTS
 #undef ZO_DMA_LAUNCH
             return hipGetLastError();
         }
