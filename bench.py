@@ -147,7 +147,7 @@ def main():
         avg_ms = gemm_ms / max(gemm_launches, 1)
         flops_per_launch = gflops * args.steps / max(gemm_launches, 1)
         achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12
-        res["roofline"] = {"bound": "mfma", "kernel": "zo_gemm_bf16_kernel", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+        res["roofline"] = {"bound": "mfma", "kernel": "zo_gemm_bf16_dma_kernel<bf16, 8 waves, BK 64, 2 stages>", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                            "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
                            "launches": gemm_launches, "avg_launch_ms": avg_ms,
                            "flops_per_launch": flops_per_launch}
