@@ -84,6 +84,9 @@ def main():
     ap.add_argument("--workload", default="llama7b_w4a8_g64_8x1024", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket launches with HIP events in the timed region")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="before the timed region copy 1 GiB device to device once (a plain copy of known size, "
+                         "against which the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs the ZO-QAT step on ONE GPU (seed-synchronous data parallelism across GPUs is a "
@@ -118,6 +121,12 @@ def main():
     ctx = zo.Context(cfg, params, B, S)
     eps, lr = 1e-3, 1e-6
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for i in range(args.warmup):
         ctx.zo_step(ids, None, B, S, seed=i, eps=eps, lr=lr)
     torch.cuda.synchronize()

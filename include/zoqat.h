@@ -175,10 +175,12 @@ zo_status zo_gemm_nt(const void* X_dev, const void* W_dev, void* Y_dev, int32_t 
  * out[b,s,h,:] = sum_{j<=s} softmax_j(q[b,s,h,:].k[b,j,h,:] / sqrt(dh)) v[b,j,h,:].
  * q, k, v: dev, storage type dtype, element (b,s,h,i) at ((b*S + s) * row_stride + h*dh + i)
  * (row_stride lets them live inside one fused [B*S][3*H*dh] buffer); out: dev [B*S][H*dh].
- * dh must be 16, 32, 64 or 128 and row_stride a multiple of 8. */
+ * dh must be 16, 32, 64 or 128 and row_stride a multiple of 8.  scratch: dev buffer of
+ * zo_attention_scratch_bytes(...) bytes (0 bytes, and NULL accepted, when the generic kernel runs). */
+size_t zo_attention_scratch_bytes(int32_t B, int32_t S, int32_t H, int32_t dh, int32_t dtype);
 zo_status zo_attention_causal(const void* q_dev, const void* k_dev, const void* v_dev, void* out_dev,
                               int32_t B, int32_t S, int32_t H, int32_t dh, int64_t row_stride, int32_t dtype,
-                              void* hip_stream);
+                              void* scratch_dev, void* hip_stream);
 
 /* Device buffers of the context's last forward, for layer-level parity tests.
  * which: 0 = final hidden state [M][d], 1 = logits fp32 [M][V] (linear arch: output Y [M][N]),

@@ -22,7 +22,8 @@ ACT_FP32, ACT_BF16 = 0, 1
 EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "zo_destroy", "zo_last_error",
            "zo_forward_quant", "zo_step", "zo_update", "zo_debug_philox_u32", "zo_debug_normal", "zo_update_tensor",
            "zo_debug_quant_weight", "zo_debug_quant_act", "zo_linear_scratch_bytes", "zo_linear_fakequant",
-           "zo_gemm_nt", "zo_debug_buffer", "zo_profile_begin", "zo_profile_end", "zo_attention_causal"]
+           "zo_gemm_nt", "zo_debug_buffer", "zo_profile_begin", "zo_profile_end", "zo_attention_causal",
+           "zo_attention_scratch_bytes"]
 PROF_NAMES = ["gemm", "weight_quant", "act_quant", "attention", "update", "other"]
 
 
@@ -66,7 +67,9 @@ _lib.zo_linear_scratch_bytes.restype = _sz
 _lib.zo_linear_fakequant.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _u64, _i32, _f32, _vp, _vp]
 _lib.zo_gemm_nt.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp]
 _lib.zo_debug_buffer.argtypes = [_vp, _i32, _i32, C.POINTER(_vp), C.POINTER(_sz)]
-_lib.zo_attention_causal.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i64, _i32, _vp]
+_lib.zo_attention_causal.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i64, _i32, _vp, _vp]
+_lib.zo_attention_scratch_bytes.argtypes = [_i32, _i32, _i32, _i32, _i32]
+_lib.zo_attention_scratch_bytes.restype = _sz
 _lib.zo_profile_begin.argtypes = [_vp]
 _lib.zo_profile_end.argtypes = [_vp, C.POINTER(C.c_float), C.POINTER(_i32)]
 
@@ -242,6 +245,8 @@ def zo_attention_causal(qkv, B, S, H, dh):
     out = torch.empty((B * S, d), dtype=qkv.dtype, device=qkv.device)
     es = qkv.element_size()
     base = qkv.data_ptr()
+    nscratch = _lib.zo_attention_scratch_bytes(B, S, H, dh, dtype)
+    scratch = torch.empty(max(nscratch, 16), dtype=torch.uint8, device=qkv.device)
     _check(_lib.zo_attention_causal(base, base + d * es, base + 2 * d * es, out.data_ptr(), B, S, H, dh, 3 * d, dtype,
-                                    _stream()), "zo_attention_causal")
+                                    scratch.data_ptr(), _stream()), "zo_attention_causal")
     return out

@@ -78,7 +78,7 @@ struct layout {
     size_t vec[2];             // perturbed small vectors of the current sub-layer, per branch
     size_t vec_stride;         // floats per vector slot
     struct per_branch {
-        size_t x, h, hq, qkv, att, gu, act, logits, rowloss;
+        size_t x, h, hq, qkv, att, vt, gu, act, logits, rowloss;
     } br[2];
     size_t total;
 };
@@ -122,6 +122,7 @@ layout make_layout(const zo_config& c, int B, int S)
         r.hq = take(M * (d > f ? d : f) * ts);
         r.qkv = take(M * 3 * d * ts);
         r.att = take(M * d * ts);
+        r.vt = take(zo_flash_attention_scratch_bytes(B, S, c.n_heads, (int)dh));
         r.gu = take(M * ffn_rows * ts);
         r.act = take(M * f * ts);
         r.logits = take(M * V * sizeof(float));
@@ -357,7 +358,7 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
                                          M, S, H, dh, 3 * d, dt, c->st));
             if (zo_flash_attention_supported(dh, dt))
                 ZO_HIP(c, zo_launch_flash_attention(qkv, qkv + (size_t)d * ts, qkv + (size_t)2 * d * ts, F.at(c->L.br[b].att),
-                                                    B, S, H, dh, 3 * d, c->st));
+                                                    F.at(c->L.br[b].vt), B, S, H, dh, 3 * d, c->st));
             else
                 ZO_HIP(c, zo_launch_attention(qkv, qkv + (size_t)d * ts, qkv + (size_t)2 * d * ts, F.at(c->L.br[b].att),
                                               B, S, H, dh, 3 * d, dt, c->st));
@@ -673,19 +674,29 @@ zo_status zo_linear_fakequant(const void* X_dev, const float* W_dev, const float
     return zo_launch_gemm(a, st) == hipSuccess ? ZO_OK : ZO_EHIP;
 }
 
+size_t zo_attention_scratch_bytes(int32_t B, int32_t S, int32_t H, int32_t dh, int32_t dtype)
+{
+    if (B <= 0 || S <= 0 || H <= 0 || !zo_flash_attention_supported(dh, dtype)) return 0;
+    return zo_flash_attention_scratch_bytes(B, S, H, dh);
+}
+
 zo_status zo_attention_causal(const void* q_dev, const void* k_dev, const void* v_dev, void* out_dev,
                               int32_t B, int32_t S, int32_t H, int32_t dh, int64_t row_stride, int32_t dtype,
-                              void* hip_stream)
+                              void* scratch_dev, void* hip_stream)
 {
     if (!q_dev || !k_dev || !v_dev || !out_dev || B < 0 || S < 0 || H <= 0) return ZO_EINVAL;
     if (dtype != ZO_ACT_FP32 && dtype != ZO_ACT_BF16) return ZO_EINVAL;
     if (dh != 16 && dh != 32 && dh != 64 && dh != 128) return ZO_EUNSUPPORTED;
     if (row_stride < (int64_t)H * dh || (row_stride & 7)) return ZO_ESHAPE;
-    if (!aligned16(q_dev) || !aligned16(k_dev) || !aligned16(v_dev) || !aligned16(out_dev)) return ZO_EALIGN;
+    if (!aligned16(q_dev) || !aligned16(k_dev) || !aligned16(v_dev) || !aligned16(out_dev) || !aligned16(scratch_dev)) return ZO_EALIGN;
     hipStream_t st = (hipStream_t)hip_stream;
-    hipError_t e = zo_flash_attention_supported(dh, dtype)
-                       ? zo_launch_flash_attention(q_dev, k_dev, v_dev, out_dev, B, S, H, dh, row_stride, st)
-                       : zo_launch_attention(q_dev, k_dev, v_dev, out_dev, B, S, H, dh, row_stride, dtype, st);
+    hipError_t e;
+    if (zo_flash_attention_supported(dh, dtype)) {
+        if (!scratch_dev && B > 0 && S > 0) return ZO_EINVAL;
+        e = zo_launch_flash_attention(q_dev, k_dev, v_dev, out_dev, scratch_dev, B, S, H, dh, row_stride, st);
+    } else {
+        e = zo_launch_attention(q_dev, k_dev, v_dev, out_dev, B, S, H, dh, row_stride, dtype, st);
+    }
     return e == hipSuccess ? ZO_OK : ZO_EHIP;
 }
 
