@@ -58,14 +58,53 @@ hipError_t zo_launch_normal(uint64_t seed, int32_t tid, int64_t start, int64_t n
 
 // ---------------------------------------------------------------------------------------------
 // update (Eq. 3): w_i <- fma(-c, u_i, w_i).  8 B of HBM traffic per parameter, u regenerated.
-// One thread owns one Philox block = 8 consecutive parameters (two 16-byte accesses).
+// Main kernel: a workgroup owns 4096 consecutive parameters; a wave sweeps 512 of them with two
+// fully coalesced 16-byte accesses per lane (elements 4L..4L+3 and 256+4L..), then neighbouring
+// lanes swap halves (DPP) so that every lane holds one whole Philox block of 8 parameters
+// (even lane: block L/2 of the first half, odd lane: block 32 + L/2), and swap back for the store.
+// The part of a tensor beyond the last multiple of 4096 goes through the simple tail kernel.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void zo_update_kernel(float* __restrict__ w, int64_t numel, zo_stream s,
+__device__ __forceinline__ float swap_adjacent_lanes(float x)
+{
+    return __uint_as_float(__builtin_amdgcn_mov_dpp(__float_as_uint(x), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+}
+
+__global__ __launch_bounds__(256) void zo_update_kernel(float* __restrict__ w, zo_stream s,
                                                         const float* __restrict__ coeff_dev, float coeff_host)
 {
     const float negc = -(coeff_dev ? *coeff_dev : coeff_host);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const bool odd = lane & 1;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int64_t e0 = ((int64_t)blockIdx.x * 2 + u) * 2048 + wave * 512;
+        float4* p = reinterpret_cast<float4*>(w + e0) + lane;
+        float4 A = p[0], B = p[64];
+        float y0 = odd ? A.x : B.x, y1 = odd ? A.y : B.y, y2 = odd ? A.z : B.z, y3 = odd ? A.w : B.w;
+        float n0 = swap_adjacent_lanes(y0), n1 = swap_adjacent_lanes(y1), n2 = swap_adjacent_lanes(y2), n3 = swap_adjacent_lanes(y3);
+        float v[8], z[8];
+        v[0] = odd ? n0 : A.x; v[1] = odd ? n1 : A.y; v[2] = odd ? n2 : A.z; v[3] = odd ? n3 : A.w;
+        v[4] = odd ? B.x : n0; v[5] = odd ? B.y : n1; v[6] = odd ? B.z : n2; v[7] = odd ? B.w : n3;
+        zo_z8(s, (uint64_t)(e0 >> 3) + (odd ? 32 : 0) + (lane >> 1), z);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = __builtin_fmaf(negc, z[i], v[i]);
+        y0 = odd ? v[0] : v[4]; y1 = odd ? v[1] : v[5]; y2 = odd ? v[2] : v[6]; y3 = odd ? v[3] : v[7];
+        n0 = swap_adjacent_lanes(y0); n1 = swap_adjacent_lanes(y1); n2 = swap_adjacent_lanes(y2); n3 = swap_adjacent_lanes(y3);
+        A = odd ? make_float4(n0, n1, n2, n3) : make_float4(v[0], v[1], v[2], v[3]);
+        B = odd ? make_float4(v[4], v[5], v[6], v[7]) : make_float4(n0, n1, n2, n3);
+        p[0] = A;
+        p[64] = B;
+    }
+}
+
+// elements [first, numel): one Philox block per thread, then the ragged end one element per thread
+__global__ __launch_bounds__(256) void zo_update_tail_kernel(float* __restrict__ w, int64_t first, int64_t numel, zo_stream s,
+                                                             const float* __restrict__ coeff_dev, float coeff_host)
+{
+    const float negc = -(coeff_dev ? *coeff_dev : coeff_host);
     const int64_t nblk = numel >> 3;
-    for (int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x; b < nblk; b += (int64_t)gridDim.x * 256) {
+    const int64_t b = (first >> 3) + (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (b < nblk) {
         float v[8], z[8];
         zo_load8(w + 8 * b, v);
         zo_z8(s, (uint64_t)b, z);
@@ -73,9 +112,8 @@ __global__ __launch_bounds__(256) void zo_update_kernel(float* __restrict__ w, i
         for (int i = 0; i < 8; ++i) v[i] = __builtin_fmaf(negc, z[i], v[i]);
         zo_store8(w + 8 * b, v);
     }
-    // ragged tail (numel not a multiple of 8)
     if (blockIdx.x == 0) {
-        int64_t i = 8 * nblk + threadIdx.x;
+        const int64_t i = 8 * nblk + threadIdx.x;
         if (i < numel) w[i] = __builtin_fmaf(negc, zo_z1(s, (uint64_t)i), w[i]);
     }
 }
@@ -84,7 +122,15 @@ hipError_t zo_launch_update(float* w, int64_t numel, uint64_t seed, int32_t tid,
                             const float* coeff_dev, float coeff_host, hipStream_t st)
 {
     if (numel == 0) return hipSuccess;
-    zo_update_kernel<<<grid_for(numel >> 3, 256, 256 * 16), 256, 0, st>>>(w, numel, make_stream(seed, tid), coeff_dev, coeff_host);
+    const zo_stream s = make_stream(seed, tid);
+    const int64_t main_blocks = numel / 4096;
+    if (main_blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+    if (main_blocks > 0) zo_update_kernel<<<(int)main_blocks, 256, 0, st>>>(w, s, coeff_dev, coeff_host);
+    const int64_t first = main_blocks * 4096;
+    if (first < numel) {
+        const int64_t tail_blk = ((numel >> 3) - (first >> 3) + 255) / 256;
+        zo_update_tail_kernel<<<(int)(tail_blk > 0 ? tail_blk : 1), 256, 0, st>>>(w, first, numel, s, coeff_dev, coeff_host);
+    }
     return hipGetLastError();
 }
 
@@ -132,10 +178,9 @@ __global__ __launch_bounds__(256) void zo_fq_weight_kernel(const float* __restri
                                                            uint8_t* codes, float* step, int32_t* zp)
 {
     const int lane = threadIdx.x & 63;
-    // trip count uniform over the wave: every lane takes part in the shuffles
-    const int64_t first = (int64_t)blockIdx.x * 256 + (threadIdx.x & ~63);
-    for (int64_t base = first; base < nblk; base += (int64_t)gridDim.x * 256) {
-        const int64_t b = base + lane;
+    // one Philox block per thread; every lane of a wave takes part in the shuffles
+    {
+        const int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
         const bool active = b < nblk;
         float w[8], z[8];
         if (active) {
@@ -240,7 +285,8 @@ template <typename TO, int GL>
 static hipError_t launch_fq_weight_gl(const float* W, int64_t nblk, zo_stream s, float eps, int bits, TO* op, TO* om,
                                       uint8_t* codes, float* step, int32_t* zp, hipStream_t st)
 {
-    const int grid = grid_for(nblk, 256, 256 * 16);
+    if ((nblk + 255) / 256 > 0x7FFFFFFF) return hipErrorInvalidValue;
+    const int grid = (int)((nblk + 255) / 256);
     if (codes || step || zp)
         zo_fq_weight_kernel<TO, GL, true><<<grid, 256, 0, st>>>(W, nblk, s, eps, bits, op, om, codes, step, zp);
     else
