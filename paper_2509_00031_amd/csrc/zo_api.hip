@@ -239,6 +239,22 @@ struct fwd {
                                      M, c->cfg.d_model, 1e-5f, dt(), c->st));
         return ZO_OK;
     }
+    // norm followed by the per-token quantizer, fused when the row fits in registers
+    zo_status norm_quant(size_t layout::per_branch::*in, bool has_beta, size_t layout::per_branch::** used)
+    {
+        const int d = c->cfg.d_model;
+        if (c->cfg.a_bits >= 16 || !zo_norm_quant_supported(d)) {
+            zo_status s_ = norm(in, &layout::per_branch::h, has_beta);
+            if (s_ != ZO_OK) return s_;
+            return act_quant(&layout::per_branch::h, d, used);
+        }
+        prof_scope ps(c, ZO_PROF_ACT_QUANT);
+        for (int b = 0; b < nb; ++b)
+            ZO_HIP(c, zo_launch_norm_quant(at(c->L.br[b].*in), vec(b, 0), has_beta ? vec(b, 1) : nullptr, at(c->L.br[b].hq),
+                                           M, d, 1e-5f, c->cfg.a_bits, c->cfg.a_sym, dt(), c->st));
+        *used = &layout::per_branch::hq;
+        return ZO_OK;
+    }
     // per-token quantizer of the input of a quantized linear; returns which buffer holds X^
     zo_status act_quant(size_t layout::per_branch::*in, int K, size_t layout::per_branch::** used)
     {
@@ -343,8 +359,7 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
         // ---- attention block
         ZO_TRY(F.vector(t++, 0));
         if (!llama) ZO_TRY(F.vector(t++, 1));
-        ZO_TRY(F.norm(&PB::x, &PB::h, !llama));
-        ZO_TRY(F.act_quant(&PB::h, d, &xin));
+        ZO_TRY(F.norm_quant(&PB::x, !llama, &xin));
         for (int i = 0; i < 3; ++i) {
             ZO_TRY(F.weights(t++, (int64_t)i * d, true));
             if (!llama) ZO_TRY(F.vector(t++, 2, (int64_t)i * d));
@@ -370,23 +385,29 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
         // ---- feed-forward block
         ZO_TRY(F.vector(t++, 0));
         if (!llama) ZO_TRY(F.vector(t++, 1));
-        ZO_TRY(F.norm(&PB::x, &PB::h, !llama));
-        ZO_TRY(F.act_quant(&PB::h, d, &xin));
+        ZO_TRY(F.norm_quant(&PB::x, !llama, &xin));
+        bool act_done = false;
         if (llama) {
             ZO_TRY(F.weights(t++, 0, true));
             ZO_TRY(F.weights(t++, f, true));
             ZO_TRY(F.gemm(xin, &PB::gu, 2 * f, d, false, false, false));
-            prof_scope ps(c, ZO_PROF_OTHER);
+            act_done = cfg.a_bits < 16 && zo_swiglu_quant_supported(f);
+            prof_scope ps(c, act_done ? ZO_PROF_ACT_QUANT : ZO_PROF_OTHER);
             for (int b = 0; b < nb; ++b) {
                 char* gu = F.at(c->L.br[b].gu);
-                ZO_HIP(c, zo_launch_swiglu(gu, gu + (size_t)f * ts, F.at(c->L.br[b].act), M, f, 2 * f, dt, c->st));
+                if (act_done)
+                    ZO_HIP(c, zo_launch_swiglu_quant(gu, gu + (size_t)f * ts, F.at(c->L.br[b].hq), M, f, 2 * f,
+                                                     cfg.a_bits, cfg.a_sym, dt, c->st));
+                else
+                    ZO_HIP(c, zo_launch_swiglu(gu, gu + (size_t)f * ts, F.at(c->L.br[b].act), M, f, 2 * f, dt, c->st));
             }
         } else {
             ZO_TRY(F.weights(t++, 0, true));
             ZO_TRY(F.vector(t++, 2));
             ZO_TRY(F.gemm(xin, &PB::act, f, d, true, true, false));
         }
-        ZO_TRY(F.act_quant(&PB::act, f, &xin));
+        if (act_done) xin = &PB::hq;
+        else ZO_TRY(F.act_quant(&PB::act, f, &xin));
         ZO_TRY(F.weights(t++, 0, true));
         if (!llama) ZO_TRY(F.vector(t++, 2));
         ZO_TRY(F.gemm(xin, &PB::x, d, f, !llama, false, true));

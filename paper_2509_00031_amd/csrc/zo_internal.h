@@ -51,6 +51,14 @@ hipError_t zo_launch_embed(const int32_t* ids, const float* tok_emb, const float
 // RMSNorm (beta = NULL) or LayerNorm; gamma/beta are already perturbed fp32 vectors
 hipError_t zo_launch_norm(const void* x, const float* gamma, const float* beta, void* out,
                           int32_t M, int32_t d, float eps, int dtype, hipStream_t st);
+// norm fused with the per-token quantizer (row kept in registers): d <= 8192
+bool zo_norm_quant_supported(int32_t d);
+hipError_t zo_launch_norm_quant(const void* x, const float* gamma, const float* beta, void* xhat, int32_t M, int32_t d,
+                                float eps, int32_t bits, int32_t sym, int dtype, hipStream_t st);
+// SwiGLU fused with the per-token quantizer: cols <= 16384
+bool zo_swiglu_quant_supported(int32_t cols);
+hipError_t zo_launch_swiglu_quant(const void* gate, const void* up, void* xhat, int64_t rows, int32_t cols, int64_t in_stride,
+                                  int32_t bits, int32_t sym, int dtype, hipStream_t st);
 hipError_t zo_launch_rope(void* q, void* k, const float* cos_tab, const float* sin_tab,
                           int32_t M, int32_t S, int32_t H, int32_t dh, int64_t row_stride, int dtype, hipStream_t st);
 hipError_t zo_launch_attention(const void* q, const void* k, const void* v, void* out,

@@ -127,6 +127,102 @@ hipError_t zo_launch_norm(const void* x, const float* gamma, const float* beta, 
 }
 
 // ---------------------------------------------------------------------------------------------
+// RMSNorm / LayerNorm fused with the per-token quantizer of the linear that follows:
+// x^ = rt(Q_A(rt(norm(x)))).  One wavefront per row, the row stays in registers (d <= 512 * NC).
+// ---------------------------------------------------------------------------------------------
+template <typename T, int NC>
+__global__ __launch_bounds__(256) void zo_norm_quant_kernel(const T* __restrict__ x, const float* __restrict__ gamma,
+                                                            const float* __restrict__ beta, T* __restrict__ xhat, int M, int d,
+                                                            float eps, int bits, int sym)
+{
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= M) return;
+    const T* xr = x + (int64_t)row * d;
+    float v[NC][8];
+    float s1 = 0.0f, s2 = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+        const int c = lane * 8 + 512 * i;
+        if (c < d) {
+            zo_load8(xr + c, v[i]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { s1 += v[i][e]; s2 = __builtin_fmaf(v[i][e], v[i][e], s2); }
+        }
+    }
+    s1 = zo_group_sum<64>(s1);
+    s2 = zo_group_sum<64>(s2);
+    float mean = 0.0f, var;
+    if (beta) {
+        mean = s1 / (float)d;
+        float sv = 0.0f;
+#pragma unroll
+        for (int i = 0; i < NC; ++i)
+            if (lane * 8 + 512 * i < d) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) { float t = v[i][e] - mean; sv = __builtin_fmaf(t, t, sv); }
+            }
+        var = zo_group_sum<64>(sv) / (float)d;
+    } else {
+        var = s2 / (float)d;
+    }
+    const float rstd = 1.0f / __builtin_sqrtf(var + eps);
+    float mn = INFINITY, mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+        const int c = lane * 8 + 512 * i;
+        if (c < d) {
+            float g[8];
+            zo_load8(gamma + c, g);
+            if (beta) {
+                float b[8];
+                zo_load8(beta + c, b);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[i][e] = zo_round_to<T>(__builtin_fmaf((v[i][e] - mean) * rstd, g[e], b[e]));
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[i][e] = zo_round_to<T>((v[i][e] * rstd) * g[e]);
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                if (sym) mx = fmaxf(mx, fabsf(v[i][e]));
+                else { mn = fminf(mn, v[i][e]); mx = fmaxf(mx, v[i][e]); }
+            }
+        }
+    }
+    mn = zo_group_min<64>(mn);
+    mx = zo_group_max<64>(mx);
+    const zo_qparams q = sym ? zo_qparams_sym(mx, bits) : zo_qparams_asym(mn, mx, bits);
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+        const int c = lane * 8 + 512 * i;
+        if (c < d) {
+            float o[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = zo_dequant(q, zo_code(q, v[i][e]));
+            zo_store8(xhat + (int64_t)row * d + c, o);
+        }
+    }
+}
+
+bool zo_norm_quant_supported(int32_t d) { return d > 0 && (d & 7) == 0 && d <= 8192; }
+
+hipError_t zo_launch_norm_quant(const void* x, const float* gamma, const float* beta, void* xhat, int32_t M, int32_t d,
+                                float eps, int32_t bits, int32_t sym, int dtype, hipStream_t st)
+{
+    if (M == 0) return hipSuccess;
+    const int grid = (M + 3) / 4;
+#define ZO_NQ(T, NC) zo_norm_quant_kernel<T, NC><<<grid, 256, 0, st>>>((const T*)x, gamma, beta, (T*)xhat, M, d, eps, bits, sym)
+    if (dtype == ZO_T_BF16) {
+        if (d <= 2048) ZO_NQ(zo_bf16, 4); else if (d <= 4096) ZO_NQ(zo_bf16, 8); else ZO_NQ(zo_bf16, 16);
+    } else {
+        if (d <= 2048) ZO_NQ(float, 4); else if (d <= 4096) ZO_NQ(float, 8); else ZO_NQ(float, 16);
+    }
+#undef ZO_NQ
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
 // rotary embedding on q and k, in place: pairs (i, i + dh/2) of every head, angle table [S][dh/2]
 // ---------------------------------------------------------------------------------------------
 template <typename T>
@@ -277,6 +373,69 @@ hipError_t zo_launch_swiglu(const void* gate, const void* up, void* out, int64_t
     int grid = (int)((total + 255) / 256 < 262144 ? (total + 255) / 256 : 262144);
     if (dtype == ZO_T_BF16) zo_swiglu_kernel<zo_bf16><<<grid, 256, 0, st>>>((const zo_bf16*)gate, (const zo_bf16*)up, (zo_bf16*)out, rows, cols, in_stride);
     else zo_swiglu_kernel<float><<<grid, 256, 0, st>>>((const float*)gate, (const float*)up, (float*)out, rows, cols, in_stride);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// SwiGLU fused with the per-token quantizer of the down projection:
+// x^ = rt(Q_A(rt(silu(gate) * up))).  One workgroup per row, the row stays in registers.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int NC>
+__global__ __launch_bounds__(256) void zo_swiglu_quant_kernel(const T* __restrict__ gate, const T* __restrict__ up, T* __restrict__ xhat,
+                                                              int cols, int64_t in_stride, int bits, int sym)
+{
+    __shared__ float red[2][4];
+    const int64_t row = blockIdx.x;
+    float v[NC][8];
+    float mn = INFINITY, mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+        const int c = threadIdx.x * 8 + 2048 * i;
+        if (c < cols) {
+            float g[8], u[8];
+            zo_load8(gate + row * in_stride + c, g);
+            zo_load8(up + row * in_stride + c, u);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                v[i][e] = zo_round_to<T>((g[e] / (1.0f + __expf(-g[e]))) * u[e]);
+                if (sym) mx = fmaxf(mx, fabsf(v[i][e]));
+                else { mn = fminf(mn, v[i][e]); mx = fmaxf(mx, v[i][e]); }
+            }
+        }
+    }
+    mn = zo_group_min<64>(mn);
+    mx = zo_group_max<64>(mx);
+    if ((threadIdx.x & 63) == 0) { red[0][threadIdx.x >> 6] = mn; red[1][threadIdx.x >> 6] = mx; }
+    __syncthreads();
+    mn = fminf(fminf(red[0][0], red[0][1]), fminf(red[0][2], red[0][3]));
+    mx = fmaxf(fmaxf(red[1][0], red[1][1]), fmaxf(red[1][2], red[1][3]));
+    const zo_qparams q = sym ? zo_qparams_sym(mx, bits) : zo_qparams_asym(mn, mx, bits);
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+        const int c = threadIdx.x * 8 + 2048 * i;
+        if (c < cols) {
+            float o[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = zo_dequant(q, zo_code(q, v[i][e]));
+            zo_store8(xhat + row * cols + c, o);
+        }
+    }
+}
+
+bool zo_swiglu_quant_supported(int32_t cols) { return cols > 0 && (cols & 7) == 0 && cols <= 16384; }
+
+hipError_t zo_launch_swiglu_quant(const void* gate, const void* up, void* xhat, int64_t rows, int32_t cols, int64_t in_stride,
+                                  int32_t bits, int32_t sym, int dtype, hipStream_t st)
+{
+    if (rows == 0) return hipSuccess;
+    if (rows > 0x7FFFFFFF) return hipErrorInvalidValue;
+#define ZO_SQ(T, NC) zo_swiglu_quant_kernel<T, NC><<<(int)rows, 256, 0, st>>>((const T*)gate, (const T*)up, (T*)xhat, cols, in_stride, bits, sym)
+    if (dtype == ZO_T_BF16) {
+        if (cols <= 4096) ZO_SQ(zo_bf16, 2); else if (cols <= 12288) ZO_SQ(zo_bf16, 6); else ZO_SQ(zo_bf16, 8);
+    } else {
+        if (cols <= 4096) ZO_SQ(float, 2); else if (cols <= 12288) ZO_SQ(float, 6); else ZO_SQ(float, 8);
+    }
+#undef ZO_SQ
     return hipGetLastError();
 }
 
