@@ -10,6 +10,8 @@
  *   - group-wise weights, per-token activations          (Appendix "Quantization settings")
  *   - the two-point zeroth-order estimate, q = 1         (Eq. 2)
  *   - the ZO-SGD update on full-precision master weights (Eq. 3)
+ *   - frozen, pre-quantized weights of the lightweight variant
+ *                                 (Section "Lightweight ZeroQAT for memory reduction")
  * The paper only says u ~ N(0, I); the concrete counter-based stream used here
  * (Philox4x32-10 of Salmon et al. 2011 + a fixed-recipe Box-Muller) is this
  * build's reading.  The *choice* of generator is "parity unpinned": nothing in
@@ -257,6 +259,106 @@ void zo_or_fakequant_weight(const float* W, int N, int K, int bits, int group,
         free(wp);
         free(hat);
     }
+}
+
+/* ------------------------------------------------------------------ */
+/* Frozen, pre-quantized weights (Section "Lightweight ZeroQAT"):       */
+/* 4-bit codes packed two per byte + one fp16 step and one int16 zero   */
+/* point per group.  The paper fixes no storage format; this one is the */
+/* build's reading.                                                     */
+/* ------------------------------------------------------------------ */
+
+/* fp32 -> IEEE binary16 bits, round to nearest even, subnormals kept,
+ * overflow to infinity.  Written with integer arithmetic only. */
+uint16_t zo_or_f32_to_f16_bits(float v)
+{
+    uint32_t u;
+    memcpy(&u, &v, 4);
+    uint32_t sign = (u >> 16) & 0x8000u;
+    uint32_t mag = u & 0x7FFFFFFFu;
+    if (mag >= 0x7F800000u)                          /* inf / nan */
+        return (uint16_t)(sign | 0x7C00u | ((mag > 0x7F800000u) ? 0x200u : 0u));
+    int32_t e = (int32_t)(mag >> 23) - 127;          /* unbiased exponent */
+    uint32_t m = (mag & 0x7FFFFFu) | 0x800000u;      /* 24-bit significand, 1.xxx */
+    if (mag < 0x00800000u) return (uint16_t)sign;    /* fp32 subnormal: far below half's range */
+    /* value = m * 2^(e-23).  half: normal needs e >= -14; below that the
+     * spacing is fixed at 2^-24. */
+    int shift;                                       /* bits dropped from m */
+    uint32_t base;                                   /* exponent field contribution */
+    if (e >= -14) { shift = 13; base = (uint32_t)(e + 15) << 10; }
+    else          { shift = 13 + (-14 - e); base = 0; }
+    if (shift > 25) return (uint16_t)sign;           /* rounds to zero */
+    uint32_t keep = m >> shift;
+    uint32_t rem  = m & ((1u << shift) - 1u);
+    uint32_t half = 1u << (shift - 1);
+    if (rem > half || (rem == half && (keep & 1u))) keep += 1u;
+    /* normal: keep has the implicit bit at position 10; adding base-0x400
+     * lets a carry out of the significand bump the exponent. */
+    uint32_t h = (e >= -14) ? (base - 0x400u + keep) : keep;
+    if (h >= 0x7C00u) h = 0x7C00u;                   /* overflow */
+    return (uint16_t)(sign | h);
+}
+
+float zo_or_f16_bits_to_f32(uint16_t h)
+{
+    uint32_t sign = ((uint32_t)h & 0x8000u) << 16;
+    int32_t e = (h >> 10) & 0x1F;
+    uint32_t m = h & 0x3FFu;
+    float mag;
+    if (e == 0)       mag = ldexpf((float)m, -24);
+    else if (e == 31) mag = m ? NAN : INFINITY;
+    else              mag = ldexpf((float)(m | 0x400u), e - 25);
+    uint32_t u;
+    memcpy(&u, &mag, 4);
+    u |= sign;
+    memcpy(&mag, &u, 4);
+    return mag;
+}
+
+/* Pre-quantize W[N,K] (no perturbation) with the asymmetric 4-bit group
+ * quantizer above.  Outputs: packed[N][K/2], byte j of a row holds the code
+ * of k = 2j in its low nibble and of k = 2j+1 in its high nibble;
+ * step_f16[N][K/group] the group step rounded to binary16;
+ * zp[N][K/group] the zero point saturated to int16. */
+void zo_or_pack_int4(const float* W, int N, int K, int group,
+                     uint8_t* packed, uint16_t* step_f16, int16_t* zp)
+{
+    int G = K / group;
+    #pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        int32_t* codes = (int32_t*)malloc(sizeof(int32_t) * (size_t)group);
+        for (int g = 0; g < G; ++g) {
+            float st;
+            int32_t z;
+            zo_or_quant_group(W + (int64_t)n * K + (int64_t)g * group, group, 4, 0, &st, &z, codes, NULL);
+            step_f16[(int64_t)n * G + g] = zo_or_f32_to_f16_bits(st);
+            zp[(int64_t)n * G + g] = (int16_t)(z < -32768 ? -32768 : (z > 32767 ? 32767 : z));
+            for (int k = 0; k < group; k += 2)
+                packed[((int64_t)n * K + (int64_t)g * group + k) / 2] =
+                    (uint8_t)((codes[k] & 15) | ((codes[k + 1] & 15) << 4));
+        }
+        free(codes);
+    }
+}
+
+/* w^[n,k] = (code - zp) * step, step read back from binary16, product in
+ * fp32 (the integer difference is exact in fp32), optionally rounded to
+ * bf16, the GEMM operand type. */
+void zo_or_dequant_int4(const uint8_t* packed, const uint16_t* step_f16, const int16_t* zp,
+                        int N, int K, int group, int round_bf16, float* what)
+{
+    int G = K / group;
+    #pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int k = 0; k < K; ++k) {
+            int64_t i = (int64_t)n * K + k;
+            uint8_t byte = packed[i / 2];
+            int code = (k & 1) ? (byte >> 4) : (byte & 15);
+            int64_t gi = (int64_t)n * G + k / group;
+            float st = zo_or_f16_bits_to_f32(step_f16[gi]);
+            float v = (float)(code - (int)zp[gi]) * st;
+            what[i] = round_bf16 ? zo_or_bf16_round(v) : v;
+        }
 }
 
 /* Per-token activation fake-quantizer: each row of X[M,K] is one group.

@@ -63,6 +63,15 @@ _lib.zo_or_fakequant_weight.argtypes = [_f32p, C.c_int, C.c_int, C.c_int, C.c_in
 _lib.zo_or_fakequant_act.argtypes = [_f32p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
 _lib.zo_or_linear.argtypes = [_f32p, _f32p, C.c_void_p, C.c_int, C.c_int, C.c_int, _f64p]
+_u8p = np.ctypeslib.ndpointer(np.uint8, flags="C_CONTIGUOUS")
+_u16p = np.ctypeslib.ndpointer(np.uint16, flags="C_CONTIGUOUS")
+_i16p = np.ctypeslib.ndpointer(np.int16, flags="C_CONTIGUOUS")
+_lib.zo_or_f32_to_f16_bits.argtypes = [C.c_float]
+_lib.zo_or_f32_to_f16_bits.restype = C.c_uint16
+_lib.zo_or_f16_bits_to_f32.argtypes = [C.c_uint16]
+_lib.zo_or_f16_bits_to_f32.restype = C.c_float
+_lib.zo_or_pack_int4.argtypes = [_f32p, C.c_int, C.c_int, C.c_int, _u8p, _u16p, _i16p]
+_lib.zo_or_dequant_int4.argtypes = [_u8p, _u16p, _i16p, C.c_int, C.c_int, C.c_int, C.c_int, _f32p]
 _lib.zo_or_projected_grad.argtypes = [C.c_float, C.c_float, C.c_float]
 _lib.zo_or_projected_grad.restype = C.c_float
 _lib.zo_or_coeff.argtypes = [C.c_float, C.c_float]
@@ -158,6 +167,41 @@ def fakequant_act(X, bits, sym=False, round_bf16=False, want_codes=True):
     xhat = np.empty((M, K), np.float32)
     _lib.zo_or_fakequant_act(X, M, K, bits, int(sym), int(round_bf16), _opt(codes), _opt(step), _opt(zp), _opt(xhat))
     return dict(codes=codes, step=step, zp=zp, xhat=xhat)
+
+
+def f32_to_f16_bits(v):
+    return int(_lib.zo_or_f32_to_f16_bits(float(np.float32(v))))
+
+
+def f16_bits_to_f32(h):
+    return np.float32(_lib.zo_or_f16_bits_to_f32(int(h)))
+
+
+class PackedInt4:
+    """A frozen, pre-quantized weight matrix of the lightweight variant: 4-bit codes two per byte
+    (low nibble = even in-feature), one binary16 step and one int16 zero point per group."""
+
+    def __init__(self, codes, step_f16, zp, N, K, group):
+        self.codes, self.step_f16, self.zp, self.N, self.K, self.group = codes, step_f16, zp, N, K, group
+
+
+def pack_int4(W, group):
+    """Pre-quantize W[N,K] with the asymmetric 4-bit group quantizer (no perturbation)."""
+    W = np.ascontiguousarray(W, np.float32)
+    N, K = W.shape
+    assert K % group == 0 and group % 2 == 0
+    codes = np.empty((N, K // 2), np.uint8)
+    step = np.empty((N, K // group), np.uint16)
+    zp = np.empty((N, K // group), np.int16)
+    _lib.zo_or_pack_int4(W, N, K, group, codes, step, zp)
+    return PackedInt4(codes, step, zp, N, K, group)
+
+
+def dequant_int4(p, round_bf16=False):
+    """w^ = (code - zp) * step of a packed matrix, fp32 (optionally rounded to bf16)."""
+    what = np.empty((p.N, p.K), np.float32)
+    _lib.zo_or_dequant_int4(p.codes, p.step_f16, p.zp, p.N, p.K, p.group, int(round_bf16), what)
+    return what
 
 
 def linear(xhat, what, bias=None):
@@ -265,6 +309,9 @@ class _Params:
         """Q(W + eps z) of a quantized linear, de-quantized, in the GEMM operand type."""
         i = self.index[name]
         cfg = self.cfg
+        if isinstance(self.params[i], PackedInt4):     # frozen and pre-quantized: used as stored
+            assert self.trainable is not None and not self.trainable[i]
+            return dequant_int4(self.params[i], round_bf16=(cfg.act_dtype == 1))
         return fakequant_weight(self.params[i], cfg.w_bits, cfg.w_group, self.seed, i, self._eps_for(i),
                                 round_bf16=(cfg.act_dtype == 1), want_codes=False)["what"]
 
@@ -420,6 +467,7 @@ def forward(cfg, params, ids=None, x=None, target=None, seed=0, eps_signed=0.0, 
 def zo_step(cfg, params, seed, eps, lr, ids=None, x=None, target=None, trainable=None):
     """One ZO-SGD step (Eq. 2 with q = 1, then Eq. 3), updating `params` in place.
 
+    Entries of `params` that are PackedInt4 are frozen (their `trainable` flag must be False).
     Returns (L+, L-, g) as fp32."""
     eps = np.float32(eps)
     lp = forward(cfg, params, ids, x, target, seed, eps, trainable)
