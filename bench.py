@@ -26,6 +26,10 @@ WORKLOADS = {
                                      w_bits=2, w_group=64, a_bits=16, B=8, S=1024),
     "opt1p3b_w4a8_g128_16x512": dict(arch="opt", n_layers=24, d_model=2048, n_heads=32, d_ffn=8192, vocab=50272,
                                      w_bits=4, w_group=128, a_bits=8, B=16, S=512),
+    # 13B shape, lightweight variant: everything frozen (linears as packed 4-bit codes + binary16 steps, group 128),
+    # only the query / value projections trainable; per-token 4-bit activations; 4 x 2048 tokens
+    "llama13b_lightweight_w4a4_g128_4x2048": dict(arch="llama", n_layers=40, d_model=5120, n_heads=40, d_ffn=13824,
+                                                  vocab=32000, w_bits=4, w_group=128, a_bits=4, B=4, S=2048, lightweight=1),
     "tiny_w4a16_g64_8x128": dict(arch="llama", n_layers=4, d_model=512, n_heads=8, d_ffn=2048, vocab=4096,
                                  w_bits=4, w_group=64, a_bits=16, B=8, S=128),
 }
@@ -61,11 +65,17 @@ def cpu_baseline(w):
     omp = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     arch = orc.ARCH_LLAMA if w["arch"] == "llama" else orc.ARCH_OPT
     cfg = orc.Config(arch, n_layers=1, d_model=w["d_model"], n_heads=w["n_heads"], d_ffn=w["d_ffn"], vocab=w["vocab"],
-                     max_seq=w["S"], w_bits=w["w_bits"], w_group=w["w_group"], a_bits=w["a_bits"], act_dtype=1)
-    params = synth.model_params(orc.param_shapes(cfg), 1234)
+                     max_seq=w["S"], w_bits=w["w_bits"], w_group=w["w_group"], a_bits=w["a_bits"], act_dtype=1,
+                     lightweight=w.get("lightweight", 0))
+    shapes = orc.param_shapes(cfg)
+    params = synth.model_params(shapes, 1234)
+    trainable = None
+    if w.get("lightweight"):
+        trainable = [name.endswith(".wq") or name.endswith(".wv") for name, _, _ in shapes]
+        params = [orc.pack_int4(p, w["w_group"]) if (q and not t) else p for p, t, (_, _, q) in zip(params, trainable, shapes)]
     ids = synth.token_ids(1, w["S"], w["vocab"], 5678)
     t0 = time.perf_counter()
-    orc.zo_step(cfg, params, 0, 1e-3, 1e-6, ids=ids)
+    orc.zo_step(cfg, params, 0, 1e-3, 1e-6, ids=ids, trainable=trainable)
     t_sample = time.perf_counter() - t0
     sample = dict(w, n_layers=1, B=1)
     ratio = gemm_flops_per_step(w) / gemm_flops_per_step(sample)
@@ -102,23 +112,34 @@ def main():
     arch = zo.ARCH_LLAMA if w["arch"] == "llama" else zo.ARCH_OPT
     cfg = zo.make_config(arch, n_layers=w["n_layers"], d_model=w["d_model"], n_heads=w["n_heads"], d_ffn=w["d_ffn"],
                          vocab=w["vocab"], max_seq=w["S"], w_bits=w["w_bits"], w_group=w["w_group"], a_bits=w["a_bits"],
-                         act_dtype=zo.ACT_BF16)
+                         act_dtype=zo.ACT_BF16, lightweight=w.get("lightweight", 0))
     n = zo.zo_num_params(cfg)
     gen = torch.Generator(device=dev)
     gen.manual_seed(1234)
     params = []
     n_params = 0
+    trainable = None
+    if w.get("lightweight"):
+        # llama tensor order: tok_emb, then per layer 9 tensors (norm, wq, wk, wv, wo, norm, gate, up, down), final norm, head
+        assert w["arch"] == "llama"
+        kind = lambda i: (i - 1) % 9 if 1 <= i <= 9 * w["n_layers"] else -1
+        trainable = [kind(i) in (1, 3) for i in range(n)]
+        packed_kinds = (2, 4, 6, 7, 8)
     for i in range(n):
         numel = zo.zo_param_numel(cfg, i)
-        n_params += numel
         t = torch.empty(numel, dtype=torch.float32, device=dev)
         t.normal_(0.0, 0.02, generator=gen)
         if numel == w["d_model"]:                       # norm gains / small vectors: around one
             t.add_(1.0)
+        if trainable is None or trainable[i]:
+            n_params += numel
+        elif kind(i) in packed_kinds:                   # frozen linear: keep only its packed 4-bit form
+            K = w["d_ffn"] if kind(i) == 8 else w["d_model"]
+            t = zo.zo_pack_weight_int4(t.view(numel // K, K), w["w_group"])
         params.append(t)
     B, S = w["B"], w["S"]
     ids = torch.randint(0, w["vocab"], (B, S), dtype=torch.int32, device=dev, generator=gen)
-    ctx = zo.Context(cfg, params, B, S)
+    ctx = zo.Context(cfg, params, B, S, trainable=trainable)
     eps, lr = 1e-3, 1e-6
 
     if args.calibrate_copy:

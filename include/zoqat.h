@@ -72,7 +72,9 @@ typedef struct {
  *            wo, bo, ln2_g, ln2_b, fc1[f][d], b1[f], fc2[d][f], b2[d]; then final_ln_g,
  *            final_ln_b, lm_head[V][d]                                                       */
 typedef struct {
-    void*   ptr;        /* dev, fp32 master weights, updated in place by zo_update / zo_step */
+    void*   ptr;        /* dev, fp32 master weights, updated in place by zo_update / zo_step; may be
+                           NULL for a frozen quantized linear of a lightweight configuration whose
+                           packed form is attached with zo_attach_frozen_int4 */
     int64_t numel;
     int32_t trainable;  /* used only when zo_config.lightweight = 1 */
     int32_t reserved;
@@ -164,6 +166,36 @@ zo_status zo_linear_fakequant(const void* X_dev, const float* W_dev, const float
                               int32_t a_bits, int32_t a_sym, int32_t dtype,
                               uint64_t seed, int32_t tensor_id, float eps_signed,
                               void* scratch_dev, void* hip_stream);
+
+/* ---- frozen, pre-quantized weights (Section "Lightweight ZeroQAT for memory reduction"): most
+ * parameters are frozen and stored quantized, only the query and value projections stay in full
+ * precision and trainable.  Storage of one frozen linear W[N][K], groups of `group` consecutive k
+ * (a power of two in 8..512 dividing K):
+ *   codes     u8   [N][K/2]      4-bit codes, k = 2j in the low nibble of byte j, k = 2j+1 in the high
+ *   step_f16  f16  [N][K/group]  group step, IEEE binary16
+ *   zp        i16  [N][K/group]  group zero point
+ * and the operand of the GEMM is w^[n][k] = (code - zp) * step, the same for both branches of
+ * Eq. 2 (no perturbation, no update). ---- */
+
+/* Pre-quantize an fp32 matrix into that form: the asymmetric 4-bit group quantizer of the Background
+ * section at eps = 0, step rounded to binary16 (nearest even), zero point saturated to int16.
+ * All pointers dev; codes 16-byte aligned.  ZO_ESHAPE if the group rule is violated. */
+zo_status zo_pack_weight_int4(const float* W_dev, int32_t N, int32_t K, int32_t group,
+                              void* codes_dev, void* step_f16_dev, int16_t* zp_dev, void* hip_stream);
+
+/* Give tensor `index` of a lightweight context its packed storage (dev pointers, owned by the
+ * caller, valid until zo_destroy).  The tensor must be a quantized linear with trainable = 0; its
+ * zo_tensor.ptr is ignored from then on.  A forward fails with ZO_EINVAL while some tensor has
+ * neither fp32 nor packed storage. */
+zo_status zo_attach_frozen_int4(zo_ctx* ctx, int32_t index, const void* codes_dev, const void* step_f16_dev,
+                                const int16_t* zp_dev, int32_t group);
+
+/* One frozen linear layer alone: Y = Q_A(X) * w^^T (+ bias), X and Y [M][*] in storage type dtype,
+ * a_bits = 16 skips the per-token quantizer.  scratch dev: zo_linear_scratch_bytes(M, N, K, dtype)
+ * bytes; on return its second part (offset = M*K*sizeof(dtype) rounded up to 256) holds w^ [N][K]. */
+zo_status zo_linear_frozen_int4(const void* X_dev, const void* codes_dev, const void* step_f16_dev, const int16_t* zp_dev,
+                                const float* bias_dev, void* Y_dev, int32_t M, int32_t N, int32_t K, int32_t group,
+                                int32_t a_bits, int32_t a_sym, int32_t dtype, void* scratch_dev, void* hip_stream);
 
 /* Plain GEMM of the path, Y[M][N] = X[M][K] * W[N][K]^T with fp32 accumulation, operands and
  * output in storage type dtype (the contraction every quantized linear runs after both operands

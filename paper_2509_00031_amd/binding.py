@@ -23,7 +23,7 @@ EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "
            "zo_forward_quant", "zo_step", "zo_update", "zo_debug_philox_u32", "zo_debug_normal", "zo_update_tensor",
            "zo_debug_quant_weight", "zo_debug_quant_act", "zo_linear_scratch_bytes", "zo_linear_fakequant",
            "zo_gemm_nt", "zo_debug_buffer", "zo_profile_begin", "zo_profile_end", "zo_attention_causal",
-           "zo_attention_scratch_bytes"]
+           "zo_attention_scratch_bytes", "zo_pack_weight_int4", "zo_attach_frozen_int4", "zo_linear_frozen_int4"]
 PROF_NAMES = ["gemm", "weight_quant", "act_quant", "attention", "update", "other"]
 
 
@@ -70,6 +70,9 @@ _lib.zo_debug_buffer.argtypes = [_vp, _i32, _i32, C.POINTER(_vp), C.POINTER(_sz)
 _lib.zo_attention_causal.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i64, _i32, _vp, _vp]
 _lib.zo_attention_scratch_bytes.argtypes = [_i32, _i32, _i32, _i32, _i32]
 _lib.zo_attention_scratch_bytes.restype = _sz
+_lib.zo_pack_weight_int4.argtypes = [_vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp]
+_lib.zo_attach_frozen_int4.argtypes = [_vp, _i32, _vp, _vp, _vp, _i32]
+_lib.zo_linear_frozen_int4.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp]
 _lib.zo_profile_begin.argtypes = [_vp]
 _lib.zo_profile_end.argtypes = [_vp, C.POINTER(C.c_float), C.POINTER(_i32)]
 
@@ -110,8 +113,21 @@ def zo_workspace_bytes(cfg, B, S):
     return _lib.zo_workspace_bytes(C.byref(cfg), B, S)
 
 
+class PackedInt4:
+    """Device storage of one frozen, pre-quantized linear (see zo_pack_weight_int4 in the header):
+    codes u8 [N][K/2], step f16 [N][K/group], zp i16 [N][K/group]."""
+
+    def __init__(self, codes, step_f16, zp, N, K, group):
+        self.codes, self.step_f16, self.zp, self.N, self.K, self.group = codes, step_f16, zp, N, K, group
+
+    def numel(self):
+        return self.N * self.K
+
+
 class Context:
-    """Owns nothing on the device except references that keep the caller's tensors alive."""
+    """Owns nothing on the device except references that keep the caller's tensors alive.
+    Entries of `params` are fp32 tensors, or PackedInt4 for frozen linears of a lightweight
+    configuration (their `trainable` flag must be false)."""
 
     def __init__(self, cfg, params, max_B, max_S, trainable=None):
         self.handle = None
@@ -120,16 +136,28 @@ class Context:
         n = len(params)
         arr = (zo_tensor * n)()
         for i, p in enumerate(params):
+            tr = 1 if (trainable is None or trainable[i]) else 0
+            if isinstance(p, PackedInt4):
+                arr[i] = zo_tensor(None, p.numel(), tr, 0)
+                continue
             assert p.is_cuda and p.dtype == torch.float32 and p.is_contiguous()
-            arr[i] = zo_tensor(p.data_ptr(), p.numel(), 1 if (trainable is None or trainable[i]) else 0, 0)
+            arr[i] = zo_tensor(p.data_ptr(), p.numel(), tr, 0)
         nbytes = zo_workspace_bytes(cfg, max_B, max_S)
         if nbytes == 0:
             raise ZoError(1, "zo_workspace_bytes")
-        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=params[0].device)
-        self.out4 = torch.zeros(4, dtype=torch.float32, device=params[0].device)
+        dev = next(p for p in params if not isinstance(p, PackedInt4)).device
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        self.out4 = torch.zeros(4, dtype=torch.float32, device=dev)
         self.handle = _vp()
         _check(_lib.zo_init(C.byref(cfg), arr, n, self.workspace.data_ptr(), nbytes, max_B, max_S, _stream(),
                             C.byref(self.handle)), "zo_init")
+        for i, p in enumerate(params):
+            if isinstance(p, PackedInt4):
+                self.zo_attach_frozen_int4(i, p)
+
+    def zo_attach_frozen_int4(self, index, p):
+        _check(_lib.zo_attach_frozen_int4(self.handle, index, p.codes.data_ptr(), p.step_f16.data_ptr(), p.zp.data_ptr(), p.group),
+               "zo_attach_frozen_int4", self.handle)
 
     def close(self):
         if self.handle:
@@ -226,6 +254,33 @@ def zo_linear_fakequant(X, W, bias, w_bits, w_group, a_bits, a_sym=0, seed=0, te
                                     a_bits, a_sym, dtype, seed, tensor_id, eps_signed, scratch.data_ptr(), _stream()),
            "zo_linear_fakequant")
     return Y
+
+
+def zo_pack_weight_int4(W, group):
+    N, K = W.shape
+    dev = W.device
+    codes = torch.empty((N, K // 2), dtype=torch.uint8, device=dev)
+    step = torch.empty((N, K // group), dtype=torch.float16, device=dev)
+    zp = torch.empty((N, K // group), dtype=torch.int16, device=dev)
+    _check(_lib.zo_pack_weight_int4(W.data_ptr(), N, K, group, codes.data_ptr(), step.data_ptr(), zp.data_ptr(), _stream()),
+           "zo_pack_weight_int4")
+    return PackedInt4(codes, step, zp, N, K, group)
+
+
+def zo_linear_frozen_int4(X, packed, bias, a_bits, a_sym=0):
+    """Returns (Y, w^) -- w^ is the de-quantized operand left in the scratch buffer."""
+    M, K = X.shape
+    N = packed.N
+    dtype = ACT_BF16 if X.dtype == torch.bfloat16 else ACT_FP32
+    scratch = torch.empty(_lib.zo_linear_scratch_bytes(M, N, K, dtype), dtype=torch.uint8, device=X.device)
+    Y = torch.empty((M, N), dtype=X.dtype, device=X.device)
+    _check(_lib.zo_linear_frozen_int4(X.data_ptr(), packed.codes.data_ptr(), packed.step_f16.data_ptr(), packed.zp.data_ptr(),
+                                      _ptr(bias), Y.data_ptr(), M, N, K, packed.group, a_bits, a_sym, dtype,
+                                      scratch.data_ptr(), _stream()), "zo_linear_frozen_int4")
+    es = X.element_size()
+    off = (M * K * es + 255) // 256 * 256
+    what = scratch[off:off + N * K * es].view(X.dtype).view(N, K)
+    return Y, what
 
 
 def zo_gemm_nt(X, W, Y=None):

@@ -138,6 +138,9 @@ struct zo_ctx {
     zo_config cfg;
     std::vector<zo_tensor> params;
     std::vector<param_desc> desc;
+    // frozen, pre-quantized storage of a non-trainable linear (lightweight variant); codes == NULL: none
+    struct frozen_int4 { const void* codes; const void* step; const int16_t* zp; int group; };
+    std::vector<frozen_int4> frozen;
     char* ws;
     size_t ws_bytes;
     int max_B, max_S;
@@ -205,8 +208,10 @@ struct fwd {
     int dt() const { return c->cfg.act_dtype; }
     float eps_of(int tensor) const { return trainable(c, tensor) ? eps : 0.0f; }
 
-    // Q(W +- eps u) of tensor `t` ([rows][cols]) into rows [row0, row0+rows) of the what buffers
-    zo_status weights(int t, int64_t row0, bool quantize)
+    bool frozen(int t) const { return c->frozen[t].codes != nullptr; }
+    // Q(W +- eps u) of tensor `t` ([rows][cols]) into rows [row0, row0+rows) of the what buffers.
+    // shared: every tensor of this GEMM is frozen, so one copy of the operand serves both branches.
+    zo_status weights(int t, int64_t row0, bool quantize, bool shared = false)
     {
         const param_desc& p = c->desc[t];
         const size_t ts = zo_tsize(dt());
@@ -214,6 +219,12 @@ struct fwd {
         void* om = nb == 2 ? at(c->L.what[1]) + (size_t)row0 * p.cols * ts : nullptr;
         const int bits = quantize ? c->cfg.w_bits : 0;
         prof_scope ps(c, ZO_PROF_WEIGHT_QUANT);
+        const zo_ctx::frozen_int4& fz = c->frozen[t];
+        if (fz.codes) {                                  // stored codes: the same operand for both branches
+            ZO_HIP(c, zo_launch_dequant_int4(fz.codes, fz.step, fz.zp, (int)p.rows, (int)p.cols, fz.group, dt(), op,
+                                             shared ? nullptr : om, c->st));
+            return ZO_OK;
+        }
         ZO_HIP(c, zo_launch_fq_weight((const float*)c->params[t].ptr, (int)p.rows, (int)p.cols, bits, c->cfg.w_group,
                                       seed, t, eps_of(t), dt(), op, om, nullptr, nullptr, nullptr, c->st));
         return ZO_OK;
@@ -267,7 +278,7 @@ struct fwd {
         return ZO_OK;
     }
     zo_status gemm(size_t layout::per_branch::*in, size_t layout::per_branch::*out, int N, int K, bool bias, bool relu,
-                   bool residual, bool out_f32 = false)
+                   bool residual, bool out_f32 = false, bool w_shared = false)
     {
         zo_gemm_args a{};
         a.X = at(c->L.br[0].*in);
@@ -280,7 +291,7 @@ struct fwd {
         const int64_t ts = (int64_t)zo_tsize(dt());
         if (nb == 2) {
             a.strideX = (int64_t)(c->L.br[1].*in - c->L.br[0].*in) / ts;
-            a.strideW = (int64_t)(c->L.what[1] - c->L.what[0]) / ts;
+            a.strideW = w_shared ? 0 : (int64_t)(c->L.what[1] - c->L.what[0]) / ts;
             a.strideY = (int64_t)(c->L.br[1].*out - c->L.br[0].*out) / (out_f32 ? 4 : ts);
             a.strideBias = (int64_t)(c->L.vec[1] - c->L.vec[0]) / 4;
             a.strideRes = a.strideY;
@@ -360,11 +371,13 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
         ZO_TRY(F.vector(t++, 0));
         if (!llama) ZO_TRY(F.vector(t++, 1));
         ZO_TRY(F.norm_quant(&PB::x, !llama, &xin));
+        const int tstep = llama ? 1 : 2;                 // OPT interleaves the biases
+        bool sh = F.frozen(t) && F.frozen(t + tstep) && F.frozen(t + 2 * tstep);
         for (int i = 0; i < 3; ++i) {
-            ZO_TRY(F.weights(t++, (int64_t)i * d, true));
+            ZO_TRY(F.weights(t++, (int64_t)i * d, true, sh));
             if (!llama) ZO_TRY(F.vector(t++, 2, (int64_t)i * d));
         }
-        ZO_TRY(F.gemm(xin, &PB::qkv, 3 * d, d, !llama, false, false));
+        ZO_TRY(F.gemm(xin, &PB::qkv, 3 * d, d, !llama, false, false, false, sh));
         for (int b = 0; b < nb; ++b) {
             prof_scope ps(c, ZO_PROF_ATTENTION);
             char* qkv = F.at(c->L.br[b].qkv);
@@ -379,18 +392,20 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
                                               B, S, H, dh, 3 * d, dt, c->st));
         }
         ZO_TRY(F.act_quant(&PB::att, d, &xin));
-        ZO_TRY(F.weights(t++, 0, true));
+        sh = F.frozen(t);
+        ZO_TRY(F.weights(t++, 0, true, sh));
         if (!llama) ZO_TRY(F.vector(t++, 2));
-        ZO_TRY(F.gemm(xin, &PB::x, d, d, !llama, false, true));
+        ZO_TRY(F.gemm(xin, &PB::x, d, d, !llama, false, true, false, sh));
         // ---- feed-forward block
         ZO_TRY(F.vector(t++, 0));
         if (!llama) ZO_TRY(F.vector(t++, 1));
         ZO_TRY(F.norm_quant(&PB::x, !llama, &xin));
         bool act_done = false;
         if (llama) {
-            ZO_TRY(F.weights(t++, 0, true));
-            ZO_TRY(F.weights(t++, f, true));
-            ZO_TRY(F.gemm(xin, &PB::gu, 2 * f, d, false, false, false));
+            sh = F.frozen(t) && F.frozen(t + 1);
+            ZO_TRY(F.weights(t++, 0, true, sh));
+            ZO_TRY(F.weights(t++, f, true, sh));
+            ZO_TRY(F.gemm(xin, &PB::gu, 2 * f, d, false, false, false, false, sh));
             act_done = cfg.a_bits < 16 && zo_swiglu_quant_supported(f);
             prof_scope ps(c, act_done ? ZO_PROF_ACT_QUANT : ZO_PROF_OTHER);
             for (int b = 0; b < nb; ++b) {
@@ -402,15 +417,17 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
                     ZO_HIP(c, zo_launch_swiglu(gu, gu + (size_t)f * ts, F.at(c->L.br[b].act), M, f, 2 * f, dt, c->st));
             }
         } else {
-            ZO_TRY(F.weights(t++, 0, true));
+            sh = F.frozen(t);
+            ZO_TRY(F.weights(t++, 0, true, sh));
             ZO_TRY(F.vector(t++, 2));
-            ZO_TRY(F.gemm(xin, &PB::act, f, d, true, true, false));
+            ZO_TRY(F.gemm(xin, &PB::act, f, d, true, true, false, false, sh));
         }
         if (act_done) xin = &PB::hq;
         else ZO_TRY(F.act_quant(&PB::act, f, &xin));
-        ZO_TRY(F.weights(t++, 0, true));
+        sh = F.frozen(t);
+        ZO_TRY(F.weights(t++, 0, true, sh));
         if (!llama) ZO_TRY(F.vector(t++, 2));
-        ZO_TRY(F.gemm(xin, &PB::x, d, f, !llama, false, true));
+        ZO_TRY(F.gemm(xin, &PB::x, d, f, !llama, false, true, false, sh));
     }
     // ---- head
     ZO_TRY(F.vector(t++, 0));
@@ -440,6 +457,8 @@ zo_status check_batch(zo_ctx* c, const void* ids, const float* target, int B, in
         if (S > c->cfg.max_seq) return fail(c, ZO_ESHAPE, "S exceeds max_seq");
     }
     if (!aligned16(ids)) return fail(c, ZO_EALIGN, "ids / input not 16-byte aligned");
+    for (size_t i = 0; i < c->params.size(); ++i)
+        if (!c->params[i].ptr && !c->frozen[i].codes) return fail(c, ZO_EINVAL, "a tensor has neither fp32 nor packed storage");
     if ((int64_t)B * S > (int64_t)c->max_B * c->max_S || S > c->max_S)
         return fail(c, ZO_EWORKSPACE, "batch larger than the one the context was created for");
     return ZO_OK;
@@ -482,7 +501,10 @@ zo_status zo_init(const zo_config* cfg, const zo_tensor* params, int32_t n_param
     describe_params(*cfg, desc);
     if (n_params != (int32_t)desc.size()) return ZO_EINVAL;
     for (int i = 0; i < n_params; ++i) {
-        if (!params[i].ptr) return ZO_EINVAL;
+        // a frozen linear of the lightweight variant may come without fp32 storage: its packed form
+        // is attached afterwards (zo_attach_frozen_int4)
+        const bool may_be_packed = cfg->lightweight && !params[i].trainable && desc[i].quantized;
+        if (!params[i].ptr && !may_be_packed) return ZO_EINVAL;
         if (params[i].numel != desc[i].rows * desc[i].cols) return ZO_ESHAPE;
         if (!aligned16(params[i].ptr)) return ZO_EALIGN;
     }
@@ -494,6 +516,7 @@ zo_status zo_init(const zo_config* cfg, const zo_tensor* params, int32_t n_param
     c->cfg = *cfg;
     c->params.assign(params, params + n_params);
     c->desc = desc;
+    c->frozen.assign(n_params, zo_ctx::frozen_int4{nullptr, nullptr, nullptr, 0});
     c->ws = (char*)workspace;
     c->ws_bytes = workspace_bytes;
     c->max_B = max_B;
@@ -517,6 +540,20 @@ zo_status zo_init(const zo_config* cfg, const zo_tensor* params, int32_t n_param
         if (e != hipSuccess) { delete c; return ZO_EHIP; }
     }
     *out = c;
+    return ZO_OK;
+}
+
+zo_status zo_attach_frozen_int4(zo_ctx* ctx, int32_t index, const void* codes, const void* step_f16, const int16_t* zp,
+                                int32_t group)
+{
+    if (!ctx) return ZO_EINVAL;
+    if (index < 0 || index >= (int32_t)ctx->params.size()) return fail(ctx, ZO_EINVAL, "tensor index out of range");
+    if (!ctx->cfg.lightweight || ctx->params[index].trainable) return fail(ctx, ZO_EINVAL, "only frozen tensors of a lightweight configuration take packed storage");
+    if (!ctx->desc[index].quantized) return fail(ctx, ZO_EINVAL, "only quantized linears take packed storage");
+    if (!codes || !step_f16 || !zp) return fail(ctx, ZO_EINVAL, "NULL packed storage");
+    if (!zo_int4_group_supported((int)ctx->desc[index].cols, group)) return fail(ctx, ZO_ESHAPE, "group must be a power of two in 8..512 dividing the in-features");
+    if (!aligned16(codes) || ((uintptr_t)step_f16 & 1) || ((uintptr_t)zp & 1)) return fail(ctx, ZO_EALIGN, "packed storage misaligned");
+    ctx->frozen[index] = zo_ctx::frozen_int4{codes, step_f16, zp, group};
     return ZO_OK;
 }
 
@@ -682,6 +719,44 @@ zo_status zo_linear_fakequant(const void* X_dev, const float* W_dev, const float
     char* what = xhat + align_up((size_t)M * K * ts);
     hipError_t e = zo_launch_fq_weight(W_dev, N, K, w_bits, w_group, seed, tensor_id, eps_signed, dtype, what, nullptr,
                                        nullptr, nullptr, nullptr, st);
+    if (e != hipSuccess) return ZO_EHIP;
+    const void* xin = X_dev;
+    if (a_bits < 16) {
+        e = zo_launch_fq_act(X_dev, xhat, M, K, a_bits, a_sym, dtype, nullptr, nullptr, nullptr, st);
+        if (e != hipSuccess) return ZO_EHIP;
+        xin = xhat;
+    }
+    zo_gemm_args a{};
+    a.X = xin; a.W = what; a.Y = Y_dev; a.bias = bias_dev;
+    a.M = M; a.N = N; a.K = K; a.batch = 1; a.dtype = dtype;
+    return zo_launch_gemm(a, st) == hipSuccess ? ZO_OK : ZO_EHIP;
+}
+
+zo_status zo_pack_weight_int4(const float* W_dev, int32_t N, int32_t K, int32_t group,
+                              void* codes_dev, void* step_f16_dev, int16_t* zp_dev, void* hip_stream)
+{
+    if (!W_dev || !codes_dev || !step_f16_dev || !zp_dev || N < 0 || K <= 0) return ZO_EINVAL;
+    if (!zo_int4_group_supported(K, group)) return ZO_ESHAPE;
+    if (!aligned16(W_dev) || !aligned16(codes_dev) || ((uintptr_t)step_f16_dev & 1) || ((uintptr_t)zp_dev & 1)) return ZO_EALIGN;
+    return zo_launch_pack_int4(W_dev, N, K, group, codes_dev, step_f16_dev, zp_dev, (hipStream_t)hip_stream) == hipSuccess ? ZO_OK : ZO_EHIP;
+}
+
+zo_status zo_linear_frozen_int4(const void* X_dev, const void* codes_dev, const void* step_f16_dev, const int16_t* zp_dev,
+                                const float* bias_dev, void* Y_dev, int32_t M, int32_t N, int32_t K, int32_t group,
+                                int32_t a_bits, int32_t a_sym, int32_t dtype, void* scratch_dev, void* hip_stream)
+{
+    if (!X_dev || !codes_dev || !step_f16_dev || !zp_dev || !Y_dev || !scratch_dev || M < 0 || N < 0 || K <= 0) return ZO_EINVAL;
+    if (dtype != ZO_ACT_FP32 && dtype != ZO_ACT_BF16) return ZO_EINVAL;
+    if (!(a_bits == 16 || (a_bits >= 2 && a_bits <= 8))) return ZO_EINVAL;
+    if (!zo_int4_group_supported(K, group)) return ZO_ESHAPE;
+    if (!aligned16(X_dev) || !aligned16(codes_dev) || !aligned16(Y_dev) || !aligned16(scratch_dev) || !aligned16(bias_dev) ||
+        ((uintptr_t)step_f16_dev & 1) || ((uintptr_t)zp_dev & 1))
+        return ZO_EALIGN;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const size_t ts = zo_tsize(dtype);
+    char* xhat = (char*)scratch_dev;
+    char* what = xhat + align_up((size_t)M * K * ts);
+    hipError_t e = zo_launch_dequant_int4(codes_dev, step_f16_dev, zp_dev, N, K, group, dtype, what, nullptr, st);
     if (e != hipSuccess) return ZO_EHIP;
     const void* xin = X_dev;
     if (a_bits < 16) {

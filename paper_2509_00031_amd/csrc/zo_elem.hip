@@ -336,6 +336,104 @@ hipError_t zo_launch_fq_weight(const float* W, int32_t N, int32_t K, int32_t bit
 }
 
 // ---------------------------------------------------------------------------------------------
+// Frozen weights of the lightweight variant (Section "Lightweight ZeroQAT for memory reduction"):
+// stored as 4-bit codes two per byte (low nibble = even k), one binary16 step and one int16 zero
+// point per group.  zo_pack_int4_kernel pre-quantizes an fp32 matrix into that form (same
+// arithmetic as the fake-quantizer at eps = 0); zo_dequant_int4_kernel expands it into the GEMM
+// operand type: w^ = (code - zp) * step.  One thread owns 8 consecutive k = 4 packed bytes.
+// ---------------------------------------------------------------------------------------------
+template <int GL>
+__global__ __launch_bounds__(256) void zo_pack_int4_kernel(const float* __restrict__ W, int64_t nblk, uint32_t* __restrict__ packed,
+                                                           _Float16* __restrict__ step, int16_t* __restrict__ zp)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const bool active = b < nblk;
+    float v[8];
+    if (active) zo_load8(W + 8 * b, v);
+    else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = 0.0f;
+    }
+    float mn = v[0], mx = v[0];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) { mn = fminf(mn, v[i]); mx = fmaxf(mx, v[i]); }
+    mn = zo_group_min<GL>(mn);
+    mx = zo_group_max<GL>(mx);
+    const zo_qparams q = zo_qparams_asym(mn, mx, 4);
+    uint32_t word = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) word |= ((uint32_t)zo_code(q, v[i]) & 15u) << (4 * i);
+    if (!active) return;
+    packed[b] = word;
+    if ((lane & (GL - 1)) == 0) {
+        step[b / GL] = (_Float16)q.step;                                  // round to nearest even, subnormals kept
+        zp[b / GL] = (int16_t)fminf(fmaxf(q.zp, -32768.0f), 32767.0f);
+    }
+}
+
+template <typename TO>
+__global__ __launch_bounds__(256) void zo_dequant_int4_kernel(const uint32_t* __restrict__ packed, const _Float16* __restrict__ step,
+                                                              const int16_t* __restrict__ zp, int64_t nblk, int gl,
+                                                              TO* __restrict__ out0, TO* __restrict__ out1)
+{
+    const int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (b >= nblk) return;
+    const uint32_t word = packed[b];
+    const int64_t g = b / gl;
+    const float st = (float)step[g];
+    const int z = zp[g];
+    float o[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = (float)((int)((word >> (4 * i)) & 15u) - z) * st;
+    zo_store8(out0 + 8 * b, o);
+    if (out1) zo_store8(out1 + 8 * b, o);
+}
+
+bool zo_int4_group_supported(int32_t K, int32_t group)
+{
+    if (group < 8 || group > 512 || (group & (group - 1)) != 0) return false;
+    return K > 0 && K % group == 0;
+}
+
+hipError_t zo_launch_pack_int4(const float* W, int32_t N, int32_t K, int32_t group, void* packed, void* step_f16, int16_t* zp,
+                               hipStream_t st)
+{
+    const int64_t nblk = (int64_t)N * K / 8;
+    if (nblk == 0) return hipSuccess;
+    if (!zo_int4_group_supported(K, group) || (nblk + 255) / 256 > 0x7FFFFFFF) return hipErrorInvalidValue;
+    const int grid = (int)((nblk + 255) / 256);
+    uint32_t* pk = (uint32_t*)packed;
+    _Float16* sp = (_Float16*)step_f16;
+    switch (group / 8) {
+        case 1:  zo_pack_int4_kernel<1><<<grid, 256, 0, st>>>(W, nblk, pk, sp, zp); break;
+        case 2:  zo_pack_int4_kernel<2><<<grid, 256, 0, st>>>(W, nblk, pk, sp, zp); break;
+        case 4:  zo_pack_int4_kernel<4><<<grid, 256, 0, st>>>(W, nblk, pk, sp, zp); break;
+        case 8:  zo_pack_int4_kernel<8><<<grid, 256, 0, st>>>(W, nblk, pk, sp, zp); break;
+        case 16: zo_pack_int4_kernel<16><<<grid, 256, 0, st>>>(W, nblk, pk, sp, zp); break;
+        case 32: zo_pack_int4_kernel<32><<<grid, 256, 0, st>>>(W, nblk, pk, sp, zp); break;
+        default: zo_pack_int4_kernel<64><<<grid, 256, 0, st>>>(W, nblk, pk, sp, zp); break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t zo_launch_dequant_int4(const void* packed, const void* step_f16, const int16_t* zp, int32_t N, int32_t K, int32_t group,
+                                  int dtype, void* out0, void* out1, hipStream_t st)
+{
+    const int64_t nblk = (int64_t)N * K / 8;
+    if (nblk == 0) return hipSuccess;
+    if (!zo_int4_group_supported(K, group) || (nblk + 255) / 256 > 0x7FFFFFFF) return hipErrorInvalidValue;
+    const int grid = (int)((nblk + 255) / 256);
+    if (dtype == ZO_T_BF16)
+        zo_dequant_int4_kernel<zo_bf16><<<grid, 256, 0, st>>>((const uint32_t*)packed, (const _Float16*)step_f16, zp, nblk, group / 8,
+                                                              (zo_bf16*)out0, (zo_bf16*)out1);
+    else
+        zo_dequant_int4_kernel<float><<<grid, 256, 0, st>>>((const uint32_t*)packed, (const _Float16*)step_f16, zp, nblk, group / 8,
+                                                            (float*)out0, (float*)out1);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
 // per-token activation fake-quantizer: one wavefront per row; range sweep, then code sweep
 // (the second sweep re-reads the row from cache).
 // ---------------------------------------------------------------------------------------------

@@ -25,6 +25,15 @@ hipError_t zo_launch_fq_weight(const float* W, int32_t N, int32_t K, int32_t bit
                                void* out_plus, void* out_minus,
                                uint8_t* codes, float* step, int32_t* zp, hipStream_t st);
 
+// ---- frozen weights (lightweight variant): packed 4-bit codes, binary16 steps, int16 zero points ----
+// group: a power of two in 8 .. 512 that divides K
+bool zo_int4_group_supported(int32_t K, int32_t group);
+hipError_t zo_launch_pack_int4(const float* W, int32_t N, int32_t K, int32_t group, void* packed, void* step_f16, int16_t* zp,
+                               hipStream_t st);
+// w^ = (code - zp) * step into out0 (and out1 if not NULL), storage type dtype
+hipError_t zo_launch_dequant_int4(const void* packed, const void* step_f16, const int16_t* zp, int32_t N, int32_t K, int32_t group,
+                                  int dtype, void* out0, void* out1, hipStream_t st);
+
 // ---- per-token activation fake-quantizer -------------------------------------------------------
 hipError_t zo_launch_fq_act(const void* X, void* Xhat, int32_t M, int32_t K, int32_t bits, int32_t sym, int dtype,
                             int16_t* codes, float* step, int32_t* zp, hipStream_t st);
