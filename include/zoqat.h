@@ -203,6 +203,13 @@ zo_status zo_linear_frozen_int4(const void* X_dev, const void* codes_dev, const 
 zo_status zo_gemm_nt(const void* X_dev, const void* W_dev, void* Y_dev, int32_t M, int32_t N, int32_t K,
                      int32_t dtype, void* hip_stream);
 
+/* The same GEMM with the epilogue the decoder layers fuse into it:
+ *   Y = relu?(X * W^T + bias) + residual,   bias dev fp32 [N] or NULL, residual dev [M][N] in
+ * storage type dtype or NULL (may be Y itself: the residual stream is updated in place), relu != 0
+ * applies max(., 0) before the residual is added.  One rounding to the storage type at the end. */
+zo_status zo_gemm_nt_fused(const void* X_dev, const void* W_dev, const float* bias_dev, const void* residual_dev, int32_t relu,
+                           void* Y_dev, int32_t M, int32_t N, int32_t K, int32_t dtype, void* hip_stream);
+
 /* Causal softmax attention of the decoder forward: for every batch b, head h and position s,
  * out[b,s,h,:] = sum_{j<=s} softmax_j(q[b,s,h,:].k[b,j,h,:] / sqrt(dh)) v[b,j,h,:].
  * q, k, v: dev, storage type dtype, element (b,s,h,i) at ((b*S + s) * row_stride + h*dh + i)

@@ -23,7 +23,7 @@ EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "
            "zo_forward_quant", "zo_step", "zo_update", "zo_debug_philox_u32", "zo_debug_normal", "zo_update_tensor",
            "zo_debug_quant_weight", "zo_debug_quant_act", "zo_linear_scratch_bytes", "zo_linear_fakequant",
            "zo_gemm_nt", "zo_debug_buffer", "zo_profile_begin", "zo_profile_end", "zo_attention_causal",
-           "zo_attention_scratch_bytes", "zo_pack_weight_int4", "zo_attach_frozen_int4", "zo_linear_frozen_int4"]
+           "zo_attention_scratch_bytes", "zo_pack_weight_int4", "zo_attach_frozen_int4", "zo_linear_frozen_int4", "zo_gemm_nt_fused"]
 PROF_NAMES = ["gemm", "weight_quant", "act_quant", "attention", "update", "other"]
 
 
@@ -73,6 +73,7 @@ _lib.zo_attention_scratch_bytes.restype = _sz
 _lib.zo_pack_weight_int4.argtypes = [_vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp]
 _lib.zo_attach_frozen_int4.argtypes = [_vp, _i32, _vp, _vp, _vp, _i32]
 _lib.zo_linear_frozen_int4.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp]
+_lib.zo_gemm_nt_fused.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _i32, _i32, _i32, _i32, _vp]
 _lib.zo_profile_begin.argtypes = [_vp]
 _lib.zo_profile_end.argtypes = [_vp, C.POINTER(C.c_float), C.POINTER(_i32)]
 
@@ -290,6 +291,17 @@ def zo_gemm_nt(X, W, Y=None):
     if Y is None:
         Y = torch.empty((M, N), dtype=X.dtype, device=X.device)
     _check(_lib.zo_gemm_nt(X.data_ptr(), W.data_ptr(), Y.data_ptr(), M, N, K, dtype, _stream()), "zo_gemm_nt")
+    return Y
+
+
+def zo_gemm_nt_fused(X, W, bias=None, residual=None, relu=False, Y=None):
+    M, K = X.shape
+    N = W.shape[0]
+    dtype = ACT_BF16 if X.dtype == torch.bfloat16 else ACT_FP32
+    if Y is None:
+        Y = torch.empty((M, N), dtype=X.dtype, device=X.device)
+    _check(_lib.zo_gemm_nt_fused(X.data_ptr(), W.data_ptr(), _ptr(bias), _ptr(residual), int(relu), Y.data_ptr(), M, N, K, dtype,
+                                 _stream()), "zo_gemm_nt_fused")
     return Y
 
 

@@ -809,4 +809,17 @@ zo_status zo_gemm_nt(const void* X_dev, const void* W_dev, void* Y_dev, int32_t 
     return zo_launch_gemm(a, (hipStream_t)hip_stream) == hipSuccess ? ZO_OK : ZO_EHIP;
 }
 
+zo_status zo_gemm_nt_fused(const void* X_dev, const void* W_dev, const float* bias_dev, const void* residual_dev, int32_t relu,
+                           void* Y_dev, int32_t M, int32_t N, int32_t K, int32_t dtype, void* hip_stream)
+{
+    if (!X_dev || !W_dev || !Y_dev || M < 0 || N < 0 || K <= 0) return ZO_EINVAL;
+    if (dtype != ZO_ACT_FP32 && dtype != ZO_ACT_BF16) return ZO_EINVAL;
+    if (K & 7) return ZO_ESHAPE;
+    if (!aligned16(X_dev) || !aligned16(W_dev) || !aligned16(Y_dev) || !aligned16(bias_dev) || !aligned16(residual_dev)) return ZO_EALIGN;
+    zo_gemm_args a{};
+    a.X = X_dev; a.W = W_dev; a.Y = Y_dev; a.bias = bias_dev; a.residual = residual_dev; a.relu = relu ? 1 : 0;
+    a.M = M; a.N = N; a.K = K; a.batch = 1; a.dtype = dtype;
+    return zo_launch_gemm(a, (hipStream_t)hip_stream) == hipSuccess ? ZO_OK : ZO_EHIP;
+}
+
 }  // extern "C"

@@ -5,6 +5,7 @@
 #include "zo_device.h"
 #include "zo_internal.h"
 #include <cstdlib>
+#include <type_traits>
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -405,6 +406,82 @@ __global__ __launch_bounds__(NW * 64) void zo_gemm_bf16_dma_kernel(zo_gemm_args 
     TY* Y = (TY*)a.Y + bz * a.strideY;
     const float* bias = a.bias ? a.bias + bz * a.strideBias : nullptr;
     const zo_bf16* res = a.residual ? (const zo_bf16*)a.residual + bz * a.strideRes : nullptr;
+    if constexpr (sizeof(TY) == 2) {
+        if ((N & 7) == 0) {
+            // bf16 output: each wave transposes its WM x WN tile through its own slice of the (now idle)
+            // LDS, so that the global stores are whole 16-byte row segments, 128 contiguous bytes per
+            // 8 lanes, instead of 8-byte pieces of 32 different rows.  A lane holds 4 consecutive n
+            // (one 8-byte granule) of row m; granule g of row m is stored at granule slot
+            // g ^ (m & 15): 16 lanes with consecutive m hit 16 different bank pairs.
+            __syncthreads();                          // every wave's copies have landed, nobody reads the stages any more
+            constexpr int ROWB = WN * 2;              // bytes per tile row
+            unsigned char* slice = lds + wave * (WM * ROWB);
+            auto stage = [&](auto fused_tag) {
+                constexpr bool FUSED = decltype(fused_tag)::value;      // bias / ReLU / residual present
+#pragma unroll
+                for (int j = 0; j < TM; ++j) {
+                    const int ml = j * 32 + (lane & 31);
+                    const int m = m0 + wm * WM + ml;
+                    uint2 r2[TN][4];
+                    if constexpr (FUSED) {
+                        // all residual pieces of this row block are requested before the first is used
+#pragma unroll
+                        for (int i = 0; i < TN; ++i)
+#pragma unroll
+                            for (int rg = 0; rg < 4; ++rg) {
+                                const int n = n0 + wn * WN + (i * 8 + rg * 2 + (lane >> 5)) * 4;
+                                r2[i][rg] = make_uint2(0, 0);
+                                if (res && m < M && n < N) r2[i][rg] = *reinterpret_cast<const uint2*>(res + (int64_t)m * N + n);
+                            }
+                    }
+#pragma unroll
+                    for (int i = 0; i < TN; ++i)
+#pragma unroll
+                        for (int rg = 0; rg < 4; ++rg) {
+                            const int g = i * 8 + rg * 2 + (lane >> 5);
+                            float v[4];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) v[e] = acc[i][j][rg * 4 + e];
+                            if constexpr (FUSED) {
+                                const int n = n0 + wn * WN + g * 4;
+                                if (bias && n < N) {
+                                    float4 b4 = *reinterpret_cast<const float4*>(bias + n);
+                                    v[0] += b4.x; v[1] += b4.y; v[2] += b4.z; v[3] += b4.w;
+                                }
+                                if (a.relu) {
+#pragma unroll
+                                    for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.0f);
+                                }
+                                if (res) {
+                                    v[0] += zo_bf16_lo(r2[i][rg].x); v[1] += zo_bf16_hi(r2[i][rg].x);
+                                    v[2] += zo_bf16_lo(r2[i][rg].y); v[3] += zo_bf16_hi(r2[i][rg].y);
+                                }
+                            }
+                            uint2 o;
+                            o.x = zo_pack_bf16x2(v[0], v[1]);
+                            o.y = zo_pack_bf16x2(v[2], v[3]);
+                            *reinterpret_cast<uint2*>(slice + ml * ROWB + ((g ^ (ml & 15)) << 3)) = o;
+                        }
+                }
+            };
+            if (bias || res || a.relu) stage(std::true_type{}); else stage(std::false_type{});
+            constexpr int LPR = ROWB / 16;            // lanes per row in the read-back
+            constexpr int RPI = 64 / LPR;             // rows per wave-level store
+#pragma unroll 4
+            for (int it = 0; it < WM / RPI; ++it) {
+                const int row = it * RPI + lane / LPR, c = lane % LPR, f = row & 15;
+                uint4 v = *reinterpret_cast<const uint4*>(slice + row * ROWB + ((c ^ (f >> 1)) << 4));
+                if (f & 1) v = make_uint4(v.z, v.w, v.x, v.y);
+                const int m = m0 + wm * WM + row, n = n0 + wn * WN + c * 8;
+                if (m < M && n < N) {
+                    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+                    u32x4 vv = {v.x, v.y, v.z, v.w};
+                    __builtin_nontemporal_store(vv, reinterpret_cast<u32x4*>((zo_bf16*)Y + (int64_t)m * N + n));
+                }
+            }
+            return;
+        }
+    }
 #pragma unroll
     for (int j = 0; j < TM; ++j)
 #pragma unroll

@@ -39,6 +39,36 @@ def test_gemm_large_tile_path():
     assert np.all(np.abs(Y - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-4)
 
 
+@pytest.mark.parametrize("M,N,K", [(3000, 2904, 256), (2051, 4096, 512), (200, 136, 64), (4096, 2048, 128)])
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("bias,relu,residual", [(True, False, False), (False, False, True), (True, True, True)])
+def test_gemm_fused_epilogue(M, N, K, dtype, bias, relu, residual):
+    """Bias / ReLU / in-place residual epilogue, on shapes that take the small-tile, the 256 x 256
+    and (bf16, N a multiple of 8) the row-coalesced store paths, ragged in M and N."""
+    torch, zo = gpu()
+    bf = dtype == "bf16"
+    td = torch.bfloat16 if bf else torch.float32
+    X = synth.activations((M, K), 55)
+    W = synth.weights((N, K), 56, scale=1.0)
+    R = synth.activations((M, N), 57)
+    b = synth.weights((N,), 58, scale=1.0)
+    if bf:
+        X, W, R = orc.bf16_round(X), orc.bf16_round(W), orc.bf16_round(R)
+    Y = to_dev(R, torch, td) if residual else None           # residual stream updated in place
+    out = zo.zo_gemm_nt_fused(to_dev(X, torch, td), to_dev(W, torch, td), to_dev(b, torch) if bias else None,
+                              Y, relu, Y).float().cpu().numpy()
+    acc = X.astype(np.float64) @ W.astype(np.float64).T
+    mag = np.abs(acc)
+    if bias:
+        acc = acc + b.astype(np.float64)
+    if relu:
+        acc = np.maximum(acc, 0.0)
+    if residual:
+        acc = acc + R.astype(np.float64)
+    tol = (2.0 ** -8 if bf else 2.0 ** -20) * (np.abs(acc) + mag) + 1e-5 * np.sqrt(K)
+    assert np.all(np.abs(out - acc) <= tol)
+
+
 @pytest.mark.parametrize("dtype,tol", [("fp32", 1e-4), ("bf16", 1e-2)])
 @pytest.mark.parametrize("M,N,K,wb,g,ab", [(8, 256, 256, 4, 64, 8), (100, 72, 512, 2, 64, 16), (33, 130, 384, 4, 128, 4)])
 def test_linear_fakequant(dtype, tol, M, N, K, wb, g, ab):
