@@ -33,6 +33,10 @@ WORKLOADS = {
     "tiny_w4a16_g64_8x128": dict(arch="llama", n_layers=4, d_model=512, n_heads=8, d_ffn=2048, vocab=4096,
                                  w_bits=4, w_group=64, a_bits=16, B=8, S=128),
 }
+# HBM-side bytes per launch of the GEMM kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes over this same
+# command (scaled by a plain copy of known size; profiles/zo_step_llama7b_w4a8_hbm_traffic.txt): 2.000 x 1359.0 MB
+# read + 1.000 x 348.3 MB written.  Counters cannot be read from inside the run, so other workloads report null.
+MEASURED_GEMM_TRAFFIC = {"llama7b_w4a8_g64_8x1024": 2.0 * 1359.0e6 + 348.3e6}
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
@@ -178,7 +182,7 @@ def main():
         flops_per_launch = gflops * args.steps / max(gemm_launches, 1)
         achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12
         res["roofline"] = {"bound": "mfma", "kernel": "zo_gemm_bf16_dma_kernel<bf16, 8 waves, BK 64, 2 stages>", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
-                           "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                           "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": MEASURED_GEMM_TRAFFIC.get(args.workload),
                            "launches": gemm_launches, "avg_launch_ms": avg_ms,
                            "flops_per_launch": flops_per_launch}
         res["gemm_tflops"] = achieved
