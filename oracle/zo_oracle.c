@@ -10,6 +10,8 @@
  *   - group-wise weights, per-token activations          (Appendix "Quantization settings")
  *   - the two-point zeroth-order estimate, q = 1         (Eq. 2)
  *   - the ZO-SGD update on full-precision master weights (Eq. 3)
+ *   - the adaptive weight quantizer with learnable step, zero point and
+ *     clipping coefficients (Eq. 5) and the channel-wise smoothing (Eq. 4)
  *   - frozen, pre-quantized weights of the lightweight variant
  *                                 (Section "Lightweight ZeroQAT for memory reduction")
  * The paper only says u ~ N(0, I); the concrete counter-based stream used here
@@ -259,6 +261,114 @@ void zo_or_fakequant_weight(const float* W, int N, int K, int bits, int group,
         free(wp);
         free(hat);
     }
+}
+
+/* ------------------------------------------------------------------ */
+/* Adaptive weight quantizer (Eq. 5): learnable step, zero point and    */
+/* clipping coefficients per group,                                     */
+/*   code = clamp(round(w/step) + z, alpha*Q_P, beta*Q_P),              */
+/*   w^   = (code - z) * step.                                          */
+/* Readings: the four are real-valued fp32 tensors that the ZO step     */
+/* perturbs and updates; inside the forward z and the two bounds are    */
+/* rounded to integers (half to even) so that codes stay integers, the  */
+/* bounds are kept inside [0, Q_P] and ordered, the step is floored at  */
+/* 1e-5 and w/step is w * (1/step) as in the dynamic quantizer.         */
+/* ------------------------------------------------------------------ */
+void zo_or_quant_group_learned(const float* x, int n, int bits, float step, float zp,
+                               float alpha, float beta, int32_t* codes, float* xhat)
+{
+    float qp = (float)((1 << bits) - 1);
+    float st = step;
+    if (!(st >= ZO_OR_STEP_MIN)) st = ZO_OR_STEP_MIN;
+    float inv = 1.0f / st;
+    float zr = rintf(zp);
+    float lo = rintf(alpha * qp);
+    float hi = rintf(beta * qp);
+    if (lo < 0.0f) lo = 0.0f;
+    if (lo > qp) lo = qp;
+    if (hi > qp) hi = qp;
+    if (hi < lo) hi = lo;
+    for (int i = 0; i < n; ++i) {
+        float q = rintf(x[i] * inv) + zr;
+        if (q < lo) q = lo;
+        if (q > hi) q = hi;
+        if (codes) codes[i] = (int32_t)q;
+        if (xhat)  xhat[i]  = (q - zr) * st;
+    }
+}
+
+/* Weight side of a linear with learnable quantizer parameters, optionally
+ * smoothed (Eq. 4: the weight operand is s (.) W, s per input feature):
+ *   w'   = fma(eps_signed, u, w)                 (perturbed master)
+ *   wbar = scale[k] * w'                         (scale == NULL: no smoothing)
+ *   w^   = Eq. 5 on wbar with the group's (step, zp, alpha, beta)
+ * scale and the four parameter arrays ([N][K/group]) are passed in already
+ * perturbed.  Any output may be NULL. */
+void zo_or_fakequant_weight_learned(const float* W, int N, int K, int bits, int group,
+                                    uint64_t seed, int32_t tensor_id, float eps_signed,
+                                    const float* scale, const float* step, const float* zp,
+                                    const float* alpha, const float* beta, int round_bf16,
+                                    int32_t* codes, float* what)
+{
+    int G = K / group;
+    #pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        float* wb  = (float*)malloc(sizeof(float) * (size_t)K);
+        float* hat = (float*)malloc(sizeof(float) * (size_t)K);
+        for (int k = 0; k < K; ++k) {
+            int64_t i = (int64_t)n * K + k;
+            float z = (eps_signed == 0.0f) ? 0.0f : zo_or_z(seed, tensor_id, i);
+            float wp = fmaf(eps_signed, z, W[i]);
+            wb[k] = scale ? scale[k] * wp : wp;
+        }
+        for (int g = 0; g < G; ++g) {
+            int64_t gi = (int64_t)n * G + g;
+            zo_or_quant_group_learned(wb + g * group, group, bits, step[gi], zp[gi], alpha[gi], beta[gi],
+                                      codes ? codes + (int64_t)n * K + g * group : NULL, hat + g * group);
+        }
+        if (what)
+            for (int k = 0; k < K; ++k)
+                what[(int64_t)n * K + k] = round_bf16 ? zo_or_bf16_round(hat[k]) : hat[k];
+        free(wb);
+        free(hat);
+    }
+}
+
+/* Initial values (Eq. 5: "initialized based on the default asymmetric
+ * quantization scheme"): step and zero point of the dynamic quantizer on
+ * scale (.) W, alpha = 0, beta = 1. */
+void zo_or_init_learned(const float* W, int N, int K, int bits, int group, const float* scale,
+                        float* step, float* zp, float* alpha, float* beta)
+{
+    int G = K / group;
+    #pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        float* wb = (float*)malloc(sizeof(float) * (size_t)K);
+        for (int k = 0; k < K; ++k) wb[k] = scale ? scale[k] * W[(int64_t)n * K + k] : W[(int64_t)n * K + k];
+        for (int g = 0; g < G; ++g) {
+            int64_t gi = (int64_t)n * G + g;
+            float st;
+            int32_t z;
+            zo_or_quant_group(wb + g * group, group, bits, 0, &st, &z, NULL, NULL);
+            step[gi] = st;
+            zp[gi] = (float)z;
+            alpha[gi] = 0.0f;
+            beta[gi] = 1.0f;
+        }
+        free(wb);
+    }
+}
+
+/* Activation side of Eq. 4: xbar = (x - delta[k]) * (1 / s[k]), fp32, one
+ * correctly rounded division per channel (inv_s is passed in). */
+void zo_or_smooth_act(const float* X, int M, int K, const float* delta, const float* inv_s, float* out)
+{
+    #pragma omp parallel for schedule(static)
+    for (int m = 0; m < M; ++m)
+        for (int k = 0; k < K; ++k) {
+            int64_t i = (int64_t)m * K + k;
+            out[i] = (X[i] - delta[k]) * inv_s[k];
+        }
 }
 
 /* ------------------------------------------------------------------ */

@@ -70,6 +70,12 @@ _lib.zo_or_f32_to_f16_bits.argtypes = [C.c_float]
 _lib.zo_or_f32_to_f16_bits.restype = C.c_uint16
 _lib.zo_or_f16_bits_to_f32.argtypes = [C.c_uint16]
 _lib.zo_or_f16_bits_to_f32.restype = C.c_float
+_lib.zo_or_quant_group_learned.argtypes = [_f32p, C.c_int, C.c_int, C.c_float, C.c_float, C.c_float, C.c_float,
+                                           C.c_void_p, C.c_void_p]
+_lib.zo_or_fakequant_weight_learned.argtypes = [_f32p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_uint64, C.c_int32, C.c_float,
+                                                C.c_void_p, _f32p, _f32p, _f32p, _f32p, C.c_int, C.c_void_p, C.c_void_p]
+_lib.zo_or_init_learned.argtypes = [_f32p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, _f32p, _f32p, _f32p, _f32p]
+_lib.zo_or_smooth_act.argtypes = [_f32p, C.c_int, C.c_int, _f32p, _f32p, _f32p]
 _lib.zo_or_pack_int4.argtypes = [_f32p, C.c_int, C.c_int, C.c_int, _u8p, _u16p, _i16p]
 _lib.zo_or_dequant_int4.argtypes = [_u8p, _u16p, _i16p, C.c_int, C.c_int, C.c_int, C.c_int, _f32p]
 _lib.zo_or_projected_grad.argtypes = [C.c_float, C.c_float, C.c_float]
@@ -169,6 +175,49 @@ def fakequant_act(X, bits, sym=False, round_bf16=False, want_codes=True):
     return dict(codes=codes, step=step, zp=zp, xhat=xhat)
 
 
+def quant_group_learned(x, bits, step, zp, alpha, beta):
+    """One group through the adaptive weight quantizer of Eq. 5: (codes, dequantized)."""
+    x = np.ascontiguousarray(x, np.float32).reshape(-1)
+    codes = np.empty(x.size, np.int32)
+    xhat = np.empty(x.size, np.float32)
+    _lib.zo_or_quant_group_learned(x, x.size, bits, step, zp, alpha, beta, _opt(codes), _opt(xhat))
+    return codes, xhat
+
+
+def fakequant_weight_learned(W, bits, group, step, zp, alpha, beta, scale=None, seed=0, tensor_id=0, eps_signed=0.0,
+                             round_bf16=False, want_codes=True):
+    """Eq. 5 on scale (.) (W + eps_signed*u) with the given (already perturbed) per-group parameters."""
+    W = np.ascontiguousarray(W, np.float32)
+    N, K = W.shape
+    group = group or K
+    f = lambda a: np.ascontiguousarray(a, np.float32).reshape(N, K // group)
+    sc = None if scale is None else np.ascontiguousarray(scale, np.float32)
+    codes = np.empty((N, K), np.int32) if want_codes else None
+    what = np.empty((N, K), np.float32)
+    _lib.zo_or_fakequant_weight_learned(W, N, K, bits, group, seed, tensor_id, eps_signed, _opt(sc), f(step), f(zp),
+                                        f(alpha), f(beta), int(round_bf16), _opt(codes), _opt(what))
+    return dict(codes=codes, what=what)
+
+
+def init_learned(W, bits, group, scale=None):
+    """Initial (step, zp, alpha, beta) per group: the default asymmetric scheme on scale (.) W; alpha 0, beta 1."""
+    W = np.ascontiguousarray(W, np.float32)
+    N, K = W.shape
+    group = group or K
+    sc = None if scale is None else np.ascontiguousarray(scale, np.float32)
+    out = [np.empty((N, K // group), np.float32) for _ in range(4)]
+    _lib.zo_or_init_learned(W, N, K, bits, group, _opt(sc), *out)
+    return out
+
+
+def smooth_act(X, delta, inv_s):
+    X = np.ascontiguousarray(X, np.float32)
+    out = np.empty_like(X)
+    _lib.zo_or_smooth_act(X, X.shape[0], X.shape[1], np.ascontiguousarray(delta, np.float32),
+                          np.ascontiguousarray(inv_s, np.float32), out)
+    return out
+
+
 def f32_to_f16_bits(v):
     return int(_lib.zo_or_f32_to_f16_bits(float(np.float32(v))))
 
@@ -241,15 +290,65 @@ class Config:
     """Mirror of the library's configuration record (field meaning identical)."""
 
     def __init__(self, arch, n_layers=0, d_model=0, n_heads=1, d_ffn=0, vocab=0, max_seq=0,
-                 w_bits=4, w_group=64, a_bits=16, a_sym=0, act_dtype=0, lightweight=0):
+                 w_bits=4, w_group=64, a_bits=16, a_sym=0, act_dtype=0, lightweight=0, learn_clip=0, learn_smooth=0):
         self.arch, self.n_layers, self.d_model, self.n_heads = arch, n_layers, d_model, n_heads
         self.d_ffn, self.vocab, self.max_seq = d_ffn, vocab, max_seq
         self.w_bits, self.w_group, self.a_bits, self.a_sym = w_bits, w_group, a_bits, a_sym
         self.act_dtype, self.lightweight = act_dtype, lightweight
+        # learnable quantizer parameters (Eq. 5) / channel-wise smoothing (Eq. 4) as ZO-trained tensors
+        self.learn_clip, self.learn_smooth = learn_clip, learn_smooth
+
+
+GROUP_MODEL, GROUP_SMOOTH, GROUP_CLIP = 0, 1, 2      # learning-rate groups (Appendix, hyperparameter table)
 
 
 def param_shapes(cfg):
-    """Ordered (name, shape, quantized?) of the trainable tensors; index = tensor id."""
+    """Ordered (name, shape, quantized?) of the trainable tensors; index = tensor id.
+
+    The model's own tensors come first; then, for every quantized linear in that order, the
+    tensors of its adaptive quantizer (Eq. 5: step, zero point, alpha, beta, one value per group)
+    when cfg.learn_clip, and of its smoothing (Eq. 4: s and delta, one value per input feature)
+    when cfg.learn_smooth."""
+    base = _base_param_shapes(cfg)
+    out = list(base)
+    for name, (N, K), q in [b for b in base if b[2]]:
+        G = K // (cfg.w_group or K)
+        if getattr(cfg, "learn_clip", 0):
+            out += [(name + sfx, (N, G), False) for sfx in (".q_step", ".q_zp", ".q_alpha", ".q_beta")]
+        if getattr(cfg, "learn_smooth", 0):
+            out += [(name + ".sm_s", (K,), False), (name + ".sm_delta", (K,), False)]
+    return out
+
+
+def param_groups(cfg):
+    """Learning-rate group of every tensor, in param_shapes order."""
+    g = []
+    for name, _, _ in param_shapes(cfg):
+        last = name.split(".")[-1]
+        g.append(GROUP_CLIP if last.startswith("q_") else GROUP_SMOOTH if last.startswith("sm_") else GROUP_MODEL)
+    return g
+
+
+def init_learned_params(cfg, params):
+    """Fill the quantizer / smoothing tensors of `params` (a list in param_shapes order) in place:
+    s = 1, delta = 0 (identity smoothing), then Eq. 5's parameters from the default scheme."""
+    index = {name: i for i, (name, _, _) in enumerate(param_shapes(cfg))}
+    for name, shape, q in _base_param_shapes(cfg):
+        if not q:
+            continue
+        scale = None
+        if cfg.learn_smooth:
+            params[index[name + ".sm_s"]][...] = 1.0
+            params[index[name + ".sm_delta"]][...] = 0.0
+            scale = params[index[name + ".sm_s"]]
+        if cfg.learn_clip:
+            vals = init_learned(params[index[name]], cfg.w_bits, cfg.w_group, scale)
+            for sfx, v in zip((".q_step", ".q_zp", ".q_alpha", ".q_beta"), vals):
+                params[index[name + sfx]][...] = v
+    return params
+
+
+def _base_param_shapes(cfg):
     d, f, V = cfg.d_model, cfg.d_ffn, cfg.vocab
     if cfg.arch == ARCH_LINEAR:
         return [("w", (f, d), True)]
@@ -312,8 +411,30 @@ class _Params:
         if isinstance(self.params[i], PackedInt4):     # frozen and pre-quantized: used as stored
             assert self.trainable is not None and not self.trainable[i]
             return dequant_int4(self.params[i], round_bf16=(cfg.act_dtype == 1))
+        scale = self.plain(name + ".sm_s") if cfg.learn_smooth else None
+        if cfg.learn_clip:
+            qp = [self.plain(name + sfx) for sfx in (".q_step", ".q_zp", ".q_alpha", ".q_beta")]
+            return fakequant_weight_learned(self.params[i], cfg.w_bits, cfg.w_group, *qp, scale=scale, seed=self.seed,
+                                            tensor_id=i, eps_signed=self._eps_for(i),
+                                            round_bf16=(cfg.act_dtype == 1), want_codes=False)["what"]
+        if scale is not None:
+            # smoothing with the dynamic quantizer: min/max of every group of s (.) (W + eps u)
+            wb = (perturb(self.params[i], self.seed, i, self._eps_for(i)) * scale[None, :]).astype(np.float32)
+            return fakequant_weight(wb, cfg.w_bits, cfg.w_group, round_bf16=(cfg.act_dtype == 1), want_codes=False)["what"]
         return fakequant_weight(self.params[i], cfg.w_bits, cfg.w_group, self.seed, i, self._eps_for(i),
                                 round_bf16=(cfg.act_dtype == 1), want_codes=False)["what"]
+
+    def smooth(self, name):
+        """Activation side and bias term of Eq. 4 for linear `name`: (delta', 1/s', delta' W'^T) or None."""
+        if not self.cfg.learn_smooth:
+            return None
+        i = self.index[name]
+        s = self.plain(name + ".sm_s")
+        delta = self.plain(name + ".sm_delta")
+        inv_s = (np.float32(1.0) / s).astype(np.float32)
+        wp = perturb(self.params[i], self.seed, i, self._eps_for(i))
+        shift = wp.astype(np.float64) @ delta.astype(np.float64)
+        return delta, inv_s, shift
 
 
 def _tie_margin(x, step):
@@ -323,8 +444,13 @@ def _tie_margin(x, step):
     return np.abs(np.abs(t - np.floor(t)) - np.float32(0.5)).min(axis=1)
 
 
-def _qlinear(cfg, x, what, bias=None, residual=None, relu=False, tie_log=None):
-    """Quantized linear: per-token Q_A on the stored input, then x^ w^T (+bias)(+relu)(+residual)."""
+def _qlinear(cfg, x, what, bias=None, residual=None, relu=False, tie_log=None, smooth=None):
+    """Quantized linear: per-token Q_A on the stored input, then x^ w^T (+bias)(+relu)(+residual).
+    With smoothing (Eq. 4) the quantizer sees (x - delta) / s and the bias gains delta W^T."""
+    if smooth is not None:
+        delta, inv_s, shift = smooth
+        x = smooth_act(x, delta, inv_s)
+        bias = shift if bias is None else bias.astype(np.float64) + shift
     qa = fakequant_act(x, cfg.a_bits, cfg.a_sym, round_bf16=(cfg.act_dtype == 1), want_codes=False)
     xq = qa["xhat"]
     if tie_log is not None and cfg.a_bits < 16:
@@ -409,7 +535,7 @@ def forward(cfg, params, ids=None, x=None, target=None, seed=0, eps_signed=0.0, 
         return val
 
     if cfg.arch == ARCH_LINEAR:
-        y = _qlinear(cfg, _rt(cfg, x), P.qweight("w"), tie_log=tie_log)
+        y = _qlinear(cfg, _rt(cfg, x), P.qweight("w"), tie_log=tie_log, smooth=P.smooth("w"))
         keep("y", y)
         return np.float32(np.mean((y.astype(np.float64) - np.asarray(target, np.float64)) ** 2))
 
@@ -428,31 +554,31 @@ def forward(cfg, params, ids=None, x=None, target=None, seed=0, eps_signed=0.0, 
         p = "l%d." % l
         if cfg.arch == ARCH_LLAMA:
             h = _rt(cfg, _rmsnorm(xres, P.plain(p + "attn_norm")))
-            q = _qlinear(cfg, h, P.qweight(p + "wq"), tie_log=tie_log)
-            k = _qlinear(cfg, h, P.qweight(p + "wk"), tie_log=tie_log)
-            v = _qlinear(cfg, h, P.qweight(p + "wv"), tie_log=tie_log)
+            q = _qlinear(cfg, h, P.qweight(p + "wq"), tie_log=tie_log, smooth=P.smooth(p + "wq"))
+            k = _qlinear(cfg, h, P.qweight(p + "wk"), tie_log=tie_log, smooth=P.smooth(p + "wk"))
+            v = _qlinear(cfg, h, P.qweight(p + "wv"), tie_log=tie_log, smooth=P.smooth(p + "wv"))
             q = _rt(cfg, _rope(q, B, S, H, dh))
             k = _rt(cfg, _rope(k, B, S, H, dh))
             a = _rt(cfg, _attention(q, k, v, B, S, H, dh))
-            xres = _qlinear(cfg, a, P.qweight(p + "wo"), residual=xres, tie_log=tie_log)
+            xres = _qlinear(cfg, a, P.qweight(p + "wo"), residual=xres, tie_log=tie_log, smooth=P.smooth(p + "wo"))
             keep(p + "attn_out", xres)
             h = _rt(cfg, _rmsnorm(xres, P.plain(p + "ffn_norm")))
-            gate = _qlinear(cfg, h, P.qweight(p + "w_gate"), tie_log=tie_log)
-            up = _qlinear(cfg, h, P.qweight(p + "w_up"), tie_log=tie_log)
+            gate = _qlinear(cfg, h, P.qweight(p + "w_gate"), tie_log=tie_log, smooth=P.smooth(p + "w_gate"))
+            up = _qlinear(cfg, h, P.qweight(p + "w_up"), tie_log=tie_log, smooth=P.smooth(p + "w_up"))
             g64 = gate.astype(np.float64)
             act = _rt(cfg, g64 / (1.0 + np.exp(-g64)) * up.astype(np.float64))
-            xres = _qlinear(cfg, act, P.qweight(p + "w_down"), residual=xres, tie_log=tie_log)
+            xres = _qlinear(cfg, act, P.qweight(p + "w_down"), residual=xres, tie_log=tie_log, smooth=P.smooth(p + "w_down"))
         else:
             h = _rt(cfg, _layernorm(xres, P.plain(p + "ln1_g"), P.plain(p + "ln1_b")))
-            q = _qlinear(cfg, h, P.qweight(p + "wq"), P.plain(p + "bq"), tie_log=tie_log)
-            k = _qlinear(cfg, h, P.qweight(p + "wk"), P.plain(p + "bk"), tie_log=tie_log)
-            v = _qlinear(cfg, h, P.qweight(p + "wv"), P.plain(p + "bv"), tie_log=tie_log)
+            q = _qlinear(cfg, h, P.qweight(p + "wq"), P.plain(p + "bq"), tie_log=tie_log, smooth=P.smooth(p + "wq"))
+            k = _qlinear(cfg, h, P.qweight(p + "wk"), P.plain(p + "bk"), tie_log=tie_log, smooth=P.smooth(p + "wk"))
+            v = _qlinear(cfg, h, P.qweight(p + "wv"), P.plain(p + "bv"), tie_log=tie_log, smooth=P.smooth(p + "wv"))
             a = _rt(cfg, _attention(q, k, v, B, S, H, dh))
-            xres = _qlinear(cfg, a, P.qweight(p + "wo"), P.plain(p + "bo"), residual=xres, tie_log=tie_log)
+            xres = _qlinear(cfg, a, P.qweight(p + "wo"), P.plain(p + "bo"), residual=xres, tie_log=tie_log, smooth=P.smooth(p + "wo"))
             keep(p + "attn_out", xres)
             h = _rt(cfg, _layernorm(xres, P.plain(p + "ln2_g"), P.plain(p + "ln2_b")))
-            f = _qlinear(cfg, h, P.qweight(p + "fc1"), P.plain(p + "b1"), relu=True, tie_log=tie_log)
-            xres = _qlinear(cfg, f, P.qweight(p + "fc2"), P.plain(p + "b2"), residual=xres, tie_log=tie_log)
+            f = _qlinear(cfg, h, P.qweight(p + "fc1"), P.plain(p + "b1"), relu=True, tie_log=tie_log, smooth=P.smooth(p + "fc1"))
+            xres = _qlinear(cfg, f, P.qweight(p + "fc2"), P.plain(p + "b2"), residual=xres, tie_log=tie_log, smooth=P.smooth(p + "fc2"))
         keep(p + "out", xres)
     if cfg.arch == ARCH_LLAMA:
         hf = _rt(cfg, _rmsnorm(xres, P.plain("final_norm")))
@@ -464,7 +590,7 @@ def forward(cfg, params, ids=None, x=None, target=None, seed=0, eps_signed=0.0, 
     return cross_entropy(logits, ids, B, S)
 
 
-def zo_step(cfg, params, seed, eps, lr, ids=None, x=None, target=None, trainable=None):
+def zo_step(cfg, params, seed, eps, lr, ids=None, x=None, target=None, trainable=None, lr_smooth=None, lr_clip=None):
     """One ZO-SGD step (Eq. 2 with q = 1, then Eq. 3), updating `params` in place.
 
     Entries of `params` that are PackedInt4 are frozen (their `trainable` flag must be False).
@@ -473,8 +599,13 @@ def zo_step(cfg, params, seed, eps, lr, ids=None, x=None, target=None, trainable
     lp = forward(cfg, params, ids, x, target, seed, eps, trainable)
     lm = forward(cfg, params, ids, x, target, seed, -eps, trainable)
     g = projected_grad(lp, lm, eps)
-    c = coeff(np.float32(lr), g)
+    # one coefficient per learning-rate group (model, smoothing, clipping); the same g and u for all
+    lrs = [lr, lr if lr_smooth is None else lr_smooth, lr if lr_clip is None else lr_clip]
+    cs = [coeff(np.float32(v), g) for v in lrs]
+    groups = param_groups(cfg)
     for i, w in enumerate(params):
+        if isinstance(w, PackedInt4):
+            continue
         if trainable is None or trainable[i]:
-            update(w, seed, i, c)
+            update(w, seed, i, cs[groups[i]])
     return lp, lm, g
