@@ -307,17 +307,25 @@ def param_shapes(cfg):
 
     The model's own tensors come first; then, for every quantized linear in that order, the
     tensors of its adaptive quantizer (Eq. 5: step, zero point, alpha, beta, one value per group)
-    when cfg.learn_clip, and of its smoothing (Eq. 4: s and delta, one value per input feature)
-    when cfg.learn_smooth."""
+    when cfg.learn_clip, and of the smoothing of its input (Eq. 4: s and delta, one value per input
+    feature) when cfg.learn_smooth.  Linears that read the same activation (q/k/v; gate/up) share
+    one smoothing pair, listed with the first of them: one activation has one quantized form."""
     base = _base_param_shapes(cfg)
     out = list(base)
     for name, (N, K), q in [b for b in base if b[2]]:
         G = K // (cfg.w_group or K)
         if getattr(cfg, "learn_clip", 0):
             out += [(name + sfx, (N, G), False) for sfx in (".q_step", ".q_zp", ".q_alpha", ".q_beta")]
-        if getattr(cfg, "learn_smooth", 0):
+        if getattr(cfg, "learn_smooth", 0) and smooth_owner(name) == name:
             out += [(name + ".sm_s", (K,), False), (name + ".sm_delta", (K,), False)]
     return out
+
+
+def smooth_owner(name):
+    """Name of the linear that carries the smoothing pair of `name`'s input activation."""
+    head, _, last = name.rpartition(".")
+    owner = {"wk": "wq", "wv": "wq", "w_up": "w_gate"}.get(last, last)
+    return (head + "." if head else "") + owner
 
 
 def param_groups(cfg):
@@ -338,9 +346,10 @@ def init_learned_params(cfg, params):
             continue
         scale = None
         if cfg.learn_smooth:
-            params[index[name + ".sm_s"]][...] = 1.0
-            params[index[name + ".sm_delta"]][...] = 0.0
-            scale = params[index[name + ".sm_s"]]
+            own = smooth_owner(name)
+            params[index[own + ".sm_s"]][...] = 1.0
+            params[index[own + ".sm_delta"]][...] = 0.0
+            scale = params[index[own + ".sm_s"]]
         if cfg.learn_clip:
             vals = init_learned(params[index[name]], cfg.w_bits, cfg.w_group, scale)
             for sfx, v in zip((".q_step", ".q_zp", ".q_alpha", ".q_beta"), vals):
@@ -411,7 +420,7 @@ class _Params:
         if isinstance(self.params[i], PackedInt4):     # frozen and pre-quantized: used as stored
             assert self.trainable is not None and not self.trainable[i]
             return dequant_int4(self.params[i], round_bf16=(cfg.act_dtype == 1))
-        scale = self.plain(name + ".sm_s") if cfg.learn_smooth else None
+        scale = self.plain(smooth_owner(name) + ".sm_s") if cfg.learn_smooth else None
         if cfg.learn_clip:
             qp = [self.plain(name + sfx) for sfx in (".q_step", ".q_zp", ".q_alpha", ".q_beta")]
             return fakequant_weight_learned(self.params[i], cfg.w_bits, cfg.w_group, *qp, scale=scale, seed=self.seed,
@@ -429,8 +438,8 @@ class _Params:
         if not self.cfg.learn_smooth:
             return None
         i = self.index[name]
-        s = self.plain(name + ".sm_s")
-        delta = self.plain(name + ".sm_delta")
+        s = self.plain(smooth_owner(name) + ".sm_s")
+        delta = self.plain(smooth_owner(name) + ".sm_delta")
         inv_s = (np.float32(1.0) / s).astype(np.float32)
         wp = perturb(self.params[i], self.seed, i, self._eps_for(i))
         shift = wp.astype(np.float64) @ delta.astype(np.float64)
