@@ -60,7 +60,13 @@ typedef struct {
     int32_t act_dtype;   /* ZO_ACT_*: storage type of activations and GEMM operands */
     int32_t lightweight; /* 0 = every tensor trainable; 1 = only tensors whose zo_tensor.trainable
                             is set are perturbed and updated (lightweight variant) */
-    int32_t reserved[3];
+    int32_t learn_clip;  /* 1 = adaptive weight quantizer (Eq. 5): every quantized linear gets four more
+                            trainable fp32 tensors [N][K/w_group] -- step, zero point, alpha, beta -- used
+                            instead of the per-forward min/max */
+    int32_t learn_smooth;/* 1 = channel-wise smoothing (Eq. 4): every distinct input activation of the
+                            quantized linears gets two more trainable fp32 tensors [K] -- s and delta;
+                            needs learn_clip = 1 and a_bits < 16 */
+    int32_t reserved[1];
 } zo_config;
 
 /* One parameter tensor.  The array given to zo_init lists them in the fixed order below; the
@@ -70,7 +76,12 @@ typedef struct {
  *            w_gate[f][d], w_up[f][d], w_down[d][f]; then final_norm[d], lm_head[V][d]
  *   opt:     tok_emb[V][d], pos_emb[max_seq][d]; per layer: ln1_g, ln1_b, wq, bq, wk, bk, wv, bv,
  *            wo, bo, ln2_g, ln2_b, fc1[f][d], b1[f], fc2[d][f], b2[d]; then final_ln_g,
- *            final_ln_b, lm_head[V][d]                                                       */
+ *            final_ln_b, lm_head[V][d]
+ *   With learn_clip / learn_smooth the list continues, for every quantized linear in the order above:
+ *   (learn_clip) step, zero point, alpha, beta, each [N][K/w_group] (per channel: [N][1]);
+ *   (learn_smooth, only for the first linear of those that read the same activation: wq for wq/wk/wv,
+ *   w_gate for w_gate/w_up, every other linear for itself) s[K], delta[K].
+ *   Learning-rate groups: the model's tensors 0, smoothing tensors 1, quantizer tensors 2.         */
 typedef struct {
     void*   ptr;        /* dev, fp32 master weights, updated in place by zo_update / zo_step; may be
                            NULL for a frozen quantized linear of a lightweight configuration whose
@@ -148,6 +159,41 @@ zo_status zo_debug_quant_weight(const float* W_dev, int32_t N, int32_t K, int32_
                                 uint64_t seed, int32_t tensor_id, float eps_signed, int32_t out_dtype,
                                 uint8_t* codes_dev, float* step_dev, int32_t* zp_dev, void* what_dev,
                                 void* hip_stream);
+
+/* ---- adaptive weight quantizer (Eq. 5) and channel-wise smoothing (Eq. 4) as ZO-trained tensors ----
+ * Eq. 5: code = clamp(round(w/step) + z, alpha Q_P, beta Q_P), w^ = (code - z) step, with step, z, alpha,
+ * beta learnable per group.  The four are real-valued fp32 tensors that the step perturbs and updates;
+ * inside a forward z and the two bounds are rounded half-to-even, the bounds kept inside [0, Q_P] and
+ * ordered, the step floored at 1e-5.  Eq. 4: Y = [(X - delta) / s] [s (.) W] + [B + delta W]: the per-token
+ * quantizer sees (x - delta) * (1/s) (one division per channel), the weight quantizer s (.) (W +- eps u),
+ * and the bias gains delta (W +- eps u)^T. */
+
+/* Fill the tensors of Eq. 5 / Eq. 4 of a context (caller's memory, on the context's stream): s = 1,
+ * delta = 0; step and zero point as the default asymmetric scheme computes them from W, alpha = 0, beta = 1
+ * ("initialized based on the default asymmetric quantization scheme").  Uses the workspace as scratch. */
+zo_status zo_init_learned_params(zo_ctx* ctx);
+
+/* zo_step with one learning rate per group (Appendix, hyperparameter table: model, smoothing, clipping).
+ * out_dev fp32[6] = { L+, L-, g, lr_model g, lr_smooth g, lr_clip g }. */
+zo_status zo_step_groups(zo_ctx* ctx, const void* ids_dev, const float* target_dev, int32_t B, int32_t S,
+                         uint64_t seed, float eps, float lr_model, float lr_smooth, float lr_clip, float* out_dev);
+
+/* zo_update with one coefficient per group: coeff_dev fp32[3] on the device, or (if NULL) coeff_host[3]. */
+zo_status zo_update_groups(zo_ctx* ctx, uint64_t seed, const float* coeff_dev, const float* coeff_host);
+
+/* Eq. 5 on scale (.) (W + eps_signed u) for one matrix W[N][K]; step/zp/alpha/beta dev fp32 [N][K/group]
+ * (already perturbed), scale dev fp32 [K] or NULL.  Outputs: codes u8 [N][K] (may be NULL), what [N][K]
+ * in storage type out_dtype. */
+zo_status zo_debug_quant_weight_learned(const float* W_dev, int32_t N, int32_t K, int32_t bits, int32_t group,
+                                        uint64_t seed, int32_t tensor_id, float eps_signed,
+                                        const float* scale_dev, const float* step_dev, const float* zp_dev,
+                                        const float* alpha_dev, const float* beta_dev, int32_t out_dtype,
+                                        uint8_t* codes_dev, void* what_dev, void* hip_stream);
+
+/* Bias term of Eq. 4: out[n] = bias[n] + sum_k delta[k] (W[n][k] + eps_signed u); bias may be NULL.
+ * fp32 accumulation in a fixed order. */
+zo_status zo_debug_smooth_bias(const float* W_dev, int32_t N, int32_t K, uint64_t seed, int32_t tensor_id, float eps_signed,
+                               const float* delta_dev, const float* bias_dev, float* out_dev, void* hip_stream);
 
 /* Per-token quantizer of the input of a quantized linear: every row of X[M][K] (storage type
  * dtype) is one group.  Outputs (any may be NULL): codes int16 [M][K], step fp32 [M], zp int32 [M],

@@ -23,14 +23,16 @@ EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "
            "zo_forward_quant", "zo_step", "zo_update", "zo_debug_philox_u32", "zo_debug_normal", "zo_update_tensor",
            "zo_debug_quant_weight", "zo_debug_quant_act", "zo_linear_scratch_bytes", "zo_linear_fakequant",
            "zo_gemm_nt", "zo_debug_buffer", "zo_profile_begin", "zo_profile_end", "zo_attention_causal",
-           "zo_attention_scratch_bytes", "zo_pack_weight_int4", "zo_attach_frozen_int4", "zo_linear_frozen_int4", "zo_gemm_nt_fused"]
+           "zo_attention_scratch_bytes", "zo_pack_weight_int4", "zo_attach_frozen_int4", "zo_linear_frozen_int4", "zo_gemm_nt_fused", "zo_init_learned_params", "zo_step_groups", "zo_update_groups",
+           "zo_debug_quant_weight_learned", "zo_debug_smooth_bias"]
 PROF_NAMES = ["gemm", "weight_quant", "act_quant", "attention", "update", "other"]
 
 
 class zo_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("arch", "n_layers", "d_model", "n_heads", "d_ffn", "vocab", "max_seq",
-                                         "w_bits", "w_group", "a_bits", "a_sym", "act_dtype", "lightweight")] + \
-               [("reserved", C.c_int32 * 3)]
+                                         "w_bits", "w_group", "a_bits", "a_sym", "act_dtype", "lightweight",
+                                         "learn_clip", "learn_smooth")] + \
+               [("reserved", C.c_int32 * 1)]
 
 
 class zo_tensor(C.Structure):
@@ -74,6 +76,11 @@ _lib.zo_pack_weight_int4.argtypes = [_vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp]
 _lib.zo_attach_frozen_int4.argtypes = [_vp, _i32, _vp, _vp, _vp, _i32]
 _lib.zo_linear_frozen_int4.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp]
 _lib.zo_gemm_nt_fused.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _i32, _i32, _i32, _i32, _vp]
+_lib.zo_init_learned_params.argtypes = [_vp]
+_lib.zo_step_groups.argtypes = [_vp, _vp, _vp, _i32, _i32, _u64, _f32, _f32, _f32, _f32, _vp]
+_lib.zo_update_groups.argtypes = [_vp, _u64, _vp, C.POINTER(C.c_float)]
+_lib.zo_debug_quant_weight_learned.argtypes = [_vp, _i32, _i32, _i32, _i32, _u64, _i32, _f32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]
+_lib.zo_debug_smooth_bias.argtypes = [_vp, _i32, _i32, _u64, _i32, _f32, _vp, _vp, _vp, _vp]
 _lib.zo_profile_begin.argtypes = [_vp]
 _lib.zo_profile_end.argtypes = [_vp, C.POINTER(C.c_float), C.POINTER(_i32)]
 
@@ -97,9 +104,9 @@ def _tdtype(dtype):
 
 
 def make_config(arch, n_layers=0, d_model=0, n_heads=1, d_ffn=0, vocab=0, max_seq=0, w_bits=4, w_group=64,
-                a_bits=16, a_sym=0, act_dtype=ACT_FP32, lightweight=0):
+                a_bits=16, a_sym=0, act_dtype=ACT_FP32, lightweight=0, learn_clip=0, learn_smooth=0):
     return zo_config(arch, n_layers, d_model, n_heads, d_ffn, vocab, max_seq, w_bits, w_group, a_bits, a_sym,
-                     act_dtype, lightweight)
+                     act_dtype, lightweight, learn_clip, learn_smooth)
 
 
 def zo_num_params(cfg):
@@ -179,6 +186,19 @@ class Context:
         _check(_lib.zo_step(self.handle, _ptr(ids), _ptr(target), B, S, seed, eps, lr, out.data_ptr()), "zo_step", self.handle)
         return out
 
+    def zo_init_learned_params(self):
+        _check(_lib.zo_init_learned_params(self.handle), "zo_init_learned_params", self.handle)
+
+    def zo_step_groups(self, ids, target, B, S, seed, eps, lr_model, lr_smooth, lr_clip, out_dev=None):
+        out = out_dev if out_dev is not None else torch.zeros(6, dtype=torch.float32, device=ids.device)
+        _check(_lib.zo_step_groups(self.handle, _ptr(ids), _ptr(target), B, S, seed, eps, lr_model, lr_smooth, lr_clip,
+                                   out.data_ptr()), "zo_step_groups", self.handle)
+        return out
+
+    def zo_update_groups(self, seed, coeff_dev=None, coeff_host=None):
+        host = None if coeff_host is None else (C.c_float * 3)(*coeff_host)
+        _check(_lib.zo_update_groups(self.handle, seed, _ptr(coeff_dev), host), "zo_update_groups", self.handle)
+
     def zo_update(self, seed, coeff_dev=None, coeff_host=0.0):
         _check(_lib.zo_update(self.handle, seed, _ptr(coeff_dev), coeff_host), "zo_update", self.handle)
 
@@ -229,6 +249,25 @@ def zo_debug_quant_weight(W, bits, group, seed=0, tensor_id=0, eps_signed=0.0, o
     _check(_lib.zo_debug_quant_weight(W.data_ptr(), N, K, bits, group, seed, tensor_id, eps_signed, out_dtype,
                                       _ptr(codes), _ptr(step), _ptr(zp), what.data_ptr(), _stream()), "zo_debug_quant_weight")
     return dict(codes=codes, step=step, zp=zp, what=what)
+
+
+def zo_debug_quant_weight_learned(W, bits, group, step, zp, alpha, beta, scale=None, seed=0, tensor_id=0, eps_signed=0.0,
+                                  out_dtype=ACT_FP32, want_codes=True):
+    N, K = W.shape
+    codes = torch.empty((N, K), dtype=torch.uint8, device=W.device) if want_codes else None
+    what = torch.empty((N, K), dtype=_tdtype(out_dtype), device=W.device)
+    _check(_lib.zo_debug_quant_weight_learned(W.data_ptr(), N, K, bits, group, seed, tensor_id, eps_signed, _ptr(scale),
+                                              step.data_ptr(), zp.data_ptr(), alpha.data_ptr(), beta.data_ptr(), out_dtype,
+                                              _ptr(codes), what.data_ptr(), _stream()), "zo_debug_quant_weight_learned")
+    return dict(codes=codes, what=what)
+
+
+def zo_debug_smooth_bias(W, delta, bias=None, seed=0, tensor_id=0, eps_signed=0.0):
+    N, K = W.shape
+    out = torch.empty(N, dtype=torch.float32, device=W.device)
+    _check(_lib.zo_debug_smooth_bias(W.data_ptr(), N, K, seed, tensor_id, eps_signed, delta.data_ptr(), _ptr(bias),
+                                     out.data_ptr(), _stream()), "zo_debug_smooth_bias")
+    return out
 
 
 def zo_debug_quant_act(X, bits, sym=0, want_codes=True):

@@ -14,16 +14,59 @@ namespace {
 inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
-struct param_desc { int64_t rows, cols; bool quantized; };
+enum { ZO_GROUP_MODEL = 0, ZO_GROUP_SMOOTH = 1, ZO_GROUP_CLIP = 2 };   // learning-rate groups
 
-// Parameter list of a configuration in the fixed order of the header.
+struct param_desc {
+    int64_t rows, cols;
+    bool quantized;
+    int lr_group = ZO_GROUP_MODEL;
+    int owner = -1;      // quantized linear: the linear that carries the smoothing pair of its input (q for q/k/v, gate for gate/up)
+    int clip = -1;       // quantized linear: index of its step tensor (zero point, alpha, beta follow), or -1
+    int smooth = -1;     // quantized linear: index of the s tensor of its input (delta follows), or -1
+};
+
+bool describe_base_params(const zo_config& c, std::vector<param_desc>& out);
+
+// Parameter list of a configuration in the fixed order of the header: the model's tensors, then for
+// every quantized linear in that order the tensors of Eq. 5 (learn_clip) and Eq. 4 (learn_smooth).
 bool describe_params(const zo_config& c, std::vector<param_desc>& out)
+{
+    if (!describe_base_params(c, out)) return false;
+    const int nbase = (int)out.size();
+    for (int t = 0; t < nbase; ++t) {
+        if (!out[t].quantized) continue;
+        const int64_t g = c.w_group > 0 ? c.w_group : out[t].cols;
+        if (c.learn_clip) {
+            out[t].clip = (int)out.size();
+            for (int j = 0; j < 4; ++j) {
+                param_desc d{out[t].rows, out[t].cols / g, false};
+                d.lr_group = ZO_GROUP_CLIP;
+                out.push_back(d);
+            }
+        }
+        if (c.learn_smooth && out[t].owner == t) {
+            out[t].smooth = (int)out.size();
+            for (int j = 0; j < 2; ++j) {
+                param_desc d{1, out[t].cols, false};
+                d.lr_group = ZO_GROUP_SMOOTH;
+                out.push_back(d);
+            }
+        }
+    }
+    if (c.learn_smooth)
+        for (int t = 0; t < nbase; ++t)
+            if (out[t].quantized) out[t].smooth = out[out[t].owner].smooth;
+    return true;
+}
+
+bool describe_base_params(const zo_config& c, std::vector<param_desc>& out)
 {
     out.clear();
     const int64_t d = c.d_model, f = c.d_ffn, V = c.vocab;
     if (c.arch == ZO_ARCH_LINEAR) {
         if (d <= 0 || f <= 0) return false;
         out.push_back({f, d, true});
+        out[0].owner = 0;
         return true;
     }
     if (c.arch != ZO_ARCH_LLAMA && c.arch != ZO_ARCH_OPT) return false;
@@ -31,19 +74,27 @@ bool describe_params(const zo_config& c, std::vector<param_desc>& out)
     out.push_back({V, d, false});
     if (c.arch == ZO_ARCH_OPT) out.push_back({c.max_seq, d, false});
     for (int l = 0; l < c.n_layers; ++l) {
+        // owner: q for q/k/v, gate for gate/up (they read the same activation), otherwise the linear itself
+        auto linear = [&](int64_t rows, int64_t cols, int owner_back) {
+            out.push_back({rows, cols, true});
+            out.back().owner = (int)out.size() - 1 - owner_back;
+        };
         if (c.arch == ZO_ARCH_LLAMA) {
             out.push_back({1, d, false});
-            for (int i = 0; i < 4; ++i) out.push_back({d, d, true});
+            linear(d, d, 0); linear(d, d, 1); linear(d, d, 2); linear(d, d, 0);
             out.push_back({1, d, false});
-            out.push_back({f, d, true});
-            out.push_back({f, d, true});
-            out.push_back({d, f, true});
+            linear(f, d, 0);
+            linear(f, d, 1);
+            linear(d, f, 0);
         } else {
             out.push_back({1, d, false}); out.push_back({1, d, false});
-            for (int i = 0; i < 4; ++i) { out.push_back({d, d, true}); out.push_back({1, d, false}); }
+            linear(d, d, 0); out.push_back({1, d, false});
+            linear(d, d, 2); out.push_back({1, d, false});
+            linear(d, d, 4); out.push_back({1, d, false});
+            linear(d, d, 0); out.push_back({1, d, false});
             out.push_back({1, d, false}); out.push_back({1, d, false});
-            out.push_back({f, d, true}); out.push_back({1, f, false});
-            out.push_back({d, f, true}); out.push_back({1, d, false});
+            linear(f, d, 0); out.push_back({1, f, false});
+            linear(d, f, 0); out.push_back({1, d, false});
         }
     }
     out.push_back({1, d, false});
@@ -62,6 +113,10 @@ zo_status check_config(const zo_config& c)
     if (c.w_group < 0) return ZO_EINVAL;
     if ((c.d_model & 7) || (c.d_ffn & 7)) return ZO_ESHAPE;
     if (c.w_bits > 0 && c.w_group > 0 && ((c.w_group & 7) || c.d_model % c.w_group || c.d_ffn % c.w_group)) return ZO_ESHAPE;
+    if (c.learn_clip < 0 || c.learn_clip > 1 || c.learn_smooth < 0 || c.learn_smooth > 1) return ZO_EINVAL;
+    if ((c.learn_clip || c.learn_smooth) && c.w_bits == 0) return ZO_EINVAL;
+    if (c.learn_smooth && (!c.learn_clip || c.a_bits >= 16)) return ZO_EUNSUPPORTED;
+    if ((c.learn_clip || c.learn_smooth) && c.lightweight) return ZO_EUNSUPPORTED;
     if (c.arch != ZO_ARCH_LINEAR) {
         if (c.d_model % c.n_heads) return ZO_ESHAPE;
         const int dh = c.d_model / c.n_heads;
@@ -72,11 +127,14 @@ zo_status check_config(const zo_config& c)
 
 // Workspace layout for B x S tokens.  Offsets in bytes, everything 256-byte aligned.
 struct layout {
-    size_t scalars;            // fp32[8]: loss[2], out4[4]
+    size_t scalars;            // fp32[16]: loss[2] at 0, {L+, L-, g, c_model, c_smooth, c_clip} at 2
     size_t rope_cos, rope_sin; // fp32 [max_seq][dh/2]
     size_t what[2];            // de-quantized weights of the current linear(s), per branch
-    size_t vec[2];             // perturbed small vectors of the current sub-layer, per branch
+    size_t vec[2];             // perturbed small vectors of the current sub-layer, per branch: slots 0 gain,
+                               // 1 norm bias, 2 linear bias, 3 smoothing s, 4 1/s, 5 smoothing delta
     size_t vec_stride;         // floats per vector slot
+    size_t qp[2][4];           // perturbed step / zero point / alpha / beta of the current linear(s), per branch
+    size_t qp_elems;
     struct per_branch {
         size_t x, h, hq, qkv, att, vt, gu, act, logits, rowloss;
     } br[2];
@@ -90,10 +148,16 @@ layout make_layout(const zo_config& c, int B, int S)
     const size_t d = c.d_model, f = c.d_ffn, V = c.vocab > 0 ? c.vocab : 0;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
-    L.scalars = take(8 * sizeof(float));
+    L.scalars = take(16 * sizeof(float));
+    const size_t gsz = c.w_group > 0 ? (size_t)c.w_group : 0;
     if (c.arch == ZO_ARCH_LINEAR) {
         const size_t M = B;
         for (int b = 0; b < 2; ++b) L.what[b] = take(f * d * ts);
+        L.vec_stride = align_up((d > f ? d : f) * sizeof(float)) / sizeof(float);
+        for (int b = 0; b < 2; ++b) L.vec[b] = take(6 * L.vec_stride * sizeof(float));
+        L.qp_elems = c.learn_clip ? f * (gsz ? d / gsz : 1) : 0;
+        for (int b = 0; b < 2; ++b)
+            for (int j = 0; j < 4; ++j) L.qp[b][j] = take(L.qp_elems * sizeof(float));
         for (int b = 0; b < 2; ++b) {
             L.br[b].hq = take(M * d * ts);
             L.br[b].logits = take(M * f * ts);      // output Y
@@ -113,8 +177,17 @@ layout make_layout(const zo_config& c, int B, int S)
     for (int b = 0; b < 2; ++b) L.what[b] = take(max_nk * ts);
     L.vec_stride = d > f ? d : f;
     if (3 * d > L.vec_stride) L.vec_stride = 3 * d;
+    if (ffn_rows > L.vec_stride) L.vec_stride = ffn_rows;
     L.vec_stride = align_up(L.vec_stride * sizeof(float)) / sizeof(float);
-    for (int b = 0; b < 2; ++b) L.vec[b] = take(3 * L.vec_stride * sizeof(float));
+    for (int b = 0; b < 2; ++b) L.vec[b] = take(6 * L.vec_stride * sizeof(float));
+    if (c.learn_clip) {
+        const size_t gd = gsz ? d / gsz : 1, gf = gsz ? f / gsz : 1;     // groups per row for K = d, K = f
+        L.qp_elems = 3 * d * gd;
+        if (ffn_rows * gd > L.qp_elems) L.qp_elems = ffn_rows * gd;
+        if (d * gf > L.qp_elems) L.qp_elems = d * gf;
+    }
+    for (int b = 0; b < 2; ++b)
+        for (int j = 0; j < 4; ++j) L.qp[b][j] = take(L.qp_elems * sizeof(float));
     for (int b = 0; b < 2; ++b) {
         auto& r = L.br[b];
         r.x = take(M * d * ts);
@@ -195,6 +268,8 @@ struct prof_scope {
         if (e_ != hipSuccess) return fail((ctx), ZO_EHIP, #call, e_);      \
     } while (0)
 
+#define ZO_TRY_(x) do { zo_status s__ = (x); if (s__ != ZO_OK) return s__; } while (0)
+
 inline bool trainable(const zo_ctx* c, int i) { return !c->cfg.lightweight || c->params[i].trainable; }
 
 // One forward for nb branches: branch 0 at +eps (or eps_signed when nb == 1), branch 1 at -eps.
@@ -204,6 +279,7 @@ struct fwd {
     float eps;          // magnitude for paired mode, signed value for single mode
     uint64_t seed;
     int M, S;
+    bool sm_on = false;   // the activation being quantized next is smoothed (set by smooth_prepare)
     template <typename T = char> T* at(size_t off) const { return (T*)(c->ws + off); }
     int dt() const { return c->cfg.act_dtype; }
     float eps_of(int tensor) const { return trainable(c, tensor) ? eps : 0.0f; }
@@ -225,8 +301,54 @@ struct fwd {
                                              shared ? nullptr : om, c->st));
             return ZO_OK;
         }
+        if (quantize && p.clip >= 0) {
+            // Eq. 5: perturb the four parameter tensors of this linear, then quantize with them
+            const int64_t G = p.cols / (c->cfg.w_group > 0 ? c->cfg.w_group : p.cols);
+            const int64_t qoff = row0 * G, qn = p.rows * G;
+            const float* q[2][4] = {};
+            for (int j = 0; j < 4; ++j) {
+                float* qp = at<float>(c->L.qp[0][j]) + qoff;
+                float* qm = nb == 2 ? at<float>(c->L.qp[1][j]) + qoff : nullptr;
+                ZO_HIP(c, zo_launch_fq_weight((const float*)c->params[p.clip + j].ptr, 1, (int)qn, 0, 0, seed, p.clip + j,
+                                              eps_of(p.clip + j), ZO_T_F32, qp, qm, nullptr, nullptr, nullptr, c->st));
+                q[0][j] = qp;
+                q[1][j] = qm;
+            }
+            const zo_learned lp{q[0][0], q[0][1], q[0][2], q[0][3], p.smooth >= 0 ? vec(0, 3) : nullptr};
+            const zo_learned lm{q[1][0], q[1][1], q[1][2], q[1][3], (p.smooth >= 0 && nb == 2) ? vec(1, 3) : nullptr};
+            ZO_HIP(c, zo_launch_fq_weight_learned((const float*)c->params[t].ptr, (int)p.rows, (int)p.cols, bits, c->cfg.w_group, seed, t,
+                                                  eps_of(t), dt(), lp, lm, op, om, nullptr, c->st));
+            return ZO_OK;
+        }
         ZO_HIP(c, zo_launch_fq_weight((const float*)c->params[t].ptr, (int)p.rows, (int)p.cols, bits, c->cfg.w_group,
                                       seed, t, eps_of(t), dt(), op, om, nullptr, nullptr, nullptr, c->st));
+        return ZO_OK;
+    }
+    // Eq. 4, activation side of the linears whose input is smoothed by the pair carried by linear `t`:
+    // perturbed s into slot 3, its reciprocal into slot 4, perturbed delta into slot 5 (no-op without smoothing)
+    zo_status smooth_prepare(int t)
+    {
+        const param_desc& p = c->desc[t];
+        sm_on = p.smooth >= 0;
+        if (!sm_on) return ZO_OK;
+        ZO_TRY_(vector(p.smooth, 3));
+        ZO_TRY_(vector(p.smooth + 1, 5));
+        prof_scope ps(c, ZO_PROF_WEIGHT_QUANT);
+        for (int b = 0; b < nb; ++b) ZO_HIP(c, zo_launch_reciprocal(vec(b, 3), vec(b, 4), p.cols, c->st));
+        return ZO_OK;
+    }
+    const float* sm_delta(int b) const { return sm_on ? vec(b, 5) : nullptr; }
+    const float* sm_inv(int b) const { return sm_on ? vec(b, 4) : nullptr; }
+    // bias of the smoothed linear `t`: slot 2 [o ..) = (perturbed bias already there, if has_bias) + delta' W'^T
+    zo_status bias_shift(int t, int64_t o, bool has_bias)
+    {
+        const param_desc& p = c->desc[t];
+        if (p.smooth < 0) return ZO_OK;
+        prof_scope ps(c, ZO_PROF_WEIGHT_QUANT);
+        float* bp = vec(0, 2) + o;
+        float* bm = nb == 2 ? vec(1, 2) + o : nullptr;
+        ZO_HIP(c, zo_launch_bias_shift((const float*)c->params[t].ptr, (int)p.rows, (int)p.cols, seed, t, eps_of(t), vec(0, 5),
+                                       nb == 2 ? vec(1, 5) : nullptr, has_bias ? bp : nullptr, has_bias ? bm : nullptr, bp, bm, c->st));
         return ZO_OK;
     }
     // perturbed fp32 vector of tensor `t` into vector slot `slot` at float offset `o`
@@ -262,7 +384,7 @@ struct fwd {
         prof_scope ps(c, ZO_PROF_ACT_QUANT);
         for (int b = 0; b < nb; ++b)
             ZO_HIP(c, zo_launch_norm_quant(at(c->L.br[b].*in), vec(b, 0), has_beta ? vec(b, 1) : nullptr, at(c->L.br[b].hq),
-                                           M, d, 1e-5f, c->cfg.a_bits, c->cfg.a_sym, dt(), c->st));
+                                           M, d, 1e-5f, c->cfg.a_bits, c->cfg.a_sym, dt(), sm_delta(b), sm_inv(b), c->st));
         *used = &layout::per_branch::hq;
         return ZO_OK;
     }
@@ -273,7 +395,7 @@ struct fwd {
         prof_scope ps(c, ZO_PROF_ACT_QUANT);
         for (int b = 0; b < nb; ++b)
             ZO_HIP(c, zo_launch_fq_act(at(c->L.br[b].*in), at(c->L.br[b].hq), M, K, c->cfg.a_bits, c->cfg.a_sym, dt(),
-                                       nullptr, nullptr, nullptr, c->st));
+                                       nullptr, nullptr, nullptr, sm_delta(b), sm_inv(b), c->st));
         *used = &layout::per_branch::hq;
         return ZO_OK;
     }
@@ -319,19 +441,27 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
         const int M = B, K = cfg.d_model, N = cfg.d_ffn;
         F.M = M;
         c->last_M = M;
+        ZO_TRY(F.smooth_prepare(0));
         ZO_TRY(F.weights(0, 0, true));
-        // input X is given by the caller; quantize into hq (same X^ for both branches)
+        ZO_TRY(F.bias_shift(0, 0, false));
+        // input X is given by the caller; quantize into hq (the same X^ for both branches unless the
+        // perturbed smoothing makes them differ)
         zo_gemm_args a{};
         const void* xin = ids_or_x;
+        const bool two_x = nb == 2 && F.sm_on;
         if (cfg.a_bits < 16) {
             prof_scope ps(c, ZO_PROF_ACT_QUANT);
-            ZO_HIP(c, zo_launch_fq_act(ids_or_x, F.at(c->L.br[0].hq), M, K, cfg.a_bits, cfg.a_sym, dt, nullptr, nullptr, nullptr, c->st));
+            for (int b = 0; b < (two_x ? 2 : 1); ++b)
+                ZO_HIP(c, zo_launch_fq_act(ids_or_x, F.at(c->L.br[b].hq), M, K, cfg.a_bits, cfg.a_sym, dt, nullptr, nullptr, nullptr,
+                                           F.sm_delta(b), F.sm_inv(b), c->st));
             xin = F.at(c->L.br[0].hq);
         }
         a.X = xin; a.W = F.at(c->L.what[0]); a.Y = F.at(c->L.br[0].logits);
+        a.bias = F.sm_on ? F.vec(0, 2) : nullptr;
         a.M = M; a.N = N; a.K = K; a.batch = nb; a.dtype = dt;
         if (nb == 2) {
-            a.strideX = 0;
+            a.strideX = two_x ? (int64_t)(c->L.br[1].hq - c->L.br[0].hq) / (int64_t)ts : 0;
+            a.strideBias = (int64_t)(c->L.vec[1] - c->L.vec[0]) / 4;
             a.strideW = (int64_t)(c->L.what[1] - c->L.what[0]) / (int64_t)ts;
             a.strideY = (int64_t)(c->L.br[1].logits - c->L.br[0].logits) / (int64_t)ts;
         }
@@ -370,14 +500,21 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
         // ---- attention block
         ZO_TRY(F.vector(t++, 0));
         if (!llama) ZO_TRY(F.vector(t++, 1));
+        ZO_TRY(F.smooth_prepare(t));                     // t: wq, which carries the pair of the q/k/v input
         ZO_TRY(F.norm_quant(&PB::x, !llama, &xin));
         const int tstep = llama ? 1 : 2;                 // OPT interleaves the biases
         bool sh = F.frozen(t) && F.frozen(t + tstep) && F.frozen(t + 2 * tstep);
-        for (int i = 0; i < 3; ++i) {
-            ZO_TRY(F.weights(t++, (int64_t)i * d, true, sh));
-            if (!llama) ZO_TRY(F.vector(t++, 2, (int64_t)i * d));
-        }
-        ZO_TRY(F.gemm(xin, &PB::qkv, 3 * d, d, !llama, false, false, false, sh));
+        // one quantized linear: weights of tensor t into rows [row0, ..) of the operand buffer, its bias
+        // (OPT-shaped) into slot 2, the smoothing term of Eq. 4 added to it
+        auto linear = [&](int64_t row0, bool shared) -> zo_status {
+            const int tw = t++;
+            ZO_TRY(F.weights(tw, row0, true, shared));
+            if (!llama) ZO_TRY(F.vector(t++, 2, row0));
+            return F.bias_shift(tw, row0, !llama);
+        };
+        const bool bias = !llama || cfg.learn_smooth;
+        for (int i = 0; i < 3; ++i) ZO_TRY(linear((int64_t)i * d, sh));
+        ZO_TRY(F.gemm(xin, &PB::qkv, 3 * d, d, bias, false, false, false, sh));
         for (int b = 0; b < nb; ++b) {
             prof_scope ps(c, ZO_PROF_ATTENTION);
             char* qkv = F.at(c->L.br[b].qkv);
@@ -391,43 +528,44 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
                 ZO_HIP(c, zo_launch_attention(qkv, qkv + (size_t)d * ts, qkv + (size_t)2 * d * ts, F.at(c->L.br[b].att),
                                               B, S, H, dh, 3 * d, dt, c->st));
         }
+        ZO_TRY(F.smooth_prepare(t));                     // wo
         ZO_TRY(F.act_quant(&PB::att, d, &xin));
         sh = F.frozen(t);
-        ZO_TRY(F.weights(t++, 0, true, sh));
-        if (!llama) ZO_TRY(F.vector(t++, 2));
-        ZO_TRY(F.gemm(xin, &PB::x, d, d, !llama, false, true, false, sh));
+        ZO_TRY(linear(0, sh));
+        ZO_TRY(F.gemm(xin, &PB::x, d, d, bias, false, true, false, sh));
         // ---- feed-forward block
         ZO_TRY(F.vector(t++, 0));
         if (!llama) ZO_TRY(F.vector(t++, 1));
+        ZO_TRY(F.smooth_prepare(t));                     // w_gate / fc1
         ZO_TRY(F.norm_quant(&PB::x, !llama, &xin));
         bool act_done = false;
         if (llama) {
             sh = F.frozen(t) && F.frozen(t + 1);
-            ZO_TRY(F.weights(t++, 0, true, sh));
-            ZO_TRY(F.weights(t++, f, true, sh));
-            ZO_TRY(F.gemm(xin, &PB::gu, 2 * f, d, false, false, false, false, sh));
+            ZO_TRY(linear(0, sh));
+            ZO_TRY(linear(f, sh));
+            ZO_TRY(F.gemm(xin, &PB::gu, 2 * f, d, bias, false, false, false, sh));
+            ZO_TRY(F.smooth_prepare(t));                 // w_down: its input is the SwiGLU output
             act_done = cfg.a_bits < 16 && zo_swiglu_quant_supported(f);
             prof_scope ps(c, act_done ? ZO_PROF_ACT_QUANT : ZO_PROF_OTHER);
             for (int b = 0; b < nb; ++b) {
                 char* gu = F.at(c->L.br[b].gu);
                 if (act_done)
                     ZO_HIP(c, zo_launch_swiglu_quant(gu, gu + (size_t)f * ts, F.at(c->L.br[b].hq), M, f, 2 * f,
-                                                     cfg.a_bits, cfg.a_sym, dt, c->st));
+                                                     cfg.a_bits, cfg.a_sym, dt, F.sm_delta(b), F.sm_inv(b), c->st));
                 else
                     ZO_HIP(c, zo_launch_swiglu(gu, gu + (size_t)f * ts, F.at(c->L.br[b].act), M, f, 2 * f, dt, c->st));
             }
         } else {
             sh = F.frozen(t);
-            ZO_TRY(F.weights(t++, 0, true, sh));
-            ZO_TRY(F.vector(t++, 2));
+            ZO_TRY(linear(0, sh));
             ZO_TRY(F.gemm(xin, &PB::act, f, d, true, true, false, false, sh));
+            ZO_TRY(F.smooth_prepare(t));                 // fc2
         }
         if (act_done) xin = &PB::hq;
         else ZO_TRY(F.act_quant(&PB::act, f, &xin));
         sh = F.frozen(t);
-        ZO_TRY(F.weights(t++, 0, true, sh));
-        if (!llama) ZO_TRY(F.vector(t++, 2));
-        ZO_TRY(F.gemm(xin, &PB::x, d, f, !llama, false, true, false, sh));
+        ZO_TRY(linear(0, sh));
+        ZO_TRY(F.gemm(xin, &PB::x, d, f, bias, false, true, false, sh));
     }
     // ---- head
     ZO_TRY(F.vector(t++, 0));
@@ -602,29 +740,86 @@ zo_status zo_forward_quant(zo_ctx* ctx, const void* ids, const float* target, in
     return run_forward(ctx, ids, target, B, S, seed, eps_signed, 1, loss_dev);
 }
 
-zo_status zo_update(zo_ctx* ctx, uint64_t seed, const float* coeff_dev, float coeff_host)
+namespace {
+// coefficient of tensor i: coeff_dev[stride * group] if coeff_dev, else coeff_host[group]
+zo_status update_all(zo_ctx* ctx, uint64_t seed, const float* coeff_dev, int stride, const float coeff_host[3])
 {
-    if (!ctx) return ZO_EINVAL;
     prof_scope ps(ctx, ZO_PROF_UPDATE);
     for (int i = 0; i < (int)ctx->params.size(); ++i) {
-        if (!trainable(ctx, i)) continue;
-        ZO_HIP(ctx, zo_launch_update((float*)ctx->params[i].ptr, ctx->params[i].numel, seed, i, coeff_dev, coeff_host, ctx->st));
+        if (!trainable(ctx, i) || !ctx->params[i].ptr) continue;
+        const int g = ctx->desc[i].lr_group;
+        ZO_HIP(ctx, zo_launch_update((float*)ctx->params[i].ptr, ctx->params[i].numel, seed, i,
+                                     coeff_dev ? coeff_dev + stride * g : nullptr, coeff_host ? coeff_host[g] : 0.0f, ctx->st));
     }
     return ZO_OK;
 }
 
-zo_status zo_step(zo_ctx* ctx, const void* ids, const float* target, int32_t B, int32_t S,
-                  uint64_t seed, float eps, float lr, float* out_dev)
+zo_status step_impl(zo_ctx* ctx, const void* ids, const float* target, int32_t B, int32_t S, uint64_t seed, float eps,
+                    const float lr[3], float* out_dev, int n_out)
 {
     zo_status s = check_batch(ctx, ids, target, B, S);
     if (s != ZO_OK) return s;
     if (!out_dev) return fail(ctx, ZO_EINVAL, "out_dev is NULL");
     if (!(eps > 0.0f)) return fail(ctx, ZO_EINVAL, "eps must be positive");
     float* loss2 = (float*)(ctx->ws + ctx->L.scalars);
+    float* out6 = loss2 + 2;
     s = run_forward(ctx, ids, target, B, S, seed, eps, 2, loss2);
     if (s != ZO_OK) return s;
-    ZO_HIP(ctx, zo_launch_projected_grad(loss2, eps, lr, out_dev, ctx->st));
-    return zo_update(ctx, seed, out_dev + 3, 0.0f);
+    ZO_HIP(ctx, zo_launch_projected_grad(loss2, eps, lr, out6, out_dev, n_out, ctx->st));
+    return update_all(ctx, seed, out6 + 3, 1, nullptr);
+}
+}  // namespace
+
+zo_status zo_update(zo_ctx* ctx, uint64_t seed, const float* coeff_dev, float coeff_host)
+{
+    if (!ctx) return ZO_EINVAL;
+    const float h[3] = {coeff_host, coeff_host, coeff_host};
+    return update_all(ctx, seed, coeff_dev, 0, h);
+}
+
+zo_status zo_update_groups(zo_ctx* ctx, uint64_t seed, const float* coeff_dev, const float* coeff_host)
+{
+    if (!ctx) return ZO_EINVAL;
+    if (!coeff_dev && !coeff_host) return fail(ctx, ZO_EINVAL, "no coefficients");
+    return update_all(ctx, seed, coeff_dev, 1, coeff_host);
+}
+
+zo_status zo_step(zo_ctx* ctx, const void* ids, const float* target, int32_t B, int32_t S,
+                  uint64_t seed, float eps, float lr, float* out_dev)
+{
+    if (!ctx) return ZO_EINVAL;
+    const float lrs[3] = {lr, lr, lr};
+    return step_impl(ctx, ids, target, B, S, seed, eps, lrs, out_dev, 4);
+}
+
+zo_status zo_step_groups(zo_ctx* ctx, const void* ids, const float* target, int32_t B, int32_t S,
+                         uint64_t seed, float eps, float lr_model, float lr_smooth, float lr_clip, float* out_dev)
+{
+    if (!ctx) return ZO_EINVAL;
+    const float lrs[3] = {lr_model, lr_smooth, lr_clip};
+    return step_impl(ctx, ids, target, B, S, seed, eps, lrs, out_dev, 6);
+}
+
+zo_status zo_init_learned_params(zo_ctx* ctx)
+{
+    if (!ctx) return ZO_EINVAL;
+    const zo_config& c = ctx->cfg;
+    if (!c.learn_clip && !c.learn_smooth) return ZO_OK;
+    for (size_t t = 0; t < ctx->desc.size(); ++t) {
+        const param_desc& p = ctx->desc[t];
+        if (!p.quantized) continue;
+        if (p.smooth >= 0 && p.owner == (int)t) {          // identity smoothing: s = 1, delta = 0
+            ZO_HIP(ctx, zo_launch_fill((float*)ctx->params[p.smooth].ptr, p.cols, 1.0f, ctx->st));
+            ZO_HIP(ctx, zo_launch_fill((float*)ctx->params[p.smooth + 1].ptr, p.cols, 0.0f, ctx->st));
+        }
+        if (p.clip >= 0) {                                  // the dynamic scheme's step and zero point; alpha 0, beta 1
+            int32_t* scratch = (int32_t*)(ctx->ws + ctx->L.what[0]);
+            ZO_HIP(ctx, zo_launch_init_learned((const float*)ctx->params[t].ptr, (int)p.rows, (int)p.cols, c.w_bits, c.w_group,
+                                               (float*)ctx->params[p.clip].ptr, (float*)ctx->params[p.clip + 1].ptr,
+                                               (float*)ctx->params[p.clip + 2].ptr, (float*)ctx->params[p.clip + 3].ptr, scratch, ctx->st));
+        }
+    }
+    return ZO_OK;
 }
 
 zo_status zo_debug_buffer(zo_ctx* ctx, int32_t which, int32_t branch, void** ptr, size_t* bytes)
@@ -683,6 +878,35 @@ zo_status zo_debug_quant_weight(const float* W_dev, int32_t N, int32_t K, int32_
     return e == hipSuccess ? ZO_OK : ZO_EHIP;
 }
 
+zo_status zo_debug_quant_weight_learned(const float* W_dev, int32_t N, int32_t K, int32_t bits, int32_t group,
+                                        uint64_t seed, int32_t tensor_id, float eps_signed,
+                                        const float* scale_dev, const float* step_dev, const float* zp_dev,
+                                        const float* alpha_dev, const float* beta_dev, int32_t out_dtype,
+                                        uint8_t* codes_dev, void* what_dev, void* hip_stream)
+{
+    if (!W_dev || !step_dev || !zp_dev || !alpha_dev || !beta_dev || !what_dev || N < 0 || K <= 0) return ZO_EINVAL;
+    if (out_dtype != ZO_ACT_FP32 && out_dtype != ZO_ACT_BF16) return ZO_EINVAL;
+    if (bits < 1 || bits > 8 || group < 0) return ZO_EINVAL;
+    const int g = group ? group : K;
+    if ((K & 7) || (g & 7) || K % g) return ZO_ESHAPE;
+    if (!aligned16(W_dev) || !aligned16(what_dev) || !aligned16(scale_dev)) return ZO_EALIGN;
+    const zo_learned p{step_dev, zp_dev, alpha_dev, beta_dev, scale_dev}, none{};
+    hipError_t e = zo_launch_fq_weight_learned(W_dev, N, K, bits, group, seed, tensor_id, eps_signed, out_dtype, p, none, what_dev,
+                                               nullptr, codes_dev, (hipStream_t)hip_stream);
+    return e == hipSuccess ? ZO_OK : ZO_EHIP;
+}
+
+zo_status zo_debug_smooth_bias(const float* W_dev, int32_t N, int32_t K, uint64_t seed, int32_t tensor_id, float eps_signed,
+                               const float* delta_dev, const float* bias_dev, float* out_dev, void* hip_stream)
+{
+    if (!W_dev || !delta_dev || !out_dev || N < 0 || K <= 0) return ZO_EINVAL;
+    if (K & 7) return ZO_ESHAPE;
+    if (!aligned16(W_dev) || !aligned16(delta_dev)) return ZO_EALIGN;
+    hipError_t e = zo_launch_bias_shift(W_dev, N, K, seed, tensor_id, eps_signed, delta_dev, nullptr, bias_dev, nullptr, out_dev, nullptr,
+                                        (hipStream_t)hip_stream);
+    return e == hipSuccess ? ZO_OK : ZO_EHIP;
+}
+
 zo_status zo_debug_quant_act(const void* X_dev, int32_t M, int32_t K, int32_t bits, int32_t sym, int32_t dtype,
                              int16_t* codes_dev, float* step_dev, int32_t* zp_dev, void* xhat_dev, void* hip_stream)
 {
@@ -691,7 +915,8 @@ zo_status zo_debug_quant_act(const void* X_dev, int32_t M, int32_t K, int32_t bi
     if (bits < 2 || bits > 8) return ZO_EINVAL;
     if (K & 7) return ZO_ESHAPE;
     if (!aligned16(X_dev) || !aligned16(xhat_dev)) return ZO_EALIGN;
-    hipError_t e = zo_launch_fq_act(X_dev, xhat_dev, M, K, bits, sym, dtype, codes_dev, step_dev, zp_dev, (hipStream_t)hip_stream);
+    hipError_t e = zo_launch_fq_act(X_dev, xhat_dev, M, K, bits, sym, dtype, codes_dev, step_dev, zp_dev, nullptr, nullptr,
+                                    (hipStream_t)hip_stream);
     return e == hipSuccess ? ZO_OK : ZO_EHIP;
 }
 
@@ -722,7 +947,7 @@ zo_status zo_linear_fakequant(const void* X_dev, const float* W_dev, const float
     if (e != hipSuccess) return ZO_EHIP;
     const void* xin = X_dev;
     if (a_bits < 16) {
-        e = zo_launch_fq_act(X_dev, xhat, M, K, a_bits, a_sym, dtype, nullptr, nullptr, nullptr, st);
+        e = zo_launch_fq_act(X_dev, xhat, M, K, a_bits, a_sym, dtype, nullptr, nullptr, nullptr, nullptr, nullptr, st);
         if (e != hipSuccess) return ZO_EHIP;
         xin = xhat;
     }
@@ -760,7 +985,7 @@ zo_status zo_linear_frozen_int4(const void* X_dev, const void* codes_dev, const 
     if (e != hipSuccess) return ZO_EHIP;
     const void* xin = X_dev;
     if (a_bits < 16) {
-        e = zo_launch_fq_act(X_dev, xhat, M, K, a_bits, a_sym, dtype, nullptr, nullptr, nullptr, st);
+        e = zo_launch_fq_act(X_dev, xhat, M, K, a_bits, a_sym, dtype, nullptr, nullptr, nullptr, nullptr, nullptr, st);
         if (e != hipSuccess) return ZO_EHIP;
         xin = xhat;
     }

@@ -341,6 +341,174 @@ hipError_t zo_launch_fq_weight(const float* W, int32_t N, int32_t K, int32_t bit
 }
 
 // ---------------------------------------------------------------------------------------------
+// Adaptive weight quantizer (Eq. 5) with learnable per-group step, zero point and clipping
+// coefficients, optionally on the smoothed weight s (.) W of Eq. 4.  The parameter arrays arrive
+// already perturbed (one set per branch); there is no min/max reduction, so any group size that is
+// a multiple of 8 works: gl = group / 8 threads share one parameter set.
+//   code = clamp(rint(w * (1/step)) + rint(zp), rint(alpha Q_P), rint(beta Q_P)),  w^ = (code - rint(zp)) * step
+// with the bounds kept inside [0, Q_P] and ordered, and the step floored at 1e-5.
+// ---------------------------------------------------------------------------------------------
+template <typename TO>
+__device__ __forceinline__ void fq_learned_branch(const float w[8], const float z[8], float e, const zo_learned& p, int64_t g, int kb,
+                                                  int bits, TO* out, int64_t b, uint8_t* codes)
+{
+    float st = p.step[g];
+    if (!(st >= 1e-5f)) st = 1e-5f;
+    const float inv = 1.0f / st;
+    const float qp = (float)((1 << bits) - 1);
+    const float zr = rintf(p.zp[g]);
+    float lo = rintf(p.alpha[g] * qp), hi = rintf(p.beta[g] * qp);
+    lo = lo < 0.0f ? 0.0f : lo;
+    lo = lo > qp ? qp : lo;
+    hi = hi > qp ? qp : hi;
+    hi = hi < lo ? lo : hi;
+    float sc[8];
+    if (p.scale) zo_load8(p.scale + kb, sc);
+    float o[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        float v = __builtin_fmaf(e, z[i], w[i]);
+        if (p.scale) v = sc[i] * v;
+        float q = rintf(v * inv) + zr;
+        q = q < lo ? lo : q;
+        q = q > hi ? hi : q;
+        if (codes) codes[8 * b + i] = (uint8_t)q;
+        o[i] = (q - zr) * st;
+    }
+    zo_store8(out + 8 * b, o);
+}
+
+template <typename TO>
+__global__ __launch_bounds__(256) void zo_fq_weight_learned_kernel(const float* __restrict__ W, int64_t nblk, int k8, int gl, zo_stream s,
+                                                                   float eps, int bits, zo_learned pp, zo_learned pm,
+                                                                   TO* __restrict__ out_p, TO* __restrict__ out_m, uint8_t* codes)
+{
+    const int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (b >= nblk) return;
+    float w[8], z[8];
+    zo_load8(W + 8 * b, w);
+    if (eps != 0.0f) zo_z8(s, (uint64_t)b, z);
+    else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) z[i] = 0.0f;
+    }
+    const int64_t g = b / gl;
+    const int kb = (int)(b % k8) * 8;
+    fq_learned_branch<TO>(w, z, eps, pp, g, kb, bits, out_p, b, codes);
+    if (out_m) fq_learned_branch<TO>(w, z, -eps, pm, g, kb, bits, out_m, b, nullptr);
+}
+
+hipError_t zo_launch_fq_weight_learned(const float* W, int32_t N, int32_t K, int32_t bits, int32_t group, uint64_t seed, int32_t tid,
+                                       float eps, int dtype, const zo_learned& pp, const zo_learned& pm, void* out_plus, void* out_minus,
+                                       uint8_t* codes, hipStream_t st)
+{
+    const int64_t nblk = (int64_t)N * K / 8;
+    if (nblk == 0) return hipSuccess;
+    if (group == 0) group = K;
+    if ((K & 7) || (group & 7) || K % group || bits < 1 || bits > 8 || (nblk + 255) / 256 > 0x7FFFFFFF) return hipErrorInvalidValue;
+    const int grid = (int)((nblk + 255) / 256);
+    const zo_stream s = make_stream(seed, tid);
+    if (dtype == ZO_T_BF16)
+        zo_fq_weight_learned_kernel<zo_bf16><<<grid, 256, 0, st>>>(W, nblk, K / 8, group / 8, s, eps, bits, pp, pm, (zo_bf16*)out_plus,
+                                                                   (zo_bf16*)out_minus, codes);
+    else
+        zo_fq_weight_learned_kernel<float><<<grid, 256, 0, st>>>(W, nblk, K / 8, group / 8, s, eps, bits, pp, pm, (float*)out_plus,
+                                                                 (float*)out_minus, codes);
+    return hipGetLastError();
+}
+
+// Initial values of Eq. 5's parameters from what the dynamic quantizer computes (zero point as a
+// real number, alpha = 0, beta = 1).
+__global__ __launch_bounds__(256) void zo_init_learned_kernel(const int32_t* __restrict__ zp_i, int64_t n, float* zp, float* alpha, float* beta)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    zp[i] = (float)zp_i[i];
+    alpha[i] = 0.0f;
+    beta[i] = 1.0f;
+}
+
+hipError_t zo_launch_init_learned(const float* W, int32_t N, int32_t K, int32_t bits, int32_t group, float* step, float* zp,
+                                  float* alpha, float* beta, int32_t* zp_scratch, hipStream_t st)
+{
+    const int g = group ? group : K;
+    const int64_t n = (int64_t)N * (K / g);
+    if (n == 0) return hipSuccess;
+    hipError_t e = zo_launch_fq_weight(W, N, K, bits, group, 0, 0, 0.0f, ZO_T_F32, nullptr, nullptr, nullptr, step, zp_scratch, st);
+    if (e != hipSuccess) return e;
+    zo_init_learned_kernel<<<(int)((n + 255) / 256), 256, 0, st>>>(zp_scratch, n, zp, alpha, beta);
+    return hipGetLastError();
+}
+
+// out[i] = value (fill) / out[i] = 1 / in[i] (correctly rounded division): the small vectors of Eq. 4
+__global__ __launch_bounds__(256) void zo_fill_kernel(float* out, int64_t n, float value)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) out[i] = value;
+}
+__global__ __launch_bounds__(256) void zo_reciprocal_kernel(const float* __restrict__ in, float* __restrict__ out, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) out[i] = 1.0f / in[i];
+}
+hipError_t zo_launch_fill(float* out, int64_t n, float value, hipStream_t st)
+{
+    if (n == 0) return hipSuccess;
+    zo_fill_kernel<<<(int)((n + 255) / 256), 256, 0, st>>>(out, n, value);
+    return hipGetLastError();
+}
+hipError_t zo_launch_reciprocal(const float* in, float* out, int64_t n, hipStream_t st)
+{
+    if (n == 0) return hipSuccess;
+    zo_reciprocal_kernel<<<(int)((n + 255) / 256), 256, 0, st>>>(in, out, n);
+    return hipGetLastError();
+}
+
+// Bias of the smoothed linear (Eq. 4): out[n] = bias[n] + sum_k delta[k] * w'[n][k], w' = w +- eps u, for both
+// branches in one pass over W.  One wavefront per output row, lane-strided partial sums in k order, then a
+// fixed xor tree: the result does not depend on the launch shape.
+__global__ __launch_bounds__(256) void zo_bias_shift_kernel(const float* __restrict__ W, int N, int K, zo_stream s, float eps,
+                                                            const float* __restrict__ delta_p, const float* __restrict__ delta_m,
+                                                            const float* __restrict__ bias_p, const float* __restrict__ bias_m,
+                                                            float* __restrict__ out_p, float* __restrict__ out_m)
+{
+    const int lane = threadIdx.x & 63;
+    const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (n >= N) return;
+    const int k8 = K / 8;
+    float ap = 0.0f, am = 0.0f;
+    for (int j = lane; j < k8; j += 64) {
+        const int64_t b = (int64_t)n * k8 + j;
+        float w[8], z[8], dp[8], dm[8];
+        zo_load8(W + 8 * b, w);
+        if (eps != 0.0f) zo_z8(s, (uint64_t)b, z);
+        zo_load8(delta_p + 8 * j, dp);
+        if (out_m) zo_load8(delta_m + 8 * j, dm);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float zi = eps != 0.0f ? z[i] : 0.0f;
+            ap = __builtin_fmaf(dp[i], __builtin_fmaf(eps, zi, w[i]), ap);
+            if (out_m) am = __builtin_fmaf(dm[i], __builtin_fmaf(-eps, zi, w[i]), am);
+        }
+    }
+    ap = zo_group_sum<64>(ap);
+    am = zo_group_sum<64>(am);
+    if (lane == 0) {
+        out_p[n] = (bias_p ? bias_p[n] : 0.0f) + ap;
+        if (out_m) out_m[n] = (bias_m ? bias_m[n] : 0.0f) + am;
+    }
+}
+
+hipError_t zo_launch_bias_shift(const float* W, int32_t N, int32_t K, uint64_t seed, int32_t tid, float eps,
+                                const float* delta_p, const float* delta_m, const float* bias_p, const float* bias_m,
+                                float* out_p, float* out_m, hipStream_t st)
+{
+    if (N == 0) return hipSuccess;
+    zo_bias_shift_kernel<<<(N + 3) / 4, 256, 0, st>>>(W, N, K, make_stream(seed, tid), eps, delta_p, delta_m, bias_p, bias_m, out_p, out_m);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
 // Frozen weights of the lightweight variant (Section "Lightweight ZeroQAT for memory reduction"):
 // stored as 4-bit codes two per byte (low nibble = even k), one binary16 step and one int16 zero
 // point per group.  zo_pack_int4_kernel pre-quantizes an fp32 matrix into that form (same
@@ -444,16 +612,27 @@ hipError_t zo_launch_dequant_int4(const void* packed, const void* step_f16, cons
 // ---------------------------------------------------------------------------------------------
 template <typename T, bool DEBUG>
 __global__ __launch_bounds__(256) void zo_fq_act_kernel(const T* __restrict__ X, T* __restrict__ Xhat, int M, int K, int bits, int sym,
-                                                        int16_t* codes, float* step, int32_t* zp)
+                                                        int16_t* codes, float* step, int32_t* zp,
+                                                        const float* __restrict__ sm_delta, const float* __restrict__ sm_inv)
 {
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= M) return;                            // whole wave leaves together
     const T* x = X + (int64_t)row * K;
     float mn = INFINITY, mx = -INFINITY;
+    // Eq. 4: with smoothing the quantizer sees (x - delta) / s
+    auto smooth8 = [&](int c, float v[8]) {
+        if (!sm_delta) return;
+        float dl[8], iv[8];
+        zo_load8(sm_delta + c, dl);
+        zo_load8(sm_inv + c, iv);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = (v[i] - dl[i]) * iv[i];
+    };
     for (int c = lane * 8; c < K; c += 512) {
         float v[8];
         zo_load8(x + c, v);
+        smooth8(c, v);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             if (sym) mx = fmaxf(mx, fabsf(v[i]));
@@ -470,6 +649,7 @@ __global__ __launch_bounds__(256) void zo_fq_act_kernel(const T* __restrict__ X,
     for (int c = lane * 8; c < K; c += 512) {
         float v[8], o[8];
         zo_load8(x + c, v);
+        smooth8(c, v);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             float cd = zo_code(q, v[i]);
@@ -481,17 +661,17 @@ __global__ __launch_bounds__(256) void zo_fq_act_kernel(const T* __restrict__ X,
 }
 
 hipError_t zo_launch_fq_act(const void* X, void* Xhat, int32_t M, int32_t K, int32_t bits, int32_t sym, int dtype,
-                            int16_t* codes, float* step, int32_t* zp, hipStream_t st)
+                            int16_t* codes, float* step, int32_t* zp, const float* sm_delta, const float* sm_inv, hipStream_t st)
 {
     if (M == 0) return hipSuccess;
     const int grid = (M + 3) / 4;
     const bool dbg = codes || step || zp;
     if (dtype == ZO_T_BF16) {
-        if (dbg) zo_fq_act_kernel<zo_bf16, true><<<grid, 256, 0, st>>>((const zo_bf16*)X, (zo_bf16*)Xhat, M, K, bits, sym, codes, step, zp);
-        else zo_fq_act_kernel<zo_bf16, false><<<grid, 256, 0, st>>>((const zo_bf16*)X, (zo_bf16*)Xhat, M, K, bits, sym, nullptr, nullptr, nullptr);
+        if (dbg) zo_fq_act_kernel<zo_bf16, true><<<grid, 256, 0, st>>>((const zo_bf16*)X, (zo_bf16*)Xhat, M, K, bits, sym, codes, step, zp, sm_delta, sm_inv);
+        else zo_fq_act_kernel<zo_bf16, false><<<grid, 256, 0, st>>>((const zo_bf16*)X, (zo_bf16*)Xhat, M, K, bits, sym, nullptr, nullptr, nullptr, sm_delta, sm_inv);
     } else {
-        if (dbg) zo_fq_act_kernel<float, true><<<grid, 256, 0, st>>>((const float*)X, (float*)Xhat, M, K, bits, sym, codes, step, zp);
-        else zo_fq_act_kernel<float, false><<<grid, 256, 0, st>>>((const float*)X, (float*)Xhat, M, K, bits, sym, nullptr, nullptr, nullptr);
+        if (dbg) zo_fq_act_kernel<float, true><<<grid, 256, 0, st>>>((const float*)X, (float*)Xhat, M, K, bits, sym, codes, step, zp, sm_delta, sm_inv);
+        else zo_fq_act_kernel<float, false><<<grid, 256, 0, st>>>((const float*)X, (float*)Xhat, M, K, bits, sym, nullptr, nullptr, nullptr, sm_delta, sm_inv);
     }
     return hipGetLastError();
 }

@@ -35,8 +35,25 @@ hipError_t zo_launch_dequant_int4(const void* packed, const void* step_f16, cons
                                   int dtype, void* out0, void* out1, hipStream_t st);
 
 // ---- per-token activation fake-quantizer -------------------------------------------------------
+// sm_delta / sm_inv (fp32 [K], or both NULL): the quantizer sees (x - delta) * inv (Eq. 4)
 hipError_t zo_launch_fq_act(const void* X, void* Xhat, int32_t M, int32_t K, int32_t bits, int32_t sym, int dtype,
-                            int16_t* codes, float* step, int32_t* zp, hipStream_t st);
+                            int16_t* codes, float* step, int32_t* zp, const float* sm_delta, const float* sm_inv, hipStream_t st);
+
+// ---- adaptive weight quantizer (Eq. 5) / smoothing (Eq. 4) -------------------------------------
+// per-group parameters [N][K/group] and the optional per-feature scale [K], all fp32, already perturbed
+struct zo_learned { const float* step; const float* zp; const float* alpha; const float* beta; const float* scale; };
+hipError_t zo_launch_fq_weight_learned(const float* W, int32_t N, int32_t K, int32_t bits, int32_t group, uint64_t seed, int32_t tid,
+                                       float eps, int dtype, const zo_learned& pp, const zo_learned& pm, void* out_plus, void* out_minus,
+                                       uint8_t* codes, hipStream_t st);
+// initial parameters from the dynamic scheme on W; zp_scratch: int32 [N][K/group]
+hipError_t zo_launch_init_learned(const float* W, int32_t N, int32_t K, int32_t bits, int32_t group, float* step, float* zp,
+                                  float* alpha, float* beta, int32_t* zp_scratch, hipStream_t st);
+hipError_t zo_launch_fill(float* out, int64_t n, float value, hipStream_t st);
+hipError_t zo_launch_reciprocal(const float* in, float* out, int64_t n, hipStream_t st);
+// out[n] = bias[n] + sum_k delta[k] * (w[n][k] +- eps u); the minus outputs may be NULL
+hipError_t zo_launch_bias_shift(const float* W, int32_t N, int32_t K, uint64_t seed, int32_t tid, float eps,
+                                const float* delta_p, const float* delta_m, const float* bias_p, const float* bias_m,
+                                float* out_p, float* out_m, hipStream_t st);
 
 // ---- GEMM: Y[b] = X[b] * W[b]^T (+bias[b]) (relu) (+residual[b]); batch over branches -----------
 struct zo_gemm_args {
@@ -63,11 +80,12 @@ hipError_t zo_launch_norm(const void* x, const float* gamma, const float* beta, 
 // norm fused with the per-token quantizer (row kept in registers): d <= 8192
 bool zo_norm_quant_supported(int32_t d);
 hipError_t zo_launch_norm_quant(const void* x, const float* gamma, const float* beta, void* xhat, int32_t M, int32_t d,
-                                float eps, int32_t bits, int32_t sym, int dtype, hipStream_t st);
+                                float eps, int32_t bits, int32_t sym, int dtype,
+                                const float* sm_delta, const float* sm_inv, hipStream_t st);
 // SwiGLU fused with the per-token quantizer: cols <= 16384
 bool zo_swiglu_quant_supported(int32_t cols);
 hipError_t zo_launch_swiglu_quant(const void* gate, const void* up, void* xhat, int64_t rows, int32_t cols, int64_t in_stride,
-                                  int32_t bits, int32_t sym, int dtype, hipStream_t st);
+                                  int32_t bits, int32_t sym, int dtype, const float* sm_delta, const float* sm_inv, hipStream_t st);
 hipError_t zo_launch_rope(void* q, void* k, const float* cos_tab, const float* sin_tab,
                           int32_t M, int32_t S, int32_t H, int32_t dh, int64_t row_stride, int dtype, hipStream_t st);
 hipError_t zo_launch_attention(const void* q, const void* k, const void* v, void* out,
@@ -85,5 +103,6 @@ hipError_t zo_launch_ce_rows(const float* logits, const int32_t* ids, float* row
 hipError_t zo_launch_sqerr_rows(const void* y, const float* target, float* row_loss, int32_t M, int32_t N, int dtype, hipStream_t st);
 // loss = sum(row_loss) * scale, fixed summation order
 hipError_t zo_launch_reduce_loss(const float* row_loss, int32_t M, float scale, float* loss, hipStream_t st);
-// out = { L+, L-, g, lr*g } from loss[0], loss[1]
-hipError_t zo_launch_projected_grad(const float* loss2, float eps, float lr, float* out4, hipStream_t st);
+// out6 = { L+, L-, g, lr[0]*g, lr[1]*g, lr[2]*g } from loss[0], loss[1]; the first n_user values also go to user_out
+hipError_t zo_launch_projected_grad(const float* loss2, float eps, const float lr[3], float* out6, float* user_out, int n_user,
+                                    hipStream_t st);

@@ -133,7 +133,8 @@ hipError_t zo_launch_norm(const void* x, const float* gamma, const float* beta, 
 template <typename T, int NC>
 __global__ __launch_bounds__(256) void zo_norm_quant_kernel(const T* __restrict__ x, const float* __restrict__ gamma,
                                                             const float* __restrict__ beta, T* __restrict__ xhat, int M, int d,
-                                                            float eps, int bits, int sym)
+                                                            float eps, int bits, int sym,
+                                                            const float* __restrict__ sm_delta, const float* __restrict__ sm_inv)
 {
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -183,6 +184,13 @@ __global__ __launch_bounds__(256) void zo_norm_quant_kernel(const T* __restrict_
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[i][e] = zo_round_to<T>((v[i][e] * rstd) * g[e]);
             }
+            if (sm_delta) {                           // Eq. 4: the quantizer sees (x - delta) / s
+                float dl[8], iv[8];
+                zo_load8(sm_delta + c, dl);
+                zo_load8(sm_inv + c, iv);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[i][e] = (v[i][e] - dl[e]) * iv[e];
+            }
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 if (sym) mx = fmaxf(mx, fabsf(v[i][e]));
@@ -208,11 +216,12 @@ __global__ __launch_bounds__(256) void zo_norm_quant_kernel(const T* __restrict_
 bool zo_norm_quant_supported(int32_t d) { return d > 0 && (d & 7) == 0 && d <= 8192; }
 
 hipError_t zo_launch_norm_quant(const void* x, const float* gamma, const float* beta, void* xhat, int32_t M, int32_t d,
-                                float eps, int32_t bits, int32_t sym, int dtype, hipStream_t st)
+                                float eps, int32_t bits, int32_t sym, int dtype,
+                                const float* sm_delta, const float* sm_inv, hipStream_t st)
 {
     if (M == 0) return hipSuccess;
     const int grid = (M + 3) / 4;
-#define ZO_NQ(T, NC) zo_norm_quant_kernel<T, NC><<<grid, 256, 0, st>>>((const T*)x, gamma, beta, (T*)xhat, M, d, eps, bits, sym)
+#define ZO_NQ(T, NC) zo_norm_quant_kernel<T, NC><<<grid, 256, 0, st>>>((const T*)x, gamma, beta, (T*)xhat, M, d, eps, bits, sym, sm_delta, sm_inv)
     if (dtype == ZO_T_BF16) {
         if (d <= 2048) ZO_NQ(zo_bf16, 4); else if (d <= 4096) ZO_NQ(zo_bf16, 8); else ZO_NQ(zo_bf16, 16);
     } else {
@@ -382,7 +391,8 @@ hipError_t zo_launch_swiglu(const void* gate, const void* up, void* out, int64_t
 // ---------------------------------------------------------------------------------------------
 template <typename T, int NC>
 __global__ __launch_bounds__(256) void zo_swiglu_quant_kernel(const T* __restrict__ gate, const T* __restrict__ up, T* __restrict__ xhat,
-                                                              int cols, int64_t in_stride, int bits, int sym)
+                                                              int cols, int64_t in_stride, int bits, int sym,
+                                                              const float* __restrict__ sm_delta, const float* __restrict__ sm_inv)
 {
     __shared__ float red[2][4];
     const int64_t row = blockIdx.x;
@@ -395,9 +405,12 @@ __global__ __launch_bounds__(256) void zo_swiglu_quant_kernel(const T* __restric
             float g[8], u[8];
             zo_load8(gate + row * in_stride + c, g);
             zo_load8(up + row * in_stride + c, u);
+            float dl[8], iv[8];
+            if (sm_delta) { zo_load8(sm_delta + c, dl); zo_load8(sm_inv + c, iv); }
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 v[i][e] = zo_round_to<T>((g[e] / (1.0f + __expf(-g[e]))) * u[e]);
+                if (sm_delta) v[i][e] = (v[i][e] - dl[e]) * iv[e];
                 if (sym) mx = fmaxf(mx, fabsf(v[i][e]));
                 else { mn = fminf(mn, v[i][e]); mx = fmaxf(mx, v[i][e]); }
             }
@@ -425,11 +438,11 @@ __global__ __launch_bounds__(256) void zo_swiglu_quant_kernel(const T* __restric
 bool zo_swiglu_quant_supported(int32_t cols) { return cols > 0 && (cols & 7) == 0 && cols <= 16384; }
 
 hipError_t zo_launch_swiglu_quant(const void* gate, const void* up, void* xhat, int64_t rows, int32_t cols, int64_t in_stride,
-                                  int32_t bits, int32_t sym, int dtype, hipStream_t st)
+                                  int32_t bits, int32_t sym, int dtype, const float* sm_delta, const float* sm_inv, hipStream_t st)
 {
     if (rows == 0) return hipSuccess;
     if (rows > 0x7FFFFFFF) return hipErrorInvalidValue;
-#define ZO_SQ(T, NC) zo_swiglu_quant_kernel<T, NC><<<(int)rows, 256, 0, st>>>((const T*)gate, (const T*)up, (T*)xhat, cols, in_stride, bits, sym)
+#define ZO_SQ(T, NC) zo_swiglu_quant_kernel<T, NC><<<(int)rows, 256, 0, st>>>((const T*)gate, (const T*)up, (T*)xhat, cols, in_stride, bits, sym, sm_delta, sm_inv)
     if (dtype == ZO_T_BF16) {
         if (cols <= 4096) ZO_SQ(zo_bf16, 2); else if (cols <= 12288) ZO_SQ(zo_bf16, 6); else ZO_SQ(zo_bf16, 8);
     } else {
@@ -537,18 +550,27 @@ hipError_t zo_launch_reduce_loss(const float* row_loss, int32_t M, float scale, 
 }
 
 // g = (L+ - L-) / (2 eps) (Eq. 2, q = 1) and c = eta * g (Eq. 3), formed in fp64, stored as fp32
-__global__ void zo_projected_grad_kernel(const float* __restrict__ loss2, float eps, float lr, float* __restrict__ out4)
+// out6 = { L+, L-, g, c_model, c_smoothing, c_clipping } (one coefficient per learning-rate group);
+// the first n_user values are also written to user_out
+__global__ void zo_projected_grad_kernel(const float* __restrict__ loss2, float eps, float lr0, float lr1, float lr2,
+                                         float* __restrict__ out6, float* __restrict__ user_out, int n_user)
 {
     const float lp = loss2[0], lm = loss2[1];
     const float g = (float)(((double)lp - (double)lm) / (2.0 * (double)eps));
-    out4[0] = lp;
-    out4[1] = lm;
-    out4[2] = g;
-    out4[3] = (float)((double)lr * (double)g);
+    float v[6];
+    v[0] = lp;
+    v[1] = lm;
+    v[2] = g;
+    v[3] = (float)((double)lr0 * (double)g);
+    v[4] = (float)((double)lr1 * (double)g);
+    v[5] = (float)((double)lr2 * (double)g);
+    for (int i = 0; i < 6; ++i) out6[i] = v[i];
+    for (int i = 0; i < n_user; ++i) user_out[i] = v[i];
 }
 
-hipError_t zo_launch_projected_grad(const float* loss2, float eps, float lr, float* out4, hipStream_t st)
+hipError_t zo_launch_projected_grad(const float* loss2, float eps, const float lr[3], float* out6, float* user_out, int n_user,
+                                    hipStream_t st)
 {
-    zo_projected_grad_kernel<<<1, 1, 0, st>>>(loss2, eps, lr, out4);
+    zo_projected_grad_kernel<<<1, 1, 0, st>>>(loss2, eps, lr[0], lr[1], lr[2], out6, user_out, n_user);
     return hipGetLastError();
 }
