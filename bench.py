@@ -30,6 +30,12 @@ WORKLOADS = {
     # only the query / value projections trainable; per-token 4-bit activations; 4 x 2048 tokens
     "llama13b_lightweight_w4a4_g128_4x2048": dict(arch="llama", n_layers=40, d_model=5120, n_heads=40, d_ffn=13824,
                                                   vocab=32000, w_bits=4, w_group=128, a_bits=4, B=4, S=2048, lightweight=1),
+    # the paper's own quantizer settings (Eq. 5 / Eq. 4 as ZO-trained tensors, learning rates of the appendix table):
+    # Llama-shaped weight-only keeps the clipping only; OPT-shaped W4A4 has smoothing and clipping
+    "llama7b_w2a16_g64_clip_8x1024": dict(arch="llama", n_layers=32, d_model=4096, n_heads=32, d_ffn=11008, vocab=32000,
+                                          w_bits=2, w_group=64, a_bits=16, B=8, S=1024, learn_clip=1),
+    "opt1p3b_w4a4_g128_smooth_clip_16x512": dict(arch="opt", n_layers=24, d_model=2048, n_heads=32, d_ffn=8192, vocab=50272,
+                                                 w_bits=4, w_group=128, a_bits=4, B=16, S=512, learn_clip=1, learn_smooth=1),
     "tiny_w4a16_g64_8x128": dict(arch="llama", n_layers=4, d_model=512, n_heads=8, d_ffn=2048, vocab=4096,
                                  w_bits=4, w_group=64, a_bits=16, B=8, S=128),
 }
@@ -70,16 +76,18 @@ def cpu_baseline(w):
     arch = orc.ARCH_LLAMA if w["arch"] == "llama" else orc.ARCH_OPT
     cfg = orc.Config(arch, n_layers=1, d_model=w["d_model"], n_heads=w["n_heads"], d_ffn=w["d_ffn"], vocab=w["vocab"],
                      max_seq=w["S"], w_bits=w["w_bits"], w_group=w["w_group"], a_bits=w["a_bits"], act_dtype=1,
-                     lightweight=w.get("lightweight", 0))
+                     lightweight=w.get("lightweight", 0), learn_clip=w.get("learn_clip", 0), learn_smooth=w.get("learn_smooth", 0))
     shapes = orc.param_shapes(cfg)
     params = synth.model_params(shapes, 1234)
+    if cfg.learn_clip or cfg.learn_smooth:
+        orc.init_learned_params(cfg, params)
     trainable = None
     if w.get("lightweight"):
         trainable = [name.endswith(".wq") or name.endswith(".wv") for name, _, _ in shapes]
         params = [orc.pack_int4(p, w["w_group"]) if (q and not t) else p for p, t, (_, _, q) in zip(params, trainable, shapes)]
     ids = synth.token_ids(1, w["S"], w["vocab"], 5678)
     t0 = time.perf_counter()
-    orc.zo_step(cfg, params, 0, 1e-3, 1e-6, ids=ids, trainable=trainable)
+    orc.zo_step(cfg, params, 0, 1e-3, 1e-6, ids=ids, trainable=trainable, lr_smooth=5e-6, lr_clip=1e-5)
     t_sample = time.perf_counter() - t0
     sample = dict(w, n_layers=1, B=1)
     ratio = gemm_flops_per_step(w) / gemm_flops_per_step(sample)
@@ -116,7 +124,8 @@ def main():
     arch = zo.ARCH_LLAMA if w["arch"] == "llama" else zo.ARCH_OPT
     cfg = zo.make_config(arch, n_layers=w["n_layers"], d_model=w["d_model"], n_heads=w["n_heads"], d_ffn=w["d_ffn"],
                          vocab=w["vocab"], max_seq=w["S"], w_bits=w["w_bits"], w_group=w["w_group"], a_bits=w["a_bits"],
-                         act_dtype=zo.ACT_BF16, lightweight=w.get("lightweight", 0))
+                         act_dtype=zo.ACT_BF16, lightweight=w.get("lightweight", 0), learn_clip=w.get("learn_clip", 0),
+                         learn_smooth=w.get("learn_smooth", 0))
     n = zo.zo_num_params(cfg)
     gen = torch.Generator(device=dev)
     gen.manual_seed(1234)
@@ -145,6 +154,16 @@ def main():
     ids = torch.randint(0, w["vocab"], (B, S), dtype=torch.int32, device=dev, generator=gen)
     ctx = zo.Context(cfg, params, B, S, trainable=trainable)
     eps, lr = 1e-3, 1e-6
+    learned = bool(w.get("learn_clip") or w.get("learn_smooth"))
+    if learned:
+        ctx.zo_init_learned_params()              # the quantizer / smoothing tensors were filled with noise above
+    lr_smooth, lr_clip = 5e-6, 1e-5               # appendix, hyperparameter table
+    out6 = torch.zeros(6, dtype=torch.float32, device=dev)
+
+    def one_step(seed):
+        if learned:
+            return ctx.zo_step_groups(ids, None, B, S, seed, eps, lr, lr_smooth, lr_clip, out6)
+        return ctx.zo_step(ids, None, B, S, seed=seed, eps=eps, lr=lr)
 
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -153,14 +172,14 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     for i in range(args.warmup):
-        ctx.zo_step(ids, None, B, S, seed=i, eps=eps, lr=lr)
+        one_step(i)
     torch.cuda.synchronize()
     if not args.no_profile:
         ctx.zo_profile_begin()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        out = ctx.zo_step(ids, None, B, S, seed=args.warmup + i, eps=eps, lr=lr)
+        out = one_step(args.warmup + i)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     prof = None if args.no_profile else ctx.zo_profile_end()
