@@ -66,7 +66,9 @@ typedef struct {
     int32_t learn_smooth;/* 1 = channel-wise smoothing (Eq. 4): every distinct input activation of the
                             quantized linears gets two more trainable fp32 tensors [K] -- s and delta;
                             needs learn_clip = 1 and a_bits < 16 */
-    int32_t reserved[1];
+    int32_t no_fused;    /* 0 = quantized linears of a forward over at most 128 tokens (bf16 storage, groups of
+                            8..128, no learned / packed tensors) build their weight tiles inside the GEMM kernel;
+                            1 = always quantize once into the workspace and run the plain GEMM */
 } zo_config;
 
 /* One parameter tensor.  The array given to zo_init lists them in the fixed order below; the
@@ -136,7 +138,8 @@ zo_status zo_update(zo_ctx* ctx, uint64_t seed, const float* coeff_dev, float co
  * ZO_PROF_CATEGORIES entries).  A "GEMM" group is exactly one launch of the GEMM kernel (both
  * branches of Eq. 2 batched in it). */
 enum { ZO_PROF_GEMM = 0, ZO_PROF_WEIGHT_QUANT = 1, ZO_PROF_ACT_QUANT = 2, ZO_PROF_ATTENTION = 3,
-       ZO_PROF_UPDATE = 4, ZO_PROF_OTHER = 5, ZO_PROF_CATEGORIES = 6 };
+       ZO_PROF_UPDATE = 4, ZO_PROF_OTHER = 5, ZO_PROF_FUSED = 6 /* one launch of the fused small-M kernel */,
+       ZO_PROF_CATEGORIES = 7 };
 zo_status zo_profile_begin(zo_ctx* ctx);
 zo_status zo_profile_end(zo_ctx* ctx, float* ms_host, int32_t* launches_host);
 
@@ -212,6 +215,20 @@ zo_status zo_linear_fakequant(const void* X_dev, const float* W_dev, const float
                               int32_t a_bits, int32_t a_sym, int32_t dtype,
                               uint64_t seed, int32_t tensor_id, float eps_signed,
                               void* scratch_dev, void* hip_stream);
+
+/* The same layer for both branches of Eq. 2 at once and a small token count (1 <= M <= 128), fused: one pass
+ * over the fp32 master builds the tiles of Q(W + eps u) and Q(W - eps u) in registers, in matrix-core operand
+ * layout, and multiplies them with the branches' (already quantized) inputs; neither set of weights is ever
+ * written anywhere.  Yp = Xp Q(W + eps u)^T + bias, Ym = Xm Q(W - eps u)^T + bias.
+ *   Xp, Xm  dev bf16 [M][K] (may be the same buffer); Ym = NULL: one branch only, at W + eps u (eps signed)
+ *   W       dev fp32 [N][K]; bias dev fp32 [N] or NULL; Yp, Ym dev [M][N], fp32 if out_f32 else bf16
+ *   w_bits 0..8 (0: perturbed, not quantized); w_group in {8, 16, 32, 64, 128} dividing K; N a multiple
+ *   of 16, K of 32; otherwise ZO_ESHAPE.  Same arithmetic per weight as zo_debug_quant_weight; only the
+ *   order of the fp32 accumulation differs from zo_linear_fakequant. */
+zo_status zo_linear_fakequant_fused(const void* Xp_dev, const void* Xm_dev, const float* W_dev, const float* bias_dev,
+                                    void* Yp_dev, void* Ym_dev, int32_t M, int32_t N, int32_t K, int32_t w_bits,
+                                    int32_t w_group, uint64_t seed, int32_t tensor_id, float eps, int32_t out_f32,
+                                    void* hip_stream);
 
 /* ---- frozen, pre-quantized weights (Section "Lightweight ZeroQAT for memory reduction"): most
  * parameters are frozen and stored quantized, only the query and value projections stay in full

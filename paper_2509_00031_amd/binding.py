@@ -24,15 +24,14 @@ EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "
            "zo_debug_quant_weight", "zo_debug_quant_act", "zo_linear_scratch_bytes", "zo_linear_fakequant",
            "zo_gemm_nt", "zo_debug_buffer", "zo_profile_begin", "zo_profile_end", "zo_attention_causal",
            "zo_attention_scratch_bytes", "zo_pack_weight_int4", "zo_attach_frozen_int4", "zo_linear_frozen_int4", "zo_gemm_nt_fused", "zo_init_learned_params", "zo_step_groups", "zo_update_groups",
-           "zo_debug_quant_weight_learned", "zo_debug_smooth_bias"]
-PROF_NAMES = ["gemm", "weight_quant", "act_quant", "attention", "update", "other"]
+           "zo_debug_quant_weight_learned", "zo_debug_smooth_bias", "zo_linear_fakequant_fused"]
+PROF_NAMES = ["gemm", "weight_quant", "act_quant", "attention", "update", "other", "fused_linear"]
 
 
 class zo_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("arch", "n_layers", "d_model", "n_heads", "d_ffn", "vocab", "max_seq",
                                          "w_bits", "w_group", "a_bits", "a_sym", "act_dtype", "lightweight",
-                                         "learn_clip", "learn_smooth")] + \
-               [("reserved", C.c_int32 * 1)]
+                                         "learn_clip", "learn_smooth", "no_fused")]
 
 
 class zo_tensor(C.Structure):
@@ -67,6 +66,7 @@ _lib.zo_debug_quant_act.argtypes = [_vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp,
 _lib.zo_linear_scratch_bytes.argtypes = [_i32, _i32, _i32, _i32]
 _lib.zo_linear_scratch_bytes.restype = _sz
 _lib.zo_linear_fakequant.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _u64, _i32, _f32, _vp, _vp]
+_lib.zo_linear_fakequant_fused.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _u64, _i32, _f32, _i32, _vp]
 _lib.zo_gemm_nt.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp]
 _lib.zo_debug_buffer.argtypes = [_vp, _i32, _i32, C.POINTER(_vp), C.POINTER(_sz)]
 _lib.zo_attention_causal.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i64, _i32, _vp, _vp]
@@ -104,9 +104,9 @@ def _tdtype(dtype):
 
 
 def make_config(arch, n_layers=0, d_model=0, n_heads=1, d_ffn=0, vocab=0, max_seq=0, w_bits=4, w_group=64,
-                a_bits=16, a_sym=0, act_dtype=ACT_FP32, lightweight=0, learn_clip=0, learn_smooth=0):
+                a_bits=16, a_sym=0, act_dtype=ACT_FP32, lightweight=0, learn_clip=0, learn_smooth=0, no_fused=0):
     return zo_config(arch, n_layers, d_model, n_heads, d_ffn, vocab, max_seq, w_bits, w_group, a_bits, a_sym,
-                     act_dtype, lightweight, learn_clip, learn_smooth)
+                     act_dtype, lightweight, learn_clip, learn_smooth, no_fused)
 
 
 def zo_num_params(cfg):
@@ -294,6 +294,18 @@ def zo_linear_fakequant(X, W, bias, w_bits, w_group, a_bits, a_sym=0, seed=0, te
                                     a_bits, a_sym, dtype, seed, tensor_id, eps_signed, scratch.data_ptr(), _stream()),
            "zo_linear_fakequant")
     return Y
+
+
+def zo_linear_fakequant_fused(Xp, Xm, W, bias, w_bits, w_group, seed=0, tensor_id=0, eps=0.0, out_f32=False):
+    """Both branches (Xm given) or one (Xm None, eps signed); returns (Yp, Ym) with Ym None for one branch."""
+    M, K = Xp.shape
+    N = W.shape[0]
+    odt = torch.float32 if out_f32 else torch.bfloat16
+    Y = torch.empty((2 if Xm is not None else 1, M, N), dtype=odt, device=Xp.device)
+    _check(_lib.zo_linear_fakequant_fused(Xp.data_ptr(), _ptr(Xm), W.data_ptr(), _ptr(bias), Y[0].data_ptr(),
+                                          Y[1].data_ptr() if Xm is not None else None, M, N, K, w_bits, w_group, seed, tensor_id,
+                                          eps, int(out_f32), _stream()), "zo_linear_fakequant_fused")
+    return Y[0], (Y[1] if Xm is not None else None)
 
 
 def zo_pack_weight_int4(W, group):

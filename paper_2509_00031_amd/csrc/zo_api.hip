@@ -117,6 +117,7 @@ zo_status check_config(const zo_config& c)
     if ((c.learn_clip || c.learn_smooth) && c.w_bits == 0) return ZO_EINVAL;
     if (c.learn_smooth && (!c.learn_clip || c.a_bits >= 16)) return ZO_EUNSUPPORTED;
     if ((c.learn_clip || c.learn_smooth) && c.lightweight) return ZO_EUNSUPPORTED;
+    if (c.no_fused < 0 || c.no_fused > 1) return ZO_EINVAL;
     if (c.arch != ZO_ARCH_LINEAR) {
         if (c.d_model % c.n_heads) return ZO_ESHAPE;
         const int dh = c.d_model / c.n_heads;
@@ -214,6 +215,7 @@ struct zo_ctx {
     // frozen, pre-quantized storage of a non-trainable linear (lightweight variant); codes == NULL: none
     struct frozen_int4 { const void* codes; const void* step; const int16_t* zp; int group; };
     std::vector<frozen_int4> frozen;
+    int n_packed = 0;     // tensors with packed storage attached
     char* ws;
     size_t ws_bytes;
     int max_B, max_S;
@@ -280,6 +282,19 @@ struct fwd {
     uint64_t seed;
     int M, S;
     bool sm_on = false;   // the activation being quantized next is smoothed (set by smooth_prepare)
+    // small-M route: the tensors of the next GEMM whose tiles are built inside the fused kernel instead of
+    // being written to the operand buffers (all of them or none: eligibility depends on the shared shape only)
+    struct pend { int t; int64_t row0; bool quantize; };
+    pend pending[4];
+    int npend = 0;
+    bool fused_ok(int t, bool quantize) const
+    {
+        const zo_config& cfg = c->cfg;
+        if (cfg.no_fused || cfg.act_dtype != ZO_ACT_BF16 || cfg.learn_clip || c->n_packed > 0) return false;
+        const param_desc& p = c->desc[t];
+        const int64_t g = cfg.w_group > 0 ? cfg.w_group : p.cols;
+        return zo_fused_supported(M, (int)p.rows, (int)p.cols, quantize ? cfg.w_bits : 0, (int)g);
+    }
     template <typename T = char> T* at(size_t off) const { return (T*)(c->ws + off); }
     int dt() const { return c->cfg.act_dtype; }
     float eps_of(int tensor) const { return trainable(c, tensor) ? eps : 0.0f; }
@@ -290,6 +305,10 @@ struct fwd {
     zo_status weights(int t, int64_t row0, bool quantize, bool shared = false)
     {
         const param_desc& p = c->desc[t];
+        if (npend < 4 && fused_ok(t, quantize)) {
+            pending[npend++] = pend{t, row0, quantize};
+            return ZO_OK;
+        }
         const size_t ts = zo_tsize(dt());
         void* op = at(c->L.what[0]) + (size_t)row0 * p.cols * ts;
         void* om = nb == 2 ? at(c->L.what[1]) + (size_t)row0 * p.cols * ts : nullptr;
@@ -402,6 +421,36 @@ struct fwd {
     zo_status gemm(size_t layout::per_branch::*in, size_t layout::per_branch::*out, int N, int K, bool bias, bool relu,
                    bool residual, bool out_f32 = false, bool w_shared = false)
     {
+        if (npend > 0) {
+            prof_scope ps(c, ZO_PROF_FUSED);
+            const int64_t ts_ = (int64_t)zo_tsize(dt());
+            for (int i = 0; i < npend; ++i) {
+                const pend& pe = pending[i];
+                const param_desc& p = c->desc[pe.t];
+                zo_fused_args f{};
+                f.X = at(c->L.br[0].*in);
+                f.W = (const float*)c->params[pe.t].ptr;
+                f.Y = at(c->L.br[0].*out) + (size_t)pe.row0 * (out_f32 ? 4 : ts_);
+                f.bias = bias ? vec(0, 2) + pe.row0 : nullptr;
+                f.residual = residual ? f.Y : nullptr;
+                f.M = M; f.N = (int)p.rows; f.K = K; f.nb = nb;
+                f.ldY = N;
+                if (nb == 2) {
+                    f.strideX = (int64_t)(c->L.br[1].*in - c->L.br[0].*in) / ts_;
+                    f.strideY = (int64_t)(c->L.br[1].*out - c->L.br[0].*out) / (out_f32 ? 4 : ts_);
+                    f.strideBias = (int64_t)(c->L.vec[1] - c->L.vec[0]) / 4;
+                    f.strideRes = f.strideY;
+                }
+                f.bits = pe.quantize ? c->cfg.w_bits : 0;
+                f.group = c->cfg.w_group;
+                f.eps = eps_of(pe.t);
+                f.relu = relu;
+                f.out_f32 = out_f32;
+                ZO_HIP(c, zo_launch_fq_gemm_fused(f, seed, pe.t, c->st));
+            }
+            npend = 0;
+            return ZO_OK;
+        }
         zo_gemm_args a{};
         a.X = at(c->L.br[0].*in);
         a.W = at(c->L.what[0]);
@@ -465,7 +514,16 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
             a.strideW = (int64_t)(c->L.what[1] - c->L.what[0]) / (int64_t)ts;
             a.strideY = (int64_t)(c->L.br[1].logits - c->L.br[0].logits) / (int64_t)ts;
         }
-        {
+        if (F.npend > 0) {                               // small M: tiles of Q(W +- eps u) built inside the GEMM kernel
+            zo_fused_args fa{};
+            fa.X = a.X; fa.W = (const float*)c->params[0].ptr; fa.Y = a.Y; fa.bias = a.bias;
+            fa.M = M; fa.N = N; fa.K = K; fa.nb = nb; fa.ldY = N;
+            fa.strideX = a.strideX; fa.strideY = a.strideY; fa.strideBias = a.strideBias;
+            fa.bits = cfg.w_bits; fa.group = cfg.w_group; fa.eps = F.eps_of(0);
+            F.npend = 0;
+            prof_scope ps(c, ZO_PROF_FUSED);
+            ZO_HIP(c, zo_launch_fq_gemm_fused(fa, seed, 0, c->st));
+        } else {
             prof_scope ps(c, ZO_PROF_GEMM);
             ZO_HIP(c, zo_launch_gemm(a, c->st));
         }
@@ -691,6 +749,7 @@ zo_status zo_attach_frozen_int4(zo_ctx* ctx, int32_t index, const void* codes, c
     if (!codes || !step_f16 || !zp) return fail(ctx, ZO_EINVAL, "NULL packed storage");
     if (!zo_int4_group_supported((int)ctx->desc[index].cols, group)) return fail(ctx, ZO_ESHAPE, "group must be a power of two in 8..512 dividing the in-features");
     if (!aligned16(codes) || ((uintptr_t)step_f16 & 1) || ((uintptr_t)zp & 1)) return fail(ctx, ZO_EALIGN, "packed storage misaligned");
+    if (!ctx->frozen[index].codes) ctx->n_packed += 1;
     ctx->frozen[index] = zo_ctx::frozen_int4{codes, step_f16, zp, group};
     return ZO_OK;
 }
@@ -955,6 +1014,28 @@ zo_status zo_linear_fakequant(const void* X_dev, const float* W_dev, const float
     a.X = xin; a.W = what; a.Y = Y_dev; a.bias = bias_dev;
     a.M = M; a.N = N; a.K = K; a.batch = 1; a.dtype = dtype;
     return zo_launch_gemm(a, st) == hipSuccess ? ZO_OK : ZO_EHIP;
+}
+
+zo_status zo_linear_fakequant_fused(const void* Xp_dev, const void* Xm_dev, const float* W_dev, const float* bias_dev,
+                                    void* Yp_dev, void* Ym_dev, int32_t M, int32_t N, int32_t K, int32_t w_bits,
+                                    int32_t w_group, uint64_t seed, int32_t tensor_id, float eps, int32_t out_f32,
+                                    void* hip_stream)
+{
+    if (!Xp_dev || !W_dev || !Yp_dev || M <= 0 || N <= 0 || K <= 0) return ZO_EINVAL;
+    if (Ym_dev && !Xm_dev) return ZO_EINVAL;
+    if (w_bits < 0 || w_bits > 8 || w_group < 0) return ZO_EINVAL;
+    if (!zo_fused_supported(M, N, K, w_bits, w_group)) return ZO_ESHAPE;
+    if (!aligned16(Xp_dev) || !aligned16(Xm_dev) || !aligned16(W_dev) || !aligned16(bias_dev) || !aligned16(Yp_dev) || !aligned16(Ym_dev))
+        return ZO_EALIGN;
+    zo_fused_args f{};
+    f.X = Xp_dev; f.W = W_dev; f.Y = Yp_dev; f.bias = bias_dev;
+    f.M = M; f.N = N; f.K = K; f.nb = Ym_dev ? 2 : 1; f.ldY = N;
+    if (Ym_dev) {
+        f.strideX = ((const char*)Xm_dev - (const char*)Xp_dev) / 2;
+        f.strideY = ((const char*)Ym_dev - (const char*)Yp_dev) / (out_f32 ? 4 : 2);
+    }
+    f.bits = w_bits; f.group = w_group; f.eps = eps; f.out_f32 = out_f32 ? 1 : 0;
+    return zo_launch_fq_gemm_fused(f, seed, tensor_id, (hipStream_t)hip_stream) == hipSuccess ? ZO_OK : ZO_EHIP;
 }
 
 zo_status zo_pack_weight_int4(const float* W_dev, int32_t N, int32_t K, int32_t group,

@@ -69,6 +69,24 @@ struct zo_gemm_args {
 };
 hipError_t zo_launch_gemm(const zo_gemm_args& a, hipStream_t st);
 
+// ---- fused fake-quantized linear for small M: Y[b] = X[b] * Q(W +- eps u)^T, tiles built in registers ----
+#define ZO_FUSED_MAX_M 128
+struct zo_fused_args {
+    const void* X;              // bf16 [nb][M][K] (strideX elements between the branches, may be 0)
+    const float* W;             // fp32 master [N][K] of ONE tensor (element index = n*K + k in its stream)
+    void* Y;                    // bf16 or fp32 [M][ldY], already offset to the tensor's first output column
+    const float* bias;          // fp32 [N] (per branch: strideBias) or NULL
+    const void* residual;       // bf16, same indexing as Y, or NULL
+    int32_t M, N, K, nb;        // nb = 1: eps is signed; nb = 2: branch 0 at +eps, branch 1 at -eps
+    int64_t strideX, strideY, strideBias, strideRes, ldY;
+    int32_t bits, group;        // bits = 0: perturbed, not quantized; group in {8, 16, 32, 64, 128}
+    float eps;
+    int32_t relu, out_f32;
+};
+// M in 1..ZO_FUSED_MAX_M, N a multiple of 16, K a multiple of 32 and of the group
+bool zo_fused_supported(int32_t M, int32_t N, int32_t K, int32_t bits, int32_t group);
+hipError_t zo_launch_fq_gemm_fused(const zo_fused_args& a, uint64_t seed, int32_t tid, hipStream_t st);
+
 // ---- the rest of the decoder forward -----------------------------------------------------------
 // x[t] = rt(fma(eps, u(tok row), tok_emb[id]) (+ fma(eps, u(pos row), pos_emb[t % S])))
 hipError_t zo_launch_embed(const int32_t* ids, const float* tok_emb, const float* pos_emb, void* out,
