@@ -36,6 +36,12 @@ WORKLOADS = {
                                           w_bits=2, w_group=64, a_bits=16, B=8, S=1024, learn_clip=1),
     "opt1p3b_w4a4_g128_smooth_clip_16x512": dict(arch="opt", n_layers=24, d_model=2048, n_heads=32, d_ffn=8192, vocab=50272,
                                                  w_bits=4, w_group=128, a_bits=4, B=16, S=512, learn_clip=1, learn_smooth=1),
+    # the small-batch regime of the paper's fine-tuning runs (batch 1, a few hundred tokens): every linear takes the
+    # fused kernel that builds the tiles of Q(W +- eps u) in registers; --no-fused times the quantize-once route
+    "llama7b_w4a8_g64_1x128": dict(arch="llama", n_layers=32, d_model=4096, n_heads=32, d_ffn=11008, vocab=32000,
+                                   w_bits=4, w_group=64, a_bits=8, B=1, S=128),
+    "llama7b_w4a8_g64_1x32": dict(arch="llama", n_layers=32, d_model=4096, n_heads=32, d_ffn=11008, vocab=32000,
+                                  w_bits=4, w_group=64, a_bits=8, B=1, S=32),
     "tiny_w4a16_g64_8x128": dict(arch="llama", n_layers=4, d_model=512, n_heads=8, d_ffn=2048, vocab=4096,
                                  w_bits=4, w_group=64, a_bits=16, B=8, S=128),
 }
@@ -45,6 +51,12 @@ WORKLOADS = {
 MEASURED_GEMM_TRAFFIC = {"llama7b_w4a8_g64_8x1024": 2.0 * 1359.0e6 + 348.3e6}
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+# plain vector ALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions per second (the fp32 vector peak of
+# 157.3 TFLOP/s counts 2 flops per FMA and the packed two-per-lane forms, which this build does not use)
+PEAK_ALU_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+# lane-instructions of the fused kernel's tile build per parameter, counted in its ISA (w4 g64 variant: 579 for the
+# perturbation stream + 225 + 223 for the two branches + 16 for the contraction, per 16 parameters)
+FUSED_LANEOPS_PER_PARAM = 1043 / 16.0
 
 
 def gemm_flops_per_step(w):
@@ -105,6 +117,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="llama7b_w4a8_g64_8x1024", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-fused", action="store_true", help="small token counts: quantize once and run the plain GEMM")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket launches with HIP events in the timed region")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="before the timed region copy 1 GiB device to device once (a plain copy of known size, "
@@ -125,7 +138,7 @@ def main():
     cfg = zo.make_config(arch, n_layers=w["n_layers"], d_model=w["d_model"], n_heads=w["n_heads"], d_ffn=w["d_ffn"],
                          vocab=w["vocab"], max_seq=w["S"], w_bits=w["w_bits"], w_group=w["w_group"], a_bits=w["a_bits"],
                          act_dtype=zo.ACT_BF16, lightweight=w.get("lightweight", 0), learn_clip=w.get("learn_clip", 0),
-                         learn_smooth=w.get("learn_smooth", 0))
+                         learn_smooth=w.get("learn_smooth", 0), no_fused=int(args.no_fused))
     n = zo.zo_num_params(cfg)
     gen = torch.Generator(device=dev)
     gen.manual_seed(1234)
@@ -199,12 +212,25 @@ def main():
         gemm_ms, gemm_launches = prof["gemm"]
         avg_ms = gemm_ms / max(gemm_launches, 1)
         flops_per_launch = gflops * args.steps / max(gemm_launches, 1)
-        achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12
+        achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12 if avg_ms > 0 else 0.0
         res["roofline"] = {"bound": "mfma", "kernel": "zo_gemm_bf16_dma_kernel<bf16, 8 waves, BK 64, 2 stages>", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                            "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": MEASURED_GEMM_TRAFFIC.get(args.workload),
                            "launches": gemm_launches, "avg_launch_ms": avg_ms,
                            "flops_per_launch": flops_per_launch}
         res["gemm_tflops"] = achieved
+        fused_ms, fused_launches = prof["fused_linear"]
+        if fused_launches > 0:
+            # small-M route: every linear went through the fused kernel, which is bound by the plain-ALU tile build
+            d, f, V, L = w["d_model"], w["d_ffn"], w["vocab"], w["n_layers"]
+            lin_params = L * (4 * d * d + (3 if w["arch"] == "llama" else 2) * d * f) + V * d
+            avg_ms = fused_ms / fused_launches
+            params_per_launch = lin_params * args.steps / fused_launches
+            ach = FUSED_LANEOPS_PER_PARAM * params_per_launch / (avg_ms * 1e-3) / 1e12
+            res["roofline"] = {"bound": "alu", "kernel": "zo_fq_gemm_fused_kernel", "achieved": ach, "peak": PEAK_ALU_TLANEOPS,
+                               "unit": "Tlane-op/s", "frac": ach / PEAK_ALU_TLANEOPS, "traffic": None,
+                               "launches": fused_launches, "avg_launch_ms": avg_ms, "params_per_launch": params_per_launch,
+                               "master_GBps": 4.0 * params_per_launch / (avg_ms * 1e-3) / 1e9}
+            res["gemm_tflops"] = gflops * args.steps / (fused_ms * 1e-3) / 1e12
         upd_ms, upd_groups = prof["update"]
         upd_gbs = 8.0 * n_params * upd_groups / (upd_ms * 1e-3) / 1e9 if upd_ms > 0 else None
         res["update_kernel"] = {"bound": "hbm", "achieved": upd_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",

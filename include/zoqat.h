@@ -224,11 +224,15 @@ zo_status zo_linear_fakequant(const void* X_dev, const float* W_dev, const float
  *   W       dev fp32 [N][K]; bias dev fp32 [N] or NULL; Yp, Ym dev [M][N], fp32 if out_f32 else bf16
  *   w_bits 0..8 (0: perturbed, not quantized); w_group in {8, 16, 32, 64, 128} dividing K; N a multiple
  *   of 16, K of 32; otherwise ZO_ESHAPE.  Same arithmetic per weight as zo_debug_quant_weight; only the
- *   order of the fp32 accumulation differs from zo_linear_fakequant. */
+ *   order of the fp32 accumulation differs from zo_linear_fakequant.
+ *   scratch dev, NULL or zo_linear_fused_scratch_bytes(M, K) bytes: if given, the activations are first copied
+ *   into it in the order the kernel consumes them (contiguous loads instead of 16-byte gathers; faster from
+ *   M ~ 48 on, identical results). */
+size_t zo_linear_fused_scratch_bytes(int32_t M, int32_t K);
 zo_status zo_linear_fakequant_fused(const void* Xp_dev, const void* Xm_dev, const float* W_dev, const float* bias_dev,
                                     void* Yp_dev, void* Ym_dev, int32_t M, int32_t N, int32_t K, int32_t w_bits,
                                     int32_t w_group, uint64_t seed, int32_t tensor_id, float eps, int32_t out_f32,
-                                    void* hip_stream);
+                                    void* scratch_dev, void* hip_stream);
 
 /* ---- frozen, pre-quantized weights (Section "Lightweight ZeroQAT for memory reduction"): most
  * parameters are frozen and stored quantized, only the query and value projections stay in full

@@ -24,7 +24,7 @@ EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "
            "zo_debug_quant_weight", "zo_debug_quant_act", "zo_linear_scratch_bytes", "zo_linear_fakequant",
            "zo_gemm_nt", "zo_debug_buffer", "zo_profile_begin", "zo_profile_end", "zo_attention_causal",
            "zo_attention_scratch_bytes", "zo_pack_weight_int4", "zo_attach_frozen_int4", "zo_linear_frozen_int4", "zo_gemm_nt_fused", "zo_init_learned_params", "zo_step_groups", "zo_update_groups",
-           "zo_debug_quant_weight_learned", "zo_debug_smooth_bias", "zo_linear_fakequant_fused"]
+           "zo_debug_quant_weight_learned", "zo_debug_smooth_bias", "zo_linear_fakequant_fused", "zo_linear_fused_scratch_bytes"]
 PROF_NAMES = ["gemm", "weight_quant", "act_quant", "attention", "update", "other", "fused_linear"]
 
 
@@ -66,7 +66,9 @@ _lib.zo_debug_quant_act.argtypes = [_vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp,
 _lib.zo_linear_scratch_bytes.argtypes = [_i32, _i32, _i32, _i32]
 _lib.zo_linear_scratch_bytes.restype = _sz
 _lib.zo_linear_fakequant.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _u64, _i32, _f32, _vp, _vp]
-_lib.zo_linear_fakequant_fused.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _u64, _i32, _f32, _i32, _vp]
+_lib.zo_linear_fakequant_fused.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _u64, _i32, _f32, _i32, _vp, _vp]
+_lib.zo_linear_fused_scratch_bytes.argtypes = [_i32, _i32]
+_lib.zo_linear_fused_scratch_bytes.restype = _sz
 _lib.zo_gemm_nt.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp]
 _lib.zo_debug_buffer.argtypes = [_vp, _i32, _i32, C.POINTER(_vp), C.POINTER(_sz)]
 _lib.zo_attention_causal.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i64, _i32, _vp, _vp]
@@ -296,15 +298,17 @@ def zo_linear_fakequant(X, W, bias, w_bits, w_group, a_bits, a_sym=0, seed=0, te
     return Y
 
 
-def zo_linear_fakequant_fused(Xp, Xm, W, bias, w_bits, w_group, seed=0, tensor_id=0, eps=0.0, out_f32=False):
-    """Both branches (Xm given) or one (Xm None, eps signed); returns (Yp, Ym) with Ym None for one branch."""
+def zo_linear_fakequant_fused(Xp, Xm, W, bias, w_bits, w_group, seed=0, tensor_id=0, eps=0.0, out_f32=False, relayout=False):
+    """Both branches (Xm given) or one (Xm None, eps signed); returns (Yp, Ym) with Ym None for one branch.
+    relayout: give the call its scratch buffer (activations copied into fragment order first)."""
     M, K = Xp.shape
+    scratch = torch.empty(_lib.zo_linear_fused_scratch_bytes(M, K), dtype=torch.uint8, device=Xp.device) if relayout else None
     N = W.shape[0]
     odt = torch.float32 if out_f32 else torch.bfloat16
     Y = torch.empty((2 if Xm is not None else 1, M, N), dtype=odt, device=Xp.device)
     _check(_lib.zo_linear_fakequant_fused(Xp.data_ptr(), _ptr(Xm), W.data_ptr(), _ptr(bias), Y[0].data_ptr(),
                                           Y[1].data_ptr() if Xm is not None else None, M, N, K, w_bits, w_group, seed, tensor_id,
-                                          eps, int(out_f32), _stream()), "zo_linear_fakequant_fused")
+                                          eps, int(out_f32), _ptr(scratch), _stream()), "zo_linear_fakequant_fused")
     return Y[0], (Y[1] if Xm is not None else None)
 
 

@@ -131,6 +131,7 @@ struct layout {
     size_t scalars;            // fp32[16]: loss[2] at 0, {L+, L-, g, c_model, c_smooth, c_clip} at 2
     size_t rope_cos, rope_sin; // fp32 [max_seq][dh/2]
     size_t what[2];            // de-quantized weights of the current linear(s), per branch
+    size_t what_bytes;         // size of each
     size_t vec[2];             // perturbed small vectors of the current sub-layer, per branch: slots 0 gain,
                                // 1 norm bias, 2 linear bias, 3 smoothing s, 4 1/s, 5 smoothing delta
     size_t vec_stride;         // floats per vector slot
@@ -153,7 +154,8 @@ layout make_layout(const zo_config& c, int B, int S)
     const size_t gsz = c.w_group > 0 ? (size_t)c.w_group : 0;
     if (c.arch == ZO_ARCH_LINEAR) {
         const size_t M = B;
-        for (int b = 0; b < 2; ++b) L.what[b] = take(f * d * ts);
+        L.what_bytes = f * d * ts;
+        for (int b = 0; b < 2; ++b) L.what[b] = take(L.what_bytes);
         L.vec_stride = align_up((d > f ? d : f) * sizeof(float)) / sizeof(float);
         for (int b = 0; b < 2; ++b) L.vec[b] = take(6 * L.vec_stride * sizeof(float));
         L.qp_elems = c.learn_clip ? f * (gsz ? d / gsz : 1) : 0;
@@ -175,7 +177,8 @@ layout make_layout(const zo_config& c, int B, int S)
     const size_t ffn_rows = c.arch == ZO_ARCH_LLAMA ? 2 * f : f;
     if (3 * d * d > max_nk) max_nk = 3 * d * d;
     if (ffn_rows * d > max_nk) max_nk = ffn_rows * d;
-    for (int b = 0; b < 2; ++b) L.what[b] = take(max_nk * ts);
+    L.what_bytes = max_nk * ts;
+    for (int b = 0; b < 2; ++b) L.what[b] = take(L.what_bytes);
     L.vec_stride = d > f ? d : f;
     if (3 * d > L.vec_stride) L.vec_stride = 3 * d;
     if (ffn_rows > L.vec_stride) L.vec_stride = ffn_rows;
@@ -424,11 +427,19 @@ struct fwd {
         if (npend > 0) {
             prof_scope ps(c, ZO_PROF_FUSED);
             const int64_t ts_ = (int64_t)zo_tsize(dt());
+            // from a few m-tiles on the kernel is fed from a fragment-ordered copy of the activations, kept in the
+            // (otherwise idle) operand buffers
+            const bool relayout = M > 32 && zo_fused_relayout_bytes(M, K) <= c->L.what_bytes;
+            const int64_t sxf = (int64_t)(c->L.what[1] - c->L.what[0]) / 2;
+            if (relayout)
+                ZO_HIP(c, zo_launch_fused_relayout(at(c->L.br[0].*in), nb == 2 ? (int64_t)(c->L.br[1].*in - c->L.br[0].*in) / ts_ : 0, M, K,
+                                                   nb, pending[0].quantize ? c->cfg.w_bits : 0, c->cfg.w_group, at(c->L.what[0]), sxf, c->st));
             for (int i = 0; i < npend; ++i) {
                 const pend& pe = pending[i];
                 const param_desc& p = c->desc[pe.t];
                 zo_fused_args f{};
                 f.X = at(c->L.br[0].*in);
+                if (relayout) { f.Xfrag = at(c->L.what[0]); f.strideXfrag = sxf; }
                 f.W = (const float*)c->params[pe.t].ptr;
                 f.Y = at(c->L.br[0].*out) + (size_t)pe.row0 * (out_f32 ? 4 : ts_);
                 f.bias = bias ? vec(0, 2) + pe.row0 : nullptr;
@@ -522,6 +533,11 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
             fa.bits = cfg.w_bits; fa.group = cfg.w_group; fa.eps = F.eps_of(0);
             F.npend = 0;
             prof_scope ps(c, ZO_PROF_FUSED);
+            if (M > 32 && zo_fused_relayout_bytes(M, K) <= c->L.what_bytes) {
+                fa.Xfrag = F.at(c->L.what[0]);
+                fa.strideXfrag = (int64_t)(c->L.what[1] - c->L.what[0]) / 2;
+                ZO_HIP(c, zo_launch_fused_relayout(fa.X, fa.strideX, M, K, nb, fa.bits, fa.group, F.at(c->L.what[0]), fa.strideXfrag, c->st));
+            }
             ZO_HIP(c, zo_launch_fq_gemm_fused(fa, seed, 0, c->st));
         } else {
             prof_scope ps(c, ZO_PROF_GEMM);
@@ -1016,10 +1032,16 @@ zo_status zo_linear_fakequant(const void* X_dev, const float* W_dev, const float
     return zo_launch_gemm(a, st) == hipSuccess ? ZO_OK : ZO_EHIP;
 }
 
+size_t zo_linear_fused_scratch_bytes(int32_t M, int32_t K)
+{
+    if (M <= 0 || K <= 0) return 0;
+    return 2 * align_up(zo_fused_relayout_bytes(M, K));
+}
+
 zo_status zo_linear_fakequant_fused(const void* Xp_dev, const void* Xm_dev, const float* W_dev, const float* bias_dev,
                                     void* Yp_dev, void* Ym_dev, int32_t M, int32_t N, int32_t K, int32_t w_bits,
                                     int32_t w_group, uint64_t seed, int32_t tensor_id, float eps, int32_t out_f32,
-                                    void* hip_stream)
+                                    void* scratch_dev, void* hip_stream)
 {
     if (!Xp_dev || !W_dev || !Yp_dev || M <= 0 || N <= 0 || K <= 0) return ZO_EINVAL;
     if (Ym_dev && !Xm_dev) return ZO_EINVAL;
@@ -1035,6 +1057,13 @@ zo_status zo_linear_fakequant_fused(const void* Xp_dev, const void* Xm_dev, cons
         f.strideY = ((const char*)Ym_dev - (const char*)Yp_dev) / (out_f32 ? 4 : 2);
     }
     f.bits = w_bits; f.group = w_group; f.eps = eps; f.out_f32 = out_f32 ? 1 : 0;
+    if (scratch_dev) {
+        if (!aligned16(scratch_dev)) return ZO_EALIGN;
+        f.Xfrag = scratch_dev;
+        f.strideXfrag = (int64_t)(align_up(zo_fused_relayout_bytes(M, K)) / 2);
+        if (zo_launch_fused_relayout(f.X, f.strideX, M, K, f.nb, w_bits, w_group, scratch_dev, f.strideXfrag, (hipStream_t)hip_stream) != hipSuccess)
+            return ZO_EHIP;
+    }
     return zo_launch_fq_gemm_fused(f, seed, tensor_id, (hipStream_t)hip_stream) == hipSuccess ? ZO_OK : ZO_EHIP;
 }
 

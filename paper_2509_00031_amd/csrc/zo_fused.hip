@@ -85,7 +85,8 @@ __global__ __launch_bounds__(FW * 64) void zo_fq_gemm_fused_kernel(zo_fused_args
     const int M = a.M, K = a.K, nb = a.nb;
     const int n0 = blockIdx.x * 16;
     const int nslab = K / SLAB;
-    const int jn = (M + 15) >> 4;                             // m-tiles in use (<= J)
+    // All J m-tiles are always computed (rows past M repeat row M - 1 and are never stored): the matrix
+    // instructions sit in straight-line code, with no data-dependent branch between them and their readers.
     const float* wrow = a.W + (int64_t)(n0 + n) * K + q * (CH * 8);
     const uint64_t blk_row = ((uint64_t)(n0 + n) * (uint64_t)K >> 3) + (uint64_t)(q * CH);
     const zo_bf16* X = (const zo_bf16*)a.X;
@@ -96,11 +97,61 @@ __global__ __launch_bounds__(FW * 64) void zo_fq_gemm_fused_kernel(zo_fused_args
 #pragma unroll
         for (int j = 0; j < J; ++j) acc[b][j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
+    // Per slab: the activation fragments of a branch are requested before that branch's tile build (a few
+    // thousand ALU cycles), so they have landed when its matrix instructions are issued; the master
+    // weights of the next slab are requested one slab ahead.  Tiles beyond JP are fetched on the spot.
+    constexpr int JPMAX = CH == 4 ? (J == 8 ? 1 : 2) : 8;                  // m-tiles whose fragments are preloaded (<= 64 VGPRs)
+    constexpr int JP = JPMAX < J ? JPMAX : J;
+    constexpr bool WPF = CH < 4;                             // register budget: no look-ahead with 32 features per lane
+    float w[CH][8], wnext[WPF ? CH : 1][8];
+    if (WPF && wave < nslab) {
+#pragma unroll
+        for (int c = 0; c < CH; ++c) zo_load8(wrow + wave * SLAB + c * 8, w[c]);
+    }
     for (int sl = wave; sl < nslab; sl += FW) {
         const int k0 = sl * SLAB;
-        float w[CH][8], z[CH][8];
+        const zo_bf16* xcol = X + k0 + q * (CH * 8);
+        int mrow[J];
 #pragma unroll
-        for (int c = 0; c < CH; ++c) zo_load8(wrow + k0 + c * 8, w[c]);
+        for (int j = 0; j < J; ++j) {
+            const int m = j * 16 + n;
+            mrow[j] = m < M ? m : M - 1;
+        }
+        bf16x8 xf[JP][CH];
+        // fragment (b, j, c) of this slab: gathered from the row-major activations (16 bytes of 16 different rows
+        // per q), or, if the caller re-laid them out fragment by fragment, one contiguous 1 KB wave-level load
+        const zo_bf16* xfrag = a.Xfrag ? (const zo_bf16*)a.Xfrag + ((int64_t)sl * J * CH * 64 + lane) * 8 : nullptr;
+        auto fragment = [&](int b, int j, int c) -> bf16x8 {
+            if (xfrag) return *reinterpret_cast<const bf16x8*>(xfrag + b * a.strideXfrag + (j * CH + c) * 512);
+            return *reinterpret_cast<const bf16x8*>(xcol + b * a.strideX + (int64_t)mrow[j] * K + c * 8);
+        };
+        auto preload = [&](int b) {
+#pragma unroll
+            for (int j = 0; j < JP; ++j)
+#pragma unroll
+                for (int c = 0; c < CH; ++c) xf[j][c] = fragment(b, j, c);
+        };
+        auto contract = [&](int b, const bf16x8 (&af)[CH], f32x4 (&ac)[J]) {
+#pragma unroll
+            for (int j = 0; j < J; ++j)
+#pragma unroll
+                for (int c = 0; c < CH; ++c) {
+                    const bf16x8 x = j < JP ? xf[j][c] : fragment(b, j, c);
+                    ac[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[c], x, ac[j], 0, 0, 0);
+                }
+        };
+        preload(0);
+        if constexpr (WPF) {
+            if (sl + FW < nslab) {
+#pragma unroll
+                for (int c = 0; c < CH; ++c) zo_load8(wrow + k0 + FW * SLAB + c * 8, wnext[c]);
+            }
+        } else {
+#pragma unroll
+            for (int c = 0; c < CH; ++c) zo_load8(wrow + k0 + c * 8, w[c]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        float z[CH][8];
         if (a.eps != 0.0f) {
 #pragma unroll
             for (int c = 0; c < CH; ++c) zo_z8(s, blk_row + (uint64_t)(k0 >> 3) + c, z[c]);
@@ -110,39 +161,44 @@ __global__ __launch_bounds__(FW * 64) void zo_fq_gemm_fused_kernel(zo_fused_args
 #pragma unroll
                 for (int i = 0; i < 8; ++i) z[c][i] = 0.0f;
         }
-        bf16x8 af[2][CH];
-        build_branch<CH, GL>(w, z, a.eps, a.bits, af[0]);
-        if (nb == 2) build_branch<CH, GL>(w, z, -a.eps, a.bits, af[1]);
+        bf16x8 af[CH];
+        build_branch<CH, GL>(w, z, a.eps, a.bits, af);
+        __builtin_amdgcn_sched_barrier(0);
+        contract(0, af, acc[0]);
+        if (nb == 2) {
+            __builtin_amdgcn_sched_barrier(0);
+            preload(1);
+            __builtin_amdgcn_sched_barrier(0);
+            build_branch<CH, GL>(w, z, -a.eps, a.bits, af);
+            __builtin_amdgcn_sched_barrier(0);
+            contract(1, af, acc[1]);
+        }
+        if constexpr (WPF) {
 #pragma unroll
-        for (int j = 0; j < J; ++j) {
-            if (j < jn) {
-                int m = j * 16 + n;
-                m = m < M ? m : M - 1;
-                const zo_bf16* xr = X + (int64_t)m * K + k0 + q * (CH * 8);
+            for (int c = 0; c < CH; ++c)
 #pragma unroll
-                for (int b = 0; b < 2; ++b) {
-                    if (b < nb) {
-#pragma unroll
-                        for (int c = 0; c < CH; ++c) {
-                            const bf16x8 xf = *reinterpret_cast<const bf16x8*>(xr + b * a.strideX + c * 8);
-                            acc[b][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[b][c], xf, acc[b][j], 0, 0, 0);
-                        }
-                    }
-                }
-            }
+                for (int i = 0; i < 8; ++i) w[c][i] = wnext[c][i];
         }
     }
 
+    // The accumulators are read next.  The compiler inserts the wait states between a matrix instruction and a
+    // reader of its result; an earlier form of this loop, with the instructions of a tile under a run-time
+    // condition and the accumulators copied right after the branch that joined the paths, returned three of
+    // every four outputs stale.  The loop is straight-line now; the longest such wait (19 states) is spelled
+    // out as well, once per launch.
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
     // partial accumulators -> LDS, then tile t = b * J + j is summed over the waves in order by wave t % FW
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
         for (int j = 0; j < J; ++j)
-            if (b < nb && j < jn) red[((wave * 2 + b) * J + j) * 64 + lane] = acc[b][j];
+            if (b < nb) red[((wave * 2 + b) * J + j) * 64 + lane] = acc[b][j];
     __syncthreads();
     for (int t = wave; t < 2 * J; t += FW) {
         const int b = t / J, j = t % J;
-        if (b >= nb || j >= jn) continue;
+        if (b >= nb) continue;
         f32x4 v = red[((0 * 2 + b) * J + j) * 64 + lane];
         for (int wv = 1; wv < FW; ++wv) {
             const f32x4 p = red[((wv * 2 + b) * J + j) * 64 + lane];
@@ -177,20 +233,48 @@ __global__ __launch_bounds__(FW * 64) void zo_fq_gemm_fused_kernel(zo_fused_args
     }
 }
 
+// Activations re-laid out fragment by fragment for the kernel above: the 16-byte piece that lane (m % 16, q) feeds
+// to matrix instruction c of m-tile j in slab sl goes to ((((sl * jn + j) * CH + c) * 64 + lane) * 16 bytes, jn = the
+// number of m-tiles the kernel variant for this M computes.  Rows past M repeat row M - 1; their products are never stored.
+__global__ __launch_bounds__(256) void zo_fused_relayout_kernel(const zo_bf16* __restrict__ X, int64_t strideX, int M, int K, int CH, int jn,
+                                                                zo_bf16* __restrict__ out, int64_t strideOut)
+{
+    const int kchunks = K >> 3;
+    const int64_t total = (int64_t)jn * 16 * kchunks;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int b = blockIdx.y;
+    const int mp = (int)(i / kchunks), kc = (int)(i % kchunks);
+    const int m = mp < M ? mp : M - 1;
+    const uint4 v = *reinterpret_cast<const uint4*>(X + b * strideX + (int64_t)m * K + kc * 8);
+    const int sl = kc / (4 * CH), r = kc % (4 * CH), q = r / CH, c = r % CH, j = mp >> 4, lane = q * 16 + (mp & 15);
+    *reinterpret_cast<uint4*>(out + b * strideOut + ((((int64_t)sl * jn + j) * CH + c) * 64 + lane) * 8) = v;
+}
+
+// m-tiles computed by the kernel variant that serves M rows
+int tiles_for(int M) { return M <= 16 ? 1 : M <= 32 ? 2 : M <= 64 ? 4 : 8; }
+
+template <int CH, int GL, int J>
+hipError_t launch_one(const zo_fused_args& a, const zo_stream& s, hipStream_t st)
+{
+    constexpr int lds = FW * 2 * J * 1024;
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void*)zo_fq_gemm_fused_kernel<CH, GL, J>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+    }
+    zo_fq_gemm_fused_kernel<CH, GL, J><<<dim3(a.N / 16), FW * 64, lds, st>>>(a, s);
+    return hipGetLastError();
+}
+
 template <int CH, int GL>
 hipError_t launch_j(const zo_fused_args& a, const zo_stream& s, hipStream_t st)
 {
-    const dim3 grid(a.N / 16);
-    if (a.M <= 32) {
-        constexpr int lds = FW * 2 * 2 * 1024;
-        zo_fq_gemm_fused_kernel<CH, GL, 2><<<grid, FW * 64, lds, st>>>(a, s);
-    } else {
-        constexpr int lds = FW * 2 * 8 * 1024;
-        hipError_t e = hipFuncSetAttribute((const void*)zo_fq_gemm_fused_kernel<CH, GL, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        zo_fq_gemm_fused_kernel<CH, GL, 8><<<grid, FW * 64, lds, st>>>(a, s);
+    switch (tiles_for(a.M)) {
+        case 1:  return launch_one<CH, GL, 1>(a, s, st);
+        case 2:  return launch_one<CH, GL, 2>(a, s, st);
+        case 4:  return launch_one<CH, GL, 4>(a, s, st);
+        default: return launch_one<CH, GL, 8>(a, s, st);
     }
-    return hipGetLastError();
 }
 
 }  // namespace
@@ -202,6 +286,20 @@ bool zo_fused_supported(int32_t M, int32_t N, int32_t K, int32_t bits, int32_t g
     if (bits < 1 || bits > 8) return false;
     if (group != 8 && group != 16 && group != 32 && group != 64 && group != 128) return false;
     return K % group == 0;
+}
+
+static int fused_ch(int bits, int group) { return bits == 0 || group <= 32 ? 1 : group / 32; }
+
+size_t zo_fused_relayout_bytes(int32_t M, int32_t K) { return (size_t)tiles_for(M) * 16 * (size_t)K * 2; }
+
+hipError_t zo_launch_fused_relayout(const void* X, int64_t strideX, int32_t M, int32_t K, int32_t nb, int32_t bits, int32_t group,
+                                    void* out, int64_t strideOut, hipStream_t st)
+{
+    const int jn = tiles_for(M);
+    const int64_t total = (int64_t)jn * 16 * (K / 8);
+    const dim3 grid((unsigned)((total + 255) / 256), nb);
+    zo_fused_relayout_kernel<<<grid, 256, 0, st>>>((const zo_bf16*)X, strideX, M, K, fused_ch(bits, group), jn, (zo_bf16*)out, strideOut);
+    return hipGetLastError();
 }
 
 hipError_t zo_launch_fq_gemm_fused(const zo_fused_args& a, uint64_t seed, int32_t tid, hipStream_t st)

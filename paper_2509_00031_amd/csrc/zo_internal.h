@@ -73,6 +73,8 @@ hipError_t zo_launch_gemm(const zo_gemm_args& a, hipStream_t st);
 #define ZO_FUSED_MAX_M 128
 struct zo_fused_args {
     const void* X;              // bf16 [nb][M][K] (strideX elements between the branches, may be 0)
+    const void* Xfrag;          // NULL, or the same activations re-laid out by zo_launch_fused_relayout (same bits / group)
+    int64_t strideXfrag;
     const float* W;             // fp32 master [N][K] of ONE tensor (element index = n*K + k in its stream)
     void* Y;                    // bf16 or fp32 [M][ldY], already offset to the tensor's first output column
     const float* bias;          // fp32 [N] (per branch: strideBias) or NULL
@@ -86,6 +88,11 @@ struct zo_fused_args {
 // M in 1..ZO_FUSED_MAX_M, N a multiple of 16, K a multiple of 32 and of the group
 bool zo_fused_supported(int32_t M, int32_t N, int32_t K, int32_t bits, int32_t group);
 hipError_t zo_launch_fq_gemm_fused(const zo_fused_args& a, uint64_t seed, int32_t tid, hipStream_t st);
+// Optional: activations in the order the fused kernel consumes them (contiguous wave-level loads instead of
+// 16-byte gathers; pays from a few m-tiles on).  out: zo_fused_relayout_bytes(M, K) bytes per branch.
+size_t zo_fused_relayout_bytes(int32_t M, int32_t K);
+hipError_t zo_launch_fused_relayout(const void* X, int64_t strideX, int32_t M, int32_t K, int32_t nb, int32_t bits, int32_t group,
+                                    void* out, int64_t strideOut, hipStream_t st);
 
 // ---- the rest of the decoder forward -----------------------------------------------------------
 // x[t] = rt(fma(eps, u(tok row), tok_emb[id]) (+ fma(eps, u(pos row), pos_emb[t % S])))

@@ -20,7 +20,7 @@ def test_fused_tiles_bit_exact(bits, g):
     W = synth.weights((N, K), 61)
     eye = torch.eye(K, dtype=torch.bfloat16, device="cuda")
     eps = np.float32(1e-3)
-    Yp, Ym = zo.zo_linear_fakequant_fused(eye, eye, to_dev(W, torch), None, bits, g, seed=7, tensor_id=3, eps=float(eps))
+    Yp, Ym = zo.zo_linear_fakequant_fused(eye, eye, to_dev(W, torch), None, bits, g, seed=7, tensor_id=3, eps=float(eps), relayout=True)
     for Y, e in ((Yp, eps), (Ym, -eps)):
         ref = orc.fakequant_weight(W, bits, g, 7, 3, np.float32(e), round_bf16=True, want_codes=False)["what"]
         assert np.array_equal(Y.float().cpu().numpy().T, ref)
@@ -34,8 +34,8 @@ def test_fused_tiles_bit_exact(bits, g):
 @pytest.mark.parametrize("M,N,K,bits,g", [(8, 256, 256, 4, 64), (1, 16, 64, 4, 64), (17, 80, 448, 2, 64), (100, 272, 1024, 4, 128),
                                           (128, 4096, 512, 4, 64), (33, 96, 4096, 4, 64), (128, 64, 11008, 4, 64),
                                           (60, 160, 992, 8, 32), (128, 512, 256, 0, 0)])
-@pytest.mark.parametrize("out_f32", [False, True])
-def test_fused_linear_vs_oracle(M, N, K, bits, g, out_f32):
+@pytest.mark.parametrize("out_f32,relayout", [(False, False), (True, False), (True, True)])
+def test_fused_linear_vs_oracle(M, N, K, bits, g, out_f32, relayout):
     """Different activations per branch, bias, ragged M, many K slabs per wave and fewer slabs than waves."""
     torch, zo = gpu()
     Xp = orc.bf16_round(synth.activations((M, K), 62))
@@ -44,7 +44,12 @@ def test_fused_linear_vs_oracle(M, N, K, bits, g, out_f32):
     bias = synth.weights((N,), 65)
     eps = np.float32(1e-3)
     Yp, Ym = zo.zo_linear_fakequant_fused(to_dev(Xp, torch, torch.bfloat16), to_dev(Xm, torch, torch.bfloat16), to_dev(W, torch),
-                                          to_dev(bias, torch), bits, g, seed=5, tensor_id=9, eps=float(eps), out_f32=out_f32)
+                                          to_dev(bias, torch), bits, g, seed=5, tensor_id=9, eps=float(eps), out_f32=out_f32,
+                                          relayout=relayout)
+    if relayout:                                    # the copy changes the order of the loads, not one bit of the result
+        Yp2, Ym2 = zo.zo_linear_fakequant_fused(to_dev(Xp, torch, torch.bfloat16), to_dev(Xm, torch, torch.bfloat16), to_dev(W, torch),
+                                                to_dev(bias, torch), bits, g, seed=5, tensor_id=9, eps=float(eps), out_f32=out_f32)
+        assert torch.equal(Yp, Yp2) and torch.equal(Ym, Ym2)
     for Y, X, e in ((Yp, Xp, eps), (Ym, Xm, -eps)):
         what = orc.fakequant_weight(W, bits, g, 5, 9, np.float32(e), round_bf16=True, want_codes=False)["what"]
         ref = orc.linear(X, what, bias)
@@ -94,7 +99,7 @@ def test_model_step_through_fused_route(arch, a_bits):
     (1e-3 relative) and against the quantize-once route; the update is the same function of the losses."""
     torch, zo = gpu()
     kw = dict(n_layers=2, d_model=128, n_heads=4, d_ffn=256, vocab=512, max_seq=48, w_bits=4, w_group=64)
-    B, S = 2, 48
+    B, S = 2, 48                                    # 96 tokens: the activations go through the fragment-ordered copy
     oarch = orc.ARCH_LLAMA if arch == "llama" else orc.ARCH_OPT
     zarch = zo.ARCH_LLAMA if arch == "llama" else zo.ARCH_OPT
     ocfg = orc.Config(oarch, act_dtype=1, a_bits=a_bits, **kw)
