@@ -138,7 +138,7 @@ zo_status zo_update(zo_ctx* ctx, uint64_t seed, const float* coeff_dev, float co
  * ZO_PROF_CATEGORIES entries).  A "GEMM" group is exactly one launch of the GEMM kernel (both
  * branches of Eq. 2 batched in it). */
 enum { ZO_PROF_GEMM = 0, ZO_PROF_WEIGHT_QUANT = 1, ZO_PROF_ACT_QUANT = 2, ZO_PROF_ATTENTION = 3,
-       ZO_PROF_UPDATE = 4, ZO_PROF_OTHER = 5, ZO_PROF_FUSED = 6 /* one launch of the fused small-M kernel */,
+       ZO_PROF_UPDATE = 4, ZO_PROF_OTHER = 5, ZO_PROF_FUSED = 6 /* a group = one launch of the fused small-M kernel (one parameter tensor) */,
        ZO_PROF_CATEGORIES = 7 };
 zo_status zo_profile_begin(zo_ctx* ctx);
 zo_status zo_profile_end(zo_ctx* ctx, float* ms_host, int32_t* launches_host);

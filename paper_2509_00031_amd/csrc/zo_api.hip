@@ -425,15 +425,16 @@ struct fwd {
                    bool residual, bool out_f32 = false, bool w_shared = false)
     {
         if (npend > 0) {
-            prof_scope ps(c, ZO_PROF_FUSED);
             const int64_t ts_ = (int64_t)zo_tsize(dt());
             // from a few m-tiles on the kernel is fed from a fragment-ordered copy of the activations, kept in the
             // (otherwise idle) operand buffers
             const bool relayout = M > 32 && zo_fused_relayout_bytes(M, K) <= c->L.what_bytes;
             const int64_t sxf = (int64_t)(c->L.what[1] - c->L.what[0]) / 2;
-            if (relayout)
+            if (relayout) {
+                prof_scope ps(c, ZO_PROF_OTHER);
                 ZO_HIP(c, zo_launch_fused_relayout(at(c->L.br[0].*in), nb == 2 ? (int64_t)(c->L.br[1].*in - c->L.br[0].*in) / ts_ : 0, M, K,
                                                    nb, pending[0].quantize ? c->cfg.w_bits : 0, c->cfg.w_group, at(c->L.what[0]), sxf, c->st));
+            }
             for (int i = 0; i < npend; ++i) {
                 const pend& pe = pending[i];
                 const param_desc& p = c->desc[pe.t];
@@ -457,6 +458,7 @@ struct fwd {
                 f.eps = eps_of(pe.t);
                 f.relu = relu;
                 f.out_f32 = out_f32;
+                prof_scope ps(c, ZO_PROF_FUSED);             // one bracket per kernel launch
                 ZO_HIP(c, zo_launch_fq_gemm_fused(f, seed, pe.t, c->st));
             }
             npend = 0;
@@ -532,12 +534,13 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
             fa.strideX = a.strideX; fa.strideY = a.strideY; fa.strideBias = a.strideBias;
             fa.bits = cfg.w_bits; fa.group = cfg.w_group; fa.eps = F.eps_of(0);
             F.npend = 0;
-            prof_scope ps(c, ZO_PROF_FUSED);
             if (M > 32 && zo_fused_relayout_bytes(M, K) <= c->L.what_bytes) {
+                prof_scope ps(c, ZO_PROF_OTHER);
                 fa.Xfrag = F.at(c->L.what[0]);
                 fa.strideXfrag = (int64_t)(c->L.what[1] - c->L.what[0]) / 2;
                 ZO_HIP(c, zo_launch_fused_relayout(fa.X, fa.strideX, M, K, nb, fa.bits, fa.group, F.at(c->L.what[0]), fa.strideXfrag, c->st));
             }
+            prof_scope ps(c, ZO_PROF_FUSED);
             ZO_HIP(c, zo_launch_fq_gemm_fused(fa, seed, 0, c->st));
         } else {
             prof_scope ps(c, ZO_PROF_GEMM);

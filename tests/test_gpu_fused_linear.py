@@ -113,9 +113,10 @@ def test_model_step_through_fused_route(arch, a_bits):
         ctx.zo_profile_begin()
         out = ctx.zo_step(to_dev(ids, torch), None, B, S, seed=13, eps=1e-3, lr=1e-4).cpu().numpy().copy()
         prof = ctx.zo_profile_end()
-        n_lin = 4 * kw["n_layers"] + 1                          # fused GEMM launches of a forward pair
+        n_gemm = 4 * kw["n_layers"] + 1                         # GEMM launches of a forward pair (q/k/v and gate/up batched)
+        n_lin = (7 if arch == "llama" else 6) * kw["n_layers"] + 1   # one fused launch per weight tensor
         if no_fused:
-            assert prof["fused_linear"][1] == 0 and prof["gemm"][1] == n_lin
+            assert prof["fused_linear"][1] == 0 and prof["gemm"][1] == n_gemm
         else:
             assert prof["gemm"][1] == 0 and prof["fused_linear"][1] == n_lin
         outs.append(out)
