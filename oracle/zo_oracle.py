@@ -618,3 +618,36 @@ def zo_step(cfg, params, seed, eps, lr, ids=None, x=None, target=None, trainable
         if trainable is None or trainable[i]:
             update(w, seed, i, cs[groups[i]])
     return lp, lm, g
+
+
+def zo_step_multi(cfg, params, seeds, eps, lr, ids=None, x=None, target=None, trainable=None, lr_smooth=None, lr_clip=None):
+    """One ZO-SGD step with q = len(seeds) directions (Eq. 2, then Eq. 3), updating `params` in place.
+
+    Every direction's pair of losses is evaluated at the same, not yet updated, W; the estimate is the
+    average (1/q) sum_i g_i u_i, so W <- W - sum_i (eta/q) g_i u_i.  Readings: the factor 1/q is folded
+    into the step size once (eta_q = fl32(eta / q)); the q rank-one terms are applied in the order of
+    `seeds`, one fp32 fused multiply-add each.  Returns [(L+, L-, g_i)] per direction."""
+    q = len(seeds)
+    eps = np.float32(eps)
+    res = []
+    for s in seeds:
+        lp = forward(cfg, params, ids, x, target, s, eps, trainable)
+        lm = forward(cfg, params, ids, x, target, s, -eps, trainable)
+        res.append((lp, lm, projected_grad(lp, lm, eps)))
+    lrs = [lr, lr if lr_smooth is None else lr_smooth, lr if lr_clip is None else lr_clip]
+    lrq = [np.float32(np.float32(v) / np.float32(q)) for v in lrs]
+    groups = param_groups(cfg)
+    for i, w in enumerate(params):
+        if isinstance(w, PackedInt4):
+            continue
+        if trainable is None or trainable[i]:
+            for s, (_, _, g) in zip(seeds, res):
+                update(w, s, i, coeff(lrq[groups[i]], g))
+    return res
+
+
+def lr_linear_decay(lr0, t, T):
+    """Step size of iteration t = 0 .. T-1 under the linear-decay schedule of the hyperparameter table
+    (pre-training); reading: eta_t = eta_0 (1 - t/T), reaching eta_0/T at the last iteration.  The
+    fine-tuning runs use a constant step size."""
+    return np.float32(float(np.float32(lr0)) * (1.0 - float(t) / float(T)))
