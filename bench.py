@@ -117,6 +117,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="llama7b_w4a8_g64_8x1024", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--directions", type=int, default=1,
+                    help="q of Eq. 2: forward pairs per step (all at the same W), followed by one multi-direction update pass")
     ap.add_argument("--no-fused", action="store_true", help="small token counts: quantize once and run the plain GEMM")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket launches with HIP events in the timed region")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -174,6 +176,9 @@ def main():
     out6 = torch.zeros(6, dtype=torch.float32, device=dev)
 
     def one_step(seed):
+        if args.directions > 1:
+            q = args.directions
+            return ctx.zo_step_multi(ids, None, B, S, [seed * q + i for i in range(q)], eps, lr, lr_smooth, lr_clip)[q - 1]
         if learned:
             return ctx.zo_step_groups(ids, None, B, S, seed, eps, lr, lr_smooth, lr_clip, out6)
         return ctx.zo_step(ids, None, B, S, seed=seed, eps=eps, lr=lr)
@@ -205,9 +210,10 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "tokens_per_step": B * S, "trainable_params": n_params,
                    "w_bits": w["w_bits"], "w_group": w["w_group"], "a_bits": w["a_bits"], "eps": eps, "lr": lr,
+                   "directions": args.directions,
                    "last_step": {"loss_plus": losses[0], "loss_minus": losses[1], "g": losses[2]}},
     }
-    gflops = gemm_flops_per_step(w)
+    gflops = gemm_flops_per_step(w) * args.directions
     if prof:
         gemm_ms, gemm_launches = prof["gemm"]
         avg_ms = gemm_ms / max(gemm_launches, 1)
@@ -237,7 +243,7 @@ def main():
                                 "frac": upd_gbs / PEAK_HBM_GBS if upd_gbs else None, "bytes_per_param": 8,
                                 "ms_per_step": upd_ms / max(upd_groups, 1)}
         res["breakdown_ms_per_step"] = {k: v[0] / args.steps for k, v in prof.items()}
-    res["step_flops"] = gflops + attention_flops_per_step(w)
+    res["step_flops"] = gflops + attention_flops_per_step(w) * args.directions
     res["step_tflops"] = res["step_flops"] / (ms_per_step * 1e-3) / 1e12
     ctx.close()
     del params, ctx

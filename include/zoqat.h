@@ -131,6 +131,25 @@ zo_status zo_step(zo_ctx* ctx, const void* ids, const float* target, int32_t B, 
  * c is read from coeff_dev (dev fp32[1]) if non-NULL, else coeff_host is used. */
 zo_status zo_update(zo_ctx* ctx, uint64_t seed, const float* coeff_dev, float coeff_host);
 
+/* ---- q > 1 directions per step (Eq. 2 as printed: the average over q directions u_i), step-size schedule, replay ----
+ * zo_step_multi: for i < q the pair of losses at W +- eps u(seeds[i]) -- every direction at the same, not yet
+ * updated W -- gives g_i; then W <- W - sum_i (lr_group / q) g_i u(seeds[i]) in ONE pass over the masters, the q
+ * terms applied in the order of the seeds, one fused multiply-add each (lr / q is one fp32 division).
+ *   seeds_host  host uint64 [q], q in 1..ZO_MAX_DIRECTIONS
+ *   out_dev     dev fp32 [q][6] = { L+, L-, g_i, (lr_model/q) g_i, (lr_smooth/q) g_i, (lr_clip/q) g_i }
+ * q = 1 is zo_step_groups. */
+enum { ZO_MAX_DIRECTIONS = 16 };
+zo_status zo_step_multi(zo_ctx* ctx, const void* ids_dev, const float* target_dev, int32_t B, int32_t S,
+                        const uint64_t* seeds_host, int32_t q, float eps, float lr_model, float lr_smooth, float lr_clip,
+                        float* out_dev);
+/* The update of zo_step_multi alone.  coeff_dev: dev fp32 [q][6] rows as zo_step_multi writes them (columns 3..5
+ * are read), or NULL and coeff_host: host fp32 [q][3] = the three group coefficients of every direction.
+ * A run is reproduced exactly, without any forward pass, by replaying its log of (seeds, coefficients). */
+zo_status zo_update_multi(zo_ctx* ctx, const uint64_t* seeds_host, int32_t q, const float* coeff_dev, const float* coeff_host);
+/* Step size of iteration t = 0 .. T-1 under the linear-decay schedule of the pre-training recipe (Appendix,
+ * hyperparameter table): lr0 (1 - t/T), evaluated in double, returned as float.  Host function. */
+float zo_lr_linear_decay(float lr0, int64_t t, int64_t T);
+
 /* Per-launch timing of the context's own work with HIP events recorded on its stream (the
  * stream the kernels run on).  Between zo_profile_begin and zo_profile_end every group of launches
  * is bracketed by two events.  zo_profile_end synchronises the stream and returns, per category,

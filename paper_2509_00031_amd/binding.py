@@ -24,7 +24,8 @@ EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "
            "zo_debug_quant_weight", "zo_debug_quant_act", "zo_linear_scratch_bytes", "zo_linear_fakequant",
            "zo_gemm_nt", "zo_debug_buffer", "zo_profile_begin", "zo_profile_end", "zo_attention_causal",
            "zo_attention_scratch_bytes", "zo_pack_weight_int4", "zo_attach_frozen_int4", "zo_linear_frozen_int4", "zo_gemm_nt_fused", "zo_init_learned_params", "zo_step_groups", "zo_update_groups",
-           "zo_debug_quant_weight_learned", "zo_debug_smooth_bias", "zo_linear_fakequant_fused", "zo_linear_fused_scratch_bytes"]
+           "zo_debug_quant_weight_learned", "zo_debug_smooth_bias", "zo_linear_fakequant_fused", "zo_linear_fused_scratch_bytes",
+           "zo_step_multi", "zo_update_multi", "zo_lr_linear_decay"]
 PROF_NAMES = ["gemm", "weight_quant", "act_quant", "attention", "update", "other", "fused_linear"]
 
 
@@ -83,6 +84,10 @@ _lib.zo_step_groups.argtypes = [_vp, _vp, _vp, _i32, _i32, _u64, _f32, _f32, _f3
 _lib.zo_update_groups.argtypes = [_vp, _u64, _vp, C.POINTER(C.c_float)]
 _lib.zo_debug_quant_weight_learned.argtypes = [_vp, _i32, _i32, _i32, _i32, _u64, _i32, _f32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]
 _lib.zo_debug_smooth_bias.argtypes = [_vp, _i32, _i32, _u64, _i32, _f32, _vp, _vp, _vp, _vp]
+_lib.zo_step_multi.argtypes = [_vp, _vp, _vp, _i32, _i32, C.POINTER(_u64), _i32, _f32, _f32, _f32, _f32, _vp]
+_lib.zo_update_multi.argtypes = [_vp, C.POINTER(_u64), _i32, _vp, C.POINTER(C.c_float)]
+_lib.zo_lr_linear_decay.argtypes = [_f32, _i64, _i64]
+_lib.zo_lr_linear_decay.restype = _f32
 _lib.zo_profile_begin.argtypes = [_vp]
 _lib.zo_profile_end.argtypes = [_vp, C.POINTER(C.c_float), C.POINTER(_i32)]
 
@@ -201,6 +206,21 @@ class Context:
         host = None if coeff_host is None else (C.c_float * 3)(*coeff_host)
         _check(_lib.zo_update_groups(self.handle, seed, _ptr(coeff_dev), host), "zo_update_groups", self.handle)
 
+    def zo_step_multi(self, ids, target, B, S, seeds, eps, lr_model, lr_smooth=None, lr_clip=None, out_dev=None):
+        q = len(seeds)
+        out = out_dev if out_dev is not None else torch.zeros((q, 6), dtype=torch.float32, device=ids.device)
+        arr = (_u64 * q)(*seeds)
+        _check(_lib.zo_step_multi(self.handle, _ptr(ids), _ptr(target), B, S, arr, q, eps, lr_model,
+                                  lr_model if lr_smooth is None else lr_smooth, lr_model if lr_clip is None else lr_clip,
+                                  out.data_ptr()), "zo_step_multi", self.handle)
+        return out
+
+    def zo_update_multi(self, seeds, coeff_dev=None, coeff_host=None):
+        q = len(seeds)
+        arr = (_u64 * q)(*seeds)
+        host = None if coeff_host is None else (C.c_float * (3 * q))(*[float(v) for row in coeff_host for v in row])
+        _check(_lib.zo_update_multi(self.handle, arr, q, _ptr(coeff_dev), host), "zo_update_multi", self.handle)
+
     def zo_update(self, seed, coeff_dev=None, coeff_host=0.0):
         _check(_lib.zo_update(self.handle, seed, _ptr(coeff_dev), coeff_host), "zo_update", self.handle)
 
@@ -219,6 +239,10 @@ class Context:
         _check(_lib.zo_debug_buffer(self.handle, which, branch, C.byref(p), C.byref(n)), "zo_debug_buffer", self.handle)
         off = p.value - self.workspace.data_ptr()
         return self.workspace[off:off + n.value]
+
+
+def zo_lr_linear_decay(lr0, t, T):
+    return _lib.zo_lr_linear_decay(lr0, t, T)
 
 
 def zo_debug_philox_u32(seed, tensor_id, nwords, device="cuda"):

@@ -14,6 +14,8 @@ namespace {
 inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
+static_assert(ZO_MAX_DIRECTIONS == ZO_MAX_DIRECTIONS_INTERNAL, "public and internal direction limits differ");
+
 enum { ZO_GROUP_MODEL = 0, ZO_GROUP_SMOOTH = 1, ZO_GROUP_CLIP = 2 };   // learning-rate groups
 
 struct param_desc {
@@ -128,7 +130,8 @@ zo_status check_config(const zo_config& c)
 
 // Workspace layout for B x S tokens.  Offsets in bytes, everything 256-byte aligned.
 struct layout {
-    size_t scalars;            // fp32[16]: loss[2] at 0, {L+, L-, g, c_model, c_smooth, c_clip} at 2
+    size_t scalars;            // fp32[16 + 8 q_max]: loss[2] at 0, {L+, L-, g, c_model, c_smooth, c_clip} at 2; direction i of a
+                               // q-direction step: loss[2] at 16 + 8 i, its six values at 16 + 8 i + 2
     size_t rope_cos, rope_sin; // fp32 [max_seq][dh/2]
     size_t what[2];            // de-quantized weights of the current linear(s), per branch
     size_t what_bytes;         // size of each
@@ -150,7 +153,7 @@ layout make_layout(const zo_config& c, int B, int S)
     const size_t d = c.d_model, f = c.d_ffn, V = c.vocab > 0 ? c.vocab : 0;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
-    L.scalars = take(16 * sizeof(float));
+    L.scalars = take((16 + 8 * ZO_MAX_DIRECTIONS) * sizeof(float));
     const size_t gsz = c.w_group > 0 ? (size_t)c.w_group : 0;
     if (c.arch == ZO_ARCH_LINEAR) {
         const size_t M = B;
@@ -847,6 +850,59 @@ zo_status step_impl(zo_ctx* ctx, const void* ids, const float* target, int32_t B
     return update_all(ctx, seed, out6 + 3, 1, nullptr);
 }
 }  // namespace
+
+namespace {
+// q directions in one pass: coefficient of (direction d, group g) = coeff_dev[d * stride + g], or coeff_host[d * 3 + g]
+zo_status update_all_multi(zo_ctx* ctx, const uint64_t* seeds, int q, const float* coeff_dev, int stride, const float* coeff_host)
+{
+    prof_scope ps(ctx, ZO_PROF_UPDATE);
+    zo_multi_seeds ms{};
+    for (int d = 0; d < q; ++d) { ms.k0[d] = (uint32_t)seeds[d]; ms.k1[d] = (uint32_t)(seeds[d] >> 32); }
+    for (int i = 0; i < (int)ctx->params.size(); ++i) {
+        if (!trainable(ctx, i) || !ctx->params[i].ptr) continue;
+        const int g = ctx->desc[i].lr_group;
+        if (!coeff_dev)
+            for (int d = 0; d < q; ++d) ms.c[d] = coeff_host[d * 3 + g];
+        ZO_HIP(ctx, zo_launch_update_multi((float*)ctx->params[i].ptr, ctx->params[i].numel, ms, q, i, coeff_dev ? coeff_dev + g : nullptr,
+                                           stride, ctx->st));
+    }
+    return ZO_OK;
+}
+}  // namespace
+
+zo_status zo_step_multi(zo_ctx* ctx, const void* ids, const float* target, int32_t B, int32_t S, const uint64_t* seeds_host,
+                        int32_t q, float eps, float lr_model, float lr_smooth, float lr_clip, float* out_dev)
+{
+    zo_status s = check_batch(ctx, ids, target, B, S);
+    if (s != ZO_OK) return s;
+    if (!out_dev || !seeds_host) return fail(ctx, ZO_EINVAL, "out_dev / seeds_host is NULL");
+    if (q < 1 || q > ZO_MAX_DIRECTIONS) return fail(ctx, ZO_EINVAL, "q must be in 1..ZO_MAX_DIRECTIONS");
+    if (!(eps > 0.0f)) return fail(ctx, ZO_EINVAL, "eps must be positive");
+    // Eq. 2's factor 1/q, folded into the step sizes once (one fp32 division each)
+    const float lrq[3] = {lr_model / (float)q, lr_smooth / (float)q, lr_clip / (float)q};
+    float* scal = (float*)(ctx->ws + ctx->L.scalars) + 16;
+    for (int d = 0; d < q; ++d) {                       // every direction at the same, not yet updated, W
+        float* loss2 = scal + 8 * d;
+        s = run_forward(ctx, ids, target, B, S, seeds_host[d], eps, 2, loss2);
+        if (s != ZO_OK) return s;
+        ZO_HIP(ctx, zo_launch_projected_grad(loss2, eps, lrq, loss2 + 2, out_dev + 6 * d, 6, ctx->st));
+    }
+    return update_all_multi(ctx, seeds_host, q, scal + 2 + 3, 8, nullptr);
+}
+
+zo_status zo_update_multi(zo_ctx* ctx, const uint64_t* seeds_host, int32_t q, const float* coeff_dev, const float* coeff_host)
+{
+    if (!ctx) return ZO_EINVAL;
+    if (!seeds_host || (!coeff_dev && !coeff_host)) return fail(ctx, ZO_EINVAL, "seeds / coefficients missing");
+    if (q < 1 || q > ZO_MAX_DIRECTIONS) return fail(ctx, ZO_EINVAL, "q must be in 1..ZO_MAX_DIRECTIONS");
+    return update_all_multi(ctx, seeds_host, q, coeff_dev ? coeff_dev + 3 : nullptr, 6, coeff_host);
+}
+
+float zo_lr_linear_decay(float lr0, int64_t t, int64_t T)
+{
+    if (T <= 0) return lr0;
+    return (float)((double)lr0 * (1.0 - (double)t / (double)T));
+}
 
 zo_status zo_update(zo_ctx* ctx, uint64_t seed, const float* coeff_dev, float coeff_host)
 {

@@ -140,6 +140,96 @@ hipError_t zo_launch_update(float* w, int64_t numel, uint64_t seed, int32_t tid,
 }
 
 // ---------------------------------------------------------------------------------------------
+// update with q directions (Eq. 2 with q > 1, Eq. 3): w_i <- fma(-c_{q-1}, u_i(seed_{q-1}), ... fma(-c_0, u_i(seed_0), w_i)),
+// the terms applied in the order of the seeds, all in one pass over the masters (8 B per parameter whatever q).
+// Same work split and lane-pair exchange as zo_update_kernel.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void zo_update_multi_kernel(float* __restrict__ w, zo_multi_seeds ms, uint32_t tensor_id, int q,
+                                                              const float* __restrict__ coeff_dev, int coeff_stride)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const bool odd = lane & 1;
+#pragma unroll 1
+    for (int u = 0; u < 2; ++u) {
+        const int64_t e0 = ((int64_t)blockIdx.x * 2 + u) * 2048 + wave * 512;
+        float4* p = reinterpret_cast<float4*>(w + e0) + lane;
+        typedef float f32x4_ __attribute__((ext_vector_type(4)));
+        const f32x4_ A_ = __builtin_nontemporal_load(reinterpret_cast<f32x4_*>(p)), B_ = __builtin_nontemporal_load(reinterpret_cast<f32x4_*>(p + 64));
+        float4 A = make_float4(A_[0], A_[1], A_[2], A_[3]), B = make_float4(B_[0], B_[1], B_[2], B_[3]);
+        float y0 = odd ? A.x : B.x, y1 = odd ? A.y : B.y, y2 = odd ? A.z : B.z, y3 = odd ? A.w : B.w;
+        float n0 = swap_adjacent_lanes(y0), n1 = swap_adjacent_lanes(y1), n2 = swap_adjacent_lanes(y2), n3 = swap_adjacent_lanes(y3);
+        float v[8], z[8];
+        v[0] = odd ? n0 : A.x; v[1] = odd ? n1 : A.y; v[2] = odd ? n2 : A.z; v[3] = odd ? n3 : A.w;
+        v[4] = odd ? B.x : n0; v[5] = odd ? B.y : n1; v[6] = odd ? B.z : n2; v[7] = odd ? B.w : n3;
+        const uint64_t blk = (uint64_t)(e0 >> 3) + (odd ? 32 : 0) + (lane >> 1);
+#pragma unroll 1
+        for (int d = 0; d < q; ++d) {
+            const zo_stream s{ms.k0[d], ms.k1[d], tensor_id};
+            const float negc = -(coeff_dev ? coeff_dev[d * coeff_stride] : ms.c[d]);
+            zo_z8(s, blk, z);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = __builtin_fmaf(negc, z[i], v[i]);
+        }
+        y0 = odd ? v[0] : v[4]; y1 = odd ? v[1] : v[5]; y2 = odd ? v[2] : v[6]; y3 = odd ? v[3] : v[7];
+        n0 = swap_adjacent_lanes(y0); n1 = swap_adjacent_lanes(y1); n2 = swap_adjacent_lanes(y2); n3 = swap_adjacent_lanes(y3);
+        A = odd ? make_float4(n0, n1, n2, n3) : make_float4(v[0], v[1], v[2], v[3]);
+        B = odd ? make_float4(v[4], v[5], v[6], v[7]) : make_float4(n0, n1, n2, n3);
+        const f32x4_ a_ = {A.x, A.y, A.z, A.w}, b_ = {B.x, B.y, B.z, B.w};
+        __builtin_nontemporal_store(a_, reinterpret_cast<f32x4_*>(p));
+        __builtin_nontemporal_store(b_, reinterpret_cast<f32x4_*>(p + 64));
+    }
+}
+
+__global__ __launch_bounds__(256) void zo_update_multi_tail_kernel(float* __restrict__ w, int64_t first, int64_t numel, zo_multi_seeds ms,
+                                                                   uint32_t tensor_id, int q, const float* __restrict__ coeff_dev,
+                                                                   int coeff_stride)
+{
+    const int64_t nblk = numel >> 3;
+    const int64_t b = (first >> 3) + (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (b < nblk) {
+        float v[8], z[8];
+        zo_load8(w + 8 * b, v);
+        for (int d = 0; d < q; ++d) {
+            const zo_stream s{ms.k0[d], ms.k1[d], tensor_id};
+            const float negc = -(coeff_dev ? coeff_dev[d * coeff_stride] : ms.c[d]);
+            zo_z8(s, (uint64_t)b, z);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = __builtin_fmaf(negc, z[i], v[i]);
+        }
+        zo_store8(w + 8 * b, v);
+    }
+    if (blockIdx.x == 0) {
+        const int64_t i = 8 * nblk + threadIdx.x;
+        if (i < numel) {
+            float x = w[i];
+            for (int d = 0; d < q; ++d) {
+                const zo_stream s{ms.k0[d], ms.k1[d], tensor_id};
+                const float negc = -(coeff_dev ? coeff_dev[d * coeff_stride] : ms.c[d]);
+                x = __builtin_fmaf(negc, zo_z1(s, (uint64_t)i), x);
+            }
+            w[i] = x;
+        }
+    }
+}
+
+hipError_t zo_launch_update_multi(float* w, int64_t numel, const zo_multi_seeds& ms, int32_t q, int32_t tid,
+                                  const float* coeff_dev, int32_t coeff_stride, hipStream_t st)
+{
+    if (numel == 0 || q == 0) return hipSuccess;
+    if (q < 0 || q > ZO_MAX_DIRECTIONS_INTERNAL) return hipErrorInvalidValue;
+    const int64_t main_blocks = numel / 4096;
+    if (main_blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+    if (main_blocks > 0) zo_update_multi_kernel<<<(int)main_blocks, 256, 0, st>>>(w, ms, (uint32_t)tid, q, coeff_dev, coeff_stride);
+    const int64_t first = main_blocks * 4096;
+    if (first < numel) {
+        const int64_t tail_blk = ((numel >> 3) - (first >> 3) + 255) / 256;
+        zo_update_multi_tail_kernel<<<(int)(tail_blk > 0 ? tail_blk : 1), 256, 0, st>>>(w, first, numel, ms, (uint32_t)tid, q, coeff_dev,
+                                                                                        coeff_stride);
+    }
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
 // weight fake-quantizer: Q(W + eps u) and/or Q(W - eps u), de-quantized, in GEMM operand type.
 // One thread owns 8 consecutive k (one Philox block); a group of G consecutive k is G/8 = GL
 // neighbouring lanes, reduced with cross-lane shuffles.  u is generated once for both branches.

@@ -16,6 +16,13 @@ hipError_t zo_launch_normal(uint64_t seed, int32_t tid, int64_t start, int64_t n
 hipError_t zo_launch_update(float* w, int64_t numel, uint64_t seed, int32_t tid,
                             const float* coeff_dev, float coeff_host, hipStream_t st);
 
+// q directions at once: terms applied in order d = 0 .. q-1; coefficient of direction d = coeff_dev[d * coeff_stride]
+// (device) if coeff_dev, else ms.c[d]
+#define ZO_MAX_DIRECTIONS_INTERNAL 16
+struct zo_multi_seeds { uint32_t k0[ZO_MAX_DIRECTIONS_INTERNAL], k1[ZO_MAX_DIRECTIONS_INTERNAL]; float c[ZO_MAX_DIRECTIONS_INTERNAL]; };
+hipError_t zo_launch_update_multi(float* w, int64_t numel, const zo_multi_seeds& ms, int32_t q, int32_t tid,
+                                  const float* coeff_dev, int32_t coeff_stride, hipStream_t st);
+
 // ---- weight fake-quantizer ---------------------------------------------------------------------
 // Emits Q(W + eps u) into out_plus and/or Q(W - eps u) into out_minus (storage type dtype); either
 // may be NULL.  bits = 0: perturbed weights, not quantized.  Debug outputs describe the '+' branch.

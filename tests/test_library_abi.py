@@ -51,3 +51,13 @@ def test_host_side_shape_logic(lib):
     bad = zo.make_config(zo.ARCH_LLAMA, n_layers=1, d_model=100, n_heads=4, d_ffn=256, vocab=64, max_seq=16)
     assert zo.zo_workspace_bytes(bad, 1, 16) == 0      # d_model not a multiple of 8
     assert zo.zo_num_params(zo.make_config(7)) == 0
+
+
+def test_linear_decay_is_the_oracles(lib):
+    """Host function of the library against the oracle's schedule (Appendix, hyperparameter table)."""
+    import numpy as np
+    from oracle import zo_oracle as orc
+    from paper_2509_00031_amd import binding as zo
+    for lr0, T in ((5e-7, 10000), (1e-8, 10000), (1e-2, 7)):
+        for t in (0, 1, T // 3, T // 2, T - 1):
+            assert np.float32(zo.zo_lr_linear_decay(lr0, t, T)) == orc.lr_linear_decay(lr0, t, T)
