@@ -14,6 +14,9 @@
  *     clipping coefficients (Eq. 5) and the channel-wise smoothing (Eq. 4)
  *   - frozen, pre-quantized weights of the lightweight variant
  *                                 (Section "Lightweight ZeroQAT for memory reduction")
+ *   - master weights kept in IEEE binary16, what the memory table of the
+ *     efficiency section implies (2 bytes per parameter), with the update of
+ *     Eq. 3 rounded to nearest even or stochastically
  * The paper only says u ~ N(0, I); the concrete counter-based stream used here
  * (Philox4x32-10 of Salmon et al. 2011 + a fixed-recipe Box-Muller) is this
  * build's reading.  The *choice* of generator is "parity unpinned": nothing in
@@ -517,4 +520,73 @@ void zo_or_update(float* w, int64_t n, uint64_t seed, int32_t tensor_id, float c
 {
     #pragma omp parallel for schedule(static)
     for (int64_t i = 0; i < n; ++i) w[i] = fmaf(-c, zo_or_z(seed, tensor_id, i), w[i]);
+}
+
+
+/* ------------------------------------------------------------------ */
+/* Master weights stored in IEEE binary16 (memory table of the         */
+/* efficiency section: the ZeroQAT rows are 2 bytes per parameter).    */
+/* Forward: the stored value, converted exactly to fp32, takes the     */
+/* place of w everywhere (w' = fma(s eps, u, w) in fp32, never stored).*/
+/* Update (Eq. 3): x = fma(-c, u, w) in fp32, then one rounding to     */
+/* binary16 -- to nearest even, or stochastically: x goes to its upper */
+/* neighbour hi with probability (x - lo) / (hi - lo), else to lo, so  */
+/* that the expectation of the stored value is x even when |c u| is    */
+/* far below the spacing of binary16 (a reading: the paper does not    */
+/* say how the 16-bit weights are rounded).                            */
+/* ------------------------------------------------------------------ */
+
+/* Uniform 24-bit integer of element i for the stochastic rounding: the top 24 bits of word (i & 3)
+ * of block (i >> 2) of a second stream, counter = (block low, block high, tensor_id, 1) -- the
+ * perturbation stream uses 0 in the last counter word, so the two never share a block. */
+uint32_t zo_or_round_bits(uint64_t seed, int32_t tensor_id, int64_t i)
+{
+    uint64_t blk = (uint64_t)i >> 2;
+    uint32_t ctr[4] = { (uint32_t)blk, (uint32_t)(blk >> 32), (uint32_t)tensor_id, 1u };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t w[4];
+    zo_or_philox4x32_10(ctr, key, w);
+    return w[i & 3] >> 8;
+}
+
+/* neighbours of a finite binary16 value on the real line (bit patterns) */
+static uint16_t f16_next_up(uint16_t h)
+{
+    if ((h & 0x7FFFu) == 0) return 0x0001u;          /* +-0 -> smallest positive */
+    return (h & 0x8000u) ? (uint16_t)(h - 1) : (uint16_t)(h + 1);
+}
+static uint16_t f16_next_down(uint16_t h)
+{
+    if ((h & 0x7FFFu) == 0) return 0x8001u;          /* +-0 -> smallest negative */
+    return (h & 0x8000u) ? (uint16_t)(h + 1) : (uint16_t)(h - 1);
+}
+
+/* x -> binary16 with stochastic rounding driven by the 24-bit integer r: exactly representable
+ * values, infinities, NaNs and values that round to infinity go through the nearest-even
+ * conversion; otherwise lo < x < hi are the neighbouring binary16 values and the result is hi
+ * iff r * (hi - lo) / 2^24 < x - lo (all three quantities exact in fp32). */
+uint16_t zo_or_f32_to_f16_stochastic(float x, uint32_t r)
+{
+    uint16_t h = zo_or_f32_to_f16_bits(x);
+    if ((h & 0x7C00u) == 0x7C00u) return h;
+    float f = zo_or_f16_bits_to_f32(h);
+    if (f == x) return h;
+    uint16_t lo = (f < x) ? h : f16_next_down(h);
+    uint16_t hi = (f < x) ? f16_next_up(h) : h;
+    float flo = zo_or_f16_bits_to_f32(lo), fhi = zo_or_f16_bits_to_f32(hi);
+    float ulp = fhi - flo;                           /* a power of two */
+    float d = x - flo;                               /* exact: 0 < d < ulp */
+    float t = (float)r * (ulp * 0x1p-24f);           /* exact: 24-bit integer times a power of two */
+    return (t < d) ? hi : lo;
+}
+
+/* Update of binary16 masters: w_i <- round16(fma(-c, u_i, w_i)). */
+void zo_or_update_f16(uint16_t* w, int64_t n, uint64_t seed, int32_t tensor_id, float c, int stochastic)
+{
+    #pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        float x = fmaf(-c, zo_or_z(seed, tensor_id, i), zo_or_f16_bits_to_f32(w[i]));
+        w[i] = stochastic ? zo_or_f32_to_f16_stochastic(x, zo_or_round_bits(seed, tensor_id, i))
+                          : zo_or_f32_to_f16_bits(x);
+    }
 }

@@ -83,6 +83,11 @@ _lib.zo_or_projected_grad.restype = C.c_float
 _lib.zo_or_coeff.argtypes = [C.c_float, C.c_float]
 _lib.zo_or_coeff.restype = C.c_float
 _lib.zo_or_update.argtypes = [_f32p, C.c_int64, C.c_uint64, C.c_int32, C.c_float]
+_lib.zo_or_update_f16.argtypes = [_u16p, C.c_int64, C.c_uint64, C.c_int32, C.c_float, C.c_int]
+_lib.zo_or_round_bits.argtypes = [C.c_uint64, C.c_int32, C.c_int64]
+_lib.zo_or_round_bits.restype = C.c_uint32
+_lib.zo_or_f32_to_f16_stochastic.argtypes = [C.c_float, C.c_uint32]
+_lib.zo_or_f32_to_f16_stochastic.restype = C.c_uint16
 
 
 # ----------------------------------------------------------------------------
@@ -273,11 +278,26 @@ def coeff(lr, g):
     return np.float32(_lib.zo_or_coeff(lr, g))
 
 
-def update(w, seed, tensor_id, c):
-    """In place: w <- fma(-c, z, w) (Eq. 3)."""
-    assert w.dtype == np.float32 and w.flags.c_contiguous
+def update(w, seed, tensor_id, c, stochastic=False):
+    """In place: w <- fma(-c, z, w) (Eq. 3).  Masters kept in binary16 (dtype float16) are rounded once
+    after the fp32 fma: to nearest even, or stochastically."""
+    assert w.flags.c_contiguous
+    if w.dtype == np.float16:
+        _lib.zo_or_update_f16(w.reshape(-1).view(np.uint16), w.size, seed, tensor_id, c, int(stochastic))
+        return w
+    assert w.dtype == np.float32
     _lib.zo_or_update(w.reshape(-1), w.size, seed, tensor_id, c)
     return w
+
+
+def round_bits(seed, tensor_id, i):
+    """The 24-bit uniform integer that decides the stochastic rounding of element i."""
+    return int(_lib.zo_or_round_bits(seed, tensor_id, i))
+
+
+def f32_to_f16_stochastic(x, r):
+    """binary16 bits of x rounded stochastically with the 24-bit integer r."""
+    return int(_lib.zo_or_f32_to_f16_stochastic(float(np.float32(x)), int(r)))
 
 
 # ----------------------------------------------------------------------------
@@ -599,7 +619,8 @@ def forward(cfg, params, ids=None, x=None, target=None, seed=0, eps_signed=0.0, 
     return cross_entropy(logits, ids, B, S)
 
 
-def zo_step(cfg, params, seed, eps, lr, ids=None, x=None, target=None, trainable=None, lr_smooth=None, lr_clip=None):
+def zo_step(cfg, params, seed, eps, lr, ids=None, x=None, target=None, trainable=None, lr_smooth=None, lr_clip=None,
+            stochastic=False):
     """One ZO-SGD step (Eq. 2 with q = 1, then Eq. 3), updating `params` in place.
 
     Entries of `params` that are PackedInt4 are frozen (their `trainable` flag must be False).
@@ -616,7 +637,7 @@ def zo_step(cfg, params, seed, eps, lr, ids=None, x=None, target=None, trainable
         if isinstance(w, PackedInt4):
             continue
         if trainable is None or trainable[i]:
-            update(w, seed, i, cs[groups[i]])
+            update(w, seed, i, cs[groups[i]], stochastic)
     return lp, lm, g
 
 
