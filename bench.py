@@ -119,6 +119,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--directions", type=int, default=1,
                     help="q of Eq. 2: forward pairs per step (all at the same W), followed by one multi-direction update pass")
+    ap.add_argument("--masters", choices=["f32", "f16", "f16sr"], default="f32",
+                    help="storage of the master weights: fp32 (the benchmark configurations), IEEE binary16 rounded to nearest "
+                         "even (f16) or stochastically (f16sr) in the update -- the 2 bytes per parameter of the paper's memory table")
     ap.add_argument("--no-fused", action="store_true", help="small token counts: quantize once and run the plain GEMM")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket launches with HIP events in the timed region")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -140,7 +143,8 @@ def main():
     cfg = zo.make_config(arch, n_layers=w["n_layers"], d_model=w["d_model"], n_heads=w["n_heads"], d_ffn=w["d_ffn"],
                          vocab=w["vocab"], max_seq=w["S"], w_bits=w["w_bits"], w_group=w["w_group"], a_bits=w["a_bits"],
                          act_dtype=zo.ACT_BF16, lightweight=w.get("lightweight", 0), learn_clip=w.get("learn_clip", 0),
-                         learn_smooth=w.get("learn_smooth", 0), no_fused=int(args.no_fused))
+                         learn_smooth=w.get("learn_smooth", 0), no_fused=int(args.no_fused),
+                         master_dtype=zo.MASTER_F16 if args.masters != "f32" else zo.MASTER_F32, master_round=int(args.masters == "f16sr"))
     n = zo.zo_num_params(cfg)
     gen = torch.Generator(device=dev)
     gen.manual_seed(1234)
@@ -155,7 +159,7 @@ def main():
         packed_kinds = (2, 4, 6, 7, 8)
     for i in range(n):
         numel = zo.zo_param_numel(cfg, i)
-        t = torch.empty(numel, dtype=torch.float32, device=dev)
+        t = torch.empty(numel, dtype=torch.float32 if args.masters == "f32" else torch.float16, device=dev)
         t.normal_(0.0, 0.02, generator=gen)
         if numel == w["d_model"]:                       # norm gains / small vectors: around one
             t.add_(1.0)
@@ -163,7 +167,7 @@ def main():
             n_params += numel
         elif kind(i) in packed_kinds:                   # frozen linear: keep only its packed 4-bit form
             K = w["d_ffn"] if kind(i) == 8 else w["d_model"]
-            t = zo.zo_pack_weight_int4(t.view(numel // K, K), w["w_group"])
+            t = zo.zo_pack_weight_int4(t.float().view(numel // K, K), w["w_group"])
         params.append(t)
     B, S = w["B"], w["S"]
     ids = torch.randint(0, w["vocab"], (B, S), dtype=torch.int32, device=dev, generator=gen)
@@ -210,7 +214,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "tokens_per_step": B * S, "trainable_params": n_params,
                    "w_bits": w["w_bits"], "w_group": w["w_group"], "a_bits": w["a_bits"], "eps": eps, "lr": lr,
-                   "directions": args.directions,
+                   "directions": args.directions, "masters": args.masters,
                    "last_step": {"loss_plus": losses[0], "loss_minus": losses[1], "g": losses[2]}},
     }
     gflops = gemm_flops_per_step(w) * args.directions
@@ -238,9 +242,10 @@ def main():
                                "master_GBps": 4.0 * params_per_launch / (avg_ms * 1e-3) / 1e9}
             res["gemm_tflops"] = gflops * args.steps / (fused_ms * 1e-3) / 1e12
         upd_ms, upd_groups = prof["update"]
-        upd_gbs = 8.0 * n_params * upd_groups / (upd_ms * 1e-3) / 1e9 if upd_ms > 0 else None
+        upd_bpp = 8 if args.masters == "f32" else 4          # one read + one write of every trainable master
+        upd_gbs = upd_bpp * n_params * upd_groups / (upd_ms * 1e-3) / 1e9 if upd_ms > 0 else None
         res["update_kernel"] = {"bound": "hbm", "achieved": upd_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                                "frac": upd_gbs / PEAK_HBM_GBS if upd_gbs else None, "bytes_per_param": 8,
+                                "frac": upd_gbs / PEAK_HBM_GBS if upd_gbs else None, "bytes_per_param": upd_bpp,
                                 "ms_per_step": upd_ms / max(upd_groups, 1)}
         res["breakdown_ms_per_step"] = {k: v[0] / args.steps for k, v in prof.items()}
     res["step_flops"] = gflops + attention_flops_per_step(w) * args.directions

@@ -46,6 +46,7 @@ typedef enum {
 
 enum { ZO_ARCH_LINEAR = 0, ZO_ARCH_LLAMA = 1, ZO_ARCH_OPT = 2 };
 enum { ZO_ACT_FP32 = 0, ZO_ACT_BF16 = 1 };
+enum { ZO_MASTER_F32 = 0, ZO_MASTER_F16 = 1 };
 
 /* Model and quantization setting ("WxAy gN" of the appendix: w_bits, a_bits, w_group). */
 typedef struct {
@@ -69,6 +70,14 @@ typedef struct {
     int32_t no_fused;    /* 0 = quantized linears of a forward over at most 128 tokens (bf16 storage, groups of
                             8..128, no learned / packed tensors) build their weight tiles inside the GEMM kernel;
                             1 = always quantize once into the workspace and run the plain GEMM */
+    int32_t master_dtype;/* ZO_MASTER_*: storage type of every tensor of the parameter list.  ZO_MASTER_F16 = IEEE binary16,
+                            the 2 bytes per parameter that the memory table of the efficiency section implies: a
+                            forward reads the stored value (exactly widened to fp32) wherever it read the fp32 master;
+                            the update of Eq. 3 computes fma(-c, u, w) in fp32 and rounds once to binary16.  Not
+                            available together with learn_clip / learn_smooth. */
+    int32_t master_round;/* binary16 masters only: 0 = round to nearest even (a step below half the spacing of
+                            binary16 is lost entirely), 1 = stochastic rounding (upper neighbour with probability
+                            (x - lo) / (hi - lo), integers from the stream (seed, element / 4, tensor, 1)) */
 } zo_config;
 
 /* One parameter tensor.  The array given to zo_init lists them in the fixed order below; the
@@ -85,7 +94,7 @@ typedef struct {
  *   w_gate for w_gate/w_up, every other linear for itself) s[K], delta[K].
  *   Learning-rate groups: the model's tensors 0, smoothing tensors 1, quantizer tensors 2.         */
 typedef struct {
-    void*   ptr;        /* dev, fp32 master weights, updated in place by zo_update / zo_step; may be
+    void*   ptr;        /* dev, master weights (fp32, or binary16 with ZO_MASTER_F16), updated in place by zo_update / zo_step; may be
                            NULL for a frozen quantized linear of a lightweight configuration whose
                            packed form is attached with zo_attach_frozen_int4 */
     int64_t numel;
@@ -172,6 +181,16 @@ zo_status zo_debug_normal(uint64_t seed, int32_t tensor_id, int64_t start, int64
 /* Seeded in-place update of one tensor (Eq. 3): w_i <- w_i - c * u(seed, tensor_id, i). */
 zo_status zo_update_tensor(float* w_dev, int64_t numel, uint64_t seed, int32_t tensor_id,
                            const float* coeff_dev, float coeff_host, void* hip_stream);
+
+/* The same for a tensor kept in IEEE binary16: w_i <- round16(fma(-c, u(seed, tensor_id, i), w_i)), nearest even or
+ * (stochastic != 0) stochastic rounding. */
+zo_status zo_update_tensor_f16(void* w_dev, int64_t numel, uint64_t seed, int32_t tensor_id,
+                               const float* coeff_dev, float coeff_host, int32_t stochastic, void* hip_stream);
+
+/* Bytes of master-weight storage a configuration asks the caller for (all tensors of the parameter list in
+ * master_dtype; -1 if the configuration is invalid): the "weights only, independent of the batch size" memory of
+ * the efficiency section's table.  Host function. */
+int64_t zo_master_bytes(const zo_config* cfg);
 
 /* Q(W + eps_signed u) of one weight matrix W[N][K] (Eq. 2's argument of L for one linear):
  * perturb, group min/max, quantize, de-quantize.  bits = 0: perturb only.  Outputs (any may be

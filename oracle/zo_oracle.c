@@ -590,3 +590,11 @@ void zo_or_update_f16(uint16_t* w, int64_t n, uint64_t seed, int32_t tensor_id, 
                           : zo_or_f32_to_f16_bits(x);
     }
 }
+
+/* One rounding of fp32 values to binary16 (nearest even, or stochastic with the rounding stream of `seed`). */
+void zo_or_round_array_f16(const float* x, int64_t n, uint64_t seed, int32_t tensor_id, int stochastic, uint16_t* out)
+{
+    #pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i)
+        out[i] = stochastic ? zo_or_f32_to_f16_stochastic(x[i], zo_or_round_bits(seed, tensor_id, i)) : zo_or_f32_to_f16_bits(x[i]);
+}

@@ -84,6 +84,7 @@ _lib.zo_or_coeff.argtypes = [C.c_float, C.c_float]
 _lib.zo_or_coeff.restype = C.c_float
 _lib.zo_or_update.argtypes = [_f32p, C.c_int64, C.c_uint64, C.c_int32, C.c_float]
 _lib.zo_or_update_f16.argtypes = [_u16p, C.c_int64, C.c_uint64, C.c_int32, C.c_float, C.c_int]
+_lib.zo_or_round_array_f16.argtypes = [_f32p, C.c_int64, C.c_uint64, C.c_int32, C.c_int, _u16p]
 _lib.zo_or_round_bits.argtypes = [C.c_uint64, C.c_int32, C.c_int64]
 _lib.zo_or_round_bits.restype = C.c_uint32
 _lib.zo_or_f32_to_f16_stochastic.argtypes = [C.c_float, C.c_uint32]
@@ -287,6 +288,21 @@ def update(w, seed, tensor_id, c, stochastic=False):
         return w
     assert w.dtype == np.float32
     _lib.zo_or_update(w.reshape(-1), w.size, seed, tensor_id, c)
+    return w
+
+
+def update_multi(w, seeds, tensor_id, cs, stochastic=False):
+    """In place: the q rank-one terms of a q-direction step in seed order, one fp32 fma each.  binary16 masters are
+    widened once, take all q terms in fp32 and are rounded once at the end (the stochastic rounding draws from the
+    rounding stream of the first seed)."""
+    if w.dtype == np.float16:
+        x = w.astype(np.float32)
+        for s, c in zip(seeds, cs):
+            update(x, s, tensor_id, c)
+        _lib.zo_or_round_array_f16(x.reshape(-1), x.size, seeds[0], tensor_id, int(stochastic), w.reshape(-1).view(np.uint16))
+        return w
+    for s, c in zip(seeds, cs):
+        update(w, s, tensor_id, c)
     return w
 
 
@@ -641,7 +657,8 @@ def zo_step(cfg, params, seed, eps, lr, ids=None, x=None, target=None, trainable
     return lp, lm, g
 
 
-def zo_step_multi(cfg, params, seeds, eps, lr, ids=None, x=None, target=None, trainable=None, lr_smooth=None, lr_clip=None):
+def zo_step_multi(cfg, params, seeds, eps, lr, ids=None, x=None, target=None, trainable=None, lr_smooth=None, lr_clip=None,
+                  stochastic=False):
     """One ZO-SGD step with q = len(seeds) directions (Eq. 2, then Eq. 3), updating `params` in place.
 
     Every direction's pair of losses is evaluated at the same, not yet updated, W; the estimate is the
@@ -662,8 +679,7 @@ def zo_step_multi(cfg, params, seeds, eps, lr, ids=None, x=None, target=None, tr
         if isinstance(w, PackedInt4):
             continue
         if trainable is None or trainable[i]:
-            for s, (_, _, g) in zip(seeds, res):
-                update(w, s, i, coeff(lrq[groups[i]], g))
+            update_multi(w, seeds, i, [coeff(lrq[groups[i]], g) for _, _, g in res], stochastic)
     return res
 
 

@@ -18,6 +18,7 @@ ZO_OK = 0
 STATUS = {0: "ZO_OK", 1: "ZO_EINVAL", 2: "ZO_ESHAPE", 3: "ZO_EALIGN", 4: "ZO_EHIP", 5: "ZO_EUNSUPPORTED", 6: "ZO_EWORKSPACE"}
 ARCH_LINEAR, ARCH_LLAMA, ARCH_OPT = 0, 1, 2
 ACT_FP32, ACT_BF16 = 0, 1
+MASTER_F32, MASTER_F16 = 0, 1
 
 EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "zo_destroy", "zo_last_error",
            "zo_forward_quant", "zo_step", "zo_update", "zo_debug_philox_u32", "zo_debug_normal", "zo_update_tensor",
@@ -25,14 +26,14 @@ EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "
            "zo_gemm_nt", "zo_debug_buffer", "zo_profile_begin", "zo_profile_end", "zo_attention_causal",
            "zo_attention_scratch_bytes", "zo_pack_weight_int4", "zo_attach_frozen_int4", "zo_linear_frozen_int4", "zo_gemm_nt_fused", "zo_init_learned_params", "zo_step_groups", "zo_update_groups",
            "zo_debug_quant_weight_learned", "zo_debug_smooth_bias", "zo_linear_fakequant_fused", "zo_linear_fused_scratch_bytes",
-           "zo_step_multi", "zo_update_multi", "zo_lr_linear_decay"]
+           "zo_step_multi", "zo_update_multi", "zo_lr_linear_decay", "zo_update_tensor_f16", "zo_master_bytes"]
 PROF_NAMES = ["gemm", "weight_quant", "act_quant", "attention", "update", "other", "fused_linear"]
 
 
 class zo_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("arch", "n_layers", "d_model", "n_heads", "d_ffn", "vocab", "max_seq",
                                          "w_bits", "w_group", "a_bits", "a_sym", "act_dtype", "lightweight",
-                                         "learn_clip", "learn_smooth", "no_fused")]
+                                         "learn_clip", "learn_smooth", "no_fused", "master_dtype", "master_round")]
 
 
 class zo_tensor(C.Structure):
@@ -88,6 +89,9 @@ _lib.zo_step_multi.argtypes = [_vp, _vp, _vp, _i32, _i32, C.POINTER(_u64), _i32,
 _lib.zo_update_multi.argtypes = [_vp, C.POINTER(_u64), _i32, _vp, C.POINTER(C.c_float)]
 _lib.zo_lr_linear_decay.argtypes = [_f32, _i64, _i64]
 _lib.zo_lr_linear_decay.restype = _f32
+_lib.zo_update_tensor_f16.argtypes = [_vp, _i64, _u64, _i32, _vp, _f32, _i32, _vp]
+_lib.zo_master_bytes.argtypes = [C.POINTER(zo_config)]
+_lib.zo_master_bytes.restype = _i64
 _lib.zo_profile_begin.argtypes = [_vp]
 _lib.zo_profile_end.argtypes = [_vp, C.POINTER(C.c_float), C.POINTER(_i32)]
 
@@ -111,9 +115,14 @@ def _tdtype(dtype):
 
 
 def make_config(arch, n_layers=0, d_model=0, n_heads=1, d_ffn=0, vocab=0, max_seq=0, w_bits=4, w_group=64,
-                a_bits=16, a_sym=0, act_dtype=ACT_FP32, lightweight=0, learn_clip=0, learn_smooth=0, no_fused=0):
+                a_bits=16, a_sym=0, act_dtype=ACT_FP32, lightweight=0, learn_clip=0, learn_smooth=0, no_fused=0,
+                master_dtype=MASTER_F32, master_round=0):
     return zo_config(arch, n_layers, d_model, n_heads, d_ffn, vocab, max_seq, w_bits, w_group, a_bits, a_sym,
-                     act_dtype, lightweight, learn_clip, learn_smooth, no_fused)
+                     act_dtype, lightweight, learn_clip, learn_smooth, no_fused, master_dtype, master_round)
+
+
+def zo_master_bytes(cfg):
+    return _lib.zo_master_bytes(C.byref(cfg))
 
 
 def zo_num_params(cfg):
@@ -155,7 +164,8 @@ class Context:
             if isinstance(p, PackedInt4):
                 arr[i] = zo_tensor(None, p.numel(), tr, 0)
                 continue
-            assert p.is_cuda and p.dtype == torch.float32 and p.is_contiguous()
+            want = torch.float16 if cfg.master_dtype == MASTER_F16 else torch.float32
+            assert p.is_cuda and p.dtype == want and p.is_contiguous()
             arr[i] = zo_tensor(p.data_ptr(), p.numel(), tr, 0)
         nbytes = zo_workspace_bytes(cfg, max_B, max_S)
         if nbytes == 0:
@@ -260,6 +270,13 @@ def zo_debug_normal(seed, tensor_id, numel, start=0, device="cuda"):
 def zo_update_tensor(w, seed, tensor_id, coeff_dev=None, coeff_host=0.0):
     _check(_lib.zo_update_tensor(w.data_ptr(), w.numel(), seed, tensor_id, _ptr(coeff_dev), coeff_host, _stream()),
            "zo_update_tensor")
+    return w
+
+
+def zo_update_tensor_f16(w, seed, tensor_id, coeff_dev=None, coeff_host=0.0, stochastic=False):
+    assert w.dtype == torch.float16
+    _check(_lib.zo_update_tensor_f16(w.data_ptr(), w.numel(), seed, tensor_id, _ptr(coeff_dev), coeff_host, int(stochastic), _stream()),
+           "zo_update_tensor_f16")
     return w
 
 

@@ -120,6 +120,8 @@ zo_status check_config(const zo_config& c)
     if (c.learn_smooth && (!c.learn_clip || c.a_bits >= 16)) return ZO_EUNSUPPORTED;
     if ((c.learn_clip || c.learn_smooth) && c.lightweight) return ZO_EUNSUPPORTED;
     if (c.no_fused < 0 || c.no_fused > 1) return ZO_EINVAL;
+    if (c.master_dtype < 0 || c.master_dtype > 1 || c.master_round < 0 || c.master_round > 1) return ZO_EINVAL;
+    if (c.master_dtype == ZO_MASTER_F16 && (c.learn_clip || c.learn_smooth)) return ZO_EUNSUPPORTED;
     if (c.arch != ZO_ARCH_LINEAR) {
         if (c.d_model % c.n_heads) return ZO_ESHAPE;
         const int dh = c.d_model / c.n_heads;
@@ -303,6 +305,7 @@ struct fwd {
     }
     template <typename T = char> T* at(size_t off) const { return (T*)(c->ws + off); }
     int dt() const { return c->cfg.act_dtype; }
+    int wd() const { return c->cfg.master_dtype == ZO_MASTER_F16 ? ZO_W_F16 : ZO_W_F32; }
     float eps_of(int tensor) const { return trainable(c, tensor) ? eps : 0.0f; }
 
     bool frozen(int t) const { return c->frozen[t].codes != nullptr; }
@@ -345,8 +348,8 @@ struct fwd {
                                                   eps_of(t), dt(), lp, lm, op, om, nullptr, c->st));
             return ZO_OK;
         }
-        ZO_HIP(c, zo_launch_fq_weight((const float*)c->params[t].ptr, (int)p.rows, (int)p.cols, bits, c->cfg.w_group,
-                                      seed, t, eps_of(t), dt(), op, om, nullptr, nullptr, nullptr, c->st));
+        ZO_HIP(c, zo_launch_fq_weight(c->params[t].ptr, (int)p.rows, (int)p.cols, bits, c->cfg.w_group,
+                                      seed, t, eps_of(t), dt(), op, om, nullptr, nullptr, nullptr, c->st, wd()));
         return ZO_OK;
     }
     // Eq. 4, activation side of the linears whose input is smoothed by the pair carried by linear `t`:
@@ -383,8 +386,8 @@ struct fwd {
         float* op = at<float>(c->L.vec[0]) + slot * c->L.vec_stride + o;
         float* om = nb == 2 ? at<float>(c->L.vec[1]) + slot * c->L.vec_stride + o : nullptr;
         prof_scope ps(c, ZO_PROF_WEIGHT_QUANT);
-        ZO_HIP(c, zo_launch_fq_weight((const float*)c->params[t].ptr, 1, (int)p.cols, 0, 0, seed, t, eps_of(t), ZO_T_F32,
-                                      op, om, nullptr, nullptr, nullptr, c->st));
+        ZO_HIP(c, zo_launch_fq_weight(c->params[t].ptr, 1, (int)p.cols, 0, 0, seed, t, eps_of(t), ZO_T_F32,
+                                      op, om, nullptr, nullptr, nullptr, c->st, wd()));
         return ZO_OK;
     }
     float* vec(int b, int slot) const { return at<float>(c->L.vec[b]) + slot * c->L.vec_stride; }
@@ -444,7 +447,8 @@ struct fwd {
                 zo_fused_args f{};
                 f.X = at(c->L.br[0].*in);
                 if (relayout) { f.Xfrag = at(c->L.what[0]); f.strideXfrag = sxf; }
-                f.W = (const float*)c->params[pe.t].ptr;
+                f.W = c->params[pe.t].ptr;
+                f.wdtype = wd();
                 f.Y = at(c->L.br[0].*out) + (size_t)pe.row0 * (out_f32 ? 4 : ts_);
                 f.bias = bias ? vec(0, 2) + pe.row0 : nullptr;
                 f.residual = residual ? f.Y : nullptr;
@@ -532,7 +536,7 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
         }
         if (F.npend > 0) {                               // small M: tiles of Q(W +- eps u) built inside the GEMM kernel
             zo_fused_args fa{};
-            fa.X = a.X; fa.W = (const float*)c->params[0].ptr; fa.Y = a.Y; fa.bias = a.bias;
+            fa.X = a.X; fa.W = c->params[0].ptr; fa.wdtype = F.wd(); fa.Y = a.Y; fa.bias = a.bias;
             fa.M = M; fa.N = N; fa.K = K; fa.nb = nb; fa.ldY = N;
             fa.strideX = a.strideX; fa.strideY = a.strideY; fa.strideBias = a.strideBias;
             fa.bits = cfg.w_bits; fa.group = cfg.w_group; fa.eps = F.eps_of(0);
@@ -570,9 +574,9 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
         prof_scope ps(c, ZO_PROF_OTHER);
         for (int b = 0; b < nb; ++b) {
             const float sgn = (b == 0) ? 1.0f : -1.0f;
-            ZO_HIP(c, zo_launch_embed(ids, (const float*)c->params[t_tok].ptr, llama ? nullptr : (const float*)c->params[t_pos].ptr,
+            ZO_HIP(c, zo_launch_embed(ids, c->params[t_tok].ptr, llama ? nullptr : c->params[t_pos].ptr,
                                       F.at(c->L.br[b].x), M, S, d, V, seed, t_tok, llama ? 0 : t_pos,
-                                      sgn * F.eps_of(t_tok), llama ? 0.0f : sgn * F.eps_of(t_pos), dt, c->st));
+                                      sgn * F.eps_of(t_tok), llama ? 0.0f : sgn * F.eps_of(t_pos), dt, c->st, F.wd()));
         }
     }
     size_t PB::* xin;
@@ -826,6 +830,19 @@ namespace {
 zo_status update_all(zo_ctx* ctx, uint64_t seed, const float* coeff_dev, int stride, const float coeff_host[3])
 {
     prof_scope ps(ctx, ZO_PROF_UPDATE);
+    if (ctx->cfg.master_dtype == ZO_MASTER_F16) {          // binary16 masters: fp32 fma, one rounding
+        zo_multi_seeds ms{};
+        ms.k0[0] = (uint32_t)seed;
+        ms.k1[0] = (uint32_t)(seed >> 32);
+        for (int i = 0; i < (int)ctx->params.size(); ++i) {
+            if (!trainable(ctx, i) || !ctx->params[i].ptr) continue;
+            const int g = ctx->desc[i].lr_group;
+            ms.c[0] = coeff_host ? coeff_host[g] : 0.0f;
+            ZO_HIP(ctx, zo_launch_update_f16(ctx->params[i].ptr, ctx->params[i].numel, ms, 1, i, coeff_dev ? coeff_dev + stride * g : nullptr, 0,
+                                             ctx->cfg.master_round, ctx->st));
+        }
+        return ZO_OK;
+    }
     for (int i = 0; i < (int)ctx->params.size(); ++i) {
         if (!trainable(ctx, i) || !ctx->params[i].ptr) continue;
         const int g = ctx->desc[i].lr_group;
@@ -863,6 +880,11 @@ zo_status update_all_multi(zo_ctx* ctx, const uint64_t* seeds, int q, const floa
         const int g = ctx->desc[i].lr_group;
         if (!coeff_dev)
             for (int d = 0; d < q; ++d) ms.c[d] = coeff_host[d * 3 + g];
+        if (ctx->cfg.master_dtype == ZO_MASTER_F16) {
+            ZO_HIP(ctx, zo_launch_update_f16(ctx->params[i].ptr, ctx->params[i].numel, ms, q, i, coeff_dev ? coeff_dev + g : nullptr, stride,
+                                             ctx->cfg.master_round, ctx->st));
+            continue;
+        }
         ZO_HIP(ctx, zo_launch_update_multi((float*)ctx->params[i].ptr, ctx->params[i].numel, ms, q, i, coeff_dev ? coeff_dev + g : nullptr,
                                            stride, ctx->st));
     }
@@ -996,6 +1018,28 @@ zo_status zo_update_tensor(float* w_dev, int64_t numel, uint64_t seed, int32_t t
     if (numel < 0 || (numel > 0 && !w_dev)) return ZO_EINVAL;
     if (!aligned16(w_dev)) return ZO_EALIGN;
     return zo_launch_update(w_dev, numel, seed, tensor_id, coeff_dev, coeff_host, (hipStream_t)hip_stream) == hipSuccess ? ZO_OK : ZO_EHIP;
+}
+
+zo_status zo_update_tensor_f16(void* w_dev, int64_t numel, uint64_t seed, int32_t tensor_id, const float* coeff_dev, float coeff_host,
+                               int32_t stochastic, void* hip_stream)
+{
+    if (numel < 0 || (numel > 0 && !w_dev)) return ZO_EINVAL;
+    if (!aligned16(w_dev)) return ZO_EALIGN;
+    zo_multi_seeds ms{};
+    ms.k0[0] = (uint32_t)seed;
+    ms.k1[0] = (uint32_t)(seed >> 32);
+    ms.c[0] = coeff_host;
+    return zo_launch_update_f16(w_dev, numel, ms, 1, tensor_id, coeff_dev, 0, stochastic ? 1 : 0, (hipStream_t)hip_stream) == hipSuccess
+               ? ZO_OK : ZO_EHIP;
+}
+
+int64_t zo_master_bytes(const zo_config* cfg)
+{
+    std::vector<param_desc> p;
+    if (!cfg || check_config(*cfg) != ZO_OK || !describe_params(*cfg, p)) return -1;
+    int64_t total = 0;
+    for (const param_desc& d : p) total += d.rows * d.cols * (cfg->master_dtype == ZO_MASTER_F16 ? 2 : 4);
+    return total;
 }
 
 zo_status zo_debug_quant_weight(const float* W_dev, int32_t N, int32_t K, int32_t bits, int32_t group,

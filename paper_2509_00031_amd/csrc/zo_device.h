@@ -61,6 +61,17 @@ ZO_DEV void zo_store8(zo_bf16* p, const float v[8])
     a.z = zo_pack_bf16x2(v[4], v[5]); a.w = zo_pack_bf16x2(v[6], v[7]);
     *reinterpret_cast<uint4*>(p) = a;
 }
+// master weights kept in IEEE binary16: exact widening on load
+typedef _Float16 zo_f16;
+ZO_DEV void zo_load8(const zo_f16* p, float v[8])
+{
+    typedef _Float16 f16x8_ __attribute__((ext_vector_type(8)));
+    const f16x8_ a = *reinterpret_cast<const f16x8_*>(p);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = (float)a[i];
+}
+ZO_DEV float zo_load(const zo_f16* p) { return (float)*p; }
+
 // value as it will be read back from storage of type T
 template <typename T> ZO_DEV float zo_round_to(float v);
 template <> ZO_DEV float zo_round_to<float>(float v) { return v; }
@@ -162,6 +173,67 @@ ZO_DEV float zo_z1(const zo_stream& s, uint64_t i)
     float z0, z1;
     zo_word_to_normals(word, z0, z1);
     return (i & 1) ? z1 : z0;
+}
+
+// ---------------------------------------------------------------------------------------------
+// rounding of an updated master to binary16: nearest even, or stochastic (the stored value's expectation is
+// the fp32 result even when the step is far below the spacing of binary16).  The random integers come from
+// a second stream: same key, counter = (element index / 4, tensor id, 1).
+// ---------------------------------------------------------------------------------------------
+ZO_DEV uint16_t zo_f16_bits(float x) { return __builtin_bit_cast(uint16_t, (zo_f16)x); }      // round to nearest even
+ZO_DEV float zo_f16_value(uint16_t h) { return (float)__builtin_bit_cast(zo_f16, h); }
+
+// r: uniform 24-bit integer.  lo < x < hi neighbouring binary16 values: hi iff r (hi - lo) / 2^24 < x - lo.
+ZO_DEV uint16_t zo_f16_stochastic(float x, uint32_t r)
+{
+    const uint16_t h = zo_f16_bits(x);
+    if ((h & 0x7C00u) == 0x7C00u) return h;            // infinity / NaN
+    const float f = zo_f16_value(h);
+    if (f == x) return h;                              // representable
+    const bool zero = (h & 0x7FFFu) == 0, neg = (h & 0x8000u) != 0;
+    const uint16_t up = zero ? (uint16_t)0x0001u : (uint16_t)(neg ? h - 1 : h + 1);
+    const uint16_t dn = zero ? (uint16_t)0x8001u : (uint16_t)(neg ? h + 1 : h - 1);
+    const bool below = f < x;
+    const uint16_t lo = below ? h : dn, hi = below ? up : h;
+    const float flo = zo_f16_value(lo), fhi = zo_f16_value(hi);
+    const float ulp = fhi - flo;
+    const float d = x - flo;
+    const float t = (float)r * (ulp * 0x1p-24f);
+    return t < d ? hi : lo;
+}
+
+// the eight 24-bit integers of elements 8*blk .. 8*blk+7 (two blocks of the rounding stream)
+ZO_DEV void zo_round_bits8(const zo_stream& s, uint64_t blk, uint32_t r[8])
+{
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const uint64_t b = 2 * blk + half;
+        uint32_t c0 = (uint32_t)b, c1 = (uint32_t)(b >> 32), c2 = s.tensor_id, c3 = 1u;
+        uint32_t k0 = s.k0, k1 = s.k1;
+#pragma unroll
+        for (int rd = 0; rd < 10; ++rd) {
+            uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
+            uint64_t p1 = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
+            uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+            uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+            c1 = (uint32_t)p1;
+            c3 = (uint32_t)p0;
+            c0 = n0;
+            c2 = n2;
+            k0 += 0x9E3779B9u;
+            k1 += 0xBB67AE85u;
+        }
+        r[4 * half + 0] = c0 >> 8; r[4 * half + 1] = c1 >> 8; r[4 * half + 2] = c2 >> 8; r[4 * half + 3] = c3 >> 8;
+    }
+}
+ZO_DEV uint32_t zo_round_bits1(const zo_stream& s, uint64_t i)
+{
+    uint32_t r[8];
+    zo_round_bits8(s, i >> 3, r);
+    uint32_t out = r[0];
+#pragma unroll
+    for (int k = 1; k < 8; ++k) out = ((uint32_t)(i & 7) == (uint32_t)k) ? r[k] : out;
+    return out;
 }
 
 // ---------------------------------------------------------------------------------------------

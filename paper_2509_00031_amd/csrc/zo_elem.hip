@@ -230,6 +230,76 @@ hipError_t zo_launch_update_multi(float* w, int64_t numel, const zo_multi_seeds&
 }
 
 // ---------------------------------------------------------------------------------------------
+// update of binary16 masters: x = fma(-c_d, u(seed_d), w) over the q directions in fp32, then ONE rounding to
+// binary16 (nearest even, or stochastic with the integers of the rounding stream of seeds[0]).  A lane's 16-byte
+// access is exactly one Philox block of 8 parameters, so no lane exchange is needed; 4 B of HBM traffic per
+// parameter.  The ragged end (numel % 8) goes one element per thread.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void zo_update_f16_kernel(uint16_t* __restrict__ w, int64_t numel, zo_multi_seeds ms, uint32_t tensor_id,
+                                                            int q, const float* __restrict__ coeff_dev, int coeff_stride, int stochastic)
+{
+    const int64_t nblk = numel >> 3;
+    const int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (b < nblk) {
+        typedef uint32_t u32x4_ __attribute__((ext_vector_type(4)));
+        u32x4_* p = reinterpret_cast<u32x4_*>(w + 8 * b);
+        const u32x4_ raw = __builtin_nontemporal_load(p);
+        float v[8], z[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = zo_f16_value((uint16_t)(raw[i] & 0xFFFFu));
+            v[2 * i + 1] = zo_f16_value((uint16_t)(raw[i] >> 16));
+        }
+#pragma unroll 1
+        for (int d = 0; d < q; ++d) {
+            const zo_stream s{ms.k0[d], ms.k1[d], tensor_id};
+            const float negc = -(coeff_dev ? coeff_dev[d * coeff_stride] : ms.c[d]);
+            zo_z8(s, (uint64_t)b, z);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = __builtin_fmaf(negc, z[i], v[i]);
+        }
+        uint16_t h[8];
+        if (stochastic) {
+            uint32_t r[8];
+            zo_round_bits8(zo_stream{ms.k0[0], ms.k1[0], tensor_id}, (uint64_t)b, r);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) h[i] = zo_f16_stochastic(v[i], r[i]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) h[i] = zo_f16_bits(v[i]);
+        }
+        u32x4_ o;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = (uint32_t)h[2 * i] | ((uint32_t)h[2 * i + 1] << 16);
+        __builtin_nontemporal_store(o, p);
+    }
+    if (blockIdx.x == 0) {
+        const int64_t i = 8 * nblk + threadIdx.x;
+        if (i < numel) {
+            float x = zo_f16_value(w[i]);
+            for (int d = 0; d < q; ++d) {
+                const zo_stream s{ms.k0[d], ms.k1[d], tensor_id};
+                const float negc = -(coeff_dev ? coeff_dev[d * coeff_stride] : ms.c[d]);
+                x = __builtin_fmaf(negc, zo_z1(s, (uint64_t)i), x);
+            }
+            w[i] = stochastic ? zo_f16_stochastic(x, zo_round_bits1(zo_stream{ms.k0[0], ms.k1[0], tensor_id}, (uint64_t)i)) : zo_f16_bits(x);
+        }
+    }
+}
+
+hipError_t zo_launch_update_f16(void* w, int64_t numel, const zo_multi_seeds& ms, int32_t q, int32_t tid,
+                                const float* coeff_dev, int32_t coeff_stride, int32_t stochastic, hipStream_t st)
+{
+    if (numel == 0 || q == 0) return hipSuccess;
+    if (q < 0 || q > ZO_MAX_DIRECTIONS_INTERNAL) return hipErrorInvalidValue;
+    const int64_t blocks = ((numel >> 3) + 255) / 256;
+    if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+    zo_update_f16_kernel<<<(int)(blocks > 0 ? blocks : 1), 256, 0, st>>>((uint16_t*)w, numel, ms, (uint32_t)tid, q, coeff_dev, coeff_stride,
+                                                                         stochastic);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
 // weight fake-quantizer: Q(W + eps u) and/or Q(W - eps u), de-quantized, in GEMM operand type.
 // One thread owns 8 consecutive k (one Philox block); a group of G consecutive k is G/8 = GL
 // neighbouring lanes, reduced with cross-lane shuffles.  u is generated once for both branches.
@@ -267,8 +337,8 @@ __device__ __forceinline__ void fq_branch(const float v[8], int bits, TO* out, i
     if (active && out) zo_store8(out + 8 * b, o);
 }
 
-template <typename TO, int GL, bool DEBUG>
-__global__ __launch_bounds__(256) void zo_fq_weight_kernel(const float* __restrict__ W, int64_t nblk, zo_stream s,
+template <typename TW, typename TO, int GL, bool DEBUG>
+__global__ __launch_bounds__(256) void zo_fq_weight_kernel(const TW* __restrict__ W, int64_t nblk, zo_stream s,
                                                            float eps, int bits, TO* __restrict__ out_p, TO* __restrict__ out_m,
                                                            uint8_t* codes, float* step, int32_t* zp)
 {
@@ -303,8 +373,8 @@ __global__ __launch_bounds__(256) void zo_fq_weight_kernel(const float* __restri
 
 // Groups wider than 512 elements (per-channel quantization): one workgroup per output channel,
 // two sweeps over the row (range, then codes); the stream is regenerated in the second sweep.
-template <typename TO, bool DEBUG>
-__global__ __launch_bounds__(256) void zo_fq_weight_row_kernel(const float* __restrict__ W, int K, int group, zo_stream s,
+template <typename TW, typename TO, bool DEBUG>
+__global__ __launch_bounds__(256) void zo_fq_weight_row_kernel(const TW* __restrict__ W, int K, int group, zo_stream s,
                                                                float eps, int bits, TO* __restrict__ out_p, TO* __restrict__ out_m,
                                                                uint8_t* codes, float* step, int32_t* zp)
 {
@@ -376,58 +446,65 @@ bool zo_fq_weight_supported(int32_t K, int32_t bits, int32_t group)
     return true;
 }
 
-template <typename TO, int GL>
-static hipError_t launch_fq_weight_gl(const float* W, int64_t nblk, zo_stream s, float eps, int bits, TO* op, TO* om,
+template <typename TW, typename TO, int GL>
+static hipError_t launch_fq_weight_gl(const TW* W, int64_t nblk, zo_stream s, float eps, int bits, TO* op, TO* om,
                                       uint8_t* codes, float* step, int32_t* zp, hipStream_t st)
 {
     if ((nblk + 255) / 256 > 0x7FFFFFFF) return hipErrorInvalidValue;
     const int grid = (int)((nblk + 255) / 256);
     if (codes || step || zp)
-        zo_fq_weight_kernel<TO, GL, true><<<grid, 256, 0, st>>>(W, nblk, s, eps, bits, op, om, codes, step, zp);
+        zo_fq_weight_kernel<TW, TO, GL, true><<<grid, 256, 0, st>>>(W, nblk, s, eps, bits, op, om, codes, step, zp);
     else
-        zo_fq_weight_kernel<TO, GL, false><<<grid, 256, 0, st>>>(W, nblk, s, eps, bits, op, om, nullptr, nullptr, nullptr);
+        zo_fq_weight_kernel<TW, TO, GL, false><<<grid, 256, 0, st>>>(W, nblk, s, eps, bits, op, om, nullptr, nullptr, nullptr);
     return hipGetLastError();
 }
 
-template <typename TO>
-static hipError_t launch_fq_weight_t(const float* W, int32_t N, int32_t K, int32_t bits, int32_t group, zo_stream s, float eps,
+template <typename TW, typename TO>
+static hipError_t launch_fq_weight_t(const TW* W, int32_t N, int32_t K, int32_t bits, int32_t group, zo_stream s, float eps,
                                      TO* op, TO* om, uint8_t* codes, float* step, int32_t* zp, hipStream_t st)
 {
     const int64_t nblk = (int64_t)N * K / 8;
     if (nblk == 0) return hipSuccess;
-    if (bits == 0) return launch_fq_weight_gl<TO, 1>(W, nblk, s, eps, 0, op, om, nullptr, nullptr, nullptr, st);
+    if (bits == 0) return launch_fq_weight_gl<TW, TO, 1>(W, nblk, s, eps, 0, op, om, nullptr, nullptr, nullptr, st);
     if (group == 0) group = K;
     const int gl = group / 8;
     const bool pow2 = (gl & (gl - 1)) == 0;
     if (pow2 && gl <= 64) {
         switch (gl) {
-            case 1:  return launch_fq_weight_gl<TO, 1>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
-            case 2:  return launch_fq_weight_gl<TO, 2>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
-            case 4:  return launch_fq_weight_gl<TO, 4>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
-            case 8:  return launch_fq_weight_gl<TO, 8>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
-            case 16: return launch_fq_weight_gl<TO, 16>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
-            case 32: return launch_fq_weight_gl<TO, 32>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
-            default: return launch_fq_weight_gl<TO, 64>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
+            case 1:  return launch_fq_weight_gl<TW, TO, 1>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
+            case 2:  return launch_fq_weight_gl<TW, TO, 2>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
+            case 4:  return launch_fq_weight_gl<TW, TO, 4>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
+            case 8:  return launch_fq_weight_gl<TW, TO, 8>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
+            case 16: return launch_fq_weight_gl<TW, TO, 16>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
+            case 32: return launch_fq_weight_gl<TW, TO, 32>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
+            default: return launch_fq_weight_gl<TW, TO, 64>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
         }
     }
     const int64_t ngroups = (int64_t)N * (K / group);
     if (ngroups > 0x7FFFFFFF) return hipErrorInvalidValue;
     if (codes || step || zp)
-        zo_fq_weight_row_kernel<TO, true><<<(int)ngroups, 256, 0, st>>>(W, K, group, s, eps, bits, op, om, codes, step, zp);
+        zo_fq_weight_row_kernel<TW, TO, true><<<(int)ngroups, 256, 0, st>>>(W, K, group, s, eps, bits, op, om, codes, step, zp);
     else
-        zo_fq_weight_row_kernel<TO, false><<<(int)ngroups, 256, 0, st>>>(W, K, group, s, eps, bits, op, om, nullptr, nullptr, nullptr);
+        zo_fq_weight_row_kernel<TW, TO, false><<<(int)ngroups, 256, 0, st>>>(W, K, group, s, eps, bits, op, om, nullptr, nullptr, nullptr);
     return hipGetLastError();
 }
 
-hipError_t zo_launch_fq_weight(const float* W, int32_t N, int32_t K, int32_t bits, int32_t group,
+hipError_t zo_launch_fq_weight(const void* W, int32_t N, int32_t K, int32_t bits, int32_t group,
                                uint64_t seed, int32_t tid, float eps, int dtype,
                                void* out_plus, void* out_minus,
-                               uint8_t* codes, float* step, int32_t* zp, hipStream_t st)
+                               uint8_t* codes, float* step, int32_t* zp, hipStream_t st, int wdtype)
 {
     zo_stream s = make_stream(seed, tid);
+    if (wdtype == ZO_W_F16) {
+        const zo_f16* Wh = (const zo_f16*)W;
+        if (dtype == ZO_T_BF16)
+            return launch_fq_weight_t<zo_f16, zo_bf16>(Wh, N, K, bits, group, s, eps, (zo_bf16*)out_plus, (zo_bf16*)out_minus, codes, step, zp, st);
+        return launch_fq_weight_t<zo_f16, float>(Wh, N, K, bits, group, s, eps, (float*)out_plus, (float*)out_minus, codes, step, zp, st);
+    }
+    const float* Wf = (const float*)W;
     if (dtype == ZO_T_BF16)
-        return launch_fq_weight_t<zo_bf16>(W, N, K, bits, group, s, eps, (zo_bf16*)out_plus, (zo_bf16*)out_minus, codes, step, zp, st);
-    return launch_fq_weight_t<float>(W, N, K, bits, group, s, eps, (float*)out_plus, (float*)out_minus, codes, step, zp, st);
+        return launch_fq_weight_t<float, zo_bf16>(Wf, N, K, bits, group, s, eps, (zo_bf16*)out_plus, (zo_bf16*)out_minus, codes, step, zp, st);
+    return launch_fq_weight_t<float, float>(Wf, N, K, bits, group, s, eps, (float*)out_plus, (float*)out_minus, codes, step, zp, st);
 }
 
 // ---------------------------------------------------------------------------------------------

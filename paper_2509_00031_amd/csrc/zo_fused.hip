@@ -74,7 +74,7 @@ ZO_DEV void build_branch(const float (&w)[CH][8], const float (&z)[CH][8], float
     for (int c = 0; c < CH; ++c) af[c] = pack8(v[c]);
 }
 
-template <int CH, int GL, int J>
+template <typename TW, int CH, int GL, int J>
 __global__ __launch_bounds__(FW * 64) void zo_fq_gemm_fused_kernel(zo_fused_args a, zo_stream s)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
@@ -87,7 +87,7 @@ __global__ __launch_bounds__(FW * 64) void zo_fq_gemm_fused_kernel(zo_fused_args
     const int nslab = K / SLAB;
     // All J m-tiles are always computed (rows past M repeat row M - 1 and are never stored): the matrix
     // instructions sit in straight-line code, with no data-dependent branch between them and their readers.
-    const float* wrow = a.W + (int64_t)(n0 + n) * K + q * (CH * 8);
+    const TW* wrow = (const TW*)a.W + (int64_t)(n0 + n) * K + q * (CH * 8);
     const uint64_t blk_row = ((uint64_t)(n0 + n) * (uint64_t)K >> 3) + (uint64_t)(q * CH);
     const zo_bf16* X = (const zo_bf16*)a.X;
 
@@ -254,16 +254,22 @@ __global__ __launch_bounds__(256) void zo_fused_relayout_kernel(const zo_bf16* _
 // m-tiles computed by the kernel variant that serves M rows
 int tiles_for(int M) { return M <= 16 ? 1 : M <= 32 ? 2 : M <= 64 ? 4 : 8; }
 
-template <int CH, int GL, int J>
-hipError_t launch_one(const zo_fused_args& a, const zo_stream& s, hipStream_t st)
+template <typename TW, int CH, int GL, int J>
+hipError_t launch_w(const zo_fused_args& a, const zo_stream& s, hipStream_t st)
 {
     constexpr int lds = FW * 2 * J * 1024;
     if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void*)zo_fq_gemm_fused_kernel<CH, GL, J>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        hipError_t e = hipFuncSetAttribute((const void*)zo_fq_gemm_fused_kernel<TW, CH, GL, J>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
     }
-    zo_fq_gemm_fused_kernel<CH, GL, J><<<dim3(a.N / 16), FW * 64, lds, st>>>(a, s);
+    zo_fq_gemm_fused_kernel<TW, CH, GL, J><<<dim3(a.N / 16), FW * 64, lds, st>>>(a, s);
     return hipGetLastError();
+}
+
+template <int CH, int GL, int J>
+hipError_t launch_one(const zo_fused_args& a, const zo_stream& s, hipStream_t st)
+{
+    return a.wdtype == ZO_W_F16 ? launch_w<zo_f16, CH, GL, J>(a, s, st) : launch_w<float, CH, GL, J>(a, s, st);
 }
 
 template <int CH, int GL>

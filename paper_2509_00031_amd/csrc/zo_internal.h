@@ -4,7 +4,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
-enum { ZO_T_F32 = 0, ZO_T_BF16 = 1 };
+enum { ZO_T_F32 = 0, ZO_T_BF16 = 1 };          // storage type of activations / GEMM operands
+enum { ZO_W_F32 = 0, ZO_W_F16 = 1 };           // storage type of the master weights (IEEE binary32 / binary16)
 
 static inline size_t zo_tsize(int dtype) { return dtype == ZO_T_BF16 ? 2 : 4; }
 
@@ -23,14 +24,18 @@ struct zo_multi_seeds { uint32_t k0[ZO_MAX_DIRECTIONS_INTERNAL], k1[ZO_MAX_DIREC
 hipError_t zo_launch_update_multi(float* w, int64_t numel, const zo_multi_seeds& ms, int32_t q, int32_t tid,
                                   const float* coeff_dev, int32_t coeff_stride, hipStream_t st);
 
+// binary16 masters: the q terms in fp32, then one rounding (stochastic != 0: driven by the rounding stream of seed 0)
+hipError_t zo_launch_update_f16(void* w, int64_t numel, const zo_multi_seeds& ms, int32_t q, int32_t tid,
+                                const float* coeff_dev, int32_t coeff_stride, int32_t stochastic, hipStream_t st);
+
 // ---- weight fake-quantizer ---------------------------------------------------------------------
 // Emits Q(W + eps u) into out_plus and/or Q(W - eps u) into out_minus (storage type dtype); either
 // may be NULL.  bits = 0: perturbed weights, not quantized.  Debug outputs describe the '+' branch.
 bool zo_fq_weight_supported(int32_t K, int32_t bits, int32_t group);
-hipError_t zo_launch_fq_weight(const float* W, int32_t N, int32_t K, int32_t bits, int32_t group,
+hipError_t zo_launch_fq_weight(const void* W, int32_t N, int32_t K, int32_t bits, int32_t group,
                                uint64_t seed, int32_t tid, float eps, int dtype,
                                void* out_plus, void* out_minus,
-                               uint8_t* codes, float* step, int32_t* zp, hipStream_t st);
+                               uint8_t* codes, float* step, int32_t* zp, hipStream_t st, int wdtype = ZO_W_F32);
 
 // ---- frozen weights (lightweight variant): packed 4-bit codes, binary16 steps, int16 zero points ----
 // group: a power of two in 8 .. 512 that divides K
@@ -82,7 +87,8 @@ struct zo_fused_args {
     const void* X;              // bf16 [nb][M][K] (strideX elements between the branches, may be 0)
     const void* Xfrag;          // NULL, or the same activations re-laid out by zo_launch_fused_relayout (same bits / group)
     int64_t strideXfrag;
-    const float* W;             // fp32 master [N][K] of ONE tensor (element index = n*K + k in its stream)
+    const void* W;              // master [N][K] of ONE tensor (element index = n*K + k in its stream), fp32 or binary16
+    int32_t wdtype;             // ZO_W_*
     void* Y;                    // bf16 or fp32 [M][ldY], already offset to the tensor's first output column
     const float* bias;          // fp32 [N] (per branch: strideBias) or NULL
     const void* residual;       // bf16, same indexing as Y, or NULL
@@ -103,9 +109,9 @@ hipError_t zo_launch_fused_relayout(const void* X, int64_t strideX, int32_t M, i
 
 // ---- the rest of the decoder forward -----------------------------------------------------------
 // x[t] = rt(fma(eps, u(tok row), tok_emb[id]) (+ fma(eps, u(pos row), pos_emb[t % S])))
-hipError_t zo_launch_embed(const int32_t* ids, const float* tok_emb, const float* pos_emb, void* out,
+hipError_t zo_launch_embed(const int32_t* ids, const void* tok_emb, const void* pos_emb, void* out,
                            int32_t M, int32_t S, int32_t d, int32_t vocab, uint64_t seed, int32_t tid_tok, int32_t tid_pos,
-                           float eps_tok, float eps_pos, int dtype, hipStream_t st);
+                           float eps_tok, float eps_pos, int dtype, hipStream_t st, int wdtype = ZO_W_F32);
 // RMSNorm (beta = NULL) or LayerNorm; gamma/beta are already perturbed fp32 vectors
 hipError_t zo_launch_norm(const void* x, const float* gamma, const float* beta, void* out,
                           int32_t M, int32_t d, float eps, int dtype, hipStream_t st);

@@ -18,9 +18,9 @@ static inline zo_stream make_stream(uint64_t seed, int32_t tid)
 // embedding: x[t][:] = rt( theta'_tok[id[t]][:] (+ theta'_pos[t % S][:]) ), theta' = fma(eps, u, theta)
 // Only the gathered rows are perturbed (the table itself is never rewritten).
 // ---------------------------------------------------------------------------------------------
-template <typename T>
-__global__ __launch_bounds__(256) void zo_embed_kernel(const int32_t* __restrict__ ids, const float* __restrict__ tok,
-                                                       const float* __restrict__ pos, T* __restrict__ out, int M, int S, int d, int vocab,
+template <typename TW, typename T>
+__global__ __launch_bounds__(256) void zo_embed_kernel(const int32_t* __restrict__ ids, const TW* __restrict__ tok,
+                                                       const TW* __restrict__ pos, T* __restrict__ out, int M, int S, int d, int vocab,
                                                        zo_stream st, zo_stream sp, float eps_tok, float eps_pos)
 {
     const int t = blockIdx.x;
@@ -50,17 +50,26 @@ __global__ __launch_bounds__(256) void zo_embed_kernel(const int32_t* __restrict
     }
 }
 
-hipError_t zo_launch_embed(const int32_t* ids, const float* tok_emb, const float* pos_emb, void* out,
+template <typename TW>
+static void launch_embed_w(const int32_t* ids, const void* tok_emb, const void* pos_emb, void* out, int32_t M, int32_t S, int32_t d,
+                           int32_t vocab, uint64_t seed, int32_t tid_tok, int32_t tid_pos, float eps_tok, float eps_pos, int dtype,
+                           hipStream_t st)
+{
+    if (dtype == ZO_T_BF16)
+        zo_embed_kernel<TW, zo_bf16><<<M, 256, 0, st>>>(ids, (const TW*)tok_emb, (const TW*)pos_emb, (zo_bf16*)out, M, S, d, vocab,
+                                                        make_stream(seed, tid_tok), make_stream(seed, tid_pos), eps_tok, eps_pos);
+    else
+        zo_embed_kernel<TW, float><<<M, 256, 0, st>>>(ids, (const TW*)tok_emb, (const TW*)pos_emb, (float*)out, M, S, d, vocab,
+                                                      make_stream(seed, tid_tok), make_stream(seed, tid_pos), eps_tok, eps_pos);
+}
+
+hipError_t zo_launch_embed(const int32_t* ids, const void* tok_emb, const void* pos_emb, void* out,
                            int32_t M, int32_t S, int32_t d, int32_t vocab, uint64_t seed, int32_t tid_tok, int32_t tid_pos,
-                           float eps_tok, float eps_pos, int dtype, hipStream_t st)
+                           float eps_tok, float eps_pos, int dtype, hipStream_t st, int wdtype)
 {
     if (M == 0) return hipSuccess;
-    if (dtype == ZO_T_BF16)
-        zo_embed_kernel<zo_bf16><<<M, 256, 0, st>>>(ids, tok_emb, pos_emb, (zo_bf16*)out, M, S, d, vocab,
-                                                    make_stream(seed, tid_tok), make_stream(seed, tid_pos), eps_tok, eps_pos);
-    else
-        zo_embed_kernel<float><<<M, 256, 0, st>>>(ids, tok_emb, pos_emb, (float*)out, M, S, d, vocab,
-                                                  make_stream(seed, tid_tok), make_stream(seed, tid_pos), eps_tok, eps_pos);
+    if (wdtype == ZO_W_F16) launch_embed_w<zo_f16>(ids, tok_emb, pos_emb, out, M, S, d, vocab, seed, tid_tok, tid_pos, eps_tok, eps_pos, dtype, st);
+    else launch_embed_w<float>(ids, tok_emb, pos_emb, out, M, S, d, vocab, seed, tid_tok, tid_pos, eps_tok, eps_pos, dtype, st);
     return hipGetLastError();
 }
 

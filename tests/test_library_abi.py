@@ -61,3 +61,21 @@ def test_linear_decay_is_the_oracles(lib):
     for lr0, T in ((5e-7, 10000), (1e-8, 10000), (1e-2, 7)):
         for t in (0, 1, T // 3, T // 2, T - 1):
             assert np.float32(zo.zo_lr_linear_decay(lr0, t, T)) == orc.lr_linear_decay(lr0, t, T)
+
+
+def test_master_storage_accounting(lib):
+    """2 bytes per parameter with binary16 masters: the OPT-shaped models of the efficiency section's table need 2.8 / 5.6 /
+    13.7 / 26.2 GB of master storage (the table prints 3.1 / 6.1 / 14.2 / 26.6 GB for "weights only" memory, whatever the
+    batch size).  Host function; the 2.7B shape is given 20 heads of 128 instead of 32 of 80 (same parameter count)."""
+    from paper_2509_00031_amd import binding as zo
+    shapes = {"1.3b": (24, 2048, 32, 8192), "2.7b": (32, 2560, 20, 10240), "6.7b": (32, 4096, 32, 16384), "13b": (40, 5120, 40, 20480)}
+    printed = {"1.3b": 3.1, "2.7b": 6.1, "6.7b": 14.2, "13b": 26.6}
+    for name, (L, d, H, f) in shapes.items():
+        kw = dict(n_layers=L, d_model=d, n_heads=H, d_ffn=f, vocab=50272, max_seq=2048, w_bits=2, w_group=128, a_bits=16)
+        cfg32 = zo.make_config(zo.ARCH_OPT, **kw)
+        b16 = zo.zo_master_bytes(zo.make_config(zo.ARCH_OPT, master_dtype=zo.MASTER_F16, **kw))
+        assert zo.zo_master_bytes(cfg32) == 2 * b16
+        assert b16 == 2 * sum(zo.zo_param_numel(cfg32, i) for i in range(zo.zo_num_params(cfg32)))
+        assert 0.85 * printed[name] < b16 / 1e9 < printed[name], (name, b16)
+    assert zo.zo_master_bytes(zo.make_config(zo.ARCH_LLAMA, n_layers=1, d_model=64, n_heads=2, d_ffn=128, vocab=64, max_seq=8,
+                                             learn_clip=1, master_dtype=zo.MASTER_F16)) == -1

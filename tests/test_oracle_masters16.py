@@ -111,3 +111,21 @@ def test_step_with_binary16_masters_reads_the_stored_values():
     assert (lp, lm, g) == (lp2, lm2, g2)
     for a, b in zip(p16, as32):
         assert a.dtype == np.float16 and np.array_equal(a, b.astype(np.float16))   # one rounding of the same fp32 result
+
+
+def test_multi_direction_update_rounds_once():
+    # q terms in fp32, one rounding: for q = 1 the same as the single update; for q > 1 not the same as rounding
+    # after every term (which loses the small ones), and within one spacing of the exact sum
+    w0 = synth.weights((3000,), 305).astype(np.float16)
+    seeds, cs = [4, 5, 6], [np.float32(2e-4), np.float32(-1e-4), np.float32(3e-4)]
+    for st in (False, True):
+        a = orc.update_multi(w0.copy(), seeds[:1], 2, cs[:1], st)
+        assert np.array_equal(a, orc.update(w0.copy(), seeds[0], 2, cs[0], st))
+    once = orc.update_multi(w0.copy(), seeds, 2, cs)
+    seq = w0.copy()
+    for s, c in zip(seeds, cs):
+        orc.update(seq, s, 2, c)
+    assert not np.array_equal(once, seq)
+    exact = w0.astype(np.float64) - sum(float(c) * orc.normal(s, 2, 3000).astype(np.float64) for s, c in zip(seeds, cs))
+    assert np.all(np.abs(once.astype(np.float64) - exact) <= 2.0 ** -11 * np.abs(exact) + 2.0 ** -25)
+    assert np.abs(once.astype(np.float64) - exact).sum() < np.abs(seq.astype(np.float64) - exact).sum()
