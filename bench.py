@@ -42,6 +42,11 @@ WORKLOADS = {
                                    w_bits=4, w_group=64, a_bits=8, B=1, S=128),
     "llama7b_w4a8_g64_1x32": dict(arch="llama", n_layers=32, d_model=4096, n_heads=32, d_ffn=11008, vocab=32000,
                                   w_bits=4, w_group=64, a_bits=8, B=1, S=32),
+    # the lightweight variant in the same regime: frozen linears expanded from their packed codes inside the kernel
+    "llama13b_lightweight_w4a4_g128_1x128": dict(arch="llama", n_layers=40, d_model=5120, n_heads=40, d_ffn=13824,
+                                                 vocab=32000, w_bits=4, w_group=128, a_bits=4, B=1, S=128, lightweight=1),
+    "llama13b_lightweight_w4a4_g128_1x32": dict(arch="llama", n_layers=40, d_model=5120, n_heads=40, d_ffn=13824,
+                                                vocab=32000, w_bits=4, w_group=128, a_bits=4, B=1, S=32, lightweight=1),
     "tiny_w4a16_g64_8x128": dict(arch="llama", n_layers=4, d_model=512, n_heads=8, d_ffn=2048, vocab=4096,
                                  w_bits=4, w_group=64, a_bits=16, B=8, S=128),
 }
@@ -229,7 +234,20 @@ def main():
                            "flops_per_launch": flops_per_launch}
         res["gemm_tflops"] = achieved
         fused_ms, fused_launches = prof["fused_linear"]
-        if fused_launches > 0:
+        int4_ms, int4_launches = prof["fused_int4_linear"]
+        if int4_launches > 0 and int4_ms >= fused_ms:
+            # lightweight variant at a small token count: the kernel that expands the packed codes dominates; it moves
+            # 0.5 B of codes per weight (+ 4 B per group of step and zero point) and nothing else of that order
+            d, f, L, g = w["d_model"], w["d_ffn"], w["n_layers"], w["w_group"]
+            packed_weights = L * (2 * d * d + 3 * d * f)              # wk, wo, gate, up, down
+            avg_ms = int4_ms / int4_launches
+            bytes_per_launch = (0.5 + 4.0 / g) * packed_weights * args.steps / int4_launches
+            ach = bytes_per_launch / (avg_ms * 1e-3) / 1e9
+            res["roofline"] = {"bound": "hbm", "kernel": "zo_int4_gemm_fused_kernel", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                               "frac": ach / PEAK_HBM_GBS, "traffic": None, "launches": int4_launches, "avg_launch_ms": avg_ms,
+                               "bytes_per_launch": bytes_per_launch}
+            res["gemm_tflops"] = gflops * args.steps / ((fused_ms + int4_ms) * 1e-3) / 1e12
+        elif fused_launches > 0:
             # small-M route: every linear went through the fused kernel, which is bound by the plain-ALU tile build
             d, f, V, L = w["d_model"], w["d_ffn"], w["vocab"], w["n_layers"]
             lin_params = L * (4 * d * d + (3 if w["arch"] == "llama" else 2) * d * f) + V * d

@@ -67,8 +67,9 @@ typedef struct {
     int32_t learn_smooth;/* 1 = channel-wise smoothing (Eq. 4): every distinct input activation of the
                             quantized linears gets two more trainable fp32 tensors [K] -- s and delta;
                             needs learn_clip = 1 and a_bits < 16 */
-    int32_t no_fused;    /* 0 = quantized linears of a forward over at most 128 tokens (bf16 storage, groups of
-                            8..128, no learned / packed tensors) build their weight tiles inside the GEMM kernel;
+    int32_t no_fused;    /* 0 = the linears of a forward over at most 128 tokens (bf16 storage, groups of 8..128 -- 32..128
+                            when packed tensors are attached --, no learned tensors) build their weight tiles inside
+                            the GEMM kernel, from the masters or from the packed codes;
                             1 = always quantize once into the workspace and run the plain GEMM */
     int32_t master_dtype;/* ZO_MASTER_*: storage type of every tensor of the parameter list.  ZO_MASTER_F16 = IEEE binary16,
                             the 2 bytes per parameter that the memory table of the efficiency section implies: a
@@ -167,7 +168,8 @@ float zo_lr_linear_decay(float lr0, int64_t t, int64_t T);
  * branches of Eq. 2 batched in it). */
 enum { ZO_PROF_GEMM = 0, ZO_PROF_WEIGHT_QUANT = 1, ZO_PROF_ACT_QUANT = 2, ZO_PROF_ATTENTION = 3,
        ZO_PROF_UPDATE = 4, ZO_PROF_OTHER = 5, ZO_PROF_FUSED = 6 /* a group = one launch of the fused small-M kernel (one parameter tensor) */,
-       ZO_PROF_CATEGORIES = 7 };
+       ZO_PROF_FUSED_INT4 = 7 /* a group = one launch of the small-M kernel that expands packed codes */,
+       ZO_PROF_CATEGORIES = 8 };
 zo_status zo_profile_begin(zo_ctx* ctx);
 zo_status zo_profile_end(zo_ctx* ctx, float* ms_host, int32_t* launches_host);
 
@@ -301,6 +303,22 @@ zo_status zo_attach_frozen_int4(zo_ctx* ctx, int32_t index, const void* codes_de
 zo_status zo_linear_frozen_int4(const void* X_dev, const void* codes_dev, const void* step_f16_dev, const int16_t* zp_dev,
                                 const float* bias_dev, void* Y_dev, int32_t M, int32_t N, int32_t K, int32_t group,
                                 int32_t a_bits, int32_t a_sym, int32_t dtype, void* scratch_dev, void* hip_stream);
+
+/* The same layer for a small token count (1 <= M <= 128) and both branches at once, fused: the operand w^ is expanded
+ * from the packed codes in registers, in matrix-core operand layout (0.5 B of HBM traffic per weight, nothing
+ * written but Y); the two branches share it.  Also the linear of plain inference on the packed model.
+ *   Xp, Xm dev bf16 [M][K] (already quantized per token if the configuration asks for it); Ym = NULL: one branch
+ *   Yp, Ym dev [M][N], fp32 if out_f32 else bf16; bias dev fp32 [N] or NULL
+ *   group in {32, 64, 128, 256, 512} dividing K, N a multiple of 16; otherwise ZO_ESHAPE
+ *   scratch dev, NULL or zo_linear_frozen_fused_scratch_bytes(M, N, K, group) bytes.  Without scratch a workgroup covers
+ *   16 channels and all of K (every workgroup then reads all of X: slow beyond a few tokens); with it the activations
+ *   are copied into fragment order, a workgroup covers 128 channels and one of several K ranges, and the partial sums
+ *   (fp32, in the scratch) are added in a fixed order by a second kernel.
+ * Same arithmetic per weight as zo_linear_frozen_int4; only the order of the fp32 accumulation differs. */
+size_t zo_linear_frozen_fused_scratch_bytes(int32_t M, int32_t N, int32_t K, int32_t group);
+zo_status zo_linear_frozen_int4_fused(const void* Xp_dev, const void* Xm_dev, const void* codes_dev, const void* step_f16_dev,
+                                      const int16_t* zp_dev, const float* bias_dev, void* Yp_dev, void* Ym_dev, int32_t M, int32_t N,
+                                      int32_t K, int32_t group, int32_t out_f32, void* scratch_dev, void* hip_stream);
 
 /* Plain GEMM of the path, Y[M][N] = X[M][K] * W[N][K]^T with fp32 accumulation, operands and
  * output in storage type dtype (the contraction every quantized linear runs after both operands

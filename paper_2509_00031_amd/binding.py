@@ -26,8 +26,8 @@ EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "
            "zo_gemm_nt", "zo_debug_buffer", "zo_profile_begin", "zo_profile_end", "zo_attention_causal",
            "zo_attention_scratch_bytes", "zo_pack_weight_int4", "zo_attach_frozen_int4", "zo_linear_frozen_int4", "zo_gemm_nt_fused", "zo_init_learned_params", "zo_step_groups", "zo_update_groups",
            "zo_debug_quant_weight_learned", "zo_debug_smooth_bias", "zo_linear_fakequant_fused", "zo_linear_fused_scratch_bytes",
-           "zo_step_multi", "zo_update_multi", "zo_lr_linear_decay", "zo_update_tensor_f16", "zo_master_bytes"]
-PROF_NAMES = ["gemm", "weight_quant", "act_quant", "attention", "update", "other", "fused_linear"]
+           "zo_step_multi", "zo_update_multi", "zo_lr_linear_decay", "zo_update_tensor_f16", "zo_master_bytes", "zo_linear_frozen_int4_fused", "zo_linear_frozen_fused_scratch_bytes"]
+PROF_NAMES = ["gemm", "weight_quant", "act_quant", "attention", "update", "other", "fused_linear", "fused_int4_linear"]
 
 
 class zo_config(C.Structure):
@@ -71,6 +71,9 @@ _lib.zo_linear_fakequant.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32,
 _lib.zo_linear_fakequant_fused.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _u64, _i32, _f32, _i32, _vp, _vp]
 _lib.zo_linear_fused_scratch_bytes.argtypes = [_i32, _i32]
 _lib.zo_linear_fused_scratch_bytes.restype = _sz
+_lib.zo_linear_frozen_fused_scratch_bytes.argtypes = [_i32, _i32, _i32, _i32]
+_lib.zo_linear_frozen_fused_scratch_bytes.restype = _sz
+_lib.zo_linear_frozen_int4_fused.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp]
 _lib.zo_gemm_nt.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp]
 _lib.zo_debug_buffer.argtypes = [_vp, _i32, _i32, C.POINTER(_vp), C.POINTER(_sz)]
 _lib.zo_attention_causal.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i64, _i32, _vp, _vp]
@@ -378,6 +381,21 @@ def zo_linear_frozen_int4(X, packed, bias, a_bits, a_sym=0):
     off = (M * K * es + 255) // 256 * 256
     what = scratch[off:off + N * K * es].view(X.dtype).view(N, K)
     return Y, what
+
+
+def zo_linear_frozen_int4_fused(Xp, Xm, packed, bias=None, out_f32=False, relayout=False):
+    """Both branches (Xm given) or one; returns (Yp, Ym).  relayout: lend the call its scratch buffer (split-K form)."""
+    M, K = Xp.shape
+    N = packed.N
+    odt = torch.float32 if out_f32 else torch.bfloat16
+    Y = torch.empty((2 if Xm is not None else 1, M, N), dtype=odt, device=Xp.device)
+    scratch = (torch.empty(_lib.zo_linear_frozen_fused_scratch_bytes(M, N, K, packed.group), dtype=torch.uint8, device=Xp.device)
+               if relayout else None)
+    _check(_lib.zo_linear_frozen_int4_fused(Xp.data_ptr(), _ptr(Xm), packed.codes.data_ptr(), packed.step_f16.data_ptr(),
+                                            packed.zp.data_ptr(), _ptr(bias), Y[0].data_ptr(),
+                                            Y[1].data_ptr() if Xm is not None else None, M, N, K, packed.group, int(out_f32),
+                                            _ptr(scratch), _stream()), "zo_linear_frozen_int4_fused")
+    return Y[0], (Y[1] if Xm is not None else None)
 
 
 def zo_gemm_nt(X, W, Y=None):

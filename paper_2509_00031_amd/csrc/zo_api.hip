@@ -224,6 +224,9 @@ struct zo_ctx {
     struct frozen_int4 { const void* codes; const void* step; const int16_t* zp; int group; };
     std::vector<frozen_int4> frozen;
     int n_packed = 0;     // tensors with packed storage attached
+    // the packed tensors can share a fused launch sequence with the trainable ones: their group gives the same
+    // slab width as the configuration's (so one fragment-ordered copy of the activations serves all tensors of a GEMM)
+    bool packed_fusable = true;
     char* ws;
     size_t ws_bytes;
     int max_B, max_S;
@@ -292,14 +295,18 @@ struct fwd {
     bool sm_on = false;   // the activation being quantized next is smoothed (set by smooth_prepare)
     // small-M route: the tensors of the next GEMM whose tiles are built inside the fused kernel instead of
     // being written to the operand buffers (all of them or none: eligibility depends on the shared shape only)
-    struct pend { int t; int64_t row0; bool quantize; };
+    struct pend { int t; int64_t row0; bool quantize; bool packed; };
     pend pending[4];
     int npend = 0;
+    int nweights = 0;     // operand tensors requested since the last GEMM (deferred or materialised)
     bool fused_ok(int t, bool quantize) const
     {
         const zo_config& cfg = c->cfg;
-        if (cfg.no_fused || cfg.act_dtype != ZO_ACT_BF16 || cfg.learn_clip || c->n_packed > 0) return false;
+        if (cfg.no_fused || cfg.act_dtype != ZO_ACT_BF16 || cfg.learn_clip) return false;
         const param_desc& p = c->desc[t];
+        if (c->frozen[t].codes)                          // stored codes: expanded inside the kernel
+            return c->packed_fusable && zo_int4_fused_supported(M, (int)p.rows, (int)p.cols, c->frozen[t].group);
+        if (c->n_packed > 0 && !c->packed_fusable) return false;
         const int64_t g = cfg.w_group > 0 ? cfg.w_group : p.cols;
         return zo_fused_supported(M, (int)p.rows, (int)p.cols, quantize ? cfg.w_bits : 0, (int)g);
     }
@@ -314,8 +321,9 @@ struct fwd {
     zo_status weights(int t, int64_t row0, bool quantize, bool shared = false)
     {
         const param_desc& p = c->desc[t];
+        nweights += 1;
         if (npend < 4 && fused_ok(t, quantize)) {
-            pending[npend++] = pend{t, row0, quantize};
+            pending[npend++] = pend{t, row0, quantize, c->frozen[t].codes != nullptr};
             return ZO_OK;
         }
         const size_t ts = zo_tsize(dt());
@@ -430,11 +438,19 @@ struct fwd {
     zo_status gemm(size_t layout::per_branch::*in, size_t layout::per_branch::*out, int N, int K, bool bias, bool relu,
                    bool residual, bool out_f32 = false, bool w_shared = false)
     {
+        const int requested = nweights;
+        nweights = 0;
+        if (npend > 0 && npend != requested) {           // cannot happen: the tensors of one GEMM share shape and route
+            npend = 0;
+            return fail(c, ZO_EUNSUPPORTED, "tensors of one GEMM took different routes");
+        }
         if (npend > 0) {
             const int64_t ts_ = (int64_t)zo_tsize(dt());
             // from a few m-tiles on the kernel is fed from a fragment-ordered copy of the activations, kept in the
             // (otherwise idle) operand buffers
-            const bool relayout = M > 32 && zo_fused_relayout_bytes(M, K) <= c->L.what_bytes;
+            bool any_packed = false;
+            for (int i = 0; i < npend; ++i) any_packed = any_packed || pending[i].packed;
+            const bool relayout = (M > 32 || any_packed) && zo_fused_relayout_bytes(M, K) <= c->L.what_bytes;
             const int64_t sxf = (int64_t)(c->L.what[1] - c->L.what[0]) / 2;
             if (relayout) {
                 prof_scope ps(c, ZO_PROF_OTHER);
@@ -465,7 +481,17 @@ struct fwd {
                 f.eps = eps_of(pe.t);
                 f.relu = relu;
                 f.out_f32 = out_f32;
-                prof_scope ps(c, ZO_PROF_FUSED);             // one bracket per kernel launch
+                prof_scope ps(c, pe.packed ? ZO_PROF_FUSED_INT4 : ZO_PROF_FUSED);   // one bracket per kernel launch
+                if (pe.packed) {
+                    const zo_ctx::frozen_int4& fz = c->frozen[pe.t];
+                    f.codes = fz.codes; f.step16 = fz.step; f.zp = fz.zp; f.group = fz.group;
+                    // split-K form when its partial sums fit into the second (idle) operand buffer
+                    if (relayout && zo_int4_splitk_scratch_bytes(M, f.N, K, f.group) <= c->L.what_bytes)
+                        ZO_HIP(c, zo_launch_int4_gemm_splitk(f, at(c->L.what[1]), c->st));
+                    else
+                        ZO_HIP(c, zo_launch_int4_gemm_fused(f, c->st));
+                    continue;
+                }
                 ZO_HIP(c, zo_launch_fq_gemm_fused(f, seed, pe.t, c->st));
             }
             npend = 0;
@@ -776,6 +802,11 @@ zo_status zo_attach_frozen_int4(zo_ctx* ctx, int32_t index, const void* codes, c
     if (!zo_int4_group_supported((int)ctx->desc[index].cols, group)) return fail(ctx, ZO_ESHAPE, "group must be a power of two in 8..512 dividing the in-features");
     if (!aligned16(codes) || ((uintptr_t)step_f16 & 1) || ((uintptr_t)zp & 1)) return fail(ctx, ZO_EALIGN, "packed storage misaligned");
     if (!ctx->frozen[index].codes) ctx->n_packed += 1;
+    {
+        const int cg = ctx->cfg.w_group > 0 ? ctx->cfg.w_group : 0;
+        auto slab = [](int g) { return g >= 128 ? 128 : g; };
+        if (ctx->cfg.w_bits == 0 || cg < 32 || cg > 128 || slab(cg) != slab(group)) ctx->packed_fusable = false;
+    }
     ctx->frozen[index] = zo_ctx::frozen_int4{codes, step_f16, zp, group};
     return ZO_OK;
 }
@@ -1206,6 +1237,41 @@ zo_status zo_linear_frozen_int4(const void* X_dev, const void* codes_dev, const 
     a.X = xin; a.W = what; a.Y = Y_dev; a.bias = bias_dev;
     a.M = M; a.N = N; a.K = K; a.batch = 1; a.dtype = dtype;
     return zo_launch_gemm(a, st) == hipSuccess ? ZO_OK : ZO_EHIP;
+}
+
+zo_status zo_linear_frozen_int4_fused(const void* Xp_dev, const void* Xm_dev, const void* codes_dev, const void* step_f16_dev,
+                                      const int16_t* zp_dev, const float* bias_dev, void* Yp_dev, void* Ym_dev, int32_t M, int32_t N,
+                                      int32_t K, int32_t group, int32_t out_f32, void* scratch_dev, void* hip_stream)
+{
+    if (!Xp_dev || !codes_dev || !step_f16_dev || !zp_dev || !Yp_dev || M <= 0 || N <= 0 || K <= 0) return ZO_EINVAL;
+    if (Ym_dev && !Xm_dev) return ZO_EINVAL;
+    if (!zo_int4_fused_supported(M, N, K, group)) return ZO_ESHAPE;
+    if (!aligned16(Xp_dev) || !aligned16(Xm_dev) || !aligned16(codes_dev) || !aligned16(bias_dev) || !aligned16(Yp_dev) ||
+        !aligned16(Ym_dev) || !aligned16(scratch_dev) || ((uintptr_t)step_f16_dev & 1) || ((uintptr_t)zp_dev & 1))
+        return ZO_EALIGN;
+    zo_fused_args f{};
+    f.X = Xp_dev; f.codes = codes_dev; f.step16 = step_f16_dev; f.zp = zp_dev; f.Y = Yp_dev; f.bias = bias_dev;
+    f.M = M; f.N = N; f.K = K; f.nb = Ym_dev ? 2 : 1; f.ldY = N; f.group = group; f.bits = 4; f.out_f32 = out_f32 ? 1 : 0;
+    if (Ym_dev) {
+        f.strideX = ((const char*)Xm_dev - (const char*)Xp_dev) / 2;
+        f.strideY = ((const char*)Ym_dev - (const char*)Yp_dev) / (out_f32 ? 4 : 2);
+    }
+    if (scratch_dev) {
+        // with scratch: fragment-ordered activations, 128 channels per workgroup, K split over workgroups
+        f.Xfrag = scratch_dev;
+        f.strideXfrag = (int64_t)(align_up(zo_fused_relayout_bytes(M, K)) / 2);
+        if (zo_launch_fused_relayout(f.X, f.strideX, M, K, f.nb, 4, group, scratch_dev, f.strideXfrag, (hipStream_t)hip_stream) != hipSuccess)
+            return ZO_EHIP;
+        void* partials = (char*)scratch_dev + zo_linear_fused_scratch_bytes(M, K);
+        return zo_launch_int4_gemm_splitk(f, partials, (hipStream_t)hip_stream) == hipSuccess ? ZO_OK : ZO_EHIP;
+    }
+    return zo_launch_int4_gemm_fused(f, (hipStream_t)hip_stream) == hipSuccess ? ZO_OK : ZO_EHIP;
+}
+
+size_t zo_linear_frozen_fused_scratch_bytes(int32_t M, int32_t N, int32_t K, int32_t group)
+{
+    if (M <= 0 || N <= 0 || K <= 0 || group <= 0) return 0;
+    return zo_linear_fused_scratch_bytes(M, K) + align_up(zo_int4_splitk_scratch_bytes(M, N, K, group));
 }
 
 size_t zo_attention_scratch_bytes(int32_t B, int32_t S, int32_t H, int32_t dh, int32_t dtype)

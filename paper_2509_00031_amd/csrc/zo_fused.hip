@@ -74,6 +74,68 @@ ZO_DEV void build_branch(const float (&w)[CH][8], const float (&z)[CH][8], float
     for (int c = 0; c < CH; ++c) af[c] = pack8(v[c]);
 }
 
+// bias / ReLU / residual and one rounding for the four outputs (m, nn .. nn + 3) of branch b
+__device__ __forceinline__ void store_outputs(const zo_fused_args& a, f32x4 v, int b, int m, int nn)
+{
+    if (m >= a.M) return;
+    if (a.bias) {
+        const float4 b4 = *reinterpret_cast<const float4*>(a.bias + b * a.strideBias + nn);
+        v[0] += b4.x; v[1] += b4.y; v[2] += b4.z; v[3] += b4.w;
+    }
+    if (a.relu) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.0f);
+    }
+    const int64_t off = (int64_t)m * a.ldY + nn;
+    if (a.residual) {
+        const uint2 r2 = *reinterpret_cast<const uint2*>((const zo_bf16*)a.residual + b * a.strideRes + off);
+        v[0] += zo_bf16_lo(r2.x); v[1] += zo_bf16_hi(r2.x);
+        v[2] += zo_bf16_lo(r2.y); v[3] += zo_bf16_hi(r2.y);
+    }
+    if (a.out_f32) {
+        *reinterpret_cast<float4*>((float*)a.Y + b * a.strideY + off) = make_float4(v[0], v[1], v[2], v[3]);
+    } else {
+        uint2 o;
+        o.x = zo_pack_bf16x2(v[0], v[1]);
+        o.y = zo_pack_bf16x2(v[2], v[3]);
+        *reinterpret_cast<uint2*>((zo_bf16*)a.Y + b * a.strideY + off) = o;
+    }
+}
+
+// Tail shared by the two kernels of this file: the partial accumulators of the FW waves are added in wave order
+// through LDS, then bias / ReLU / residual and one rounding.
+template <int J>
+__device__ __forceinline__ void reduce_and_store(const zo_fused_args& a, f32x4 (&acc)[2][J], f32x4* red, int wave, int lane, int n0)
+{
+    const int n = lane & 15, q = lane >> 4;
+    const int nb = a.nb;
+    // The accumulators are read next.  The compiler inserts the wait states between a matrix instruction and a
+    // reader of its result; an earlier form of this loop, with the instructions of a tile under a run-time
+    // condition and the accumulators copied right after the branch that joined the paths, returned three of
+    // every four outputs stale.  The loop is straight-line now; the longest such wait (19 states) is spelled
+    // out as well, once per launch.
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+    // partial accumulators -> LDS, then tile t = b * J + j is summed over the waves in order by wave t % FW
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int j = 0; j < J; ++j)
+            if (b < nb) red[((wave * 2 + b) * J + j) * 64 + lane] = acc[b][j];
+    __syncthreads();
+    for (int t = wave; t < 2 * J; t += FW) {
+        const int b = t / J, j = t % J;
+        if (b >= nb) continue;
+        f32x4 v = red[((0 * 2 + b) * J + j) * 64 + lane];
+        for (int wv = 1; wv < FW; ++wv) {
+            const f32x4 p = red[((wv * 2 + b) * J + j) * 64 + lane];
+            v[0] += p[0]; v[1] += p[1]; v[2] += p[2]; v[3] += p[3];
+        }
+        store_outputs(a, v, b, j * 16 + n, n0 + 4 * q);
+    }
+}
+
 template <typename TW, int CH, int GL, int J>
 __global__ __launch_bounds__(FW * 64) void zo_fq_gemm_fused_kernel(zo_fused_args a, zo_stream s)
 {
@@ -181,56 +243,271 @@ __global__ __launch_bounds__(FW * 64) void zo_fq_gemm_fused_kernel(zo_fused_args
         }
     }
 
-    // The accumulators are read next.  The compiler inserts the wait states between a matrix instruction and a
-    // reader of its result; an earlier form of this loop, with the instructions of a tile under a run-time
-    // condition and the accumulators copied right after the branch that joined the paths, returned three of
-    // every four outputs stale.  The loop is straight-line now; the longest such wait (19 states) is spelled
-    // out as well, once per launch.
-    __builtin_amdgcn_sched_barrier(0);
-    asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
-    __builtin_amdgcn_sched_barrier(0);
-    // partial accumulators -> LDS, then tile t = b * J + j is summed over the waves in order by wave t % FW
+    reduce_and_store<J>(a, acc, red, wave, lane, n0);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same contraction for a frozen, pre-quantized linear (lightweight variant; also plain inference on the
+// packed model): Y[b] = X[b] * w^^T with w^ = (code - zp) * step expanded from the 4-bit codes in registers, in
+// operand layout, 0.5 B of HBM traffic per weight.  Both branches of Eq. 2 share the operand (no perturbation).
+// Lane (n, q) owns CH consecutive 32-bit words of codes (8 features each); a slab of 32*CH features lies inside
+// one quantization group (group = 32, 64 or a multiple of 128), whose binary16 step and int16 zero point every
+// lane of the row reads.  Same arithmetic per weight as zo_dequant_int4_kernel.
+// ---------------------------------------------------------------------------------------------
+template <int CH> ZO_DEV void load_words(const uint32_t* p, uint32_t (&w)[CH])
+{
+    if constexpr (CH == 4) {
+        const uint4 v = *reinterpret_cast<const uint4*>(p);
+        w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+    } else if constexpr (CH == 2) {
+        const uint2 v = *reinterpret_cast<const uint2*>(p);
+        w[0] = v.x; w[1] = v.y;
+    } else {
+        w[0] = *p;
+    }
+}
+
+template <int CH, int J>
+__global__ __launch_bounds__(FW * 64) void zo_int4_gemm_fused_kernel(zo_fused_args a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    f32x4* red = reinterpret_cast<f32x4*>(lds_raw);
+    constexpr int SLAB = 32 * CH;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = lane & 15, q = lane >> 4;
+    const int M = a.M, K = a.K, nb = a.nb;
+    const int n0 = blockIdx.x * 16;
+    const int nslab = K / SLAB;
+    const int G = K / a.group;
+    const uint32_t* crow = (const uint32_t*)a.codes + (((int64_t)(n0 + n) * K) >> 3) + q * CH;
+    const _Float16* srow = (const _Float16*)a.step16 + (int64_t)(n0 + n) * G;
+    const int16_t* zrow = a.zp + (int64_t)(n0 + n) * G;
+    const zo_bf16* X = (const zo_bf16*)a.X;
+
+    f32x4 acc[2][J];
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
-        for (int j = 0; j < J; ++j)
-            if (b < nb) red[((wave * 2 + b) * J + j) * 64 + lane] = acc[b][j];
-    __syncthreads();
-    for (int t = wave; t < 2 * J; t += FW) {
-        const int b = t / J, j = t % J;
-        if (b >= nb) continue;
-        f32x4 v = red[((0 * 2 + b) * J + j) * 64 + lane];
-        for (int wv = 1; wv < FW; ++wv) {
-            const f32x4 p = red[((wv * 2 + b) * J + j) * 64 + lane];
-            v[0] += p[0]; v[1] += p[1]; v[2] += p[2]; v[3] += p[3];
-        }
-        // lane holds outputs (m, n0 + 4 q .. + 3)
-        const int m = j * 16 + n;
-        if (m >= M) continue;
-        const int nn = n0 + 4 * q;
-        if (a.bias) {
-            const float4 b4 = *reinterpret_cast<const float4*>(a.bias + b * a.strideBias + nn);
-            v[0] += b4.x; v[1] += b4.y; v[2] += b4.z; v[3] += b4.w;
-        }
-        if (a.relu) {
+        for (int j = 0; j < J; ++j) acc[b][j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+
+    uint32_t words[CH], wnext[CH];
+    if (wave < nslab) load_words<CH>(crow + wave * (SLAB / 8), words);
+    for (int sl = wave; sl < nslab; sl += FW) {
+        const int k0 = sl * SLAB;
+        const zo_bf16* xcol = X + k0 + q * (CH * 8);
+        int mrow[J];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.0f);
+        for (int j = 0; j < J; ++j) {
+            const int m = j * 16 + n;
+            mrow[j] = m < M ? m : M - 1;
         }
-        const int64_t off = (int64_t)m * a.ldY + nn;
-        if (a.residual) {
-            const uint2 r2 = *reinterpret_cast<const uint2*>((const zo_bf16*)a.residual + b * a.strideRes + off);
-            v[0] += zo_bf16_lo(r2.x); v[1] += zo_bf16_hi(r2.x);
-            v[2] += zo_bf16_lo(r2.y); v[3] += zo_bf16_hi(r2.y);
+        const zo_bf16* xfrag = a.Xfrag ? (const zo_bf16*)a.Xfrag + ((int64_t)sl * J * CH * 64 + lane) * 8 : nullptr;
+        auto fragment = [&](int b, int j, int c) -> bf16x8 {
+            if (xfrag) return *reinterpret_cast<const bf16x8*>(xfrag + b * a.strideXfrag + (j * CH + c) * 512);
+            return *reinterpret_cast<const bf16x8*>(xcol + b * a.strideX + (int64_t)mrow[j] * K + c * 8);
+        };
+        if (sl + FW < nslab) load_words<CH>(crow + (sl + FW) * (SLAB / 8), wnext);
+        const int g = k0 / a.group;
+        const float st = (float)srow[g];
+        const int z = zrow[g];
+        bf16x8 af[CH];
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            float o[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) o[i] = (float)((int)((words[c] >> (4 * i)) & 15u) - z) * st;
+            af[c] = pack8(o);
         }
-        if (a.out_f32) {
-            *reinterpret_cast<float4*>((float*)a.Y + b * a.strideY + off) = make_float4(v[0], v[1], v[2], v[3]);
-        } else {
-            uint2 o;
-            o.x = zo_pack_bf16x2(v[0], v[1]);
-            o.y = zo_pack_bf16x2(v[2], v[3]);
-            *reinterpret_cast<uint2*>((zo_bf16*)a.Y + b * a.strideY + off) = o;
+#pragma unroll
+        for (int j = 0; j < J; ++j)
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+                if (b < nb) {
+#pragma unroll
+                    for (int c = 0; c < CH; ++c)
+                        acc[b][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[c], fragment(b, j, c), acc[b][j], 0, 0, 0);
+                }
+#pragma unroll
+        for (int c = 0; c < CH; ++c) words[c] = wnext[c];
+    }
+    reduce_and_store<J>(a, acc, red, wave, lane, n0);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Split-K form of the kernel above, for when the caller lends scratch memory.  With 16 channels per workgroup every
+// workgroup reads all of X (N/16 times in total, far more than the 0.5 B per weight of the codes), and with one
+// 16-channel operand per wave every matrix instruction needs a fresh 1 KB activation fragment.  Here
+//   * a workgroup = 4 waves covers 256 channels (wave w: 64 of them = four 16-channel operands per K step, so a
+//     fragment read from LDS feeds four matrix instructions) and one of KS ranges of K;
+//   * the activation fragments of a slab (already in fragment order in a.Xfrag) are copied global -> LDS by the load
+//     unit itself (16 B per lane, no staging registers), two stages, one barrier per slab;
+//   * a workgroup handles MT <= 8 m-tiles: both branches together while they fit (MT = nb * J), else one branch per
+//     workgroup (blockIdx.z), which expands the same codes twice;
+//   * every wave owns its outputs over the workgroup's K range: KS = 1 stores them directly, otherwise partial sums go
+//     to P[ks][b][m][n] (fp32) and zo_splitk_reduce_kernel adds the KS partials in order (no atomics).
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t lds_offset_of(const void* p)
+{
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+// one wave-level 1 KB copy: lane fetches 16 bytes at base + voff, LDS destination dst + lane * 16
+__device__ __forceinline__ void lds_copy16(const void* base, uint32_t voff, uint32_t dst)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2\n" ::"s"(dst), "v"(voff), "s"(base) : "memory");
+}
+
+constexpr int SW = 4;            // waves per workgroup of the split-K kernel
+constexpr int SRG = 4;           // 16-channel operands per wave
+
+template <int CH, int MT>
+__global__ __launch_bounds__(SW * 64) void zo_int4_gemm_splitk_kernel(zo_fused_args a, float* __restrict__ P, int KS, int J)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    constexpr int SLAB = 32 * CH;
+    constexpr int NF = MT * CH;                              // 1 KB fragments per stage
+    constexpr int STAGE = NF * 1024;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = lane & 15, q = lane >> 4;
+    const int M = a.M, N = a.N, K = a.K, nb = a.nb;
+    const bool per_branch = gridDim.z > 1;                   // one branch per workgroup
+    const int zb = blockIdx.z;
+    const int nbase = blockIdx.x * (SW * SRG * 16) + wave * (SRG * 16);
+    const int nslab = K / SLAB;
+    const int per = (nslab + KS - 1) / KS;
+    const int s_begin = blockIdx.y * per;
+    const int s_end = s_begin + per < nslab ? s_begin + per : nslab;
+    const int G = K / a.group;
+    const uint32_t* crow[SRG];
+    const _Float16* srow[SRG];
+    const int16_t* zrow[SRG];
+    bool rg_ok[SRG];
+#pragma unroll
+    for (int r = 0; r < SRG; ++r) {
+        rg_ok[r] = nbase + 16 * r < N;                       // N is a multiple of 16
+        const int ch = rg_ok[r] ? nbase + 16 * r + n : 0;
+        crow[r] = (const uint32_t*)a.codes + (((int64_t)ch * K) >> 3) + q * CH;
+        srow[r] = (const _Float16*)a.step16 + (int64_t)ch * G;
+        zrow[r] = a.zp + (int64_t)ch * G;
+    }
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_offset_of(lds_raw));
+    const zo_bf16* xf_base = (const zo_bf16*)a.Xfrag;
+    // fragment fi = t * CH + c of slab sl: m-tile t is (branch, j) = (zb, t) or (t / J, t % J)
+    auto issue = [&](int stage, int sl) {
+        for (int fi = wave; fi < NF; fi += SW) {
+            const int t = fi / CH, c = fi % CH;
+            const int b = per_branch ? zb : t / J, j = per_branch ? t : t % J;
+            const zo_bf16* src = xf_base + b * a.strideXfrag + (((int64_t)sl * J + j) * CH + c) * 512;
+            lds_copy16(src, (uint32_t)lane * 16u, lds0 + stage * STAGE + fi * 1024);
+        }
+    };
+
+    f32x4 acc[SRG][MT];
+#pragma unroll
+    for (int r = 0; r < SRG; ++r)
+#pragma unroll
+        for (int t = 0; t < MT; ++t) acc[r][t] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+
+    uint32_t words[SRG][CH], wnext[SRG][CH];
+#pragma unroll
+    for (int r = 0; r < SRG; ++r)
+#pragma unroll
+        for (int c = 0; c < CH; ++c) words[r][c] = wnext[r][c] = 0u;
+    float st[SRG], stn[SRG];
+    int zq[SRG], zqn[SRG];
+#pragma unroll
+    for (int r = 0; r < SRG; ++r) { st[r] = stn[r] = 0.0f; zq[r] = zqn[r] = 0; }
+    if (s_begin < s_end) {
+        issue(0, s_begin);
+        const int g0 = s_begin * SLAB / a.group;
+#pragma unroll
+        for (int r = 0; r < SRG; ++r) {
+            load_words<CH>(crow[r] + s_begin * (SLAB / 8), words[r]);
+            st[r] = (float)srow[r][g0];
+            zq[r] = zrow[r][g0];
         }
     }
+    __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0): this wave's copies have landed
+    __syncthreads();
+    int stage = 0;
+    for (int sl = s_begin; sl < s_end; ++sl) {
+        if (sl + 1 < s_end) {                                // stage ^ 1 was last read before the barrier just passed
+            issue(stage ^ 1, sl + 1);
+            const int gn = (sl + 1) * SLAB / a.group;        // codes, step and zero point of the next slab: one slab ahead
+#pragma unroll
+            for (int r = 0; r < SRG; ++r) {
+                load_words<CH>(crow[r] + (sl + 1) * (SLAB / 8), wnext[r]);
+                stn[r] = (float)srow[r][gn];
+                zqn[r] = zrow[r][gn];
+            }
+        }
+        bf16x8 af[SRG][CH];
+#pragma unroll
+        for (int r = 0; r < SRG; ++r) {
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                float o[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) o[i] = (float)((int)((words[r][c] >> (4 * i)) & 15u) - zq[r]) * st[r];
+                af[r][c] = pack8(o);
+            }
+        }
+        const unsigned char* sb = lds_raw + stage * STAGE + lane * 16;
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                const bf16x8 xf = *reinterpret_cast<const bf16x8*>(sb + ((t * CH + c) << 10));
+#pragma unroll
+                for (int r = 0; r < SRG; ++r) acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[r][c], xf, acc[r][t], 0, 0, 0);
+            }
+        __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): own copies of the next slab (and its codes) are in
+        __syncthreads();
+        stage ^= 1;
+#pragma unroll
+        for (int r = 0; r < SRG; ++r) {
+            st[r] = stn[r];
+            zq[r] = zqn[r];
+#pragma unroll
+            for (int c = 0; c < CH; ++c) words[r][c] = wnext[r][c];
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int r = 0; r < SRG; ++r)
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            const int b = per_branch ? zb : t / J, j = per_branch ? t : t % J;
+            const int m = j * 16 + n, nn = nbase + 16 * r + 4 * q;
+            if (!rg_ok[r] || b >= nb || j >= J) continue;
+            if (P) {
+                if (m < M)
+                    *reinterpret_cast<float4*>(P + (((int64_t)blockIdx.y * nb + b) * M + m) * N + nn) =
+                        make_float4(acc[r][t][0], acc[r][t][1], acc[r][t][2], acc[r][t][3]);
+            } else {
+                store_outputs(a, acc[r][t], b, m, nn);
+            }
+        }
+}
+
+// Y = epilogue(sum over ks of P[ks][b][m][n]), the KS terms added in order; one thread per four consecutive n
+__global__ __launch_bounds__(256) void zo_splitk_reduce_kernel(zo_fused_args a, const float* __restrict__ P, int KS)
+{
+    const int64_t per_b = (int64_t)a.M * (a.N >> 2);
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= per_b * a.nb) return;
+    const int b = (int)(i / per_b);
+    const int64_t r = i % per_b;
+    const int m = (int)(r / (a.N >> 2)), nn = (int)(r % (a.N >> 2)) * 4;
+    const int64_t plane = (int64_t)a.nb * a.M * a.N;
+    const float* p = P + ((int64_t)b * a.M + m) * a.N + nn;
+    f32x4 v = *reinterpret_cast<const f32x4*>(p);
+    for (int ks = 1; ks < KS; ++ks) {
+        const f32x4 t = *reinterpret_cast<const f32x4*>(p + ks * plane);
+        v[0] += t[0]; v[1] += t[1]; v[2] += t[2]; v[3] += t[3];
+    }
+    store_outputs(a, v, b, m, nn);
 }
 
 // Activations re-laid out fragment by fragment for the kernel above: the 16-byte piece that lane (m % 16, q) feeds
@@ -294,7 +571,110 @@ bool zo_fused_supported(int32_t M, int32_t N, int32_t K, int32_t bits, int32_t g
     return K % group == 0;
 }
 
-static int fused_ch(int bits, int group) { return bits == 0 || group <= 32 ? 1 : group / 32; }
+template <int CH, int J>
+static hipError_t launch_int4_one(const zo_fused_args& a, hipStream_t st)
+{
+    constexpr int lds = FW * 2 * J * 1024;
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void*)zo_int4_gemm_fused_kernel<CH, J>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+    }
+    zo_int4_gemm_fused_kernel<CH, J><<<dim3(a.N / 16), FW * 64, lds, st>>>(a);
+    return hipGetLastError();
+}
+
+template <int CH>
+static hipError_t launch_int4_j(const zo_fused_args& a, hipStream_t st)
+{
+    switch (tiles_for(a.M)) {
+        case 1:  return launch_int4_one<CH, 1>(a, st);
+        case 2:  return launch_int4_one<CH, 2>(a, st);
+        case 4:  return launch_int4_one<CH, 4>(a, st);
+        default: return launch_int4_one<CH, 8>(a, st);
+    }
+}
+
+// number of K ranges: enough workgroups for about two per CU (one per two CUs when a workgroup carries 8 m-tiles and
+// its partial sums are large: measured optimum), at least two slabs each, at most 16
+static int splitk_ranges(int N, int K, int group, int zdim, int MT)
+{
+    const int slab = group >= 128 ? 128 : group;
+    const int tiles = ((N + 255) / 256) * zdim, nslab = K / slab;
+    const int target = MT >= 8 ? 128 : 512;
+    int ks = (target + tiles - 1) / tiles;
+    if (ks > nslab / 2) ks = nslab / 2;
+    if (ks > 16) ks = 16;
+    return ks < 1 ? 1 : ks;
+}
+// m-tiles per workgroup and workgroups along z for M rows and nb branches
+static void splitk_shape(int M, int nb, int& MT, int& zdim)
+{
+    const int J = tiles_for(M);
+    if (nb * J <= 8) { MT = nb * J; zdim = 1; } else { MT = J; zdim = nb; }
+}
+
+template <int CH, int MT>
+static hipError_t launch_splitk_one(const zo_fused_args& a, float* P, int KS, int zdim, hipStream_t st)
+{
+    const int lds = 2 * MT * CH * 1024;
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void*)zo_int4_gemm_splitk_kernel<CH, MT>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+    }
+    zo_int4_gemm_splitk_kernel<CH, MT><<<dim3((a.N + 255) / 256, KS, zdim), SW * 64, lds, st>>>(a, KS > 1 ? P : nullptr, KS, tiles_for(a.M));
+    if (KS > 1) {
+        const int64_t items = (int64_t)a.nb * a.M * (a.N / 4);
+        zo_splitk_reduce_kernel<<<(unsigned)((items + 255) / 256), 256, 0, st>>>(a, P, KS);
+    }
+    return hipGetLastError();
+}
+
+template <int CH>
+static hipError_t launch_splitk_mt(const zo_fused_args& a, float* P, int KS, int MT, int zdim, hipStream_t st)
+{
+    switch (MT) {
+        case 1:  return launch_splitk_one<CH, 1>(a, P, KS, zdim, st);
+        case 2:  return launch_splitk_one<CH, 2>(a, P, KS, zdim, st);
+        case 4:  return launch_splitk_one<CH, 4>(a, P, KS, zdim, st);
+        default: return launch_splitk_one<CH, 8>(a, P, KS, zdim, st);
+    }
+}
+
+size_t zo_int4_splitk_scratch_bytes(int32_t M, int32_t N, int32_t K, int32_t group)
+{
+    return (size_t)16 * 2 * (size_t)M * (size_t)N * sizeof(float);      // KS <= 16, two branches
+}
+
+hipError_t zo_launch_int4_gemm_splitk(const zo_fused_args& a, void* partials, hipStream_t st)
+{
+    if (!zo_int4_fused_supported(a.M, a.N, a.K, a.group) || (a.nb != 1 && a.nb != 2) || (a.ldY & 3) || !a.codes || !a.step16 || !a.zp ||
+        !partials || !a.Xfrag)
+        return hipErrorInvalidValue;
+    int MT, zdim;
+    splitk_shape(a.M, a.nb, MT, zdim);
+    const int KS = splitk_ranges(a.N, a.K, a.group, zdim, MT);
+    if (a.group == 32) return launch_splitk_mt<1>(a, (float*)partials, KS, MT, zdim, st);
+    if (a.group == 64) return launch_splitk_mt<2>(a, (float*)partials, KS, MT, zdim, st);
+    return launch_splitk_mt<4>(a, (float*)partials, KS, MT, zdim, st);
+}
+
+bool zo_int4_fused_supported(int32_t M, int32_t N, int32_t K, int32_t group)
+{
+    if (M < 1 || M > ZO_FUSED_MAX_M || N < 16 || (N & 15) || K <= 0) return false;
+    if (group != 32 && group != 64 && group != 128 && group != 256 && group != 512) return false;
+    return K % group == 0;
+}
+
+hipError_t zo_launch_int4_gemm_fused(const zo_fused_args& a, hipStream_t st)
+{
+    if (!zo_int4_fused_supported(a.M, a.N, a.K, a.group) || (a.nb != 1 && a.nb != 2) || (a.ldY & 3) || !a.codes || !a.step16 || !a.zp)
+        return hipErrorInvalidValue;
+    if (a.group == 32) return launch_int4_j<1>(a, st);
+    if (a.group == 64) return launch_int4_j<2>(a, st);
+    return launch_int4_j<4>(a, st);
+}
+
+static int fused_ch(int bits, int group) { return bits == 0 || group <= 32 ? 1 : group >= 128 ? 4 : group / 32; }
 
 size_t zo_fused_relayout_bytes(int32_t M, int32_t K) { return (size_t)tiles_for(M) * 16 * (size_t)K * 2; }
 

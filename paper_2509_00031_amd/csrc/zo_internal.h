@@ -87,6 +87,9 @@ struct zo_fused_args {
     const void* X;              // bf16 [nb][M][K] (strideX elements between the branches, may be 0)
     const void* Xfrag;          // NULL, or the same activations re-laid out by zo_launch_fused_relayout (same bits / group)
     int64_t strideXfrag;
+    const void* codes;          // frozen linear (zo_launch_int4_gemm_fused): 4-bit codes [N][K/2], binary16 steps and
+    const void* step16;         // int16 zero points [N][K/group]
+    const int16_t* zp;
     const void* W;              // master [N][K] of ONE tensor (element index = n*K + k in its stream), fp32 or binary16
     int32_t wdtype;             // ZO_W_*
     void* Y;                    // bf16 or fp32 [M][ldY], already offset to the tensor's first output column
@@ -101,6 +104,15 @@ struct zo_fused_args {
 // M in 1..ZO_FUSED_MAX_M, N a multiple of 16, K a multiple of 32 and of the group
 bool zo_fused_supported(int32_t M, int32_t N, int32_t K, int32_t bits, int32_t group);
 hipError_t zo_launch_fq_gemm_fused(const zo_fused_args& a, uint64_t seed, int32_t tid, hipStream_t st);
+// Frozen, pre-quantized linear at small M: the operand is expanded from the packed codes in registers (a.codes /
+// step16 / zp / group; W, bits, eps, seed unused).  group in {32, 64, 128, 256, 512}.  The fragment-ordered copy
+// of the activations is laid out as for bits = 4 and the same group capped at 128.
+bool zo_int4_fused_supported(int32_t M, int32_t N, int32_t K, int32_t group);
+hipError_t zo_launch_int4_gemm_fused(const zo_fused_args& a, hipStream_t st);
+// Split-K form (128 channels per workgroup, activations shared through LDS, partial sums reduced in a fixed order by
+// a second kernel): needs zo_int4_splitk_scratch_bytes of fp32 scratch.  Same results up to the order of the fp32 sums.
+size_t zo_int4_splitk_scratch_bytes(int32_t M, int32_t N, int32_t K, int32_t group);
+hipError_t zo_launch_int4_gemm_splitk(const zo_fused_args& a, void* partials, hipStream_t st);
 // Optional: activations in the order the fused kernel consumes them (contiguous wave-level loads instead of
 // 16-byte gathers; pays from a few m-tiles on).  out: zo_fused_relayout_bytes(M, K) bytes per branch.
 size_t zo_fused_relayout_bytes(int32_t M, int32_t K);

@@ -124,3 +124,93 @@ def test_lightweight_step_with_packed_tensors(arch, act_dtype, a_bits):
         else:
             assert np.array_equal(g_params[i].cpu().numpy(), w0)
     ctx.close()
+
+
+def _packed(zo, torch, ref_p, N, K, group):
+    return zo.PackedInt4(to_dev(ref_p.codes, torch), to_dev(ref_p.step_f16.view(np.int16), torch).view(torch.float16),
+                         to_dev(ref_p.zp, torch), N, K, group)
+
+
+@pytest.mark.parametrize("K,group", [(128, 32), (128, 64), (128, 128), (512, 256), (512, 512)])
+def test_frozen_fused_operand_bit_exact(K, group):
+    """Small-M kernel that expands the packed codes in registers: with one-hot activations it returns its operand."""
+    torch, zo = gpu()
+    N = 48
+    W = synth.weights((N, K), 511)
+    W[1] = np.abs(W[1]) + 0.5
+    ref_p = orc.pack_int4(W, group)
+    what = orc.dequant_int4(ref_p, round_bf16=True)
+    packed = _packed(zo, torch, ref_p, N, K, group)
+    for k0 in range(0, K, 128):
+        X = torch.zeros((128, K), dtype=torch.bfloat16, device="cuda")
+        X[:, k0:k0 + 128] = torch.eye(128, dtype=torch.bfloat16, device="cuda")
+        for relayout in (False, True):
+            Yp, Ym = zo.zo_linear_frozen_int4_fused(X, X, packed, relayout=relayout)
+            assert np.array_equal(Yp.float().cpu().numpy().T, what[:, k0:k0 + 128])
+            assert torch.equal(Yp, Ym)
+
+
+@pytest.mark.parametrize("M,N,K,group", [(1, 16, 128, 128), (8, 256, 256, 64), (33, 80, 1024, 128), (100, 272, 5120, 128),
+                                         (128, 64, 13824, 128), (60, 160, 992, 32), (128, 512, 1024, 256)])
+@pytest.mark.parametrize("out_f32,relayout", [(False, False), (True, True)])
+def test_frozen_fused_linear_vs_oracle(M, N, K, group, out_f32, relayout):
+    torch, zo = gpu()
+    Xp = orc.bf16_round(synth.activations((M, K), 512))
+    Xm = orc.bf16_round(synth.activations((M, K), 513))
+    W = synth.weights((N, K), 514)
+    bias = synth.weights((N,), 515)
+    ref_p = orc.pack_int4(W, group)
+    what = orc.dequant_int4(ref_p, round_bf16=True)
+    Yp, Ym = zo.zo_linear_frozen_int4_fused(to_dev(Xp, torch, torch.bfloat16), to_dev(Xm, torch, torch.bfloat16),
+                                            _packed(zo, torch, ref_p, N, K, group), to_dev(bias, torch), out_f32=out_f32,
+                                            relayout=relayout)
+    for Y, X in ((Yp, Xp), (Ym, Xm)):
+        ref = orc.linear(X, what, bias)
+        got = Y.float().cpu().numpy()
+        mag = np.abs(X.astype(np.float64)) @ np.abs(what.astype(np.float64)).T + np.abs(bias)
+        assert np.all(np.abs(got - ref) <= 2.0 ** -20 * mag + (2.0 ** -8 * np.abs(ref) if not out_f32 else 0.0) + 1e-30)
+    with pytest.raises(zo.ZoError):
+        zo.zo_linear_frozen_int4_fused(torch.zeros((129, K), dtype=torch.bfloat16, device="cuda"), None,
+                                       _packed(zo, torch, ref_p, N, K, group))
+
+
+@pytest.mark.parametrize("arch", [1, 2])
+def test_lightweight_step_small_batch_routes(arch):
+    """48 tokens, bf16: the trainable Q / V go through the kernel that builds their tiles from the masters, the packed
+    tensors through the one that expands the codes; same losses as the quantize-once route, same update."""
+    torch, zo = gpu()
+    B, S = 2, 24
+    base = dict(n_layers=2, d_model=128, n_heads=4, d_ffn=256, vocab=512, max_seq=S, w_bits=4, w_group=64, a_bits=8)
+    ocfg = orc.Config(arch, act_dtype=1, lightweight=1, **base)
+    shapes = orc.param_shapes(ocfg)
+    params = synth.model_params(shapes, 516)
+    trainable = [n.endswith(".wq") or n.endswith(".wv") for n, _, _ in shapes]
+    ids = to_dev(synth.token_ids(B, S, 512, 517), torch)
+    outs, ws = [], []
+    for no_fused in (0, 1):
+        cfg = zo.make_config(arch, act_dtype=1, lightweight=1, no_fused=no_fused, **base)
+        g_params = [zo.zo_pack_weight_int4(to_dev(w, torch), 64) if (q and not t) else to_dev(w, torch)
+                    for w, t, (_, _, q) in zip(params, trainable, shapes)]
+        ctx = zo.Context(cfg, g_params, B, S, trainable=trainable)
+        ctx.zo_profile_begin()
+        outs.append(ctx.zo_step(ids, None, B, S, seed=6, eps=1e-3, lr=1e-2).cpu().numpy().copy())
+        prof = ctx.zo_profile_end()
+        n_packed = (5 if arch == 1 else 4) * base["n_layers"]          # every linear but Q and V
+        n_master = 2 * base["n_layers"] + 1                             # Q, V and the lm_head
+        assert prof["fused_int4_linear"][1] == (0 if no_fused else n_packed)
+        assert prof["fused_linear"][1] == (0 if no_fused else n_master)
+        assert prof["gemm"][1] == (4 * base["n_layers"] + 1 if no_fused else 0)
+        ws.append([p.cpu().numpy() for p in g_params if not isinstance(p, zo.PackedInt4)])
+        ctx.close()
+    assert np.allclose(outs[0][:2], outs[1][:2], rtol=3e-4)
+    names = [n for (n, _, _), p in zip(shapes, [None] * len(shapes))]
+    k = 0
+    for i, ((n, _, q), t) in enumerate(zip(shapes, trainable)):
+        if q and not t:
+            continue
+        if t:       # moved exactly by its own coefficient in both runs
+            for r in (0, 1):
+                assert np.array_equal(ws[r][k], orc.update(params[i].copy(), 6, i, np.float32(outs[r][3])))
+        else:
+            assert np.array_equal(ws[0][k], params[i])
+        k += 1
