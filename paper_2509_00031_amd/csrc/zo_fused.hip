@@ -451,15 +451,20 @@ __global__ __launch_bounds__(SW * 64) void zo_int4_gemm_splitk_kernel(zo_fused_a
                 af[r][c] = pack8(o);
             }
         }
+        // fragments are read from LDS two ahead of their use (ring of three), in the order c-major / t-minor so that
+        // consecutive matrix instructions never wait for one another's accumulator
         const unsigned char* sb = lds_raw + stage * STAGE + lane * 16;
+        auto frag = [&](int f) { return *reinterpret_cast<const bf16x8*>(sb + (((f % MT) * CH + f / MT) << 10)); };
+        bf16x8 xq[3];
+        xq[0] = frag(0);
+        if (NF > 1) xq[1] = frag(1);
 #pragma unroll
-        for (int t = 0; t < MT; ++t)
+        for (int f = 0; f < NF; ++f) {
+            if (f + 2 < NF) xq[(f + 2) % 3] = frag(f + 2);
+            const int c = f / MT, t = f % MT;
 #pragma unroll
-            for (int c = 0; c < CH; ++c) {
-                const bf16x8 xf = *reinterpret_cast<const bf16x8*>(sb + ((t * CH + c) << 10));
-#pragma unroll
-                for (int r = 0; r < SRG; ++r) acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[r][c], xf, acc[r][t], 0, 0, 0);
-            }
+            for (int r = 0; r < SRG; ++r) acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[r][c], xq[f % 3], acc[r][t], 0, 0, 0);
+        }
         __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): own copies of the next slab (and its codes) are in
         __syncthreads();
         stage ^= 1;
