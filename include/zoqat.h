@@ -69,7 +69,8 @@ typedef struct {
                             needs learn_clip = 1 and a_bits < 16 */
     int32_t no_fused;    /* 0 = the linears of a forward over at most 128 tokens (bf16 storage, groups of 8..128 -- 32..128
                             when packed tensors are attached --, no learned tensors) build their weight tiles inside
-                            the GEMM kernel, from the masters or from the packed codes;
+                            the GEMM kernel, from the masters or from the packed codes; large bf16 Llama-shaped forwards
+                            interleave the gate and up rows in the operand buffer and take silu(gate) * up in the GEMM epilogue;
                             1 = always quantize once into the workspace and run the plain GEMM */
     int32_t master_dtype;/* ZO_MASTER_*: storage type of every tensor of the parameter list.  ZO_MASTER_F16 = IEEE binary16,
                             the 2 bytes per parameter that the memory table of the efficiency section implies: a
@@ -332,6 +333,13 @@ zo_status zo_gemm_nt(const void* X_dev, const void* W_dev, void* Y_dev, int32_t 
  * applies max(., 0) before the residual is added.  One rounding to the storage type at the end. */
 zo_status zo_gemm_nt_fused(const void* X_dev, const void* W_dev, const float* bias_dev, const void* residual_dev, int32_t relu,
                            void* Y_dev, int32_t M, int32_t N, int32_t K, int32_t dtype, void* hip_stream);
+
+/* The gate / up GEMM of a SwiGLU block with the activation in its epilogue (what large bf16 Llama-shaped forwards run):
+ *   W dev bf16 [N2][K]: rows of the gate and the up projection interleaved in blocks of 32 channels -- rows 64 i .. 64 i + 31
+ *   = gate channels 32 i .., rows 64 i + 32 .. 64 i + 63 = up channels 32 i ..;  X dev bf16 [M][K];
+ *   Y dev bf16 [M][N2/2] = rt(silu(rt(X gate^T)) * rt(X up^T)), silu(x) = x / (1 + exp(-x)), rt = rounding to bf16 (the
+ *   same values as storing gate and up first).  ZO_EUNSUPPORTED unless M * N2 >= 2^23, N2 and K multiples of 64. */
+zo_status zo_gemm_nt_swiglu(const void* X_dev, const void* W_dev, void* Y_dev, int32_t M, int32_t N2, int32_t K, void* hip_stream);
 
 /* Causal softmax attention of the decoder forward: for every batch b, head h and position s,
  * out[b,s,h,:] = sum_{j<=s} softmax_j(q[b,s,h,:].k[b,j,h,:] / sqrt(dh)) v[b,j,h,:].

@@ -26,7 +26,7 @@ EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "
            "zo_gemm_nt", "zo_debug_buffer", "zo_profile_begin", "zo_profile_end", "zo_attention_causal",
            "zo_attention_scratch_bytes", "zo_pack_weight_int4", "zo_attach_frozen_int4", "zo_linear_frozen_int4", "zo_gemm_nt_fused", "zo_init_learned_params", "zo_step_groups", "zo_update_groups",
            "zo_debug_quant_weight_learned", "zo_debug_smooth_bias", "zo_linear_fakequant_fused", "zo_linear_fused_scratch_bytes",
-           "zo_step_multi", "zo_update_multi", "zo_lr_linear_decay", "zo_update_tensor_f16", "zo_master_bytes", "zo_linear_frozen_int4_fused", "zo_linear_frozen_fused_scratch_bytes"]
+           "zo_step_multi", "zo_update_multi", "zo_lr_linear_decay", "zo_update_tensor_f16", "zo_master_bytes", "zo_linear_frozen_int4_fused", "zo_linear_frozen_fused_scratch_bytes", "zo_gemm_nt_swiglu"]
 PROF_NAMES = ["gemm", "weight_quant", "act_quant", "attention", "update", "other", "fused_linear", "fused_int4_linear"]
 
 
@@ -74,6 +74,7 @@ _lib.zo_linear_fused_scratch_bytes.restype = _sz
 _lib.zo_linear_frozen_fused_scratch_bytes.argtypes = [_i32, _i32, _i32, _i32]
 _lib.zo_linear_frozen_fused_scratch_bytes.restype = _sz
 _lib.zo_linear_frozen_int4_fused.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp]
+_lib.zo_gemm_nt_swiglu.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _vp]
 _lib.zo_gemm_nt.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp]
 _lib.zo_debug_buffer.argtypes = [_vp, _i32, _i32, C.POINTER(_vp), C.POINTER(_sz)]
 _lib.zo_attention_causal.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i64, _i32, _vp, _vp]
@@ -405,6 +406,15 @@ def zo_gemm_nt(X, W, Y=None):
     if Y is None:
         Y = torch.empty((M, N), dtype=X.dtype, device=X.device)
     _check(_lib.zo_gemm_nt(X.data_ptr(), W.data_ptr(), Y.data_ptr(), M, N, K, dtype, _stream()), "zo_gemm_nt")
+    return Y
+
+
+def zo_gemm_nt_swiglu(X, W_interleaved):
+    """Y[M][N2/2] = silu(X gate^T) * (X up^T) with the gate / up rows of W interleaved in blocks of 32 channels."""
+    M, K = X.shape
+    N2 = W_interleaved.shape[0]
+    Y = torch.empty((M, N2 // 2), dtype=torch.bfloat16, device=X.device)
+    _check(_lib.zo_gemm_nt_swiglu(X.data_ptr(), W_interleaved.data_ptr(), Y.data_ptr(), M, N2, K, _stream()), "zo_gemm_nt_swiglu")
     return Y
 
 

@@ -318,11 +318,11 @@ struct fwd {
     bool frozen(int t) const { return c->frozen[t].codes != nullptr; }
     // Q(W +- eps u) of tensor `t` ([rows][cols]) into rows [row0, row0+rows) of the what buffers.
     // shared: every tensor of this GEMM is frozen, so one copy of the operand serves both branches.
-    zo_status weights(int t, int64_t row0, bool quantize, bool shared = false)
+    zo_status weights(int t, int64_t row0, bool quantize, bool shared = false, int ilv = 0)
     {
         const param_desc& p = c->desc[t];
         nweights += 1;
-        if (npend < 4 && fused_ok(t, quantize)) {
+        if (ilv == 0 && npend < 4 && fused_ok(t, quantize)) {
             pending[npend++] = pend{t, row0, quantize, c->frozen[t].codes != nullptr};
             return ZO_OK;
         }
@@ -334,7 +334,7 @@ struct fwd {
         const zo_ctx::frozen_int4& fz = c->frozen[t];
         if (fz.codes) {                                  // stored codes: the same operand for both branches
             ZO_HIP(c, zo_launch_dequant_int4(fz.codes, fz.step, fz.zp, (int)p.rows, (int)p.cols, fz.group, dt(), op,
-                                             shared ? nullptr : om, c->st));
+                                             shared ? nullptr : om, c->st, ilv));
             return ZO_OK;
         }
         if (quantize && p.clip >= 0) {
@@ -357,8 +357,18 @@ struct fwd {
             return ZO_OK;
         }
         ZO_HIP(c, zo_launch_fq_weight(c->params[t].ptr, (int)p.rows, (int)p.cols, bits, c->cfg.w_group,
-                                      seed, t, eps_of(t), dt(), op, om, nullptr, nullptr, nullptr, c->st, wd()));
+                                      seed, t, eps_of(t), dt(), op, om, nullptr, nullptr, nullptr, c->st, wd(), ilv));
         return ZO_OK;
+    }
+    // The gate / up pair of a Llama-shaped block can leave the GEMM as silu(gate) * up: large bf16 shapes, plain
+    // quantizer (no learned tensors, groups the streaming quantizer kernel handles), tensors not on the small-M route.
+    bool swiglu_in_gemm(int t_gate) const
+    {
+        const zo_config& cfg = c->cfg;
+        if (cfg.no_fused || cfg.arch != ZO_ARCH_LLAMA || cfg.learn_clip || cfg.learn_smooth) return false;
+        if (cfg.w_bits != 0 && (cfg.w_group == 0 || cfg.w_group > 512)) return false;
+        if ((cfg.d_ffn & 31) || fused_ok(t_gate, true) || fused_ok(t_gate + 1, true)) return false;
+        return zo_gemm_swiglu_supported(M, 2 * cfg.d_ffn, cfg.d_model, dt());
     }
     // Eq. 4, activation side of the linears whose input is smoothed by the pair carried by linear `t`:
     // perturbed s into slot 3, its reciprocal into slot 4, perturbed delta into slot 5 (no-op without smoothing)
@@ -429,14 +439,19 @@ struct fwd {
     {
         if (c->cfg.a_bits >= 16) { *used = in; return ZO_OK; }
         prof_scope ps(c, ZO_PROF_ACT_QUANT);
-        for (int b = 0; b < nb; ++b)
-            ZO_HIP(c, zo_launch_fq_act(at(c->L.br[b].*in), at(c->L.br[b].hq), M, K, c->cfg.a_bits, c->cfg.a_sym, dt(),
-                                       nullptr, nullptr, nullptr, sm_delta(b), sm_inv(b), c->st));
+        for (int b = 0; b < nb; ++b) {
+            if (zo_swiglu_quant_supported(K))             // row kept in registers: one read and one write per element
+                ZO_HIP(c, zo_launch_swiglu_quant(at(c->L.br[b].*in), nullptr, at(c->L.br[b].hq), M, K, K, c->cfg.a_bits, c->cfg.a_sym,
+                                                 dt(), sm_delta(b), sm_inv(b), c->st));
+            else
+                ZO_HIP(c, zo_launch_fq_act(at(c->L.br[b].*in), at(c->L.br[b].hq), M, K, c->cfg.a_bits, c->cfg.a_sym, dt(),
+                                           nullptr, nullptr, nullptr, sm_delta(b), sm_inv(b), c->st));
+        }
         *used = &layout::per_branch::hq;
         return ZO_OK;
     }
     zo_status gemm(size_t layout::per_branch::*in, size_t layout::per_branch::*out, int N, int K, bool bias, bool relu,
-                   bool residual, bool out_f32 = false, bool w_shared = false)
+                   bool residual, bool out_f32 = false, bool w_shared = false, bool swiglu = false)
     {
         const int requested = nweights;
         nweights = 0;
@@ -516,6 +531,7 @@ struct fwd {
         a.relu = relu;
         a.out_f32 = out_f32;
         a.dtype = dt();
+        a.swiglu = swiglu ? 1 : 0;
         prof_scope ps(c, ZO_PROF_GEMM);
         ZO_HIP(c, zo_launch_gemm(a, c->st));
         return ZO_OK;
@@ -649,7 +665,13 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
         ZO_TRY(F.smooth_prepare(t));                     // w_gate / fc1
         ZO_TRY(F.norm_quant(&PB::x, !llama, &xin));
         bool act_done = false;
-        if (llama) {
+        if (llama && F.swiglu_in_gemm(t)) {
+            // gate and up rows interleaved in the operand buffer; the GEMM writes silu(gate) * up
+            sh = F.frozen(t) && F.frozen(t + 1);
+            ZO_TRY(F.weights(t++, 0, true, sh, 1));
+            ZO_TRY(F.weights(t++, 0, true, sh, 2));
+            ZO_TRY(F.gemm(xin, &PB::act, 2 * f, d, false, false, false, false, sh, true));
+        } else if (llama) {
             sh = F.frozen(t) && F.frozen(t + 1);
             ZO_TRY(linear(0, sh));
             ZO_TRY(linear(f, sh));
@@ -1310,6 +1332,17 @@ zo_status zo_gemm_nt(const void* X_dev, const void* W_dev, void* Y_dev, int32_t 
     zo_gemm_args a{};
     a.X = X_dev; a.W = W_dev; a.Y = Y_dev;
     a.M = M; a.N = N; a.K = K; a.batch = 1; a.dtype = dtype;
+    return zo_launch_gemm(a, (hipStream_t)hip_stream) == hipSuccess ? ZO_OK : ZO_EHIP;
+}
+
+zo_status zo_gemm_nt_swiglu(const void* X_dev, const void* W_dev, void* Y_dev, int32_t M, int32_t N2, int32_t K, void* hip_stream)
+{
+    if (!X_dev || !W_dev || !Y_dev || M <= 0 || N2 <= 0 || K <= 0) return ZO_EINVAL;
+    if (!aligned16(X_dev) || !aligned16(W_dev) || !aligned16(Y_dev)) return ZO_EALIGN;
+    if (!zo_gemm_swiglu_supported(M, N2, K, ZO_T_BF16)) return ZO_EUNSUPPORTED;
+    zo_gemm_args a{};
+    a.X = X_dev; a.W = W_dev; a.Y = Y_dev;
+    a.M = M; a.N = N2; a.K = K; a.batch = 1; a.dtype = ZO_T_BF16; a.swiglu = 1;
     return zo_launch_gemm(a, (hipStream_t)hip_stream) == hipSuccess ? ZO_OK : ZO_EHIP;
 }
 

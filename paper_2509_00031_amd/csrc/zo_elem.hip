@@ -305,8 +305,19 @@ hipError_t zo_launch_update_f16(void* w, int64_t numel, const zo_multi_seeds& ms
 // neighbouring lanes, reduced with cross-lane shuffles.  u is generated once for both branches.
 // HBM traffic: 4 B read + sizeof(TO) written per branch and element.
 // ---------------------------------------------------------------------------------------------
+// Output position (in 8-element blocks) of input block b of a matrix with kb blocks per row when the rows go out
+// interleaved for the gate / up GEMM with SwiGLU in its epilogue: blocks of 32 gate rows (ilv = 1) alternate with the
+// 32 up rows (ilv = 2) of the same channels.
+__device__ __forceinline__ int64_t interleaved_block(int64_t b, int kb, int ilv)
+{
+    if (ilv == 0) return b;
+    const int64_t n = b / kb, kblk = b - n * kb;
+    const int64_t row = ((n >> 5) << 6) + (n & 31) + (ilv == 2 ? 32 : 0);
+    return row * kb + kblk;
+}
+
 template <typename TO, int GL, bool DEBUG>
-__device__ __forceinline__ void fq_branch(const float v[8], int bits, TO* out, int64_t b, bool active,
+__device__ __forceinline__ void fq_branch(const float v[8], int bits, TO* out, int64_t b, int64_t ob, bool active,
                                           uint8_t* codes, float* step, int32_t* zp, int lane)
 {
     float o[8];
@@ -334,19 +345,20 @@ __device__ __forceinline__ void fq_branch(const float v[8], int bits, TO* out, i
             }
         }
     }
-    if (active && out) zo_store8(out + 8 * b, o);
+    if (active && out) zo_store8(out + 8 * ob, o);
 }
 
 template <typename TW, typename TO, int GL, bool DEBUG>
 __global__ __launch_bounds__(256) void zo_fq_weight_kernel(const TW* __restrict__ W, int64_t nblk, zo_stream s,
                                                            float eps, int bits, TO* __restrict__ out_p, TO* __restrict__ out_m,
-                                                           uint8_t* codes, float* step, int32_t* zp)
+                                                           uint8_t* codes, float* step, int32_t* zp, int kb, int ilv)
 {
     const int lane = threadIdx.x & 63;
     // one Philox block per thread; every lane of a wave takes part in the shuffles
     {
         const int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
         const bool active = b < nblk;
+        const int64_t ob = interleaved_block(b, kb, ilv);
         float w[8], z[8];
         if (active) {
             zo_load8(W + 8 * b, w);
@@ -360,13 +372,13 @@ __global__ __launch_bounds__(256) void zo_fq_weight_kernel(const TW* __restrict_
             float v[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) v[i] = __builtin_fmaf(eps, z[i], w[i]);
-            fq_branch<TO, GL, DEBUG>(v, bits, out_p, b, active, codes, step, zp, lane);
+            fq_branch<TO, GL, DEBUG>(v, bits, out_p, b, ob, active, codes, step, zp, lane);
         }
         if (out_m) {
             float v[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) v[i] = __builtin_fmaf(-eps, z[i], w[i]);
-            fq_branch<TO, GL, false>(v, bits, out_m, b, active, nullptr, nullptr, nullptr, lane);
+            fq_branch<TO, GL, false>(v, bits, out_m, b, ob, active, nullptr, nullptr, nullptr, lane);
         }
     }
 }
@@ -448,36 +460,38 @@ bool zo_fq_weight_supported(int32_t K, int32_t bits, int32_t group)
 
 template <typename TW, typename TO, int GL>
 static hipError_t launch_fq_weight_gl(const TW* W, int64_t nblk, zo_stream s, float eps, int bits, TO* op, TO* om,
-                                      uint8_t* codes, float* step, int32_t* zp, hipStream_t st)
+                                      uint8_t* codes, float* step, int32_t* zp, hipStream_t st, int kb = 1, int ilv = 0)
 {
     if ((nblk + 255) / 256 > 0x7FFFFFFF) return hipErrorInvalidValue;
     const int grid = (int)((nblk + 255) / 256);
     if (codes || step || zp)
-        zo_fq_weight_kernel<TW, TO, GL, true><<<grid, 256, 0, st>>>(W, nblk, s, eps, bits, op, om, codes, step, zp);
+        zo_fq_weight_kernel<TW, TO, GL, true><<<grid, 256, 0, st>>>(W, nblk, s, eps, bits, op, om, codes, step, zp, kb, ilv);
     else
-        zo_fq_weight_kernel<TW, TO, GL, false><<<grid, 256, 0, st>>>(W, nblk, s, eps, bits, op, om, nullptr, nullptr, nullptr);
+        zo_fq_weight_kernel<TW, TO, GL, false><<<grid, 256, 0, st>>>(W, nblk, s, eps, bits, op, om, nullptr, nullptr, nullptr, kb, ilv);
     return hipGetLastError();
 }
 
 template <typename TW, typename TO>
 static hipError_t launch_fq_weight_t(const TW* W, int32_t N, int32_t K, int32_t bits, int32_t group, zo_stream s, float eps,
-                                     TO* op, TO* om, uint8_t* codes, float* step, int32_t* zp, hipStream_t st)
+                                     TO* op, TO* om, uint8_t* codes, float* step, int32_t* zp, hipStream_t st, int ilv)
 {
+    const int kb = K / 8;
+    if (ilv != 0 && ((N & 31) || (bits != 0 && (group ? group : K) > 512))) return hipErrorInvalidValue;
     const int64_t nblk = (int64_t)N * K / 8;
     if (nblk == 0) return hipSuccess;
-    if (bits == 0) return launch_fq_weight_gl<TW, TO, 1>(W, nblk, s, eps, 0, op, om, nullptr, nullptr, nullptr, st);
+    if (bits == 0) return launch_fq_weight_gl<TW, TO, 1>(W, nblk, s, eps, 0, op, om, nullptr, nullptr, nullptr, st, kb, ilv);
     if (group == 0) group = K;
     const int gl = group / 8;
     const bool pow2 = (gl & (gl - 1)) == 0;
     if (pow2 && gl <= 64) {
         switch (gl) {
-            case 1:  return launch_fq_weight_gl<TW, TO, 1>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
-            case 2:  return launch_fq_weight_gl<TW, TO, 2>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
-            case 4:  return launch_fq_weight_gl<TW, TO, 4>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
-            case 8:  return launch_fq_weight_gl<TW, TO, 8>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
-            case 16: return launch_fq_weight_gl<TW, TO, 16>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
-            case 32: return launch_fq_weight_gl<TW, TO, 32>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
-            default: return launch_fq_weight_gl<TW, TO, 64>(W, nblk, s, eps, bits, op, om, codes, step, zp, st);
+            case 1:  return launch_fq_weight_gl<TW, TO, 1>(W, nblk, s, eps, bits, op, om, codes, step, zp, st, kb, ilv);
+            case 2:  return launch_fq_weight_gl<TW, TO, 2>(W, nblk, s, eps, bits, op, om, codes, step, zp, st, kb, ilv);
+            case 4:  return launch_fq_weight_gl<TW, TO, 4>(W, nblk, s, eps, bits, op, om, codes, step, zp, st, kb, ilv);
+            case 8:  return launch_fq_weight_gl<TW, TO, 8>(W, nblk, s, eps, bits, op, om, codes, step, zp, st, kb, ilv);
+            case 16: return launch_fq_weight_gl<TW, TO, 16>(W, nblk, s, eps, bits, op, om, codes, step, zp, st, kb, ilv);
+            case 32: return launch_fq_weight_gl<TW, TO, 32>(W, nblk, s, eps, bits, op, om, codes, step, zp, st, kb, ilv);
+            default: return launch_fq_weight_gl<TW, TO, 64>(W, nblk, s, eps, bits, op, om, codes, step, zp, st, kb, ilv);
         }
     }
     const int64_t ngroups = (int64_t)N * (K / group);
@@ -492,19 +506,19 @@ static hipError_t launch_fq_weight_t(const TW* W, int32_t N, int32_t K, int32_t 
 hipError_t zo_launch_fq_weight(const void* W, int32_t N, int32_t K, int32_t bits, int32_t group,
                                uint64_t seed, int32_t tid, float eps, int dtype,
                                void* out_plus, void* out_minus,
-                               uint8_t* codes, float* step, int32_t* zp, hipStream_t st, int wdtype)
+                               uint8_t* codes, float* step, int32_t* zp, hipStream_t st, int wdtype, int ilv)
 {
     zo_stream s = make_stream(seed, tid);
     if (wdtype == ZO_W_F16) {
         const zo_f16* Wh = (const zo_f16*)W;
         if (dtype == ZO_T_BF16)
-            return launch_fq_weight_t<zo_f16, zo_bf16>(Wh, N, K, bits, group, s, eps, (zo_bf16*)out_plus, (zo_bf16*)out_minus, codes, step, zp, st);
-        return launch_fq_weight_t<zo_f16, float>(Wh, N, K, bits, group, s, eps, (float*)out_plus, (float*)out_minus, codes, step, zp, st);
+            return launch_fq_weight_t<zo_f16, zo_bf16>(Wh, N, K, bits, group, s, eps, (zo_bf16*)out_plus, (zo_bf16*)out_minus, codes, step, zp, st, ilv);
+        return launch_fq_weight_t<zo_f16, float>(Wh, N, K, bits, group, s, eps, (float*)out_plus, (float*)out_minus, codes, step, zp, st, ilv);
     }
     const float* Wf = (const float*)W;
     if (dtype == ZO_T_BF16)
-        return launch_fq_weight_t<float, zo_bf16>(Wf, N, K, bits, group, s, eps, (zo_bf16*)out_plus, (zo_bf16*)out_minus, codes, step, zp, st);
-    return launch_fq_weight_t<float, float>(Wf, N, K, bits, group, s, eps, (float*)out_plus, (float*)out_minus, codes, step, zp, st);
+        return launch_fq_weight_t<float, zo_bf16>(Wf, N, K, bits, group, s, eps, (zo_bf16*)out_plus, (zo_bf16*)out_minus, codes, step, zp, st, ilv);
+    return launch_fq_weight_t<float, float>(Wf, N, K, bits, group, s, eps, (float*)out_plus, (float*)out_minus, codes, step, zp, st, ilv);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -715,10 +729,11 @@ __global__ __launch_bounds__(256) void zo_pack_int4_kernel(const float* __restri
 template <typename TO>
 __global__ __launch_bounds__(256) void zo_dequant_int4_kernel(const uint32_t* __restrict__ packed, const _Float16* __restrict__ step,
                                                               const int16_t* __restrict__ zp, int64_t nblk, int gl,
-                                                              TO* __restrict__ out0, TO* __restrict__ out1)
+                                                              TO* __restrict__ out0, TO* __restrict__ out1, int kb, int ilv)
 {
     const int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (b >= nblk) return;
+    const int64_t ob = interleaved_block(b, kb, ilv);
     const uint32_t word = packed[b];
     const int64_t g = b / gl;
     const float st = (float)step[g];
@@ -726,8 +741,8 @@ __global__ __launch_bounds__(256) void zo_dequant_int4_kernel(const uint32_t* __
     float o[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) o[i] = (float)((int)((word >> (4 * i)) & 15u) - z) * st;
-    zo_store8(out0 + 8 * b, o);
-    if (out1) zo_store8(out1 + 8 * b, o);
+    zo_store8(out0 + 8 * ob, o);
+    if (out1) zo_store8(out1 + 8 * ob, o);
 }
 
 bool zo_int4_group_supported(int32_t K, int32_t group)
@@ -758,18 +773,18 @@ hipError_t zo_launch_pack_int4(const float* W, int32_t N, int32_t K, int32_t gro
 }
 
 hipError_t zo_launch_dequant_int4(const void* packed, const void* step_f16, const int16_t* zp, int32_t N, int32_t K, int32_t group,
-                                  int dtype, void* out0, void* out1, hipStream_t st)
+                                  int dtype, void* out0, void* out1, hipStream_t st, int ilv)
 {
     const int64_t nblk = (int64_t)N * K / 8;
     if (nblk == 0) return hipSuccess;
-    if (!zo_int4_group_supported(K, group) || (nblk + 255) / 256 > 0x7FFFFFFF) return hipErrorInvalidValue;
+    if (!zo_int4_group_supported(K, group) || (nblk + 255) / 256 > 0x7FFFFFFF || (ilv != 0 && (N & 31))) return hipErrorInvalidValue;
     const int grid = (int)((nblk + 255) / 256);
     if (dtype == ZO_T_BF16)
         zo_dequant_int4_kernel<zo_bf16><<<grid, 256, 0, st>>>((const uint32_t*)packed, (const _Float16*)step_f16, zp, nblk, group / 8,
-                                                              (zo_bf16*)out0, (zo_bf16*)out1);
+                                                              (zo_bf16*)out0, (zo_bf16*)out1, K / 8, ilv);
     else
         zo_dequant_int4_kernel<float><<<grid, 256, 0, st>>>((const uint32_t*)packed, (const _Float16*)step_f16, zp, nblk, group / 8,
-                                                            (float*)out0, (float*)out1);
+                                                            (float*)out0, (float*)out1, K / 8, ilv);
     return hipGetLastError();
 }
 

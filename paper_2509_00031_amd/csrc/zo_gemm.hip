@@ -259,7 +259,11 @@ __device__ __forceinline__ void store_tile(const f32x16& acc, const zo_gemm_args
     }
 }
 
-template <typename TY, int NW, int BK, int ST>
+// SWIGLU (bf16 output only): the rows of W are the gate and up projections interleaved in blocks of 32 channels
+// (32 gate rows, the 32 up rows of the same channels, ...), so the two 32 x 32 accumulator tiles a wave holds side
+// by side along n are gate and up of the same (m, channel) in the same lane and register; the epilogue rounds both
+// to the storage type (as if they had been stored), forms silu(gate) * up and writes Y[M][N/2].
+template <typename TY, int NW, int BK, int ST, bool SWIGLU = false>
 __global__ __launch_bounds__(NW * 64) void zo_gemm_bf16_dma_kernel(zo_gemm_args a)
 {
     constexpr int BM = 256, BN = 256;
@@ -406,6 +410,44 @@ __global__ __launch_bounds__(NW * 64) void zo_gemm_bf16_dma_kernel(zo_gemm_args 
     TY* Y = (TY*)a.Y + bz * a.strideY;
     const float* bias = a.bias ? a.bias + bz * a.strideBias : nullptr;
     const zo_bf16* res = a.residual ? (const zo_bf16*)a.residual + bz * a.strideRes : nullptr;
+    if constexpr (SWIGLU) {
+        static_assert(sizeof(TY) == 2 && TN == 2, "gate / up pairs need two n-tiles per wave and bf16 output");
+        // each wave: 128 rows x 32 channels, staged through its LDS slice (64-byte rows, 8-byte granules XOR-swizzled by
+        // the row) and written as whole 16-byte pieces, four lanes per row
+        __syncthreads();
+        constexpr int ROWB = 64;
+        unsigned char* slice = lds + wave * (WM * ROWB);
+#pragma unroll
+        for (int j = 0; j < TM; ++j) {
+            const int ml = j * 32 + (lane & 31);
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+                const int g = rg * 2 + (lane >> 5);
+                float v[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float gt = zo_round_to<zo_bf16>(acc[0][j][rg * 4 + e]), up = zo_round_to<zo_bf16>(acc[1][j][rg * 4 + e]);
+                    v[e] = (gt / (1.0f + __expf(-gt))) * up;
+                }
+                uint2 o;
+                o.x = zo_pack_bf16x2(v[0], v[1]);
+                o.y = zo_pack_bf16x2(v[2], v[3]);
+                *reinterpret_cast<uint2*>(slice + ml * ROWB + ((g ^ (ml & 7)) << 3)) = o;
+            }
+        }
+        const int No = N >> 1;
+#pragma unroll 4
+        for (int it = 0; it < WM / 16; ++it) {
+            const int row = it * 16 + (lane >> 2), c = lane & 3, f = row & 7;
+            uint4 v = *reinterpret_cast<const uint4*>(slice + row * ROWB + ((c ^ (f >> 1)) << 4));
+            if (f & 1) v = make_uint4(v.z, v.w, v.x, v.y);
+            const int m = m0 + wm * WM + row, n = (n0 >> 1) + wn * 32 + c * 8;
+            // a wave's row piece is half a cache line (its n-neighbour writes the other half): cached stores, the
+            // streaming hint is for whole lines only
+            if (m < M && n < No) *reinterpret_cast<uint4*>((zo_bf16*)Y + (int64_t)m * No + n) = v;
+        }
+        return;
+    }
     if constexpr (sizeof(TY) == 2) {
         if ((N & 7) == 0) {
             // bf16 output: each wave transposes its WM x WN tile through its own slice of the (now idle)
@@ -568,6 +610,14 @@ static hipError_t launch_bf16(const zo_gemm_args& a, hipStream_t st)
     return hipGetLastError();
 }
 
+// the gate / up GEMM with SwiGLU in its epilogue runs in the large-shape kernel only
+bool zo_gemm_swiglu_supported(int32_t M, int32_t N, int32_t K, int dtype)
+{
+    if (dtype != ZO_T_BF16 || M <= 0 || N <= 0 || (N & 63) || (K & 63)) return false;
+    if ((int64_t)M * N < (int64_t)256 * 256 * 128) return false;
+    return (int64_t)M * K * 2 < ((int64_t)1 << 32) && (int64_t)N * K * 2 < ((int64_t)1 << 32);
+}
+
 hipError_t zo_launch_gemm(const zo_gemm_args& a, hipStream_t st)
 {
     if (a.M == 0 || a.N == 0) return hipSuccess;
@@ -575,6 +625,16 @@ hipError_t zo_launch_gemm(const zo_gemm_args& a, hipStream_t st)
         const bool large = (int64_t)a.M * a.N >= (int64_t)256 * 256 * 128;
         // operand bytes must be addressable with 32-bit offsets from the (batch) base pointers
         const bool off32 = (int64_t)a.M * a.K * 2 < ((int64_t)1 << 32) && (int64_t)a.N * a.K * 2 < ((int64_t)1 << 32);
+        if (a.swiglu) {
+            if (!zo_gemm_swiglu_supported(a.M, a.N, a.K, a.dtype) || a.bias || a.residual || a.relu || a.out_f32) return hipErrorInvalidValue;
+            const int tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
+            constexpr int lds_bytes = 2 * 512 * 64 * 2;
+            hipError_t e_ = hipFuncSetAttribute((const void*)zo_gemm_bf16_dma_kernel<zo_bf16, 8, 64, 2, true>,
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+            if (e_ != hipSuccess) return e_;
+            zo_gemm_bf16_dma_kernel<zo_bf16, 8, 64, 2, true><<<dim3(tiles, 1, a.batch), 8 * 64, lds_bytes, st>>>(a);
+            return hipGetLastError();
+        }
         if (large && (a.K & 63) == 0 && off32) {
             const int tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
             const dim3 grid(tiles, 1, a.batch);

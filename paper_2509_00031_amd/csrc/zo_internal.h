@@ -35,7 +35,9 @@ bool zo_fq_weight_supported(int32_t K, int32_t bits, int32_t group);
 hipError_t zo_launch_fq_weight(const void* W, int32_t N, int32_t K, int32_t bits, int32_t group,
                                uint64_t seed, int32_t tid, float eps, int dtype,
                                void* out_plus, void* out_minus,
-                               uint8_t* codes, float* step, int32_t* zp, hipStream_t st, int wdtype = ZO_W_F32);
+                               uint8_t* codes, float* step, int32_t* zp, hipStream_t st, int wdtype = ZO_W_F32, int ilv = 0);
+// ilv: 0 = rows written where they are read; 1 / 2 = rows of a gate / up projection written interleaved in blocks of 32
+// channels (gate block, up block, ...) for the GEMM with SwiGLU in its epilogue (N a multiple of 32, groups <= 512)
 
 // ---- frozen weights (lightweight variant): packed 4-bit codes, binary16 steps, int16 zero points ----
 // group: a power of two in 8 .. 512 that divides K
@@ -44,7 +46,7 @@ hipError_t zo_launch_pack_int4(const float* W, int32_t N, int32_t K, int32_t gro
                                hipStream_t st);
 // w^ = (code - zp) * step into out0 (and out1 if not NULL), storage type dtype
 hipError_t zo_launch_dequant_int4(const void* packed, const void* step_f16, const int16_t* zp, int32_t N, int32_t K, int32_t group,
-                                  int dtype, void* out0, void* out1, hipStream_t st);
+                                  int dtype, void* out0, void* out1, hipStream_t st, int ilv = 0);
 
 // ---- per-token activation fake-quantizer -------------------------------------------------------
 // sm_delta / sm_inv (fp32 [K], or both NULL): the quantizer sees (x - delta) * inv (Eq. 4)
@@ -78,7 +80,10 @@ struct zo_gemm_args {
     int32_t relu;
     int32_t out_f32;            // 1: Y is fp32 whatever the operand type
     int dtype;                  // operand (and default output) storage type
+    int32_t swiglu;             // 1: W holds gate and up rows interleaved in blocks of 32 channels; Y[M][N/2] = silu(gate) * up
+                                //    (bf16, large shapes only: zo_gemm_swiglu_supported; no bias / residual / relu)
 };
+bool zo_gemm_swiglu_supported(int32_t M, int32_t N, int32_t K, int dtype);
 hipError_t zo_launch_gemm(const zo_gemm_args& a, hipStream_t st);
 
 // ---- fused fake-quantized linear for small M: Y[b] = X[b] * Q(W +- eps u)^T, tiles built in registers ----
@@ -132,7 +137,7 @@ bool zo_norm_quant_supported(int32_t d);
 hipError_t zo_launch_norm_quant(const void* x, const float* gamma, const float* beta, void* xhat, int32_t M, int32_t d,
                                 float eps, int32_t bits, int32_t sym, int dtype,
                                 const float* sm_delta, const float* sm_inv, hipStream_t st);
-// SwiGLU fused with the per-token quantizer: cols <= 16384
+// SwiGLU fused with the per-token quantizer: cols <= 16384; up = NULL: the quantizer alone on the rows of `gate`
 bool zo_swiglu_quant_supported(int32_t cols);
 hipError_t zo_launch_swiglu_quant(const void* gate, const void* up, void* xhat, int64_t rows, int32_t cols, int64_t in_stride,
                                   int32_t bits, int32_t sym, int dtype, const float* sm_delta, const float* sm_inv, hipStream_t st);

@@ -397,6 +397,7 @@ hipError_t zo_launch_swiglu(const void* gate, const void* up, void* out, int64_t
 // ---------------------------------------------------------------------------------------------
 // SwiGLU fused with the per-token quantizer of the down projection:
 // x^ = rt(Q_A(rt(silu(gate) * up))).  One workgroup per row, the row stays in registers.
+// up = NULL: the per-token quantizer alone on the row `gate` (one read, one write per element).
 // ---------------------------------------------------------------------------------------------
 template <typename T, int NC>
 __global__ __launch_bounds__(256) void zo_swiglu_quant_kernel(const T* __restrict__ gate, const T* __restrict__ up, T* __restrict__ xhat,
@@ -413,12 +414,12 @@ __global__ __launch_bounds__(256) void zo_swiglu_quant_kernel(const T* __restric
         if (c < cols) {
             float g[8], u[8];
             zo_load8(gate + row * in_stride + c, g);
-            zo_load8(up + row * in_stride + c, u);
+            if (up) zo_load8(up + row * in_stride + c, u);
             float dl[8], iv[8];
             if (sm_delta) { zo_load8(sm_delta + c, dl); zo_load8(sm_inv + c, iv); }
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                v[i][e] = zo_round_to<T>((g[e] / (1.0f + __expf(-g[e]))) * u[e]);
+                v[i][e] = up ? zo_round_to<T>((g[e] / (1.0f + __expf(-g[e]))) * u[e]) : g[e];
                 if (sm_delta) v[i][e] = (v[i][e] - dl[e]) * iv[e];
                 if (sym) mx = fmaxf(mx, fabsf(v[i][e]));
                 else { mn = fminf(mn, v[i][e]); mx = fmaxf(mx, v[i][e]); }
