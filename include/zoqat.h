@@ -352,6 +352,13 @@ zo_status zo_attention_causal(const void* q_dev, const void* k_dev, const void* 
                               int32_t B, int32_t S, int32_t H, int32_t dh, int64_t row_stride, int32_t dtype,
                               void* scratch_dev, void* hip_stream);
 
+/* Which optional routes the context's last forward (or step) took: an OR of ZO_ROUTE_* bits.  Host function. */
+enum { ZO_ROUTE_FUSED_SMALL_M = 1,    /* linears built from the masters inside the small-M kernel */
+       ZO_ROUTE_FUSED_INT4 = 2,       /* frozen linears expanded from their packed codes inside the small-M kernel */
+       ZO_ROUTE_SWIGLU_IN_GEMM = 4,   /* SwiGLU applied by the epilogue of the gate / up GEMM */
+       ZO_ROUTE_ROPE_IN_GEMM = 8 };   /* rotary embedding applied by the epilogue of the q | k | v GEMM */
+uint32_t zo_debug_routes(const zo_ctx* ctx);
+
 /* Device buffers of the context's last forward, for layer-level parity tests.
  * which: 0 = final hidden state [M][d], 1 = logits fp32 [M][V] (linear arch: output Y [M][N]),
  *        2 = residual stream after the last layer [M][d].  branch: 0 = '+' (or the single

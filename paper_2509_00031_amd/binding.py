@@ -19,6 +19,7 @@ STATUS = {0: "ZO_OK", 1: "ZO_EINVAL", 2: "ZO_ESHAPE", 3: "ZO_EALIGN", 4: "ZO_EHI
 ARCH_LINEAR, ARCH_LLAMA, ARCH_OPT = 0, 1, 2
 ACT_FP32, ACT_BF16 = 0, 1
 MASTER_F32, MASTER_F16 = 0, 1
+ROUTE_FUSED_SMALL_M, ROUTE_FUSED_INT4, ROUTE_SWIGLU_IN_GEMM, ROUTE_ROPE_IN_GEMM = 1, 2, 4, 8
 
 EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "zo_destroy", "zo_last_error",
            "zo_forward_quant", "zo_step", "zo_update", "zo_debug_philox_u32", "zo_debug_normal", "zo_update_tensor",
@@ -26,7 +27,7 @@ EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "
            "zo_gemm_nt", "zo_debug_buffer", "zo_profile_begin", "zo_profile_end", "zo_attention_causal",
            "zo_attention_scratch_bytes", "zo_pack_weight_int4", "zo_attach_frozen_int4", "zo_linear_frozen_int4", "zo_gemm_nt_fused", "zo_init_learned_params", "zo_step_groups", "zo_update_groups",
            "zo_debug_quant_weight_learned", "zo_debug_smooth_bias", "zo_linear_fakequant_fused", "zo_linear_fused_scratch_bytes",
-           "zo_step_multi", "zo_update_multi", "zo_lr_linear_decay", "zo_update_tensor_f16", "zo_master_bytes", "zo_linear_frozen_int4_fused", "zo_linear_frozen_fused_scratch_bytes", "zo_gemm_nt_swiglu"]
+           "zo_step_multi", "zo_update_multi", "zo_lr_linear_decay", "zo_update_tensor_f16", "zo_master_bytes", "zo_linear_frozen_int4_fused", "zo_linear_frozen_fused_scratch_bytes", "zo_gemm_nt_swiglu", "zo_debug_routes"]
 PROF_NAMES = ["gemm", "weight_quant", "act_quant", "attention", "update", "other", "fused_linear", "fused_int4_linear"]
 
 
@@ -96,6 +97,8 @@ _lib.zo_lr_linear_decay.restype = _f32
 _lib.zo_update_tensor_f16.argtypes = [_vp, _i64, _u64, _i32, _vp, _f32, _i32, _vp]
 _lib.zo_master_bytes.argtypes = [C.POINTER(zo_config)]
 _lib.zo_master_bytes.restype = _i64
+_lib.zo_debug_routes.argtypes = [_vp]
+_lib.zo_debug_routes.restype = C.c_uint32
 _lib.zo_profile_begin.argtypes = [_vp]
 _lib.zo_profile_end.argtypes = [_vp, C.POINTER(C.c_float), C.POINTER(_i32)]
 
@@ -237,6 +240,9 @@ class Context:
 
     def zo_update(self, seed, coeff_dev=None, coeff_host=0.0):
         _check(_lib.zo_update(self.handle, seed, _ptr(coeff_dev), coeff_host), "zo_update", self.handle)
+
+    def zo_debug_routes(self):
+        return int(_lib.zo_debug_routes(self.handle))
 
     def zo_profile_begin(self):
         _check(_lib.zo_profile_begin(self.handle), "zo_profile_begin", self.handle)

@@ -233,6 +233,7 @@ struct zo_ctx {
     hipStream_t st;
     layout L;           // for max_B x max_S
     int last_M;
+    uint32_t routes = 0;  // ZO_ROUTE_* bits of the last forward
     std::string err;
     // optional per-launch timing (zo_profile_begin / zo_profile_end)
     bool prof = false;
@@ -362,6 +363,16 @@ struct fwd {
     }
     // The gate / up pair of a Llama-shaped block can leave the GEMM as silu(gate) * up: large bf16 shapes, plain
     // quantizer (no learned tensors, groups the streaming quantizer kernel handles), tensors not on the small-M route.
+    // The rotary embedding of a Llama-shaped block can be applied by the epilogue of the fused q | k | v GEMM: head
+    // dimension 128, large bf16 shapes, plain quantizer, tensors not on the small-M route.
+    bool rope_in_gemm(int t_q) const
+    {
+        const zo_config& cfg = c->cfg;
+        if (cfg.no_fused || cfg.arch != ZO_ARCH_LLAMA || cfg.learn_clip || cfg.learn_smooth) return false;
+        if (cfg.w_bits != 0 && (cfg.w_group == 0 || cfg.w_group > 512)) return false;
+        if (cfg.d_model / cfg.n_heads != 128 || fused_ok(t_q, true)) return false;
+        return zo_gemm_rope_supported(M, 3 * cfg.d_model, cfg.d_model, dt());
+    }
     bool swiglu_in_gemm(int t_gate) const
     {
         const zo_config& cfg = c->cfg;
@@ -451,10 +462,12 @@ struct fwd {
         return ZO_OK;
     }
     zo_status gemm(size_t layout::per_branch::*in, size_t layout::per_branch::*out, int N, int K, bool bias, bool relu,
-                   bool residual, bool out_f32 = false, bool w_shared = false, bool swiglu = false)
+                   bool residual, bool out_f32 = false, bool w_shared = false, bool swiglu = false, bool rope = false)
     {
         const int requested = nweights;
         nweights = 0;
+        if (swiglu) c->routes |= ZO_ROUTE_SWIGLU_IN_GEMM;
+        if (rope) c->routes |= ZO_ROUTE_ROPE_IN_GEMM;
         if (npend > 0 && npend != requested) {           // cannot happen: the tensors of one GEMM share shape and route
             npend = 0;
             return fail(c, ZO_EUNSUPPORTED, "tensors of one GEMM took different routes");
@@ -496,6 +509,7 @@ struct fwd {
                 f.eps = eps_of(pe.t);
                 f.relu = relu;
                 f.out_f32 = out_f32;
+                c->routes |= pe.packed ? ZO_ROUTE_FUSED_INT4 : ZO_ROUTE_FUSED_SMALL_M;
                 prof_scope ps(c, pe.packed ? ZO_PROF_FUSED_INT4 : ZO_PROF_FUSED);   // one bracket per kernel launch
                 if (pe.packed) {
                     const zo_ctx::frozen_int4& fz = c->frozen[pe.t];
@@ -532,6 +546,12 @@ struct fwd {
         a.out_f32 = out_f32;
         a.dtype = dt();
         a.swiglu = swiglu ? 1 : 0;
+        if (rope) {
+            a.rope_cos = at<float>(c->L.rope_cos);
+            a.rope_sin = at<float>(c->L.rope_sin);
+            a.rope_cols = 2 * c->cfg.d_model;
+            a.rope_S = S;
+        }
         prof_scope ps(c, ZO_PROF_GEMM);
         ZO_HIP(c, zo_launch_gemm(a, c->st));
         return ZO_OK;
@@ -545,6 +565,7 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
 {
     const zo_config& cfg = c->cfg;
     using PB = layout::per_branch;
+    c->routes = 0;
     fwd F{c, nb, eps, seed, 0, S};
     const int dt = cfg.act_dtype;
     const size_t ts = zo_tsize(dt);
@@ -583,6 +604,7 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
             fa.strideX = a.strideX; fa.strideY = a.strideY; fa.strideBias = a.strideBias;
             fa.bits = cfg.w_bits; fa.group = cfg.w_group; fa.eps = F.eps_of(0);
             F.npend = 0;
+            c->routes |= ZO_ROUTE_FUSED_SMALL_M;
             if (M > 32 && zo_fused_relayout_bytes(M, K) <= c->L.what_bytes) {
                 prof_scope ps(c, ZO_PROF_OTHER);
                 fa.Xfrag = F.at(c->L.what[0]);
@@ -632,19 +654,20 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
         bool sh = F.frozen(t) && F.frozen(t + tstep) && F.frozen(t + 2 * tstep);
         // one quantized linear: weights of tensor t into rows [row0, ..) of the operand buffer, its bias
         // (OPT-shaped) into slot 2, the smoothing term of Eq. 4 added to it
-        auto linear = [&](int64_t row0, bool shared) -> zo_status {
+        auto linear = [&](int64_t row0, bool shared, int ilv = 0) -> zo_status {
             const int tw = t++;
-            ZO_TRY(F.weights(tw, row0, true, shared));
+            ZO_TRY(F.weights(tw, row0, true, shared, ilv));
             if (!llama) ZO_TRY(F.vector(t++, 2, row0));
             return F.bias_shift(tw, row0, !llama);
         };
         const bool bias = !llama || cfg.learn_smooth;
-        for (int i = 0; i < 3; ++i) ZO_TRY(linear((int64_t)i * d, sh));
-        ZO_TRY(F.gemm(xin, &PB::qkv, 3 * d, d, bias, false, false, false, sh));
+        const bool rope_fused = llama && F.rope_in_gemm(t);      // head blocks permuted in the operand, rotation in the epilogue
+        for (int i = 0; i < 3; ++i) ZO_TRY(linear((int64_t)i * d, sh, rope_fused ? 3 : 0));
+        ZO_TRY(F.gemm(xin, &PB::qkv, 3 * d, d, bias, false, false, false, sh, false, rope_fused));
         for (int b = 0; b < nb; ++b) {
             prof_scope ps(c, ZO_PROF_ATTENTION);
             char* qkv = F.at(c->L.br[b].qkv);
-            if (llama)
+            if (llama && !rope_fused)
                 ZO_HIP(c, zo_launch_rope(qkv, qkv + (size_t)d * ts, F.at<float>(c->L.rope_cos), F.at<float>(c->L.rope_sin),
                                          M, S, H, dh, 3 * d, dt, c->st));
             if (zo_flash_attention_supported(dh, dt))
@@ -1030,6 +1053,8 @@ zo_status zo_init_learned_params(zo_ctx* ctx)
     }
     return ZO_OK;
 }
+
+uint32_t zo_debug_routes(const zo_ctx* ctx) { return ctx ? ctx->routes : 0u; }
 
 zo_status zo_debug_buffer(zo_ctx* ctx, int32_t which, int32_t branch, void** ptr, size_t* bytes)
 {

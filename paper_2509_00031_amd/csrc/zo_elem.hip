@@ -307,12 +307,18 @@ hipError_t zo_launch_update_f16(void* w, int64_t numel, const zo_multi_seeds& ms
 // ---------------------------------------------------------------------------------------------
 // Output position (in 8-element blocks) of input block b of a matrix with kb blocks per row when the rows go out
 // interleaved for the gate / up GEMM with SwiGLU in its epilogue: blocks of 32 gate rows (ilv = 1) alternate with the
-// 32 up rows (ilv = 2) of the same channels.
+// 32 up rows (ilv = 2) of the same channels; or (ilv = 3) for the q | k | v GEMM with the rotary embedding in its epilogue.
 __device__ __forceinline__ int64_t interleaved_block(int64_t b, int kb, int ilv)
 {
     if (ilv == 0) return b;
     const int64_t n = b / kb, kblk = b - n * kb;
-    const int64_t row = ((n >> 5) << 6) + (n & 31) + (ilv == 2 ? 32 : 0);
+    int64_t row;
+    if (ilv == 3) {                                  // blocks 1 and 2 of every 128-row head trade places
+        const int64_t blk = (n >> 5) & 3;
+        row = (blk == 1) ? n + 32 : (blk == 2) ? n - 32 : n;
+    } else {
+        row = ((n >> 5) << 6) + (n & 31) + (ilv == 2 ? 32 : 0);
+    }
     return row * kb + kblk;
 }
 
@@ -476,7 +482,7 @@ static hipError_t launch_fq_weight_t(const TW* W, int32_t N, int32_t K, int32_t 
                                      TO* op, TO* om, uint8_t* codes, float* step, int32_t* zp, hipStream_t st, int ilv)
 {
     const int kb = K / 8;
-    if (ilv != 0 && ((N & 31) || (bits != 0 && (group ? group : K) > 512))) return hipErrorInvalidValue;
+    if (ilv != 0 && ((N & (ilv == 3 ? 127 : 31)) || (bits != 0 && (group ? group : K) > 512))) return hipErrorInvalidValue;
     const int64_t nblk = (int64_t)N * K / 8;
     if (nblk == 0) return hipSuccess;
     if (bits == 0) return launch_fq_weight_gl<TW, TO, 1>(W, nblk, s, eps, 0, op, om, nullptr, nullptr, nullptr, st, kb, ilv);
@@ -777,7 +783,7 @@ hipError_t zo_launch_dequant_int4(const void* packed, const void* step_f16, cons
 {
     const int64_t nblk = (int64_t)N * K / 8;
     if (nblk == 0) return hipSuccess;
-    if (!zo_int4_group_supported(K, group) || (nblk + 255) / 256 > 0x7FFFFFFF || (ilv != 0 && (N & 31))) return hipErrorInvalidValue;
+    if (!zo_int4_group_supported(K, group) || (nblk + 255) / 256 > 0x7FFFFFFF || (ilv != 0 && (N & (ilv == 3 ? 127 : 31)))) return hipErrorInvalidValue;
     const int grid = (int)((nblk + 255) / 256);
     if (dtype == ZO_T_BF16)
         zo_dequant_int4_kernel<zo_bf16><<<grid, 256, 0, st>>>((const uint32_t*)packed, (const _Float16*)step_f16, zp, nblk, group / 8,

@@ -263,7 +263,12 @@ __device__ __forceinline__ void store_tile(const f32x16& acc, const zo_gemm_args
 // (32 gate rows, the 32 up rows of the same channels, ...), so the two 32 x 32 accumulator tiles a wave holds side
 // by side along n are gate and up of the same (m, channel) in the same lane and register; the epilogue rounds both
 // to the storage type (as if they had been stored), forms silu(gate) * up and writes Y[M][N/2].
-template <typename TY, int NW, int BK, int ST, bool SWIGLU = false>
+// EPI = 2 (bf16 output, head dimension 128): the rows of W are the fused q | k | v projections with the four 32-row
+// blocks of every head in the order [0, 2, 1, 3], so the two n-tiles of a wave hold dimensions i and i + 64 of the same
+// head -- the pair the rotary embedding mixes -- in the same lane and register.  Columns below rope_cols (q and k) are
+// rounded to the storage type, rotated by the angle table (position = row % rope_S) exactly as the stand-alone
+// kernel does, and every column is written back in its natural place.
+template <typename TY, int NW, int BK, int ST, int EPI = 0>
 __global__ __launch_bounds__(NW * 64) void zo_gemm_bf16_dma_kernel(zo_gemm_args a)
 {
     constexpr int BM = 256, BN = 256;
@@ -410,7 +415,7 @@ __global__ __launch_bounds__(NW * 64) void zo_gemm_bf16_dma_kernel(zo_gemm_args 
     TY* Y = (TY*)a.Y + bz * a.strideY;
     const float* bias = a.bias ? a.bias + bz * a.strideBias : nullptr;
     const zo_bf16* res = a.residual ? (const zo_bf16*)a.residual + bz * a.strideRes : nullptr;
-    if constexpr (SWIGLU) {
+    if constexpr (EPI == 1) {
         static_assert(sizeof(TY) == 2 && TN == 2, "gate / up pairs need two n-tiles per wave and bf16 output");
         // each wave: 128 rows x 32 channels, staged through its LDS slice (64-byte rows, 8-byte granules XOR-swizzled by
         // the row) and written as whole 16-byte pieces, four lanes per row
@@ -445,6 +450,60 @@ __global__ __launch_bounds__(NW * 64) void zo_gemm_bf16_dma_kernel(zo_gemm_args 
             // a wave's row piece is half a cache line (its n-neighbour writes the other half): cached stores, the
             // streaming hint is for whole lines only
             if (m < M && n < No) *reinterpret_cast<uint4*>((zo_bf16*)Y + (int64_t)m * No + n) = v;
+        }
+        return;
+    }
+    if constexpr (EPI == 2) {
+        static_assert(sizeof(TY) == 2 && TN == 2 && WN == 64, "rotary pairs need two 32-column tiles per wave");
+        __syncthreads();
+        constexpr int ROWB = WN * 2;
+        unsigned char* slice = lds + wave * (WM * ROWB);
+        const bool rotate = n0 < a.rope_cols;               // a 256-column tile is two whole heads of q / k, or of v
+        const int jh = wn & 1;                              // which 32 dimensions of the half head this wave holds
+#pragma unroll
+        for (int j = 0; j < TM; ++j) {
+            const int ml = j * 32 + (lane & 31);
+            int m = m0 + wm * WM + ml;
+            m = m < M ? m : M - 1;
+            const int64_t trow = (int64_t)(m % a.rope_S) * 64 + jh * 32 + (lane >> 5) * 4;
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+                float x0[4], x1[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    x0[e] = zo_round_to<zo_bf16>(acc[0][j][rg * 4 + e]);
+                    x1[e] = zo_round_to<zo_bf16>(acc[1][j][rg * 4 + e]);
+                }
+                if (rotate) {
+                    const float4 c4 = *reinterpret_cast<const float4*>(a.rope_cos + trow + rg * 8);
+                    const float4 s4 = *reinterpret_cast<const float4*>(a.rope_sin + trow + rg * 8);
+                    const float cc[4] = {c4.x, c4.y, c4.z, c4.w}, ss[4] = {s4.x, s4.y, s4.z, s4.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float p = x0[e], r = x1[e];
+                        x0[e] = __builtin_fmaf(p, cc[e], -(r * ss[e]));
+                        x1[e] = __builtin_fmaf(r, cc[e], p * ss[e]);
+                    }
+                }
+                const int g = rg * 2 + (lane >> 5);
+                uint2 o;
+                o.x = zo_pack_bf16x2(x0[0], x0[1]);
+                o.y = zo_pack_bf16x2(x0[2], x0[3]);
+                *reinterpret_cast<uint2*>(slice + ml * ROWB + ((g ^ (ml & 15)) << 3)) = o;
+                o.x = zo_pack_bf16x2(x1[0], x1[1]);
+                o.y = zo_pack_bf16x2(x1[2], x1[3]);
+                *reinterpret_cast<uint2*>(slice + ml * ROWB + (((8 + g) ^ (ml & 15)) << 3)) = o;
+            }
+        }
+        // read-back as in the plain path; chunk c < 4 is the first-half piece, c >= 4 the second-half piece of the row
+#pragma unroll 4
+        for (int it = 0; it < WM / 8; ++it) {
+            const int row = it * 8 + (lane >> 3), c = lane & 7, f = row & 15;
+            uint4 v = *reinterpret_cast<const uint4*>(slice + row * ROWB + ((c ^ (f >> 1)) << 4));
+            if (f & 1) v = make_uint4(v.z, v.w, v.x, v.y);
+            const int m = m0 + wm * WM + row;
+            const int n = n0 + (wn >> 1) * 128 + (c >> 2) * 64 + jh * 32 + (c & 3) * 8;
+            if (m < M && n < N) *reinterpret_cast<uint4*>((zo_bf16*)Y + (int64_t)m * N + n) = v;
         }
         return;
     }
@@ -618,6 +677,14 @@ bool zo_gemm_swiglu_supported(int32_t M, int32_t N, int32_t K, int dtype)
     return (int64_t)M * K * 2 < ((int64_t)1 << 32) && (int64_t)N * K * 2 < ((int64_t)1 << 32);
 }
 
+// the fused q | k | v GEMM with the rotary embedding in its epilogue: large shapes, whole heads of 128 per half tile
+bool zo_gemm_rope_supported(int32_t M, int32_t N, int32_t K, int dtype)
+{
+    if (dtype != ZO_T_BF16 || M <= 0 || N <= 0 || (N & 255) || (K & 63)) return false;
+    if ((int64_t)M * N < (int64_t)256 * 256 * 128) return false;
+    return (int64_t)M * K * 2 < ((int64_t)1 << 32) && (int64_t)N * K * 2 < ((int64_t)1 << 32);
+}
+
 hipError_t zo_launch_gemm(const zo_gemm_args& a, hipStream_t st)
 {
     if (a.M == 0 || a.N == 0) return hipSuccess;
@@ -625,14 +692,26 @@ hipError_t zo_launch_gemm(const zo_gemm_args& a, hipStream_t st)
         const bool large = (int64_t)a.M * a.N >= (int64_t)256 * 256 * 128;
         // operand bytes must be addressable with 32-bit offsets from the (batch) base pointers
         const bool off32 = (int64_t)a.M * a.K * 2 < ((int64_t)1 << 32) && (int64_t)a.N * a.K * 2 < ((int64_t)1 << 32);
+        if (a.rope_cos) {
+            if (!zo_gemm_rope_supported(a.M, a.N, a.K, a.dtype) || a.bias || a.residual || a.relu || a.out_f32 || !a.rope_sin || a.rope_S <= 0 ||
+                (a.rope_cols & 255))
+                return hipErrorInvalidValue;
+            const int tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
+            constexpr int lds_bytes = 2 * 512 * 64 * 2;
+            hipError_t e_ = hipFuncSetAttribute((const void*)zo_gemm_bf16_dma_kernel<zo_bf16, 8, 64, 2, 2>,
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+            if (e_ != hipSuccess) return e_;
+            zo_gemm_bf16_dma_kernel<zo_bf16, 8, 64, 2, 2><<<dim3(tiles, 1, a.batch), 8 * 64, lds_bytes, st>>>(a);
+            return hipGetLastError();
+        }
         if (a.swiglu) {
             if (!zo_gemm_swiglu_supported(a.M, a.N, a.K, a.dtype) || a.bias || a.residual || a.relu || a.out_f32) return hipErrorInvalidValue;
             const int tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
             constexpr int lds_bytes = 2 * 512 * 64 * 2;
-            hipError_t e_ = hipFuncSetAttribute((const void*)zo_gemm_bf16_dma_kernel<zo_bf16, 8, 64, 2, true>,
+            hipError_t e_ = hipFuncSetAttribute((const void*)zo_gemm_bf16_dma_kernel<zo_bf16, 8, 64, 2, 1>,
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
             if (e_ != hipSuccess) return e_;
-            zo_gemm_bf16_dma_kernel<zo_bf16, 8, 64, 2, true><<<dim3(tiles, 1, a.batch), 8 * 64, lds_bytes, st>>>(a);
+            zo_gemm_bf16_dma_kernel<zo_bf16, 8, 64, 2, 1><<<dim3(tiles, 1, a.batch), 8 * 64, lds_bytes, st>>>(a);
             return hipGetLastError();
         }
         if (large && (a.K & 63) == 0 && off32) {

@@ -37,7 +37,9 @@ hipError_t zo_launch_fq_weight(const void* W, int32_t N, int32_t K, int32_t bits
                                void* out_plus, void* out_minus,
                                uint8_t* codes, float* step, int32_t* zp, hipStream_t st, int wdtype = ZO_W_F32, int ilv = 0);
 // ilv: 0 = rows written where they are read; 1 / 2 = rows of a gate / up projection written interleaved in blocks of 32
-// channels (gate block, up block, ...) for the GEMM with SwiGLU in its epilogue (N a multiple of 32, groups <= 512)
+// channels (gate block, up block, ...) for the GEMM with SwiGLU in its epilogue (N a multiple of 32, groups <= 512);
+// 3 = the 32-row blocks of every 128-row head written in the order [0, 2, 1, 3] for the GEMM with the rotary embedding
+// in its epilogue (N a multiple of 128)
 
 // ---- frozen weights (lightweight variant): packed 4-bit codes, binary16 steps, int16 zero points ----
 // group: a power of two in 8 .. 512 that divides K
@@ -82,7 +84,12 @@ struct zo_gemm_args {
     int dtype;                  // operand (and default output) storage type
     int32_t swiglu;             // 1: W holds gate and up rows interleaved in blocks of 32 channels; Y[M][N/2] = silu(gate) * up
                                 //    (bf16, large shapes only: zo_gemm_swiglu_supported; no bias / residual / relu)
+    // rotary embedding in the epilogue of the fused q | k | v GEMM (head dimension 128; rope_cos != NULL switches it on): W rows
+    // with the 32-row blocks of every head in the order [0, 2, 1, 3]; columns < rope_cols rotated, position = row % rope_S
+    const float* rope_cos; const float* rope_sin;   // fp32 [max_seq][64]
+    int32_t rope_cols, rope_S;
 };
+bool zo_gemm_rope_supported(int32_t M, int32_t N, int32_t K, int dtype);
 bool zo_gemm_swiglu_supported(int32_t M, int32_t N, int32_t K, int dtype);
 hipError_t zo_launch_gemm(const zo_gemm_args& a, hipStream_t st);
 

