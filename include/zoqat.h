@@ -346,7 +346,7 @@ zo_status zo_gemm_nt_swiglu(const void* X_dev, const void* W_dev, void* Y_dev, i
  * q, k, v: dev, storage type dtype, element (b,s,h,i) at ((b*S + s) * row_stride + h*dh + i)
  * (row_stride lets them live inside one fused [B*S][3*H*dh] buffer); out: dev [B*S][H*dh].
  * dh must be 16, 32, 64 or 128 and row_stride a multiple of 8.  scratch: dev buffer of
- * zo_attention_scratch_bytes(...) bytes (0 bytes, and NULL accepted, when the generic kernel runs). */
+ * zo_attention_scratch_bytes(...) bytes; no kernel uses one any more: the size is 0 and NULL is accepted. */
 size_t zo_attention_scratch_bytes(int32_t B, int32_t S, int32_t H, int32_t dh, int32_t dtype);
 zo_status zo_attention_causal(const void* q_dev, const void* k_dev, const void* v_dev, void* out_dev,
                               int32_t B, int32_t S, int32_t H, int32_t dh, int64_t row_stride, int32_t dtype,

@@ -143,7 +143,7 @@ struct layout {
     size_t qp[2][4];           // perturbed step / zero point / alpha / beta of the current linear(s), per branch
     size_t qp_elems;
     struct per_branch {
-        size_t x, h, hq, qkv, att, vt, gu, act, logits, rowloss;
+        size_t x, h, hq, qkv, att, gu, act, logits, rowloss;
     } br[2];
     size_t total;
 };
@@ -204,7 +204,6 @@ layout make_layout(const zo_config& c, int B, int S)
         r.hq = take(M * (d > f ? d : f) * ts);
         r.qkv = take(M * 3 * d * ts);
         r.att = take(M * d * ts);
-        r.vt = take(zo_flash_attention_scratch_bytes(B, S, c.n_heads, (int)dh));
         r.gu = take(M * ffn_rows * ts);
         r.act = take(M * f * ts);
         r.logits = take(M * V * sizeof(float));
@@ -672,7 +671,7 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
                                          M, S, H, dh, 3 * d, dt, c->st));
             if (zo_flash_attention_supported(dh, dt))
                 ZO_HIP(c, zo_launch_flash_attention(qkv, qkv + (size_t)d * ts, qkv + (size_t)2 * d * ts, F.at(c->L.br[b].att),
-                                                    F.at(c->L.br[b].vt), B, S, H, dh, 3 * d, c->st));
+                                                    B, S, H, dh, 3 * d, c->st));
             else
                 ZO_HIP(c, zo_launch_attention(qkv, qkv + (size_t)d * ts, qkv + (size_t)2 * d * ts, F.at(c->L.br[b].att),
                                               B, S, H, dh, 3 * d, dt, c->st));
@@ -1321,11 +1320,7 @@ size_t zo_linear_frozen_fused_scratch_bytes(int32_t M, int32_t N, int32_t K, int
     return zo_linear_fused_scratch_bytes(M, K) + align_up(zo_int4_splitk_scratch_bytes(M, N, K, group));
 }
 
-size_t zo_attention_scratch_bytes(int32_t B, int32_t S, int32_t H, int32_t dh, int32_t dtype)
-{
-    if (B <= 0 || S <= 0 || H <= 0 || !zo_flash_attention_supported(dh, dtype)) return 0;
-    return zo_flash_attention_scratch_bytes(B, S, H, dh);
-}
+size_t zo_attention_scratch_bytes(int32_t, int32_t, int32_t, int32_t, int32_t) { return 0; }   // no kernel needs one
 
 zo_status zo_attention_causal(const void* q_dev, const void* k_dev, const void* v_dev, void* out_dev,
                               int32_t B, int32_t S, int32_t H, int32_t dh, int64_t row_stride, int32_t dtype,
@@ -1339,8 +1334,7 @@ zo_status zo_attention_causal(const void* q_dev, const void* k_dev, const void* 
     hipStream_t st = (hipStream_t)hip_stream;
     hipError_t e;
     if (zo_flash_attention_supported(dh, dtype)) {
-        if (!scratch_dev && B > 0 && S > 0) return ZO_EINVAL;
-        e = zo_launch_flash_attention(q_dev, k_dev, v_dev, out_dev, scratch_dev, B, S, H, dh, row_stride, st);
+        e = zo_launch_flash_attention(q_dev, k_dev, v_dev, out_dev, B, S, H, dh, row_stride, st);
     } else {
         e = zo_launch_attention(q_dev, k_dev, v_dev, out_dev, B, S, H, dh, row_stride, dtype, st);
     }

@@ -154,8 +154,7 @@ hipError_t zo_launch_attention(const void* q, const void* k, const void* v, void
                                int32_t B, int32_t S, int32_t H, int32_t dh, int64_t row_stride, int dtype, hipStream_t st);
 // bf16, head dimension 64 / 128: matrix-core kernel
 bool zo_flash_attention_supported(int32_t dh, int dtype);
-size_t zo_flash_attention_scratch_bytes(int32_t B, int32_t S, int32_t H, int32_t dh);   // transposed V
-hipError_t zo_launch_flash_attention(const void* q, const void* k, const void* v, void* out, void* scratch,
+hipError_t zo_launch_flash_attention(const void* q, const void* k, const void* v, void* out,
                                      int32_t B, int32_t S, int32_t H, int32_t dh, int64_t row_stride, hipStream_t st);
 hipError_t zo_launch_swiglu(const void* gate, const void* up, void* out, int64_t rows, int32_t cols,
                             int64_t in_stride, int dtype, hipStream_t st);

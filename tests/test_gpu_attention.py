@@ -28,7 +28,8 @@ def test_attention_fp32(B, S, H, dh):
 
 
 @pytest.mark.parametrize("B,S,H,dh", [(2, 40, 2, 64), (1, 200, 1, 128), (2, 128, 2, 64), (1, 257, 2, 128),
-                                      (1, 1024, 1, 128), (3, 64, 1, 64), (1, 1, 1, 64), (2, 96, 3, 32)])
+                                      (1, 1024, 1, 128), (3, 64, 1, 64), (1, 1, 1, 64), (2, 96, 3, 32),
+                                      (5, 70, 15, 64), (2, 150, 40, 128)])     # more (batch, head) pairs than one chunk of the work list
 @pytest.mark.parametrize("sharp", [0.5, 3.0])
 def test_attention_bf16(B, S, H, dh, sharp):
     torch, zo = gpu()
@@ -41,3 +42,25 @@ def test_attention_bf16(B, S, H, dh, sharp):
     # position 0 attends to itself only: output = v[0] exactly
     d = H * dh
     assert np.array_equal(out[0], qkv[0, 2 * d:])
+
+
+@pytest.mark.parametrize("rise", [4.0, 40.0, 400.0])
+@pytest.mark.parametrize("dh", [64, 128])
+def test_attention_bf16_growing_scores(rise, dh):
+    """Scores that climb by `rise` (natural-log units) from the first key to the last: the kernel moves the reference
+    point of its exponentials only when the maximum has outgrown it by 2^8, so a slow climb keeps a stale reference
+    for many tiles and a steep one moves it in every tile; the output must not depend on that."""
+    torch, zo = gpu()
+    B, S, H = 1, 448, 2
+    d = H * dh
+    qkv = synth.activations((B * S, 3 * d), 73) * 0.25
+    ramp = np.linspace(0.0, 1.0, S, dtype=np.float32)
+    for h in range(H):
+        qkv[:, h * dh] = 4.0                                            # q: one large component ...
+        qkv[:, d + h * dh] = ramp * np.float32(rise * np.sqrt(dh) / 4.0)    # ... meets a key component that grows with the position
+    qkv = orc.bf16_round(qkv)
+    out = zo.zo_attention_causal(to_dev(qkv, torch, torch.bfloat16), B, S, H, dh).float().cpu().numpy()
+    ref = _ref(qkv, B, S, H, dh)
+    row = np.linalg.norm(out - ref, axis=1) / np.linalg.norm(ref, axis=1)
+    assert rel_l2(out, ref) < 4e-3, rel_l2(out, ref)
+    assert row.max() < 8e-3, row.max()
