@@ -361,8 +361,9 @@ uint32_t zo_debug_routes(const zo_ctx* ctx);
 
 /* Device buffers of the context's last forward, for layer-level parity tests.
  * which: 0 = final hidden state [M][d], 1 = logits fp32 [M][V] (linear arch: output Y [M][N]),
- *        2 = residual stream after the last layer [M][d].  branch: 0 = '+' (or the single
- * forward), 1 = '-'.  Returns the dev pointer in *ptr and its size in *bytes. */
+ *        2 = residual stream after the last layer [M][d], 3 = q | k | v of the last layer [M][3d] (q and k after the
+ *        rotary embedding where the architecture has one), 4 = attention output of the last layer [M][d].
+ *        branch: 0 = '+' (or the single forward), 1 = '-'.  Returns the dev pointer in *ptr and its size in *bytes. */
 zo_status zo_debug_buffer(zo_ctx* ctx, int32_t which, int32_t branch, void** ptr, size_t* bytes);
 
 #ifdef __cplusplus

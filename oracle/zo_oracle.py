@@ -604,7 +604,8 @@ def forward(cfg, params, ids=None, x=None, target=None, seed=0, eps_signed=0.0, 
             v = _qlinear(cfg, h, P.qweight(p + "wv"), tie_log=tie_log, smooth=P.smooth(p + "wv"))
             q = _rt(cfg, _rope(q, B, S, H, dh))
             k = _rt(cfg, _rope(k, B, S, H, dh))
-            a = _rt(cfg, _attention(q, k, v, B, S, H, dh))
+            keep(p + "qkv", np.concatenate([q, k, v], axis=1))
+            a = keep(p + "attn", _rt(cfg, _attention(q, k, v, B, S, H, dh)))
             xres = _qlinear(cfg, a, P.qweight(p + "wo"), residual=xres, tie_log=tie_log, smooth=P.smooth(p + "wo"))
             keep(p + "attn_out", xres)
             h = _rt(cfg, _rmsnorm(xres, P.plain(p + "ffn_norm")))
@@ -618,7 +619,8 @@ def forward(cfg, params, ids=None, x=None, target=None, seed=0, eps_signed=0.0, 
             q = _qlinear(cfg, h, P.qweight(p + "wq"), P.plain(p + "bq"), tie_log=tie_log, smooth=P.smooth(p + "wq"))
             k = _qlinear(cfg, h, P.qweight(p + "wk"), P.plain(p + "bk"), tie_log=tie_log, smooth=P.smooth(p + "wk"))
             v = _qlinear(cfg, h, P.qweight(p + "wv"), P.plain(p + "bv"), tie_log=tie_log, smooth=P.smooth(p + "wv"))
-            a = _rt(cfg, _attention(q, k, v, B, S, H, dh))
+            keep(p + "qkv", np.concatenate([q, k, v], axis=1))
+            a = keep(p + "attn", _rt(cfg, _attention(q, k, v, B, S, H, dh)))
             xres = _qlinear(cfg, a, P.qweight(p + "wo"), P.plain(p + "bo"), residual=xres, tie_log=tie_log, smooth=P.smooth(p + "wo"))
             keep(p + "attn_out", xres)
             h = _rt(cfg, _layernorm(xres, P.plain(p + "ln2_g"), P.plain(p + "ln2_b")))

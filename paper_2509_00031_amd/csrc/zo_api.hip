@@ -1072,6 +1072,8 @@ zo_status zo_debug_buffer(zo_ctx* ctx, int32_t which, int32_t branch, void** ptr
         case 0: *ptr = ctx->ws + r.h; *bytes = M * c.d_model * ts; return ZO_OK;
         case 1: *ptr = ctx->ws + r.logits; *bytes = M * (size_t)c.vocab * 4; return ZO_OK;
         case 2: *ptr = ctx->ws + r.x; *bytes = M * c.d_model * ts; return ZO_OK;
+        case 3: *ptr = ctx->ws + r.qkv; *bytes = M * 3 * (size_t)c.d_model * ts; return ZO_OK;
+        case 4: *ptr = ctx->ws + r.att; *bytes = M * c.d_model * ts; return ZO_OK;
         default: return ZO_EINVAL;
     }
 }

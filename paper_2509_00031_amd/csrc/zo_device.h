@@ -277,21 +277,40 @@ ZO_DEV float zo_dequant(const zo_qparams& q, float code) { return (code - q.zp) 
 // ---------------------------------------------------------------------------------------------
 // wavefront helpers (64 lanes)
 // ---------------------------------------------------------------------------------------------
+// Reductions over aligned groups of WIDTH lanes (a power of two); every lane of a group gets the group's result.
+// The exchanges are register-to-register: lane ^ 1 and lane ^ 2 by quad permutes, then the mirror images of the
+// 8 and 16 lanes of a row (the lanes met there all hold their half's result already), then the row and half-wave
+// swaps of gfx950 -- no trip through the LDS crossbar.  The association order is fixed, so sums are reproducible.
+template <int CTRL> ZO_DEV float zo_dpp(float v)
+{
+    return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+template <int WIDTH, typename OP> ZO_DEV float zo_group_reduce(float v, OP op)
+{
+    static_assert(WIDTH >= 1 && WIDTH <= 64 && (WIDTH & (WIDTH - 1)) == 0, "group width");
+    if (WIDTH >= 2) v = op(v, zo_dpp<0xB1>(v));      // quad_perm [1,0,3,2]
+    if (WIDTH >= 4) v = op(v, zo_dpp<0x4E>(v));      // quad_perm [2,3,0,1]
+    if (WIDTH >= 8) v = op(v, zo_dpp<0x141>(v));     // row_half_mirror: lane 7 - i of each 8
+    if (WIDTH >= 16) v = op(v, zo_dpp<0x140>(v));    // row_mirror: lane 15 - i of each 16
+    if (WIDTH >= 32) {                               // rows 1 and 3 of the first copy <-> rows 0 and 2 of the second
+        const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+        v = op(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    }
+    if (WIDTH >= 64) {                               // upper half of the first copy <-> lower half of the second
+        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+        v = op(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    }
+    return v;
+}
 template <int WIDTH> ZO_DEV float zo_group_min(float v)
 {
-#pragma unroll
-    for (int o = WIDTH / 2; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o, 64));
-    return v;
+    return zo_group_reduce<WIDTH>(v, [](float a, float b) { return fminf(a, b); });
 }
 template <int WIDTH> ZO_DEV float zo_group_max(float v)
 {
-#pragma unroll
-    for (int o = WIDTH / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
+    return zo_group_reduce<WIDTH>(v, [](float a, float b) { return fmaxf(a, b); });
 }
 template <int WIDTH> ZO_DEV float zo_group_sum(float v)
 {
-#pragma unroll
-    for (int o = WIDTH / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
+    return zo_group_reduce<WIDTH>(v, [](float a, float b) { return a + b; });
 }

@@ -26,17 +26,27 @@ namespace {
 
 constexpr int FW = 8;            // waves per workgroup
 
+// min / max over the GL lanes lane % 16 + 16 q that share a quantization group: row swap (lane ^ 16), then half-wave
+// swap (lane ^ 32), both register-to-register
+template <int GL, typename OP> ZO_DEV float q_reduce(float v, OP op)
+{
+    if (GL >= 2) {
+        const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+        v = op(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    }
+    if (GL >= 4) {
+        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+        v = op(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    }
+    return v;
+}
 template <int GL> ZO_DEV float q_min(float v)
 {
-    if (GL >= 2) v = fminf(v, __shfl_xor(v, 16, 64));
-    if (GL >= 4) v = fminf(v, __shfl_xor(v, 32, 64));
-    return v;
+    return q_reduce<GL>(v, [](float a, float b) { return fminf(a, b); });
 }
 template <int GL> ZO_DEV float q_max(float v)
 {
-    if (GL >= 2) v = fmaxf(v, __shfl_xor(v, 16, 64));
-    if (GL >= 4) v = fmaxf(v, __shfl_xor(v, 32, 64));
-    return v;
+    return q_reduce<GL>(v, [](float a, float b) { return fmaxf(a, b); });
 }
 
 ZO_DEV bf16x8 pack8(const float o[8])

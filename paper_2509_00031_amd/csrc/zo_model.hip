@@ -137,42 +137,58 @@ hipError_t zo_launch_norm(const void* x, const float* gamma, const float* beta, 
 
 // ---------------------------------------------------------------------------------------------
 // RMSNorm / LayerNorm fused with the per-token quantizer of the linear that follows:
-// x^ = rt(Q_A(rt(norm(x)))).  One wavefront per row, the row stays in registers (d <= 512 * NC).
+// x^ = rt(Q_A(rt(norm(x)))).  The row stays in registers: WPR = 1 wavefront per row for short rows
+// (4 rows per workgroup), WPR = 4 (the whole workgroup, 16 bytes per thread and 4 KB chunk) for long
+// ones; the four partial results of a row meet in LDS and are combined in a fixed order.
 // ---------------------------------------------------------------------------------------------
-template <typename T, int NC>
+template <typename T, int NC, int WPR>
 __global__ __launch_bounds__(256) void zo_norm_quant_kernel(const T* __restrict__ x, const float* __restrict__ gamma,
                                                             const float* __restrict__ beta, T* __restrict__ xhat, int M, int d,
                                                             float eps, int bits, int sym,
                                                             const float* __restrict__ sm_delta, const float* __restrict__ sm_inv)
 {
-    const int lane = threadIdx.x & 63;
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= M) return;
+    __shared__ float red[5][4];
+    constexpr int TPR = 64 * WPR;                    // threads per row
+    const int tr = threadIdx.x % TPR, wave = threadIdx.x >> 6;
+    const int row = blockIdx.x * (4 / WPR) + threadIdx.x / TPR;
+    if (row >= M) return;                            // a whole wavefront (WPR = 1) or workgroup (WPR = 4)
     const T* xr = x + (int64_t)row * d;
     float v[NC][8];
     float s1 = 0.0f, s2 = 0.0f;
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
-        const int c = lane * 8 + 512 * i;
+        const int c = tr * 8 + 8 * TPR * i;
         if (c < d) {
             zo_load8(xr + c, v[i]);
 #pragma unroll
             for (int e = 0; e < 8; ++e) { s1 += v[i][e]; s2 = __builtin_fmaf(v[i][e], v[i][e], s2); }
         }
     }
-    s1 = zo_group_sum<64>(s1);
     s2 = zo_group_sum<64>(s2);
+    if (beta) s1 = zo_group_sum<64>(s1);
+    if (WPR == 4) {
+        if ((threadIdx.x & 63) == 0) { red[0][wave] = s1; red[1][wave] = s2; }
+        __syncthreads();
+        s1 = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+        s2 = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+    }
     float mean = 0.0f, var;
     if (beta) {
         mean = s1 / (float)d;
         float sv = 0.0f;
 #pragma unroll
         for (int i = 0; i < NC; ++i)
-            if (lane * 8 + 512 * i < d) {
+            if (tr * 8 + 8 * TPR * i < d) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) { float t = v[i][e] - mean; sv = __builtin_fmaf(t, t, sv); }
             }
-        var = zo_group_sum<64>(sv) / (float)d;
+        sv = zo_group_sum<64>(sv);
+        if (WPR == 4) {
+            if ((threadIdx.x & 63) == 0) red[2][wave] = sv;
+            __syncthreads();
+            sv = (red[2][0] + red[2][1]) + (red[2][2] + red[2][3]);
+        }
+        var = sv / (float)d;
     } else {
         var = s2 / (float)d;
     }
@@ -180,7 +196,7 @@ __global__ __launch_bounds__(256) void zo_norm_quant_kernel(const T* __restrict_
     float mn = INFINITY, mx = -INFINITY;
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
-        const int c = lane * 8 + 512 * i;
+        const int c = tr * 8 + 8 * TPR * i;
         if (c < d) {
             float g[8];
             zo_load8(gamma + c, g);
@@ -209,10 +225,16 @@ __global__ __launch_bounds__(256) void zo_norm_quant_kernel(const T* __restrict_
     }
     mn = zo_group_min<64>(mn);
     mx = zo_group_max<64>(mx);
+    if (WPR == 4) {
+        if ((threadIdx.x & 63) == 0) { red[3][wave] = mn; red[4][wave] = mx; }
+        __syncthreads();
+        mn = fminf(fminf(red[3][0], red[3][1]), fminf(red[3][2], red[3][3]));
+        mx = fmaxf(fmaxf(red[4][0], red[4][1]), fmaxf(red[4][2], red[4][3]));
+    }
     const zo_qparams q = sym ? zo_qparams_sym(mx, bits) : zo_qparams_asym(mn, mx, bits);
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
-        const int c = lane * 8 + 512 * i;
+        const int c = tr * 8 + 8 * TPR * i;
         if (c < d) {
             float o[8];
 #pragma unroll
@@ -229,13 +251,16 @@ hipError_t zo_launch_norm_quant(const void* x, const float* gamma, const float* 
                                 const float* sm_delta, const float* sm_inv, hipStream_t st)
 {
     if (M == 0) return hipSuccess;
-    const int grid = (M + 3) / 4;
-#define ZO_NQ(T, NC) zo_norm_quant_kernel<T, NC><<<grid, 256, 0, st>>>((const T*)x, gamma, beta, (T*)xhat, M, d, eps, bits, sym, sm_delta, sm_inv)
-    if (dtype == ZO_T_BF16) {
-        if (d <= 2048) ZO_NQ(zo_bf16, 4); else if (d <= 4096) ZO_NQ(zo_bf16, 8); else ZO_NQ(zo_bf16, 16);
-    } else {
-        if (d <= 2048) ZO_NQ(float, 4); else if (d <= 4096) ZO_NQ(float, 8); else ZO_NQ(float, 16);
-    }
+    // rows up to 1024 elements: one wavefront each; longer ones: one workgroup each
+#define ZO_NQ(T, NC, WPR) zo_norm_quant_kernel<T, NC, WPR><<<(WPR == 4 ? M : (M + 3) / 4), 256, 0, st>>>((const T*)x, gamma, beta, (T*)xhat, M, d, eps, bits, sym, sm_delta, sm_inv)
+#define ZO_NQ_ALL(T)                          \
+    if (d <= 512) ZO_NQ(T, 1, 1);             \
+    else if (d <= 1024) ZO_NQ(T, 2, 1);       \
+    else if (d <= 2048) ZO_NQ(T, 1, 4);       \
+    else if (d <= 4096) ZO_NQ(T, 2, 4);       \
+    else ZO_NQ(T, 4, 4)
+    if (dtype == ZO_T_BF16) { ZO_NQ_ALL(zo_bf16); } else { ZO_NQ_ALL(float); }
+#undef ZO_NQ_ALL
 #undef ZO_NQ
     return hipGetLastError();
 }
