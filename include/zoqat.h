@@ -341,6 +341,16 @@ zo_status zo_gemm_nt_fused(const void* X_dev, const void* W_dev, const float* bi
  *   same values as storing gate and up first).  ZO_EUNSUPPORTED unless M * N2 >= 2^23, N2 and K multiples of 64. */
 zo_status zo_gemm_nt_swiglu(const void* X_dev, const void* W_dev, void* Y_dev, int32_t M, int32_t N2, int32_t K, void* hip_stream);
 
+/* The lm_head GEMM with the next-token cross entropy formed in its epilogue (the loss of the ZO objective, Eq. 2, on a
+ * decoder: the logits X W^T are never stored).  X dev bf16 [M][K] (M = B*S rows, S positions per sequence), W dev bf16
+ * [N][K] (N = vocabulary), ids dev int32 [M]: row m's target is ids[m + 1], clamped to [0, N); rows at the last position of a
+ * sequence have none.  row_loss dev fp32 [M] = log sum_n exp(logit[m][n]) - logit[m][target] (0 at last positions).
+ * scratch dev, zo_gemm_nt_ce_scratch_bytes(M, N) bytes, 16-byte aligned, overwritten.  ZO_EUNSUPPORTED unless
+ * M * N >= 2^23 and K a multiple of 64; ZO_ESHAPE unless S divides M. */
+size_t zo_gemm_nt_ce_scratch_bytes(int32_t M, int32_t N);
+zo_status zo_gemm_nt_ce(const void* X_dev, const void* W_dev, const int32_t* ids_dev, float* row_loss_dev, int32_t M, int32_t S,
+                        int32_t N, int32_t K, void* scratch_dev, void* hip_stream);
+
 /* Causal softmax attention of the decoder forward: for every batch b, head h and position s,
  * out[b,s,h,:] = sum_{j<=s} softmax_j(q[b,s,h,:].k[b,j,h,:] / sqrt(dh)) v[b,j,h,:].
  * q, k, v: dev, storage type dtype, element (b,s,h,i) at ((b*S + s) * row_stride + h*dh + i)
@@ -356,11 +366,13 @@ zo_status zo_attention_causal(const void* q_dev, const void* k_dev, const void* 
 enum { ZO_ROUTE_FUSED_SMALL_M = 1,    /* linears built from the masters inside the small-M kernel */
        ZO_ROUTE_FUSED_INT4 = 2,       /* frozen linears expanded from their packed codes inside the small-M kernel */
        ZO_ROUTE_SWIGLU_IN_GEMM = 4,   /* SwiGLU applied by the epilogue of the gate / up GEMM */
-       ZO_ROUTE_ROPE_IN_GEMM = 8 };   /* rotary embedding applied by the epilogue of the q | k | v GEMM */
+       ZO_ROUTE_ROPE_IN_GEMM = 8,     /* rotary embedding applied by the epilogue of the q | k | v GEMM */
+       ZO_ROUTE_CE_IN_GEMM = 16 };    /* cross entropy formed by the epilogue of the lm_head GEMM, no logits stored */
 uint32_t zo_debug_routes(const zo_ctx* ctx);
 
 /* Device buffers of the context's last forward, for layer-level parity tests.
- * which: 0 = final hidden state [M][d], 1 = logits fp32 [M][V] (linear arch: output Y [M][N]),
+ * which: 0 = final hidden state [M][d], 1 = logits fp32 [M][V] (linear arch: output Y [M][N]; ZO_EUNSUPPORTED after a
+ *        forward that took ZO_ROUTE_CE_IN_GEMM: it stored none),
  *        2 = residual stream after the last layer [M][d], 3 = q | k | v of the last layer [M][3d] (q and k after the
  *        rotary embedding where the architecture has one), 4 = attention output of the last layer [M][d].
  *        branch: 0 = '+' (or the single forward), 1 = '-'.  Returns the dev pointer in *ptr and its size in *bytes. */

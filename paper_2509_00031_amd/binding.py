@@ -19,7 +19,7 @@ STATUS = {0: "ZO_OK", 1: "ZO_EINVAL", 2: "ZO_ESHAPE", 3: "ZO_EALIGN", 4: "ZO_EHI
 ARCH_LINEAR, ARCH_LLAMA, ARCH_OPT = 0, 1, 2
 ACT_FP32, ACT_BF16 = 0, 1
 MASTER_F32, MASTER_F16 = 0, 1
-ROUTE_FUSED_SMALL_M, ROUTE_FUSED_INT4, ROUTE_SWIGLU_IN_GEMM, ROUTE_ROPE_IN_GEMM = 1, 2, 4, 8
+ROUTE_FUSED_SMALL_M, ROUTE_FUSED_INT4, ROUTE_SWIGLU_IN_GEMM, ROUTE_ROPE_IN_GEMM, ROUTE_CE_IN_GEMM = 1, 2, 4, 8, 16
 
 EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "zo_destroy", "zo_last_error",
            "zo_forward_quant", "zo_step", "zo_update", "zo_debug_philox_u32", "zo_debug_normal", "zo_update_tensor",
@@ -27,7 +27,7 @@ EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "
            "zo_gemm_nt", "zo_debug_buffer", "zo_profile_begin", "zo_profile_end", "zo_attention_causal",
            "zo_attention_scratch_bytes", "zo_pack_weight_int4", "zo_attach_frozen_int4", "zo_linear_frozen_int4", "zo_gemm_nt_fused", "zo_init_learned_params", "zo_step_groups", "zo_update_groups",
            "zo_debug_quant_weight_learned", "zo_debug_smooth_bias", "zo_linear_fakequant_fused", "zo_linear_fused_scratch_bytes",
-           "zo_step_multi", "zo_update_multi", "zo_lr_linear_decay", "zo_update_tensor_f16", "zo_master_bytes", "zo_linear_frozen_int4_fused", "zo_linear_frozen_fused_scratch_bytes", "zo_gemm_nt_swiglu", "zo_debug_routes"]
+           "zo_step_multi", "zo_update_multi", "zo_lr_linear_decay", "zo_update_tensor_f16", "zo_master_bytes", "zo_linear_frozen_int4_fused", "zo_linear_frozen_fused_scratch_bytes", "zo_gemm_nt_swiglu", "zo_debug_routes", "zo_gemm_nt_ce", "zo_gemm_nt_ce_scratch_bytes"]
 PROF_NAMES = ["gemm", "weight_quant", "act_quant", "attention", "update", "other", "fused_linear", "fused_int4_linear"]
 
 
@@ -77,6 +77,9 @@ _lib.zo_linear_frozen_fused_scratch_bytes.restype = _sz
 _lib.zo_linear_frozen_int4_fused.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp]
 _lib.zo_gemm_nt_swiglu.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _vp]
 _lib.zo_gemm_nt.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp]
+_lib.zo_gemm_nt_ce.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp]
+_lib.zo_gemm_nt_ce_scratch_bytes.argtypes = [_i32, _i32]
+_lib.zo_gemm_nt_ce_scratch_bytes.restype = _sz
 _lib.zo_debug_buffer.argtypes = [_vp, _i32, _i32, C.POINTER(_vp), C.POINTER(_sz)]
 _lib.zo_attention_causal.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i64, _i32, _vp, _vp]
 _lib.zo_attention_scratch_bytes.argtypes = [_i32, _i32, _i32, _i32, _i32]
@@ -422,6 +425,17 @@ def zo_gemm_nt_swiglu(X, W_interleaved):
     Y = torch.empty((M, N2 // 2), dtype=torch.bfloat16, device=X.device)
     _check(_lib.zo_gemm_nt_swiglu(X.data_ptr(), W_interleaved.data_ptr(), Y.data_ptr(), M, N2, K, _stream()), "zo_gemm_nt_swiglu")
     return Y
+
+
+def zo_gemm_nt_ce(X, W, ids, S):
+    """Row losses [M] of the next-token cross entropy of the logits X W^T (bf16 operands), which are not stored."""
+    M, K = X.shape
+    N = W.shape[0]
+    out = torch.empty(M, dtype=torch.float32, device=X.device)
+    scratch = torch.empty(max(_lib.zo_gemm_nt_ce_scratch_bytes(M, N), 16), dtype=torch.uint8, device=X.device)
+    _check(_lib.zo_gemm_nt_ce(X.data_ptr(), W.data_ptr(), ids.data_ptr(), out.data_ptr(), M, S, N, K, scratch.data_ptr(), _stream()),
+           "zo_gemm_nt_ce")
+    return out
 
 
 def zo_gemm_nt_fused(X, W, bias=None, residual=None, relu=False, Y=None):

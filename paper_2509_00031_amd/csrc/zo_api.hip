@@ -206,7 +206,15 @@ layout make_layout(const zo_config& c, int B, int S)
         r.att = take(M * d * ts);
         r.gu = take(M * ffn_rows * ts);
         r.act = take(M * f * ts);
-        r.logits = take(M * V * sizeof(float));
+        // logits: fp32 [M][V] -- or, where the lm_head GEMM forms the cross entropy in its epilogue, its per-tile
+        // partial results and target logits (and room for the logits of calls too small for that route)
+        size_t lg = M * V * sizeof(float);
+        if (zo_gemm_ce_supported((int)M, (int)V, (int)d, c.act_dtype == ZO_ACT_BF16 ? ZO_T_BF16 : ZO_T_F32)) {
+            const size_t small = ((size_t)256 * 256 * 128 + (size_t)ZO_FUSED_MAX_M * V) * sizeof(float);
+            const size_t ce = (zo_gemm_ce_part_floats((int)M, (int)V) + M) * sizeof(float);
+            lg = lg < small ? lg : (ce > small ? ce : small);
+        }
+        r.logits = take(lg);
         r.rowloss = take(M * sizeof(float));
     }
     L.total = off;
@@ -461,12 +469,14 @@ struct fwd {
         return ZO_OK;
     }
     zo_status gemm(size_t layout::per_branch::*in, size_t layout::per_branch::*out, int N, int K, bool bias, bool relu,
-                   bool residual, bool out_f32 = false, bool w_shared = false, bool swiglu = false, bool rope = false)
+                   bool residual, bool out_f32 = false, bool w_shared = false, bool swiglu = false, bool rope = false,
+                   const int32_t* ce_ids = nullptr)
     {
         const int requested = nweights;
         nweights = 0;
         if (swiglu) c->routes |= ZO_ROUTE_SWIGLU_IN_GEMM;
         if (rope) c->routes |= ZO_ROUTE_ROPE_IN_GEMM;
+        if (ce_ids) c->routes |= ZO_ROUTE_CE_IN_GEMM;
         if (npend > 0 && npend != requested) {           // cannot happen: the tensors of one GEMM share shape and route
             npend = 0;
             return fail(c, ZO_EUNSUPPORTED, "tensors of one GEMM took different routes");
@@ -550,6 +560,13 @@ struct fwd {
             a.rope_sin = at<float>(c->L.rope_sin);
             a.rope_cols = 2 * c->cfg.d_model;
             a.rope_S = S;
+        }
+        if (ce_ids) {                                    // `out` receives the partial results, then the target logits
+            a.ce_part = at<float>(c->L.br[0].*out);
+            a.ce_tgt = a.ce_part + zo_gemm_ce_part_floats(M, N);
+            a.ce_ids = ce_ids;
+            a.ce_S = S;
+            a.stridePart = a.strideTgt = nb == 2 ? (int64_t)(c->L.br[1].*out - c->L.br[0].*out) / 4 : 0;
         }
         prof_scope ps(c, ZO_PROF_GEMM);
         ZO_HIP(c, zo_launch_gemm(a, c->st));
@@ -726,10 +743,16 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
     if (!llama) ZO_TRY(F.vector(t++, 1));
     ZO_TRY(F.norm(&PB::x, &PB::h, !llama));
     ZO_TRY(F.weights(t++, 0, false));
-    ZO_TRY(F.gemm(&PB::h, &PB::logits, V, d, false, false, false, true));
+    // large bf16 forwards: the logits are never stored, the GEMM's epilogue leaves per-tile (maximum, sum of exponentials)
+    const bool ce_in_gemm = F.npend == 0 && zo_gemm_ce_supported(M, V, d, F.dt());
+    ZO_TRY(F.gemm(&PB::h, &PB::logits, V, d, false, false, false, true, false, false, false, ce_in_gemm ? ids : nullptr));
     prof_scope ps(c, ZO_PROF_OTHER);
     for (int b = 0; b < nb; ++b) {
-        ZO_HIP(c, zo_launch_ce_rows(F.at<float>(c->L.br[b].logits), ids, F.at<float>(c->L.br[b].rowloss), M, S, V, c->st));
+        if (ce_in_gemm) {
+            const float* part = F.at<float>(c->L.br[b].logits);
+            ZO_HIP(c, zo_launch_ce_combine(part, part + zo_gemm_ce_part_floats(M, V), F.at<float>(c->L.br[b].rowloss), M, S, V, c->st));
+        } else
+            ZO_HIP(c, zo_launch_ce_rows(F.at<float>(c->L.br[b].logits), ids, F.at<float>(c->L.br[b].rowloss), M, S, V, c->st));
         ZO_HIP(c, zo_launch_reduce_loss(F.at<float>(c->L.br[b].rowloss), M, 1.0f / ((float)B * (float)(S - 1)), loss_out + b, c->st));
     }
     return ZO_OK;
@@ -1070,7 +1093,9 @@ zo_status zo_debug_buffer(zo_ctx* ctx, int32_t which, int32_t branch, void** ptr
     }
     switch (which) {
         case 0: *ptr = ctx->ws + r.h; *bytes = M * c.d_model * ts; return ZO_OK;
-        case 1: *ptr = ctx->ws + r.logits; *bytes = M * (size_t)c.vocab * 4; return ZO_OK;
+        case 1:
+            if (ctx->routes & ZO_ROUTE_CE_IN_GEMM) return ZO_EUNSUPPORTED;   // that forward stored no logits
+            *ptr = ctx->ws + r.logits; *bytes = M * (size_t)c.vocab * 4; return ZO_OK;
         case 2: *ptr = ctx->ws + r.x; *bytes = M * c.d_model * ts; return ZO_OK;
         case 3: *ptr = ctx->ws + r.qkv; *bytes = M * 3 * (size_t)c.d_model * ts; return ZO_OK;
         case 4: *ptr = ctx->ws + r.att; *bytes = M * c.d_model * ts; return ZO_OK;
@@ -1365,6 +1390,30 @@ zo_status zo_gemm_nt_swiglu(const void* X_dev, const void* W_dev, void* Y_dev, i
     a.X = X_dev; a.W = W_dev; a.Y = Y_dev;
     a.M = M; a.N = N2; a.K = K; a.batch = 1; a.dtype = ZO_T_BF16; a.swiglu = 1;
     return zo_launch_gemm(a, (hipStream_t)hip_stream) == hipSuccess ? ZO_OK : ZO_EHIP;
+}
+
+size_t zo_gemm_nt_ce_scratch_bytes(int32_t M, int32_t N)
+{
+    if (M <= 0 || N <= 0) return 0;
+    return (zo_gemm_ce_part_floats(M, N) + (size_t)M) * sizeof(float);
+}
+
+zo_status zo_gemm_nt_ce(const void* X_dev, const void* W_dev, const int32_t* ids_dev, float* row_loss_dev, int32_t M, int32_t S,
+                        int32_t N, int32_t K, void* scratch_dev, void* hip_stream)
+{
+    if (!X_dev || !W_dev || !ids_dev || !row_loss_dev || !scratch_dev || M <= 0 || S <= 0 || N <= 0 || K <= 0) return ZO_EINVAL;
+    if (M % S) return ZO_ESHAPE;
+    if (!aligned16(X_dev) || !aligned16(W_dev) || !aligned16(scratch_dev)) return ZO_EALIGN;
+    if (!zo_gemm_ce_supported(M, N, K, ZO_T_BF16)) return ZO_EUNSUPPORTED;
+    zo_gemm_args a{};
+    a.X = X_dev; a.W = W_dev;
+    a.M = M; a.N = N; a.K = K; a.batch = 1; a.dtype = ZO_T_BF16; a.out_f32 = 1;
+    a.ce_part = (float*)scratch_dev;
+    a.ce_tgt = a.ce_part + zo_gemm_ce_part_floats(M, N);
+    a.ce_ids = ids_dev;
+    a.ce_S = S;
+    if (zo_launch_gemm(a, (hipStream_t)hip_stream) != hipSuccess) return ZO_EHIP;
+    return zo_launch_ce_combine(a.ce_part, a.ce_tgt, row_loss_dev, M, S, N, (hipStream_t)hip_stream) == hipSuccess ? ZO_OK : ZO_EHIP;
 }
 
 zo_status zo_gemm_nt_fused(const void* X_dev, const void* W_dev, const float* bias_dev, const void* residual_dev, int32_t relu,

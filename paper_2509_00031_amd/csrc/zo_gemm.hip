@@ -268,6 +268,10 @@ __device__ __forceinline__ void store_tile(const f32x16& acc, const zo_gemm_args
 // head -- the pair the rotary embedding mixes -- in the same lane and register.  Columns below rope_cols (q and k) are
 // rounded to the storage type, rotated by the angle table (position = row % rope_S) exactly as the stand-alone
 // kernel does, and every column is written back in its natural place.
+// EPI = 3 (lm_head): no output matrix at all.  A lane holds 32 logits of one token per 32-row block; per token and
+// 256-column tile the maximum and the sum of exp(logit - maximum) are formed (lane, its partner half, then the four
+// waves along n through LDS) and written to ce_part, and the lane that holds the token's target column writes that
+// logit to ce_tgt.  The cross entropy of a row is then a 2 * tiles_n-float reduction instead of a pass over V logits.
 template <typename TY, int NW, int BK, int ST, int EPI = 0>
 __global__ __launch_bounds__(NW * 64) void zo_gemm_bf16_dma_kernel(zo_gemm_args a)
 {
@@ -415,6 +419,71 @@ __global__ __launch_bounds__(NW * 64) void zo_gemm_bf16_dma_kernel(zo_gemm_args 
     TY* Y = (TY*)a.Y + bz * a.strideY;
     const float* bias = a.bias ? a.bias + bz * a.strideBias : nullptr;
     const zo_bf16* res = a.residual ? (const zo_bf16*)a.residual + bz * a.strideRes : nullptr;
+    if constexpr (EPI == 3) {
+        static_assert(TN == 2 && WN == 64 && WN_WAVES == 4, "a lane holds 32 of a wave's 64 columns");
+        constexpr float LOG2E = 1.4426950408889634f;
+        __syncthreads();                                    // the stages are idle: [2][4 waves along n][256 rows] floats
+        float* red = reinterpret_cast<float*>(lds);
+        const int g = lane >> 5;
+        float* part = a.ce_part + bz * a.stridePart;
+        float* tgt_out = a.ce_tgt + bz * a.strideTgt;
+        const int col0 = n0 + wn * WN + g * 4;              // column of the lane's value (i, rg, e) = col0 + 32 i + 8 rg + e
+#pragma unroll
+        for (int j = 0; j < TM; ++j) {
+            const int ml = wm * WM + j * 32 + (lane & 31);
+            const int m = m0 + ml;
+            float v[32];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int col = col0 + 32 * i + 8 * (r >> 2) + (r & 3);
+                    v[16 * i + r] = col < N ? acc[i][j][r] : -INFINITY;
+                }
+            float mx = fmaxf(fmaxf(v[0], v[1]), v[2]);
+#pragma unroll
+            for (int r = 3; r < 31; r += 2) mx = fmaxf(fmaxf(mx, v[r]), v[r + 1]);
+            mx = fmaxf(mx, v[31]);
+            {
+                const auto h = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+                mx = fmaxf(__uint_as_float(h[0]), __uint_as_float(h[1]));
+            }
+            const float ref = mx == -INFINITY ? 0.0f : mx;  // a wave whose 64 columns all lie past N contributes (-inf, 0)
+            float se = 0.0f;
+#pragma unroll
+            for (int r = 0; r < 32; ++r) se += __builtin_amdgcn_exp2f((v[r] - ref) * LOG2E);
+            {
+                const auto h = __builtin_amdgcn_permlane32_swap(__float_as_uint(se), __float_as_uint(se), false, false);
+                se = __uint_as_float(h[0]) + __uint_as_float(h[1]);
+            }
+            if (g == 0) { red[wn * 256 + ml] = mx; red[(4 + wn) * 256 + ml] = se; }
+            if (m < M && (m % a.ce_S) != a.ce_S - 1) {
+                int t = a.ce_ids[m + 1];
+                t = t < 0 ? 0 : (t >= N ? N - 1 : t);
+                const int rel = t - col0;
+                if (rel >= 0 && rel < 64 && (rel & 4) == 0) {
+                    const int idx = (rel >> 5) * 16 + ((rel >> 3) & 3) * 4 + (rel & 3);
+                    float tv = v[0];
+#pragma unroll
+                    for (int r = 1; r < 32; ++r) tv = idx == r ? v[r] : tv;
+                    tgt_out[m] = tv;
+                }
+            }
+        }
+        __syncthreads();
+        if (tid < 256 && m0 + tid < M) {
+            float mw[4], sw[4];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) { mw[w] = red[w * 256 + tid]; sw[w] = red[(4 + w) * 256 + tid]; }
+            const float mt = fmaxf(fmaxf(mw[0], mw[1]), fmaxf(mw[2], mw[3]));   // finite: a tile has a column below N
+            float st = 0.0f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) st += sw[w] * __builtin_amdgcn_exp2f((mw[w] - mt) * LOG2E);
+            float2* dst = reinterpret_cast<float2*>(part) + (int64_t)(m0 + tid) * tiles_n + tile_n;
+            *dst = make_float2(mt, st);
+        }
+        return;
+    }
     if constexpr (EPI == 1) {
         static_assert(sizeof(TY) == 2 && TN == 2, "gate / up pairs need two n-tiles per wave and bf16 output");
         // each wave: 128 rows x 32 channels, staged through its LDS slice (64-byte rows, 8-byte granules XOR-swizzled by
@@ -677,6 +746,43 @@ bool zo_gemm_swiglu_supported(int32_t M, int32_t N, int32_t K, int dtype)
     return (int64_t)M * K * 2 < ((int64_t)1 << 32) && (int64_t)N * K * 2 < ((int64_t)1 << 32);
 }
 
+// the lm_head GEMM with the cross entropy in its epilogue: the large-shape kernel
+bool zo_gemm_ce_supported(int32_t M, int32_t N, int32_t K, int dtype)
+{
+    if (dtype != ZO_T_BF16 || M <= 0 || N <= 0 || (K & 63)) return false;
+    if ((int64_t)M * N < (int64_t)256 * 256 * 128) return false;
+    return (int64_t)M * K * 2 < ((int64_t)1 << 32) && (int64_t)N * K * 2 < ((int64_t)1 << 32);
+}
+size_t zo_gemm_ce_part_floats(int32_t M, int32_t N) { return (size_t)M * ((N + 255) / 256) * 2; }
+
+// one wavefront per row: the tiles' (maximum, sum) pairs are merged in a fixed order
+__global__ __launch_bounds__(256) void zo_ce_combine_kernel(const float* __restrict__ part, const float* __restrict__ tgt,
+                                                            float* __restrict__ row_loss, int M, int S, int tiles_n)
+{
+    const int lane = threadIdx.x & 63;
+    const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (m >= M) return;
+    if ((m % S) == S - 1) {
+        if (lane == 0) row_loss[m] = 0.0f;
+        return;
+    }
+    const float2* p = reinterpret_cast<const float2*>(part) + (int64_t)m * tiles_n;
+    float mx = -INFINITY;
+    for (int t = lane; t < tiles_n; t += 64) mx = fmaxf(mx, p[t].x);
+    mx = zo_group_max<64>(mx);
+    float se = 0.0f;
+    for (int t = lane; t < tiles_n; t += 64) se += p[t].y * __expf(p[t].x - mx);
+    se = zo_group_sum<64>(se);
+    if (lane == 0) row_loss[m] = (logf(se) + mx) - tgt[m];
+}
+
+hipError_t zo_launch_ce_combine(const float* part, const float* tgt, float* row_loss, int32_t M, int32_t S, int32_t N, hipStream_t st)
+{
+    if (M == 0) return hipSuccess;
+    zo_ce_combine_kernel<<<(M + 3) / 4, 256, 0, st>>>(part, tgt, row_loss, M, S, (N + 255) / 256);
+    return hipGetLastError();
+}
+
 // the fused q | k | v GEMM with the rotary embedding in its epilogue: large shapes, whole heads of 128 per half tile
 bool zo_gemm_rope_supported(int32_t M, int32_t N, int32_t K, int dtype)
 {
@@ -692,6 +798,17 @@ hipError_t zo_launch_gemm(const zo_gemm_args& a, hipStream_t st)
         const bool large = (int64_t)a.M * a.N >= (int64_t)256 * 256 * 128;
         // operand bytes must be addressable with 32-bit offsets from the (batch) base pointers
         const bool off32 = (int64_t)a.M * a.K * 2 < ((int64_t)1 << 32) && (int64_t)a.N * a.K * 2 < ((int64_t)1 << 32);
+        if (a.ce_part) {
+            if (!zo_gemm_ce_supported(a.M, a.N, a.K, a.dtype) || a.bias || a.residual || a.relu || !a.ce_tgt || !a.ce_ids || a.ce_S <= 0)
+                return hipErrorInvalidValue;
+            const int tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
+            constexpr int lds_bytes = 2 * 512 * 64 * 2;
+            hipError_t e_ = hipFuncSetAttribute((const void*)zo_gemm_bf16_dma_kernel<float, 8, 64, 2, 3>,
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+            if (e_ != hipSuccess) return e_;
+            zo_gemm_bf16_dma_kernel<float, 8, 64, 2, 3><<<dim3(tiles, 1, a.batch), 8 * 64, lds_bytes, st>>>(a);
+            return hipGetLastError();
+        }
         if (a.rope_cos) {
             if (!zo_gemm_rope_supported(a.M, a.N, a.K, a.dtype) || a.bias || a.residual || a.relu || a.out_f32 || !a.rope_sin || a.rope_S <= 0 ||
                 (a.rope_cols & 255))
@@ -717,27 +834,18 @@ hipError_t zo_launch_gemm(const zo_gemm_args& a, hipStream_t st)
         if (large && (a.K & 63) == 0 && off32) {
             const int tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
             const dim3 grid(tiles, 1, a.batch);
-            static const int variant = getenv("ZO_GEMM_VARIANT") ? atoi(getenv("ZO_GEMM_VARIANT")) : 2;
-            if (variant < 0) return launch_bf16<256, 256>(a, st);
-#define ZO_DMA_LAUNCH(TY, NW, BK, ST)                                                                                      \
-    do {                                                                                                                   \
-        constexpr int lds_bytes = ST * 512 * BK * 2;                                                                       \
-        hipError_t e_ = hipFuncSetAttribute((const void*)zo_gemm_bf16_dma_kernel<TY, NW, BK, ST>,                          \
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);                        \
-        if (e_ != hipSuccess) return e_;                                                                                   \
-        zo_gemm_bf16_dma_kernel<TY, NW, BK, ST><<<grid, NW * 64, lds_bytes, st>>>(a);                                      \
-    } while (0)
-#define ZO_DMA_VARIANTS(TY)                                                                                                \
-    do {                                                                                                                   \
-        if (variant == 0) ZO_DMA_LAUNCH(TY, 4, 64, 2);                                                                     \
-        else if (variant == 1) ZO_DMA_LAUNCH(TY, 4, 32, 4);                                                                \
-        else if (variant == 2) ZO_DMA_LAUNCH(TY, 8, 64, 2);                                                                \
-        else if (variant == 3) ZO_DMA_LAUNCH(TY, 8, 32, 4);                                                                \
-        else ZO_DMA_LAUNCH(TY, 8, 32, 3);                                                                                  \
-    } while (0)
-            if (a.out_f32) ZO_DMA_VARIANTS(float); else ZO_DMA_VARIANTS(zo_bf16);
-#undef ZO_DMA_VARIANTS
-#undef ZO_DMA_LAUNCH
+            constexpr int lds_bytes = 2 * 512 * 64 * 2;
+            if (a.out_f32) {
+                hipError_t e_ = hipFuncSetAttribute((const void*)zo_gemm_bf16_dma_kernel<float, 8, 64, 2>,
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+                if (e_ != hipSuccess) return e_;
+                zo_gemm_bf16_dma_kernel<float, 8, 64, 2><<<grid, 8 * 64, lds_bytes, st>>>(a);
+            } else {
+                hipError_t e_ = hipFuncSetAttribute((const void*)zo_gemm_bf16_dma_kernel<zo_bf16, 8, 64, 2>,
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+                if (e_ != hipSuccess) return e_;
+                zo_gemm_bf16_dma_kernel<zo_bf16, 8, 64, 2><<<grid, 8 * 64, lds_bytes, st>>>(a);
+            }
             return hipGetLastError();
         }
         if (large) return launch_bf16<256, 256>(a, st);

@@ -88,7 +88,18 @@ struct zo_gemm_args {
     // with the 32-row blocks of every head in the order [0, 2, 1, 3]; columns < rope_cols rotated, position = row % rope_S
     const float* rope_cos; const float* rope_sin;   // fp32 [max_seq][64]
     int32_t rope_cols, rope_S;
+    // cross entropy in the epilogue of the lm_head GEMM (ce_part != NULL switches it on; Y is not written): per row and
+    // 256-column tile the maximum logit and the sum of exp(logit - maximum) go to ce_part[m][tiles_n][2]; the logit of
+    // the row's target ce_ids[m + 1] (clamped to the vocabulary; no target at positions m % ce_S == ce_S - 1) to ce_tgt[m]
+    float* ce_part; float* ce_tgt;
+    const int32_t* ce_ids;      // shared by the batch entries
+    int32_t ce_S;
+    int64_t stridePart, strideTgt;   // floats between batch entries
 };
+bool zo_gemm_ce_supported(int32_t M, int32_t N, int32_t K, int dtype);
+size_t zo_gemm_ce_part_floats(int32_t M, int32_t N);     // floats of ce_part for one batch entry
+// row_loss[m] = log sum exp(logits[m][:]) - logits[m][target], from the partial results above; 0 at the last position
+hipError_t zo_launch_ce_combine(const float* part, const float* tgt, float* row_loss, int32_t M, int32_t S, int32_t N, hipStream_t st);
 bool zo_gemm_rope_supported(int32_t M, int32_t N, int32_t K, int dtype);
 bool zo_gemm_swiglu_supported(int32_t M, int32_t N, int32_t K, int dtype);
 hipError_t zo_launch_gemm(const zo_gemm_args& a, hipStream_t st);
