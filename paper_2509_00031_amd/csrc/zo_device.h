@@ -267,10 +267,8 @@ ZO_DEV zo_qparams zo_qparams_sym(float amax, int bits)
 }
 ZO_DEV float zo_code(const zo_qparams& q, float x)
 {
-    float c = __builtin_rintf(x * q.inv) + q.zp;
-    c = c < q.qn ? q.qn : c;
-    c = c > q.qp ? q.qp : c;
-    return c;
+    const float c = __builtin_rintf(x * q.inv) + q.zp;
+    return __builtin_amdgcn_fmed3f(c, q.qn, q.qp);       // clamp to [qn, qp] in one instruction
 }
 ZO_DEV float zo_dequant(const zo_qparams& q, float code) { return (code - q.zp) * q.step; }
 
