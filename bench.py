@@ -55,6 +55,7 @@ WORKLOADS = {
 # read + 1.000 x 256.7 MB written, averaged over the GEMM launches of a step (all epilogue forms).  Counters cannot be
 # read from inside the run, so other workloads report null.
 MEASURED_GEMM_TRAFFIC = {"llama7b_w4a8_g64_8x1024": 2.0 * 1376.5e6 + 256.7e6}
+BREAKDOWN_STEPS = 2
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 # plain vector ALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions per second (the fp32 vector peak of
@@ -202,8 +203,13 @@ def main():
     for i in range(args.warmup):
         one_step(i)
     torch.cuda.synchronize()
+    # Timed region: only the launches of the kernel the roofline object is about (the GEMM; the fused kernels on the
+    # small-batch workloads) are bracketed with events -- a bracket leaves the stream idle for a few microseconds, and a
+    # step has about a thousand launches.  The per-category breakdown and the update kernel's figure come from
+    # BREAKDOWN_STEPS further steps, after the timed region, with every launch bracketed.
+    ROOFLINE_CATEGORIES = ("gemm", "fused_linear", "fused_int4_linear")
     if not args.no_profile:
-        ctx.zo_profile_begin()
+        ctx.zo_profile_begin_mask(ROOFLINE_CATEGORIES)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -212,6 +218,12 @@ def main():
     elapsed = time.perf_counter() - t0
     prof = None if args.no_profile else ctx.zo_profile_end()
     losses = out.cpu().tolist()
+    prof_all = None
+    if not args.no_profile:
+        ctx.zo_profile_begin()
+        for i in range(BREAKDOWN_STEPS):
+            one_step(args.warmup + args.steps + i)
+        prof_all = ctx.zo_profile_end()
 
     ms_per_step = 1e3 * elapsed / args.steps
     res = {
@@ -260,13 +272,14 @@ def main():
                                "launches": fused_launches, "avg_launch_ms": avg_ms, "params_per_launch": params_per_launch,
                                "master_GBps": 4.0 * params_per_launch / (avg_ms * 1e-3) / 1e9}
             res["gemm_tflops"] = gflops * args.steps / (fused_ms * 1e-3) / 1e12
-        upd_ms, upd_groups = prof["update"]
+        upd_ms, upd_groups = prof_all["update"]
         upd_bpp = 8 if args.masters == "f32" else 4          # one read + one write of every trainable master
         upd_gbs = upd_bpp * n_params * upd_groups / (upd_ms * 1e-3) / 1e9 if upd_ms > 0 else None
         res["update_kernel"] = {"bound": "hbm", "achieved": upd_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                 "frac": upd_gbs / PEAK_HBM_GBS if upd_gbs else None, "bytes_per_param": upd_bpp,
                                 "ms_per_step": upd_ms / max(upd_groups, 1)}
-        res["breakdown_ms_per_step"] = {k: v[0] / args.steps for k, v in prof.items()}
+        res["breakdown_ms_per_step"] = {k: v[0] / BREAKDOWN_STEPS for k, v in prof_all.items()}
+        res["breakdown_source"] = "%d further steps after the timed region, every launch bracketed by events" % BREAKDOWN_STEPS
     res["step_flops"] = gflops + attention_flops_per_step(w) * args.directions
     res["step_tflops"] = res["step_flops"] / (ms_per_step * 1e-3) / 1e12
     ctx.close()

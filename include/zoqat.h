@@ -172,6 +172,10 @@ enum { ZO_PROF_GEMM = 0, ZO_PROF_WEIGHT_QUANT = 1, ZO_PROF_ACT_QUANT = 2, ZO_PRO
        ZO_PROF_FUSED_INT4 = 7 /* a group = one launch of the small-M kernel that expands packed codes */,
        ZO_PROF_CATEGORIES = 8 };
 zo_status zo_profile_begin(zo_ctx* ctx);
+/* The same with only the categories whose bit (1 << ZO_PROF_*) is set in category_mask bracketed: an event pair costs a few
+ * microseconds of idle stream between two kernels (about 1.5 % of a 7B-shaped step when every launch is bracketed), so a timed
+ * region brackets only the kernel whose duration it needs. */
+zo_status zo_profile_begin_mask(zo_ctx* ctx, uint32_t category_mask);
 zo_status zo_profile_end(zo_ctx* ctx, float* ms_host, int32_t* launches_host);
 
 /* ---- stand-alone pieces of the path (same device code as the step), for tests and benches ---- */

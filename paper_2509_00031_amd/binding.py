@@ -27,7 +27,7 @@ EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "
            "zo_gemm_nt", "zo_debug_buffer", "zo_profile_begin", "zo_profile_end", "zo_attention_causal",
            "zo_attention_scratch_bytes", "zo_pack_weight_int4", "zo_attach_frozen_int4", "zo_linear_frozen_int4", "zo_gemm_nt_fused", "zo_init_learned_params", "zo_step_groups", "zo_update_groups",
            "zo_debug_quant_weight_learned", "zo_debug_smooth_bias", "zo_linear_fakequant_fused", "zo_linear_fused_scratch_bytes",
-           "zo_step_multi", "zo_update_multi", "zo_lr_linear_decay", "zo_update_tensor_f16", "zo_master_bytes", "zo_linear_frozen_int4_fused", "zo_linear_frozen_fused_scratch_bytes", "zo_gemm_nt_swiglu", "zo_debug_routes", "zo_gemm_nt_ce", "zo_gemm_nt_ce_scratch_bytes"]
+           "zo_step_multi", "zo_update_multi", "zo_lr_linear_decay", "zo_update_tensor_f16", "zo_master_bytes", "zo_linear_frozen_int4_fused", "zo_linear_frozen_fused_scratch_bytes", "zo_gemm_nt_swiglu", "zo_debug_routes", "zo_gemm_nt_ce", "zo_gemm_nt_ce_scratch_bytes", "zo_profile_begin_mask"]
 PROF_NAMES = ["gemm", "weight_quant", "act_quant", "attention", "update", "other", "fused_linear", "fused_int4_linear"]
 
 
@@ -80,6 +80,7 @@ _lib.zo_gemm_nt.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp]
 _lib.zo_gemm_nt_ce.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp]
 _lib.zo_gemm_nt_ce_scratch_bytes.argtypes = [_i32, _i32]
 _lib.zo_gemm_nt_ce_scratch_bytes.restype = _sz
+_lib.zo_profile_begin_mask.argtypes = [_vp, C.c_uint32]
 _lib.zo_debug_buffer.argtypes = [_vp, _i32, _i32, C.POINTER(_vp), C.POINTER(_sz)]
 _lib.zo_attention_causal.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i64, _i32, _vp, _vp]
 _lib.zo_attention_scratch_bytes.argtypes = [_i32, _i32, _i32, _i32, _i32]
@@ -249,6 +250,13 @@ class Context:
 
     def zo_profile_begin(self):
         _check(_lib.zo_profile_begin(self.handle), "zo_profile_begin", self.handle)
+
+    def zo_profile_begin_mask(self, categories):
+        """categories: names out of PROF_NAMES whose launches are bracketed."""
+        mask = 0
+        for name in categories:
+            mask |= 1 << PROF_NAMES.index(name)
+        _check(_lib.zo_profile_begin_mask(self.handle, mask), "zo_profile_begin_mask", self.handle)
 
     def zo_profile_end(self):
         """Synchronises; returns {category: (milliseconds, launches)}."""

@@ -244,6 +244,7 @@ struct zo_ctx {
     std::string err;
     // optional per-launch timing (zo_profile_begin / zo_profile_end)
     bool prof = false;
+    uint32_t prof_mask = 0xFFFFFFFFu;     // categories whose launches are bracketed
     std::vector<hipEvent_t> ev_pool;      // created on demand, reused across sessions
     size_t ev_used = 0;
     std::vector<int> ev_cat;              // category of event pair i = events 2i, 2i+1
@@ -264,7 +265,7 @@ zo_status fail(zo_ctx* c, zo_status s, const char* what, hipError_t e = hipSucce
 struct prof_scope {
     zo_ctx* c;
     bool on;
-    prof_scope(zo_ctx* ctx, int cat) : c(ctx), on(ctx && ctx->prof)
+    prof_scope(zo_ctx* ctx, int cat) : c(ctx), on(ctx && ctx->prof && ((ctx->prof_mask >> cat) & 1u))
     {
         if (!on) return;
         while (c->ev_pool.size() < c->ev_used + 2) {
@@ -886,10 +887,13 @@ zo_status zo_destroy(zo_ctx* ctx)
     return ZO_OK;
 }
 
-zo_status zo_profile_begin(zo_ctx* ctx)
+zo_status zo_profile_begin(zo_ctx* ctx) { return zo_profile_begin_mask(ctx, 0xFFFFFFFFu); }
+
+zo_status zo_profile_begin_mask(zo_ctx* ctx, uint32_t category_mask)
 {
     if (!ctx) return ZO_EINVAL;
     ctx->prof = true;
+    ctx->prof_mask = category_mask;
     ctx->ev_used = 0;
     ctx->ev_cat.clear();
     return ZO_OK;
