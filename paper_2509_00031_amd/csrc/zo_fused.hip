@@ -609,13 +609,14 @@ static hipError_t launch_int4_j(const zo_fused_args& a, hipStream_t st)
     }
 }
 
-// number of K ranges: enough workgroups for about two per CU (one per two CUs when a workgroup carries 8 m-tiles and
-// its partial sums are large: measured optimum), at least two slabs each, at most 16
+// number of K ranges: enough workgroups for about one per CU (one per two CUs when a workgroup carries 8 m-tiles): every
+// further range adds a set of fp32 partial sums that is written and read back, and that traffic, not the codes', is what
+// the kernel waits for (measured optimum); at least two slabs each, at most 16
 static int splitk_ranges(int N, int K, int group, int zdim, int MT)
 {
     const int slab = group >= 128 ? 128 : group;
     const int tiles = ((N + 255) / 256) * zdim, nslab = K / slab;
-    const int target = MT >= 8 ? 128 : 512;
+    const int target = MT >= 8 ? 128 : 256;
     int ks = (target + tiles - 1) / tiles;
     if (ks > nslab / 2) ks = nslab / 2;
     if (ks > 16) ks = 16;
