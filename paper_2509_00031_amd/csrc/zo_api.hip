@@ -362,7 +362,7 @@ struct fwd {
             const zo_learned lp{q[0][0], q[0][1], q[0][2], q[0][3], p.smooth >= 0 ? vec(0, 3) : nullptr};
             const zo_learned lm{q[1][0], q[1][1], q[1][2], q[1][3], (p.smooth >= 0 && nb == 2) ? vec(1, 3) : nullptr};
             ZO_HIP(c, zo_launch_fq_weight_learned((const float*)c->params[t].ptr, (int)p.rows, (int)p.cols, bits, c->cfg.w_group, seed, t,
-                                                  eps_of(t), dt(), lp, lm, op, om, nullptr, c->st));
+                                                  eps_of(t), dt(), lp, lm, op, om, nullptr, c->st, ilv));
             return ZO_OK;
         }
         ZO_HIP(c, zo_launch_fq_weight(c->params[t].ptr, (int)p.rows, (int)p.cols, bits, c->cfg.w_group,
@@ -376,16 +376,16 @@ struct fwd {
     bool rope_in_gemm(int t_q) const
     {
         const zo_config& cfg = c->cfg;
-        if (cfg.no_fused || cfg.arch != ZO_ARCH_LLAMA || cfg.learn_clip || cfg.learn_smooth) return false;
-        if (cfg.w_bits != 0 && (cfg.w_group == 0 || cfg.w_group > 512)) return false;
+        if (cfg.no_fused || cfg.arch != ZO_ARCH_LLAMA || cfg.learn_smooth) return false;      // smoothing gives these linears a bias
+        if (cfg.w_bits != 0 && !cfg.learn_clip && (cfg.w_group == 0 || cfg.w_group > 512)) return false;
         if (cfg.d_model / cfg.n_heads != 128 || fused_ok(t_q, true)) return false;
         return zo_gemm_rope_supported(M, 3 * cfg.d_model, cfg.d_model, dt());
     }
     bool swiglu_in_gemm(int t_gate) const
     {
         const zo_config& cfg = c->cfg;
-        if (cfg.no_fused || cfg.arch != ZO_ARCH_LLAMA || cfg.learn_clip || cfg.learn_smooth) return false;
-        if (cfg.w_bits != 0 && (cfg.w_group == 0 || cfg.w_group > 512)) return false;
+        if (cfg.no_fused || cfg.arch != ZO_ARCH_LLAMA || cfg.learn_smooth) return false;      // smoothing gives these linears a bias
+        if (cfg.w_bits != 0 && !cfg.learn_clip && (cfg.w_group == 0 || cfg.w_group > 512)) return false;
         if ((cfg.d_ffn & 31) || fused_ok(t_gate, true) || fused_ok(t_gate + 1, true)) return false;
         return zo_gemm_swiglu_supported(M, 2 * cfg.d_ffn, cfg.d_model, dt());
     }

@@ -537,7 +537,7 @@ hipError_t zo_launch_fq_weight(const void* W, int32_t N, int32_t K, int32_t bits
 // ---------------------------------------------------------------------------------------------
 template <typename TO>
 __device__ __forceinline__ void fq_learned_branch(const float w[8], const float z[8], float e, const zo_learned& p, int64_t g, int kb,
-                                                  int bits, TO* out, int64_t b, uint8_t* codes)
+                                                  int bits, TO* out, int64_t b, int64_t ob, uint8_t* codes)
 {
     float st = p.step[g];
     if (!(st >= 1e-5f)) st = 1e-5f;
@@ -562,16 +562,17 @@ __device__ __forceinline__ void fq_learned_branch(const float w[8], const float 
         if (codes) codes[8 * b + i] = (uint8_t)q;
         o[i] = (q - zr) * st;
     }
-    zo_store8(out + 8 * b, o);
+    zo_store8(out + 8 * ob, o);
 }
 
 template <typename TO>
 __global__ __launch_bounds__(256) void zo_fq_weight_learned_kernel(const float* __restrict__ W, int64_t nblk, int k8, int gl, zo_stream s,
                                                                    float eps, int bits, zo_learned pp, zo_learned pm,
-                                                                   TO* __restrict__ out_p, TO* __restrict__ out_m, uint8_t* codes)
+                                                                   TO* __restrict__ out_p, TO* __restrict__ out_m, uint8_t* codes, int ilv)
 {
     const int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (b >= nblk) return;
+    const int64_t ob = interleaved_block(b, k8, ilv);          // rows interleaved for the GEMM epilogues (0: as stored)
     float w[8], z[8];
     zo_load8(W + 8 * b, w);
     if (eps != 0.0f) zo_z8(s, (uint64_t)b, z);
@@ -581,13 +582,13 @@ __global__ __launch_bounds__(256) void zo_fq_weight_learned_kernel(const float* 
     }
     const int64_t g = b / gl;
     const int kb = (int)(b % k8) * 8;
-    fq_learned_branch<TO>(w, z, eps, pp, g, kb, bits, out_p, b, codes);
-    if (out_m) fq_learned_branch<TO>(w, z, -eps, pm, g, kb, bits, out_m, b, nullptr);
+    fq_learned_branch<TO>(w, z, eps, pp, g, kb, bits, out_p, b, ob, codes);
+    if (out_m) fq_learned_branch<TO>(w, z, -eps, pm, g, kb, bits, out_m, b, ob, nullptr);
 }
 
 hipError_t zo_launch_fq_weight_learned(const float* W, int32_t N, int32_t K, int32_t bits, int32_t group, uint64_t seed, int32_t tid,
                                        float eps, int dtype, const zo_learned& pp, const zo_learned& pm, void* out_plus, void* out_minus,
-                                       uint8_t* codes, hipStream_t st)
+                                       uint8_t* codes, hipStream_t st, int ilv)
 {
     const int64_t nblk = (int64_t)N * K / 8;
     if (nblk == 0) return hipSuccess;
@@ -597,10 +598,10 @@ hipError_t zo_launch_fq_weight_learned(const float* W, int32_t N, int32_t K, int
     const zo_stream s = make_stream(seed, tid);
     if (dtype == ZO_T_BF16)
         zo_fq_weight_learned_kernel<zo_bf16><<<grid, 256, 0, st>>>(W, nblk, K / 8, group / 8, s, eps, bits, pp, pm, (zo_bf16*)out_plus,
-                                                                   (zo_bf16*)out_minus, codes);
+                                                                   (zo_bf16*)out_minus, codes, ilv);
     else
         zo_fq_weight_learned_kernel<float><<<grid, 256, 0, st>>>(W, nblk, K / 8, group / 8, s, eps, bits, pp, pm, (float*)out_plus,
-                                                                 (float*)out_minus, codes);
+                                                                 (float*)out_minus, codes, ilv);
     return hipGetLastError();
 }
 

@@ -60,7 +60,7 @@ hipError_t zo_launch_fq_act(const void* X, void* Xhat, int32_t M, int32_t K, int
 struct zo_learned { const float* step; const float* zp; const float* alpha; const float* beta; const float* scale; };
 hipError_t zo_launch_fq_weight_learned(const float* W, int32_t N, int32_t K, int32_t bits, int32_t group, uint64_t seed, int32_t tid,
                                        float eps, int dtype, const zo_learned& pp, const zo_learned& pm, void* out_plus, void* out_minus,
-                                       uint8_t* codes, hipStream_t st);
+                                       uint8_t* codes, hipStream_t st, int ilv = 0);
 // initial parameters from the dynamic scheme on W; zp_scratch: int32 [N][K/group]
 hipError_t zo_launch_init_learned(const float* W, int32_t N, int32_t K, int32_t bits, int32_t group, float* step, float* zp,
                                   float* alpha, float* beta, int32_t* zp_scratch, hipStream_t st);

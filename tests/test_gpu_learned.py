@@ -160,3 +160,42 @@ def test_unsupported_combinations_are_refused():
     for kw in (dict(a_bits=16, learn_clip=1, learn_smooth=1), dict(a_bits=8, learn_smooth=1), dict(a_bits=8, learn_clip=1, lightweight=1)):
         cfg = zo.make_config(1, act_dtype=0, **base, **kw)
         assert zo.zo_workspace_bytes(cfg, 1, 8) == 0
+
+
+def test_learned_clipping_through_the_gemm_epilogues():
+    """6 x 1024 tokens, 4 heads of 128, learned clipping (Eq. 5) without smoothing: the learned weight quantizer writes the
+    q | k | v rows with the head blocks permuted and the gate / up rows interleaved, so the rotary embedding and SwiGLU
+    run in the GEMM epilogues as they do with the dynamic quantizer.  Loss against the oracle and against the route with
+    the stand-alone kernels; every parameter group moved by its own coefficient."""
+    torch, zo = gpu()
+    kw = dict(n_layers=1, d_model=512, n_heads=4, d_ffn=1024, vocab=256, max_seq=1024, w_bits=4, w_group=64, a_bits=8, learn_clip=1)
+    B, S = 6, 1024
+    ocfg = orc.Config(orc.ARCH_LLAMA, act_dtype=1, **kw)
+    shapes = orc.param_shapes(ocfg)
+    params = synth.model_params(shapes, 711)
+    orc.init_learned_params(ocfg, params)
+    for i, (name, shape, _) in enumerate(shapes):
+        if name.endswith(".q_alpha"):
+            params[i][...] = 0.04
+        if name.endswith(".q_beta"):
+            params[i][...] = 0.97
+    ids = synth.token_ids(B, S, 256, 712)
+    ref = orc.forward(ocfg, params, ids=ids, seed=8, eps_signed=1e-3)
+    losses = []
+    for no_fused in (0, 1):
+        cfg = zo.make_config(zo.ARCH_LLAMA, act_dtype=1, no_fused=no_fused, **kw)
+        gp = [to_dev(w, torch) for w in params]
+        ctx = zo.Context(cfg, gp, B, S)
+        idd = to_dev(ids, torch)
+        losses.append(ctx.zo_forward_quant(idd, None, B, S, seed=8, eps_signed=1e-3).item())
+        assert ctx.zo_debug_routes() == (0 if no_fused else zo.ROUTE_SWIGLU_IN_GEMM | zo.ROUTE_ROPE_IN_GEMM)
+        assert abs(losses[-1] - ref) <= 3e-3 * abs(ref), (losses[-1], ref)
+        if not no_fused:
+            lrs = (1e-2, 3e-2, 5e-2)
+            out = ctx.zo_step_groups(idd, None, B, S, 6, 1e-3, *lrs).cpu().numpy()
+            groups = orc.param_groups(ocfg)
+            for i in (0, 1, 2, len(params) - 1):
+                want = orc.update(params[i].copy(), 6, i, np.float32(out[3 + groups[i]]))
+                assert np.array_equal(gp[i].cpu().numpy().reshape(params[i].shape), want), i
+        ctx.close()
+    assert abs(losses[0] - losses[1]) <= 2e-4 * abs(ref)
