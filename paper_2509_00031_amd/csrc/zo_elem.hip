@@ -308,18 +308,33 @@ hipError_t zo_launch_update_f16(void* w, int64_t numel, const zo_multi_seeds& ms
 // Output position (in 8-element blocks) of input block b of a matrix with kb blocks per row when the rows go out
 // interleaved for the gate / up GEMM with SwiGLU in its epilogue: blocks of 32 gate rows (ilv = 1) alternate with the
 // 32 up rows (ilv = 2) of the same channels; or (ilv = 3) for the q | k | v GEMM with the rotary embedding in its epilogue.
-__device__ __forceinline__ int64_t interleaved_block(int64_t b, int kb, int ilv)
+// The row of a block is b / kb: a 64-bit division per thread would cost dozens of instructions, so the host passes the
+// multiplier and shift that make it one multiply (exact for b < 2^31: m = ceil(2^(31 + l) / kb), l = ceil(log2 kb)).
+struct zo_rowdiv { int32_t kb; uint32_t magic; int32_t shift; };
+static zo_rowdiv make_rowdiv(int kb)
+{
+    int l = 0;
+    while ((1u << l) < (unsigned)kb) ++l;
+    const int sh = 31 + l;
+    return zo_rowdiv{kb, (uint32_t)((((uint64_t)1 << sh) + (uint64_t)kb - 1) / (uint64_t)kb), sh};
+}
+__device__ __forceinline__ uint32_t zo_quot(uint32_t b, const zo_rowdiv& d)      // b / d.kb for b < 2^31
+{
+    return (uint32_t)(((uint64_t)b * d.magic) >> d.shift);
+}
+__device__ __forceinline__ int64_t interleaved_block(int64_t b, const zo_rowdiv& d, int ilv)
 {
     if (ilv == 0) return b;
-    const int64_t n = b / kb, kblk = b - n * kb;
-    int64_t row;
+    const uint32_t n = zo_quot((uint32_t)b, d);
+    const uint32_t kblk = (uint32_t)b - n * (uint32_t)d.kb;
+    uint32_t row;
     if (ilv == 3) {                                  // blocks 1 and 2 of every 128-row head trade places
-        const int64_t blk = (n >> 5) & 3;
+        const uint32_t blk = (n >> 5) & 3;
         row = (blk == 1) ? n + 32 : (blk == 2) ? n - 32 : n;
     } else {
         row = ((n >> 5) << 6) + (n & 31) + (ilv == 2 ? 32 : 0);
     }
-    return row * kb + kblk;
+    return (int64_t)row * d.kb + kblk;
 }
 
 template <typename TO, int GL, bool DEBUG>
@@ -357,7 +372,7 @@ __device__ __forceinline__ void fq_branch(const float v[8], int bits, TO* out, i
 template <typename TW, typename TO, int GL, bool DEBUG>
 __global__ __launch_bounds__(256) void zo_fq_weight_kernel(const TW* __restrict__ W, int64_t nblk, zo_stream s,
                                                            float eps, int bits, TO* __restrict__ out_p, TO* __restrict__ out_m,
-                                                           uint8_t* codes, float* step, int32_t* zp, int kb, int ilv)
+                                                           uint8_t* codes, float* step, int32_t* zp, zo_rowdiv kb, int ilv)
 {
     const int lane = threadIdx.x & 63;
     // one Philox block per thread; every lane of a wave takes part in the shuffles
@@ -468,12 +483,13 @@ template <typename TW, typename TO, int GL>
 static hipError_t launch_fq_weight_gl(const TW* W, int64_t nblk, zo_stream s, float eps, int bits, TO* op, TO* om,
                                       uint8_t* codes, float* step, int32_t* zp, hipStream_t st, int kb = 1, int ilv = 0)
 {
-    if ((nblk + 255) / 256 > 0x7FFFFFFF) return hipErrorInvalidValue;
+    if ((nblk + 255) / 256 > 0x7FFFFFFF || (ilv != 0 && nblk >= ((int64_t)1 << 31))) return hipErrorInvalidValue;
     const int grid = (int)((nblk + 255) / 256);
+    const zo_rowdiv rd = make_rowdiv(kb);
     if (codes || step || zp)
-        zo_fq_weight_kernel<TW, TO, GL, true><<<grid, 256, 0, st>>>(W, nblk, s, eps, bits, op, om, codes, step, zp, kb, ilv);
+        zo_fq_weight_kernel<TW, TO, GL, true><<<grid, 256, 0, st>>>(W, nblk, s, eps, bits, op, om, codes, step, zp, rd, ilv);
     else
-        zo_fq_weight_kernel<TW, TO, GL, false><<<grid, 256, 0, st>>>(W, nblk, s, eps, bits, op, om, nullptr, nullptr, nullptr, kb, ilv);
+        zo_fq_weight_kernel<TW, TO, GL, false><<<grid, 256, 0, st>>>(W, nblk, s, eps, bits, op, om, nullptr, nullptr, nullptr, rd, ilv);
     return hipGetLastError();
 }
 
@@ -566,7 +582,7 @@ __device__ __forceinline__ void fq_learned_branch(const float w[8], const float 
 }
 
 template <typename TO>
-__global__ __launch_bounds__(256) void zo_fq_weight_learned_kernel(const float* __restrict__ W, int64_t nblk, int k8, int gl, zo_stream s,
+__global__ __launch_bounds__(256) void zo_fq_weight_learned_kernel(const float* __restrict__ W, int64_t nblk, zo_rowdiv k8, zo_rowdiv gl, zo_stream s,
                                                                    float eps, int bits, zo_learned pp, zo_learned pm,
                                                                    TO* __restrict__ out_p, TO* __restrict__ out_m, uint8_t* codes, int ilv)
 {
@@ -580,8 +596,8 @@ __global__ __launch_bounds__(256) void zo_fq_weight_learned_kernel(const float* 
 #pragma unroll
         for (int i = 0; i < 8; ++i) z[i] = 0.0f;
     }
-    const int64_t g = b / gl;
-    const int kb = (int)(b % k8) * 8;
+    const int64_t g = zo_quot((uint32_t)b, gl);
+    const int kb = (int)((uint32_t)b - zo_quot((uint32_t)b, k8) * (uint32_t)k8.kb) * 8;
     fq_learned_branch<TO>(w, z, eps, pp, g, kb, bits, out_p, b, ob, codes);
     if (out_m) fq_learned_branch<TO>(w, z, -eps, pm, g, kb, bits, out_m, b, ob, nullptr);
 }
@@ -593,14 +609,14 @@ hipError_t zo_launch_fq_weight_learned(const float* W, int32_t N, int32_t K, int
     const int64_t nblk = (int64_t)N * K / 8;
     if (nblk == 0) return hipSuccess;
     if (group == 0) group = K;
-    if ((K & 7) || (group & 7) || K % group || bits < 1 || bits > 8 || (nblk + 255) / 256 > 0x7FFFFFFF) return hipErrorInvalidValue;
+    if ((K & 7) || (group & 7) || K % group || bits < 1 || bits > 8 || nblk >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
     const int grid = (int)((nblk + 255) / 256);
     const zo_stream s = make_stream(seed, tid);
     if (dtype == ZO_T_BF16)
-        zo_fq_weight_learned_kernel<zo_bf16><<<grid, 256, 0, st>>>(W, nblk, K / 8, group / 8, s, eps, bits, pp, pm, (zo_bf16*)out_plus,
+        zo_fq_weight_learned_kernel<zo_bf16><<<grid, 256, 0, st>>>(W, nblk, make_rowdiv(K / 8), make_rowdiv(group / 8), s, eps, bits, pp, pm, (zo_bf16*)out_plus,
                                                                    (zo_bf16*)out_minus, codes, ilv);
     else
-        zo_fq_weight_learned_kernel<float><<<grid, 256, 0, st>>>(W, nblk, K / 8, group / 8, s, eps, bits, pp, pm, (float*)out_plus,
+        zo_fq_weight_learned_kernel<float><<<grid, 256, 0, st>>>(W, nblk, make_rowdiv(K / 8), make_rowdiv(group / 8), s, eps, bits, pp, pm, (float*)out_plus,
                                                                  (float*)out_minus, codes, ilv);
     return hipGetLastError();
 }
@@ -735,14 +751,14 @@ __global__ __launch_bounds__(256) void zo_pack_int4_kernel(const float* __restri
 
 template <typename TO>
 __global__ __launch_bounds__(256) void zo_dequant_int4_kernel(const uint32_t* __restrict__ packed, const _Float16* __restrict__ step,
-                                                              const int16_t* __restrict__ zp, int64_t nblk, int gl,
-                                                              TO* __restrict__ out0, TO* __restrict__ out1, int kb, int ilv)
+                                                              const int16_t* __restrict__ zp, int64_t nblk, zo_rowdiv gl,
+                                                              TO* __restrict__ out0, TO* __restrict__ out1, zo_rowdiv kb, int ilv)
 {
     const int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (b >= nblk) return;
     const int64_t ob = interleaved_block(b, kb, ilv);
     const uint32_t word = packed[b];
-    const int64_t g = b / gl;
+    const int64_t g = zo_quot((uint32_t)b, gl);
     const float st = (float)step[g];
     const int z = zp[g];
     float o[8];
@@ -784,14 +800,14 @@ hipError_t zo_launch_dequant_int4(const void* packed, const void* step_f16, cons
 {
     const int64_t nblk = (int64_t)N * K / 8;
     if (nblk == 0) return hipSuccess;
-    if (!zo_int4_group_supported(K, group) || (nblk + 255) / 256 > 0x7FFFFFFF || (ilv != 0 && (N & (ilv == 3 ? 127 : 31)))) return hipErrorInvalidValue;
+    if (!zo_int4_group_supported(K, group) || nblk >= ((int64_t)1 << 31) || (ilv != 0 && (N & (ilv == 3 ? 127 : 31)))) return hipErrorInvalidValue;
     const int grid = (int)((nblk + 255) / 256);
     if (dtype == ZO_T_BF16)
-        zo_dequant_int4_kernel<zo_bf16><<<grid, 256, 0, st>>>((const uint32_t*)packed, (const _Float16*)step_f16, zp, nblk, group / 8,
-                                                              (zo_bf16*)out0, (zo_bf16*)out1, K / 8, ilv);
+        zo_dequant_int4_kernel<zo_bf16><<<grid, 256, 0, st>>>((const uint32_t*)packed, (const _Float16*)step_f16, zp, nblk, make_rowdiv(group / 8),
+                                                              (zo_bf16*)out0, (zo_bf16*)out1, make_rowdiv(K / 8), ilv);
     else
-        zo_dequant_int4_kernel<float><<<grid, 256, 0, st>>>((const uint32_t*)packed, (const _Float16*)step_f16, zp, nblk, group / 8,
-                                                            (float*)out0, (float*)out1, K / 8, ilv);
+        zo_dequant_int4_kernel<float><<<grid, 256, 0, st>>>((const uint32_t*)packed, (const _Float16*)step_f16, zp, nblk, make_rowdiv(group / 8),
+                                                            (float*)out0, (float*)out1, make_rowdiv(K / 8), ilv);
     return hipGetLastError();
 }
 
