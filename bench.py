@@ -61,9 +61,9 @@ PEAK_HBM_GBS = 8000.0
 # plain vector ALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions per second (the fp32 vector peak of
 # 157.3 TFLOP/s counts 2 flops per FMA and the packed two-per-lane forms, which this build does not use)
 PEAK_ALU_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
-# lane-instructions of the fused kernel's tile build per parameter, counted in its ISA (w4 g64 variant, two m-tiles: 579 for
+# lane-instructions of the fused kernel's tile build per parameter, counted in its ISA (w4 g64 variant, two m-tiles: 523 for
 # the perturbation stream + 16 for W +- eps u + 179 + 210 for the two branches + 8 matrix instructions, per 16 parameters)
-FUSED_LANEOPS_PER_PARAM = 992 / 16.0
+FUSED_LANEOPS_PER_PARAM = 936 / 16.0
 
 
 def gemm_flops_per_step(w):

@@ -105,6 +105,19 @@ ZO_DEV void zo_philox(const zo_stream& s, uint64_t blk, uint32_t out[4])
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
+// Correctly rounded square root for 2^-96 < x < 2^96 (S below lies in [1.5e-5, 23.6]): the hardware estimate, whose
+// error is below one ulp, moved to the neighbour that the exact residuals x - r * (r -+ ulp) ask for.  This is the
+// sequence the compiler emits for sqrtf, without its rescaling of tiny inputs and its special cases for 0 and infinity.
+ZO_DEV float zo_sqrt_in_range(float x)
+{
+    const float r = __builtin_amdgcn_sqrtf(x);
+    const float dn = __uint_as_float(__float_as_uint(r) - 1u), up = __uint_as_float(__float_as_uint(r) + 1u);
+    const float vd = __builtin_fmaf(-dn, r, x), vu = __builtin_fmaf(-up, r, x);
+    float s = vd <= 0.0f ? dn : r;
+    s = vu > 0.0f ? up : s;
+    return s;
+}
+
 // One 32-bit word -> (r cos t, r sin t): low half is the radius uniform, high half the angle.
 ZO_DEV void zo_word_to_normals(uint32_t w, float& z0, float& z1)
 {
@@ -127,7 +140,7 @@ ZO_DEV void zo_word_to_normals(uint32_t w, float& z0, float& z1)
     float E = (float)(e - 17);
     float ln_u1 = __builtin_fmaf(E, 0x1.62e430p-1f, lnm);
     float S = -2.0f * ln_u1;
-    float r = __builtin_sqrtf(S);                       // correctly rounded (compiler default)
+    float r = zo_sqrt_in_range(S);                      // correctly rounded
     // angle: quadrant from the top two bits, x in (-pi/4, pi/4) from the other fourteen
     uint32_t b = w >> 16;
     int32_t j = (int32_t)((b & 0x3FFFu) << 1) - 16383;
