@@ -120,8 +120,8 @@ def cpu_baseline(w):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama7b_w4a8_g64_8x1024", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--directions", type=int, default=1,
@@ -210,12 +210,16 @@ def main():
     ROOFLINE_CATEGORIES = ("gemm", "fused_linear", "fused_int4_linear")
     if not args.no_profile:
         ctx.zo_profile_begin_mask(ROOFLINE_CATEGORIES)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # one event per step boundary, same stream
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    marks[0].record()
     for i in range(args.steps):
         out = one_step(args.warmup + i)
+        marks[i + 1].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     prof = None if args.no_profile else ctx.zo_profile_end()
     losses = out.cpu().tolist()
     prof_all = None
@@ -229,6 +233,7 @@ def main():
     res = {
         "metric": "ZO steps/sec (2 quantized fwd + update)", "value": args.steps / elapsed, "unit": "steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "tokens_per_step": B * S, "trainable_params": n_params,
                    "w_bits": w["w_bits"], "w_group": w["w_group"], "a_bits": w["a_bits"], "eps": eps, "lr": lr,
