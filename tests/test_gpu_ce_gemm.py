@@ -81,4 +81,9 @@ def test_decoder_step_with_ce_in_the_gemm(arch):
     with pytest.raises(zo.ZoError) as e:
         ctx.zo_debug_buffer(1)
     assert e.value.status == 5
+    # a single forward (one branch per launch) takes the same route and gives the step's losses bit for bit (lr was 0)
+    for sign, want in ((1.0, out[0]), (-1.0, out[1])):
+        got = ctx.zo_forward_quant(to_dev(ids, torch), None, B, S, seed=21, eps_signed=sign * 1e-3).item()
+        assert ctx.zo_debug_routes() & zo.ROUTE_CE_IN_GEMM
+        assert np.float32(got) == np.float32(want), (got, want)
     ctx.close()
