@@ -70,8 +70,12 @@ typedef struct {
     int32_t no_fused;    /* 0 = the linears of a forward over at most 128 tokens (bf16 storage, groups of 8..128 -- 32..128
                             when packed tensors are attached --, no learned tensors) build their weight tiles inside
                             the GEMM kernel, from the masters or from the packed codes; large bf16 Llama-shaped forwards
-                            interleave the gate and up rows in the operand buffer and take silu(gate) * up in the GEMM epilogue;
-                            1 = always quantize once into the workspace and run the plain GEMM */
+                            without smoothing interleave the gate and up rows in the operand buffer and take silu(gate) * up
+                            in the GEMM epilogue, and (head dimension 128) permute the head blocks of q | k | v and apply
+                            the rotary embedding there (zo_debug_routes tells which routes a forward took);
+                            1 = always quantize once into the workspace and run the plain GEMM with the stand-alone kernels.
+                            Independent of this flag, a large bf16 forward forms its cross entropy in the lm_head GEMM's
+                            epilogue and stores no logits. */
     int32_t master_dtype;/* ZO_MASTER_*: storage type of every tensor of the parameter list.  ZO_MASTER_F16 = IEEE binary16,
                             the 2 bytes per parameter that the memory table of the efficiency section implies: a
                             forward reads the stored value (exactly widened to fp32) wherever it read the fp32 master;
