@@ -54,6 +54,47 @@ def test_gemm_full_shape_sampled_outputs(N, K):
     assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * np.sqrt(K))
 
 
+def test_gate_up_gemm_with_swiglu_full_shape_sampled_outputs():
+    """The 8192 x 22016 x 4096 gate | up GEMM of the benchmark with SwiGLU in its epilogue (rows interleaved in blocks of
+    32 channels): sampled (token, channel) outputs against the definition with the same rounding points."""
+    torch, zo = gpu()
+    X = orc.bf16_round(synth.activations((M, D), 87))
+    G = orc.bf16_round(synth.weights((F, D), 88, scale=0.3))
+    U = orc.bf16_round(synth.weights((F, D), 89, scale=0.3))
+    Wi = np.stack([G.reshape(F // 32, 32, D), U.reshape(F // 32, 32, D)], axis=1).reshape(2 * F, D)
+    Y = zo.zo_gemm_nt_swiglu(to_dev(X, torch, torch.bfloat16), to_dev(Wi, torch, torch.bfloat16))
+    rng = synth.rng(90)
+    ms = np.concatenate([[0, 255, 256, M - 1], rng.integers(0, M, 60)])
+    cs = np.concatenate([[0, 31, 32, 127, 128, F - 1], rng.integers(0, F, 58)])
+    got = Y[torch.from_numpy(ms).cuda()][:, torch.from_numpy(cs).cuda()].float().cpu().numpy()
+    g = orc.bf16_round((X[ms].astype(np.float64) @ G[cs].astype(np.float64).T).astype(np.float32)).astype(np.float64)
+    u = orc.bf16_round((X[ms].astype(np.float64) @ U[cs].astype(np.float64).T).astype(np.float32)).astype(np.float64)
+    ref = g / (1.0 + np.exp(-g)) * u
+    # one bf16 rounding of the product; gate / up may round to the neighbouring bf16 value (fp32 against fp64 sums)
+    assert np.mean(np.abs(got - ref) > 2.0 ** -8 * np.abs(ref) + 1e-6) < 3e-2
+    assert np.all(np.abs(got - ref) <= 2.0 ** -6 * np.abs(ref) + 2e-2)
+
+
+def test_lm_head_loss_full_shape_sampled_rows():
+    """The 8192 x 32000 x 4096 lm_head GEMM of the benchmark with the cross entropy in its epilogue: sampled row losses
+    against the definition in fp64 (logits of a row: 32000 dot products the host computes one row at a time)."""
+    torch, zo = gpu()
+    V, S = 32000, 1024
+    X = orc.bf16_round(synth.activations((M, D), 91) * 0.5)
+    W = orc.bf16_round(synth.weights((V, D), 92, scale=0.05))
+    ids = synth.token_ids(M // S, S, V, 93).reshape(-1).astype(np.int32)
+    got = zo.zo_gemm_nt_ce(to_dev(X, torch, torch.bfloat16), to_dev(W, torch, torch.bfloat16), to_dev(ids, torch), S).cpu().numpy()
+    assert np.array_equal(got[S - 1::S], np.zeros(M // S, np.float32))
+    rng = synth.rng(94)
+    W64 = W.astype(np.float64)
+    for m in np.concatenate([[0, 255, 256, M - 2], rng.integers(0, M, 12)]):
+        if m % S == S - 1:
+            continue
+        lg = W64 @ X[m].astype(np.float64)
+        ref = np.log(np.exp(lg - lg.max()).sum()) + lg.max() - lg[ids[m + 1]]
+        assert abs(got[m] - ref) <= 2e-5 * (np.abs(lg).max() + np.log(V)) + 1e-5, (m, got[m], ref)
+
+
 def test_attention_full_shape_sampled_heads():
     torch, zo = gpu()
     B, S, H, dh = 8, 1024, 32, 128
