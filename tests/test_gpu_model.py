@@ -255,3 +255,22 @@ def test_matrix_core_attention_path(heads, S):
     assert rel_l2(x, trace["l0.out"]) < 1e-2
     assert _row_rel(x, trace["l0.out"]).max() < 2e-2
     ctx.close()
+
+
+def test_profile_mask_brackets_only_the_selected_categories():
+    """Per-launch timing restricted to one category: the others report no bracketed group, the selected one the same
+    launch count as the unrestricted session."""
+    torch, zo = gpu()
+    B, S = 2, 80                                               # 160 tokens: the quantize-once route, batched GEMMs
+    ocfg, params, ids, gp, ctx = _setup(zo, torch, "llama", 1, B, S)
+    idd = to_dev(ids, torch)
+    ctx.zo_profile_begin()
+    ctx.zo_step(idd, None, B, S, seed=3, eps=1e-3, lr=0.0)
+    full = ctx.zo_profile_end()
+    ctx.zo_profile_begin_mask(("gemm",))
+    ctx.zo_step(idd, None, B, S, seed=3, eps=1e-3, lr=0.0)
+    only = ctx.zo_profile_end()
+    assert only["gemm"][1] == full["gemm"][1] > 0 and only["gemm"][0] > 0.0
+    assert all(only[k][1] == 0 for k in only if k != "gemm")
+    assert full["weight_quant"][1] > 0 and full["update"][1] > 0
+    ctx.close()
