@@ -42,6 +42,11 @@ WORKLOADS = {
                                    w_bits=4, w_group=64, a_bits=8, B=1, S=128),
     "llama7b_w4a8_g64_1x32": dict(arch="llama", n_layers=32, d_model=4096, n_heads=32, d_ffn=11008, vocab=32000,
                                   w_bits=4, w_group=64, a_bits=8, B=1, S=32),
+    # between the two regimes (the fine-tuning table's 384-token sequences, batch 1 and 16): quantize once, then GEMMs
+    "llama7b_w4a8_g64_1x384": dict(arch="llama", n_layers=32, d_model=4096, n_heads=32, d_ffn=11008, vocab=32000,
+                                   w_bits=4, w_group=64, a_bits=8, B=1, S=384),
+    "llama7b_w4a8_g64_16x384": dict(arch="llama", n_layers=32, d_model=4096, n_heads=32, d_ffn=11008, vocab=32000,
+                                    w_bits=4, w_group=64, a_bits=8, B=16, S=384),
     # the lightweight variant in the same regime: frozen linears expanded from their packed codes inside the kernel
     "llama13b_lightweight_w4a4_g128_1x128": dict(arch="llama", n_layers=40, d_model=5120, n_heads=40, d_ffn=13824,
                                                  vocab=32000, w_bits=4, w_group=128, a_bits=4, B=1, S=128, lightweight=1),

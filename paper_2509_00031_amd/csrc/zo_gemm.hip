@@ -272,17 +272,20 @@ __device__ __forceinline__ void store_tile(const f32x16& acc, const zo_gemm_args
 // 256-column tile the maximum and the sum of exp(logit - maximum) are formed (lane, its partner half, then the four
 // waves along n through LDS) and written to ce_part, and the lane that holds the token's target column writes that
 // logit to ce_tgt.  The cross entropy of a row is then a 2 * tiles_n-float reduction instead of a pass over V logits.
-template <typename TY, int NW, int BK, int ST, int EPI = 0>
+// BT = 128 (4 waves, 64 x 64 per wave, two workgroups per CU) is the form for shapes with too few 256 x 256 tiles to
+// fill the chip; it has the plain epilogue only.
+template <typename TY, int NW, int BK, int ST, int EPI = 0, int BT = 256>
 __global__ __launch_bounds__(NW * 64) void zo_gemm_bf16_dma_kernel(zo_gemm_args a)
 {
-    constexpr int BM = 256, BN = 256;
+    constexpr int BM = BT, BN = BT;
+    static_assert(BT == 256 || (BT == 128 && NW == 4 && EPI == 0), "tile forms");
     constexpr int RB = BK * 2;                       // bytes per tile row
     constexpr int CPR = RB / 16;                     // 16-byte chunks per row
     constexpr int STAGE = (BM + BN) * RB;            // bytes per LDS stage
     constexpr int RPD = 1024 / RB;                   // tile rows per wave-level copy
     constexpr int DPW = (BM + BN) / RPD / NW;        // copies per wave per stage
     constexpr int WN_WAVES = NW / 2;                 // waves along n (2 along m)
-    constexpr int WM = 128, WN = BN / WN_WAVES;
+    constexpr int WM = BM / 2, WN = BN / WN_WAVES;
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int KS = BK / 16;                      // MFMA K steps per stage
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -352,16 +355,18 @@ __global__ __launch_bounds__(NW * 64) void zo_gemm_bf16_dma_kernel(zo_gemm_args 
     // With two stages all copies of a tile are issued in that last K step (they are needed one tile
     // later); with more stages they are spread over the KS steps that follow the barrier.
     constexpr int SPAN = ST == 2 ? 1 : KS;            // K steps over which one tile's copies are issued
-    constexpr int Q = DPW / SPAN;                     // copies per K step
-    constexpr int MPQ = TN * TM / Q;                  // MFMAs between two copies
-    static_assert(DPW % SPAN == 0 && (TN * TM) % Q == 0 && KS % 2 == 0, "copy / MFMA interleave");
+    constexpr int CPS = DPW / SPAN;                   // copies per K step
+    constexpr int Q = CPS < TN * TM ? CPS : TN * TM;  // groups per K step: MPQ MFMAs, then CPQ copies
+    constexpr int MPQ = TN * TM / Q;                  // MFMAs between two groups of copies
+    constexpr int CPQ = CPS / Q;                      // copies per group
+    static_assert(DPW % SPAN == 0 && (TN * TM) % Q == 0 && CPS % Q == 0 && KS % 2 == 0, "copy / MFMA interleave");
     const int nk = K / BK;
     auto tile_clamped = [&](int t) { return t < nk ? t : nk - 1; };   // past the end: refetch the last tile
 #pragma unroll
     for (int s0 = 0; s0 < ST - 1; ++s0) issue(s0, tile_clamped(s0));
 #pragma unroll
-    for (int i = 0; i < Q; ++i) issue_one(ST - 1, tile_clamped(ST - 1), i);
-    wait_vmcnt<(ST - 2) * DPW + Q>();                 // tile 0 has landed (copies complete in order)
+    for (int i = 0; i < CPS; ++i) issue_one(ST - 1, tile_clamped(ST - 1), i);
+    wait_vmcnt<(ST - 2) * DPW + CPS>();               // tile 0 has landed (copies complete in order)
     __syncthreads();
     bf16x8 xf[2][TM], wf[2][TN];
     auto load_frags = [&](int stage, int ks, int sel) {
@@ -406,8 +411,11 @@ __global__ __launch_bounds__(NW * 64) void zo_gemm_bf16_dma_kernel(zo_gemm_args 
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[sel][i], xf[sel][j], acc[i][j], 0, 0, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                if (last) issue_one(cur, t_cur, qq);                          // stage freed just above
-                else if (SPAN > 1) issue_one(prev, t_prev, Q * (1 + ks) + qq);   // rest of the previous refill
+#pragma unroll
+                for (int cc = 0; cc < CPQ; ++cc) {
+                    if (last) issue_one(cur, t_cur, qq * CPQ + cc);           // stage freed just above
+                    else if (SPAN > 1) issue_one(prev, t_prev, CPS * (1 + ks) + qq * CPQ + cc);   // rest of the previous refill
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -831,7 +839,10 @@ hipError_t zo_launch_gemm(const zo_gemm_args& a, hipStream_t st)
             zo_gemm_bf16_dma_kernel<zo_bf16, 8, 64, 2, 1><<<dim3(tiles, 1, a.batch), 8 * 64, lds_bytes, st>>>(a);
             return hipGetLastError();
         }
-        if (large && (a.K & 63) == 0 && off32) {
+        // plain epilogue: 256 x 256 tiles once they give five eighths of the CUs a workgroup (both branches of a batched
+        // launch count; measured crossover); below that the 128 x 128 form further down fills the chip better
+        const bool fill256 = (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256) * a.batch >= 160;
+        if (fill256 && (a.K & 63) == 0 && off32) {
             const int tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
             const dim3 grid(tiles, 1, a.batch);
             constexpr int lds_bytes = 2 * 512 * 64 * 2;
@@ -848,7 +859,24 @@ hipError_t zo_launch_gemm(const zo_gemm_args& a, hipStream_t st)
             }
             return hipGetLastError();
         }
-        if (large) return launch_bf16<256, 256>(a, st);
+        if ((a.K & 63) == 0 && off32 && a.K >= 128) {    // too few 256 x 256 tiles to fill the chip: 128 x 128 tiles, same pipeline
+            const int tiles = ((a.M + 127) / 128) * ((a.N + 127) / 128);
+            const dim3 grid(tiles, 1, a.batch);
+            constexpr int lds_bytes = 2 * 256 * 64 * 2;
+            if (a.out_f32) {
+                hipError_t e_ = hipFuncSetAttribute((const void*)zo_gemm_bf16_dma_kernel<float, 4, 64, 2, 0, 128>,
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+                if (e_ != hipSuccess) return e_;
+                zo_gemm_bf16_dma_kernel<float, 4, 64, 2, 0, 128><<<grid, 4 * 64, lds_bytes, st>>>(a);
+            } else {
+                hipError_t e_ = hipFuncSetAttribute((const void*)zo_gemm_bf16_dma_kernel<zo_bf16, 4, 64, 2, 0, 128>,
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+                if (e_ != hipSuccess) return e_;
+                zo_gemm_bf16_dma_kernel<zo_bf16, 4, 64, 2, 0, 128><<<grid, 4 * 64, lds_bytes, st>>>(a);
+            }
+            return hipGetLastError();
+        }
+        if (large) return launch_bf16<256, 256>(a, st);     // K not a multiple of 64: the register-staged kernel
         return launch_bf16<128, 128>(a, st);
     }
     const int tiles = ((a.M + 63) / 64) * ((a.N + 63) / 64);
