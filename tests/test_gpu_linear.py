@@ -39,12 +39,14 @@ def test_gemm_large_tile_path():
     assert np.all(np.abs(Y - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-4)
 
 
-@pytest.mark.parametrize("M,N,K", [(3000, 2904, 256), (2051, 4096, 512), (200, 136, 64), (4096, 2048, 128)])
+@pytest.mark.parametrize("M,N,K", [(3000, 2904, 256), (2051, 4096, 512), (200, 136, 64), (4096, 2048, 128), (3300, 3304, 256),
+                                   (3201, 3500, 192)])
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
 @pytest.mark.parametrize("bias,relu,residual", [(True, False, False), (False, False, True), (True, True, True)])
 def test_gemm_fused_epilogue(M, N, K, dtype, bias, relu, residual):
-    """Bias / ReLU / in-place residual epilogue, on shapes that take the small-tile, the 256 x 256
-    and (bf16, N a multiple of 8) the row-coalesced store paths, ragged in M and N."""
+    """Bias / ReLU / in-place residual epilogue, on shapes that take the register-staged kernel (K = 64), the 128 x 128
+    and the 256 x 256 tiles of the load-unit pipeline (13 x 13 and more tiles of 256), with (bf16, N a multiple of 8) and
+    without (N = 3500) the row-coalesced store path, ragged in M and N."""
     torch, zo = gpu()
     bf = dtype == "bf16"
     td = torch.bfloat16 if bf else torch.float32
