@@ -56,10 +56,10 @@ WORKLOADS = {
                                  w_bits=4, w_group=64, a_bits=16, B=8, S=128),
 }
 # HBM-side bytes per launch of the GEMM kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes over this same
-# command (scaled by a plain copy of known size; profiles/zo_step_llama7b_w4a8_hbm_traffic.txt): 2.000 x 1376.5 MB
-# read + 1.000 x 256.7 MB written, averaged over the GEMM launches of a step (all epilogue forms).  Counters cannot be
+# command (scaled by a plain copy of known size; profiles/zo_step_llama7b_w4a8_hbm_traffic.txt): 2.000 x 1380.6 MB
+# read + 1.000 x 256.9 MB written, averaged over the GEMM launches of a step (all epilogue forms).  Counters cannot be
 # read from inside the run, so other workloads report null.
-MEASURED_GEMM_TRAFFIC = {"llama7b_w4a8_g64_8x1024": 2.0 * 1376.5e6 + 256.7e6}
+MEASURED_GEMM_TRAFFIC = {"llama7b_w4a8_g64_8x1024": 2.0 * 1380.6e6 + 256.9e6}
 BREAKDOWN_STEPS = 2
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
