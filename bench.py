@@ -43,6 +43,8 @@ WORKLOADS = {
     "llama7b_w4a8_g64_1x32": dict(arch="llama", n_layers=32, d_model=4096, n_heads=32, d_ffn=11008, vocab=32000,
                                   w_bits=4, w_group=64, a_bits=8, B=1, S=32),
     # between the two regimes (the fine-tuning table's 384-token sequences, batch 1 and 16): quantize once, then GEMMs
+    "llama7b_w4a8_g64_1x256": dict(arch="llama", n_layers=32, d_model=4096, n_heads=32, d_ffn=11008, vocab=32000,
+                                   w_bits=4, w_group=64, a_bits=8, B=1, S=256),
     "llama7b_w4a8_g64_1x384": dict(arch="llama", n_layers=32, d_model=4096, n_heads=32, d_ffn=11008, vocab=32000,
                                    w_bits=4, w_group=64, a_bits=8, B=1, S=384),
     "llama7b_w4a8_g64_16x384": dict(arch="llama", n_layers=32, d_model=4096, n_heads=32, d_ffn=11008, vocab=32000,

@@ -342,6 +342,20 @@ zo_status zo_gemm_nt(const void* X_dev, const void* W_dev, void* Y_dev, int32_t 
 zo_status zo_gemm_nt_fused(const void* X_dev, const void* W_dev, const float* bias_dev, const void* residual_dev, int32_t relu,
                            void* Y_dev, int32_t M, int32_t N, int32_t K, int32_t dtype, void* hip_stream);
 
+/* The same fused GEMM with scratch memory that lets the library split K (the GEMM of the quantized linear layers at the
+ * token counts of the paper's fine-tuning runs: a few hundred tokens and the narrow outputs of the attention-output
+ * and down projections give too few tiles to occupy the chip).  zo_gemm_nt_splitk_ranges tells how many K ranges the shape
+ * gets (1: computed exactly as zo_gemm_nt_fused does, scratch unused), zo_gemm_nt_splitk_scratch_bytes how much scratch
+ * they need (0 for one range).  Every range's partial sums are kept in fp32 in the scratch and added in range order by a
+ * second kernel, which applies the epilogue: the result does not depend on scheduling; it differs from the unsplit
+ * kernel's only by the order of the fp32 additions.  scratch dev, 16-byte aligned, or NULL (no split); a scratch smaller
+ * than asked for also means no split.  Errors as zo_gemm_nt_fused. */
+int32_t zo_gemm_nt_splitk_ranges(int32_t M, int32_t N, int32_t K, int32_t dtype);
+size_t zo_gemm_nt_splitk_scratch_bytes(int32_t M, int32_t N, int32_t K, int32_t dtype);
+zo_status zo_gemm_nt_fused_splitk(const void* X_dev, const void* W_dev, const float* bias_dev, const void* residual_dev, int32_t relu,
+                                  void* Y_dev, int32_t M, int32_t N, int32_t K, int32_t dtype, void* scratch_dev, size_t scratch_bytes,
+                                  void* hip_stream);
+
 /* The gate / up GEMM of a SwiGLU block with the activation in its epilogue (what large bf16 Llama-shaped forwards run):
  *   W dev bf16 [N2][K]: rows of the gate and the up projection interleaved in blocks of 32 channels -- rows 64 i .. 64 i + 31
  *   = gate channels 32 i .., rows 64 i + 32 .. 64 i + 63 = up channels 32 i ..;  X dev bf16 [M][K];
@@ -375,7 +389,8 @@ enum { ZO_ROUTE_FUSED_SMALL_M = 1,    /* linears built from the masters inside t
        ZO_ROUTE_FUSED_INT4 = 2,       /* frozen linears expanded from their packed codes inside the small-M kernel */
        ZO_ROUTE_SWIGLU_IN_GEMM = 4,   /* SwiGLU applied by the epilogue of the gate / up GEMM */
        ZO_ROUTE_ROPE_IN_GEMM = 8,     /* rotary embedding applied by the epilogue of the q | k | v GEMM */
-       ZO_ROUTE_CE_IN_GEMM = 16 };    /* cross entropy formed by the epilogue of the lm_head GEMM, no logits stored */
+       ZO_ROUTE_CE_IN_GEMM = 16,      /* cross entropy formed by the epilogue of the lm_head GEMM, no logits stored */
+       ZO_ROUTE_GEMM_SPLIT_K = 32 };  /* some linear's GEMM ran with K split into ranges (see zo_gemm_nt_fused_splitk) */
 uint32_t zo_debug_routes(const zo_ctx* ctx);
 
 /* Device buffers of the context's last forward, for layer-level parity tests.

@@ -19,7 +19,7 @@ STATUS = {0: "ZO_OK", 1: "ZO_EINVAL", 2: "ZO_ESHAPE", 3: "ZO_EALIGN", 4: "ZO_EHI
 ARCH_LINEAR, ARCH_LLAMA, ARCH_OPT = 0, 1, 2
 ACT_FP32, ACT_BF16 = 0, 1
 MASTER_F32, MASTER_F16 = 0, 1
-ROUTE_FUSED_SMALL_M, ROUTE_FUSED_INT4, ROUTE_SWIGLU_IN_GEMM, ROUTE_ROPE_IN_GEMM, ROUTE_CE_IN_GEMM = 1, 2, 4, 8, 16
+ROUTE_FUSED_SMALL_M, ROUTE_FUSED_INT4, ROUTE_SWIGLU_IN_GEMM, ROUTE_ROPE_IN_GEMM, ROUTE_CE_IN_GEMM, ROUTE_GEMM_SPLIT_K = 1, 2, 4, 8, 16, 32
 
 EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "zo_destroy", "zo_last_error",
            "zo_forward_quant", "zo_step", "zo_update", "zo_debug_philox_u32", "zo_debug_normal", "zo_update_tensor",
@@ -27,7 +27,8 @@ EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "
            "zo_gemm_nt", "zo_debug_buffer", "zo_profile_begin", "zo_profile_end", "zo_attention_causal",
            "zo_attention_scratch_bytes", "zo_pack_weight_int4", "zo_attach_frozen_int4", "zo_linear_frozen_int4", "zo_gemm_nt_fused", "zo_init_learned_params", "zo_step_groups", "zo_update_groups",
            "zo_debug_quant_weight_learned", "zo_debug_smooth_bias", "zo_linear_fakequant_fused", "zo_linear_fused_scratch_bytes",
-           "zo_step_multi", "zo_update_multi", "zo_lr_linear_decay", "zo_update_tensor_f16", "zo_master_bytes", "zo_linear_frozen_int4_fused", "zo_linear_frozen_fused_scratch_bytes", "zo_gemm_nt_swiglu", "zo_debug_routes", "zo_gemm_nt_ce", "zo_gemm_nt_ce_scratch_bytes", "zo_profile_begin_mask"]
+           "zo_step_multi", "zo_update_multi", "zo_lr_linear_decay", "zo_update_tensor_f16", "zo_master_bytes", "zo_linear_frozen_int4_fused", "zo_linear_frozen_fused_scratch_bytes", "zo_gemm_nt_swiglu", "zo_debug_routes", "zo_gemm_nt_ce", "zo_gemm_nt_ce_scratch_bytes", "zo_profile_begin_mask",
+           "zo_gemm_nt_splitk_ranges", "zo_gemm_nt_splitk_scratch_bytes", "zo_gemm_nt_fused_splitk"]
 PROF_NAMES = ["gemm", "weight_quant", "act_quant", "attention", "update", "other", "fused_linear", "fused_int4_linear"]
 
 
@@ -89,6 +90,11 @@ _lib.zo_pack_weight_int4.argtypes = [_vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp]
 _lib.zo_attach_frozen_int4.argtypes = [_vp, _i32, _vp, _vp, _vp, _i32]
 _lib.zo_linear_frozen_int4.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp]
 _lib.zo_gemm_nt_fused.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _i32, _i32, _i32, _i32, _vp]
+_lib.zo_gemm_nt_fused_splitk.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _i32, _i32, _i32, _i32, _vp, _sz, _vp]
+_lib.zo_gemm_nt_splitk_ranges.argtypes = [_i32, _i32, _i32, _i32]
+_lib.zo_gemm_nt_splitk_ranges.restype = _i32
+_lib.zo_gemm_nt_splitk_scratch_bytes.argtypes = [_i32, _i32, _i32, _i32]
+_lib.zo_gemm_nt_splitk_scratch_bytes.restype = _sz
 _lib.zo_init_learned_params.argtypes = [_vp]
 _lib.zo_step_groups.argtypes = [_vp, _vp, _vp, _i32, _i32, _u64, _f32, _f32, _f32, _f32, _vp]
 _lib.zo_update_groups.argtypes = [_vp, _u64, _vp, C.POINTER(C.c_float)]
@@ -454,6 +460,23 @@ def zo_gemm_nt_fused(X, W, bias=None, residual=None, relu=False, Y=None):
         Y = torch.empty((M, N), dtype=X.dtype, device=X.device)
     _check(_lib.zo_gemm_nt_fused(X.data_ptr(), W.data_ptr(), _ptr(bias), _ptr(residual), int(relu), Y.data_ptr(), M, N, K, dtype,
                                  _stream()), "zo_gemm_nt_fused")
+    return Y
+
+
+def zo_gemm_nt_splitk_ranges(M, N, K, dtype=ACT_BF16):
+    return int(_lib.zo_gemm_nt_splitk_ranges(M, N, K, dtype))
+
+
+def zo_gemm_nt_fused_splitk(X, W, bias=None, residual=None, relu=False, Y=None):
+    M, K = X.shape
+    N = W.shape[0]
+    dtype = ACT_BF16 if X.dtype == torch.bfloat16 else ACT_FP32
+    if Y is None:
+        Y = torch.empty((M, N), dtype=X.dtype, device=X.device)
+    nbytes = int(_lib.zo_gemm_nt_splitk_scratch_bytes(M, N, K, dtype))
+    scratch = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=X.device)
+    _check(_lib.zo_gemm_nt_fused_splitk(X.data_ptr(), W.data_ptr(), _ptr(bias), _ptr(residual), int(relu), Y.data_ptr(), M, N, K, dtype,
+                                        scratch.data_ptr(), nbytes, _stream()), "zo_gemm_nt_fused_splitk")
     return Y
 
 

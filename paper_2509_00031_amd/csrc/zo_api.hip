@@ -145,6 +145,7 @@ struct layout {
     struct per_branch {
         size_t x, h, hq, qkv, att, gu, act, logits, rowloss;
     } br[2];
+    size_t kpart, kpart_bytes; // fp32 partial sums of GEMMs whose K is split (a few hundred tokens, narrow N); 0 bytes: none
     size_t total;
 };
 
@@ -217,6 +218,10 @@ layout make_layout(const zo_config& c, int B, int S)
         r.logits = take(lg);
         r.rowloss = take(M * sizeof(float));
     }
+    // K-split scratch: calls with fewer tokens than (B, S) may split where the full shape does not, so room for the most any
+    // shape can ask for (at most 1024 workgroups, each a 128 x 128 fp32 tile)
+    L.kpart_bytes = c.act_dtype == ZO_ACT_BF16 ? (size_t)1024 * 128 * 128 * sizeof(float) : 0;
+    L.kpart = take(L.kpart_bytes);
     L.total = off;
     return L;
 }
@@ -568,6 +573,12 @@ struct fwd {
             a.ce_ids = ce_ids;
             a.ce_S = S;
             a.stridePart = a.strideTgt = nb == 2 ? (int64_t)(c->L.br[1].*out - c->L.br[0].*out) / 4 : 0;
+        }
+        if (c->L.kpart_bytes && !swiglu && !rope && !ce_ids) {
+            a.ks_part = at<float>(c->L.kpart);
+            a.ks_part_bytes = c->L.kpart_bytes;
+            const size_t need = zo_gemm_splitk_bytes(M, N, K, nb, dt());
+            if (need && need <= a.ks_part_bytes) c->routes |= ZO_ROUTE_GEMM_SPLIT_K;
         }
         prof_scope ps(c, ZO_PROF_GEMM);
         ZO_HIP(c, zo_launch_gemm(a, c->st));
@@ -1430,6 +1441,35 @@ zo_status zo_gemm_nt_fused(const void* X_dev, const void* W_dev, const float* bi
     zo_gemm_args a{};
     a.X = X_dev; a.W = W_dev; a.Y = Y_dev; a.bias = bias_dev; a.residual = residual_dev; a.relu = relu ? 1 : 0;
     a.M = M; a.N = N; a.K = K; a.batch = 1; a.dtype = dtype;
+    return zo_launch_gemm(a, (hipStream_t)hip_stream) == hipSuccess ? ZO_OK : ZO_EHIP;
+}
+
+size_t zo_gemm_nt_splitk_scratch_bytes(int32_t M, int32_t N, int32_t K, int32_t dtype)
+{
+    return zo_gemm_splitk_bytes(M, N, K, 1, dtype == ZO_ACT_BF16 ? ZO_T_BF16 : ZO_T_F32);
+}
+
+int32_t zo_gemm_nt_splitk_ranges(int32_t M, int32_t N, int32_t K, int32_t dtype)
+{
+    if (zo_gemm_splitk_bytes(M, N, K, 1, dtype == ZO_ACT_BF16 ? ZO_T_BF16 : ZO_T_F32) == 0) return 1;
+    return zo_gemm_splitk(M, N, K, 1, ZO_T_BF16);
+}
+
+zo_status zo_gemm_nt_fused_splitk(const void* X_dev, const void* W_dev, const float* bias_dev, const void* residual_dev, int32_t relu,
+                                  void* Y_dev, int32_t M, int32_t N, int32_t K, int32_t dtype, void* scratch_dev, size_t scratch_bytes,
+                                  void* hip_stream)
+{
+    if (!X_dev || !W_dev || !Y_dev || M < 0 || N < 0 || K <= 0) return ZO_EINVAL;
+    if (dtype != ZO_ACT_FP32 && dtype != ZO_ACT_BF16) return ZO_EINVAL;
+    if (K & 7) return ZO_ESHAPE;
+    if (!aligned16(X_dev) || !aligned16(W_dev) || !aligned16(Y_dev) || !aligned16(bias_dev) || !aligned16(residual_dev) ||
+        !aligned16(scratch_dev))
+        return ZO_EALIGN;
+    zo_gemm_args a{};
+    a.X = X_dev; a.W = W_dev; a.Y = Y_dev; a.bias = bias_dev; a.residual = residual_dev; a.relu = relu ? 1 : 0;
+    a.M = M; a.N = N; a.K = K; a.batch = 1; a.dtype = dtype;
+    a.ks_part = (float*)scratch_dev;
+    a.ks_part_bytes = scratch_dev ? scratch_bytes : 0;
     return zo_launch_gemm(a, (hipStream_t)hip_stream) == hipSuccess ? ZO_OK : ZO_EHIP;
 }
 

@@ -9,6 +9,7 @@
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // ---------------------------------------------------------------------------------------------
 // bf16 MFMA kernel.
@@ -291,7 +292,15 @@ __global__ __launch_bounds__(NW * 64) void zo_gemm_bf16_dma_kernel(zo_gemm_args 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN_WAVES, wn = wave % WN_WAVES;
-    const int M = a.M, N = a.N, K = a.K;
+    const int M = a.M, N = a.N, LDK = a.K;            // LDK: row pitch of both operands
+    int K = a.K, bz = blockIdx.z, krange = 0;         // K: length of this workgroup's K range
+    if constexpr (BT == 128 && sizeof(TY) == 4) {
+        if (a.kspl > 1) {                             // blockIdx.z = batch entry * kspl + range
+            krange = __builtin_amdgcn_readfirstlane(bz % a.kspl);   // (divisions run in the vector unit)
+            bz = __builtin_amdgcn_readfirstlane(bz / a.kspl);
+            K = __builtin_amdgcn_readfirstlane(a.K / a.kspl);
+        }
+    }
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     // XCD-aware renumbering, then grouped (8 m-tiles) ordering
     int vid = blockIdx.x;
@@ -304,9 +313,8 @@ __global__ __launch_bounds__(NW * 64) void zo_gemm_bf16_dma_kernel(zo_gemm_args 
     const int tile_m = first_m + (vid % group_sz) % gm;
     const int tile_n = (vid % group_sz) / gm;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
-    const int bz = blockIdx.z;
-    const zo_bf16* X = (const zo_bf16*)a.X + bz * a.strideX;
-    const zo_bf16* W = (const zo_bf16*)a.W + bz * a.strideW;
+    const zo_bf16* X = (const zo_bf16*)a.X + bz * a.strideX + krange * K;
+    const zo_bf16* W = (const zo_bf16*)a.W + bz * a.strideW + krange * K;
 
     // copy plan: (BM + BN) / RPD row-blocks per stage (X rows first, then W rows)
     const int lrow = lane / CPR, slot = lane % CPR;
@@ -320,7 +328,7 @@ __global__ __launch_bounds__(NW * 64) void zo_gemm_bf16_dma_kernel(zo_gemm_args 
         const int lim = isw ? N : M;
         grow = grow < lim ? grow : lim - 1;
         const int c = slot ^ swz_bk<BK>(trow);
-        voff[i] = (uint32_t)(((int64_t)grow * K + c * 8) * 2);
+        voff[i] = (uint32_t)(((int64_t)grow * LDK + c * 8) * 2);
     }
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_offset(lds));
     auto issue = [&](int stage, int kt) {
@@ -424,7 +432,8 @@ __global__ __launch_bounds__(NW * 64) void zo_gemm_bf16_dma_kernel(zo_gemm_args 
     }
     wait_vmcnt<0>();
 
-    TY* Y = (TY*)a.Y + bz * a.strideY;
+    // a K range writes its partial sums to plane [range][batch entry] of the scratch (the launcher has pointed Y there)
+    TY* Y = (TY*)a.Y + (bz + krange * (int)(gridDim.z / (a.kspl > 1 ? a.kspl : 1))) * a.strideY;
     const float* bias = a.bias ? a.bias + bz * a.strideBias : nullptr;
     const zo_bf16* res = a.residual ? (const zo_bf16*)a.residual + bz * a.strideRes : nullptr;
     if constexpr (EPI == 3) {
@@ -799,6 +808,79 @@ bool zo_gemm_rope_supported(int32_t M, int32_t N, int32_t K, int dtype)
     return (int64_t)M * K * 2 < ((int64_t)1 << 32) && (int64_t)N * K * 2 < ((int64_t)1 << 32);
 }
 
+// ---------------------------------------------------------------------------------------------
+// K split of the 128 x 128-tile form.  A few hundred tokens times a narrow N (the attention output and down projections)
+// give fewer workgroups than the chip has slots (two per CU), and each of them walks a long K with one tile in flight:
+// the launch is bound by the latency of a tile's copies.  The launcher then cuts K into 2 / 4 / 8 ranges, every
+// (tile, range) is a workgroup that writes fp32 partial sums P[range][batch entry][M][N], and the kernel below adds the
+// ranges in order (no atomics: the result does not depend on scheduling) and applies bias / ReLU / residual / rounding.
+// ---------------------------------------------------------------------------------------------
+int zo_gemm_splitk(int32_t M, int32_t N, int32_t K, int32_t batch, int dtype)
+{
+    if (dtype != ZO_T_BF16 || M <= 0 || N <= 0 || (K & 63) || (N & 3)) return 1;
+    if ((int64_t)((M + 255) / 256) * ((N + 255) / 256) * batch >= 160) return 1;      // the 256 x 256-tile form runs
+    const int64_t wgs = (int64_t)((M + 127) / 128) * ((N + 127) / 128) * batch;
+    const int64_t nk = K / 64;
+    // Measured (128 x 128 tiles): an unsplit launch with no more workgroups than CUs takes about 0.62 us per K tile whatever
+    // their number; split into ranges that together give every CU a workgroup it takes about 14 us (second kernel, shorter
+    // pipelines) + 0.6 us x K tiles x workgroups / 256.  Split where that is the smaller figure ...
+    if (wgs >= 256 || nk * (256 - wgs) <= 23 * 256) return 1;
+    // ... into the fewest ranges that reach one and a half workgroups per CU (measured inside the step at 256 and 384 tokens:
+    // better than one or two per CU; more ranges only add partial sums), at least 16 K tiles each
+    int best = 1;
+    for (int ks = 2; ks <= 8; ks <<= 1) {
+        if (nk % ks != 0 || nk / ks < 16) break;
+        best = ks;
+        if (wgs * ks >= 384) break;
+    }
+    return best;
+}
+size_t zo_gemm_splitk_bytes(int32_t M, int32_t N, int32_t K, int32_t batch, int dtype)
+{
+    const int ks = zo_gemm_splitk(M, N, K, batch, dtype);
+    return ks > 1 ? (size_t)ks * batch * M * N * sizeof(float) : 0;
+}
+
+// one thread per four consecutive n of one batch entry (blockIdx.y)
+template <typename TY>
+__global__ __launch_bounds__(256) void zo_gemm_splitk_reduce_kernel(zo_gemm_args a, const float* __restrict__ P, int KS)
+{
+    const int N4 = a.N >> 2;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (int64_t)a.M * N4) return;
+    const int b = blockIdx.y;
+    const int m = (int)(i / N4), n = (int)(i % N4) * 4;
+    const int64_t plane = (int64_t)a.M * a.N;
+    const float* p = P + b * plane + (int64_t)m * a.N + n;
+    f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+    for (int ks = 1; ks < KS; ++ks) {
+        const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p + (int64_t)ks * a.batch * plane));
+        v[0] += t[0]; v[1] += t[1]; v[2] += t[2]; v[3] += t[3];
+    }
+    if (a.bias) {
+        const float4 b4 = *reinterpret_cast<const float4*>(a.bias + b * a.strideBias + n);
+        v[0] += b4.x; v[1] += b4.y; v[2] += b4.z; v[3] += b4.w;
+    }
+    if (a.relu) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.0f);
+    }
+    const int64_t off = (int64_t)m * a.N + n;
+    if (a.residual) {
+        const uint2 r2 = *reinterpret_cast<const uint2*>((const zo_bf16*)a.residual + b * a.strideRes + off);
+        v[0] += zo_bf16_lo(r2.x); v[1] += zo_bf16_hi(r2.x);
+        v[2] += zo_bf16_lo(r2.y); v[3] += zo_bf16_hi(r2.y);
+    }
+    if constexpr (sizeof(TY) == 4) {
+        *reinterpret_cast<float4*>((float*)a.Y + b * a.strideY + off) = make_float4(v[0], v[1], v[2], v[3]);
+    } else {
+        uint2 o;
+        o.x = zo_pack_bf16x2(v[0], v[1]);
+        o.y = zo_pack_bf16x2(v[2], v[3]);
+        *reinterpret_cast<uint2*>((zo_bf16*)a.Y + b * a.strideY + off) = o;
+    }
+}
+
 hipError_t zo_launch_gemm(const zo_gemm_args& a, hipStream_t st)
 {
     if (a.M == 0 || a.N == 0) return hipSuccess;
@@ -863,6 +945,24 @@ hipError_t zo_launch_gemm(const zo_gemm_args& a, hipStream_t st)
             const int tiles = ((a.M + 127) / 128) * ((a.N + 127) / 128);
             const dim3 grid(tiles, 1, a.batch);
             constexpr int lds_bytes = 2 * 256 * 64 * 2;
+            const int ks = a.ks_part ? zo_gemm_splitk(a.M, a.N, a.K, a.batch, a.dtype) : 1;
+            if (ks > 1 && a.ks_part_bytes >= zo_gemm_splitk_bytes(a.M, a.N, a.K, a.batch, a.dtype)) {
+                zo_gemm_args p = a;                      // the partial-sum pass: fp32, no epilogue
+                p.Y = a.ks_part;
+                p.strideY = (int64_t)a.M * a.N;
+                p.bias = nullptr; p.residual = nullptr; p.relu = 0; p.out_f32 = 1;
+                p.kspl = ks;
+                hipError_t e_ = hipFuncSetAttribute((const void*)zo_gemm_bf16_dma_kernel<float, 4, 64, 2, 0, 128>,
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+                if (e_ != hipSuccess) return e_;
+                zo_gemm_bf16_dma_kernel<float, 4, 64, 2, 0, 128><<<dim3(tiles, 1, a.batch * ks), 4 * 64, lds_bytes, st>>>(p);
+                e_ = hipGetLastError();
+                if (e_ != hipSuccess) return e_;
+                const dim3 rgrid((unsigned)(((int64_t)a.M * (a.N >> 2) + 255) / 256), a.batch, 1);
+                if (a.out_f32) zo_gemm_splitk_reduce_kernel<float><<<rgrid, 256, 0, st>>>(a, a.ks_part, ks);
+                else zo_gemm_splitk_reduce_kernel<zo_bf16><<<rgrid, 256, 0, st>>>(a, a.ks_part, ks);
+                return hipGetLastError();
+            }
             if (a.out_f32) {
                 hipError_t e_ = hipFuncSetAttribute((const void*)zo_gemm_bf16_dma_kernel<float, 4, 64, 2, 0, 128>,
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);

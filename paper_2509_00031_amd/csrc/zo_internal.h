@@ -95,7 +95,14 @@ struct zo_gemm_args {
     const int32_t* ce_ids;      // shared by the batch entries
     int32_t ce_S;
     int64_t stridePart, strideTgt;   // floats between batch entries
+    // K split of the 128 x 128-tile form (shapes that leave most CUs without a workgroup): ks_part = NULL, or fp32 scratch of
+    // ks_part_bytes >= zo_gemm_splitk_bytes(M, N, K, batch); the launcher then gives every K range a workgroup of its own,
+    // which writes its partial sums there, and a second kernel adds the ranges in order and applies the epilogue
+    float* ks_part; size_t ks_part_bytes;
+    int32_t kspl;               // set by the launcher: K ranges of this launch (0 / 1: none)
 };
+int zo_gemm_splitk(int32_t M, int32_t N, int32_t K, int32_t batch, int dtype);            // K ranges the launcher would use (1: no split)
+size_t zo_gemm_splitk_bytes(int32_t M, int32_t N, int32_t K, int32_t batch, int dtype);   // scratch for them (0: no split)
 bool zo_gemm_ce_supported(int32_t M, int32_t N, int32_t K, int dtype);
 size_t zo_gemm_ce_part_floats(int32_t M, int32_t N);     // floats of ce_part for one batch entry
 // row_loss[m] = log sum exp(logits[m][:]) - logits[m][target], from the partial results above; 0 at the last position

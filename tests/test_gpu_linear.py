@@ -71,6 +71,48 @@ def test_gemm_fused_epilogue(M, N, K, dtype, bias, relu, residual):
     assert np.all(np.abs(out - acc) <= tol)
 
 
+@pytest.mark.parametrize("M,N,K,ranges", [(384, 1024, 4096, 4), (200, 516, 2048, 2), (130, 260, 8192, 8), (384, 1024, 2752, 1),
+                                          (300, 1030, 4096, 1), (4096, 4096, 4096, 1)])
+@pytest.mark.parametrize("out", ["bf16", "residual_f32acc"])
+@pytest.mark.parametrize("bias,relu,residual", [(False, False, False), (True, True, True)])
+def test_gemm_split_k(M, N, K, ranges, out, bias, relu, residual):
+    """The K-split form of the 128 x 128-tile kernel (few tokens, narrow N, long K): 2, 4 and 8 ranges, ragged M and N, and
+    shapes the planner leaves whole (K tiles not divisible, N not a multiple of 4, enough tiles), which must then equal the
+    unsplit entry point bit for bit.  Against the fp64 product; and against the unsplit kernel, from which only the order of
+    the fp32 additions differs."""
+    torch, zo = gpu()
+    if out != "bf16" and not residual:
+        pytest.skip("one output type per epilogue is enough")
+    assert zo.zo_gemm_nt_splitk_ranges(M, N, K) == ranges
+    td = torch.bfloat16
+    X = orc.bf16_round(synth.activations((M, K), 61))
+    W = orc.bf16_round(synth.weights((N, K), 62, scale=1.0))
+    R = orc.bf16_round(synth.activations((M, N), 63))
+    b = synth.weights((N,), 64, scale=1.0)
+    Xd, Wd, bd = to_dev(X, torch, td), to_dev(W, torch, td), to_dev(b, torch) if bias else None
+    Y = to_dev(R, torch, td) if residual else None
+    got = zo.zo_gemm_nt_fused_splitk(Xd, Wd, bd, Y, relu, Y).float().cpu().numpy()
+    Y2 = to_dev(R, torch, td) if residual else None
+    whole = zo.zo_gemm_nt_fused(Xd, Wd, bd, Y2, relu, Y2).float().cpu().numpy()
+    acc = X.astype(np.float64) @ W.astype(np.float64).T
+    mag = np.abs(acc)
+    if bias:
+        acc = acc + b.astype(np.float64)
+    if relu:
+        acc = np.maximum(acc, 0.0)
+    if residual:
+        acc = acc + R.astype(np.float64)
+    tol = 2.0 ** -8 * (np.abs(acc) + mag) + 1e-5 * np.sqrt(K)
+    assert np.all(np.abs(got - acc) <= tol)
+    if ranges == 1:
+        assert np.array_equal(got, whole)
+    else:
+        # same sums in another order: the fp32 sums differ by their accumulated rounding (a few 2^-24 of the largest running
+        # sum per addition), the outputs by at most one bf16 step more, and only where a sum straddles a rounding boundary
+        assert np.all(np.abs(got - whole) <= 2.0 ** -7 * np.abs(whole) + 1e-4 * (mag + np.abs(acc)) + 1e-4)
+        assert np.mean(got != whole) < 0.05
+
+
 @pytest.mark.parametrize("dtype,tol", [("fp32", 1e-4), ("bf16", 1e-2)])
 @pytest.mark.parametrize("M,N,K,wb,g,ab", [(8, 256, 256, 4, 64, 8), (100, 72, 512, 2, 64, 16), (33, 130, 384, 4, 128, 4)])
 def test_linear_fakequant(dtype, tol, M, N, K, wb, g, ab):

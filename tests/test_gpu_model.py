@@ -117,6 +117,32 @@ def _check_forward(arch, act_dtype, a_bits, B, S, eps_list=(1e-3, -1e-3, 0.0), *
 
 
 @pytest.mark.parametrize("arch", ["llama", "opt"])
+def test_forward_with_split_k_gemms(arch):
+    """A couple of hundred tokens, narrow d_model, long d_ffn: the down projection (and nothing else) runs with its K split
+    into ranges whose fp32 partial sums a second kernel adds; same checks as the other bf16 forwards.  (16-bit activations:
+    with activation codes, 200 keys and head dimension 64 the bf16 probabilities of the matrix-core attention flip codes in
+    most rows, and only a loose bound would hold.)"""
+    a_bits = 16
+    torch, zo = gpu()
+    B, S = 1, 200
+    kw = dict(n_layers=1, d_model=256, n_heads=4, d_ffn=2048, vocab=512)
+    _check_forward(arch, 1, a_bits, B, S, eps_list=(1e-3,), **kw)
+    ocfg, params, ids, gp, ctx = _setup(zo, torch, arch, 1, B, S, a_bits=a_bits, **kw)
+    ctx.zo_forward_quant(to_dev(ids, torch), None, B, S, seed=9, eps_signed=1e-3)
+    assert ctx.zo_debug_routes() & zo.ROUTE_GEMM_SPLIT_K
+    # both branches of a step in one launch: (branch, range) pairs share the grid's third dimension
+    out = ctx.zo_step(to_dev(ids, torch), None, B, S, seed=100, eps=1e-3, lr=1e-3).cpu().numpy()
+    assert ctx.zo_debug_routes() & zo.ROUTE_GEMM_SPLIT_K
+    for branch, sign in ((0, 1.0), (1, -1.0)):           # the residual stream each branch left behind
+        trace = {}
+        ref = orc.forward(ocfg, params, ids=ids, seed=100, eps_signed=np.float32(sign * 1e-3), trace=trace)
+        assert abs(out[branch] - ref) <= 1e-3 * abs(ref), (branch, out, ref)
+        x = ctx.zo_debug_buffer(2, branch).view(torch.bfloat16).float().cpu().numpy().reshape(B * S, -1)
+        assert _row_rel(x, trace["l0.out"]).max() < 1e-2
+    ctx.close()
+
+
+@pytest.mark.parametrize("arch", ["llama", "opt"])
 @pytest.mark.parametrize("a_bits", [16, 8])
 def test_zo_step_fp32_mode(arch, a_bits):
     torch, zo = gpu()
