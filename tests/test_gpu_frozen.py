@@ -195,7 +195,7 @@ def test_lightweight_step_small_batch_routes(arch):
         ctx.zo_profile_begin()
         outs.append(ctx.zo_step(ids, None, B, S, seed=6, eps=1e-3, lr=1e-2).cpu().numpy().copy())
         prof = ctx.zo_profile_end()
-        assert ctx.zo_debug_routes() == (0 if no_fused else zo.ROUTE_FUSED_SMALL_M | zo.ROUTE_FUSED_INT4)
+        assert ctx.zo_debug_routes() & ~zo.ROUTE_GEMM_SPLIT_K == (0 if no_fused else zo.ROUTE_FUSED_SMALL_M | zo.ROUTE_FUSED_INT4)
         n_packed = (5 if arch == 1 else 4) * base["n_layers"]          # every linear but Q and V
         n_master = 2 * base["n_layers"] + 1                             # Q, V and the lm_head
         assert prof["fused_int4_linear"][1] == (0 if no_fused else n_packed)
