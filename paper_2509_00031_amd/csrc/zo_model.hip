@@ -153,17 +153,22 @@ __global__ __launch_bounds__(256) void zo_norm_quant_kernel(const T* __restrict_
     const int row = blockIdx.x * (4 / WPR) + threadIdx.x / TPR;
     if (row >= M) return;                            // a whole wavefront (WPR = 1) or workgroup (WPR = 4)
     const T* xr = x + (int64_t)row * d;
-    float v[NC][8];
+    float v[NC][8], g[NC][8];
     float s1 = 0.0f, s2 = 0.0f;
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
         const int c = tr * 8 + 8 * TPR * i;
         if (c < d) {
             zo_load8(xr + c, v[i]);
+            zo_load8(gamma + c, g[i]);               // requested with the row: not needed before the statistics are known
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < NC; ++i)
+        if (tr * 8 + 8 * TPR * i < d) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) { s1 += v[i][e]; s2 = __builtin_fmaf(v[i][e], v[i][e], s2); }
         }
-    }
     s2 = zo_group_sum<64>(s2);
     if (beta) s1 = zo_group_sum<64>(s1);
     if (WPR == 4) {
@@ -198,16 +203,14 @@ __global__ __launch_bounds__(256) void zo_norm_quant_kernel(const T* __restrict_
     for (int i = 0; i < NC; ++i) {
         const int c = tr * 8 + 8 * TPR * i;
         if (c < d) {
-            float g[8];
-            zo_load8(gamma + c, g);
             if (beta) {
                 float b[8];
                 zo_load8(beta + c, b);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[i][e] = zo_round_to<T>(__builtin_fmaf((v[i][e] - mean) * rstd, g[e], b[e]));
+                for (int e = 0; e < 8; ++e) v[i][e] = zo_round_to<T>(__builtin_fmaf((v[i][e] - mean) * rstd, g[i][e], b[e]));
             } else {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[i][e] = zo_round_to<T>((v[i][e] * rstd) * g[e]);
+                for (int e = 0; e < 8; ++e) v[i][e] = zo_round_to<T>((v[i][e] * rstd) * g[i][e]);
             }
             if (sm_delta) {                           // Eq. 4: the quantizer sees (x - delta) / s
                 float dl[8], iv[8];
