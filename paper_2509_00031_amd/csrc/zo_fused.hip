@@ -347,8 +347,8 @@ __global__ __launch_bounds__(FW * 64) void zo_int4_gemm_fused_kernel(zo_fused_ar
 // Split-K form of the kernel above, for when the caller lends scratch memory.  With 16 channels per workgroup every
 // workgroup reads all of X (N/16 times in total, far more than the 0.5 B per weight of the codes), and with one
 // 16-channel operand per wave every matrix instruction needs a fresh 1 KB activation fragment.  Here
-//   * a workgroup = 4 waves covers 256 channels (wave w: 64 of them = four 16-channel operands per K step, so a
-//     fragment read from LDS feeds four matrix instructions) and one of KS ranges of K;
+//   * a workgroup = 4 waves covers 256 or 128 channels (wave w: 64 or 32 of them = four or two 16-channel operands per K step, so a
+//     fragment read from LDS feeds four or two matrix instructions) and one of KS ranges of K;
 //   * the activation fragments of a slab (already in fragment order in a.Xfrag) are copied global -> LDS by the load
 //     unit itself (16 B per lane, no staging registers), two stages, one barrier per slab;
 //   * a workgroup handles MT <= 8 m-tiles: both branches together while they fit (MT = nb * J), else one branch per
@@ -367,9 +367,8 @@ __device__ __forceinline__ void lds_copy16(const void* base, uint32_t voff, uint
 }
 
 constexpr int SW = 4;            // waves per workgroup of the split-K kernel
-constexpr int SRG = 4;           // 16-channel operands per wave
 
-template <int CH, int MT>
+template <int CH, int MT, int SRG>               // SRG: 16-channel operands per wave
 __global__ __launch_bounds__(SW * 64) void zo_int4_gemm_splitk_kernel(zo_fused_args a, float* __restrict__ P, int KS, int J)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
@@ -609,13 +608,18 @@ static hipError_t launch_int4_j(const zo_fused_args& a, hipStream_t st)
     }
 }
 
+// 16-channel operands per wave: four (256 channels per workgroup) where a workgroup carries 8 m-tiles, else two -- measured at
+// the 13B shapes: half the partial sums for twice the activation re-reads pays at 32 tokens (36.5 against 41.7 us per launch)
+// and costs at 128 (104 against 94 us)
+static int splitk_srg(int MT) { return MT >= 8 ? 4 : 2; }
 // number of K ranges: enough workgroups for about one per CU (one per two CUs when a workgroup carries 8 m-tiles): every
 // further range adds a set of fp32 partial sums that is written and read back, and that traffic, not the codes', is what
 // the kernel waits for (measured optimum); at least two slabs each, at most 16
 static int splitk_ranges(int N, int K, int group, int zdim, int MT)
 {
     const int slab = group >= 128 ? 128 : group;
-    const int tiles = ((N + 255) / 256) * zdim, nslab = K / slab;
+    const int chw = SW * splitk_srg(MT) * 16;
+    const int tiles = ((N + chw - 1) / chw) * zdim, nslab = K / slab;
     const int target = MT >= 8 ? 128 : 256;
     int ks = (target + tiles - 1) / tiles;
     if (ks > nslab / 2) ks = nslab / 2;
@@ -633,11 +637,13 @@ template <int CH, int MT>
 static hipError_t launch_splitk_one(const zo_fused_args& a, float* P, int KS, int zdim, hipStream_t st)
 {
     const int lds = 2 * MT * CH * 1024;
+    constexpr int SRG = MT >= 8 ? 4 : 2;             // = splitk_srg(MT)
+    constexpr int chw = SW * SRG * 16;
     if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void*)zo_int4_gemm_splitk_kernel<CH, MT>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        hipError_t e = hipFuncSetAttribute((const void*)zo_int4_gemm_splitk_kernel<CH, MT, SRG>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
     }
-    zo_int4_gemm_splitk_kernel<CH, MT><<<dim3((a.N + 255) / 256, KS, zdim), SW * 64, lds, st>>>(a, KS > 1 ? P : nullptr, KS, tiles_for(a.M));
+    zo_int4_gemm_splitk_kernel<CH, MT, SRG><<<dim3((a.N + chw - 1) / chw, KS, zdim), SW * 64, lds, st>>>(a, KS > 1 ? P : nullptr, KS, tiles_for(a.M));
     if (KS > 1) {
         const int64_t items = (int64_t)a.nb * a.M * (a.N / 4);
         zo_splitk_reduce_kernel<<<(unsigned)((items + 255) / 256), 256, 0, st>>>(a, P, KS);
