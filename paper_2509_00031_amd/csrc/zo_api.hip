@@ -500,7 +500,9 @@ struct fwd {
                 ZO_HIP(c, zo_launch_fused_relayout(at(c->L.br[0].*in), nb == 2 ? (int64_t)(c->L.br[1].*in - c->L.br[0].*in) / ts_ : 0, M, K,
                                                    nb, pending[0].quantize ? c->cfg.w_bits : 0, c->cfg.w_group, at(c->L.what[0]), sxf, c->st));
             }
+            bool launched[4] = {false, false, false, false};
             for (int i = 0; i < npend; ++i) {
+                if (launched[i]) continue;
                 const pend& pe = pending[i];
                 const param_desc& p = c->desc[pe.t];
                 zo_fused_args f{};
@@ -534,6 +536,27 @@ struct fwd {
                         ZO_HIP(c, zo_launch_int4_gemm_splitk(f, at(c->L.what[1]), c->st));
                     else
                         ZO_HIP(c, zo_launch_int4_gemm_fused(f, c->st));
+                    continue;
+                }
+                // a later tensor of the same shape and settings (query and value projections, gate and up) shares the launch:
+                // together their workgroups leave fewer CUs idle in the last round
+                int j = -1;
+                for (int k2 = i + 1; k2 < npend && j < 0; ++k2) {
+                    const pend& pk = pending[k2];
+                    if (!launched[k2] && !pk.packed && pk.quantize == pe.quantize && c->desc[pk.t].rows == p.rows &&
+                        eps_of(pk.t) == f.eps)
+                        j = k2;
+                }
+                if (j >= 0) {
+                    const pend& pk = pending[j];
+                    zo_fused_second f2{};
+                    f2.W = c->params[pk.t].ptr;
+                    f2.Y = at(c->L.br[0].*out) + (size_t)pk.row0 * (out_f32 ? 4 : ts_);
+                    f2.bias = bias ? vec(0, 2) + pk.row0 : nullptr;
+                    f2.residual = residual ? f2.Y : nullptr;
+                    f2.tid = pk.t;
+                    launched[j] = true;
+                    ZO_HIP(c, zo_launch_fq_gemm_fused_pair(f, f2, seed, pe.t, c->st));
                     continue;
                 }
                 ZO_HIP(c, zo_launch_fq_gemm_fused(f, seed, pe.t, c->st));

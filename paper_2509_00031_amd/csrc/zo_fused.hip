@@ -147,8 +147,12 @@ __device__ __forceinline__ void reduce_and_store(const zo_fused_args& a, f32x4 (
 }
 
 template <typename TW, int CH, int GL, int J>
-__global__ __launch_bounds__(FW * 64) void zo_fq_gemm_fused_kernel(zo_fused_args a, zo_stream s)
+__global__ __launch_bounds__(FW * 64) void zo_fq_gemm_fused_kernel(zo_fused_args a, zo_stream s, zo_fused_second second)
 {
+    if (blockIdx.y) {                                        // second tensor of a paired launch
+        a.W = second.W; a.Y = second.Y; a.bias = second.bias; a.residual = second.residual;
+        s.tensor_id = (uint32_t)second.tid;
+    }
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     f32x4* red = reinterpret_cast<f32x4*>(lds_raw);          // [FW][2 * J][64]
     constexpr int SLAB = 32 * CH;
@@ -546,31 +550,31 @@ __global__ __launch_bounds__(256) void zo_fused_relayout_kernel(const zo_bf16* _
 int tiles_for(int M) { return M <= 16 ? 1 : M <= 32 ? 2 : M <= 64 ? 4 : 8; }
 
 template <typename TW, int CH, int GL, int J>
-hipError_t launch_w(const zo_fused_args& a, const zo_stream& s, hipStream_t st)
+hipError_t launch_w(const zo_fused_args& a, const zo_stream& s, const zo_fused_second* second, hipStream_t st)
 {
     constexpr int lds = FW * 2 * J * 1024;
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void*)zo_fq_gemm_fused_kernel<TW, CH, GL, J>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
     }
-    zo_fq_gemm_fused_kernel<TW, CH, GL, J><<<dim3(a.N / 16), FW * 64, lds, st>>>(a, s);
+    zo_fq_gemm_fused_kernel<TW, CH, GL, J><<<dim3(a.N / 16, second ? 2 : 1), FW * 64, lds, st>>>(a, s, second ? *second : zo_fused_second{});
     return hipGetLastError();
 }
 
 template <int CH, int GL, int J>
-hipError_t launch_one(const zo_fused_args& a, const zo_stream& s, hipStream_t st)
+hipError_t launch_one(const zo_fused_args& a, const zo_stream& s, const zo_fused_second* second, hipStream_t st)
 {
-    return a.wdtype == ZO_W_F16 ? launch_w<zo_f16, CH, GL, J>(a, s, st) : launch_w<float, CH, GL, J>(a, s, st);
+    return a.wdtype == ZO_W_F16 ? launch_w<zo_f16, CH, GL, J>(a, s, second, st) : launch_w<float, CH, GL, J>(a, s, second, st);
 }
 
 template <int CH, int GL>
-hipError_t launch_j(const zo_fused_args& a, const zo_stream& s, hipStream_t st)
+hipError_t launch_j(const zo_fused_args& a, const zo_stream& s, const zo_fused_second* second, hipStream_t st)
 {
     switch (tiles_for(a.M)) {
-        case 1:  return launch_one<CH, GL, 1>(a, s, st);
-        case 2:  return launch_one<CH, GL, 2>(a, s, st);
-        case 4:  return launch_one<CH, GL, 4>(a, s, st);
-        default: return launch_one<CH, GL, 8>(a, s, st);
+        case 1:  return launch_one<CH, GL, 1>(a, s, second, st);
+        case 2:  return launch_one<CH, GL, 2>(a, s, second, st);
+        case 4:  return launch_one<CH, GL, 4>(a, s, second, st);
+        default: return launch_one<CH, GL, 8>(a, s, second, st);
     }
 }
 
@@ -710,19 +714,28 @@ hipError_t zo_launch_fused_relayout(const void* X, int64_t strideX, int32_t M, i
     return hipGetLastError();
 }
 
-hipError_t zo_launch_fq_gemm_fused(const zo_fused_args& a, uint64_t seed, int32_t tid, hipStream_t st)
+static hipError_t launch_fq_gemm_fused(const zo_fused_args& a, const zo_fused_second* second, uint64_t seed, int32_t tid, hipStream_t st)
 {
     if (!zo_fused_supported(a.M, a.N, a.K, a.bits, a.group) || (a.nb != 1 && a.nb != 2) || (a.ldY & 3)) return hipErrorInvalidValue;
     zo_stream s;
     s.k0 = (uint32_t)seed;
     s.k1 = (uint32_t)(seed >> 32);
     s.tensor_id = (uint32_t)tid;
-    if (a.bits == 0) return launch_j<1, 1>(a, s, st);
+    if (a.bits == 0) return launch_j<1, 1>(a, s, second, st);
     switch (a.group) {
-        case 8:   return launch_j<1, 1>(a, s, st);
-        case 16:  return launch_j<1, 2>(a, s, st);
-        case 32:  return launch_j<1, 4>(a, s, st);
-        case 64:  return launch_j<2, 4>(a, s, st);
-        default:  return launch_j<4, 4>(a, s, st);
+        case 8:   return launch_j<1, 1>(a, s, second, st);
+        case 16:  return launch_j<1, 2>(a, s, second, st);
+        case 32:  return launch_j<1, 4>(a, s, second, st);
+        case 64:  return launch_j<2, 4>(a, s, second, st);
+        default:  return launch_j<4, 4>(a, s, second, st);
     }
+}
+hipError_t zo_launch_fq_gemm_fused(const zo_fused_args& a, uint64_t seed, int32_t tid, hipStream_t st)
+{
+    return launch_fq_gemm_fused(a, nullptr, seed, tid, st);
+}
+hipError_t zo_launch_fq_gemm_fused_pair(const zo_fused_args& a, const zo_fused_second& second, uint64_t seed, int32_t tid, hipStream_t st)
+{
+    if (!second.W || !second.Y) return hipErrorInvalidValue;
+    return launch_fq_gemm_fused(a, &second, seed, tid, st);
 }

@@ -134,6 +134,10 @@ struct zo_fused_args {
 // M in 1..ZO_FUSED_MAX_M, N a multiple of 16, K a multiple of 32 and of the group
 bool zo_fused_supported(int32_t M, int32_t N, int32_t K, int32_t bits, int32_t group);
 hipError_t zo_launch_fq_gemm_fused(const zo_fused_args& a, uint64_t seed, int32_t tid, hipStream_t st);
+// Two tensors of the same shape and settings (say the query and value projections) in one launch, so that their workgroups
+// share the rounds over the CUs: `second` replaces W, Y, bias and residual of `a` for the second tensor (stream tid2).
+struct zo_fused_second { const void* W; void* Y; const float* bias; const void* residual; int32_t tid; };
+hipError_t zo_launch_fq_gemm_fused_pair(const zo_fused_args& a, const zo_fused_second& second, uint64_t seed, int32_t tid, hipStream_t st);
 // Frozen, pre-quantized linear at small M: the operand is expanded from the packed codes in registers (a.codes /
 // step16 / zp / group; W, bits, eps, seed unused).  group in {32, 64, 128, 256, 512}.  The fragment-ordered copy
 // of the activations is laid out as for bits = 4 and the same group capped at 128.

@@ -115,7 +115,9 @@ def test_model_step_through_fused_route(arch, a_bits):
         prof = ctx.zo_profile_end()
         assert ctx.zo_debug_routes() & ~zo.ROUTE_GEMM_SPLIT_K == (0 if no_fused else zo.ROUTE_FUSED_SMALL_M)
         n_gemm = 4 * kw["n_layers"] + 1                         # GEMM launches of a forward pair (q/k/v and gate/up batched)
-        n_lin = (7 if arch == "llama" else 6) * kw["n_layers"] + 1   # one fused launch per weight tensor
+        # one fused launch per weight tensor, two tensors of one shape that feed on the same input in one launch: per layer
+        # q + k, v, o, gate + up (Llama) or fc1 (OPT), down / fc2; and the lm_head
+        n_lin = 5 * kw["n_layers"] + 1
         if no_fused:
             assert prof["fused_linear"][1] == 0 and prof["gemm"][1] == n_gemm
         else:
