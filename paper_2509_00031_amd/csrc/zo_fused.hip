@@ -372,14 +372,18 @@ __device__ __forceinline__ void lds_copy16(const void* base, uint32_t voff, uint
 
 constexpr int SW = 4;            // waves per workgroup of the split-K kernel
 
-template <int CH, int MT, int SRG>               // SRG: 16-channel operands per wave
-__global__ __launch_bounds__(SW * 64) void zo_int4_gemm_splitk_kernel(zo_fused_args a, float* __restrict__ P, int KS, int J)
+// SRG: 16-channel operands per wave.  KG: wave groups of SW waves each; the groups work on the same channels and deal the
+// slabs of the workgroup's K range among themselves (group g takes slabs g, g + KG, ...), so that a SIMD holds KG waves that
+// hide one another's waits; at the end the groups' accumulators are added through LDS in group order.
+template <int CH, int MT, int SRG, int KG>
+__global__ __launch_bounds__(SW * KG * 64) void zo_int4_gemm_splitk_kernel(zo_fused_args a, float* __restrict__ P, int KS, int J)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     constexpr int SLAB = 32 * CH;
-    constexpr int NF = MT * CH;                              // 1 KB fragments per stage
+    constexpr int NF = MT * CH;                              // 1 KB fragments per stage and wave group
     constexpr int STAGE = NF * 1024;
-    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63, wave_all = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int kg = wave_all / SW, wave = wave_all % SW;
     const int n = lane & 15, q = lane >> 4;
     const int M = a.M, N = a.N, K = a.K, nb = a.nb;
     const bool per_branch = gridDim.z > 1;                   // one branch per workgroup
@@ -389,6 +393,7 @@ __global__ __launch_bounds__(SW * 64) void zo_int4_gemm_splitk_kernel(zo_fused_a
     const int per = (nslab + KS - 1) / KS;
     const int s_begin = blockIdx.y * per;
     const int s_end = s_begin + per < nslab ? s_begin + per : nslab;
+    const int iters = s_end > s_begin ? (s_end - s_begin + KG - 1) / KG : 0;   // the same for every wave of the workgroup
     const int G = K / a.group;
     const uint32_t* crow[SRG];
     const _Float16* srow[SRG];
@@ -404,13 +409,15 @@ __global__ __launch_bounds__(SW * 64) void zo_int4_gemm_splitk_kernel(zo_fused_a
     }
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_offset_of(lds_raw));
     const zo_bf16* xf_base = (const zo_bf16*)a.Xfrag;
-    // fragment fi = t * CH + c of slab sl: m-tile t is (branch, j) = (zb, t) or (t / J, t % J)
+    // fragment fi = t * CH + c of slab sl: m-tile t is (branch, j) = (zb, t) or (t / J, t % J).  A group whose turn falls past the
+    // end of the range copies the range's last slab again (finite values) and multiplies it by all-zero weights.
     auto issue = [&](int stage, int sl) {
+        const int slc = sl < s_end ? sl : s_end - 1;
         for (int fi = wave; fi < NF; fi += SW) {
             const int t = fi / CH, c = fi % CH;
             const int b = per_branch ? zb : t / J, j = per_branch ? t : t % J;
-            const zo_bf16* src = xf_base + b * a.strideXfrag + (((int64_t)sl * J + j) * CH + c) * 512;
-            lds_copy16(src, (uint32_t)lane * 16u, lds0 + stage * STAGE + fi * 1024);
+            const zo_bf16* src = xf_base + b * a.strideXfrag + (((int64_t)slc * J + j) * CH + c) * 512;
+            lds_copy16(src, (uint32_t)lane * 16u, lds0 + (stage * KG + kg) * STAGE + fi * 1024);
         }
     };
 
@@ -429,28 +436,42 @@ __global__ __launch_bounds__(SW * 64) void zo_int4_gemm_splitk_kernel(zo_fused_a
     int zq[SRG], zqn[SRG];
 #pragma unroll
     for (int r = 0; r < SRG; ++r) { st[r] = stn[r] = 0.0f; zq[r] = zqn[r] = 0; }
-    if (s_begin < s_end) {
-        issue(0, s_begin);
-        const int g0 = s_begin * SLAB / a.group;
+    if (iters > 0) {
+        const int sl0 = s_begin + kg;
+        issue(0, sl0);
+        if (sl0 < s_end) {
+            const int g0 = sl0 * SLAB / a.group;
 #pragma unroll
-        for (int r = 0; r < SRG; ++r) {
-            load_words<CH>(crow[r] + s_begin * (SLAB / 8), words[r]);
-            st[r] = (float)srow[r][g0];
-            zq[r] = zrow[r][g0];
+            for (int r = 0; r < SRG; ++r) {
+                load_words<CH>(crow[r] + sl0 * (SLAB / 8), words[r]);
+                st[r] = (float)srow[r][g0];
+                zq[r] = zrow[r][g0];
+            }
         }
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0): this wave's copies have landed
     __syncthreads();
     int stage = 0;
-    for (int sl = s_begin; sl < s_end; ++sl) {
-        if (sl + 1 < s_end) {                                // stage ^ 1 was last read before the barrier just passed
-            issue(stage ^ 1, sl + 1);
-            const int gn = (sl + 1) * SLAB / a.group;        // codes, step and zero point of the next slab: one slab ahead
+    for (int it = 0; it < iters; ++it) {
+        const int sln = s_begin + (it + 1) * KG + kg;        // this group's next slab
+        if (it + 1 < iters) {                                // stage ^ 1 was last read before the barrier just passed
+            issue(stage ^ 1, sln);
+            if (sln < s_end) {                               // codes, step and zero point of the next slab: one slab ahead
+                const int gn = sln * SLAB / a.group;
 #pragma unroll
-            for (int r = 0; r < SRG; ++r) {
-                load_words<CH>(crow[r] + (sl + 1) * (SLAB / 8), wnext[r]);
-                stn[r] = (float)srow[r][gn];
-                zqn[r] = zrow[r][gn];
+                for (int r = 0; r < SRG; ++r) {
+                    load_words<CH>(crow[r] + sln * (SLAB / 8), wnext[r]);
+                    stn[r] = (float)srow[r][gn];
+                    zqn[r] = zrow[r][gn];
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < SRG; ++r) {
+                    stn[r] = 0.0f;
+                    zqn[r] = 0;
+#pragma unroll
+                    for (int c = 0; c < CH; ++c) wnext[r][c] = 0u;
+                }
             }
         }
         bf16x8 af[SRG][CH];
@@ -466,7 +487,7 @@ __global__ __launch_bounds__(SW * 64) void zo_int4_gemm_splitk_kernel(zo_fused_a
         }
         // fragments are read from LDS two ahead of their use (ring of three), in the order c-major / t-minor so that
         // consecutive matrix instructions never wait for one another's accumulator
-        const unsigned char* sb = lds_raw + stage * STAGE + lane * 16;
+        const unsigned char* sb = lds_raw + (stage * KG + kg) * STAGE + lane * 16;
         auto frag = [&](int f) { return *reinterpret_cast<const bf16x8*>(sb + (((f % MT) * CH + f / MT) << 10)); };
         bf16x8 xq[3];
         xq[0] = frag(0);
@@ -492,6 +513,27 @@ __global__ __launch_bounds__(SW * 64) void zo_int4_gemm_splitk_kernel(zo_fused_a
     __builtin_amdgcn_sched_barrier(0);
     asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
+    if constexpr (KG > 1) {
+        // the last barrier of the loop is behind every wave: the stages are free.  Groups 1 .. KG-1 hand their sums to group 0.
+        f32x4* red = reinterpret_cast<f32x4*>(lds_raw);      // [KG - 1][SW][SRG][MT][64]
+        if (kg > 0) {
+#pragma unroll
+            for (int r = 0; r < SRG; ++r)
+#pragma unroll
+                for (int t = 0; t < MT; ++t) red[((((kg - 1) * SW + wave) * SRG + r) * MT + t) * 64 + lane] = acc[r][t];
+        }
+        __syncthreads();
+        if (kg > 0) return;
+#pragma unroll
+        for (int g = 1; g < KG; ++g)
+#pragma unroll
+            for (int r = 0; r < SRG; ++r)
+#pragma unroll
+                for (int t = 0; t < MT; ++t) {
+                    const f32x4 p = red[((((g - 1) * SW + wave) * SRG + r) * MT + t) * 64 + lane];
+                    acc[r][t][0] += p[0]; acc[r][t][1] += p[1]; acc[r][t][2] += p[2]; acc[r][t][3] += p[3];
+                }
+    }
 #pragma unroll
     for (int r = 0; r < SRG; ++r)
 #pragma unroll
@@ -616,19 +658,26 @@ static hipError_t launch_int4_j(const zo_fused_args& a, hipStream_t st)
 // the 13B shapes: half the partial sums for twice the activation re-reads pays at 32 tokens (36.5 against 41.7 us per launch)
 // and costs at 128 (104 against 94 us)
 static int splitk_srg(int MT) { return MT >= 8 ? 4 : 2; }
-// number of K ranges: enough workgroups for about one per CU (one per two CUs when a workgroup carries 8 m-tiles): every
-// further range adds a set of fp32 partial sums that is written and read back, and that traffic, not the codes', is what
-// the kernel waits for (measured optimum); at least two slabs each, at most 16
-static int splitk_ranges(int N, int K, int group, int zdim, int MT)
+// Number of K ranges.  Timers inside the kernel: a workgroup spends about 0.9 us per slab and wave (operand expansion, LDS
+// reads and matrix instructions mostly one after the other) and 30 % more waiting for the next slab, so a launch lasts about as
+// long as the CU with the most slabs to work through: (rounds of workgroups over the 256 CUs) x (slabs per workgroup).  Every
+// further range also adds a set of fp32 partial sums, written and read back (8 B per output at about 4 TB/s, in units of a
+// slab's 0.9 us).  The count that minimises the sum is taken; at least two slabs per range, at most 16 ranges.  Against "one
+// workgroup per CU, rounded up": 34.0 instead of 36.9 us per launch at 32 tokens, 86.8 instead of 94.7 at 128 (13B shapes).
+static int splitk_ranges(int M, int nb, int N, int K, int group, int zdim, int MT)
 {
     const int slab = group >= 128 ? 128 : group;
     const int chw = SW * splitk_srg(MT) * 16;
     const int tiles = ((N + chw - 1) / chw) * zdim, nslab = K / slab;
-    const int target = MT >= 8 ? 128 : 256;
-    int ks = (target + tiles - 1) / tiles;
-    if (ks > nslab / 2) ks = nslab / 2;
-    if (ks > 16) ks = 16;
-    return ks < 1 ? 1 : ks;
+    const double per_range = 2.2e-6 * nb * (double)M * N;
+    int best = 1;
+    double best_cost = 0.0;
+    for (int ks = 1; ks <= 16 && (ks == 1 || ks <= nslab / 2); ++ks) {
+        const int rounds = (tiles * ks + 255) / 256, slabs = (nslab + ks - 1) / ks;
+        const double cost = (double)rounds * slabs + (ks > 1 ? ks * per_range : 0.0);
+        if (ks == 1 || cost < best_cost) { best = ks; best_cost = cost; }
+    }
+    return best;
 }
 // m-tiles per workgroup and workgroups along z for M rows and nb branches
 static void splitk_shape(int M, int nb, int& MT, int& zdim)
@@ -640,14 +689,17 @@ static void splitk_shape(int M, int nb, int& MT, int& zdim)
 template <int CH, int MT>
 static hipError_t launch_splitk_one(const zo_fused_args& a, float* P, int KS, int zdim, hipStream_t st)
 {
-    const int lds = 2 * MT * CH * 1024;
     constexpr int SRG = MT >= 8 ? 4 : 2;             // = splitk_srg(MT)
+    constexpr int KG = MT >= 8 ? 1 : 2;              // two wave groups (two waves per SIMD) while their registers fit
     constexpr int chw = SW * SRG * 16;
+    constexpr int lds_stages = 2 * KG * MT * CH * 1024, lds_red = (KG - 1) * SW * SRG * MT * 1024;
+    constexpr int lds = lds_stages > lds_red ? lds_stages : lds_red;
+    static_assert(lds <= 160 * 1024, "LDS of the split-K kernel");
     if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void*)zo_int4_gemm_splitk_kernel<CH, MT, SRG>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        hipError_t e = hipFuncSetAttribute((const void*)zo_int4_gemm_splitk_kernel<CH, MT, SRG, KG>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
     }
-    zo_int4_gemm_splitk_kernel<CH, MT, SRG><<<dim3((a.N + chw - 1) / chw, KS, zdim), SW * 64, lds, st>>>(a, KS > 1 ? P : nullptr, KS, tiles_for(a.M));
+    zo_int4_gemm_splitk_kernel<CH, MT, SRG, KG><<<dim3((a.N + chw - 1) / chw, KS, zdim), SW * KG * 64, lds, st>>>(a, KS > 1 ? P : nullptr, KS, tiles_for(a.M));
     if (KS > 1) {
         const int64_t items = (int64_t)a.nb * a.M * (a.N / 4);
         zo_splitk_reduce_kernel<<<(unsigned)((items + 255) / 256), 256, 0, st>>>(a, P, KS);
@@ -678,7 +730,7 @@ hipError_t zo_launch_int4_gemm_splitk(const zo_fused_args& a, void* partials, hi
         return hipErrorInvalidValue;
     int MT, zdim;
     splitk_shape(a.M, a.nb, MT, zdim);
-    const int KS = splitk_ranges(a.N, a.K, a.group, zdim, MT);
+    const int KS = splitk_ranges(a.M, a.nb, a.N, a.K, a.group, zdim, MT);
     if (a.group == 32) return launch_splitk_mt<1>(a, (float*)partials, KS, MT, zdim, st);
     if (a.group == 64) return launch_splitk_mt<2>(a, (float*)partials, KS, MT, zdim, st);
     return launch_splitk_mt<4>(a, (float*)partials, KS, MT, zdim, st);
