@@ -75,7 +75,8 @@ typedef struct {
                             the rotary embedding there (zo_debug_routes tells which routes a forward took);
                             1 = always quantize once into the workspace and run the plain GEMM with the stand-alone kernels.
                             Independent of this flag, a large bf16 forward forms its cross entropy in the lm_head GEMM's
-                            epilogue and stores no logits. */
+                            epilogue and stores no logits, and the bf16 GEMMs of a few hundred tokens onto a narrow output
+                            split K into ranges whose fp32 partial sums a second kernel adds in order. */
     int32_t master_dtype;/* ZO_MASTER_*: storage type of every tensor of the parameter list.  ZO_MASTER_F16 = IEEE binary16,
                             the 2 bytes per parameter that the memory table of the efficiency section implies: a
                             forward reads the stored value (exactly widened to fp32) wherever it read the fp32 master;
