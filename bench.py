@@ -40,6 +40,8 @@ WORKLOADS = {
     # fused kernel that builds the tiles of Q(W +- eps u) in registers; --no-fused times the quantize-once route
     "llama7b_w4a8_g64_1x128": dict(arch="llama", n_layers=32, d_model=4096, n_heads=32, d_ffn=11008, vocab=32000,
                                    w_bits=4, w_group=64, a_bits=8, B=1, S=128),
+    "llama7b_w4a8_g64_1x64": dict(arch="llama", n_layers=32, d_model=4096, n_heads=32, d_ffn=11008, vocab=32000,
+                                  w_bits=4, w_group=64, a_bits=8, B=1, S=64),
     "llama7b_w4a8_g64_1x32": dict(arch="llama", n_layers=32, d_model=4096, n_heads=32, d_ffn=11008, vocab=32000,
                                   w_bits=4, w_group=64, a_bits=8, B=1, S=32),
     # between the two regimes (the fine-tuning table's 384-token sequences, batch 1 and 16): quantize once, then GEMMs
@@ -52,6 +54,8 @@ WORKLOADS = {
     # the lightweight variant in the same regime: frozen linears expanded from their packed codes inside the kernel
     "llama13b_lightweight_w4a4_g128_1x128": dict(arch="llama", n_layers=40, d_model=5120, n_heads=40, d_ffn=13824,
                                                  vocab=32000, w_bits=4, w_group=128, a_bits=4, B=1, S=128, lightweight=1),
+    "llama13b_lightweight_w4a4_g128_1x64": dict(arch="llama", n_layers=40, d_model=5120, n_heads=40, d_ffn=13824,
+                                                vocab=32000, w_bits=4, w_group=128, a_bits=4, B=1, S=64, lightweight=1),
     "llama13b_lightweight_w4a4_g128_1x32": dict(arch="llama", n_layers=40, d_model=5120, n_heads=40, d_ffn=13824,
                                                 vocab=32000, w_bits=4, w_group=128, a_bits=4, B=1, S=32, lightweight=1),
     "tiny_w4a16_g64_8x128": dict(arch="llama", n_layers=4, d_model=512, n_heads=8, d_ffn=2048, vocab=4096,

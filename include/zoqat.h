@@ -67,8 +67,8 @@ typedef struct {
     int32_t learn_smooth;/* 1 = channel-wise smoothing (Eq. 4): every distinct input activation of the
                             quantized linears gets two more trainable fp32 tensors [K] -- s and delta;
                             needs learn_clip = 1 and a_bits < 16 */
-    int32_t no_fused;    /* 0 = the linears of a forward over at most 128 tokens (bf16 storage, groups of 8..128 -- 32..128
-                            when packed tensors are attached --, no learned tensors) build their weight tiles inside
+    int32_t no_fused;    /* 0 = the linears of a forward over at most 128 tokens (bf16 storage, groups of 8..128 -- at most 64
+                            tokens and groups of 32..128 when packed tensors are attached --, no learned tensors) build their weight tiles inside
                             the GEMM kernel, from the masters or from the packed codes; large bf16 Llama-shaped forwards
                             without smoothing interleave the gate and up rows in the operand buffer and take silu(gate) * up
                             in the GEMM epilogue, and (head dimension 128) permute the head blocks of q | k | v and apply

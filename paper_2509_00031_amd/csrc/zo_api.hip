@@ -318,6 +318,10 @@ struct fwd {
         const zo_config& cfg = c->cfg;
         if (cfg.no_fused || cfg.act_dtype != ZO_ACT_BF16 || cfg.learn_clip) return false;
         const param_desc& p = c->desc[t];
+        // with packed tensors attached the small-M kernels pay up to 64 tokens only: the packed-codes kernel's time grows with the
+        // m-tiles it carries, expanding the codes once and running the plain GEMM does not (13B shapes, 128 tokens: 35.3 ms per
+        // step through the small-M kernels, 31.4 ms without; 64 tokens: 25.7 against 29.4 ms)
+        if (c->n_packed > 0 && M > 64) return false;
         if (c->frozen[t].codes)                          // stored codes: expanded inside the kernel
             return c->packed_fusable && zo_int4_fused_supported(M, (int)p.rows, (int)p.cols, c->frozen[t].group);
         if (c->n_packed > 0 && !c->packed_fusable) return false;
