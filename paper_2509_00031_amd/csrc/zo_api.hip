@@ -497,8 +497,11 @@ struct fwd {
             // (otherwise idle) operand buffers
             bool any_packed = false;
             for (int i = 0; i < npend; ++i) any_packed = any_packed || pending[i].packed;
-            const bool relayout = (M > 32 || any_packed) && zo_fused_relayout_bytes(M, K) <= c->L.what_bytes;
-            const int64_t sxf = (int64_t)(c->L.what[1] - c->L.what[0]) / 2;
+            // both branches' copies sit side by side in the FIRST operand buffer; the second one stays free for the fp32
+            // partial sums of the packed-codes kernel's K split
+            const size_t rl_bytes = align_up(zo_fused_relayout_bytes(M, K));
+            const bool relayout = (M > 32 || any_packed) && 2 * rl_bytes <= c->L.what_bytes;
+            const int64_t sxf = (int64_t)(rl_bytes / 2);
             if (relayout) {
                 prof_scope ps(c, ZO_PROF_OTHER);
                 ZO_HIP(c, zo_launch_fused_relayout(at(c->L.br[0].*in), nb == 2 ? (int64_t)(c->L.br[1].*in - c->L.br[0].*in) / ts_ : 0, M, K,
@@ -863,6 +866,7 @@ zo_status zo_init(const zo_config* cfg, const zo_tensor* params, int32_t n_param
         if (!aligned16(params[i].ptr)) return ZO_EALIGN;
     }
     if (cfg->arch != ZO_ARCH_LINEAR && max_S > cfg->max_seq) return ZO_ESHAPE;
+    if (cfg->arch == ZO_ARCH_LINEAR && max_S != 1) return ZO_ESHAPE;      // its workspace is sized for max_B rows
     if (!aligned16(workspace)) return ZO_EALIGN;
     layout L = make_layout(*cfg, max_B, max_S);
     if (workspace_bytes < L.total) return ZO_EWORKSPACE;

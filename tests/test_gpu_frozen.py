@@ -215,3 +215,37 @@ def test_lightweight_step_small_batch_routes(arch):
         else:
             assert np.array_equal(ws[0][k], params[i])
         k += 1
+
+
+@pytest.mark.parametrize("S", [24, 8])
+def test_lightweight_small_batch_two_packed_tensors_with_k_split(S):
+    """Wide enough (d_model 512, groups of 64: 8 slabs along K) that the packed-codes kernel splits K for the gate | up
+    pair -- two packed tensors applied to one input, one launch after the other, each with fp32 partial sums in scratch --
+    and for the down projection, with both branches of Eq. 2 in flight.  The activations' fragment-ordered copies of the
+    two branches and the partial sums must not share memory: L+ and L- against the oracle and against the
+    quantize-once route."""
+    torch, zo = gpu()
+    B = 2
+    base = dict(n_layers=2, d_model=512, n_heads=4, d_ffn=1024, vocab=512, max_seq=S, w_bits=4, w_group=64, a_bits=8)
+    ocfg = orc.Config(1, act_dtype=1, lightweight=1, **base)
+    shapes = orc.param_shapes(ocfg)
+    params = synth.model_params(shapes, 518)
+    params = [p * (2.0 if p.ndim == 2 else 1.0) for p in params]
+    trainable = [n.endswith(".wq") or n.endswith(".wv") for n, _, _ in shapes]
+    ids = synth.token_ids(B, S, 512, 519)
+    o_params = [orc.pack_int4(w, 64) if (q and not t) else w.copy() for w, t, (_, _, q) in zip(params, trainable, shapes)]
+    lp = orc.forward(ocfg, o_params, ids=ids, seed=6, eps_signed=np.float32(1e-3), trainable=trainable)
+    lm = orc.forward(ocfg, o_params, ids=ids, seed=6, eps_signed=np.float32(-1e-3), trainable=trainable)
+    outs = []
+    for no_fused in (0, 1):
+        cfg = zo.make_config(1, act_dtype=1, lightweight=1, no_fused=no_fused, **base)
+        g_params = [zo.zo_pack_weight_int4(to_dev(w, torch), 64) if (q and not t) else to_dev(w, torch)
+                    for w, t, (_, _, q) in zip(params, trainable, shapes)]
+        ctx = zo.Context(cfg, g_params, B, S, trainable=trainable)
+        outs.append(ctx.zo_step(to_dev(ids, torch), None, B, S, seed=6, eps=1e-3, lr=0.0).cpu().numpy().copy())
+        if not no_fused:
+            assert ctx.zo_debug_routes() & zo.ROUTE_FUSED_INT4
+        ctx.close()
+    for out in outs:
+        assert abs(out[0] - lp) <= 1e-3 * abs(lp) and abs(out[1] - lm) <= 1e-3 * abs(lm), (out, lp, lm)
+    assert np.allclose(outs[0][:2], outs[1][:2], rtol=3e-4)
