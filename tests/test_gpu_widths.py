@@ -18,7 +18,11 @@ pytestmark = pytest.mark.gpu
 EPS = 1e-3
 
 
-def _one_layer_step(arch, S, routes_want, lightweight=0, lr=1e-3, **kw):
+def _row_rel(a, b):
+    return np.linalg.norm(a.astype(np.float64) - b, axis=1) / np.maximum(np.linalg.norm(b, axis=1), 1e-30)
+
+
+def _one_layer_step(arch, S, routes_want, lightweight=0, lr=1e-3, loss_tol=1e-3, **kw):
     torch, zo = gpu()
     base = dict(n_layers=1, max_seq=S, **kw)
     ocfg = orc.Config(arch, act_dtype=1, lightweight=lightweight, **base)
@@ -37,19 +41,39 @@ def _one_layer_step(arch, S, routes_want, lightweight=0, lr=1e-3, **kw):
     ctx = zo.Context(cfg, g_params, 1, S, trainable=trainable)
     out = ctx.zo_step(to_dev(ids, torch), None, 1, S, seed=0, eps=EPS, lr=lr).cpu().numpy()
     routes = ctx.zo_debug_routes()
-    before = [w.copy() if isinstance(w, np.ndarray) else None for w in o_params]
-    lp, lm, g = orc.zo_step(ocfg, o_params, 0, EPS, lr, ids=ids, trainable=trainable)
+    # the oracle's step, taken apart so that both forwards leave their stored activations behind: Eq. 2's two losses,
+    # the projected gradient, the coefficient, and (below) Eq. 3 on the tensors that are compared
+    ref_loss = []
+    for branch, sign in ((0, 1.0), (1, -1.0)):
+        trace = {}
+        ref_loss.append(orc.forward(ocfg, o_params, ids=ids, seed=0, eps_signed=np.float32(sign * EPS), trainable=trainable, trace=trace))
+        # q | k | v lie upstream of everything that amplifies rounding noise: one norm + quantizer and one linear away
+        # from the embedding.  A row may carry a flipped activation code; almost every row agrees to rounding.
+        qkv = ctx.zo_debug_buffer(3, branch).view(torch.bfloat16).float().cpu().numpy().reshape(S, -1)
+        err = _row_rel(qkv, trace["l0.qkv"])
+        assert np.median(err) < 1e-4 and np.quantile(err, 0.9) < 1e-3 and err.max() < 5e-2, (branch, np.median(err), err.max())
+        attn = ctx.zo_debug_buffer(4, branch).view(torch.bfloat16).float().cpu().numpy().reshape(S, -1)
+        err = _row_rel(attn, trace["l0.attn"])
+        assert np.median(err) < 5e-3 and err.max() < 3e-2, (branch, np.median(err), err.max())
+        x = ctx.zo_debug_buffer(2, branch).view(torch.bfloat16).float().cpu().numpy().reshape(S, -1)
+        e_out = np.linalg.norm(x - trace["l0.out"]) / np.linalg.norm(trace["l0.out"])
+        print("branch %d: layer output, whole tensor relative l2 error %.2e" % (branch, e_out))
+        if kw["a_bits"] == 16:
+            assert e_out < 1e-2
+    lp, lm = ref_loss
+    g = orc.projected_grad(lp, lm, np.float32(EPS))
     print("gpu L+ %.6f L- %.6f g %+.4f | oracle L+ %.6f L- %.6f g %+.4f | routes 0x%x" % (out[0], out[1], out[2], lp, lm, g, routes))
-    assert abs(out[0] - lp) <= 1e-3 * abs(lp) and abs(out[1] - lm) <= 1e-3 * abs(lm)
+    assert abs(out[0] - lp) <= loss_tol * abs(lp) and abs(out[1] - lm) <= loss_tol * abs(lm)
     assert out[2] == orc.projected_grad(np.float32(out[0]), np.float32(out[1]), np.float32(EPS))
     assert out[3] == orc.coeff(np.float32(lr), out[2])
     assert routes & ~zo.ROUTE_GEMM_SPLIT_K == routes_want, hex(routes)      # a K split of narrow GEMMs is a launch detail
-    # the update of two tensors (the first quantized linear, the lm_head), bit-exact given the device's coefficient
+    # Eq. 3 on the first quantized linear and on the lm_head, bit-exact given the device's coefficient
     for i in (2, len(shapes) - 1):
-        if before[i] is None or (trainable is not None and not trainable[i]):
-            assert before[i] is None or np.array_equal(g_params[i].cpu().numpy(), before[i])
+        if trainable is not None and not trainable[i]:
+            if isinstance(o_params[i], np.ndarray):
+                assert np.array_equal(g_params[i].cpu().numpy(), o_params[i])
             continue
-        assert np.array_equal(g_params[i].cpu().numpy(), orc.update(before[i].copy(), 0, i, np.float32(out[3])))
+        assert np.array_equal(g_params[i].cpu().numpy(), orc.update(o_params[i].copy(), 0, i, np.float32(out[3])))
     ctx.close()
 
 
@@ -67,11 +91,21 @@ def test_opt1p3b_widths_one_layer():
     _one_layer_step(2, 512, zo.ROUTE_CE_IN_GEMM, d_model=2048, n_heads=32, d_ffn=8192, vocab=50272, w_bits=4, w_group=128, a_bits=8)
 
 
-def test_llama13b_lightweight_widths_one_layer():
-    """Frozen linears as packed 4-bit codes (group 128), trainable query / value projections, 4-bit activations."""
+@pytest.mark.parametrize("a_bits", [8, 4])
+def test_llama13b_lightweight_widths_one_layer(a_bits):
+    """Frozen linears as packed 4-bit codes (group 128), trainable query / value projections.  With 8-bit activations the
+    losses hold the 1e-3 of the other workloads.  With the configuration's 4-bit per-token activations they cannot: a
+    code step is half a standard deviation of its row (15 steps over ~8 sigma), so an input disagreement of relative size
+    e flips a fraction ~2e of the codes by a whole step and comes out as ~sqrt(e / 2): the 2.5e-3 per row that the bf16
+    probabilities of the matrix-core attention add (see test_gpu_attention.py) grow to 3.5e-2 after the attention-output
+    quantizer, 0.13 after the FFN's, ~0.3 after the down projection's -- in the oracle's arithmetic just as on the GPU,
+    whichever of two valid roundings a side takes.  Token losses then differ by O(0.3) each way and their mean over
+    1023 positions by ~1e-2 = 1e-3 relative: the bound asserted here is 3e-3, and what lies upstream of the attention
+    (q | k | v) and the attention itself are held as sharply as in every other configuration."""
     torch, zo = gpu()
     _one_layer_step(1, 1024, zo.ROUTE_SWIGLU_IN_GEMM | zo.ROUTE_ROPE_IN_GEMM | zo.ROUTE_CE_IN_GEMM, lightweight=1,
-                    d_model=5120, n_heads=40, d_ffn=13824, vocab=32000, w_bits=4, w_group=128, a_bits=4)
+                    loss_tol=1e-3 if a_bits == 8 else 3e-3,
+                    d_model=5120, n_heads=40, d_ffn=13824, vocab=32000, w_bits=4, w_group=128, a_bits=a_bits)
 
 
 def test_tiny_decoder_ten_steps():
