@@ -326,13 +326,18 @@ class Config:
     """Mirror of the library's configuration record (field meaning identical)."""
 
     def __init__(self, arch, n_layers=0, d_model=0, n_heads=1, d_ffn=0, vocab=0, max_seq=0,
-                 w_bits=4, w_group=64, a_bits=16, a_sym=0, act_dtype=0, lightweight=0, learn_clip=0, learn_smooth=0):
+                 w_bits=4, w_group=64, a_bits=16, a_sym=0, act_dtype=0, lightweight=0, learn_clip=0, learn_smooth=0, mma=0):
         self.arch, self.n_layers, self.d_model, self.n_heads = arch, n_layers, d_model, n_heads
         self.d_ffn, self.vocab, self.max_seq = d_ffn, vocab, max_seq
         self.w_bits, self.w_group, self.a_bits, self.a_sym = w_bits, w_group, a_bits, a_sym
         self.act_dtype, self.lightweight = act_dtype, lightweight
         # learnable quantizer parameters (Eq. 5) / channel-wise smoothing (Eq. 4) as ZO-trained tensors
         self.learn_clip, self.learn_smooth = learn_clip, learn_smooth
+        # mma = 1: a quantized linear with weight and activation codes contracts the integer codes themselves, so its
+        # operands are the quantizer's outputs (code - zp) * step as they are -- NOT rounded to bf16 first, whatever the
+        # storage type of activations (the rounding of GEMM operands in bf16 mode is a property of the bf16 contraction,
+        # not of the quantizer of the Background section).  Stored activations are still rounded to act_dtype.
+        self.mma = mma
 
 
 GROUP_MODEL, GROUP_SMOOTH, GROUP_CLIP = 0, 1, 2      # learning-rate groups (Appendix, hyperparameter table)
@@ -419,6 +424,11 @@ def _base_param_shapes(cfg):
     return out
 
 
+def _operand_bf16(cfg):
+    """Are the operands of a quantized linear rounded to bf16 before they are multiplied?"""
+    return cfg.act_dtype == 1 and not (cfg.mma == 1 and cfg.w_bits > 0 and cfg.a_bits <= 8)
+
+
 def _rt(cfg, a):
     """Round to the storage type of activations (bf16 in bf16 mode, fp32 otherwise)."""
     a32 = np.asarray(a, np.float64).astype(np.float32)
@@ -455,19 +465,19 @@ class _Params:
         cfg = self.cfg
         if isinstance(self.params[i], PackedInt4):     # frozen and pre-quantized: used as stored
             assert self.trainable is not None and not self.trainable[i]
-            return dequant_int4(self.params[i], round_bf16=(cfg.act_dtype == 1))
+            return dequant_int4(self.params[i], round_bf16=_operand_bf16(cfg))
         scale = self.plain(smooth_owner(name) + ".sm_s") if cfg.learn_smooth else None
         if cfg.learn_clip:
             qp = [self.plain(name + sfx) for sfx in (".q_step", ".q_zp", ".q_alpha", ".q_beta")]
             return fakequant_weight_learned(self.params[i], cfg.w_bits, cfg.w_group, *qp, scale=scale, seed=self.seed,
                                             tensor_id=i, eps_signed=self._eps_for(i),
-                                            round_bf16=(cfg.act_dtype == 1), want_codes=False)["what"]
+                                            round_bf16=_operand_bf16(cfg), want_codes=False)["what"]
         if scale is not None:
             # smoothing with the dynamic quantizer: min/max of every group of s (.) (W + eps u)
             wb = (perturb(self.params[i], self.seed, i, self._eps_for(i)) * scale[None, :]).astype(np.float32)
-            return fakequant_weight(wb, cfg.w_bits, cfg.w_group, round_bf16=(cfg.act_dtype == 1), want_codes=False)["what"]
+            return fakequant_weight(wb, cfg.w_bits, cfg.w_group, round_bf16=_operand_bf16(cfg), want_codes=False)["what"]
         return fakequant_weight(self.params[i], cfg.w_bits, cfg.w_group, self.seed, i, self._eps_for(i),
-                                round_bf16=(cfg.act_dtype == 1), want_codes=False)["what"]
+                                round_bf16=_operand_bf16(cfg), want_codes=False)["what"]
 
     def smooth(self, name):
         """Activation side and bias term of Eq. 4 for linear `name`: (delta', 1/s', delta' W'^T) or None."""
@@ -496,7 +506,7 @@ def _qlinear(cfg, x, what, bias=None, residual=None, relu=False, tie_log=None, s
         delta, inv_s, shift = smooth
         x = smooth_act(x, delta, inv_s)
         bias = shift if bias is None else bias.astype(np.float64) + shift
-    qa = fakequant_act(x, cfg.a_bits, cfg.a_sym, round_bf16=(cfg.act_dtype == 1), want_codes=False)
+    qa = fakequant_act(x, cfg.a_bits, cfg.a_sym, round_bf16=_operand_bf16(cfg), want_codes=False)
     xq = qa["xhat"]
     if tie_log is not None and cfg.a_bits < 16:
         tie_log.append(_tie_margin(x, qa["step"]))
