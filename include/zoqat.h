@@ -357,6 +357,20 @@ zo_status zo_gemm_nt_fused_splitk(const void* X_dev, const void* W_dev, const fl
                                   void* Y_dev, int32_t M, int32_t N, int32_t K, int32_t dtype, void* scratch_dev, size_t scratch_bytes,
                                   void* hip_stream);
 
+/* zo_gemm_nt_fused_splitk for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): no scratch argument.  The partial sums of the K ranges go to a device
+ * array that is part of the library (zo_gemm_nt_splitk_static_max_bytes() = 32 MiB, held on every GPU the library is
+ * loaded on until the process ends); the call allocates and frees nothing, on the device or through any library.
+ * Same kernels, same K ranges, bit-identical results to zo_gemm_nt_fused_splitk with a scratch of
+ * zo_gemm_nt_splitk_scratch_bytes bytes.  ZO_EWORKSPACE (nothing launched) if the shape's K ranges need more than the
+ * array holds; other errors as zo_gemm_nt_fused.  All calls on one GPU share the one array: calls that may overlap on a
+ * GPU (different streams, different threads) race on it -- keep them on one stream or order them with events.  Nothing
+ * has to be cleared between calls (every partial sum is written before it is read). */
+size_t zo_gemm_nt_splitk_static_max_bytes(void);
+zo_status zo_gemm_nt_fused_splitk_static(const void* X_dev, const void* W_dev, const float* bias_dev, const void* residual_dev,
+                                         int32_t relu, void* Y_dev, int32_t M, int32_t N, int32_t K, int32_t dtype,
+                                         void* hip_stream);
+
 /* The gate / up GEMM of a SwiGLU block with the activation in its epilogue (what large bf16 Llama-shaped forwards run):
  *   W dev bf16 [N2][K]: rows of the gate and the up projection interleaved in blocks of 32 channels -- rows 64 i .. 64 i + 31
  *   = gate channels 32 i .., rows 64 i + 32 .. 64 i + 63 = up channels 32 i ..;  X dev bf16 [M][K];

@@ -28,7 +28,8 @@ EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "
            "zo_attention_scratch_bytes", "zo_pack_weight_int4", "zo_attach_frozen_int4", "zo_linear_frozen_int4", "zo_gemm_nt_fused", "zo_init_learned_params", "zo_step_groups", "zo_update_groups",
            "zo_debug_quant_weight_learned", "zo_debug_smooth_bias", "zo_linear_fakequant_fused", "zo_linear_fused_scratch_bytes",
            "zo_step_multi", "zo_update_multi", "zo_lr_linear_decay", "zo_update_tensor_f16", "zo_master_bytes", "zo_linear_frozen_int4_fused", "zo_linear_frozen_fused_scratch_bytes", "zo_gemm_nt_swiglu", "zo_debug_routes", "zo_gemm_nt_ce", "zo_gemm_nt_ce_scratch_bytes", "zo_profile_begin_mask",
-           "zo_gemm_nt_splitk_ranges", "zo_gemm_nt_splitk_scratch_bytes", "zo_gemm_nt_fused_splitk"]
+           "zo_gemm_nt_splitk_ranges", "zo_gemm_nt_splitk_scratch_bytes", "zo_gemm_nt_fused_splitk",
+           "zo_gemm_nt_splitk_static_max_bytes", "zo_gemm_nt_fused_splitk_static"]
 PROF_NAMES = ["gemm", "weight_quant", "act_quant", "attention", "update", "other", "fused_linear", "fused_int4_linear"]
 
 
@@ -91,6 +92,9 @@ _lib.zo_attach_frozen_int4.argtypes = [_vp, _i32, _vp, _vp, _vp, _i32]
 _lib.zo_linear_frozen_int4.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp]
 _lib.zo_gemm_nt_fused.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _i32, _i32, _i32, _i32, _vp]
 _lib.zo_gemm_nt_fused_splitk.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _i32, _i32, _i32, _i32, _vp, _sz, _vp]
+_lib.zo_gemm_nt_fused_splitk_static.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _i32, _i32, _i32, _i32, _vp]
+_lib.zo_gemm_nt_splitk_static_max_bytes.argtypes = []
+_lib.zo_gemm_nt_splitk_static_max_bytes.restype = _sz
 _lib.zo_gemm_nt_splitk_ranges.argtypes = [_i32, _i32, _i32, _i32]
 _lib.zo_gemm_nt_splitk_ranges.restype = _i32
 _lib.zo_gemm_nt_splitk_scratch_bytes.argtypes = [_i32, _i32, _i32, _i32]
@@ -477,6 +481,24 @@ def zo_gemm_nt_fused_splitk(X, W, bias=None, residual=None, relu=False, Y=None):
     scratch = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=X.device)
     _check(_lib.zo_gemm_nt_fused_splitk(X.data_ptr(), W.data_ptr(), _ptr(bias), _ptr(residual), int(relu), Y.data_ptr(), M, N, K, dtype,
                                         scratch.data_ptr(), nbytes, _stream()), "zo_gemm_nt_fused_splitk")
+    return Y
+
+
+def zo_gemm_nt_splitk_scratch_bytes(M, N, K, dtype=ACT_BF16):
+    return int(_lib.zo_gemm_nt_splitk_scratch_bytes(M, N, K, dtype))
+
+
+def zo_gemm_nt_splitk_static_max_bytes():
+    return int(_lib.zo_gemm_nt_splitk_static_max_bytes())
+
+
+def zo_gemm_nt_fused_splitk_static(X, W, Y, bias=None, residual=None, relu=False):
+    """The caller passes every buffer, Y included: the call itself allocates nothing."""
+    M, K = X.shape
+    N = W.shape[0]
+    dtype = ACT_BF16 if X.dtype == torch.bfloat16 else ACT_FP32
+    _check(_lib.zo_gemm_nt_fused_splitk_static(X.data_ptr(), W.data_ptr(), _ptr(bias), _ptr(residual), int(relu), Y.data_ptr(),
+                                               M, N, K, dtype, _stream()), "zo_gemm_nt_fused_splitk_static")
     return Y
 
 

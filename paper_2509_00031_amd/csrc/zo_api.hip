@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstring>
 #include <string>
+#include <mutex>
 #include <vector>
 
 namespace {
@@ -1501,6 +1502,47 @@ zo_status zo_gemm_nt_fused_splitk(const void* X_dev, const void* W_dev, const fl
     a.M = M; a.N = N; a.K = K; a.batch = 1; a.dtype = dtype;
     a.ks_part = (float*)scratch_dev;
     a.ks_part_bytes = scratch_dev ? scratch_bytes : 0;
+    return zo_launch_gemm(a, (hipStream_t)hip_stream) == hipSuccess ? ZO_OK : ZO_EHIP;
+}
+
+// ---- the K-split GEMM for callers that cannot allocate -------------------------------------------------------------
+// The partial sums live in a file-scope device array instead of caller-provided scratch.  The array's name is a host-side
+// stand-in only; its device address is looked up once per device (every GPU holds its own copy) and that pointer is
+// what the kernels receive.
+enum { ZO_STATIC_SCRATCH_BYTES = 32 << 20, ZO_STATIC_MAX_DEVICES = 64 };
+static __device__ __align__(256) float zo_static_scratch[ZO_STATIC_SCRATCH_BYTES / sizeof(float)];
+static float* zo_static_scratch_ptr[ZO_STATIC_MAX_DEVICES];
+static std::mutex zo_static_scratch_mutex;
+
+size_t zo_gemm_nt_splitk_static_max_bytes(void) { return (size_t)ZO_STATIC_SCRATCH_BYTES; }
+
+zo_status zo_gemm_nt_fused_splitk_static(const void* X_dev, const void* W_dev, const float* bias_dev, const void* residual_dev,
+                                         int32_t relu, void* Y_dev, int32_t M, int32_t N, int32_t K, int32_t dtype, void* hip_stream)
+{
+    if (!X_dev || !W_dev || !Y_dev || M < 0 || N < 0 || K <= 0) return ZO_EINVAL;
+    if (dtype != ZO_ACT_FP32 && dtype != ZO_ACT_BF16) return ZO_EINVAL;
+    if (K & 7) return ZO_ESHAPE;
+    if (!aligned16(X_dev) || !aligned16(W_dev) || !aligned16(Y_dev) || !aligned16(bias_dev) || !aligned16(residual_dev))
+        return ZO_EALIGN;
+    const size_t need = zo_gemm_splitk_bytes(M, N, K, 1, dtype == ZO_ACT_BF16 ? ZO_T_BF16 : ZO_T_F32);
+    if (need > (size_t)ZO_STATIC_SCRATCH_BYTES) return ZO_EWORKSPACE;     // the K ranges of this shape need more than the array holds
+    float* scratch = nullptr;
+    if (need) {
+        int dev = -1;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= ZO_STATIC_MAX_DEVICES) return ZO_EHIP;
+        std::lock_guard<std::mutex> lock(zo_static_scratch_mutex);
+        if (!zo_static_scratch_ptr[dev]) {
+            void* p = nullptr;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(zo_static_scratch)) != hipSuccess || !p) return ZO_EHIP;
+            zo_static_scratch_ptr[dev] = (float*)p;
+        }
+        scratch = zo_static_scratch_ptr[dev];
+    }
+    zo_gemm_args a{};
+    a.X = X_dev; a.W = W_dev; a.Y = Y_dev; a.bias = bias_dev; a.residual = residual_dev; a.relu = relu ? 1 : 0;
+    a.M = M; a.N = N; a.K = K; a.batch = 1; a.dtype = dtype;
+    a.ks_part = scratch;                                   // every range's partial sums are written before they are read:
+    a.ks_part_bytes = scratch ? need : 0;                  // nothing left by an earlier call is ever seen
     return zo_launch_gemm(a, (hipStream_t)hip_stream) == hipSuccess ? ZO_OK : ZO_EHIP;
 }
 
