@@ -29,7 +29,8 @@ EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "
            "zo_debug_quant_weight_learned", "zo_debug_smooth_bias", "zo_linear_fakequant_fused", "zo_linear_fused_scratch_bytes",
            "zo_step_multi", "zo_update_multi", "zo_lr_linear_decay", "zo_update_tensor_f16", "zo_master_bytes", "zo_linear_frozen_int4_fused", "zo_linear_frozen_fused_scratch_bytes", "zo_gemm_nt_swiglu", "zo_debug_routes", "zo_gemm_nt_ce", "zo_gemm_nt_ce_scratch_bytes", "zo_profile_begin_mask",
            "zo_gemm_nt_splitk_ranges", "zo_gemm_nt_splitk_scratch_bytes", "zo_gemm_nt_fused_splitk",
-           "zo_gemm_nt_splitk_static_max_bytes", "zo_gemm_nt_fused_splitk_static"]
+           "zo_gemm_nt_splitk_static_max_bytes", "zo_gemm_nt_fused_splitk_static",
+           "zo_linear_mma_scratch_bytes", "zo_linear_fakequant_mma"]
 PROF_NAMES = ["gemm", "weight_quant", "act_quant", "attention", "update", "other", "fused_linear", "fused_int4_linear"]
 
 
@@ -95,6 +96,10 @@ _lib.zo_gemm_nt_fused_splitk.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _i32, _i
 _lib.zo_gemm_nt_fused_splitk_static.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _i32, _i32, _i32, _i32, _vp]
 _lib.zo_gemm_nt_splitk_static_max_bytes.argtypes = []
 _lib.zo_gemm_nt_splitk_static_max_bytes.restype = _sz
+_lib.zo_linear_mma_scratch_bytes.argtypes = [_i32, _i32, _i32, _i32, _i32, _i32, C.POINTER(_sz)]
+_lib.zo_linear_mma_scratch_bytes.restype = _sz
+_lib.zo_linear_fakequant_mma.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _u64, _i32, _f32,
+                                         _vp, _vp, _vp]
 _lib.zo_gemm_nt_splitk_ranges.argtypes = [_i32, _i32, _i32, _i32]
 _lib.zo_gemm_nt_splitk_ranges.restype = _i32
 _lib.zo_gemm_nt_splitk_scratch_bytes.argtypes = [_i32, _i32, _i32, _i32]
@@ -482,6 +487,38 @@ def zo_gemm_nt_fused_splitk(X, W, bias=None, residual=None, relu=False, Y=None):
     _check(_lib.zo_gemm_nt_fused_splitk(X.data_ptr(), W.data_ptr(), _ptr(bias), _ptr(residual), int(relu), Y.data_ptr(), M, N, K, dtype,
                                         scratch.data_ptr(), nbytes, _stream()), "zo_gemm_nt_fused_splitk")
     return Y
+
+
+MMA_BF16, MMA_INT8 = 0, 1
+
+
+def zo_linear_fakequant_mma(X, W, w_bits, w_group, a_bits, seed, tensor_id, eps_signed, mma=MMA_INT8, bias=None, a_sym=False,
+                            out_f32=False, parts=False):
+    """Returns Y, or (Y, dict of the scratch pieces) with parts=True (integer-code route only).  Raises ZoError(5) if a
+    weight operand did not fit a signed byte."""
+    M, K = X.shape
+    N = W.shape[0]
+    dtype = ACT_BF16 if X.dtype == torch.bfloat16 else ACT_FP32
+    off = (_sz * 8)()
+    nbytes = int(_lib.zo_linear_mma_scratch_bytes(M, N, K, w_group, dtype, mma, off))
+    if nbytes == 0:
+        raise ZoError(2, "zo_linear_mma_scratch_bytes")
+    scratch = torch.empty(nbytes, dtype=torch.uint8, device=X.device)
+    flag = torch.zeros(1, dtype=torch.int32, device=X.device)
+    Y = torch.empty((M, N), dtype=torch.float32 if out_f32 else torch.bfloat16, device=X.device)
+    _check(_lib.zo_linear_fakequant_mma(X.data_ptr(), W.data_ptr(), _ptr(bias), Y.data_ptr(), M, N, K, w_bits, w_group, a_bits,
+                                        int(a_sym), dtype, int(out_f32), mma, seed, tensor_id, eps_signed, scratch.data_ptr(),
+                                        flag.data_ptr(), _stream()), "zo_linear_fakequant_mma")
+    if int(flag.item()) != 0:
+        raise ZoError(5, "zo_linear_fakequant_mma", "a weight operand q - zp does not fit a signed byte")
+    if not parts:
+        return Y
+    G = K // (w_group or K)
+    o = list(off)
+    piece = lambda i, n, dt: scratch[o[i]:o[i] + n * torch.empty(0, dtype=dt).element_size()].view(dt)
+    return Y, dict(x_codes=piece(0, M * K, torch.int8).view(M, K), x_step=piece(1, M, torch.float32), x_off=piece(2, M, torch.float32),
+                   w_codes=piece(3, N * K, torch.int8).view(N, K), w_r=piece(5, N, torch.float32),
+                   w_rpart=piece(6, N * G, torch.float32).view(N, G))
 
 
 def zo_gemm_nt_splitk_scratch_bytes(M, N, K, dtype=ACT_BF16):

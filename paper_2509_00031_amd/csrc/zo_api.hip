@@ -1286,6 +1286,75 @@ zo_status zo_linear_fakequant(const void* X_dev, const float* W_dev, const float
     return zo_launch_gemm(a, st) == hipSuccess ? ZO_OK : ZO_EHIP;
 }
 
+// scratch of the integer-code route: [0] activation codes, [1] token steps, [2] token offsets, [3] weight codes,
+// [4] weight steps, [5] r, [6] per-group parts of r, [7] end
+static void linear_i8_layout(int32_t M, int32_t N, int32_t K, int32_t w_group, size_t off[8])
+{
+    const size_t G = (size_t)(K / (w_group ? w_group : K));
+    size_t o = 0;
+    off[0] = o; o += align_up((size_t)M * K);
+    off[1] = o; o += align_up((size_t)M * 4);
+    off[2] = o; o += align_up((size_t)M * 4);
+    off[3] = o; o += align_up((size_t)N * K);
+    off[4] = o; o += align_up(zo_i8_scale_floats(N, K, w_group) * 4);
+    off[5] = o; o += align_up((size_t)N * 4);
+    off[6] = o; o += align_up((size_t)N * G * 4);
+    off[7] = o;
+}
+
+size_t zo_linear_mma_scratch_bytes(int32_t M, int32_t N, int32_t K, int32_t w_group, int32_t dtype, int32_t mma, size_t* offsets_host)
+{
+    if (M < 0 || N < 0 || K <= 0 || w_group < 0) return 0;
+    if (mma == ZO_MMA_BF16) return zo_linear_scratch_bytes(M, N, K, dtype);
+    if (mma != ZO_MMA_INT8 || (w_group && K % w_group)) return 0;
+    size_t off[8];
+    linear_i8_layout(M, N, K, w_group, off);
+    if (offsets_host) memcpy(offsets_host, off, sizeof(off));
+    return off[7];
+}
+
+zo_status zo_linear_fakequant_mma(const void* X_dev, const float* W_dev, const float* bias_dev, void* Y_dev,
+                                  int32_t M, int32_t N, int32_t K, int32_t w_bits, int32_t w_group,
+                                  int32_t a_bits, int32_t a_sym, int32_t dtype, int32_t out_f32, int32_t mma,
+                                  uint64_t seed, int32_t tensor_id, float eps_signed, void* scratch_dev, int32_t* flag_dev,
+                                  void* hip_stream)
+{
+    if (mma == ZO_MMA_BF16) {
+        if (out_f32 != (dtype == ZO_ACT_FP32)) return ZO_EUNSUPPORTED;
+        return zo_linear_fakequant(X_dev, W_dev, bias_dev, Y_dev, M, N, K, w_bits, w_group, a_bits, a_sym, dtype, seed, tensor_id,
+                                   eps_signed, scratch_dev, hip_stream);
+    }
+    if (mma != ZO_MMA_INT8) return ZO_EINVAL;
+    if (!X_dev || !W_dev || !Y_dev || !scratch_dev || !flag_dev || M < 0 || N < 0 || K <= 0) return ZO_EINVAL;
+    if (dtype != ZO_ACT_FP32 && dtype != ZO_ACT_BF16) return ZO_EINVAL;
+    if (w_group < 0) return ZO_EINVAL;
+    if (M == 0 || N == 0) return ZO_OK;
+    if (!zo_i8_supported(M, N, K, w_bits, w_group, a_bits)) return ZO_EUNSUPPORTED;    // needs weight AND activation codes
+    if (!aligned16(X_dev) || !aligned16(W_dev) || !aligned16(Y_dev) || !aligned16(scratch_dev) || !aligned16(bias_dev) ||
+        ((uintptr_t)flag_dev & 3))
+        return ZO_EALIGN;
+    hipStream_t st = (hipStream_t)hip_stream;
+    size_t off[8];
+    linear_i8_layout(M, N, K, w_group, off);
+    char* sc = (char*)scratch_dev;
+    int8_t* xc = (int8_t*)(sc + off[0]);
+    float* xs = (float*)(sc + off[1]);
+    float* xo = (float*)(sc + off[2]);
+    int8_t* wc = (int8_t*)(sc + off[3]);
+    float* ws = (float*)(sc + off[4]);
+    float* wr = (float*)(sc + off[5]);
+    float* rpart = (float*)(sc + off[6]);
+    if (zo_launch_act_codes_i8(X_dev, xc, xs, xo, M, K, a_bits, a_sym, dtype, st) != hipSuccess) return ZO_EHIP;
+    if (zo_launch_weight_codes_i8(W_dev, N, K, w_bits, w_group, seed, tensor_id, eps_signed, ZO_W_F32, wc, nullptr, ws, nullptr, wr,
+                                  nullptr, rpart, nullptr, flag_dev, st) != hipSuccess)
+        return ZO_EHIP;
+    zo_i8_gemm_args a{};
+    a.X = xc; a.W = wc; a.xs = xs; a.xo = xo; a.ws = ws; a.wr = wr; a.Y = Y_dev; a.bias = bias_dev;
+    a.M = M; a.N = N; a.K = K; a.batch = 1;
+    a.sgroup = w_group ? w_group : K;
+    return zo_launch_gemm_i8(a, out_f32, st) == hipSuccess ? ZO_OK : ZO_EHIP;
+}
+
 size_t zo_linear_fused_scratch_bytes(int32_t M, int32_t K)
 {
     if (M <= 0 || K <= 0) return 0;

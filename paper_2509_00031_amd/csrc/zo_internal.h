@@ -189,3 +189,25 @@ hipError_t zo_launch_reduce_loss(const float* row_loss, int32_t M, float scale, 
 // out6 = { L+, L-, g, lr[0]*g, lr[1]*g, lr[2]*g } from loss[0], loss[1]; the first n_user values also go to user_out
 hipError_t zo_launch_projected_grad(const float* loss2, float eps, const float lr[3], float* out6, float* user_out, int n_user,
                                     hipStream_t st);
+
+// ---- quantized linear on the integer codes (int8 matrix instructions) ----------------------------
+// y = step_x (sum_g step_w S_g + (O - zx) r): see zo_i8.hip.  w_group 64 or a multiple of 128 (at most 512), K a multiple of 128.
+bool zo_i8_supported(int32_t M, int32_t N, int32_t K, int32_t w_bits, int32_t w_group, int32_t a_bits);
+size_t zo_i8_scale_floats(int32_t N, int32_t K, int32_t w_group);       // floats of one branch's array of weight steps
+hipError_t zo_launch_act_codes_i8(const void* X, int8_t* codes, float* xs, float* xo, int32_t M, int32_t K, int32_t bits, int32_t sym,
+                                  int dtype, hipStream_t st);
+hipError_t zo_launch_weight_codes_i8(const void* W, int32_t N, int32_t K, int32_t bits, int32_t group, uint64_t seed, int32_t tid, float eps,
+                                     int wdtype, int8_t* cp, int8_t* cm, float* wsp, float* wsm, float* rp, float* rm, float* rpart_p,
+                                     float* rpart_m, int* overflow, hipStream_t st);
+struct zo_i8_gemm_args {
+    const int8_t* X; const int8_t* W;        // codes [M][K], [N][K]
+    const float* xs; const float* xo;        // per token: step, O - zero point
+    const float* ws;                         // [K / sgroup][tiles_n * 256] weight steps
+    const float* wr;                         // [N]
+    void* Y; const float* bias; const void* residual;
+    int32_t M, N, K, batch, sgroup;          // sgroup: k per weight step (64, or a multiple of 128)
+    int64_t strideX, strideW, strideXs, strideWs, strideWr, strideY, strideBias, strideRes;
+    int32_t relu;
+};
+hipError_t zo_launch_gemm_i8(const zo_i8_gemm_args& a, int out_f32, hipStream_t st);
+
