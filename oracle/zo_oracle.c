@@ -198,6 +198,17 @@ void zo_or_perturb(const float* w, int64_t n, uint64_t seed, int32_t tensor_id,
 /* ------------------------------------------------------------------ */
 #define ZO_OR_STEP_MIN 1e-5f
 
+/* float -> int32 for REPORTED integers (codes, zero points): saturating, NaN -> 0.  The zero point of the Background
+ * section, -round(min / step), is unbounded (a constant group far from zero, whose step is the floor, can exceed 2^31);
+ * the arithmetic keeps it as a float, only the integer handed back saturates. */
+static int32_t sat_i32(float v)
+{
+    if (!(v == v)) return 0;
+    if (v >= 2147483648.0f) return INT32_MAX;
+    if (v <= -2147483648.0f) return INT32_MIN;
+    return (int32_t)v;
+}
+
 void zo_or_quant_group(const float* x, int n, int bits, int sym,
                        float* step_out, int32_t* zp_out, int32_t* codes, float* xhat)
 {
@@ -223,11 +234,11 @@ void zo_or_quant_group(const float* x, int n, int bits, int sym,
         float q = rintf(x[i] * inv) + zpf;
         if (q < qn) q = qn;
         if (q > qp) q = qp;
-        if (codes) codes[i] = (int32_t)q;
+        if (codes) codes[i] = sat_i32(q);
         if (xhat)  xhat[i]  = (q - zpf) * step;
     }
     if (step_out) *step_out = step;
-    if (zp_out)   *zp_out   = (int32_t)zpf;
+    if (zp_out)   *zp_out   = sat_i32(zpf);
 }
 
 /* Weight fake-quantizer: W[N,K] row-major, groups of `group` consecutive k
@@ -295,7 +306,7 @@ void zo_or_quant_group_learned(const float* x, int n, int bits, float step, floa
         float q = rintf(x[i] * inv) + zr;
         if (q < lo) q = lo;
         if (q > hi) q = hi;
-        if (codes) codes[i] = (int32_t)q;
+        if (codes) codes[i] = sat_i32(q);
         if (xhat)  xhat[i]  = (q - zr) * st;
     }
 }
