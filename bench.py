@@ -61,11 +61,21 @@ WORKLOADS = {
     "tiny_w4a16_g64_8x128": dict(arch="llama", n_layers=4, d_model=512, n_heads=8, d_ffn=2048, vocab=4096,
                                  w_bits=4, w_group=64, a_bits=16, B=8, S=128),
 }
-# HBM-side bytes per launch of the GEMM kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes over this same
-# command (scaled by a plain copy of known size; profiles/zo_step_llama7b_w4a8_hbm_traffic.txt): 2.000 x 1380.6 MB
-# read + 1.000 x 256.9 MB written, averaged over the GEMM launches of a step (all epilogue forms).  Counters cannot be
-# read from inside the run, so other workloads report null.
-MEASURED_GEMM_TRAFFIC = {"llama7b_w4a8_g64_8x1024": 2.0 * 1380.6e6 + 256.9e6}
+# HBM-side bytes per launch of the GEMM kernel: counters cannot be read from inside the run, so the figure is the one
+# the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary of this same command holds (profiles/zo_step_<workload>_hbm_traffic.txt,
+# line "gemm_traffic_bytes_per_launch = ..."; it says how the counters were scaled by a plain copy of known size).  A workload
+# without such a summary reports null; the summary is regenerated whenever the GEMM kernel or its launch order changes.
+def measured_gemm_traffic(workload):
+    path = os.path.join(ROOT, "profiles", "zo_step_%s_hbm_traffic.txt" % workload.replace("_g64_8x1024", ""))
+    try:
+        for line in open(path):
+            if line.strip().startswith("gemm_traffic_bytes_per_launch"):
+                return float(line.split("=")[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
 BREAKDOWN_STEPS = 2
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
@@ -258,7 +268,7 @@ def main():
         flops_per_launch = gflops * args.steps / max(gemm_launches, 1)
         achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12 if avg_ms > 0 else 0.0
         res["roofline"] = {"bound": "mfma", "kernel": "zo_gemm_bf16_dma_kernel<bf16, 8 waves, BK 64, 2 stages>", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
-                           "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": MEASURED_GEMM_TRAFFIC.get(args.workload),
+                           "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_gemm_traffic(args.workload),
                            "launches": gemm_launches, "avg_launch_ms": avg_ms,
                            "flops_per_launch": flops_per_launch}
         res["gemm_tflops"] = achieved
@@ -295,6 +305,18 @@ def main():
                                 "frac": upd_gbs / PEAK_HBM_GBS if upd_gbs else None, "bytes_per_param": upd_bpp,
                                 "ms_per_step": upd_ms / max(upd_groups, 1)}
         res["breakdown_ms_per_step"] = {k: v[0] / BREAKDOWN_STEPS for k, v in prof_all.items()}
+        if res["roofline"]["bound"] == "mfma":
+            # The weights are quantized once per step into the operand buffers (the prologue of every fake-quantized GEMM):
+            # "frac" is the GEMM kernel alone, "frac_with_prologue" counts 2 M N K against GEMM time + weight-quantizer time
+            # (timed region's GEMM time per step + the weight-quantizer time of the fully bracketed steps).
+            gemm_ms_step = gemm_ms / args.steps
+            wq_ms_step = res["breakdown_ms_per_step"]["weight_quant"]
+            with_pro = gflops / ((gemm_ms_step + wq_ms_step) * 1e-3) / 1e12
+            res["roofline"].update({"frac_gemm_only": res["roofline"]["frac"], "frac_with_prologue": with_pro / PEAK_BF16_TFLOPS,
+                                    "achieved_with_prologue": with_pro, "prologue": "zo_fq_weight_kernel (quantize once per step)",
+                                    "prologue_ms_per_step": wq_ms_step, "gemm_ms_per_step": gemm_ms_step,
+                                    "note": "frac = GEMM kernel alone (2MNK / its launch time); frac_with_prologue = 2MNK / (GEMM + weight "
+                                            "quantizer time); the 0.50 target is compared with both"})
         res["breakdown_source"] = "%d further steps after the timed region, every launch bracketed by events" % BREAKDOWN_STEPS
     res["step_flops"] = gflops + attention_flops_per_step(w) * args.directions
     res["step_tflops"] = res["step_flops"] / (ms_per_step * 1e-3) / 1e12

@@ -16,7 +16,8 @@
  *   - "dev" pointers are device (HBM) addresses, "host" pointers are host addresses;
  *   - the caller owns every device buffer (master weights, workspace, ids, outputs); the library
  *     never allocates or frees device memory, and it launches all work asynchronously on the
- *     hipStream_t given at zo_init / in the call (passed as void*); it never synchronises;
+ *     hipStream_t given at zo_init / in the call (passed as void*); the only call that waits for the
+ *     stream is zo_profile_end, which has to read its events;
  *   - matrices are row-major; a linear weight is W[N][K] (N outputs, K inputs, K contiguous) and
  *     Y[M][N] = X[M][K] * W^T;
  *   - element i (flat, row-major) of tensor number t under seed s always receives the same
@@ -223,7 +224,7 @@ zo_status zo_debug_quant_weight(const float* W_dev, int32_t N, int32_t K, int32_
 
 /* Fill the tensors of Eq. 5 / Eq. 4 of a context (caller's memory, on the context's stream): s = 1,
  * delta = 0; step and zero point as the default asymmetric scheme computes them from W, alpha = 0, beta = 1
- * ("initialized based on the default asymmetric quantization scheme").  Uses the workspace as scratch. */
+ * (the initial values the paragraph on the adaptive weight quantizer, Eq. 5, prescribes).  Uses the workspace as scratch. */
 zo_status zo_init_learned_params(zo_ctx* ctx);
 
 /* zo_step with one learning rate per group (Appendix, hyperparameter table: model, smoothing, clipping).

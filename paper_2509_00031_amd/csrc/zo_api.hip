@@ -254,6 +254,7 @@ struct zo_ctx {
     std::vector<hipEvent_t> ev_pool;      // created on demand, reused across sessions
     size_t ev_used = 0;
     std::vector<int> ev_cat;              // category of event pair i = events 2i, 2i+1
+    std::vector<float> rope_host[2];      // source of the asynchronous upload of the rotary table: lives as long as the context
 };
 
 namespace {
@@ -886,16 +887,18 @@ zo_status zo_init(const zo_config* cfg, const zo_tensor* params, int32_t n_param
     if (cfg->arch == ZO_ARCH_LLAMA) {
         // rotary angle table: cos / sin of pos * 10000^(-2i/dh), evaluated in fp64, stored fp32
         const int dh = cfg->d_model / cfg->n_heads, half = dh / 2;
-        std::vector<float> cs((size_t)cfg->max_seq * half), sn((size_t)cfg->max_seq * half);
+        std::vector<float>&cs = c->rope_host[0], &sn = c->rope_host[1];
+        cs.resize((size_t)cfg->max_seq * half);
+        sn.resize((size_t)cfg->max_seq * half);
         for (int p = 0; p < cfg->max_seq; ++p)
             for (int i = 0; i < half; ++i) {
                 const double ang = (double)p * std::pow(10000.0, -2.0 * (double)i / (double)dh);
                 cs[(size_t)p * half + i] = (float)std::cos(ang);
                 sn[(size_t)p * half + i] = (float)std::sin(ang);
             }
+        // asynchronous: the host copies belong to the context, so nothing has to be waited for here
         hipError_t e = hipMemcpyAsync(c->ws + L.rope_cos, cs.data(), cs.size() * 4, hipMemcpyHostToDevice, c->st);
         if (e == hipSuccess) e = hipMemcpyAsync(c->ws + L.rope_sin, sn.data(), sn.size() * 4, hipMemcpyHostToDevice, c->st);
-        if (e == hipSuccess) e = hipStreamSynchronize(c->st);      // host vectors die at return
         if (e != hipSuccess) { delete c; return ZO_EHIP; }
     }
     *out = c;
