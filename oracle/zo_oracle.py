@@ -647,6 +647,122 @@ def forward(cfg, params, ids=None, x=None, target=None, seed=0, eps_signed=0.0, 
     return cross_entropy(logits, ids, B, S)
 
 
+# ---- inference on the trained (quantized) model: prompt pass + token-by-token decoding with a key / value cache ----
+# The efficiency section's on-device table runs the quantized model as a generator (prompt of a few hundred tokens,
+# then one token at a time).  The computation is the quantized forward above at eps = 0 restricted to what a generator
+# needs: every layer keeps the keys (after the rotary embedding) and values of the positions seen so far, as stored
+# activations; a new token's query attends to all of them.  Per-token activation quantizers make every row independent of
+# the others, so a cached step computes exactly what the full forward computes at that position.
+
+def _rope_rows(x, pos, H, dh):
+    """Rotate pairs (i, i + dh/2) of every head of row r by the angle of position pos[r]."""
+    cos, sin = rope_table(int(np.max(pos)) + 1, dh)
+    T = x.shape[0]
+    x = x.astype(np.float64).reshape(T, H, dh)
+    x1, x2 = x[..., : dh // 2], x[..., dh // 2:]
+    c = cos.astype(np.float64)[pos][:, None, :]
+    s_ = sin.astype(np.float64)[pos][:, None, :]
+    return np.concatenate([x1 * c - x2 * s_, x2 * c + x1 * s_], -1).reshape(T, H * dh)
+
+
+def _attend_rows(q, K, V, pos, H, dh):
+    """Row r (position pos[r]) attends to cache rows 0 .. pos[r]; plain loops over rows and heads, fp64."""
+    T = q.shape[0]
+    out = np.zeros((T, H * dh), np.float64)
+    for r in range(T):
+        n = int(pos[r]) + 1
+        for h in range(H):
+            sl = slice(h * dh, (h + 1) * dh)
+            sc = K[:n, sl].astype(np.float64) @ q[r, sl].astype(np.float64) / np.sqrt(dh)
+            sc = np.exp(sc - sc.max())
+            out[r, sl] = (sc / sc.sum()) @ V[:n, sl].astype(np.float64)
+    return out
+
+
+def _infer_rows(cfg, params, tokens, pos, kv, trainable):
+    """Rows for `tokens` at positions `pos` (consecutive, starting at the cache length); extends kv; returns the final
+    hidden states (stored type) of those rows."""
+    P = _Params(cfg, params, 0, 0.0, trainable)
+    d, H = cfg.d_model, cfg.n_heads
+    dh = d // H
+    tokens = np.asarray(tokens).reshape(-1)
+    pos = np.asarray(pos).reshape(-1)
+    emb = P.plain("tok_emb")
+    if cfg.arch == ARCH_OPT:
+        xres = _rt(cfg, emb[tokens].astype(np.float64) + P.plain("pos_emb")[pos].astype(np.float64))
+    else:
+        xres = _rt(cfg, emb[tokens])
+    for l in range(cfg.n_layers):
+        p = "l%d." % l
+        llama = cfg.arch == ARCH_LLAMA
+        if llama:
+            h = _rt(cfg, _rmsnorm(xres, P.plain(p + "attn_norm")))
+            bq = bk = bv = bo = None
+        else:
+            h = _rt(cfg, _layernorm(xres, P.plain(p + "ln1_g"), P.plain(p + "ln1_b")))
+            bq, bk, bv, bo = (P.plain(p + n) for n in ("bq", "bk", "bv", "bo"))
+        q = _qlinear(cfg, h, P.qweight(p + "wq"), bq)
+        k = _qlinear(cfg, h, P.qweight(p + "wk"), bk)
+        v = _qlinear(cfg, h, P.qweight(p + "wv"), bv)
+        if llama:
+            q = _rt(cfg, _rope_rows(q, pos, H, dh))
+            k = _rt(cfg, _rope_rows(k, pos, H, dh))
+        K = k if kv[l][0] is None else np.concatenate([kv[l][0], k], 0)
+        V = v if kv[l][1] is None else np.concatenate([kv[l][1], v], 0)
+        kv[l] = (K, V)
+        a = _rt(cfg, _attend_rows(q, K, V, pos, H, dh))
+        xres = _qlinear(cfg, a, P.qweight(p + "wo"), bo, residual=xres)
+        if llama:
+            h = _rt(cfg, _rmsnorm(xres, P.plain(p + "ffn_norm")))
+            gate = _qlinear(cfg, h, P.qweight(p + "w_gate"))
+            up = _qlinear(cfg, h, P.qweight(p + "w_up"))
+            g64 = gate.astype(np.float64)
+            act = _rt(cfg, g64 / (1.0 + np.exp(-g64)) * up.astype(np.float64))
+            xres = _qlinear(cfg, act, P.qweight(p + "w_down"), residual=xres)
+        else:
+            h = _rt(cfg, _layernorm(xres, P.plain(p + "ln2_g"), P.plain(p + "ln2_b")))
+            f = _qlinear(cfg, h, P.qweight(p + "fc1"), P.plain(p + "b1"), relu=True)
+            xres = _qlinear(cfg, f, P.qweight(p + "fc2"), P.plain(p + "b2"), residual=xres)
+    if cfg.arch == ARCH_LLAMA:
+        return _rt(cfg, _rmsnorm(xres, P.plain("final_norm"))), P
+    return _rt(cfg, _layernorm(xres, P.plain("final_ln_g"), P.plain("final_ln_b"))), P
+
+
+def new_kv(cfg):
+    return [(None, None) for _ in range(cfg.n_layers)]
+
+
+def infer_prefill(cfg, params, prompt, kv, trainable=None):
+    """Prompt pass of one sequence: fills kv (per layer: keys after the rotary embedding and values of every position, in
+    the activation storage type) and returns the logits (fp64 [V]) of the LAST position -- the distribution of the first
+    generated token."""
+    assert not (cfg.learn_clip or cfg.learn_smooth)
+    prompt = np.asarray(prompt).reshape(-1)
+    hf, P = _infer_rows(cfg, params, prompt, np.arange(prompt.size), kv, trainable)
+    return hf[-1].astype(np.float64) @ P.lm_head("lm_head").astype(np.float64).T
+
+
+def infer_decode(cfg, params, token, kv, trainable=None):
+    """One more token: its position is the current cache length; returns the logits (fp64 [V]) of the token after it."""
+    n = kv[0][0].shape[0]
+    hf, P = _infer_rows(cfg, params, [int(token)], [n], kv, trainable)
+    return hf[0].astype(np.float64) @ P.lm_head("lm_head").astype(np.float64).T
+
+
+def greedy_generate(cfg, params, prompt, n_new, trainable=None):
+    """Greedy decoding: n_new tokens, each the arg max (lowest index on ties) of the previous step's logits.  Returns
+    (tokens int32 [n_new], logits fp64 [n_new][V])."""
+    kv = new_kv(cfg)
+    logits = infer_prefill(cfg, params, prompt, kv, trainable)
+    toks, lgs = [], []
+    for _ in range(n_new):
+        lgs.append(logits)
+        toks.append(int(np.argmax(logits)))
+        if len(toks) < n_new:
+            logits = infer_decode(cfg, params, toks[-1], kv, trainable)
+    return np.array(toks, np.int32), np.stack(lgs)
+
+
 def zo_step(cfg, params, seed, eps, lr, ids=None, x=None, target=None, trainable=None, lr_smooth=None, lr_clip=None,
             stochastic=False):
     """One ZO-SGD step (Eq. 2 with q = 1, then Eq. 3), updating `params` in place.
