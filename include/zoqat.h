@@ -424,6 +424,25 @@ zo_status zo_attention_causal(const void* q_dev, const void* k_dev, const void* 
                               int32_t B, int32_t S, int32_t H, int32_t dh, int64_t row_stride, int32_t dtype,
                               void* scratch_dev, void* hip_stream);
 
+/* ---- the quantized model as a generator (efficiency section, on-device table: inference on the quantized model,
+ * prompts of a few hundred tokens, one token at a time afterwards) ----
+ * The same quantized forward at eps = 0 on ONE sequence, with a key / value cache in caller-owned memory:
+ *   kv_dev  dev, zo_kv_cache_bytes(cfg, kv_max_seq) bytes, 16-byte aligned, layout [n_layers][K | V][kv_max_seq][d_model] in the
+ *           activation storage type; keys are stored after the rotary embedding.  kv_max_seq <= cfg.max_seq.
+ * zo_prefill: rows 0 .. S-1 of the prompt ids_dev (dev int32 [S], S <= max_B * max_S of the context) fill the cache; logits_dev
+ *   (dev fp32 [vocab]) receives the logits of the LAST position (the distribution of the first generated token).
+ * zo_decode: one more token (*token_dev, dev int32 -- typically written by the previous step's arg max) at position pos
+ *   (= number of cached rows): its keys / values are appended, its query attends to rows 0 .. pos; logits_dev as above.
+ * zo_generate_greedy: zo_prefill, then n_new times { tokens_dev[i] = arg max of the logits (lowest index on ties);
+ *   zo_decode(tokens_dev + i, S + i) } -- everything queued on the context's stream, no host round trip between tokens.
+ * Works on any decoder context without learned quantizer tensors; meant for a lightweight context whose quantized linears
+ * are all attached as packed 4-bit codes (zo_attach_frozen_int4), where a decoding step reads 0.5 B per weight. */
+size_t zo_kv_cache_bytes(const zo_config* cfg, int32_t kv_max_seq);
+zo_status zo_prefill(zo_ctx* ctx, const int32_t* ids_dev, int32_t S, void* kv_dev, int32_t kv_max_seq, float* logits_dev);
+zo_status zo_decode(zo_ctx* ctx, const int32_t* token_dev, int32_t pos, void* kv_dev, int32_t kv_max_seq, float* logits_dev);
+zo_status zo_generate_greedy(zo_ctx* ctx, const int32_t* prompt_dev, int32_t S, int32_t n_new, void* kv_dev, int32_t kv_max_seq,
+                             int32_t* tokens_dev, float* logits_dev);
+
 /* Which optional routes the context's last forward (or step) took: an OR of ZO_ROUTE_* bits.  Host function. */
 enum { ZO_ROUTE_FUSED_SMALL_M = 1,    /* linears built from the masters inside the small-M kernel */
        ZO_ROUTE_FUSED_INT4 = 2,       /* frozen linears expanded from their packed codes inside the small-M kernel */

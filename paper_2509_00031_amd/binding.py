@@ -30,7 +30,8 @@ EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "
            "zo_step_multi", "zo_update_multi", "zo_lr_linear_decay", "zo_update_tensor_f16", "zo_master_bytes", "zo_linear_frozen_int4_fused", "zo_linear_frozen_fused_scratch_bytes", "zo_gemm_nt_swiglu", "zo_debug_routes", "zo_gemm_nt_ce", "zo_gemm_nt_ce_scratch_bytes", "zo_profile_begin_mask",
            "zo_gemm_nt_splitk_ranges", "zo_gemm_nt_splitk_scratch_bytes", "zo_gemm_nt_fused_splitk",
            "zo_gemm_nt_splitk_static_max_bytes", "zo_gemm_nt_fused_splitk_static",
-           "zo_linear_mma_scratch_bytes", "zo_linear_fakequant_mma"]
+           "zo_linear_mma_scratch_bytes", "zo_linear_fakequant_mma",
+           "zo_kv_cache_bytes", "zo_prefill", "zo_decode", "zo_generate_greedy"]
 PROF_NAMES = ["gemm", "weight_quant", "act_quant", "attention", "update", "other", "fused_linear", "fused_int4_linear"]
 
 
@@ -100,6 +101,11 @@ _lib.zo_linear_mma_scratch_bytes.argtypes = [_i32, _i32, _i32, _i32, _i32, _i32,
 _lib.zo_linear_mma_scratch_bytes.restype = _sz
 _lib.zo_linear_fakequant_mma.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _u64, _i32, _f32,
                                          _vp, _vp, _vp]
+_lib.zo_kv_cache_bytes.argtypes = [C.POINTER(zo_config), _i32]
+_lib.zo_kv_cache_bytes.restype = _sz
+_lib.zo_prefill.argtypes = [_vp, _vp, _i32, _vp, _i32, _vp]
+_lib.zo_decode.argtypes = [_vp, _vp, _i32, _vp, _i32, _vp]
+_lib.zo_generate_greedy.argtypes = [_vp, _vp, _i32, _i32, _vp, _i32, _vp, _vp]
 _lib.zo_gemm_nt_splitk_ranges.argtypes = [_i32, _i32, _i32, _i32]
 _lib.zo_gemm_nt_splitk_ranges.restype = _i32
 _lib.zo_gemm_nt_splitk_scratch_bytes.argtypes = [_i32, _i32, _i32, _i32]
@@ -223,6 +229,34 @@ class Context:
         _check(_lib.zo_forward_quant(self.handle, _ptr(ids), _ptr(target), B, S, seed, eps_signed, loss.data_ptr()),
                "zo_forward_quant", self.handle)
         return loss
+
+    # ---- generator on the quantized model (the caller owns the cache, the logits and the token buffers) ----
+    def new_kv_cache(self, kv_max_seq):
+        nbytes = int(_lib.zo_kv_cache_bytes(C.byref(self.cfg), kv_max_seq))
+        if nbytes == 0:
+            raise ZoError(1, "zo_kv_cache_bytes")
+        return torch.zeros(nbytes, dtype=torch.uint8, device=self.workspace.device)
+
+    def zo_prefill(self, ids, kv, kv_max_seq, logits=None):
+        if logits is None:
+            logits = torch.empty(self.cfg.vocab, dtype=torch.float32, device=ids.device)
+        _check(_lib.zo_prefill(self.handle, ids.data_ptr(), ids.numel(), kv.data_ptr(), kv_max_seq, logits.data_ptr()), "zo_prefill", self.handle)
+        return logits
+
+    def zo_decode(self, token, pos, kv, kv_max_seq, logits=None):
+        if logits is None:
+            logits = torch.empty(self.cfg.vocab, dtype=torch.float32, device=token.device)
+        _check(_lib.zo_decode(self.handle, token.data_ptr(), pos, kv.data_ptr(), kv_max_seq, logits.data_ptr()), "zo_decode", self.handle)
+        return logits
+
+    def zo_generate_greedy(self, prompt, n_new, kv, kv_max_seq, tokens=None, logits=None):
+        if tokens is None:
+            tokens = torch.zeros(n_new, dtype=torch.int32, device=prompt.device)
+        if logits is None:
+            logits = torch.empty(self.cfg.vocab, dtype=torch.float32, device=prompt.device)
+        _check(_lib.zo_generate_greedy(self.handle, prompt.data_ptr(), prompt.numel(), n_new, kv.data_ptr(), kv_max_seq, tokens.data_ptr(),
+                                       logits.data_ptr()), "zo_generate_greedy", self.handle)
+        return tokens, logits
 
     def zo_step(self, ids, target, B, S, seed, eps, lr, out_dev=None):
         out = out_dev if out_dev is not None else self.out4

@@ -309,6 +309,7 @@ struct fwd {
     uint64_t seed;
     int M, S;
     bool sm_on = false;   // the activation being quantized next is smoothed (set by smooth_prepare)
+    int pos0 = 0;         // generator: position of the first row (rotary angles / learned positions start there)
     // small-M route: the tensors of the next GEMM whose tiles are built inside the fused kernel instead of
     // being written to the operand buffers (all of them or none: eligibility depends on the shared shape only)
     struct pend { int t; int64_t row0; bool quantize; bool packed; };
@@ -594,8 +595,8 @@ struct fwd {
         a.dtype = dt();
         a.swiglu = swiglu ? 1 : 0;
         if (rope) {
-            a.rope_cos = at<float>(c->L.rope_cos);
-            a.rope_sin = at<float>(c->L.rope_sin);
+            a.rope_cos = at<float>(c->L.rope_cos) + (size_t)pos0 * (c->cfg.d_model / c->cfg.n_heads / 2);
+            a.rope_sin = at<float>(c->L.rope_sin) + (size_t)pos0 * (c->cfg.d_model / c->cfg.n_heads / 2);
             a.rope_cols = 2 * c->cfg.d_model;
             a.rope_S = S;
         }
@@ -620,13 +621,19 @@ struct fwd {
 
 #define ZO_TRY(x) do { zo_status s_ = (x); if (s_ != ZO_OK) return s_; } while (0)
 
+// Generator mode (inf != NULL; one sequence, eps = 0, nb = 1): rows are positions pos0 .. pos0 + S - 1; every layer's keys (after
+// the rotary embedding) and values are appended to the cache; with pos0 > 0 (S = 1) the query attends to the cached rows
+// instead of the batch; no loss -- the logits of the LAST row go to logits_out.
+struct infer_opts { char* kv; int kv_max_seq; int pos0; float* logits_out; };
+
 zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int B, int S, uint64_t seed,
-                      float eps, int nb, float* loss_out /* dev fp32[nb] */)
+                      float eps, int nb, float* loss_out /* dev fp32[nb] */, const infer_opts* inf = nullptr)
 {
     const zo_config& cfg = c->cfg;
     using PB = layout::per_branch;
     c->routes = 0;
     fwd F{c, nb, eps, seed, 0, S};
+    if (inf) F.pos0 = inf->pos0;
     const int dt = cfg.act_dtype;
     const size_t ts = zo_tsize(dt);
     if (cfg.arch == ZO_ARCH_LINEAR) {
@@ -698,7 +705,9 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
         prof_scope ps(c, ZO_PROF_OTHER);
         for (int b = 0; b < nb; ++b) {
             const float sgn = (b == 0) ? 1.0f : -1.0f;
-            ZO_HIP(c, zo_launch_embed(ids, c->params[t_tok].ptr, llama ? nullptr : c->params[t_pos].ptr,
+            const char* pos_tab = llama ? nullptr : (const char*)c->params[t_pos].ptr +
+                                                     (size_t)F.pos0 * d * (F.wd() == ZO_W_F16 ? 2 : 4);   // (offset rows: eps = 0 there)
+            ZO_HIP(c, zo_launch_embed(ids, c->params[t_tok].ptr, pos_tab,
                                       F.at(c->L.br[b].x), M, S, d, V, seed, t_tok, llama ? 0 : t_pos,
                                       sgn * F.eps_of(t_tok), llama ? 0.0f : sgn * F.eps_of(t_pos), dt, c->st, F.wd()));
         }
@@ -728,8 +737,21 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
             prof_scope ps(c, ZO_PROF_ATTENTION);
             char* qkv = F.at(c->L.br[b].qkv);
             if (llama && !rope_fused)
-                ZO_HIP(c, zo_launch_rope(qkv, qkv + (size_t)d * ts, F.at<float>(c->L.rope_cos), F.at<float>(c->L.rope_sin),
-                                         M, S, H, dh, 3 * d, dt, c->st));
+                ZO_HIP(c, zo_launch_rope(qkv, qkv + (size_t)d * ts, F.at<float>(c->L.rope_cos) + (size_t)F.pos0 * (dh / 2),
+                                         F.at<float>(c->L.rope_sin) + (size_t)F.pos0 * (dh / 2), M, S, H, dh, 3 * d, dt, c->st));
+            if (inf) {
+                // keys and values of these rows join the cache: [layer][K | V][kv_max_seq][d]
+                char* kc = inf->kv + ((size_t)l * 2) * inf->kv_max_seq * d * ts;
+                char* vc = kc + (size_t)inf->kv_max_seq * d * ts;
+                ZO_HIP(c, hipMemcpy2DAsync(kc + (size_t)inf->pos0 * d * ts, (size_t)d * ts, qkv + (size_t)d * ts, (size_t)3 * d * ts,
+                                           (size_t)d * ts, (size_t)M, hipMemcpyDeviceToDevice, c->st));
+                ZO_HIP(c, hipMemcpy2DAsync(vc + (size_t)inf->pos0 * d * ts, (size_t)d * ts, qkv + (size_t)2 * d * ts, (size_t)3 * d * ts,
+                                           (size_t)d * ts, (size_t)M, hipMemcpyDeviceToDevice, c->st));
+                if (inf->pos0 > 0) {                     // one new query over everything cached so far
+                    ZO_HIP(c, zo_launch_decode_attention(qkv, kc, vc, F.at(c->L.br[b].att), inf->pos0 + 1, H, dh, dt, c->st));
+                    continue;
+                }
+            }
             if (zo_flash_attention_supported(dh, dt))
                 ZO_HIP(c, zo_launch_flash_attention(qkv, qkv + (size_t)d * ts, qkv + (size_t)2 * d * ts, F.at(c->L.br[b].att),
                                                     B, S, H, dh, 3 * d, c->st));
@@ -785,6 +807,20 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
     // ---- head
     ZO_TRY(F.vector(t++, 0));
     if (!llama) ZO_TRY(F.vector(t++, 1));
+    if (inf) {
+        // generator: only the last row is normalised (into row 0 of h) and multiplied with the lm_head; fp32 logits out
+        {
+            prof_scope ps(c, ZO_PROF_OTHER);
+            ZO_HIP(c, zo_launch_norm(F.at(c->L.br[0].x) + (size_t)(M - 1) * d * ts, F.vec(0, 0), llama ? nullptr : F.vec(0, 1),
+                                     F.at(c->L.br[0].h), 1, d, 1e-5f, dt, c->st));
+        }
+        F.M = 1;
+        ZO_TRY(F.weights(t++, 0, false));
+        ZO_TRY(F.gemm(&PB::h, &PB::logits, V, d, false, false, false, true));
+        F.M = M;
+        ZO_HIP(c, hipMemcpyAsync(inf->logits_out, F.at(c->L.br[0].logits), (size_t)V * sizeof(float), hipMemcpyDeviceToDevice, c->st));
+        return ZO_OK;
+    }
     ZO_TRY(F.norm(&PB::x, &PB::h, !llama));
     ZO_TRY(F.weights(t++, 0, false));
     // large bf16 forwards: the logits are never stored, the GEMM's epilogue leaves per-tile (maximum, sum of exponentials)
@@ -971,6 +1007,60 @@ zo_status zo_forward_quant(zo_ctx* ctx, const void* ids, const float* target, in
     if (s != ZO_OK) return s;
     if (!loss_dev) return fail(ctx, ZO_EINVAL, "loss_dev is NULL");
     return run_forward(ctx, ids, target, B, S, seed, eps_signed, 1, loss_dev);
+}
+
+// ---- generator on the quantized model ----
+size_t zo_kv_cache_bytes(const zo_config* cfg, int32_t kv_max_seq)
+{
+    if (!cfg || kv_max_seq <= 0 || cfg->arch == ZO_ARCH_LINEAR || check_config(*cfg) != ZO_OK) return 0;
+    return (size_t)cfg->n_layers * 2 * (size_t)kv_max_seq * (size_t)cfg->d_model * zo_tsize(cfg->act_dtype);
+}
+
+namespace {
+zo_status check_infer(zo_ctx* ctx, const void* ids, int S, int pos0, const void* kv, int kv_max_seq, const float* logits)
+{
+    if (!ctx) return ZO_EINVAL;
+    if (ctx->cfg.arch == ZO_ARCH_LINEAR) return fail(ctx, ZO_EUNSUPPORTED, "the generator needs a decoder");
+    if (ctx->cfg.learn_clip || ctx->cfg.learn_smooth) return fail(ctx, ZO_EUNSUPPORTED, "the generator runs the plain quantizer");
+    if (!ids || !kv || !logits) return fail(ctx, ZO_EINVAL, "NULL argument");
+    if (S < 1 || pos0 < 0 || kv_max_seq < 1) return fail(ctx, ZO_EINVAL, "S, pos, kv_max_seq must be positive");
+    if (kv_max_seq > ctx->cfg.max_seq || pos0 + S > kv_max_seq) return fail(ctx, ZO_ESHAPE, "position beyond the cache / max_seq");
+    if (S > ctx->max_B * ctx->max_S) return fail(ctx, ZO_EWORKSPACE, "prompt longer than the context was created for");
+    if (!aligned16(kv) || !aligned16(logits) || ((uintptr_t)ids & 3)) return fail(ctx, ZO_EALIGN, "kv / logits / ids misaligned");
+    for (size_t i = 0; i < ctx->params.size(); ++i)
+        if (!ctx->params[i].ptr && !ctx->frozen[i].codes) return fail(ctx, ZO_EINVAL, "a tensor has neither fp32 nor packed storage");
+    return ZO_OK;
+}
+}  // namespace
+
+zo_status zo_prefill(zo_ctx* ctx, const int32_t* ids_dev, int32_t S, void* kv_dev, int32_t kv_max_seq, float* logits_dev)
+{
+    zo_status s = check_infer(ctx, ids_dev, S, 0, kv_dev, kv_max_seq, logits_dev);
+    if (s != ZO_OK) return s;
+    const infer_opts inf{(char*)kv_dev, kv_max_seq, 0, logits_dev};
+    return run_forward(ctx, ids_dev, nullptr, 1, S, 0, 0.0f, 1, nullptr, &inf);
+}
+
+zo_status zo_decode(zo_ctx* ctx, const int32_t* token_dev, int32_t pos, void* kv_dev, int32_t kv_max_seq, float* logits_dev)
+{
+    zo_status s = check_infer(ctx, token_dev, 1, pos, kv_dev, kv_max_seq, logits_dev);
+    if (s != ZO_OK) return s;
+    const infer_opts inf{(char*)kv_dev, kv_max_seq, pos, logits_dev};
+    return run_forward(ctx, token_dev, nullptr, 1, 1, 0, 0.0f, 1, nullptr, &inf);
+}
+
+zo_status zo_generate_greedy(zo_ctx* ctx, const int32_t* prompt_dev, int32_t S, int32_t n_new, void* kv_dev, int32_t kv_max_seq,
+                             int32_t* tokens_dev, float* logits_dev)
+{
+    if (!ctx) return ZO_EINVAL;
+    if (!tokens_dev || n_new < 1) return fail(ctx, ZO_EINVAL, "tokens_dev is NULL or n_new < 1");
+    if (S + n_new - 1 > kv_max_seq) return fail(ctx, ZO_ESHAPE, "prompt + generated tokens exceed the cache");
+    zo_status s = zo_prefill(ctx, prompt_dev, S, kv_dev, kv_max_seq, logits_dev);
+    for (int i = 0; s == ZO_OK && i < n_new; ++i) {
+        ZO_HIP(ctx, zo_launch_argmax(logits_dev, ctx->cfg.vocab, tokens_dev + i, ctx->st));
+        if (i + 1 < n_new) s = zo_decode(ctx, tokens_dev + i, S + i, kv_dev, kv_max_seq, logits_dev);
+    }
+    return s;
 }
 
 namespace {

@@ -211,3 +211,9 @@ struct zo_i8_gemm_args {
 };
 hipError_t zo_launch_gemm_i8(const zo_i8_gemm_args& a, int out_f32, hipStream_t st);
 
+// ---- generator on the quantized model (prompt pass + cached decoding) ----------------------------
+// out[h*dh + i] = sum_j softmax_j(q_h . K[j]_h / sqrt(dh)) V[j]_h[i] over the n cached rows (row pitch H*dh); fp32 math
+hipError_t zo_launch_decode_attention(const void* q, const void* Kc, const void* Vc, void* out, int32_t n, int32_t H, int32_t dh,
+                                      int dtype, hipStream_t st);
+hipError_t zo_launch_argmax(const float* logits, int32_t V, int32_t* token, hipStream_t st);
+
