@@ -58,6 +58,12 @@ WORKLOADS = {
                                                 vocab=32000, w_bits=4, w_group=128, a_bits=4, B=1, S=64, lightweight=1),
     "llama13b_lightweight_w4a4_g128_1x32": dict(arch="llama", n_layers=40, d_model=5120, n_heads=40, d_ffn=13824,
                                                 vocab=32000, w_bits=4, w_group=128, a_bits=4, B=1, S=32, lightweight=1),
+    # the trained model as a generator (efficiency section, on-device table: W4A4 inference, 384-token prompts): every quantized
+    # linear stored as packed 4-bit codes, prompt pass over 384 tokens, then greedy decoding token by token
+    "llama13b_w4a4_g128_generate_384": dict(arch="llama", n_layers=40, d_model=5120, n_heads=40, d_ffn=13824, vocab=32000,
+                                            w_bits=4, w_group=128, a_bits=4, B=1, S=384, lightweight=1, generate=64),
+    "llama7b_w4a4_g128_generate_384": dict(arch="llama", n_layers=32, d_model=4096, n_heads=32, d_ffn=11008, vocab=32000,
+                                           w_bits=4, w_group=128, a_bits=4, B=1, S=384, lightweight=1, generate=64),
     "tiny_w4a16_g64_8x128": dict(arch="llama", n_layers=4, d_model=512, n_heads=8, d_ffn=2048, vocab=4096,
                                  w_bits=4, w_group=64, a_bits=16, B=8, S=128),
 }
@@ -138,6 +144,72 @@ def cpu_baseline(w):
                       % (w["B"], w["S"], t_sample, ratio, est)}
 
 
+def bench_generate(args, w):
+    """Prompt pass + greedy decoding on the packed model.  A "step" here is one generated token; value = decoded tokens / s."""
+    import torch
+    from paper_2509_00031_amd import binding as zo
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    S, n_new = w["S"], w["generate"]
+    kv_len = S + n_new
+    cfg = zo.make_config(zo.ARCH_LLAMA, n_layers=w["n_layers"], d_model=w["d_model"], n_heads=w["n_heads"], d_ffn=w["d_ffn"],
+                         vocab=w["vocab"], max_seq=kv_len, w_bits=w["w_bits"], w_group=w["w_group"], a_bits=w["a_bits"],
+                         act_dtype=zo.ACT_BF16, lightweight=1)
+    n = zo.zo_num_params(cfg)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1234)
+    kind = lambda i: (i - 1) % 9 if 1 <= i <= 9 * w["n_layers"] else -1
+    params, code_bytes, other_bytes = [], 0, 0
+    for i in range(n):
+        numel = zo.zo_param_numel(cfg, i)
+        t = torch.empty(numel, dtype=torch.float32, device=dev).normal_(0.0, 0.02, generator=gen)
+        if numel == w["d_model"]:
+            t.add_(1.0)
+        if kind(i) in (1, 2, 3, 4, 6, 7, 8):            # every quantized linear: packed codes + binary16 step + int16 zero point per group
+            K = w["d_ffn"] if kind(i) == 8 else w["d_model"]
+            t = zo.zo_pack_weight_int4(t.view(numel // K, K), w["w_group"])
+            code_bytes += numel // 2 + 4 * (numel // w["w_group"])
+        elif i == n - 1:
+            other_bytes += 4 * numel                     # the lm_head stays fp32 and is read once per token
+        params.append(t)
+    ctx = zo.Context(cfg, params, 1, S, trainable=[False] * n)
+    prompt = torch.randint(0, w["vocab"], (S,), dtype=torch.int32, device=dev, generator=gen)
+    kv = ctx.new_kv_cache(kv_len)
+    tokens = torch.zeros(n_new, dtype=torch.int32, device=dev)
+    logits = torch.empty(w["vocab"], dtype=torch.float32, device=dev)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    for _ in range(max(args.warmup, 1)):
+        ctx.zo_generate_greedy(prompt, n_new, kv, kv_len, tokens, logits)
+    torch.cuda.synchronize()
+    t_pre, t_gen = [], []
+    for _ in range(args.steps):
+        a, b, c_ = ev(), ev(), ev()
+        a.record()
+        ctx.zo_prefill(prompt, kv, kv_len, logits)
+        b.record()
+        ctx.zo_generate_greedy(prompt, n_new, kv, kv_len, tokens, logits)
+        c_.record()
+        torch.cuda.synchronize()
+        t_pre.append(a.elapsed_time(b))
+        t_gen.append(b.elapsed_time(c_))
+    pre_ms = sorted(t_pre)[len(t_pre) // 2]
+    gen_ms = sorted(t_gen)[len(t_gen) // 2]
+    per_tok_ms = (gen_ms - pre_ms) / (n_new - 1)        # n_new - 1 cached steps follow the prompt pass
+    bytes_per_tok = code_bytes + other_bytes
+    ach = bytes_per_tok / (per_tok_ms * 1e-3) / 1e9
+    res = {"metric": "decoded tokens/sec (greedy, batch 1, packed 4-bit model)", "value": 1e3 / per_tok_ms, "unit": "tokens/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": per_tok_ms, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": args.workload, "prompt_tokens": S, "generated_tokens": n_new, "w_bits": w["w_bits"], "w_group": w["w_group"],
+                      "a_bits": w["a_bits"], "first_tokens": tokens[:4].cpu().tolist()},
+           "prefill_ms": pre_ms, "prefill_tokens_per_s": S / (pre_ms * 1e-3),
+           "roofline": {"bound": "hbm", "kernel": "decoding step (packed-codes small-M kernels + lm_head)", "achieved": ach, "peak": PEAK_HBM_GBS,
+                        "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": None, "bytes_per_token": bytes_per_tok,
+                        "codes_bytes_per_token": code_bytes}}
+    ctx.close()
+    print(json.dumps(res))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -165,6 +237,8 @@ def main():
     from paper_2509_00031_amd import binding as zo
 
     w = WORKLOADS[args.workload]
+    if w.get("generate"):
+        return bench_generate(args, w)
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
     arch = zo.ARCH_LLAMA if w["arch"] == "llama" else zo.ARCH_OPT

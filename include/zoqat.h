@@ -355,6 +355,17 @@ zo_status zo_linear_frozen_int4_fused(const void* Xp_dev, const void* Xm_dev, co
                                       const int16_t* zp_dev, const float* bias_dev, void* Yp_dev, void* Ym_dev, int32_t M, int32_t N,
                                       int32_t K, int32_t group, int32_t out_f32, void* scratch_dev, void* hip_stream);
 
+/* The frozen linear for ONE token (the linear of a decoding step of the generator below; Lightweight section: pre-quantized
+ * weights): y[n] = relu?(sum_k x[k] (code[n][k] - zp[n][g]) step[n][g] + bias[n]) + residual[n], reading 0.5 B per weight.
+ *   x dev bf16 [K]; y dev [N] bf16, or fp32 if out_f32; bias dev fp32 [N] or NULL; residual dev bf16 [N] or NULL (may be y)
+ *   N a multiple of 4, K a multiple of 32, group a power of two >= 32 dividing K; otherwise ZO_ESHAPE.
+ * The products x (code - zp) step are formed WITHOUT rounding the de-quantized weight to bf16 first (exact bf16 x integer
+ * products summed in fp32, one multiplication by the step per 32 weights): closer to the quantizer's definition than the
+ * bf16-rounded operand of zo_linear_frozen_int4, from which it differs by at most 2^-9 relative per weight. */
+zo_status zo_linear_frozen_int4_token(const void* x_dev, const void* codes_dev, const void* step_f16_dev, const int16_t* zp_dev,
+                                      const float* bias_dev, const void* residual_dev, int32_t relu, void* y_dev, int32_t N, int32_t K,
+                                      int32_t group, int32_t out_f32, void* hip_stream);
+
 /* Plain GEMM of the path, Y[M][N] = X[M][K] * W[N][K]^T with fp32 accumulation, operands and
  * output in storage type dtype (the contraction every quantized linear runs after both operands
  * have been de-quantized).  Exposed for roofline measurement and parity. */

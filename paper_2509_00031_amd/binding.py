@@ -31,7 +31,7 @@ EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "
            "zo_gemm_nt_splitk_ranges", "zo_gemm_nt_splitk_scratch_bytes", "zo_gemm_nt_fused_splitk",
            "zo_gemm_nt_splitk_static_max_bytes", "zo_gemm_nt_fused_splitk_static",
            "zo_linear_mma_scratch_bytes", "zo_linear_fakequant_mma",
-           "zo_kv_cache_bytes", "zo_prefill", "zo_decode", "zo_generate_greedy"]
+           "zo_kv_cache_bytes", "zo_prefill", "zo_decode", "zo_generate_greedy", "zo_linear_frozen_int4_token"]
 PROF_NAMES = ["gemm", "weight_quant", "act_quant", "attention", "update", "other", "fused_linear", "fused_int4_linear"]
 
 
@@ -101,6 +101,7 @@ _lib.zo_linear_mma_scratch_bytes.argtypes = [_i32, _i32, _i32, _i32, _i32, _i32,
 _lib.zo_linear_mma_scratch_bytes.restype = _sz
 _lib.zo_linear_fakequant_mma.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _u64, _i32, _f32,
                                          _vp, _vp, _vp]
+_lib.zo_linear_frozen_int4_token.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _i32, _i32, _i32, _i32, _vp]
 _lib.zo_kv_cache_bytes.argtypes = [C.POINTER(zo_config), _i32]
 _lib.zo_kv_cache_bytes.restype = _sz
 _lib.zo_prefill.argtypes = [_vp, _vp, _i32, _vp, _i32, _vp]
@@ -521,6 +522,14 @@ def zo_gemm_nt_fused_splitk(X, W, bias=None, residual=None, relu=False, Y=None):
     _check(_lib.zo_gemm_nt_fused_splitk(X.data_ptr(), W.data_ptr(), _ptr(bias), _ptr(residual), int(relu), Y.data_ptr(), M, N, K, dtype,
                                         scratch.data_ptr(), nbytes, _stream()), "zo_gemm_nt_fused_splitk")
     return Y
+
+
+def zo_linear_frozen_int4_token(x, packed, bias=None, residual=None, relu=False, out_f32=False):
+    y = torch.empty(packed.N, dtype=torch.float32 if out_f32 else torch.bfloat16, device=x.device)
+    _check(_lib.zo_linear_frozen_int4_token(x.data_ptr(), packed.codes.data_ptr(), packed.step_f16.data_ptr(), packed.zp.data_ptr(),
+                                            _ptr(bias), _ptr(residual), int(relu), y.data_ptr(), packed.N, packed.K, packed.group,
+                                            int(out_f32), _stream()), "zo_linear_frozen_int4_token")
+    return y
 
 
 MMA_BF16, MMA_INT8 = 0, 1

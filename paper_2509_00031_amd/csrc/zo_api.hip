@@ -502,8 +502,13 @@ struct fwd {
             for (int i = 0; i < npend; ++i) any_packed = any_packed || pending[i].packed;
             // both branches' copies sit side by side in the FIRST operand buffer; the second one stays free for the fp32
             // partial sums of the packed-codes kernel's K split
+            // one token, one branch (a decoding step): packed tensors take the matrix-vector kernel, which reads X as it lies
+            bool all_gemv = true;
+            for (int i = 0; i < npend; ++i)
+                all_gemv = all_gemv && pending[i].packed &&
+                           zo_int4_gemv_supported(M, nb, (int)c->desc[pending[i].t].rows, K, c->frozen[pending[i].t].group);
             const size_t rl_bytes = align_up(zo_fused_relayout_bytes(M, K));
-            const bool relayout = (M > 32 || any_packed) && 2 * rl_bytes <= c->L.what_bytes;
+            const bool relayout = (M > 32 || (any_packed && !all_gemv)) && 2 * rl_bytes <= c->L.what_bytes;
             const int64_t sxf = (int64_t)(rl_bytes / 2);
             if (relayout) {
                 prof_scope ps(c, ZO_PROF_OTHER);
@@ -541,6 +546,10 @@ struct fwd {
                 if (pe.packed) {
                     const zo_ctx::frozen_int4& fz = c->frozen[pe.t];
                     f.codes = fz.codes; f.step16 = fz.step; f.zp = fz.zp; f.group = fz.group;
+                    if (zo_int4_gemv_supported(M, nb, f.N, K, f.group)) {
+                        ZO_HIP(c, zo_launch_int4_gemv(f, c->st));
+                        continue;
+                    }
                     // split-K form when its partial sums fit into the second (idle) operand buffer
                     if (relayout && zo_int4_splitk_scratch_bytes(M, f.N, K, f.group) <= c->L.what_bytes)
                         ZO_HIP(c, zo_launch_int4_gemm_splitk(f, at(c->L.what[1]), c->st));
@@ -1548,6 +1557,21 @@ zo_status zo_linear_frozen_int4_fused(const void* Xp_dev, const void* Xm_dev, co
         return zo_launch_int4_gemm_splitk(f, partials, (hipStream_t)hip_stream) == hipSuccess ? ZO_OK : ZO_EHIP;
     }
     return zo_launch_int4_gemm_fused(f, (hipStream_t)hip_stream) == hipSuccess ? ZO_OK : ZO_EHIP;
+}
+
+zo_status zo_linear_frozen_int4_token(const void* x_dev, const void* codes_dev, const void* step_f16_dev, const int16_t* zp_dev,
+                                      const float* bias_dev, const void* residual_dev, int32_t relu, void* y_dev, int32_t N, int32_t K,
+                                      int32_t group, int32_t out_f32, void* hip_stream)
+{
+    if (!x_dev || !codes_dev || !step_f16_dev || !zp_dev || !y_dev || N <= 0 || K <= 0) return ZO_EINVAL;
+    if (!zo_int4_gemv_supported(1, 1, N, K, group)) return ZO_ESHAPE;
+    if (!aligned16(x_dev) || !aligned16(codes_dev) || ((uintptr_t)step_f16_dev & 1) || ((uintptr_t)zp_dev & 1) || ((uintptr_t)bias_dev & 3) ||
+        ((uintptr_t)residual_dev & 1) || ((uintptr_t)y_dev & 3))
+        return ZO_EALIGN;
+    zo_fused_args f{};
+    f.X = x_dev; f.codes = codes_dev; f.step16 = step_f16_dev; f.zp = zp_dev; f.Y = y_dev; f.bias = bias_dev; f.residual = residual_dev;
+    f.M = 1; f.N = N; f.K = K; f.nb = 1; f.ldY = N; f.group = group; f.bits = 4; f.relu = relu ? 1 : 0; f.out_f32 = out_f32 ? 1 : 0;
+    return zo_launch_int4_gemv(f, (hipStream_t)hip_stream) == hipSuccess ? ZO_OK : ZO_EHIP;
 }
 
 size_t zo_linear_frozen_fused_scratch_bytes(int32_t M, int32_t N, int32_t K, int32_t group)

@@ -216,4 +216,7 @@ hipError_t zo_launch_gemm_i8(const zo_i8_gemm_args& a, int out_f32, hipStream_t 
 hipError_t zo_launch_decode_attention(const void* q, const void* Kc, const void* Vc, void* out, int32_t n, int32_t H, int32_t dh,
                                       int dtype, hipStream_t st);
 hipError_t zo_launch_argmax(const float* logits, int32_t V, int32_t* token, hipStream_t st);
+// frozen (packed 4-bit) linear of ONE token (M = 1, one branch): a.X bf16 [K], a.Y [N] (bf16, or fp32 with out_f32), 0.5 B per weight
+bool zo_int4_gemv_supported(int32_t M, int32_t nb, int32_t N, int32_t K, int32_t group);
+hipError_t zo_launch_int4_gemv(const zo_fused_args& a, hipStream_t st);
 

@@ -250,3 +250,30 @@ def test_lightweight_small_batch_two_packed_tensors_with_k_split(S):
     for out in outs:
         assert abs(out[0] - lp) <= 2e-3 * abs(lp) and abs(out[1] - lm) <= 2e-3 * abs(lm), (out, lp, lm)
     assert np.allclose(outs[0][:2], outs[1][:2], rtol=1e-3)
+
+
+@pytest.mark.parametrize("N,K,group", [(16, 128, 128), (4, 32, 32), (260, 4096, 64), (1024, 11008, 128), (512, 5120, 512), (64, 13824, 128)])
+def test_frozen_linear_for_one_token(N, K, group):
+    """The matrix-vector kernel of a decoding step against the definition sum_k x (code - zp) step on UN-rounded
+    de-quantized weights (fp64), to the fp32 accumulation bound; K spans fewer chunks than lanes, a ragged number of
+    chunks, and several sweeps; with bias, ReLU and residual; an all-positive channel (zero point below zero)."""
+    torch, zo = gpu()
+    x = orc.bf16_round(synth.activations((1, K), 520))
+    W = synth.weights((N, K), 521)
+    W[1] = np.abs(W[1]) + 0.5
+    bias = synth.weights((N,), 522)
+    res = orc.bf16_round(synth.activations((1, N), 523))[0]
+    ref_p = orc.pack_int4(W, group)
+    what = orc.dequant_int4(ref_p, round_bf16=False)
+    packed = _packed(zo, torch, ref_p, N, K, group)
+    xd = to_dev(x[0], torch, torch.bfloat16)
+    mag = np.abs(x.astype(np.float64)) @ np.abs(what.astype(np.float64)).T
+    plain = orc.linear(x, what)[0]
+    got = zo.zo_linear_frozen_int4_token(xd, packed, out_f32=True).cpu().numpy()
+    # the kernel sums x (128 + code) and removes (128 + zp) sum x afterwards: the bound carries that magnitude
+    step = ref_p.step_f16.view(np.float16).astype(np.float64)
+    big = np.abs(x.astype(np.float64)).sum() * (128.0 + np.abs(ref_p.zp).max() + 15.0) * step.max()
+    assert np.all(np.abs(got - plain) <= 2.0 ** -20 * (mag[0] + big)), np.abs(got - plain).max()
+    full = np.maximum(plain + bias, 0.0) + res
+    got = zo.zo_linear_frozen_int4_token(xd, packed, bias=to_dev(bias, torch), residual=to_dev(res, torch, torch.bfloat16), relu=True).float().cpu().numpy()
+    assert np.all(np.abs(got - full) <= 2.0 ** -8 * np.abs(full) + 2.0 ** -20 * (mag[0] + big) + 1e-6)
