@@ -310,6 +310,7 @@ struct fwd {
     int M, S;
     bool sm_on = false;   // the activation being quantized next is smoothed (set by smooth_prepare)
     int pos0 = 0;         // generator: position of the first row (rotary angles / learned positions start there)
+    float* alias[2] = {nullptr, nullptr};   // vector slots 0 / 1 served straight from an un-perturbed fp32 master (see vector())
     // small-M route: the tensors of the next GEMM whose tiles are built inside the fused kernel instead of
     // being written to the operand buffers (all of them or none: eligibility depends on the shared shape only)
     struct pend { int t; int64_t row0; bool quantize; bool packed; };
@@ -432,6 +433,11 @@ struct fwd {
     zo_status vector(int t, int slot, int64_t o = 0)
     {
         const param_desc& p = c->desc[t];
+        // a norm gain / bias that is not perturbed (frozen tensor, or eps = 0) and lies in fp32 is read where it is
+        if (slot < 2) {
+            alias[slot] = (o == 0 && eps_of(t) == 0.0f && wd() == ZO_W_F32) ? (float*)c->params[t].ptr : nullptr;
+            if (alias[slot]) return ZO_OK;
+        }
         float* op = at<float>(c->L.vec[0]) + slot * c->L.vec_stride + o;
         float* om = nb == 2 ? at<float>(c->L.vec[1]) + slot * c->L.vec_stride + o : nullptr;
         prof_scope ps(c, ZO_PROF_WEIGHT_QUANT);
@@ -439,7 +445,11 @@ struct fwd {
                                       op, om, nullptr, nullptr, nullptr, c->st, wd()));
         return ZO_OK;
     }
-    float* vec(int b, int slot) const { return at<float>(c->L.vec[b]) + slot * c->L.vec_stride; }
+    float* vec(int b, int slot) const
+    {
+        if (slot < 2 && alias[slot]) return alias[slot];
+        return at<float>(c->L.vec[b]) + slot * c->L.vec_stride;
+    }
 
     zo_status norm(size_t layout::per_branch::*in, size_t layout::per_branch::*out, bool has_beta)
     {

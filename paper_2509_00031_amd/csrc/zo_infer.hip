@@ -3,40 +3,41 @@
 #include "zo_device.h"
 #include "zo_internal.h"
 
-// One workgroup per head.  scores[j] = q . K[j] / sqrt(dh) for the n cached positions (a thread per key, strided), a
-// numerically safe softmax in fp32 (fixed-order reductions: lanes, then the four waves in order), then
-// out[i] = sum_j p_j V[j][i] with the keys dealt to 256 / dh thread groups whose partial sums are added in group order.
-template <typename T>
+// One workgroup per head, dh / 8 lanes per cached row (each lane owns 8 consecutive dimensions: one 16-byte load per row).
+// scores[j] = q . K[j] / sqrt(dh): partial dot products of the lanes of a row are added with register-to-register
+// exchanges; a numerically safe softmax in fp32 (fixed-order reductions); out = sum_j p_j V[j]: the 256 / (dh / 8) row
+// groups accumulate their rows j = group, group + groups, ... and their partial sums are added in group order through
+// LDS.  The row loops are unrolled so that several 16-byte loads are in flight per lane.
+template <typename T, int LPK>
 __global__ __launch_bounds__(256) void zo_decode_attention_kernel(const T* __restrict__ q, const T* __restrict__ Kc, const T* __restrict__ Vc,
-                                                                  T* __restrict__ out, int n, int d, int dh, float scale)
+                                                                  T* __restrict__ out, int n, int d, float scale)
 {
-    extern __shared__ float sm[];                     // [n] scores, then [dh] query, then [256] reduction scratch
+    constexpr int DH = LPK * 8, KG = 256 / LPK;
+    extern __shared__ float sm[];                     // [n] scores, [8] wave results, [KG][DH] partial outputs
     float* sc = sm;
-    float* qs = sm + n;
-    float* red = qs + dh;
+    float* red = sm + n;
+    float* part = red + 8;
     const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t hoff = (int64_t)h * dh;
-    for (int i = tid; i < dh; i += 256) qs[i] = zo_load(q + hoff + i);
-    __syncthreads();
+    const int sub = tid % LPK, kg = tid / LPK;
+    const int64_t hoff = (int64_t)h * DH + sub * 8;
+    float qv[8];
+    zo_load8(q + hoff, qv);
     float mx = -INFINITY;
-    for (int j = tid; j < n; j += 256) {
-        const T* kr = Kc + (int64_t)j * d + hoff;
+#pragma unroll 4
+    for (int j = kg; j < n; j += KG) {
+        float v[8];
+        zo_load8(Kc + (int64_t)j * d + hoff, v);
         float acc = 0.0f;
-        for (int i = 0; i < dh; i += 8) {
-            float v[8];
-            zo_load8(kr + i, v);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc = __builtin_fmaf(v[e], qs[i + e], acc);
-        }
-        acc *= scale;
-        sc[j] = acc;
+        for (int e = 0; e < 8; ++e) acc = __builtin_fmaf(v[e], qv[e], acc);
+        acc = zo_group_sum<LPK>(acc) * scale;
+        if (sub == 0) sc[j] = acc;
         mx = fmaxf(mx, acc);
     }
     mx = zo_group_max<64>(mx);
     if (lane == 0) red[wave] = mx;
     __syncthreads();
     mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-    __syncthreads();
     float sum = 0.0f;
     for (int j = tid; j < n; j += 256) {
         const float p = __expf(sc[j] - mx);
@@ -44,44 +45,62 @@ __global__ __launch_bounds__(256) void zo_decode_attention_kernel(const T* __res
         sum += p;
     }
     sum = zo_group_sum<64>(sum);
-    if (lane == 0) red[wave] = sum;
+    if (lane == 0) red[4 + wave] = sum;
     __syncthreads();
-    sum = ((red[0] + red[1]) + red[2]) + red[3];
-    __syncthreads();
-    const int parts = 256 / dh, i = tid % dh, part = tid / dh;      // dh in {16, 32, 64, 128}
-    float o = 0.0f;
-    for (int j = part; j < n; j += parts) o = __builtin_fmaf(sc[j], zo_load(Vc + (int64_t)j * d + hoff + i), o);
-    red[tid] = o;
-    __syncthreads();
-    if (tid < dh) {
-        float t = red[tid];
-        for (int p2 = 1; p2 < parts; ++p2) t += red[p2 * dh + tid];
-        zo_store(out + hoff + tid, t / sum);
+    sum = ((red[4] + red[5]) + red[6]) + red[7];
+    float o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = 0.0f;
+#pragma unroll 4
+    for (int j = kg; j < n; j += KG) {
+        float v[8];
+        zo_load8(Vc + (int64_t)j * d + hoff, v);
+        const float p = sc[j];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = __builtin_fmaf(p, v[e], o[e]);
     }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) part[kg * DH + sub * 8 + e] = o[e];
+    __syncthreads();
+    if (tid < DH) {
+        float t = part[tid];
+        for (int g = 1; g < KG; ++g) t += part[g * DH + tid];
+        zo_store(out + (int64_t)h * DH + tid, t / sum);
+    }
+}
+
+template <typename T>
+static hipError_t launch_decode_attention_t(const T* q, const T* Kc, const T* Vc, T* out, int n, int H, int dh, hipStream_t st)
+{
+    const int d = H * dh;
+    const size_t lds = ((size_t)n + 8 + 2048) * sizeof(float);
+    if (lds > 160 * 1024) return hipErrorInvalidValue;
+    const float scale = 1.0f / sqrtf((float)dh);
+#define ZO_DEC_ATT(L)                                                                                                              \
+    do {                                                                                                                           \
+        if (lds > 64 * 1024) {                                                                                                     \
+            hipError_t e = hipFuncSetAttribute((const void*)zo_decode_attention_kernel<T, L>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+            if (e != hipSuccess) return e;                                                                                         \
+        }                                                                                                                          \
+        zo_decode_attention_kernel<T, L><<<H, 256, lds, st>>>(q, Kc, Vc, out, n, d, scale);                                        \
+    } while (0)
+    switch (dh) {
+        case 16:  ZO_DEC_ATT(2); break;
+        case 32:  ZO_DEC_ATT(4); break;
+        case 64:  ZO_DEC_ATT(8); break;
+        default:  ZO_DEC_ATT(16); break;
+    }
+#undef ZO_DEC_ATT
+    return hipGetLastError();
 }
 
 hipError_t zo_launch_decode_attention(const void* q, const void* Kc, const void* Vc, void* out, int32_t n, int32_t H, int32_t dh,
                                       int dtype, hipStream_t st)
 {
     if (n <= 0 || H <= 0 || (dh != 16 && dh != 32 && dh != 64 && dh != 128)) return hipErrorInvalidValue;
-    const int d = H * dh;
-    const size_t lds = ((size_t)n + dh + 256) * sizeof(float);
-    if (lds > 160 * 1024) return hipErrorInvalidValue;
-    const float scale = 1.0f / sqrtf((float)dh);
-    if (dtype == ZO_T_BF16) {
-        if (lds > 64 * 1024) {
-            hipError_t e = hipFuncSetAttribute((const void*)zo_decode_attention_kernel<zo_bf16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-        }
-        zo_decode_attention_kernel<zo_bf16><<<H, 256, lds, st>>>((const zo_bf16*)q, (const zo_bf16*)Kc, (const zo_bf16*)Vc, (zo_bf16*)out, n, d, dh, scale);
-    } else {
-        if (lds > 64 * 1024) {
-            hipError_t e = hipFuncSetAttribute((const void*)zo_decode_attention_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-        }
-        zo_decode_attention_kernel<float><<<H, 256, lds, st>>>((const float*)q, (const float*)Kc, (const float*)Vc, (float*)out, n, d, dh, scale);
-    }
-    return hipGetLastError();
+    if (dtype == ZO_T_BF16)
+        return launch_decode_attention_t<zo_bf16>((const zo_bf16*)q, (const zo_bf16*)Kc, (const zo_bf16*)Vc, (zo_bf16*)out, n, H, dh, st);
+    return launch_decode_attention_t<float>((const float*)q, (const float*)Kc, (const float*)Vc, (float*)out, n, H, dh, st);
 }
 
 // token = lowest index of the largest logit (NaNs never win).  One workgroup.
