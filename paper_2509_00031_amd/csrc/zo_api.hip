@@ -515,7 +515,7 @@ struct fwd {
             // one token, one branch (a decoding step): packed tensors take the matrix-vector kernel, which reads X as it lies
             bool all_gemv = true;
             for (int i = 0; i < npend; ++i)
-                all_gemv = all_gemv && pending[i].packed &&
+                all_gemv = all_gemv && pending[i].packed && c->frozen[pending[i].t].group == c->frozen[pending[0].t].group &&
                            zo_int4_gemv_supported(M, nb, (int)c->desc[pending[i].t].rows, K, c->frozen[pending[i].t].group);
             const size_t rl_bytes = align_up(zo_fused_relayout_bytes(M, K));
             const bool relayout = (M > 32 || (any_packed && !all_gemv)) && 2 * rl_bytes <= c->L.what_bytes;
@@ -526,6 +526,28 @@ struct fwd {
                                                    nb, pending[0].quantize ? c->cfg.w_bits : 0, c->cfg.w_group, at(c->L.what[0]), sxf, c->st));
             }
             bool launched[4] = {false, false, false, false};
+            if (all_gemv) {
+                // a decoding step: every tensor of this GEMM is a packed matrix applied to the one token -- one launch for all
+                zo_fused_args fa[4];
+                for (int i = 0; i < npend; ++i) {
+                    const pend& pe = pending[i];
+                    const zo_ctx::frozen_int4& fz = c->frozen[pe.t];
+                    zo_fused_args f{};
+                    f.X = at(c->L.br[0].*in);
+                    f.Y = at(c->L.br[0].*out) + (size_t)pe.row0 * (out_f32 ? 4 : ts_);
+                    f.bias = bias ? vec(0, 2) + pe.row0 : nullptr;
+                    f.residual = residual ? f.Y : nullptr;
+                    f.M = M; f.N = (int)c->desc[pe.t].rows; f.K = K; f.nb = nb; f.ldY = N;
+                    f.codes = fz.codes; f.step16 = fz.step; f.zp = fz.zp; f.group = fz.group;
+                    f.relu = relu; f.out_f32 = out_f32;
+                    fa[i] = f;
+                }
+                c->routes |= ZO_ROUTE_FUSED_INT4;
+                prof_scope ps(c, ZO_PROF_FUSED_INT4);
+                ZO_HIP(c, zo_launch_int4_gemv_multi(fa, npend, c->st));
+                npend = 0;
+                return ZO_OK;
+            }
             for (int i = 0; i < npend; ++i) {
                 if (launched[i]) continue;
                 const pend& pe = pending[i];

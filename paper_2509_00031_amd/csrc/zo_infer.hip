@@ -155,18 +155,39 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c)
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
 }
 
+// Up to four tensors that read the same token (query | key | value, gate | up) share one launch: tensor i owns the
+// workgroups [wg_end[i-1], wg_end[i]).
+struct zo_gemv_multi {
+    int32_t nt;
+    const void* codes[4]; const void* step16[4]; const int16_t* zp[4];
+    void* Y[4]; const float* bias[4]; const void* residual[4];
+    int32_t wg_end[4];
+    const void* X;
+    int32_t K, group, relu;
+};
+
 template <typename TY>
-__global__ __launch_bounds__(128) void zo_int4_gemv_kernel(zo_fused_args a)
+__global__ __launch_bounds__(128) void zo_int4_gemv_kernel(zo_gemv_multi mt)
 {
     constexpr int R = 4;
     __shared__ float red[R];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int n0 = blockIdx.x * R;
-    const int K = a.K, G = K / a.group, gshift = __builtin_ctz(a.group);
+    int ti = 0, wg0 = 0;
+#pragma unroll
+    for (int i = 1; i < 4; ++i)
+        if (i < mt.nt && (int)blockIdx.x >= mt.wg_end[i - 1]) { ti = i; wg0 = mt.wg_end[i - 1]; }
+    struct { const void* codes; const void* step16; const int16_t* zp; void* Y; const float* bias; const void* residual; int relu; } a;
+    a.codes = mt.codes[0]; a.step16 = mt.step16[0]; a.zp = mt.zp[0]; a.Y = mt.Y[0]; a.bias = mt.bias[0]; a.residual = mt.residual[0];
+#pragma unroll
+    for (int i = 1; i < 4; ++i)
+        if (ti == i) { a.codes = mt.codes[i]; a.step16 = mt.step16[i]; a.zp = mt.zp[i]; a.Y = mt.Y[i]; a.bias = mt.bias[i]; a.residual = mt.residual[i]; }
+    a.relu = mt.relu;
+    const int n0 = ((int)blockIdx.x - wg0) * R;
+    const int K = mt.K, G = K / mt.group, gshift = __builtin_ctz(mt.group);
     const int chunks = K >> 5;
     const uint8_t* codes = (const uint8_t*)a.codes;
     const _Float16* step16 = (const _Float16*)a.step16;
-    const uint4* xv = (const uint4*)a.X;
+    const uint4* xv = (const uint4*)mt.X;
     float acc[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) acc[r] = 0.0f;
@@ -225,10 +246,25 @@ bool zo_int4_gemv_supported(int32_t M, int32_t nb, int32_t N, int32_t K, int32_t
     return M == 1 && nb == 1 && N >= 4 && (N & 3) == 0 && K >= 32 && (K & 31) == 0 && group >= 32 && (group & (group - 1)) == 0 && K % group == 0;
 }
 
-hipError_t zo_launch_int4_gemv(const zo_fused_args& a, hipStream_t st)
+hipError_t zo_launch_int4_gemv_multi(const zo_fused_args* t, int nt, hipStream_t st)
 {
-    if (!zo_int4_gemv_supported(a.M, a.nb, a.N, a.K, a.group) || !a.codes || !a.step16 || !a.zp || !a.X || !a.Y) return hipErrorInvalidValue;
-    if (a.out_f32) zo_int4_gemv_kernel<float><<<a.N / 4, 128, 0, st>>>(a);
-    else zo_int4_gemv_kernel<zo_bf16><<<a.N / 4, 128, 0, st>>>(a);
+    if (nt < 1 || nt > 4) return hipErrorInvalidValue;
+    zo_gemv_multi mt{};
+    mt.nt = nt;
+    int wgs = 0;
+    for (int i = 0; i < nt; ++i) {
+        const zo_fused_args& a = t[i];
+        if (!zo_int4_gemv_supported(a.M, a.nb, a.N, a.K, a.group) || !a.codes || !a.step16 || !a.zp || !a.X || !a.Y) return hipErrorInvalidValue;
+        if (a.K != t[0].K || a.group != t[0].group || a.X != t[0].X || a.relu != t[0].relu || a.out_f32 != t[0].out_f32) return hipErrorInvalidValue;
+        mt.codes[i] = a.codes; mt.step16[i] = a.step16; mt.zp[i] = a.zp; mt.Y[i] = a.Y; mt.bias[i] = a.bias; mt.residual[i] = a.residual;
+        wgs += a.N / 4;
+        mt.wg_end[i] = wgs;
+    }
+    for (int i = nt; i < 4; ++i) mt.wg_end[i] = wgs;
+    mt.X = t[0].X; mt.K = t[0].K; mt.group = t[0].group; mt.relu = t[0].relu;
+    if (t[0].out_f32) zo_int4_gemv_kernel<float><<<wgs, 128, 0, st>>>(mt);
+    else zo_int4_gemv_kernel<zo_bf16><<<wgs, 128, 0, st>>>(mt);
     return hipGetLastError();
 }
+
+hipError_t zo_launch_int4_gemv(const zo_fused_args& a, hipStream_t st) { return zo_launch_int4_gemv_multi(&a, 1, st); }

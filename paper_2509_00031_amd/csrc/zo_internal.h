@@ -219,4 +219,6 @@ hipError_t zo_launch_argmax(const float* logits, int32_t V, int32_t* token, hipS
 // frozen (packed 4-bit) linear of ONE token (M = 1, one branch): a.X bf16 [K], a.Y [N] (bf16, or fp32 with out_f32), 0.5 B per weight
 bool zo_int4_gemv_supported(int32_t M, int32_t nb, int32_t N, int32_t K, int32_t group);
 hipError_t zo_launch_int4_gemv(const zo_fused_args& a, hipStream_t st);
+// the same for up to four tensors that read the same token (same X, K, group, epilogue flags) in one launch
+hipError_t zo_launch_int4_gemv_multi(const zo_fused_args* t, int nt, hipStream_t st);
 
