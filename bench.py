@@ -88,9 +88,9 @@ PEAK_HBM_GBS = 8000.0
 # plain vector ALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions per second (the fp32 vector peak of
 # 157.3 TFLOP/s counts 2 flops per FMA and the packed two-per-lane forms, which this build does not use)
 PEAK_ALU_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
-# lane-instructions of the fused kernel's tile build per parameter, counted in its ISA (w4 g64 variant, two m-tiles: 523 for
-# the perturbation stream + 16 for W +- eps u + 179 + 210 for the two branches + 8 matrix instructions, per 16 parameters)
-FUSED_LANEOPS_PER_PARAM = 936 / 16.0
+# lane-instructions of the fused small-M kernel per parameter: SQ_INSTS_VALU of a rocprofv3 counter pass over the 1 x 32 workload
+# (profiles/zo_step_llama7b_w4a8_1x32_fused_kernel_valu.txt: 3.8297e7 wave-instructions x 64 lanes / 4.0475e7 parameters per launch)
+FUSED_LANEOPS_PER_PARAM = 60.6
 
 
 def gemm_flops_per_step(w):
