@@ -774,7 +774,11 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
         const bool rope_fused = llama && F.rope_in_gemm(t);      // head blocks permuted in the operand, rotation in the epilogue
         for (int i = 0; i < 3; ++i) ZO_TRY(linear((int64_t)i * d, sh, rope_fused ? 3 : 0));
         ZO_TRY(F.gemm(xin, &PB::qkv, 3 * d, d, bias, false, false, false, sh, false, rope_fused));
-        for (int b = 0; b < nb; ++b) {
+        // a decoding step (one new row, rows cached before it): rotation, cache append, attention over key ranges and the
+        // per-token quantizer of the attention output run in two launches further down
+        const bool dec_split = inf && inf->pos0 > 0 && M == 1 && zo_decode_attention_split_supported(H, dh) &&
+                               zo_decode_attention_split_bytes(inf->pos0 + 1, H, dh) <= c->L.what_bytes;
+        for (int b = 0; b < nb && !dec_split; ++b) {
             prof_scope ps(c, ZO_PROF_ATTENTION);
             char* qkv = F.at(c->L.br[b].qkv);
             if (llama && !rope_fused)
@@ -801,7 +805,20 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
                                               B, S, H, dh, 3 * d, dt, c->st));
         }
         ZO_TRY(F.smooth_prepare(t));                     // wo
-        ZO_TRY(F.act_quant(&PB::att, d, &xin));
+        if (dec_split) {
+            prof_scope ps(c, ZO_PROF_ATTENTION);
+            char* kc = inf->kv + ((size_t)l * 2) * inf->kv_max_seq * d * ts;
+            char* vc = kc + (size_t)inf->kv_max_seq * d * ts;
+            const bool aq = cfg.a_bits < 16;
+            ZO_HIP(c, zo_launch_decode_attention_split(F.at(c->L.br[0].qkv), kc, vc,
+                                                       llama ? F.at<float>(c->L.rope_cos) + (size_t)inf->pos0 * (dh / 2) : nullptr,
+                                                       llama ? F.at<float>(c->L.rope_sin) + (size_t)inf->pos0 * (dh / 2) : nullptr,
+                                                       F.at(c->L.what[1]), F.at(c->L.br[0].att), aq ? F.at(c->L.br[0].hq) : nullptr,
+                                                       inf->pos0 + 1, H, dh, cfg.a_bits, cfg.a_sym, F.sm_delta(0), F.sm_inv(0), dt, c->st));
+            xin = aq ? &PB::hq : &PB::att;
+        } else {
+            ZO_TRY(F.act_quant(&PB::att, d, &xin));
+        }
         sh = F.frozen(t);
         ZO_TRY(linear(0, sh));
         ZO_TRY(F.gemm(xin, &PB::x, d, d, bias, false, true, false, sh));

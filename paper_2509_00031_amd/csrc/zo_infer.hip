@@ -103,6 +103,273 @@ hipError_t zo_launch_decode_attention(const void* q, const void* Kc, const void*
     return launch_decode_attention_t<float>((const float*)q, (const float*)Kc, (const float*)Vc, (float*)out, n, H, dh, st);
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same attention in two launches that fill the chip and do the bookkeeping of a decoding step on the way.
+// Launch 1, one workgroup per (range of cached rows, head): the new row's query and key are rotated here (same
+// arithmetic and rounding as the stand-alone rotary kernel; ROPE = false for learned positions), the workgroup of the last
+// range appends the new key / value row to the cache and attends to it from registers; every row group runs a streaming
+// softmax over its rows (four rows' loads in flight), the groups are merged in group order, and the workgroup leaves
+// (maximum, sum of exponentials, un-normalised output) of its range.  Launch 2, one workgroup: merges the ranges of every
+// head in range order, rounds the attention output to the storage type, and -- the row now sitting in registers --
+// applies the per-token quantizer of the attention-output projection's input (same arithmetic as the stand-alone one).
+// ---------------------------------------------------------------------------------------------
+template <typename T, int LPK, bool ROPE>
+__global__ __launch_bounds__(256) void zo_decode_attn_part_kernel(const T* __restrict__ qkv, T* __restrict__ Kc, T* __restrict__ Vc,
+                                                                  const float* __restrict__ cosr, const float* __restrict__ sinr,
+                                                                  float* __restrict__ po, float* __restrict__ ml, int n, int d, int rps,
+                                                                  float scale)
+{
+    constexpr int DH = LPK * 8, KG = 256 / LPK, HL = LPK / 2;
+    __shared__ float gm[KG], gl[KG];
+    __shared__ float part[KG * DH];
+    const int s = blockIdx.x, KS = gridDim.x, h = blockIdx.y, tid = threadIdx.x;
+    const int sub = tid % LPK, kg = tid / LPK;
+    const int64_t hbase = (int64_t)h * DH, hoff = hbase + sub * 8;
+    float cs[8], sn[8];
+    const bool first = sub < HL;
+    if (ROPE) {
+        zo_load8(cosr + (sub % HL) * 8, cs);
+        zo_load8(sinr + (sub % HL) * 8, sn);
+    }
+    auto rotated = [&](const T* row, float out[8]) {
+        zo_load8(row + hoff, out);
+        if (ROPE) {
+            float oth[8];
+            zo_load8(row + hbase + (sub ^ HL) * 8, oth);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                out[e] = zo_round_to<T>(first ? __builtin_fmaf(out[e], cs[e], -(oth[e] * sn[e])) : __builtin_fmaf(out[e], cs[e], oth[e] * sn[e]));
+        }
+    };
+    float qv[8];
+    rotated(qkv, qv);
+    const int r0 = s * rps;
+    const int r1 = r0 + rps < n ? r0 + rps : n;
+    const int rc = r1 < n - 1 ? r1 : n - 1;              // cached rows of this range: [r0, rc); row n - 1 is the new one
+    float m = -INFINITY, l = 0.0f, o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = 0.0f;
+    auto absorb = [&](const float (&sc)[4], const float (&vv)[4][8]) {
+        const float mnew = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), m);
+        const float corr = __expf(m - mnew);             // 0 the first time (m = -inf, mnew finite)
+        l *= corr;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] *= corr;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float pr = __expf(sc[u] - mnew);        // 0 for a row that does not exist (score -inf)
+            l += pr;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = __builtin_fmaf(pr, vv[u][e], o[e]);
+        }
+        m = mnew;
+    };
+    for (int j0 = r0 + kg; j0 < rc; j0 += 4 * KG) {
+        float kv[4][8], vv[4][8], sc[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int j = j0 + u * KG < rc ? j0 + u * KG : j0;
+            zo_load8(Kc + (int64_t)j * d + hoff, kv[u]);
+            zo_load8(Vc + (int64_t)j * d + hoff, vv[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float acc = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc = __builtin_fmaf(kv[u][e], qv[e], acc);
+            acc = zo_group_sum<LPK>(acc) * scale;
+            sc[u] = j0 + u * KG < rc ? acc : -INFINITY;
+        }
+        absorb(sc, vv);
+    }
+    if (r1 == n) {
+        // the new row: every row group computes its score (no divergence around the lane exchanges), the group whose turn
+        // it is stores it into the cache and counts it
+        const bool mine = kg == (n - 1 - r0) % KG;
+        float kn[8], vv[4][8], sc[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+        rotated(qkv + d, kn);
+        zo_load8(qkv + 2 * (int64_t)d + hoff, vv[0]);
+#pragma unroll
+        for (int u = 1; u < 4; ++u)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) vv[u][e] = 0.0f;
+        float acc = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc = __builtin_fmaf(kn[e], qv[e], acc);
+        acc = zo_group_sum<LPK>(acc) * scale;
+        if (mine) {
+            zo_store8(Kc + (int64_t)(n - 1) * d + hoff, kn);
+            zo_store8(Vc + (int64_t)(n - 1) * d + hoff, vv[0]);
+            sc[0] = acc;
+            absorb(sc, vv);
+        }
+    }
+    if (sub == 0) { gm[kg] = m; gl[kg] = l; }
+    __syncthreads();
+    float mx = gm[0];
+    for (int g = 1; g < KG; ++g) mx = fmaxf(mx, gm[g]);
+    const float w = __expf(m - mx);                       // a group without rows: m = -inf, weight 0
+#pragma unroll
+    for (int e = 0; e < 8; ++e) part[kg * DH + sub * 8 + e] = o[e] * w;
+    __syncthreads();
+    const int64_t slot = (int64_t)h * KS + s;
+    if (tid < DH) {
+        float t = part[tid];
+        for (int g = 1; g < KG; ++g) t += part[g * DH + tid];
+        po[slot * DH + tid] = t;
+    }
+    if (tid == 0) {
+        float lt = 0.0f;
+        for (int g = 0; g < KG; ++g) lt += gl[g] * __expf(gm[g] - mx);
+        ml[slot * 2] = mx;
+        ml[slot * 2 + 1] = lt;
+    }
+}
+
+// launch 2 (see above); NC chunks of 2048 columns per workgroup, a lane's 8 columns lie in one head
+template <typename T, int NC>
+__global__ __launch_bounds__(256) void zo_decode_attn_merge_kernel(const float* __restrict__ po, const float* __restrict__ ml, int KS, int H, int dh,
+                                                                   T* __restrict__ att, T* __restrict__ xhat, int bits, int sym,
+                                                                   const float* __restrict__ sm_delta, const float* __restrict__ sm_inv)
+{
+    __shared__ float wgt[1024];                         // weight of (head, range): exp(m - head maximum) / head sum
+    __shared__ float red[2][4];
+    const int cols = H * dh;
+    for (int h = threadIdx.x; h < H; h += 256) {
+        float mx = ml[(int64_t)h * KS * 2];
+        for (int s = 1; s < KS; ++s) mx = fmaxf(mx, ml[((int64_t)h * KS + s) * 2]);
+        float lt = 0.0f;
+        for (int s = 0; s < KS; ++s) {
+            const float e = __expf(ml[((int64_t)h * KS + s) * 2] - mx);
+            wgt[h * KS + s] = e;
+            lt += ml[((int64_t)h * KS + s) * 2 + 1] * e;
+        }
+        const float inv = 1.0f / lt;
+        for (int s = 0; s < KS; ++s) wgt[h * KS + s] *= inv;
+    }
+    __syncthreads();
+    float v[NC][8];
+    float mn = INFINITY, mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+        const int c = threadIdx.x * 8 + 2048 * i;
+        if (c < cols) {
+            const int h = c / dh, col = c - h * dh;
+            float o[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = 0.0f;
+            for (int s = 0; s < KS; ++s) {
+                float t[8];
+                zo_load8(po + ((int64_t)h * KS + s) * dh + col, t);
+                const float w = wgt[h * KS + s];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = __builtin_fmaf(w, t[e], o[e]);
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[i][e] = zo_round_to<T>(o[e]);
+            zo_store8(att + c, v[i]);
+            if (xhat) {
+                float dl[8], iv[8];
+                if (sm_delta) { zo_load8(sm_delta + c, dl); zo_load8(sm_inv + c, iv); }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    if (sm_delta) v[i][e] = (v[i][e] - dl[e]) * iv[e];
+                    if (sym) mx = fmaxf(mx, fabsf(v[i][e]));
+                    else { mn = fminf(mn, v[i][e]); mx = fmaxf(mx, v[i][e]); }
+                }
+            }
+        }
+    }
+    if (!xhat) return;
+    mn = zo_group_min<64>(mn);
+    mx = zo_group_max<64>(mx);
+    if ((threadIdx.x & 63) == 0) { red[0][threadIdx.x >> 6] = mn; red[1][threadIdx.x >> 6] = mx; }
+    __syncthreads();
+    mn = fminf(fminf(red[0][0], red[0][1]), fminf(red[0][2], red[0][3]));
+    mx = fmaxf(fmaxf(red[1][0], red[1][1]), fmaxf(red[1][2], red[1][3]));
+    const zo_qparams q = sym ? zo_qparams_sym(mx, bits) : zo_qparams_asym(mn, mx, bits);
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+        const int c = threadIdx.x * 8 + 2048 * i;
+        if (c < cols) {
+            float o[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = zo_dequant(q, zo_code(q, v[i][e]));
+            zo_store8(xhat + c, o);
+        }
+    }
+}
+
+// Ranges of cached rows per head: enough workgroups for two per CU, at least two rounds of row groups per range.
+static int decode_attn_rows_per_range(int n, int H, int dh)
+{
+    const int kg = 256 / (dh / 8);
+    int ks_max = 512 / H;
+    ks_max = ks_max < 1 ? 1 : (ks_max > 16 ? 16 : ks_max);
+    int rps = (n + ks_max - 1) / ks_max;
+    rps = (rps + kg - 1) / kg * kg;
+    return rps < 2 * kg ? 2 * kg : rps;
+}
+
+bool zo_decode_attention_split_supported(int32_t H, int32_t dh)
+{
+    return H >= 1 && H <= 256 && (dh == 16 || dh == 32 || dh == 64 || dh == 128) && H * dh <= 16384;
+}
+
+size_t zo_decode_attention_split_bytes(int32_t n, int32_t H, int32_t dh)
+{
+    const int rps = decode_attn_rows_per_range(n, H, dh);
+    const int ks = (n + rps - 1) / rps;
+    return (size_t)H * ks * (dh + 2) * sizeof(float);
+}
+
+template <typename T>
+static hipError_t launch_decode_attention_split_t(const T* qkv, T* Kc, T* Vc, const float* cosr, const float* sinr, float* scratch, T* att,
+                                                  T* xhat, int n, int H, int dh, int bits, int sym, const float* sm_delta,
+                                                  const float* sm_inv, hipStream_t st)
+{
+    const int d = H * dh;
+    const int rps = decode_attn_rows_per_range(n, H, dh);
+    const int ks = (n + rps - 1) / rps;
+    float* po = scratch;
+    float* ml = scratch + (size_t)H * ks * dh;
+    const float scale = 1.0f / sqrtf((float)dh);
+    const dim3 grid(ks, H);
+#define ZO_DEC_PART(L)                                                                                                                   \
+    do {                                                                                                                                 \
+        if (cosr) zo_decode_attn_part_kernel<T, L, true><<<grid, 256, 0, st>>>(qkv, Kc, Vc, cosr, sinr, po, ml, n, d, rps, scale);       \
+        else zo_decode_attn_part_kernel<T, L, false><<<grid, 256, 0, st>>>(qkv, Kc, Vc, cosr, sinr, po, ml, n, d, rps, scale);           \
+    } while (0)
+    switch (dh) {
+        case 16:  ZO_DEC_PART(2); break;
+        case 32:  ZO_DEC_PART(4); break;
+        case 64:  ZO_DEC_PART(8); break;
+        default:  ZO_DEC_PART(16); break;
+    }
+#undef ZO_DEC_PART
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+#define ZO_DEC_MERGE(NC) zo_decode_attn_merge_kernel<T, NC><<<1, 256, 0, st>>>(po, ml, ks, H, dh, att, xhat, bits, sym, sm_delta, sm_inv)
+    if (d <= 4096) ZO_DEC_MERGE(2); else if (d <= 8192) ZO_DEC_MERGE(4); else ZO_DEC_MERGE(8);
+#undef ZO_DEC_MERGE
+    return hipGetLastError();
+}
+
+// qkv: the new row (q | k | v, 3 H dh elements; q and k not yet rotated); Kc / Vc: this layer's cache, row n - 1 is written;
+// cos_row / sin_row: the rotary table's row of position n - 1, or NULL (no rotation); scratch: zo_decode_attention_split_bytes;
+// att: the attention output row; xhat: its per-token-quantized copy, or NULL.
+hipError_t zo_launch_decode_attention_split(const void* qkv, void* Kc, void* Vc, const float* cos_row, const float* sin_row, void* scratch,
+                                            void* att, void* xhat, int32_t n, int32_t H, int32_t dh, int32_t bits, int32_t sym,
+                                            const float* sm_delta, const float* sm_inv, int dtype, hipStream_t st)
+{
+    if (n <= 0 || !zo_decode_attention_split_supported(H, dh) || (cos_row == nullptr) != (sin_row == nullptr)) return hipErrorInvalidValue;
+    if (dtype == ZO_T_BF16)
+        return launch_decode_attention_split_t<zo_bf16>((const zo_bf16*)qkv, (zo_bf16*)Kc, (zo_bf16*)Vc, cos_row, sin_row, (float*)scratch,
+                                                        (zo_bf16*)att, (zo_bf16*)xhat, n, H, dh, bits, sym, sm_delta, sm_inv, st);
+    return launch_decode_attention_split_t<float>((const float*)qkv, (float*)Kc, (float*)Vc, cos_row, sin_row, (float*)scratch, (float*)att,
+                                                  (float*)xhat, n, H, dh, bits, sym, sm_delta, sm_inv, st);
+}
+
 // token = lowest index of the largest logit (NaNs never win).  One workgroup.
 __global__ __launch_bounds__(1024) void zo_argmax_kernel(const float* __restrict__ logits, int V, int32_t* __restrict__ token)
 {

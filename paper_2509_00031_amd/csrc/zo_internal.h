@@ -215,6 +215,11 @@ hipError_t zo_launch_gemm_i8(const zo_i8_gemm_args& a, int out_f32, hipStream_t 
 // out[h*dh + i] = sum_j softmax_j(q_h . K[j]_h / sqrt(dh)) V[j]_h[i] over the n cached rows (row pitch H*dh); fp32 math
 hipError_t zo_launch_decode_attention(const void* q, const void* Kc, const void* Vc, void* out, int32_t n, int32_t H, int32_t dh,
                                       int dtype, hipStream_t st);
+bool zo_decode_attention_split_supported(int32_t H, int32_t dh);
+size_t zo_decode_attention_split_bytes(int32_t n, int32_t H, int32_t dh);
+hipError_t zo_launch_decode_attention_split(const void* qkv, void* Kc, void* Vc, const float* cos_row, const float* sin_row, void* scratch,
+                                            void* att, void* xhat, int32_t n, int32_t H, int32_t dh, int32_t bits, int32_t sym,
+                                            const float* sm_delta, const float* sm_inv, int dtype, hipStream_t st);
 hipError_t zo_launch_argmax(const float* logits, int32_t V, int32_t* token, hipStream_t st);
 // frozen (packed 4-bit) linear of ONE token (M = 1, one branch): a.X bf16 [K], a.Y [N] (bf16, or fp32 with out_f32), 0.5 B per weight
 bool zo_int4_gemv_supported(int32_t M, int32_t nb, int32_t N, int32_t K, int32_t group);

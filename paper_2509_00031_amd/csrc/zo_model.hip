@@ -426,19 +426,20 @@ hipError_t zo_launch_swiglu(const void* gate, const void* up, void* out, int64_t
 // SwiGLU fused with the per-token quantizer of the down projection:
 // x^ = rt(Q_A(rt(silu(gate) * up))).  One workgroup per row, the row stays in registers.
 // up = NULL: the per-token quantizer alone on the row `gate` (one read, one write per element).
+// NT threads per row: 256, or 1024 where there are only a few rows (a decoding step), which shortens a lane's serial chain.
 // ---------------------------------------------------------------------------------------------
-template <typename T, int NC>
-__global__ __launch_bounds__(256) void zo_swiglu_quant_kernel(const T* __restrict__ gate, const T* __restrict__ up, T* __restrict__ xhat,
+template <typename T, int NC, int NT = 256>
+__global__ __launch_bounds__(NT) void zo_swiglu_quant_kernel(const T* __restrict__ gate, const T* __restrict__ up, T* __restrict__ xhat,
                                                               int cols, int64_t in_stride, int bits, int sym,
                                                               const float* __restrict__ sm_delta, const float* __restrict__ sm_inv)
 {
-    __shared__ float red[2][4];
+    __shared__ float red[2][NT / 64];
     const int64_t row = blockIdx.x;
     float v[NC][8];
     float mn = INFINITY, mx = -INFINITY;
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
-        const int c = threadIdx.x * 8 + 2048 * i;
+        const int c = threadIdx.x * 8 + NT * 8 * i;
         if (c < cols) {
             float g[8], u[8];
             zo_load8(gate + row * in_stride + c, g);
@@ -458,12 +459,14 @@ __global__ __launch_bounds__(256) void zo_swiglu_quant_kernel(const T* __restric
     mx = zo_group_max<64>(mx);
     if ((threadIdx.x & 63) == 0) { red[0][threadIdx.x >> 6] = mn; red[1][threadIdx.x >> 6] = mx; }
     __syncthreads();
-    mn = fminf(fminf(red[0][0], red[0][1]), fminf(red[0][2], red[0][3]));
-    mx = fmaxf(fmaxf(red[1][0], red[1][1]), fmaxf(red[1][2], red[1][3]));
+    mn = red[0][0];
+    mx = red[1][0];
+#pragma unroll
+    for (int w = 1; w < NT / 64; ++w) { mn = fminf(mn, red[0][w]); mx = fmaxf(mx, red[1][w]); }
     const zo_qparams q = sym ? zo_qparams_sym(mx, bits) : zo_qparams_asym(mn, mx, bits);
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
-        const int c = threadIdx.x * 8 + 2048 * i;
+        const int c = threadIdx.x * 8 + NT * 8 * i;
         if (c < cols) {
             float o[8];
 #pragma unroll
@@ -481,12 +484,19 @@ hipError_t zo_launch_swiglu_quant(const void* gate, const void* up, void* xhat, 
     if (rows == 0) return hipSuccess;
     if (rows > 0x7FFFFFFF) return hipErrorInvalidValue;
 #define ZO_SQ(T, NC) zo_swiglu_quant_kernel<T, NC><<<(int)rows, 256, 0, st>>>((const T*)gate, (const T*)up, (T*)xhat, cols, in_stride, bits, sym, sm_delta, sm_inv)
+#define ZO_SQW(T, NC) zo_swiglu_quant_kernel<T, NC, 1024><<<(int)rows, 1024, 0, st>>>((const T*)gate, (const T*)up, (T*)xhat, cols, in_stride, bits, sym, sm_delta, sm_inv)
+    if (rows <= 16 && cols > 2048) {                 // too few rows to fill the chip anyway: more lanes per row
+        if (dtype == ZO_T_BF16) { if (cols <= 8192) ZO_SQW(zo_bf16, 1); else ZO_SQW(zo_bf16, 2); }
+        else { if (cols <= 8192) ZO_SQW(float, 1); else ZO_SQW(float, 2); }
+        return hipGetLastError();
+    }
     if (dtype == ZO_T_BF16) {
         if (cols <= 4096) ZO_SQ(zo_bf16, 2); else if (cols <= 12288) ZO_SQ(zo_bf16, 6); else ZO_SQ(zo_bf16, 8);
     } else {
         if (cols <= 4096) ZO_SQ(float, 2); else if (cols <= 12288) ZO_SQ(float, 6); else ZO_SQ(float, 8);
     }
 #undef ZO_SQ
+#undef ZO_SQW
     return hipGetLastError();
 }
 
