@@ -58,6 +58,12 @@ WORKLOADS = {
                                                 vocab=32000, w_bits=4, w_group=128, a_bits=4, B=1, S=64, lightweight=1),
     "llama13b_lightweight_w4a4_g128_1x32": dict(arch="llama", n_layers=40, d_model=5120, n_heads=40, d_ffn=13824,
                                                 vocab=32000, w_bits=4, w_group=128, a_bits=4, B=1, S=32, lightweight=1),
+    # the shapes of the paper's fine-tuning rows for the lightweight variant (efficiency section, GPU table: sequences of at
+    # most 384 tokens, batch 1 and 16; its figures there are for another card and W2A16 g128: context only)
+    "llama13b_lightweight_w4a4_g128_1x384": dict(arch="llama", n_layers=40, d_model=5120, n_heads=40, d_ffn=13824,
+                                                 vocab=32000, w_bits=4, w_group=128, a_bits=4, B=1, S=384, lightweight=1),
+    "llama13b_lightweight_w4a4_g128_16x384": dict(arch="llama", n_layers=40, d_model=5120, n_heads=40, d_ffn=13824,
+                                                  vocab=32000, w_bits=4, w_group=128, a_bits=4, B=16, S=384, lightweight=1),
     # the trained model as a generator (efficiency section, on-device table: W4A4 inference, 384-token prompts): every quantized
     # linear stored as packed 4-bit codes, prompt pass over 384 tokens, then greedy decoding token by token
     "llama13b_w4a4_g128_generate_384": dict(arch="llama", n_layers=40, d_model=5120, n_heads=40, d_ffn=13824, vocab=32000,
