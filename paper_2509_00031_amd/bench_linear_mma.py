@@ -1,7 +1,8 @@
 #!/usr/bin/env python3
 """Times one fake-quantized linear layer (zo_linear_fakequant_mma) through both contractions -- bf16 matrix instructions on
 de-quantized operands, and int8 matrix instructions on the integer codes with a per-group rescale -- at the linear shapes of
-the Llama-2-7B-shaped workload (8 x 1024 tokens), W4A8, groups of 64 and 128.  Whole-call times come from events on the
+the Llama-2-7B-shaped workload (8 x 1024 tokens), W4A8, groups of 64 and 128 and per-channel steps (group 0: the integer
+route then has no rescale inside its loop).  Whole-call times come from events on the
 launch stream; per-kernel times and counters come from running this file under rocprofv3.
 
     python3 -m paper_2509_00031_amd.bench_linear_mma [--iters 10]
@@ -18,7 +19,7 @@ SHAPES = [(8192, 12288, 4096), (8192, 4096, 4096), (8192, 22016, 4096), (8192, 4
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--iters", type=int, default=10)
-    ap.add_argument("--groups", default="64,128")
+    ap.add_argument("--groups", default="64,128,0")
     args = ap.parse_args()
     import torch
     from paper_2509_00031_amd import binding as zo

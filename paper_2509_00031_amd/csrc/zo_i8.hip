@@ -171,11 +171,94 @@ __global__ __launch_bounds__(256) void zo_rowsum_kernel(const float* __restrict_
     r[n] = acc;
 }
 
+// Per-channel quantization (one group = one whole row of W, the weight setting of the W4A4 rows of the appendix's
+// quantization settings): one workgroup per output channel, two sweeps over the row (range, then codes; the stream is
+// generated again in the second sweep).  The channel's step goes to the same slot layout (a single row of steps) and
+// r[n] = step * (sum of the row's operands) is written directly -- a sum of at most 65536 integers below 128 is exact in fp32.
+template <typename TW>
+__global__ __launch_bounds__(256) void zo_weight_codes_i8_row_kernel(const TW* __restrict__ W, int K, zo_stream s, float eps, int bits,
+                                                                     int8_t* cp, int8_t* cm, float* wsp, float* wsm, float* rp, float* rm,
+                                                                     int* overflow)
+{
+    __shared__ float red[4][4];
+    const int n = blockIdx.x, nb = K / 8;
+    const int64_t b0 = (int64_t)n * nb;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float mnp = INFINITY, mxp = -INFINITY, mnm = INFINITY, mxm = -INFINITY;
+    for (int j = threadIdx.x; j < nb; j += 256) {
+        float w[8], z[8];
+        zo_load8(W + 8 * (b0 + j), w);
+        if (eps != 0.0f) zo_z8(s, (uint64_t)(b0 + j), z);
+        else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) z[i] = 0.0f;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float vp = __builtin_fmaf(eps, z[i], w[i]), vm = __builtin_fmaf(-eps, z[i], w[i]);
+            mnp = fminf(mnp, vp); mxp = fmaxf(mxp, vp); mnm = fminf(mnm, vm); mxm = fmaxf(mxm, vm);
+        }
+    }
+    mnp = zo_group_min<64>(mnp); mxp = zo_group_max<64>(mxp);
+    mnm = zo_group_min<64>(mnm); mxm = zo_group_max<64>(mxm);
+    if (lane == 0) { red[wave][0] = mnp; red[wave][1] = mxp; red[wave][2] = mnm; red[wave][3] = mxm; }
+    __syncthreads();
+    mnp = fminf(fminf(red[0][0], red[1][0]), fminf(red[2][0], red[3][0]));
+    mxp = fmaxf(fmaxf(red[0][1], red[1][1]), fmaxf(red[2][1], red[3][1]));
+    mnm = fminf(fminf(red[0][2], red[1][2]), fminf(red[2][2], red[3][2]));
+    mxm = fmaxf(fmaxf(red[0][3], red[1][3]), fmaxf(red[2][3], red[3][3]));
+    __syncthreads();
+    const zo_qparams qp = zo_qparams_asym(mnp, mxp, bits), qm = zo_qparams_asym(mnm, mxm, bits);
+    float sump = 0.0f, summ = 0.0f;
+    bool over = false;
+    for (int j = threadIdx.x; j < nb; j += 256) {
+        float w[8], z[8];
+        zo_load8(W + 8 * (b0 + j), w);
+        if (eps != 0.0f) zo_z8(s, (uint64_t)(b0 + j), z);
+        else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) z[i] = 0.0f;
+        }
+        uint32_t up[2] = {0u, 0u}, um[2] = {0u, 0u};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            float d = zo_code(qp, __builtin_fmaf(eps, z[i], w[i])) - qp.zp;          // integer valued
+            over = over || d > 127.0f || d < -128.0f;
+            d = __builtin_amdgcn_fmed3f(d, -128.0f, 127.0f);
+            sump += d;
+            up[i >> 2] |= ((uint32_t)(int)d & 0xFFu) << (8 * (i & 3));
+            if (cm) {
+                float dm = zo_code(qm, __builtin_fmaf(-eps, z[i], w[i])) - qm.zp;
+                over = over || dm > 127.0f || dm < -128.0f;
+                dm = __builtin_amdgcn_fmed3f(dm, -128.0f, 127.0f);
+                summ += dm;
+                um[i >> 2] |= ((uint32_t)(int)dm & 0xFFu) << (8 * (i & 3));
+            }
+        }
+        *reinterpret_cast<uint2*>(cp + 8 * (b0 + j)) = make_uint2(up[0], up[1]);
+        if (cm) *reinterpret_cast<uint2*>(cm + 8 * (b0 + j)) = make_uint2(um[0], um[1]);
+    }
+    if (over) atomicOr(overflow, 1);
+    sump = zo_group_sum<64>(sump);
+    summ = zo_group_sum<64>(summ);
+    if (lane == 0) { red[wave][0] = sump; red[wave][1] = summ; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int slot = (n >> 8) * 256 + scale_slot(n);
+        wsp[slot] = qp.step;
+        rp[n] = qp.step * (((red[0][0] + red[1][0]) + red[2][0]) + red[3][0]);
+        if (cm) {
+            wsm[slot] = qm.step;
+            rm[n] = qm.step * (((red[0][1] + red[1][1]) + red[2][1]) + red[3][1]);
+        }
+    }
+}
+
 bool zo_i8_supported(int32_t M, int32_t N, int32_t K, int32_t w_bits, int32_t w_group, int32_t a_bits)
 {
     if (M < 1 || N < 1 || K < 128 || (K & 127)) return false;
     if (w_bits < 1 || w_bits > 7 || a_bits < 2 || a_bits > 8) return false;        // 8-bit weight codes minus their zero point span 9 bits
-    if (w_group == 0) w_group = K;
+    if (w_group == 0 || w_group == K) return K <= 65536;                            // per channel: integer sums over K stay below 2^31
     if (w_group != 64 && w_group != 128 && w_group != 256 && w_group != 512) return false;   // a step per 64 k, or per whole K tiles;
     if (K % w_group) return false;                                                           // at most 64 lanes per group in the quantizer
     return true;
@@ -215,6 +298,14 @@ hipError_t zo_launch_weight_codes_i8(const void* W, int32_t N, int32_t K, int32_
 {
     if (group == 0) group = K;
     const zo_stream s = make_stream_i8(seed, tid);
+    if (group == K) {                                                               // per channel
+        if (N == 0) return hipSuccess;
+        if (wdtype == ZO_W_F16)
+            zo_weight_codes_i8_row_kernel<zo_f16><<<N, 256, 0, st>>>((const zo_f16*)W, K, s, eps, bits, cp, cm, wsp, wsm, rp, rm, overflow);
+        else
+            zo_weight_codes_i8_row_kernel<float><<<N, 256, 0, st>>>((const float*)W, K, s, eps, bits, cp, cm, wsp, wsm, rp, rm, overflow);
+        return hipGetLastError();
+    }
     hipError_t e = wdtype == ZO_W_F16
         ? launch_weight_codes_t<zo_f16>((const zo_f16*)W, N, K, bits, group, s, eps, cp, cm, wsp, wsm, rpart_p, rpart_m, overflow, st)
         : launch_weight_codes_t<float>((const float*)W, N, K, bits, group, s, eps, cp, cm, wsp, wsm, rpart_p, rpart_m, overflow, st);
@@ -299,9 +390,11 @@ __global__ __launch_bounds__(512) void zo_gemm_i8_kernel(zo_i8_gemm_args a)
             const int rb = wave * 8 + i;
             lds_dma16_i8(rb >= 32 ? (const void*)(W + kt * BKB) : (const void*)(X + kt * BKB), voff[i], lds0 + stage * STAGE + rb * 1024);
         }
-        // the steps of slice (wave % SPT) of this K tile, into this wave's own 1 KB slot (waves >= SPT duplicate)
-        const int row = __builtin_amdgcn_readfirstlane(SPT == 2 ? kt * 2 + (wave & 1) : kt / tpr);
-        lds_dma16_i8((const void*)(ws + (size_t)(uint32_t)(row * ws_row)), (uint32_t)(lane * 16), lds0 + stage * STAGE + OPER + wave * 1024);
+        if constexpr (SPT != 0) {
+            // the steps of slice (wave % SPT) of this K tile, into this wave's own 1 KB slot (waves >= SPT duplicate)
+            const int row = __builtin_amdgcn_readfirstlane(SPT == 2 ? kt * 2 + (wave & 1) : kt / tpr);
+            lds_dma16_i8((const void*)(ws + (size_t)(uint32_t)(row * ws_row)), (uint32_t)(lane * 16), lds0 + stage * STAGE + OPER + wave * 1024);
+        }
     };
 
     f32x4 acc[TM][TN];
@@ -348,6 +441,51 @@ __global__ __launch_bounds__(512) void zo_gemm_i8_kernel(zo_i8_gemm_args a)
         sc_next = sc;
     }
     const i32x4 zero = {0, 0, 0, 0};
+    if constexpr (SPT == 0) {
+        // One step per channel for the whole of K: the 32 integer tiles stay in the matrix unit's accumulators over all K
+        // tiles (|sum| <= 128 * 128 * K < 2^31) and meet their step once, behind the loop -- nothing for the vector unit inside
+        // it.  Fragments are refilled in place as they die (wf[j] behind tile (7, j), xf[i] behind tile (i, 3)); the workgroup
+        // synchronises behind the first channel block of a K tile's second slice, as in the grouped form below.
+        i32x4 iacc[TM][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) iacc[i][j] = zero;
+        for (int kt = 0; kt < nk; ++kt) {
+            const int cur = kt & 1;
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                const int nstage = ks == 0 ? cur : cur ^ 1, nks = ks ^ 1;
+                uint32_t nsb = (uint32_t)(nstage * STAGE);
+                asm volatile("" : "+s"(nsb));
+#pragma unroll
+                for (int idx = 0; idx < TM * TN; ++idx) {
+                    const int j = idx / TM, i = idx % TM;
+                    __builtin_amdgcn_sched_barrier(0);
+                    iacc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(xf[i], wf[j], iacc[i][j], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (ks == 1 && idx == TM - 1) {
+                        wait_vmcnt_i8<0>();                       // own copies of K tile kt + 1 have landed
+                        __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0): own reads of this stage have returned
+                        __syncthreads();
+                        issue(cur, kt + 2 < nk ? kt + 2 : nk - 1);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if (i == TM - 1) wf[j] = *reinterpret_cast<const i32x4*>(lds + waddr(nsb, nks, j) + j * 16 * BKB);
+                    if (j == TN - 1) xf[i] = *reinterpret_cast<const i32x4*>(lds + xaddr(nsb, nks, i) + i * 16 * BKB);
+                }
+            }
+        }
+        float stp[TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) stp[j] = ws[scale_slot(wn * 64 + j * 16 + j16)];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[i][j][r] = (float)iacc[i][j][r] * stp[j];
+    } else {
     i32x4 t = __builtin_amdgcn_mfma_i32_16x16x64_i8(xf[0], wf[0], zero, 0, 0, 0);
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = kt & 1;
@@ -385,6 +523,7 @@ __global__ __launch_bounds__(512) void zo_gemm_i8_kernel(zo_i8_gemm_args a)
             }
             sc = sc_next;
         }
+    }
     }
     wait_vmcnt_i8<0>();
     __syncthreads();
@@ -480,6 +619,7 @@ hipError_t zo_launch_gemm_i8(const zo_i8_gemm_args& a, int out_f32, hipStream_t 
 {
     if (a.M <= 0 || a.N <= 0) return hipSuccess;
     if (a.K < 128 || (a.K & 127) || (a.sgroup != 64 && (a.sgroup & 127)) || a.K % a.sgroup) return hipErrorInvalidValue;
+    if (a.sgroup == a.K) return out_f32 ? launch_gemm_i8_t<float, 0>(a, st) : launch_gemm_i8_t<zo_bf16, 0>(a, st);
     if (a.sgroup == 64) return out_f32 ? launch_gemm_i8_t<float, 2>(a, st) : launch_gemm_i8_t<zo_bf16, 2>(a, st);
     return out_f32 ? launch_gemm_i8_t<float, 1>(a, st) : launch_gemm_i8_t<zo_bf16, 1>(a, st);
 }

@@ -20,6 +20,8 @@ pytestmark = pytest.mark.gpu
     (64, 100, 1024, 2, 256, 4, False),       # a step per two K tiles, 4-bit activations
     (130, 272, 512, 7, 512, 8, True),        # per channel (K = 512), symmetric activations
     (1, 16, 128, 3, 64, 6, False),
+    (300, 520, 1152, 4, 0, 8, False),        # per channel: integer accumulation over all nine K tiles, ragged M and N
+    (40, 96, 11008, 4, 0, 4, False),         # per channel over the widest row of the benchmark shapes, 4-bit activations
 ])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_int8_linear_vs_oracle(M, N, K, w_bits, group, a_bits, sym, dtype):
@@ -41,11 +43,13 @@ def test_int8_linear_vs_oracle(M, N, K, w_bits, group, a_bits, sym, dtype):
         assert np.array_equal(parts["x_codes"].cpu().numpy().astype(np.int32) + off, qa["codes"])
         assert np.array_equal(parts["x_step"].cpu().numpy().view(np.uint32), qa["step"].view(np.uint32))
         assert np.array_equal(parts["x_off"].cpu().numpy(), (off - qa["zp"]).astype(np.float32))
-        G = K // group
-        wc = parts["w_codes"].cpu().numpy().astype(np.int32).reshape(N, G, group)
-        assert np.array_equal(wc + qw["zp"][:, :, None], qw["codes"].reshape(N, G, group))
+        gsz = group or K
+        G = K // gsz
+        wc = parts["w_codes"].cpu().numpy().astype(np.int32).reshape(N, G, gsz)
+        assert np.array_equal(wc + qw["zp"][:, :, None], qw["codes"].reshape(N, G, gsz))
         rp = qw["step"].astype(np.float64) * wc.sum(-1)
-        assert np.allclose(parts["w_rpart"].cpu().numpy(), rp, rtol=1e-6, atol=0)
+        if G > 1:                                                         # (per channel there are no per-group parts: r is written directly)
+            assert np.allclose(parts["w_rpart"].cpu().numpy(), rp, rtol=1e-6, atol=0)
         assert np.allclose(parts["w_r"].cpu().numpy(), rp.sum(-1), rtol=1e-5, atol=1e-6 * np.abs(rp).sum(-1).max())
         ref = orc.linear(qa["xhat"], qw["what"], bias)                    # un-rounded operands
         mag = np.abs(qa["xhat"].astype(np.float64)) @ np.abs(qw["what"].astype(np.float64)).T + np.abs(bias)
