@@ -70,6 +70,12 @@ WORKLOADS = {
                                             w_bits=4, w_group=128, a_bits=4, B=1, S=384, lightweight=1, generate=64),
     "llama7b_w4a4_g128_generate_384": dict(arch="llama", n_layers=32, d_model=4096, n_heads=32, d_ffn=11008, vocab=32000,
                                            w_bits=4, w_group=128, a_bits=4, B=1, S=384, lightweight=1, generate=64),
+    # per-channel weight steps (the weight setting of the W4A4 rows of the appendix's quantization settings) at the 7B shape:
+    # with --mma int8 the quantized linears contract their integer codes and the loop has no rescale at all
+    "llama7b_w4a8_perchannel_8x1024": dict(arch="llama", n_layers=32, d_model=4096, n_heads=32, d_ffn=11008, vocab=32000,
+                                           w_bits=4, w_group=0, a_bits=8, B=8, S=1024),
+    "llama7b_w4a4_perchannel_8x1024": dict(arch="llama", n_layers=32, d_model=4096, n_heads=32, d_ffn=11008, vocab=32000,
+                                           w_bits=4, w_group=0, a_bits=4, B=8, S=1024),
     "tiny_w4a16_g64_8x128": dict(arch="llama", n_layers=4, d_model=512, n_heads=8, d_ffn=2048, vocab=4096,
                                  w_bits=4, w_group=64, a_bits=16, B=8, S=128),
 }
@@ -90,6 +96,7 @@ def measured_gemm_traffic(workload):
 
 BREAKDOWN_STEPS = 2
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_INT8_TOPS = 5000.0        # MI355X dense int8 MFMA
 PEAK_HBM_GBS = 8000.0
 # plain vector ALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions per second (the fp32 vector peak of
 # 157.3 TFLOP/s counts 2 flops per FMA and the packed two-per-lane forms, which this build does not use)
@@ -229,6 +236,9 @@ def main():
                     help="storage of the master weights: fp32 (the benchmark configurations), IEEE binary16 rounded to nearest "
                          "even (f16) or stochastically (f16sr) in the update -- the 2 bytes per parameter of the paper's memory table")
     ap.add_argument("--no-fused", action="store_true", help="small token counts: quantize once and run the plain GEMM")
+    ap.add_argument("--mma", choices=["bf16", "int8"], default="bf16",
+                    help="contraction of the quantized linears: bf16 matrix instructions on de-quantized operands (the benchmark "
+                         "configurations), or int8 matrix instructions on the integer codes (zo_config.mma)")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket launches with HIP events in the timed region")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="before the timed region copy 1 GiB device to device once (a plain copy of known size, "
@@ -252,7 +262,8 @@ def main():
                          vocab=w["vocab"], max_seq=w["S"], w_bits=w["w_bits"], w_group=w["w_group"], a_bits=w["a_bits"],
                          act_dtype=zo.ACT_BF16, lightweight=w.get("lightweight", 0), learn_clip=w.get("learn_clip", 0),
                          learn_smooth=w.get("learn_smooth", 0), no_fused=int(args.no_fused),
-                         master_dtype=zo.MASTER_F16 if args.masters != "f32" else zo.MASTER_F32, master_round=int(args.masters == "f16sr"))
+                         master_dtype=zo.MASTER_F16 if args.masters != "f32" else zo.MASTER_F32, master_round=int(args.masters == "f16sr"),
+                         mma=zo.MMA_INT8 if args.mma == "int8" else zo.MMA_BF16)
     n = zo.zo_num_params(cfg)
     gen = torch.Generator(device=dev)
     gen.manual_seed(1234)
@@ -335,8 +346,8 @@ def main():
         "metric": "ZO steps/sec (2 quantized fwd + update)", "value": args.steps / elapsed, "unit": "steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": args.workload, "tokens_per_step": B * S, "trainable_params": n_params,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8" if args.mma == "int8" else "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "mma": args.mma, "tokens_per_step": B * S, "trainable_params": n_params,
                    "w_bits": w["w_bits"], "w_group": w["w_group"], "a_bits": w["a_bits"], "eps": eps, "lr": lr,
                    "directions": args.directions, "masters": args.masters,
                    "last_step": {"loss_plus": losses[0], "loss_minus": losses[1], "g": losses[2]}},
@@ -352,6 +363,11 @@ def main():
                            "launches": gemm_launches, "avg_launch_ms": avg_ms,
                            "flops_per_launch": flops_per_launch}
         res["gemm_tflops"] = achieved
+        if args.mma == "int8":
+            # the quantized linears run zo_gemm_i8_kernel (98.8 % of the operations at the 7B shape; the un-quantized lm_head
+            # keeps its bf16 launch, counted with them): priced against the dense int8 peak
+            res["roofline"].update({"kernel": "zo_gemm_i8_kernel<8 waves, 128-byte K tiles, 2 stages> (+ the bf16 lm_head launch)",
+                                    "peak": PEAK_INT8_TOPS, "unit": "TOP/s", "frac": achieved / PEAK_INT8_TOPS, "traffic": None})
         fused_ms, fused_launches = prof["fused_linear"]
         int4_ms, int4_launches = prof["fused_int4_linear"]
         if int4_launches > 0 and int4_ms >= fused_ms:
@@ -392,7 +408,7 @@ def main():
             gemm_ms_step = gemm_ms / args.steps
             wq_ms_step = res["breakdown_ms_per_step"]["weight_quant"]
             with_pro = gflops / ((gemm_ms_step + wq_ms_step) * 1e-3) / 1e12
-            res["roofline"].update({"frac_gemm_only": res["roofline"]["frac"], "frac_with_prologue": with_pro / PEAK_BF16_TFLOPS,
+            res["roofline"].update({"frac_gemm_only": res["roofline"]["frac"], "frac_with_prologue": with_pro / res["roofline"]["peak"],
                                     "achieved_with_prologue": with_pro, "prologue": "zo_fq_weight_kernel (quantize once per step)",
                                     "prologue_ms_per_step": wq_ms_step, "gemm_ms_per_step": gemm_ms_step,
                                     "note": "frac = GEMM kernel alone (2MNK / its launch time); frac_with_prologue = 2MNK / (GEMM + weight "

@@ -86,6 +86,16 @@ typedef struct {
     int32_t master_round;/* binary16 masters only: 0 = round to nearest even (a step below half the spacing of
                             binary16 is lost entirely), 1 = stochastic rounding (upper neighbour with probability
                             (x - lo) / (hi - lo), integers from the stream (seed, element / 4, tensor, 1)) */
+    int32_t mma;         /* contraction of the quantized linears (ZO_MMA_*, see zo_linear_fakequant_mma): 0 = ZO_MMA_BF16, de-quantized
+                            operands rounded to the storage type; 1 = ZO_MMA_INT8, the integer codes themselves (Background/Quantization:
+                            X_INT) on the int8 matrix instructions, steps and zero points applied in fp32, neither operand rounded.
+                            ZO_MMA_INT8 needs activation codes (a_bits <= 8), w_bits 1..7, w_group 64 / 128 / 256 / 512 or 0 (per
+                            channel: then the loop has no rescale and the linear runs about 1.5 times faster than in bf16), d_model and
+                            d_ffn multiples of 256, no learned tensors, no lightweight variant -- zo_init returns ZO_EUNSUPPORTED
+                            otherwise.  It applies to forwards that quantize once (more than 128 tokens, or no_fused = 1); the lm_head is
+                            not quantized and keeps its bf16 contraction.  A weight group whose zero point lies so far outside its
+                            range that code - zero point does not fit a signed byte cannot be represented: the forward then reports
+                            NaN losses (use ZO_MMA_BF16 for such weights). */
 } zo_config;
 
 /* One parameter tensor.  The array given to zo_init lists them in the fixed order below; the
@@ -460,7 +470,8 @@ enum { ZO_ROUTE_FUSED_SMALL_M = 1,    /* linears built from the masters inside t
        ZO_ROUTE_SWIGLU_IN_GEMM = 4,   /* SwiGLU applied by the epilogue of the gate / up GEMM */
        ZO_ROUTE_ROPE_IN_GEMM = 8,     /* rotary embedding applied by the epilogue of the q | k | v GEMM */
        ZO_ROUTE_CE_IN_GEMM = 16,      /* cross entropy formed by the epilogue of the lm_head GEMM, no logits stored */
-       ZO_ROUTE_GEMM_SPLIT_K = 32 };  /* some linear's GEMM ran with K split into ranges (see zo_gemm_nt_fused_splitk) */
+       ZO_ROUTE_GEMM_SPLIT_K = 32,    /* some linear's GEMM ran with K split into ranges (see zo_gemm_nt_fused_splitk) */
+       ZO_ROUTE_INT8_MMA = 64 };      /* quantized linears contracted on their integer codes (zo_config.mma = ZO_MMA_INT8) */
 uint32_t zo_debug_routes(const zo_ctx* ctx);
 
 /* Device buffers of the context's last forward, for layer-level parity tests.

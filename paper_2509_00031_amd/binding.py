@@ -19,7 +19,7 @@ STATUS = {0: "ZO_OK", 1: "ZO_EINVAL", 2: "ZO_ESHAPE", 3: "ZO_EALIGN", 4: "ZO_EHI
 ARCH_LINEAR, ARCH_LLAMA, ARCH_OPT = 0, 1, 2
 ACT_FP32, ACT_BF16 = 0, 1
 MASTER_F32, MASTER_F16 = 0, 1
-ROUTE_FUSED_SMALL_M, ROUTE_FUSED_INT4, ROUTE_SWIGLU_IN_GEMM, ROUTE_ROPE_IN_GEMM, ROUTE_CE_IN_GEMM, ROUTE_GEMM_SPLIT_K = 1, 2, 4, 8, 16, 32
+ROUTE_FUSED_SMALL_M, ROUTE_FUSED_INT4, ROUTE_SWIGLU_IN_GEMM, ROUTE_ROPE_IN_GEMM, ROUTE_CE_IN_GEMM, ROUTE_GEMM_SPLIT_K, ROUTE_INT8_MMA = 1, 2, 4, 8, 16, 32, 64
 
 EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "zo_destroy", "zo_last_error",
            "zo_forward_quant", "zo_step", "zo_update", "zo_debug_philox_u32", "zo_debug_normal", "zo_update_tensor",
@@ -38,7 +38,7 @@ PROF_NAMES = ["gemm", "weight_quant", "act_quant", "attention", "update", "other
 class zo_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("arch", "n_layers", "d_model", "n_heads", "d_ffn", "vocab", "max_seq",
                                          "w_bits", "w_group", "a_bits", "a_sym", "act_dtype", "lightweight",
-                                         "learn_clip", "learn_smooth", "no_fused", "master_dtype", "master_round")]
+                                         "learn_clip", "learn_smooth", "no_fused", "master_dtype", "master_round", "mma")]
 
 
 class zo_tensor(C.Structure):
@@ -149,9 +149,9 @@ def _tdtype(dtype):
 
 def make_config(arch, n_layers=0, d_model=0, n_heads=1, d_ffn=0, vocab=0, max_seq=0, w_bits=4, w_group=64,
                 a_bits=16, a_sym=0, act_dtype=ACT_FP32, lightweight=0, learn_clip=0, learn_smooth=0, no_fused=0,
-                master_dtype=MASTER_F32, master_round=0):
+                master_dtype=MASTER_F32, master_round=0, mma=0):
     return zo_config(arch, n_layers, d_model, n_heads, d_ffn, vocab, max_seq, w_bits, w_group, a_bits, a_sym,
-                     act_dtype, lightweight, learn_clip, learn_smooth, no_fused, master_dtype, master_round)
+                     act_dtype, lightweight, learn_clip, learn_smooth, no_fused, master_dtype, master_round, mma)
 
 
 def zo_master_bytes(cfg):

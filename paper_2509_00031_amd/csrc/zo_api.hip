@@ -128,6 +128,17 @@ zo_status check_config(const zo_config& c)
         const int dh = c.d_model / c.n_heads;
         if (dh != 16 && dh != 32 && dh != 64 && dh != 128) return ZO_EUNSUPPORTED;
     }
+    if (c.mma != ZO_MMA_BF16 && c.mma != ZO_MMA_INT8) return ZO_EINVAL;
+    if (c.mma == ZO_MMA_INT8) {
+        // every quantized linear must be expressible on the integer route (K = d_model and K = d_ffn); fused operands
+        // (q | k | v, gate | up) put each tensor at a 256-channel tile boundary of the rows of steps
+        if (c.lightweight || c.learn_clip || c.learn_smooth) return ZO_EUNSUPPORTED;
+        if (!zo_i8_supported(1, 256, c.d_model, c.w_bits, c.w_group, c.a_bits)) return ZO_EUNSUPPORTED;
+        if (c.arch != ZO_ARCH_LINEAR) {
+            if (!zo_i8_supported(1, 256, c.d_ffn, c.w_bits, c.w_group, c.a_bits)) return ZO_EUNSUPPORTED;
+            if ((c.d_model & 255) || (c.d_ffn & 255)) return ZO_EUNSUPPORTED;
+        }
+    }
     return ZO_OK;
 }
 
@@ -169,7 +180,7 @@ layout make_layout(const zo_config& c, int B, int S)
         for (int b = 0; b < 2; ++b)
             for (int j = 0; j < 4; ++j) L.qp[b][j] = take(L.qp_elems * sizeof(float));
         for (int b = 0; b < 2; ++b) {
-            L.br[b].hq = take(M * d * ts);
+            L.br[b].hq = take(M * d * ts + (c.mma == ZO_MMA_INT8 ? 512 + 8 * M : 0));   // integer route: codes, then per-row step / offset
             L.br[b].logits = take(M * f * ts);      // output Y
             L.br[b].rowloss = take(M * sizeof(float));
         }
@@ -203,7 +214,7 @@ layout make_layout(const zo_config& c, int B, int S)
         auto& r = L.br[b];
         r.x = take(M * d * ts);
         r.h = take(M * d * ts);
-        r.hq = take(M * (d > f ? d : f) * ts);
+        r.hq = take(M * (d > f ? d : f) * ts + (c.mma == ZO_MMA_INT8 ? 512 + 8 * M : 0));   // integer route: codes, then per-row step / offset
         r.qkv = take(M * 3 * d * ts);
         r.att = take(M * d * ts);
         r.gu = take(M * ffn_rows * ts);
@@ -317,6 +328,40 @@ struct fwd {
     pend pending[4];
     int npend = 0;
     int nweights = 0;     // operand tensors requested since the last GEMM (deferred or materialised)
+    // integer route (zo_config.mma = ZO_MMA_INT8): the operand buffers hold signed-byte codes instead of de-quantized values.
+    //   what[b]: [0, what_bytes / 2) codes [N][K]; then the rows of steps at what_bytes / 2, r[N] at + what_bytes / 8 and the
+    //            per-group parts of r at + what_bytes / 4 (all far below those bounds: K / group >= ... floats per channel)
+    //   hq of branch b: codes [M][K]; per-token step and offset (two fp32 rows of M) behind M * max(d, f) bytes
+    int next_t = -1;      // the quantized linear whose input is being prepared (set by smooth_prepare)
+    int gemm_N = 0;       // rows of the fused operand the next tensors are blocks of (set before their weights() calls)
+    bool x_codes = false, w_codes = false;
+    bool i8_route(int t) const
+    {
+        return c->cfg.mma == ZO_MMA_INT8 && t >= 0 && c->desc[t].quantized && !c->frozen[t].codes && !fused_ok(t, true);
+    }
+    size_t i8_ws_off() const { return c->L.what_bytes / 2; }
+    size_t i8_wr_off() const { return c->L.what_bytes / 2 + c->L.what_bytes / 8; }
+    size_t i8_rpart_off() const { return c->L.what_bytes / 2 + c->L.what_bytes / 4; }
+    size_t i8_xs_off() const
+    {
+        const size_t w = c->cfg.arch == ZO_ARCH_LINEAR ? (size_t)c->cfg.d_model
+                                                         : (size_t)(c->cfg.d_model > c->cfg.d_ffn ? c->cfg.d_model : c->cfg.d_ffn);
+        return align_up((size_t)M * w);
+    }
+    int* i8_flag() const { return at<int>(c->L.scalars) + 15; }
+    // per-token codes of the stored activation `in` (K columns) into hq, for the integer route
+    zo_status act_codes(size_t layout::per_branch::*in, int K, size_t layout::per_branch::** used)
+    {
+        prof_scope ps(c, ZO_PROF_ACT_QUANT);
+        for (int b = 0; b < nb; ++b) {
+            char* hq = at(c->L.br[b].hq);
+            ZO_HIP(c, zo_launch_act_codes_i8(at(c->L.br[b].*in), (int8_t*)hq, (float*)(hq + i8_xs_off()), (float*)(hq + i8_xs_off()) + M, M, K,
+                                             c->cfg.a_bits, c->cfg.a_sym, dt(), c->st));
+        }
+        x_codes = true;
+        *used = &layout::per_branch::hq;
+        return ZO_OK;
+    }
     bool fused_ok(int t, bool quantize) const
     {
         const zo_config& cfg = c->cfg;
@@ -349,6 +394,24 @@ struct fwd {
             return ZO_OK;
         }
         const size_t ts = zo_tsize(dt());
+        if (quantize && i8_route(t)) {
+            // signed-byte operands of both branches, their steps in the slot layout of the fused operand, r[n]
+            const int K = (int)p.cols, G = K / (c->cfg.w_group > 0 ? c->cfg.w_group : K);
+            const int n_total = gemm_N > 0 ? gemm_N : (int)p.rows;
+            if ((row0 & 255) || row0 + p.rows > n_total) return fail(c, ZO_EUNSUPPORTED, "integer route: operand block not at a tile boundary");
+            char* w0 = at(c->L.what[0]);
+            char* w1 = nb == 2 ? at(c->L.what[1]) : nullptr;
+            auto f32at = [&](char* base, size_t off, size_t idx) { return base ? (float*)(base + off) + idx : nullptr; };
+            prof_scope ps(c, ZO_PROF_WEIGHT_QUANT);
+            ZO_HIP(c, zo_launch_weight_codes_i8(c->params[t].ptr, (int)p.rows, K, c->cfg.w_bits, c->cfg.w_group, seed, t, eps_of(t), wd(),
+                                                (int8_t*)w0 + (size_t)row0 * K, w1 ? (int8_t*)w1 + (size_t)row0 * K : nullptr,
+                                                f32at(w0, i8_ws_off(), (size_t)row0), f32at(w1, i8_ws_off(), (size_t)row0),
+                                                f32at(w0, i8_wr_off(), (size_t)row0), f32at(w1, i8_wr_off(), (size_t)row0),
+                                                f32at(w0, i8_rpart_off(), (size_t)row0 * G), f32at(w1, i8_rpart_off(), (size_t)row0 * G),
+                                                i8_flag(), c->st, (n_total + 255) / 256));
+            w_codes = true;
+            return ZO_OK;
+        }
         void* op = at(c->L.what[0]) + (size_t)row0 * p.cols * ts;
         void* om = nb == 2 ? at(c->L.what[1]) + (size_t)row0 * p.cols * ts : nullptr;
         const int bits = quantize ? c->cfg.w_bits : 0;
@@ -391,7 +454,7 @@ struct fwd {
         const zo_config& cfg = c->cfg;
         if (cfg.no_fused || cfg.arch != ZO_ARCH_LLAMA || cfg.learn_smooth) return false;      // smoothing gives these linears a bias
         if (cfg.w_bits != 0 && !cfg.learn_clip && (cfg.w_group == 0 || cfg.w_group > 512)) return false;
-        if (cfg.d_model / cfg.n_heads != 128 || fused_ok(t_q, true)) return false;
+        if (cfg.d_model / cfg.n_heads != 128 || fused_ok(t_q, true) || i8_route(t_q)) return false;
         return zo_gemm_rope_supported(M, 3 * cfg.d_model, cfg.d_model, dt());
     }
     bool swiglu_in_gemm(int t_gate) const
@@ -399,7 +462,7 @@ struct fwd {
         const zo_config& cfg = c->cfg;
         if (cfg.no_fused || cfg.arch != ZO_ARCH_LLAMA || cfg.learn_smooth) return false;      // smoothing gives these linears a bias
         if (cfg.w_bits != 0 && !cfg.learn_clip && (cfg.w_group == 0 || cfg.w_group > 512)) return false;
-        if ((cfg.d_ffn & 31) || fused_ok(t_gate, true) || fused_ok(t_gate + 1, true)) return false;
+        if ((cfg.d_ffn & 31) || fused_ok(t_gate, true) || fused_ok(t_gate + 1, true) || i8_route(t_gate)) return false;
         return zo_gemm_swiglu_supported(M, 2 * cfg.d_ffn, cfg.d_model, dt());
     }
     // Eq. 4, activation side of the linears whose input is smoothed by the pair carried by linear `t`:
@@ -407,6 +470,7 @@ struct fwd {
     zo_status smooth_prepare(int t)
     {
         const param_desc& p = c->desc[t];
+        next_t = t;
         sm_on = p.smooth >= 0;
         if (!sm_on) return ZO_OK;
         ZO_TRY_(vector(p.smooth, 3));
@@ -463,7 +527,7 @@ struct fwd {
     zo_status norm_quant(size_t layout::per_branch::*in, bool has_beta, size_t layout::per_branch::** used)
     {
         const int d = c->cfg.d_model;
-        if (c->cfg.a_bits >= 16 || !zo_norm_quant_supported(d)) {
+        if (c->cfg.a_bits >= 16 || !zo_norm_quant_supported(d) || i8_route(next_t)) {
             zo_status s_ = norm(in, &layout::per_branch::h, has_beta);
             if (s_ != ZO_OK) return s_;
             return act_quant(&layout::per_branch::h, d, used);
@@ -479,6 +543,7 @@ struct fwd {
     zo_status act_quant(size_t layout::per_branch::*in, int K, size_t layout::per_branch::** used)
     {
         if (c->cfg.a_bits >= 16) { *used = in; return ZO_OK; }
+        if (i8_route(next_t)) return act_codes(in, K, used);
         prof_scope ps(c, ZO_PROF_ACT_QUANT);
         for (int b = 0; b < nb; ++b) {
             if (zo_swiglu_quant_supported(K))             // row kept in registers: one read and one write per element
@@ -615,6 +680,40 @@ struct fwd {
             npend = 0;
             return ZO_OK;
         }
+        if (w_codes != x_codes) {
+            w_codes = x_codes = false;
+            return fail(c, ZO_EUNSUPPORTED, "integer route: operands of one GEMM prepared differently");
+        }
+        if (w_codes) {
+            w_codes = x_codes = false;
+            if (swiglu || rope || ce_ids || w_shared || (out_f32 && dt() != ZO_T_F32)) return fail(c, ZO_EUNSUPPORTED, "integer route: epilogue");
+            zo_i8_gemm_args g{};
+            char* x0 = at(c->L.br[0].*in);
+            char* w0 = at(c->L.what[0]);
+            g.X = (const int8_t*)x0; g.W = (const int8_t*)w0;
+            g.xs = (const float*)(x0 + i8_xs_off()); g.xo = g.xs + M;
+            g.ws = (const float*)(w0 + i8_ws_off()); g.wr = (const float*)(w0 + i8_wr_off());
+            g.Y = at(c->L.br[0].*out);
+            g.bias = bias ? vec(0, 2) : nullptr;
+            g.residual = residual ? g.Y : nullptr;
+            g.M = M; g.N = N; g.K = K; g.batch = nb;
+            g.sgroup = c->cfg.w_group > 0 ? c->cfg.w_group : K;
+            g.relu = relu;
+            if (nb == 2) {
+                const int64_t ts_ = (int64_t)zo_tsize(dt());
+                g.strideX = (int64_t)(c->L.br[1].*in - c->L.br[0].*in);
+                g.strideXs = g.strideX / 4;
+                g.strideW = (int64_t)(c->L.what[1] - c->L.what[0]);
+                g.strideWs = g.strideWr = g.strideW / 4;
+                g.strideY = (int64_t)(c->L.br[1].*out - c->L.br[0].*out) / ts_;
+                g.strideBias = (int64_t)(c->L.vec[1] - c->L.vec[0]) / 4;
+                g.strideRes = g.strideY;
+            }
+            c->routes |= ZO_ROUTE_INT8_MMA;
+            prof_scope ps(c, ZO_PROF_GEMM);
+            ZO_HIP(c, zo_launch_gemm_i8(g, dt() == ZO_T_F32, c->st));
+            return ZO_OK;
+        }
         zo_gemm_args a{};
         a.X = at(c->L.br[0].*in);
         a.W = at(c->L.what[0]);
@@ -686,6 +785,25 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
         ZO_TRY(F.bias_shift(0, 0, false));
         // input X is given by the caller; quantize into hq (the same X^ for both branches unless the
         // perturbed smoothing makes them differ)
+        if (F.i8_route(0)) {
+            // integer route: codes of X (the same for both branches) into hq of branch 0 -- and of branch 1, which the batched
+            // launch reads through its stride
+            prof_scope ps(c, ZO_PROF_ACT_QUANT);
+            for (int b = 0; b < nb; ++b) {
+                char* hq = F.at(c->L.br[b].hq);
+                ZO_HIP(c, zo_launch_act_codes_i8(ids_or_x, (int8_t*)hq, (float*)(hq + F.i8_xs_off()), (float*)(hq + F.i8_xs_off()) + M, M, K,
+                                                 cfg.a_bits, cfg.a_sym, dt, c->st));
+            }
+            F.x_codes = true;
+            ZO_TRY(F.gemm(&PB::hq, &PB::logits, N, K, false, false, false));
+            prof_scope ps2(c, ZO_PROF_OTHER);
+            for (int b = 0; b < nb; ++b) {
+                ZO_HIP(c, zo_launch_sqerr_rows(F.at(c->L.br[b].logits), target, F.at<float>(c->L.br[b].rowloss), M, N, dt, c->st));
+                ZO_HIP(c, zo_launch_reduce_loss(F.at<float>(c->L.br[b].rowloss), M, 1.0f / ((float)M * (float)N), loss_out + b, c->st));
+            }
+            ZO_HIP(c, zo_launch_i8_flag_to_loss(F.i8_flag(), loss_out, nb, c->st));
+            return ZO_OK;
+        }
         zo_gemm_args a{};
         const void* xin = ids_or_x;
         const bool two_x = nb == 2 && F.sm_on;
@@ -772,6 +890,7 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
         };
         const bool bias = !llama || cfg.learn_smooth;
         const bool rope_fused = llama && F.rope_in_gemm(t);      // head blocks permuted in the operand, rotation in the epilogue
+        F.gemm_N = 3 * d;
         for (int i = 0; i < 3; ++i) ZO_TRY(linear((int64_t)i * d, sh, rope_fused ? 3 : 0));
         ZO_TRY(F.gemm(xin, &PB::qkv, 3 * d, d, bias, false, false, false, sh, false, rope_fused));
         // a decoding step (one new row, rows cached before it): rotation, cache append, attention over key ranges and the
@@ -820,6 +939,7 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
             ZO_TRY(F.act_quant(&PB::att, d, &xin));
         }
         sh = F.frozen(t);
+        F.gemm_N = d;
         ZO_TRY(linear(0, sh));
         ZO_TRY(F.gemm(xin, &PB::x, d, d, bias, false, true, false, sh));
         // ---- feed-forward block
@@ -836,11 +956,12 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
             ZO_TRY(F.gemm(xin, &PB::act, 2 * f, d, false, false, false, false, sh, true));
         } else if (llama) {
             sh = F.frozen(t) && F.frozen(t + 1);
+            F.gemm_N = 2 * f;
             ZO_TRY(linear(0, sh));
             ZO_TRY(linear(f, sh));
             ZO_TRY(F.gemm(xin, &PB::gu, 2 * f, d, bias, false, false, false, sh));
             ZO_TRY(F.smooth_prepare(t));                 // w_down: its input is the SwiGLU output
-            act_done = cfg.a_bits < 16 && zo_swiglu_quant_supported(f);
+            act_done = cfg.a_bits < 16 && zo_swiglu_quant_supported(f) && !F.i8_route(t);
             prof_scope ps(c, act_done ? ZO_PROF_ACT_QUANT : ZO_PROF_OTHER);
             for (int b = 0; b < nb; ++b) {
                 char* gu = F.at(c->L.br[b].gu);
@@ -852,6 +973,7 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
             }
         } else {
             sh = F.frozen(t);
+            F.gemm_N = f;
             ZO_TRY(linear(0, sh));
             ZO_TRY(F.gemm(xin, &PB::act, f, d, true, true, false, false, sh));
             ZO_TRY(F.smooth_prepare(t));                 // fc2
@@ -859,6 +981,7 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
         if (act_done) xin = &PB::hq;
         else ZO_TRY(F.act_quant(&PB::act, f, &xin));
         sh = F.frozen(t);
+        F.gemm_N = d;
         ZO_TRY(linear(0, sh));
         ZO_TRY(F.gemm(xin, &PB::x, d, f, bias, false, true, false, sh));
     }
@@ -893,6 +1016,7 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
             ZO_HIP(c, zo_launch_ce_rows(F.at<float>(c->L.br[b].logits), ids, F.at<float>(c->L.br[b].rowloss), M, S, V, c->st));
         ZO_HIP(c, zo_launch_reduce_loss(F.at<float>(c->L.br[b].rowloss), M, 1.0f / ((float)B * (float)(S - 1)), loss_out + b, c->st));
     }
+    if (c->routes & ZO_ROUTE_INT8_MMA) ZO_HIP(c, zo_launch_i8_flag_to_loss(F.i8_flag(), loss_out, nb, c->st));
     return ZO_OK;
 }
 
@@ -994,6 +1118,10 @@ zo_status zo_init(const zo_config* cfg, const zo_tensor* params, int32_t n_param
         hipError_t e = hipMemcpyAsync(c->ws + L.rope_cos, cs.data(), cs.size() * 4, hipMemcpyHostToDevice, c->st);
         if (e == hipSuccess) e = hipMemcpyAsync(c->ws + L.rope_sin, sn.data(), sn.size() * 4, hipMemcpyHostToDevice, c->st);
         if (e != hipSuccess) { delete c; return ZO_EHIP; }
+    }
+    if (cfg->mma == ZO_MMA_INT8) {
+        // the integer route's overflow flag starts clear (afterwards the forward that reads it clears it again)
+        if (hipMemsetAsync(c->ws + L.scalars + 15 * sizeof(float), 0, sizeof(int), c->st) != hipSuccess) { delete c; return ZO_EHIP; }
     }
     *out = c;
     return ZO_OK;

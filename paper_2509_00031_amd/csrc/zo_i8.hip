@@ -271,7 +271,8 @@ size_t zo_i8_scale_floats(int32_t N, int32_t K, int32_t w_group)
 
 template <typename TW>
 static hipError_t launch_weight_codes_t(const TW* W, int32_t N, int32_t K, int32_t bits, int32_t group, zo_stream s, float eps, int8_t* cp,
-                                        int8_t* cm, float* wsp, float* wsm, float* rpp, float* rpm, int* overflow, hipStream_t st)
+                                        int8_t* cm, float* wsp, float* wsm, float* rpp, float* rpm, int* overflow, hipStream_t st,
+                                        int scale_row_tiles)
 {
     const int kb = K / 8;
     const int64_t nblk = (int64_t)N * kb;
@@ -279,7 +280,9 @@ static hipError_t launch_weight_codes_t(const TW* W, int32_t N, int32_t K, int32
     if (nblk >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
     const int grid = (int)((nblk + 255) / 256);
     const zo_i8_rowdiv rd = make_rowdiv_i8(kb);
-    const int tiles_n = (N + 255) / 256;
+    // 256-channel tiles per row of steps: this matrix alone, or the fused operand it is a row block of (then wsp / wsm point at
+    // the block's first tile inside the row of steps of group 0)
+    const int tiles_n = scale_row_tiles > 0 ? scale_row_tiles : (N + 255) / 256;
     switch (group / 8) {
         case 8:  zo_weight_codes_i8_kernel<TW, 8><<<grid, 256, 0, st>>>(W, nblk, s, eps, bits, cp, cm, wsp, wsm, rpp, rpm, overflow, rd, tiles_n); break;
         case 16: zo_weight_codes_i8_kernel<TW, 16><<<grid, 256, 0, st>>>(W, nblk, s, eps, bits, cp, cm, wsp, wsm, rpp, rpm, overflow, rd, tiles_n); break;
@@ -294,7 +297,7 @@ static hipError_t launch_weight_codes_t(const TW* W, int32_t N, int32_t K, int32
 // per branch.  *overflow (device int) is OR-ed with 1 if some |qw - zw| did not fit a signed byte.
 hipError_t zo_launch_weight_codes_i8(const void* W, int32_t N, int32_t K, int32_t bits, int32_t group, uint64_t seed, int32_t tid, float eps,
                                      int wdtype, int8_t* cp, int8_t* cm, float* wsp, float* wsm, float* rp, float* rm, float* rpart_p,
-                                     float* rpart_m, int* overflow, hipStream_t st)
+                                     float* rpart_m, int* overflow, hipStream_t st, int32_t scale_row_tiles)
 {
     if (group == 0) group = K;
     const zo_stream s = make_stream_i8(seed, tid);
@@ -307,12 +310,25 @@ hipError_t zo_launch_weight_codes_i8(const void* W, int32_t N, int32_t K, int32_
         return hipGetLastError();
     }
     hipError_t e = wdtype == ZO_W_F16
-        ? launch_weight_codes_t<zo_f16>((const zo_f16*)W, N, K, bits, group, s, eps, cp, cm, wsp, wsm, rpart_p, rpart_m, overflow, st)
-        : launch_weight_codes_t<float>((const float*)W, N, K, bits, group, s, eps, cp, cm, wsp, wsm, rpart_p, rpart_m, overflow, st);
+        ? launch_weight_codes_t<zo_f16>((const zo_f16*)W, N, K, bits, group, s, eps, cp, cm, wsp, wsm, rpart_p, rpart_m, overflow, st, scale_row_tiles)
+        : launch_weight_codes_t<float>((const float*)W, N, K, bits, group, s, eps, cp, cm, wsp, wsm, rpart_p, rpart_m, overflow, st, scale_row_tiles);
     if (e != hipSuccess) return e;
     const int G = K / group;
     zo_rowsum_kernel<<<(N + 255) / 256, 256, 0, st>>>(rpart_p, rp, N, G);
     if (cm) zo_rowsum_kernel<<<(N + 255) / 256, 256, 0, st>>>(rpart_m, rm, N, G);
+    return hipGetLastError();
+}
+
+__global__ void zo_i8_flag_to_loss_kernel(int* flag, float* loss, int nb)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0 && *flag) {
+        for (int b = 0; b < nb; ++b) loss[b] = __builtin_nanf("");
+        *flag = 0;
+    }
+}
+hipError_t zo_launch_i8_flag_to_loss(int* flag, float* loss, int32_t nb, hipStream_t st)
+{
+    zo_i8_flag_to_loss_kernel<<<1, 64, 0, st>>>(flag, loss, nb);
     return hipGetLastError();
 }
 
@@ -533,7 +549,7 @@ __global__ __launch_bounds__(512) void zo_gemm_i8_kernel(zo_i8_gemm_args a)
     // g ^ (4 * ((row >> 2) & 1))) and leave as row pieces
     TY* Y = (TY*)a.Y + bz * a.strideY;
     const float* bias = a.bias ? a.bias + bz * a.strideBias : nullptr;
-    const zo_bf16* res = a.residual ? (const zo_bf16*)a.residual + bz * a.strideRes : nullptr;
+    const TY* res = a.residual ? (const TY*)a.residual + bz * a.strideRes : nullptr;     // the residual has the output's type
     const float* xs = a.xs + bz * a.strideXs;
     const float* xo = a.xo + bz * a.strideXs;
     const float* wr = a.wr + bz * a.strideWr;
@@ -582,8 +598,13 @@ __global__ __launch_bounds__(512) void zo_gemm_i8_kernel(zo_i8_gemm_args a)
             const int64_t off = (int64_t)m * N + n;
             if ((N & 3) == 0) {
                 if (res) {
-                    const uint2 r2 = *reinterpret_cast<const uint2*>(res + off);
-                    v[0] += zo_bf16_lo(r2.x); v[1] += zo_bf16_hi(r2.x); v[2] += zo_bf16_lo(r2.y); v[3] += zo_bf16_hi(r2.y);
+                    if constexpr (sizeof(TY) == 4) {
+                        const float4 r4 = *reinterpret_cast<const float4*>(res + off);
+                        v[0] += r4.x; v[1] += r4.y; v[2] += r4.z; v[3] += r4.w;
+                    } else {
+                        const uint2 r2 = *reinterpret_cast<const uint2*>(res + off);
+                        v[0] += zo_bf16_lo(r2.x); v[1] += zo_bf16_hi(r2.x); v[2] += zo_bf16_lo(r2.y); v[3] += zo_bf16_hi(r2.y);
+                    }
                 }
                 if constexpr (sizeof(TY) == 4) {
                     *reinterpret_cast<float4*>((float*)Y + off) = make_float4(v[0], v[1], v[2], v[3]);

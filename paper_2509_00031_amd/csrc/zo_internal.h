@@ -198,7 +198,9 @@ hipError_t zo_launch_act_codes_i8(const void* X, int8_t* codes, float* xs, float
                                   int dtype, hipStream_t st);
 hipError_t zo_launch_weight_codes_i8(const void* W, int32_t N, int32_t K, int32_t bits, int32_t group, uint64_t seed, int32_t tid, float eps,
                                      int wdtype, int8_t* cp, int8_t* cm, float* wsp, float* wsm, float* rp, float* rm, float* rpart_p,
-                                     float* rpart_m, int* overflow, hipStream_t st);
+                                     float* rpart_m, int* overflow, hipStream_t st, int32_t scale_row_tiles = 0);
+// the forward's overflow flag: a set flag turns the nb losses into NaN and is cleared for the next forward
+hipError_t zo_launch_i8_flag_to_loss(int* flag, float* loss, int32_t nb, hipStream_t st);
 struct zo_i8_gemm_args {
     const int8_t* X; const int8_t* W;        // codes [M][K], [N][K]
     const float* xs; const float* xo;        // per token: step, O - zero point
