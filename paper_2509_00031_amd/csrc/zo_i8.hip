@@ -175,28 +175,42 @@ __global__ __launch_bounds__(256) void zo_rowsum_kernel(const float* __restrict_
 // quantization settings): one workgroup per output channel, two sweeps over the row (range, then codes; the stream is
 // generated again in the second sweep).  The channel's step goes to the same slot layout (a single row of steps) and
 // r[n] = step * (sum of the row's operands) is written directly -- a sum of at most 65536 integers below 128 is exact in fp32.
-template <typename TW>
+// NB > 0: a thread's (at most NB) blocks of 8 weights and their perturbations stay in registers between the two sweeps
+// (rows of up to 2048 NB weights), so the stream is generated once; NB = 0: any row length, stream generated in both sweeps.
+template <typename TW, int NB>
 __global__ __launch_bounds__(256) void zo_weight_codes_i8_row_kernel(const TW* __restrict__ W, int K, zo_stream s, float eps, int bits,
                                                                      int8_t* cp, int8_t* cm, float* wsp, float* wsm, float* rp, float* rm,
                                                                      int* overflow)
 {
     __shared__ float red[4][4];
+    constexpr int HELD = NB > 0 ? NB : 1;
     const int n = blockIdx.x, nb = K / 8;
     const int64_t b0 = (int64_t)n * nb;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    float mnp = INFINITY, mxp = -INFINITY, mnm = INFINITY, mxm = -INFINITY;
-    for (int j = threadIdx.x; j < nb; j += 256) {
-        float w[8], z[8];
+    const int sweeps = NB > 0 ? NB : (nb + 255) / 256;
+    float wv[HELD][8], zv[HELD][8];
+    auto fetch = [&](int j, float (&w)[8], float (&z)[8]) {
         zo_load8(W + 8 * (b0 + j), w);
         if (eps != 0.0f) zo_z8(s, (uint64_t)(b0 + j), z);
         else {
 #pragma unroll
             for (int i = 0; i < 8; ++i) z[i] = 0.0f;
         }
+    };
+    float mnp = INFINITY, mxp = -INFINITY, mnm = INFINITY, mxm = -INFINITY;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const float vp = __builtin_fmaf(eps, z[i], w[i]), vm = __builtin_fmaf(-eps, z[i], w[i]);
-            mnp = fminf(mnp, vp); mxp = fmaxf(mxp, vp); mnm = fminf(mnm, vm); mxm = fmaxf(mxm, vm);
+    for (int u = 0; u < sweeps; ++u) {
+        const int j = threadIdx.x + 256 * u;
+        if (j < nb) {
+            float wl[8], zl[8];
+            float (&w)[8] = NB > 0 ? wv[NB > 0 ? u : 0] : wl;
+            float (&z)[8] = NB > 0 ? zv[NB > 0 ? u : 0] : zl;
+            fetch(j, w, z);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float vp = __builtin_fmaf(eps, z[i], w[i]), vm = __builtin_fmaf(-eps, z[i], w[i]);
+                mnp = fminf(mnp, vp); mxp = fmaxf(mxp, vp); mnm = fminf(mnm, vm); mxm = fmaxf(mxm, vm);
+            }
         }
     }
     mnp = zo_group_min<64>(mnp); mxp = zo_group_max<64>(mxp);
@@ -211,32 +225,33 @@ __global__ __launch_bounds__(256) void zo_weight_codes_i8_row_kernel(const TW* _
     const zo_qparams qp = zo_qparams_asym(mnp, mxp, bits), qm = zo_qparams_asym(mnm, mxm, bits);
     float sump = 0.0f, summ = 0.0f;
     bool over = false;
-    for (int j = threadIdx.x; j < nb; j += 256) {
-        float w[8], z[8];
-        zo_load8(W + 8 * (b0 + j), w);
-        if (eps != 0.0f) zo_z8(s, (uint64_t)(b0 + j), z);
-        else {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) z[i] = 0.0f;
-        }
-        uint32_t up[2] = {0u, 0u}, um[2] = {0u, 0u};
+    for (int u = 0; u < sweeps; ++u) {
+        const int j = threadIdx.x + 256 * u;
+        if (j < nb) {
+            float wl[8], zl[8];
+            float (&w)[8] = NB > 0 ? wv[NB > 0 ? u : 0] : wl;
+            float (&z)[8] = NB > 0 ? zv[NB > 0 ? u : 0] : zl;
+            if (NB == 0) fetch(j, w, z);
+            uint32_t up[2] = {0u, 0u}, um[2] = {0u, 0u};
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            float d = zo_code(qp, __builtin_fmaf(eps, z[i], w[i])) - qp.zp;          // integer valued
-            over = over || d > 127.0f || d < -128.0f;
-            d = __builtin_amdgcn_fmed3f(d, -128.0f, 127.0f);
-            sump += d;
-            up[i >> 2] |= ((uint32_t)(int)d & 0xFFu) << (8 * (i & 3));
-            if (cm) {
-                float dm = zo_code(qm, __builtin_fmaf(-eps, z[i], w[i])) - qm.zp;
-                over = over || dm > 127.0f || dm < -128.0f;
-                dm = __builtin_amdgcn_fmed3f(dm, -128.0f, 127.0f);
-                summ += dm;
-                um[i >> 2] |= ((uint32_t)(int)dm & 0xFFu) << (8 * (i & 3));
+            for (int i = 0; i < 8; ++i) {
+                float d = zo_code(qp, __builtin_fmaf(eps, z[i], w[i])) - qp.zp;          // integer valued
+                over = over || d > 127.0f || d < -128.0f;
+                d = __builtin_amdgcn_fmed3f(d, -128.0f, 127.0f);
+                sump += d;
+                up[i >> 2] |= ((uint32_t)(int)d & 0xFFu) << (8 * (i & 3));
+                if (cm) {
+                    float dm = zo_code(qm, __builtin_fmaf(-eps, z[i], w[i])) - qm.zp;
+                    over = over || dm > 127.0f || dm < -128.0f;
+                    dm = __builtin_amdgcn_fmed3f(dm, -128.0f, 127.0f);
+                    summ += dm;
+                    um[i >> 2] |= ((uint32_t)(int)dm & 0xFFu) << (8 * (i & 3));
+                }
             }
+            *reinterpret_cast<uint2*>(cp + 8 * (b0 + j)) = make_uint2(up[0], up[1]);
+            if (cm) *reinterpret_cast<uint2*>(cm + 8 * (b0 + j)) = make_uint2(um[0], um[1]);
         }
-        *reinterpret_cast<uint2*>(cp + 8 * (b0 + j)) = make_uint2(up[0], up[1]);
-        if (cm) *reinterpret_cast<uint2*>(cm + 8 * (b0 + j)) = make_uint2(um[0], um[1]);
     }
     if (over) atomicOr(overflow, 1);
     sump = zo_group_sum<64>(sump);
@@ -252,6 +267,16 @@ __global__ __launch_bounds__(256) void zo_weight_codes_i8_row_kernel(const TW* _
             rm[n] = qm.step * (((red[0][1] + red[1][1]) + red[2][1]) + red[3][1]);
         }
     }
+}
+
+template <typename TW>
+static hipError_t launch_weight_codes_row_t(const TW* W, int32_t N, int32_t K, int32_t bits, zo_stream s, float eps, int8_t* cp, int8_t* cm,
+                                            float* wsp, float* wsm, float* rp, float* rm, int* overflow, hipStream_t st)
+{
+#define ZO_ROWQ(NB) zo_weight_codes_i8_row_kernel<TW, NB><<<N, 256, 0, st>>>(W, K, s, eps, bits, cp, cm, wsp, wsm, rp, rm, overflow)
+    if (K <= 4096) ZO_ROWQ(2); else if (K <= 8192) ZO_ROWQ(4); else if (K <= 12288) ZO_ROWQ(6); else if (K <= 16384) ZO_ROWQ(8); else ZO_ROWQ(0);
+#undef ZO_ROWQ
+    return hipGetLastError();
 }
 
 bool zo_i8_supported(int32_t M, int32_t N, int32_t K, int32_t w_bits, int32_t w_group, int32_t a_bits)
@@ -304,10 +329,8 @@ hipError_t zo_launch_weight_codes_i8(const void* W, int32_t N, int32_t K, int32_
     if (group == K) {                                                               // per channel
         if (N == 0) return hipSuccess;
         if (wdtype == ZO_W_F16)
-            zo_weight_codes_i8_row_kernel<zo_f16><<<N, 256, 0, st>>>((const zo_f16*)W, K, s, eps, bits, cp, cm, wsp, wsm, rp, rm, overflow);
-        else
-            zo_weight_codes_i8_row_kernel<float><<<N, 256, 0, st>>>((const float*)W, K, s, eps, bits, cp, cm, wsp, wsm, rp, rm, overflow);
-        return hipGetLastError();
+            return launch_weight_codes_row_t<zo_f16>((const zo_f16*)W, N, K, bits, s, eps, cp, cm, wsp, wsm, rp, rm, overflow, st);
+        return launch_weight_codes_row_t<float>((const float*)W, N, K, bits, s, eps, cp, cm, wsp, wsm, rp, rm, overflow, st);
     }
     hipError_t e = wdtype == ZO_W_F16
         ? launch_weight_codes_t<zo_f16>((const zo_f16*)W, N, K, bits, group, s, eps, cp, cm, wsp, wsm, rpart_p, rpart_m, overflow, st, scale_row_tiles)
