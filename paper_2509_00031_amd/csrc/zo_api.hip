@@ -527,15 +527,21 @@ struct fwd {
     zo_status norm_quant(size_t layout::per_branch::*in, bool has_beta, size_t layout::per_branch::** used)
     {
         const int d = c->cfg.d_model;
-        if (c->cfg.a_bits >= 16 || !zo_norm_quant_supported(d) || i8_route(next_t)) {
+        if (c->cfg.a_bits >= 16 || !zo_norm_quant_supported(d)) {
             zo_status s_ = norm(in, &layout::per_branch::h, has_beta);
             if (s_ != ZO_OK) return s_;
             return act_quant(&layout::per_branch::h, d, used);
         }
+        const bool i8 = i8_route(next_t);                // integer route: the same kernel leaves signed-byte codes
         prof_scope ps(c, ZO_PROF_ACT_QUANT);
-        for (int b = 0; b < nb; ++b)
-            ZO_HIP(c, zo_launch_norm_quant(at(c->L.br[b].*in), vec(b, 0), has_beta ? vec(b, 1) : nullptr, at(c->L.br[b].hq),
-                                           M, d, 1e-5f, c->cfg.a_bits, c->cfg.a_sym, dt(), sm_delta(b), sm_inv(b), c->st));
+        for (int b = 0; b < nb; ++b) {
+            char* hq = at(c->L.br[b].hq);
+            ZO_HIP(c, zo_launch_norm_quant(at(c->L.br[b].*in), vec(b, 0), has_beta ? vec(b, 1) : nullptr, hq,
+                                           M, d, 1e-5f, c->cfg.a_bits, c->cfg.a_sym, dt(), sm_delta(b), sm_inv(b), c->st,
+                                           i8 ? (int8_t*)hq : nullptr, i8 ? (float*)(hq + i8_xs_off()) : nullptr,
+                                           i8 ? (float*)(hq + i8_xs_off()) + M : nullptr));
+        }
+        x_codes = i8;
         *used = &layout::per_branch::hq;
         return ZO_OK;
     }
@@ -543,16 +549,20 @@ struct fwd {
     zo_status act_quant(size_t layout::per_branch::*in, int K, size_t layout::per_branch::** used)
     {
         if (c->cfg.a_bits >= 16) { *used = in; return ZO_OK; }
-        if (i8_route(next_t)) return act_codes(in, K, used);
+        const bool i8 = i8_route(next_t);
+        if (i8 && !zo_swiglu_quant_supported(K)) return act_codes(in, K, used);
         prof_scope ps(c, ZO_PROF_ACT_QUANT);
         for (int b = 0; b < nb; ++b) {
+            char* hq = at(c->L.br[b].hq);
             if (zo_swiglu_quant_supported(K))             // row kept in registers: one read and one write per element
-                ZO_HIP(c, zo_launch_swiglu_quant(at(c->L.br[b].*in), nullptr, at(c->L.br[b].hq), M, K, K, c->cfg.a_bits, c->cfg.a_sym,
-                                                 dt(), sm_delta(b), sm_inv(b), c->st));
+                ZO_HIP(c, zo_launch_swiglu_quant(at(c->L.br[b].*in), nullptr, hq, M, K, K, c->cfg.a_bits, c->cfg.a_sym,
+                                                 dt(), sm_delta(b), sm_inv(b), c->st, i8 ? (int8_t*)hq : nullptr,
+                                                 i8 ? (float*)(hq + i8_xs_off()) : nullptr, i8 ? (float*)(hq + i8_xs_off()) + M : nullptr));
             else
                 ZO_HIP(c, zo_launch_fq_act(at(c->L.br[b].*in), at(c->L.br[b].hq), M, K, c->cfg.a_bits, c->cfg.a_sym, dt(),
                                            nullptr, nullptr, nullptr, sm_delta(b), sm_inv(b), c->st));
         }
+        x_codes = i8;
         *used = &layout::per_branch::hq;
         return ZO_OK;
     }
@@ -961,13 +971,17 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
             ZO_TRY(linear(f, sh));
             ZO_TRY(F.gemm(xin, &PB::gu, 2 * f, d, bias, false, false, false, sh));
             ZO_TRY(F.smooth_prepare(t));                 // w_down: its input is the SwiGLU output
-            act_done = cfg.a_bits < 16 && zo_swiglu_quant_supported(f) && !F.i8_route(t);
+            act_done = cfg.a_bits < 16 && zo_swiglu_quant_supported(f);
+            const bool i8 = act_done && F.i8_route(t);   // integer route: the same kernel leaves signed-byte codes
             prof_scope ps(c, act_done ? ZO_PROF_ACT_QUANT : ZO_PROF_OTHER);
             for (int b = 0; b < nb; ++b) {
                 char* gu = F.at(c->L.br[b].gu);
+                char* hq = F.at(c->L.br[b].hq);
                 if (act_done)
-                    ZO_HIP(c, zo_launch_swiglu_quant(gu, gu + (size_t)f * ts, F.at(c->L.br[b].hq), M, f, 2 * f,
-                                                     cfg.a_bits, cfg.a_sym, dt, F.sm_delta(b), F.sm_inv(b), c->st));
+                    ZO_HIP(c, zo_launch_swiglu_quant(gu, gu + (size_t)f * ts, hq, M, f, 2 * f,
+                                                     cfg.a_bits, cfg.a_sym, dt, F.sm_delta(b), F.sm_inv(b), c->st,
+                                                     i8 ? (int8_t*)hq : nullptr, i8 ? (float*)(hq + F.i8_xs_off()) : nullptr,
+                                                     i8 ? (float*)(hq + F.i8_xs_off()) + M : nullptr));
                 else
                     ZO_HIP(c, zo_launch_swiglu(gu, gu + (size_t)f * ts, F.at(c->L.br[b].act), M, f, 2 * f, dt, c->st));
             }
@@ -978,7 +992,7 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
             ZO_TRY(F.gemm(xin, &PB::act, f, d, true, true, false, false, sh));
             ZO_TRY(F.smooth_prepare(t));                 // fc2
         }
-        if (act_done) xin = &PB::hq;
+        if (act_done) { xin = &PB::hq; F.x_codes = F.i8_route(t); }
         else ZO_TRY(F.act_quant(&PB::act, f, &xin));
         sh = F.frozen(t);
         F.gemm_N = d;

@@ -284,6 +284,17 @@ ZO_DEV float zo_code(const zo_qparams& q, float x)
     return __builtin_amdgcn_fmed3f(c, q.qn, q.qp);       // clamp to [qn, qp] in one instruction
 }
 ZO_DEV float zo_dequant(const zo_qparams& q, float code) { return (code - q.zp) * q.step; }
+// eight codes minus `off` (the re-centring of the integer route: the results lie in [-128, 127]) as eight signed bytes
+ZO_DEV uint2 zo_pack_codes8(const zo_qparams& q, const float v[8], float off)
+{
+    uint32_t w[2] = {0u, 0u};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int cd = (int)(zo_code(q, v[i]) - off);
+        w[i >> 2] |= ((uint32_t)cd & 0xFFu) << (8 * (i & 3));
+    }
+    return make_uint2(w[0], w[1]);
+}
 
 // ---------------------------------------------------------------------------------------------
 // wavefront helpers (64 lanes)

@@ -165,11 +165,13 @@ hipError_t zo_launch_norm(const void* x, const float* gamma, const float* beta, 
 bool zo_norm_quant_supported(int32_t d);
 hipError_t zo_launch_norm_quant(const void* x, const float* gamma, const float* beta, void* xhat, int32_t M, int32_t d,
                                 float eps, int32_t bits, int32_t sym, int dtype,
-                                const float* sm_delta, const float* sm_inv, hipStream_t st);
+                                const float* sm_delta, const float* sm_inv, hipStream_t st,
+                                int8_t* codes = nullptr, float* xs = nullptr, float* xo = nullptr);   // codes != NULL: integer route
 // SwiGLU fused with the per-token quantizer: cols <= 16384; up = NULL: the quantizer alone on the rows of `gate`
 bool zo_swiglu_quant_supported(int32_t cols);
 hipError_t zo_launch_swiglu_quant(const void* gate, const void* up, void* xhat, int64_t rows, int32_t cols, int64_t in_stride,
-                                  int32_t bits, int32_t sym, int dtype, const float* sm_delta, const float* sm_inv, hipStream_t st);
+                                  int32_t bits, int32_t sym, int dtype, const float* sm_delta, const float* sm_inv, hipStream_t st,
+                                  int8_t* codes = nullptr, float* xs = nullptr, float* xo = nullptr);   // codes != NULL: integer route
 hipError_t zo_launch_rope(void* q, void* k, const float* cos_tab, const float* sin_tab,
                           int32_t M, int32_t S, int32_t H, int32_t dh, int64_t row_stride, int dtype, hipStream_t st);
 hipError_t zo_launch_attention(const void* q, const void* k, const void* v, void* out,

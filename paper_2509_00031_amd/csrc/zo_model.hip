@@ -145,7 +145,8 @@ template <typename T, int NC, int WPR>
 __global__ __launch_bounds__(256) void zo_norm_quant_kernel(const T* __restrict__ x, const float* __restrict__ gamma,
                                                             const float* __restrict__ beta, T* __restrict__ xhat, int M, int d,
                                                             float eps, int bits, int sym,
-                                                            const float* __restrict__ sm_delta, const float* __restrict__ sm_inv)
+                                                            const float* __restrict__ sm_delta, const float* __restrict__ sm_inv,
+                                                            int8_t* __restrict__ codes, float* __restrict__ xs, float* __restrict__ xo)
 {
     __shared__ float red[5][4];
     constexpr int TPR = 64 * WPR;                    // threads per row
@@ -235,6 +236,17 @@ __global__ __launch_bounds__(256) void zo_norm_quant_kernel(const T* __restrict_
         mx = fmaxf(fmaxf(red[4][0], red[4][1]), fmaxf(red[4][2], red[4][3]));
     }
     const zo_qparams q = sym ? zo_qparams_sym(mx, bits) : zo_qparams_asym(mn, mx, bits);
+    if (codes) {
+        // integer route: the codes themselves, re-centred into a signed byte, and the row's step and offset - zero point
+        const float off = sym ? 0.0f : (float)(1 << (bits - 1));
+        if (tr == 0) { xs[row] = q.step; xo[row] = off - q.zp; }
+#pragma unroll
+        for (int i = 0; i < NC; ++i) {
+            const int c = tr * 8 + 8 * TPR * i;
+            if (c < d) *reinterpret_cast<uint2*>(codes + (int64_t)row * d + c) = zo_pack_codes8(q, v[i], off);
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
         const int c = tr * 8 + 8 * TPR * i;
@@ -251,11 +263,12 @@ bool zo_norm_quant_supported(int32_t d) { return d > 0 && (d & 7) == 0 && d <= 8
 
 hipError_t zo_launch_norm_quant(const void* x, const float* gamma, const float* beta, void* xhat, int32_t M, int32_t d,
                                 float eps, int32_t bits, int32_t sym, int dtype,
-                                const float* sm_delta, const float* sm_inv, hipStream_t st)
+                                const float* sm_delta, const float* sm_inv, hipStream_t st, int8_t* codes, float* xs, float* xo)
 {
     if (M == 0) return hipSuccess;
+    if (codes && (!xs || !xo)) return hipErrorInvalidValue;
     // rows up to 1024 elements: one wavefront each; longer ones: one workgroup each
-#define ZO_NQ(T, NC, WPR) zo_norm_quant_kernel<T, NC, WPR><<<(WPR == 4 ? M : (M + 3) / 4), 256, 0, st>>>((const T*)x, gamma, beta, (T*)xhat, M, d, eps, bits, sym, sm_delta, sm_inv)
+#define ZO_NQ(T, NC, WPR) zo_norm_quant_kernel<T, NC, WPR><<<(WPR == 4 ? M : (M + 3) / 4), 256, 0, st>>>((const T*)x, gamma, beta, (T*)xhat, M, d, eps, bits, sym, sm_delta, sm_inv, codes, xs, xo)
 #define ZO_NQ_ALL(T)                          \
     if (d <= 512) ZO_NQ(T, 1, 1);             \
     else if (d <= 1024) ZO_NQ(T, 2, 1);       \
@@ -431,7 +444,8 @@ hipError_t zo_launch_swiglu(const void* gate, const void* up, void* out, int64_t
 template <typename T, int NC, int NT = 256>
 __global__ __launch_bounds__(NT) void zo_swiglu_quant_kernel(const T* __restrict__ gate, const T* __restrict__ up, T* __restrict__ xhat,
                                                               int cols, int64_t in_stride, int bits, int sym,
-                                                              const float* __restrict__ sm_delta, const float* __restrict__ sm_inv)
+                                                              const float* __restrict__ sm_delta, const float* __restrict__ sm_inv,
+                                                              int8_t* __restrict__ codes, float* __restrict__ xs, float* __restrict__ xo)
 {
     __shared__ float red[2][NT / 64];
     const int64_t row = blockIdx.x;
@@ -464,6 +478,16 @@ __global__ __launch_bounds__(NT) void zo_swiglu_quant_kernel(const T* __restrict
 #pragma unroll
     for (int w = 1; w < NT / 64; ++w) { mn = fminf(mn, red[0][w]); mx = fmaxf(mx, red[1][w]); }
     const zo_qparams q = sym ? zo_qparams_sym(mx, bits) : zo_qparams_asym(mn, mx, bits);
+    if (codes) {                                     // integer route (see zo_norm_quant_kernel)
+        const float off = sym ? 0.0f : (float)(1 << (bits - 1));
+        if (threadIdx.x == 0) { xs[row] = q.step; xo[row] = off - q.zp; }
+#pragma unroll
+        for (int i = 0; i < NC; ++i) {
+            const int c = threadIdx.x * 8 + NT * 8 * i;
+            if (c < cols) *reinterpret_cast<uint2*>(codes + row * cols + c) = zo_pack_codes8(q, v[i], off);
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
         const int c = threadIdx.x * 8 + NT * 8 * i;
@@ -479,12 +503,14 @@ __global__ __launch_bounds__(NT) void zo_swiglu_quant_kernel(const T* __restrict
 bool zo_swiglu_quant_supported(int32_t cols) { return cols > 0 && (cols & 7) == 0 && cols <= 16384; }
 
 hipError_t zo_launch_swiglu_quant(const void* gate, const void* up, void* xhat, int64_t rows, int32_t cols, int64_t in_stride,
-                                  int32_t bits, int32_t sym, int dtype, const float* sm_delta, const float* sm_inv, hipStream_t st)
+                                  int32_t bits, int32_t sym, int dtype, const float* sm_delta, const float* sm_inv, hipStream_t st,
+                                  int8_t* codes, float* xs, float* xo)
 {
     if (rows == 0) return hipSuccess;
+    if (codes && (!xs || !xo)) return hipErrorInvalidValue;
     if (rows > 0x7FFFFFFF) return hipErrorInvalidValue;
-#define ZO_SQ(T, NC) zo_swiglu_quant_kernel<T, NC><<<(int)rows, 256, 0, st>>>((const T*)gate, (const T*)up, (T*)xhat, cols, in_stride, bits, sym, sm_delta, sm_inv)
-#define ZO_SQW(T, NC) zo_swiglu_quant_kernel<T, NC, 1024><<<(int)rows, 1024, 0, st>>>((const T*)gate, (const T*)up, (T*)xhat, cols, in_stride, bits, sym, sm_delta, sm_inv)
+#define ZO_SQ(T, NC) zo_swiglu_quant_kernel<T, NC><<<(int)rows, 256, 0, st>>>((const T*)gate, (const T*)up, (T*)xhat, cols, in_stride, bits, sym, sm_delta, sm_inv, codes, xs, xo)
+#define ZO_SQW(T, NC) zo_swiglu_quant_kernel<T, NC, 1024><<<(int)rows, 1024, 0, st>>>((const T*)gate, (const T*)up, (T*)xhat, cols, in_stride, bits, sym, sm_delta, sm_inv, codes, xs, xo)
     if (rows <= 16 && cols > 2048) {                 // too few rows to fill the chip anyway: more lanes per row
         if (dtype == ZO_T_BF16) { if (cols <= 8192) ZO_SQW(zo_bf16, 1); else ZO_SQW(zo_bf16, 2); }
         else { if (cols <= 8192) ZO_SQW(float, 1); else ZO_SQW(float, 2); }
