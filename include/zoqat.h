@@ -284,7 +284,8 @@ zo_status zo_linear_fakequant(const void* X_dev, const float* W_dev, const float
  *                    y[t][n] = step_x[t] * sum_g step_w[n][g] * sum_{k in g} (qx[t][k] - zx[t]) (qw[n][k] - zw[n][g])
  *                i.e. x^ w^^T with NEITHER operand rounded -- the inner sums are exact integers, one fp32 multiply-add per
  *                weight group.  Needs weight and activation codes (1 <= w_bits <= 7, 2 <= a_bits <= 8), K a multiple of
- *                128, w_group 64 or a multiple of 128 up to 512 (0 = K); otherwise ZO_EUNSUPPORTED.  A weight group whose
+ *                128, w_group 64, 128, 256 or 512, or 0 / K = per channel (K <= 65536: the integer sums then run over all of K
+ *                inside the matrix unit and the loop has no rescale at all); otherwise ZO_EUNSUPPORTED.  A weight group whose
  *                |qw - zw| exceeds 127 (a group far from zero compared with its own range: the zero point is not clamped)
  *                does not fit a signed byte: its operands are saturated and *flag_dev is OR-ed with 1 -- the caller clears
  *                the flag before the call and must discard Y if it is set.
@@ -292,7 +293,7 @@ zo_status zo_linear_fakequant(const void* X_dev, const float* W_dev, const float
  *   scratch dev, zo_linear_mma_scratch_bytes(...) bytes; offsets_host (may be NULL) receives, for ZO_MMA_INT8, the byte
  *   offsets inside the scratch of: activation codes qx - O as int8 [M][K] (O = 2^(a_bits-1), 0 if a_sym), token steps fp32 [M],
  *   O - zx fp32 [M], weight operands qw - zw int8 [N][K], weight steps (kernel order), r[n] = sum_g step_w sum_k (qw - zw)
- *   fp32 [N], its per-group parts fp32 [N][K/w_group], end -- for parity tests. */
+ *   fp32 [N], its per-group parts fp32 [N][K/w_group] (not written per channel), end -- for parity tests. */
 enum { ZO_MMA_BF16 = 0, ZO_MMA_INT8 = 1 };
 size_t zo_linear_mma_scratch_bytes(int32_t M, int32_t N, int32_t K, int32_t w_group, int32_t dtype, int32_t mma, size_t* offsets_host);
 zo_status zo_linear_fakequant_mma(const void* X_dev, const float* W_dev, const float* bias_dev, void* Y_dev,

@@ -193,7 +193,7 @@ hipError_t zo_launch_projected_grad(const float* loss2, float eps, const float l
                                     hipStream_t st);
 
 // ---- quantized linear on the integer codes (int8 matrix instructions) ----------------------------
-// y = step_x (sum_g step_w S_g + (O - zx) r): see zo_i8.hip.  w_group 64 or a multiple of 128 (at most 512), K a multiple of 128.
+// y = step_x (sum_g step_w S_g + (O - zx) r): see zo_i8.hip.  w_group 64, 128, 256, 512 or 0 / K (per channel), K a multiple of 128.
 bool zo_i8_supported(int32_t M, int32_t N, int32_t K, int32_t w_bits, int32_t w_group, int32_t a_bits);
 size_t zo_i8_scale_floats(int32_t N, int32_t K, int32_t w_group);       // floats of one branch's array of weight steps
 hipError_t zo_launch_act_codes_i8(const void* X, int8_t* codes, float* xs, float* xo, int32_t M, int32_t K, int32_t bits, int32_t sym,
