@@ -173,3 +173,31 @@ def test_generator_at_7b_widths_one_layer(a_bits):
         assert np.median(err[S:]) < (2e-2 if a_bits == 8 else 0.2), (j, err[S:])
     assert not cache[0, :, S + n_new:].any()
     ctx.close()
+
+
+@pytest.mark.parametrize("arch,act_dtype", [(2, 0), (1, 0), (2, 1)])
+def test_cached_steps_over_several_ranges_of_rows(arch, act_dtype):
+    """Enough cached rows for the decoding step's attention to split them into ranges (64-wide heads: 32 row groups of 8
+    lanes, ranges of 64 rows), with learned positions (no rotation in the kernel) and with the rotary embedding, fp32 and
+    bf16 storage: logits of cached steps and the appended cache rows against the oracle."""
+    torch, zo = gpu()
+    S, S_max, n_new = 150, 160, 3
+    ocfg, o_params, trainable, ctx = _model(zo, torch, arch, act_dtype, False, S_max, d_model=256, n_heads=4, a_bits=16, d_ffn=256,
+                                            n_layers=1, wscale=1.0)
+    prompt = synth.token_ids(1, S, 512, 1408)[0]
+    extra = synth.token_ids(1, n_new, 512, 1409)[0]
+    kv = ctx.new_kv_cache(S_max)
+    okv = orc.new_kv(ocfg)
+    ctx.zo_prefill(to_dev(prompt, torch), kv, S_max)
+    orc.infer_prefill(ocfg, o_params, prompt, okv, trainable)
+    for i in range(n_new):
+        got = ctx.zo_decode(to_dev(extra[i:i + 1], torch), S + i, kv, S_max).cpu().numpy()
+        ref = orc.infer_decode(ocfg, o_params, extra[i], okv, trainable)
+        _check_logits(got, ref, act_dtype, i)
+    td = torch.bfloat16 if act_dtype else torch.float32
+    cache = kv.view(td).float().cpu().numpy().reshape(1, 2, S_max, 256)
+    for j in range(2):
+        want = okv[0][j]
+        err = np.linalg.norm(cache[0, j, S:S + n_new] - want[S:]) / np.linalg.norm(want[S:])
+        assert err <= (2e-2 if act_dtype else 1e-4), (j, err)
+    ctx.close()
