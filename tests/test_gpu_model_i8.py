@@ -115,3 +115,23 @@ def test_operands_that_do_not_fit_a_byte_poison_the_losses():
     out = ctx.zo_forward_quant(ids, None, 4, 64, seed=1, eps_signed=0.0).cpu().numpy()
     assert np.isfinite(out[0])
     ctx.close()
+
+
+def test_integer_route_with_binary16_masters():
+    """Masters kept in IEEE binary16 (per-channel steps, so the row quantizer's register-held form reads them)."""
+    torch, zo = gpu()
+    B, S = 4, 64
+    base = dict(n_layers=1, d_model=256, n_heads=4, d_ffn=512, vocab=512, max_seq=S, w_bits=4, w_group=0, a_bits=8)
+    ocfg = orc.Config(1, act_dtype=1, mma=1, **base)
+    cfg = zo.make_config(1, act_dtype=1, mma=zo.MMA_INT8, master_dtype=zo.MASTER_F16, **base)
+    params = [p.astype(np.float16) for p in synth.model_params(orc.param_shapes(ocfg), 2330)]
+    ids = synth.token_ids(B, S, 512, 2331)
+    lp, lm, g = orc.zo_step(ocfg, [p.copy() for p in params], 5, EPS, 1e-3, ids=ids, stochastic=False)
+    gp = [to_dev(p, torch) for p in params]
+    ctx = zo.Context(cfg, gp, B, S)
+    out = ctx.zo_step(to_dev(ids, torch), None, B, S, seed=5, eps=EPS, lr=1e-3).cpu().numpy()
+    assert ctx.zo_debug_routes() & zo.ROUTE_INT8_MMA
+    assert abs(out[0] - lp) <= 1e-3 * abs(lp) and abs(out[1] - lm) <= 1e-3 * abs(lm), (out, lp, lm)
+    want = orc.update(params[2].copy(), 5, 2, np.float32(out[3]), False)
+    assert np.array_equal(gp[2].cpu().numpy().view(np.uint16), want.view(np.uint16))
+    ctx.close()
