@@ -223,6 +223,36 @@ def bench_generate(args, w):
     print(json.dumps(res))
 
 
+def measured_ceilings(torch, zo):
+    """What this card sustains with nothing in the way, measured in the same process (events on the launch stream): bf16
+    matrix instructions on register-resident operands (zo_probe_mfma_only; the power-managed clock depends on the operand
+    data, so both random and all-zero operands are timed), and an in-place read-modify-write stream over 1 GiB."""
+    out = {}
+    buf = None
+    for name, zero in (("mfma_only_random_operands_tflops", 0), ("mfma_only_zero_operands_tflops", 1)):
+        buf, _ = zo.zo_probe_mfma_only(512, 500, zero, buf)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        buf, flop = zo.zo_probe_mfma_only(512, 20000, zero, buf)
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    x = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+    x.mul_(1.0)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        x.mul_(1.0)
+    e1.record()
+    torch.cuda.synchronize()
+    out["inplace_stream_gbs"] = 5 * 2.0 * x.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del x, buf
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -257,6 +287,7 @@ def main():
         return bench_generate(args, w)
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+    ceilings = None if args.no_profile else measured_ceilings(torch, zo)
     arch = zo.ARCH_LLAMA if w["arch"] == "llama" else zo.ARCH_OPT
     cfg = zo.make_config(arch, n_layers=w["n_layers"], d_model=w["d_model"], n_heads=w["n_heads"], d_ffn=w["d_ffn"],
                          vocab=w["vocab"], max_seq=w["S"], w_bits=w["w_bits"], w_group=w["w_group"], a_bits=w["a_bits"],
@@ -401,6 +432,13 @@ def main():
                                 "frac": upd_gbs / PEAK_HBM_GBS if upd_gbs else None, "bytes_per_param": upd_bpp,
                                 "ms_per_step": upd_ms / max(upd_groups, 1)}
         res["breakdown_ms_per_step"] = {k: v[0] / BREAKDOWN_STEPS for k, v in prof_all.items()}
+        if ceilings:
+            # next to the published peaks: the same figures against what the card sustains in this process with nothing in the way
+            res["measured_ceilings"] = ceilings
+            if res["roofline"]["bound"] == "mfma" and args.mma == "bf16":
+                res["roofline"]["frac_of_measured_mfma_only"] = res["roofline"]["achieved"] / ceilings["mfma_only_random_operands_tflops"]
+            if upd_gbs:
+                res["update_kernel"]["frac_of_measured_stream"] = upd_gbs / ceilings["inplace_stream_gbs"]
         if res["roofline"]["bound"] == "mfma":
             # The weights are quantized once per step into the operand buffers (the prologue of every fake-quantized GEMM):
             # "frac" is the GEMM kernel alone, "frac_with_prologue" counts 2 M N K against GEMM time + weight-quantizer time

@@ -198,6 +198,12 @@ zo_status zo_profile_end(zo_ctx* ctx, float* ms_host, int32_t* launches_host);
 
 /* out[j] = word (j & 3) of Philox4x32-10 block (j >> 2) of the stream (seed, tensor_id). */
 zo_status zo_debug_philox_u32(uint64_t seed, int32_t tensor_id, int64_t nwords, uint32_t* out_dev, void* hip_stream);
+/* Measurement probe (for benchmarks; no part of the step -- it serves the measurement contract, not a passage of the paper):
+ * `workgroups` workgroups of four waves issue iters * 8 bf16 matrix instructions (32 x 32 x 16) per wave on register-resident
+ * operands, with no memory traffic: 4 * 8 * 32768 * iters flop per workgroup.  zero_operands = 1: all-zero operands; 0: random
+ * mantissas (the power-managed clock depends on the data).  out_dev: dev fp32 [workgroups * 256], receives the accumulator sums.
+ * The caller times the launch on hip_stream. */
+zo_status zo_probe_mfma_only(float* out_dev, int32_t workgroups, int32_t iters, int32_t zero_operands, void* hip_stream);
 /* out[i] = u(seed, tensor_id, start + i), i < numel: the perturbation of Eq. 2. */
 zo_status zo_debug_normal(uint64_t seed, int32_t tensor_id, int64_t start, int64_t numel, float* out_dev, void* hip_stream);
 

@@ -22,7 +22,7 @@ MASTER_F32, MASTER_F16 = 0, 1
 ROUTE_FUSED_SMALL_M, ROUTE_FUSED_INT4, ROUTE_SWIGLU_IN_GEMM, ROUTE_ROPE_IN_GEMM, ROUTE_CE_IN_GEMM, ROUTE_GEMM_SPLIT_K, ROUTE_INT8_MMA = 1, 2, 4, 8, 16, 32, 64
 
 EXPORTS = ["zo_num_params", "zo_param_numel", "zo_workspace_bytes", "zo_init", "zo_destroy", "zo_last_error",
-           "zo_forward_quant", "zo_step", "zo_update", "zo_debug_philox_u32", "zo_debug_normal", "zo_update_tensor",
+           "zo_forward_quant", "zo_step", "zo_update", "zo_probe_mfma_only", "zo_debug_philox_u32", "zo_debug_normal", "zo_update_tensor",
            "zo_debug_quant_weight", "zo_debug_quant_act", "zo_linear_scratch_bytes", "zo_linear_fakequant",
            "zo_gemm_nt", "zo_debug_buffer", "zo_profile_begin", "zo_profile_end", "zo_attention_causal",
            "zo_attention_scratch_bytes", "zo_pack_weight_int4", "zo_attach_frozen_int4", "zo_linear_frozen_int4", "zo_gemm_nt_fused", "zo_init_learned_params", "zo_step_groups", "zo_update_groups",
@@ -66,6 +66,7 @@ _lib.zo_forward_quant.argtypes = [_vp, _vp, _vp, _i32, _i32, _u64, _f32, _vp]
 _lib.zo_step.argtypes = [_vp, _vp, _vp, _i32, _i32, _u64, _f32, _f32, _vp]
 _lib.zo_update.argtypes = [_vp, _u64, _vp, _f32]
 _lib.zo_debug_philox_u32.argtypes = [_u64, _i32, _i64, _vp, _vp]
+_lib.zo_probe_mfma_only.argtypes = [_vp, _i32, _i32, _i32, _vp]
 _lib.zo_debug_normal.argtypes = [_u64, _i32, _i64, _i64, _vp, _vp]
 _lib.zo_update_tensor.argtypes = [_vp, _i64, _u64, _i32, _vp, _f32, _vp]
 _lib.zo_debug_quant_weight.argtypes = [_vp, _i32, _i32, _i32, _i32, _u64, _i32, _f32, _i32, _vp, _vp, _vp, _vp, _vp]
@@ -324,6 +325,14 @@ class Context:
 
 def zo_lr_linear_decay(lr0, t, T):
     return _lib.zo_lr_linear_decay(lr0, t, T)
+
+
+def zo_probe_mfma_only(workgroups, iters, zero_operands, out=None):
+    """Launches the matrix-instruction-only probe on the current stream; returns (out, flop of the launch)."""
+    if out is None:
+        out = torch.empty(workgroups * 256, dtype=torch.float32, device="cuda")
+    _check(_lib.zo_probe_mfma_only(out.data_ptr(), workgroups, iters, int(zero_operands), _stream()), "zo_probe_mfma_only")
+    return out, 4.0 * 8 * 32768 * iters * workgroups
 
 
 def zo_debug_philox_u32(seed, tensor_id, nwords, device="cuda"):

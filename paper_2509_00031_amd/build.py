@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libzoqat.so")
-SOURCES = ["zo_api.hip", "zo_elem.hip", "zo_gemm.hip", "zo_model.hip", "zo_attn.hip", "zo_fused.hip", "zo_i8.hip", "zo_infer.hip"]
+SOURCES = ["zo_api.hip", "zo_elem.hip", "zo_gemm.hip", "zo_model.hip", "zo_attn.hip", "zo_fused.hip", "zo_i8.hip", "zo_infer.hip", "zo_probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option"]
