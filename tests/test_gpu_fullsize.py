@@ -75,6 +75,28 @@ def test_gate_up_gemm_with_swiglu_full_shape_sampled_outputs():
     assert np.all(np.abs(got - ref) <= 2.0 ** -6 * np.abs(ref) + 2e-2)
 
 
+@pytest.mark.parametrize("group", [0, 64])
+def test_integer_route_linear_full_shape_sampled_outputs(group):
+    """One quantized linear of the benchmark's q | k | v shape (8192 x 12288 x 4096, W4A8) on the integer route -- per-channel
+    steps (integer accumulation over all of K inside the matrix unit) and groups of 64 (rescale per slice) -- at eps = 0, so
+    that sampled rows of W quantize as they do inside the whole matrix: sampled outputs against the un-rounded operand
+    product of the oracle's codes."""
+    torch, zo = gpu()
+    N, K = 12288, 4096
+    X = orc.bf16_round(synth.activations((M, K), 95))
+    W = synth.weights((N, K), 96)
+    Y = zo.zo_linear_fakequant_mma(to_dev(X, torch, torch.bfloat16), to_dev(W, torch), 4, group, 8, 0, 0, 0.0, out_f32=True)
+    rng = synth.rng(97)
+    ms = np.concatenate([[0, 255, 256, M - 1], rng.integers(0, M, 28)])
+    ns = np.concatenate([[0, 255, 256, N - 1], rng.integers(0, N, 28)])
+    qa = orc.fakequant_act(X[ms], 8, False)
+    qw = orc.fakequant_weight(W[ns], 4, group, eps_signed=0.0)
+    ref = qa["xhat"].astype(np.float64) @ qw["what"].astype(np.float64).T
+    mag = np.abs(qa["xhat"].astype(np.float64)) @ np.abs(qw["what"].astype(np.float64)).T
+    got = Y[torch.from_numpy(ms).cuda()][:, torch.from_numpy(ns).cuda()].cpu().numpy()
+    assert np.all(np.abs(got - ref) <= 4e-6 * mag + 1e-30), (np.abs(got - ref) / mag).max()
+
+
 def test_lm_head_loss_full_shape_sampled_rows():
     """The 8192 x 32000 x 4096 lm_head GEMM of the benchmark with the cross entropy in its epilogue: sampled row losses
     against the definition in fp64 (logits of a row: 32000 dot products the host computes one row at a time)."""
