@@ -398,7 +398,9 @@ struct fwd {
             // signed-byte operands of both branches, their steps in the slot layout of the fused operand, r[n]
             const int K = (int)p.cols, G = K / (c->cfg.w_group > 0 ? c->cfg.w_group : K);
             const int n_total = gemm_N > 0 ? gemm_N : (int)p.rows;
-            if ((row0 & 255) || row0 + p.rows > n_total) return fail(c, ZO_EUNSUPPORTED, "integer route: operand block not at a tile boundary");
+            // (SwiGLU: gate and up interleave into one block of 2 f rows starting at row0 = 0)
+            if ((row0 & 255) || row0 + p.rows * (ilv == 1 || ilv == 2 ? 2 : 1) > n_total)
+                return fail(c, ZO_EUNSUPPORTED, "integer route: operand block not at a tile boundary");
             char* w0 = at(c->L.what[0]);
             char* w1 = nb == 2 ? at(c->L.what[1]) : nullptr;
             auto f32at = [&](char* base, size_t off, size_t idx) { return base ? (float*)(base + off) + idx : nullptr; };
@@ -408,7 +410,7 @@ struct fwd {
                                                 f32at(w0, i8_ws_off(), (size_t)row0), f32at(w1, i8_ws_off(), (size_t)row0),
                                                 f32at(w0, i8_wr_off(), (size_t)row0), f32at(w1, i8_wr_off(), (size_t)row0),
                                                 f32at(w0, i8_rpart_off(), (size_t)row0 * G), f32at(w1, i8_rpart_off(), (size_t)row0 * G),
-                                                i8_flag(), c->st, (n_total + 255) / 256));
+                                                i8_flag(), c->st, (n_total + 255) / 256, ilv));
             w_codes = true;
             return ZO_OK;
         }
@@ -453,16 +455,18 @@ struct fwd {
     {
         const zo_config& cfg = c->cfg;
         if (cfg.no_fused || cfg.arch != ZO_ARCH_LLAMA || cfg.learn_smooth) return false;      // smoothing gives these linears a bias
+        if (cfg.d_model / cfg.n_heads != 128 || fused_ok(t_q, true)) return false;
+        if (i8_route(t_q)) return false;                 // (measured slower in the integer GEMM's epilogue than stand-alone)
         if (cfg.w_bits != 0 && !cfg.learn_clip && (cfg.w_group == 0 || cfg.w_group > 512)) return false;
-        if (cfg.d_model / cfg.n_heads != 128 || fused_ok(t_q, true) || i8_route(t_q)) return false;
         return zo_gemm_rope_supported(M, 3 * cfg.d_model, cfg.d_model, dt());
     }
     bool swiglu_in_gemm(int t_gate) const
     {
         const zo_config& cfg = c->cfg;
         if (cfg.no_fused || cfg.arch != ZO_ARCH_LLAMA || cfg.learn_smooth) return false;      // smoothing gives these linears a bias
+        if ((cfg.d_ffn & 31) || fused_ok(t_gate, true) || fused_ok(t_gate + 1, true)) return false;
+        if (i8_route(t_gate)) return dt() == ZO_T_BF16;              // the integer GEMM has the same epilogue (bf16 output)
         if (cfg.w_bits != 0 && !cfg.learn_clip && (cfg.w_group == 0 || cfg.w_group > 512)) return false;
-        if ((cfg.d_ffn & 31) || fused_ok(t_gate, true) || fused_ok(t_gate + 1, true) || i8_route(t_gate)) return false;
         return zo_gemm_swiglu_supported(M, 2 * cfg.d_ffn, cfg.d_model, dt());
     }
     // Eq. 4, activation side of the linears whose input is smoothed by the pair carried by linear `t`:
@@ -696,7 +700,7 @@ struct fwd {
         }
         if (w_codes) {
             w_codes = x_codes = false;
-            if (swiglu || rope || ce_ids || w_shared || (out_f32 && dt() != ZO_T_F32)) return fail(c, ZO_EUNSUPPORTED, "integer route: epilogue");
+            if (ce_ids || w_shared || rope || (out_f32 && dt() != ZO_T_F32)) return fail(c, ZO_EUNSUPPORTED, "integer route: epilogue");
             zo_i8_gemm_args g{};
             char* x0 = at(c->L.br[0].*in);
             char* w0 = at(c->L.what[0]);
@@ -709,6 +713,7 @@ struct fwd {
             g.M = M; g.N = N; g.K = K; g.batch = nb;
             g.sgroup = c->cfg.w_group > 0 ? c->cfg.w_group : K;
             g.relu = relu;
+            g.epi = swiglu ? 1 : 0;
             if (nb == 2) {
                 const int64_t ts_ = (int64_t)zo_tsize(dt());
                 g.strideX = (int64_t)(c->L.br[1].*in - c->L.br[0].*in);
@@ -961,6 +966,7 @@ zo_status run_forward(zo_ctx* c, const void* ids_or_x, const float* target, int 
         if (llama && F.swiglu_in_gemm(t)) {
             // gate and up rows interleaved in the operand buffer; the GEMM writes silu(gate) * up
             sh = F.frozen(t) && F.frozen(t + 1);
+            F.gemm_N = 2 * f;
             ZO_TRY(F.weights(t++, 0, true, sh, 1));
             ZO_TRY(F.weights(t++, 0, true, sh, 2));
             ZO_TRY(F.gemm(xin, &PB::act, 2 * f, d, false, false, false, false, sh, true));

@@ -32,6 +32,15 @@ __host__ __device__ static inline int scale_slot(int n)
     return (c & ~63) + ((c & 15) << 2) + ((c >> 4) & 3);
 }
 
+// Output row of input row n when the rows of a matrix go out interleaved for the GEMM epilogue that pairs channels: ilv = 1 / 2:
+// the gate / up rows of a SwiGLU pair in alternating blocks of 32 channels (gate block, up block of the same channels, ...).
+// The GEMM's 16-channel tiles j and j + 2 of a wave then hold the two partners in the same lane and register.
+__host__ __device__ static inline uint32_t ilv_row(uint32_t n, int ilv)
+{
+    if (ilv == 0) return n;
+    return ((n >> 5) << 6) + (n & 31) + (ilv == 2 ? 32 : 0);
+}
+
 // ---------------------------------------------------------------------------------------------
 // per-token activation quantizer -> signed-byte codes: one wavefront per row, two sweeps
 // ---------------------------------------------------------------------------------------------
@@ -96,6 +105,7 @@ static zo_i8_rowdiv make_rowdiv_i8(int kb)
     return zo_i8_rowdiv{kb, (uint32_t)((((uint64_t)1 << sh) + (uint64_t)kb - 1) / (uint64_t)kb), sh};
 }
 
+// (b: output position of the lane's 8 codes in blocks of 8; n: output row)
 template <int GL>
 __device__ __forceinline__ void weight_codes_branch(const float v[8], int bits, bool active, int lane, int64_t b, uint32_t n, uint32_t g,
                                                     int G, int tiles_n, int8_t* codes, float* ws, float* rpart, int* overflow)
@@ -130,7 +140,7 @@ __device__ __forceinline__ void weight_codes_branch(const float v[8], int bits, 
 template <typename TW, int GL>
 __global__ __launch_bounds__(256) void zo_weight_codes_i8_kernel(const TW* __restrict__ W, int64_t nblk, zo_stream s, float eps, int bits,
                                                                  int8_t* cp, int8_t* cm, float* wsp, float* wsm, float* rp, float* rm,
-                                                                 int* overflow, zo_i8_rowdiv kb, int tiles_n)
+                                                                 int* overflow, zo_i8_rowdiv kb, int tiles_n, int ilv)
 {
     const int lane = threadIdx.x & 63;
     const int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -145,29 +155,33 @@ __global__ __launch_bounds__(256) void zo_weight_codes_i8_kernel(const TW* __res
         for (int i = 0; i < 8; ++i) { z[i] = 0.0f; if (!active) w[i] = 0.0f; }
     }
     const uint32_t n = (uint32_t)(((uint64_t)(uint32_t)b * kb.magic) >> kb.shift);
-    const uint32_t g = ((uint32_t)b - n * (uint32_t)kb.kb) / GL;
+    const uint32_t kblk = (uint32_t)b - n * (uint32_t)kb.kb;
+    const uint32_t g = kblk / GL;
     const int G = kb.kb / GL;
+    const uint32_t no = ilv_row(n, ilv);                      // where the row goes
+    const int64_t ob = (int64_t)no * kb.kb + kblk;
     {
         float v[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) v[i] = __builtin_fmaf(eps, z[i], w[i]);
-        weight_codes_branch<GL>(v, bits, active, lane, b, n, g, G, tiles_n, cp, wsp, rp, overflow);
+        weight_codes_branch<GL>(v, bits, active, lane, ob, no, g, G, tiles_n, cp, wsp, rp, overflow);
     }
     if (cm) {
         float v[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) v[i] = __builtin_fmaf(-eps, z[i], w[i]);
-        weight_codes_branch<GL>(v, bits, active, lane, b, n, g, G, tiles_n, cm, wsm, rm, overflow);
+        weight_codes_branch<GL>(v, bits, active, lane, ob, no, g, G, tiles_n, cm, wsm, rm, overflow);
     }
 }
 
-// r[n] = sum_g rpart[n][g], added in the order of g (one thread per output channel; G is a few dozen)
-__global__ __launch_bounds__(256) void zo_rowsum_kernel(const float* __restrict__ rpart, float* __restrict__ r, int N, int G)
+// r[n] = sum_g rpart[n][g], added in the order of g (one thread per channel of the matrix, at its output row; G is a few dozen)
+__global__ __launch_bounds__(256) void zo_rowsum_kernel(const float* __restrict__ rpart, float* __restrict__ r, int N, int G, int ilv)
 {
-    const int n = blockIdx.x * 256 + threadIdx.x;
-    if (n >= N) return;
+    const int n0 = blockIdx.x * 256 + threadIdx.x;
+    if (n0 >= N) return;
+    const int64_t n = ilv_row((uint32_t)n0, ilv);
     float acc = 0.0f;
-    for (int g = 0; g < G; ++g) acc += rpart[(int64_t)n * G + g];
+    for (int g = 0; g < G; ++g) acc += rpart[n * G + g];
     r[n] = acc;
 }
 
@@ -180,12 +194,13 @@ __global__ __launch_bounds__(256) void zo_rowsum_kernel(const float* __restrict_
 template <typename TW, int NB>
 __global__ __launch_bounds__(256) void zo_weight_codes_i8_row_kernel(const TW* __restrict__ W, int K, zo_stream s, float eps, int bits,
                                                                      int8_t* cp, int8_t* cm, float* wsp, float* wsm, float* rp, float* rm,
-                                                                     int* overflow)
+                                                                     int* overflow, int ilv)
 {
     __shared__ float red[4][4];
     constexpr int HELD = NB > 0 ? NB : 1;
     const int n = blockIdx.x, nb = K / 8;
-    const int64_t b0 = (int64_t)n * nb;
+    const int no = (int)ilv_row((uint32_t)n, ilv);            // where the row goes
+    const int64_t b0 = (int64_t)n * nb, ob0 = (int64_t)no * nb;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sweeps = NB > 0 ? NB : (nb + 255) / 256;
     float wv[HELD][8], zv[HELD][8];
@@ -249,8 +264,8 @@ __global__ __launch_bounds__(256) void zo_weight_codes_i8_row_kernel(const TW* _
                     um[i >> 2] |= ((uint32_t)(int)dm & 0xFFu) << (8 * (i & 3));
                 }
             }
-            *reinterpret_cast<uint2*>(cp + 8 * (b0 + j)) = make_uint2(up[0], up[1]);
-            if (cm) *reinterpret_cast<uint2*>(cm + 8 * (b0 + j)) = make_uint2(um[0], um[1]);
+            *reinterpret_cast<uint2*>(cp + 8 * (ob0 + j)) = make_uint2(up[0], up[1]);
+            if (cm) *reinterpret_cast<uint2*>(cm + 8 * (ob0 + j)) = make_uint2(um[0], um[1]);
         }
     }
     if (over) atomicOr(overflow, 1);
@@ -259,21 +274,21 @@ __global__ __launch_bounds__(256) void zo_weight_codes_i8_row_kernel(const TW* _
     if (lane == 0) { red[wave][0] = sump; red[wave][1] = summ; }
     __syncthreads();
     if (threadIdx.x == 0) {
-        const int slot = (n >> 8) * 256 + scale_slot(n);
+        const int slot = (no >> 8) * 256 + scale_slot(no);
         wsp[slot] = qp.step;
-        rp[n] = qp.step * (((red[0][0] + red[1][0]) + red[2][0]) + red[3][0]);
+        rp[no] = qp.step * (((red[0][0] + red[1][0]) + red[2][0]) + red[3][0]);
         if (cm) {
             wsm[slot] = qm.step;
-            rm[n] = qm.step * (((red[0][1] + red[1][1]) + red[2][1]) + red[3][1]);
+            rm[no] = qm.step * (((red[0][1] + red[1][1]) + red[2][1]) + red[3][1]);
         }
     }
 }
 
 template <typename TW>
 static hipError_t launch_weight_codes_row_t(const TW* W, int32_t N, int32_t K, int32_t bits, zo_stream s, float eps, int8_t* cp, int8_t* cm,
-                                            float* wsp, float* wsm, float* rp, float* rm, int* overflow, hipStream_t st)
+                                            float* wsp, float* wsm, float* rp, float* rm, int* overflow, hipStream_t st, int ilv)
 {
-#define ZO_ROWQ(NB) zo_weight_codes_i8_row_kernel<TW, NB><<<N, 256, 0, st>>>(W, K, s, eps, bits, cp, cm, wsp, wsm, rp, rm, overflow)
+#define ZO_ROWQ(NB) zo_weight_codes_i8_row_kernel<TW, NB><<<N, 256, 0, st>>>(W, K, s, eps, bits, cp, cm, wsp, wsm, rp, rm, overflow, ilv)
     if (K <= 4096) ZO_ROWQ(2); else if (K <= 8192) ZO_ROWQ(4); else if (K <= 12288) ZO_ROWQ(6); else if (K <= 16384) ZO_ROWQ(8); else ZO_ROWQ(0);
 #undef ZO_ROWQ
     return hipGetLastError();
@@ -297,7 +312,7 @@ size_t zo_i8_scale_floats(int32_t N, int32_t K, int32_t w_group)
 template <typename TW>
 static hipError_t launch_weight_codes_t(const TW* W, int32_t N, int32_t K, int32_t bits, int32_t group, zo_stream s, float eps, int8_t* cp,
                                         int8_t* cm, float* wsp, float* wsm, float* rpp, float* rpm, int* overflow, hipStream_t st,
-                                        int scale_row_tiles)
+                                        int scale_row_tiles, int ilv)
 {
     const int kb = K / 8;
     const int64_t nblk = (int64_t)N * kb;
@@ -309,10 +324,10 @@ static hipError_t launch_weight_codes_t(const TW* W, int32_t N, int32_t K, int32
     // the block's first tile inside the row of steps of group 0)
     const int tiles_n = scale_row_tiles > 0 ? scale_row_tiles : (N + 255) / 256;
     switch (group / 8) {
-        case 8:  zo_weight_codes_i8_kernel<TW, 8><<<grid, 256, 0, st>>>(W, nblk, s, eps, bits, cp, cm, wsp, wsm, rpp, rpm, overflow, rd, tiles_n); break;
-        case 16: zo_weight_codes_i8_kernel<TW, 16><<<grid, 256, 0, st>>>(W, nblk, s, eps, bits, cp, cm, wsp, wsm, rpp, rpm, overflow, rd, tiles_n); break;
-        case 32: zo_weight_codes_i8_kernel<TW, 32><<<grid, 256, 0, st>>>(W, nblk, s, eps, bits, cp, cm, wsp, wsm, rpp, rpm, overflow, rd, tiles_n); break;
-        case 64: zo_weight_codes_i8_kernel<TW, 64><<<grid, 256, 0, st>>>(W, nblk, s, eps, bits, cp, cm, wsp, wsm, rpp, rpm, overflow, rd, tiles_n); break;
+        case 8:  zo_weight_codes_i8_kernel<TW, 8><<<grid, 256, 0, st>>>(W, nblk, s, eps, bits, cp, cm, wsp, wsm, rpp, rpm, overflow, rd, tiles_n, ilv); break;
+        case 16: zo_weight_codes_i8_kernel<TW, 16><<<grid, 256, 0, st>>>(W, nblk, s, eps, bits, cp, cm, wsp, wsm, rpp, rpm, overflow, rd, tiles_n, ilv); break;
+        case 32: zo_weight_codes_i8_kernel<TW, 32><<<grid, 256, 0, st>>>(W, nblk, s, eps, bits, cp, cm, wsp, wsm, rpp, rpm, overflow, rd, tiles_n, ilv); break;
+        case 64: zo_weight_codes_i8_kernel<TW, 64><<<grid, 256, 0, st>>>(W, nblk, s, eps, bits, cp, cm, wsp, wsm, rpp, rpm, overflow, rd, tiles_n, ilv); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -322,23 +337,24 @@ static hipError_t launch_weight_codes_t(const TW* W, int32_t N, int32_t K, int32
 // per branch.  *overflow (device int) is OR-ed with 1 if some |qw - zw| did not fit a signed byte.
 hipError_t zo_launch_weight_codes_i8(const void* W, int32_t N, int32_t K, int32_t bits, int32_t group, uint64_t seed, int32_t tid, float eps,
                                      int wdtype, int8_t* cp, int8_t* cm, float* wsp, float* wsm, float* rp, float* rm, float* rpart_p,
-                                     float* rpart_m, int* overflow, hipStream_t st, int32_t scale_row_tiles)
+                                     float* rpart_m, int* overflow, hipStream_t st, int32_t scale_row_tiles, int32_t ilv)
 {
+    if (ilv < 0 || ilv > 2 || (ilv != 0 && (N & 31))) return hipErrorInvalidValue;
     if (group == 0) group = K;
     const zo_stream s = make_stream_i8(seed, tid);
     if (group == K) {                                                               // per channel
         if (N == 0) return hipSuccess;
         if (wdtype == ZO_W_F16)
-            return launch_weight_codes_row_t<zo_f16>((const zo_f16*)W, N, K, bits, s, eps, cp, cm, wsp, wsm, rp, rm, overflow, st);
-        return launch_weight_codes_row_t<float>((const float*)W, N, K, bits, s, eps, cp, cm, wsp, wsm, rp, rm, overflow, st);
+            return launch_weight_codes_row_t<zo_f16>((const zo_f16*)W, N, K, bits, s, eps, cp, cm, wsp, wsm, rp, rm, overflow, st, ilv);
+        return launch_weight_codes_row_t<float>((const float*)W, N, K, bits, s, eps, cp, cm, wsp, wsm, rp, rm, overflow, st, ilv);
     }
     hipError_t e = wdtype == ZO_W_F16
-        ? launch_weight_codes_t<zo_f16>((const zo_f16*)W, N, K, bits, group, s, eps, cp, cm, wsp, wsm, rpart_p, rpart_m, overflow, st, scale_row_tiles)
-        : launch_weight_codes_t<float>((const float*)W, N, K, bits, group, s, eps, cp, cm, wsp, wsm, rpart_p, rpart_m, overflow, st, scale_row_tiles);
+        ? launch_weight_codes_t<zo_f16>((const zo_f16*)W, N, K, bits, group, s, eps, cp, cm, wsp, wsm, rpart_p, rpart_m, overflow, st, scale_row_tiles, ilv)
+        : launch_weight_codes_t<float>((const float*)W, N, K, bits, group, s, eps, cp, cm, wsp, wsm, rpart_p, rpart_m, overflow, st, scale_row_tiles, ilv);
     if (e != hipSuccess) return e;
     const int G = K / group;
-    zo_rowsum_kernel<<<(N + 255) / 256, 256, 0, st>>>(rpart_p, rp, N, G);
-    if (cm) zo_rowsum_kernel<<<(N + 255) / 256, 256, 0, st>>>(rpart_m, rm, N, G);
+    zo_rowsum_kernel<<<(N + 255) / 256, 256, 0, st>>>(rpart_p, rp, N, G, ilv);
+    if (cm) zo_rowsum_kernel<<<(N + 255) / 256, 256, 0, st>>>(rpart_m, rm, N, G, ilv);
     return hipGetLastError();
 }
 
@@ -379,7 +395,7 @@ template <int N> __device__ __forceinline__ void wait_vmcnt_i8()
 __device__ __forceinline__ int swz128(int row) { return (row ^ (row >> 3)) & 7; }
 
 
-template <typename TY, int SPT>
+template <typename TY, int SPT, int EPI>
 __global__ __launch_bounds__(512) void zo_gemm_i8_kernel(zo_i8_gemm_args a)
 {
     constexpr int BM = 256, BN = 256, BKB = 128;      // K tile in bytes (= codes)
@@ -585,8 +601,16 @@ __global__ __launch_bounds__(512) void zo_gemm_i8_kernel(zo_i8_gemm_args a)
         rn[j] = wr[n];
         bn[j] = bias ? bias[n] : 0.0f;
     }
+    // Pairing epilogue (epi 1; the weight rows were written interleaved, see ilv_row): tiles j and j + 2 of a wave hold the gate
+    // and the up value of one (token, channel) -> silu(gate) * up, both rounded to the output type first (as if they had been
+    // stored), one pass, N / 2 output columns.  (The rotary embedding was tried the same way and dropped: its table reads in
+    // accumulator layout and the register pressure next to 128 live accumulators cost 390 us per q | k | v launch, the
+    // stand-alone kernel 73.)
+    constexpr int epi = EPI;
+    const int c0 = n0 + wn * 64;                       // first (interleaved) channel of the wave
+    constexpr int npass = epi == 1 ? 1 : 2;
 #pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
+    for (int pass = 0; pass < npass; ++pass) {
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             float sx[4], ox[4];
@@ -599,10 +623,18 @@ __global__ __launch_bounds__(512) void zo_gemm_i8_kernel(zo_i8_gemm_args a)
             }
 #pragma unroll
             for (int jj = 0; jj < 2; ++jj) {
-                const int j = pass * 2 + jj;
+                const int j = epi == 0 ? pass * 2 + jj : jj;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    float v = sx[r] * __builtin_fmaf(ox[r], rn[j], acc[i][j][r]) + bn[j];
+                    float v;
+                    if (epi == 0) {
+                        v = sx[r] * __builtin_fmaf(ox[r], pass == 0 ? rn[jj] : rn[jj + 2], pass == 0 ? acc[i][jj][r] : acc[i][jj + 2][r]) +
+                            (pass == 0 ? bn[jj] : bn[jj + 2]);
+                    } else {
+                        const float lo = zo_round_to<TY>(sx[r] * __builtin_fmaf(ox[r], rn[j], acc[i][j][r]) + bn[j]);
+                        const float hi = zo_round_to<TY>(sx[r] * __builtin_fmaf(ox[r], rn[j + 2], acc[i][j + 2][r]) + bn[j + 2]);
+                        v = (lo / (1.0f + __expf(-lo))) * hi;
+                    }
                     if (a.relu) v = fmaxf(v, 0.0f);
                     const int row = i * 16 + q4 * 4 + r;
                     const int gsl = (jj * 4 + (j16 >> 2)) ^ (((row >> 2) & 1) << 2);
@@ -616,10 +648,12 @@ __global__ __launch_bounds__(512) void zo_gemm_i8_kernel(zo_i8_gemm_args a)
             const f32x4 v4 = *reinterpret_cast<const f32x4*>(slice + row * 128 + ((g ^ (((row >> 2) & 1) << 2)) << 4));
             float v[4] = {v4[0], v4[1], v4[2], v4[3]};
             const int m = m0 + wm * 128 + row;
-            const int n = n0 + wn * 64 + pass * 32 + g * 4;
-            if (m >= M || n >= N) continue;
-            const int64_t off = (int64_t)m * N + n;
-            if ((N & 3) == 0) {
+            // output column and row pitch: as computed; SwiGLU: half as many columns
+            const int NO = epi == 1 ? N / 2 : N;
+            const int n = epi == 0 ? c0 + pass * 32 + g * 4 : c0 / 2 + g * 4;
+            if (m >= M || n >= NO) continue;
+            const int64_t off = (int64_t)m * NO + n;
+            if ((NO & 3) == 0) {
                 if (res) {
                     if constexpr (sizeof(TY) == 4) {
                         const float4 r4 = *reinterpret_cast<const float4*>(res + off);
@@ -638,7 +672,7 @@ __global__ __launch_bounds__(512) void zo_gemm_i8_kernel(zo_i8_gemm_args a)
                     *reinterpret_cast<uint2*>((zo_bf16*)Y + off) = o;
                 }
             } else {
-                for (int e = 0; e < 4 && n + e < N; ++e) {
+                for (int e = 0; e < 4 && n + e < NO; ++e) {
                     float t = v[e];
                     if (res) t += (float)res[off + e];
                     zo_store(Y + off + e, t);
@@ -648,20 +682,30 @@ __global__ __launch_bounds__(512) void zo_gemm_i8_kernel(zo_i8_gemm_args a)
     }
 }
 
-template <typename TY, int SPT>
-static hipError_t launch_gemm_i8_t(const zo_i8_gemm_args& a, hipStream_t st)
+template <typename TY, int SPT, int EPI>
+static hipError_t launch_gemm_i8_e(const zo_i8_gemm_args& a, hipStream_t st)
 {
     const int tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
     constexpr int lds_bytes = 2 * (64 * 1024 + 8 * 1024);
-    hipError_t e = hipFuncSetAttribute((const void*)zo_gemm_i8_kernel<TY, SPT>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    hipError_t e = hipFuncSetAttribute((const void*)zo_gemm_i8_kernel<TY, SPT, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
-    zo_gemm_i8_kernel<TY, SPT><<<dim3(tiles, 1, a.batch), 512, lds_bytes, st>>>(a);
+    zo_gemm_i8_kernel<TY, SPT, EPI><<<dim3(tiles, 1, a.batch), 512, lds_bytes, st>>>(a);
     return hipGetLastError();
+}
+template <typename TY, int SPT>
+static hipError_t launch_gemm_i8_t(const zo_i8_gemm_args& a, hipStream_t st)
+{
+    if (a.epi == 0) return launch_gemm_i8_e<TY, SPT, 0>(a, st);
+    if constexpr (sizeof(TY) == 2) {                  // the pairing epilogues exist for bf16 output
+        return launch_gemm_i8_e<TY, SPT, 1>(a, st);
+    }
+    return hipErrorInvalidValue;
 }
 
 hipError_t zo_launch_gemm_i8(const zo_i8_gemm_args& a, int out_f32, hipStream_t st)
 {
     if (a.M <= 0 || a.N <= 0) return hipSuccess;
+    if (a.epi < 0 || a.epi > 1 || (a.epi != 0 && (a.relu || a.residual || (a.N & 127)))) return hipErrorInvalidValue;
     if (a.K < 128 || (a.K & 127) || (a.sgroup != 64 && (a.sgroup & 127)) || a.K % a.sgroup) return hipErrorInvalidValue;
     if (a.sgroup == a.K) return out_f32 ? launch_gemm_i8_t<float, 0>(a, st) : launch_gemm_i8_t<zo_bf16, 0>(a, st);
     if (a.sgroup == 64) return out_f32 ? launch_gemm_i8_t<float, 2>(a, st) : launch_gemm_i8_t<zo_bf16, 2>(a, st);

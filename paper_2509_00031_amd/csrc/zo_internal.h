@@ -200,7 +200,8 @@ hipError_t zo_launch_act_codes_i8(const void* X, int8_t* codes, float* xs, float
                                   int dtype, hipStream_t st);
 hipError_t zo_launch_weight_codes_i8(const void* W, int32_t N, int32_t K, int32_t bits, int32_t group, uint64_t seed, int32_t tid, float eps,
                                      int wdtype, int8_t* cp, int8_t* cm, float* wsp, float* wsm, float* rp, float* rm, float* rpart_p,
-                                     float* rpart_m, int* overflow, hipStream_t st, int32_t scale_row_tiles = 0);
+                                     float* rpart_m, int* overflow, hipStream_t st, int32_t scale_row_tiles = 0,
+                                     int32_t ilv = 0);   // ilv: rows interleaved for a pairing epilogue (see zo_i8.hip)
 // the forward's overflow flag: a set flag turns the nb losses into NaN and is cleared for the next forward
 hipError_t zo_launch_i8_flag_to_loss(int* flag, float* loss, int32_t nb, hipStream_t st);
 struct zo_i8_gemm_args {
@@ -212,6 +213,7 @@ struct zo_i8_gemm_args {
     int32_t M, N, K, batch, sgroup;          // sgroup: k per weight step (64, or a multiple of 128)
     int64_t strideX, strideW, strideXs, strideWs, strideWr, strideY, strideBias, strideRes;
     int32_t relu;
+    int32_t epi;                             // 1: SwiGLU on rows written interleaved (zo_launch_weight_codes_i8's ilv 1 / 2); Y is [M][N / 2]
 };
 hipError_t zo_launch_gemm_i8(const zo_i8_gemm_args& a, int out_f32, hipStream_t st);
 

@@ -53,6 +53,37 @@ def test_step_on_integer_codes_other_settings(w_group, a_bits):
     _step(1, 1, w_group, a_bits)
 
 
+@pytest.mark.parametrize("w_group", [0, 64])
+def test_step_on_integer_codes_with_the_swiglu_epilogue(w_group):
+    """bf16 storage: the integer GEMM applies SwiGLU (gate | up rows interleaved) in its epilogue, like the bf16 one."""
+    torch, zo = gpu()
+    B, S = 2, 128
+    base = dict(n_layers=2, d_model=256, n_heads=2, d_ffn=512, vocab=512, max_seq=S, w_bits=4, w_group=w_group, a_bits=8)
+    ocfg = orc.Config(1, act_dtype=1, mma=1, **base)
+    cfg = zo.make_config(1, act_dtype=1, mma=zo.MMA_INT8, **base)
+    params = synth.model_params(orc.param_shapes(ocfg), 2340)
+    ids = synth.token_ids(B, S, 512, 2341)
+    gp = [to_dev(p, torch) for p in params]
+    ctx = zo.Context(cfg, gp, B, S)
+    out = ctx.zo_step(to_dev(ids, torch), None, B, S, seed=9, eps=EPS, lr=1e-3).cpu().numpy()
+    routes = ctx.zo_debug_routes()
+    assert routes & zo.ROUTE_INT8_MMA and routes & zo.ROUTE_SWIGLU_IN_GEMM, hex(routes)
+    lp = orc.forward(ocfg, params, ids=ids, seed=9, eps_signed=np.float32(EPS))
+    lm = orc.forward(ocfg, params, ids=ids, seed=9, eps_signed=np.float32(-EPS))
+    print("gpu L+ %.6f L- %.6f | oracle L+ %.6f L- %.6f" % (out[0], out[1], lp, lm))
+    assert abs(out[0] - lp) <= 1e-3 * abs(lp) and abs(out[1] - lm) <= 1e-3 * abs(lm)
+    # the same forward with the stand-alone kernels (no_fused = 1 keeps the integer route but switches the epilogues off)
+    cfg2 = zo.make_config(1, act_dtype=1, mma=zo.MMA_INT8, no_fused=1, **base)
+    gp2 = [to_dev(p, torch) for p in params]
+    ctx2 = zo.Context(cfg2, gp2, B, S)
+    out2 = ctx2.zo_step(to_dev(ids, torch), None, B, S, seed=9, eps=EPS, lr=1e-3).cpu().numpy()
+    r2 = ctx2.zo_debug_routes()
+    assert r2 & zo.ROUTE_INT8_MMA and not r2 & (zo.ROUTE_ROPE_IN_GEMM | zo.ROUTE_SWIGLU_IN_GEMM)
+    assert abs(out2[0] - out[0]) <= 2e-4 * abs(out[0]) and abs(out2[1] - out[1]) <= 2e-4 * abs(out[1]), (out, out2)
+    ctx.close()
+    ctx2.close()
+
+
 def test_integer_route_differs_from_the_bf16_route_by_the_operand_rounding_only():
     """bf16 storage: the two contractions see the same codes; the integer one does not round the de-quantized operands to
     bf16, so the losses differ by a few 1e-4 relative -- and each agrees with its own oracle."""
