@@ -457,7 +457,6 @@ struct fwd {
         if (cfg.no_fused || cfg.arch != ZO_ARCH_LLAMA || cfg.learn_smooth) return false;      // smoothing gives these linears a bias
         if (cfg.d_model / cfg.n_heads != 128 || fused_ok(t_q, true)) return false;
         if (i8_route(t_q)) return false;                 // (measured slower in the integer GEMM's epilogue than stand-alone)
-        if (cfg.w_bits != 0 && !cfg.learn_clip && (cfg.w_group == 0 || cfg.w_group > 512)) return false;
         return zo_gemm_rope_supported(M, 3 * cfg.d_model, cfg.d_model, dt());
     }
     bool swiglu_in_gemm(int t_gate) const
@@ -466,7 +465,6 @@ struct fwd {
         if (cfg.no_fused || cfg.arch != ZO_ARCH_LLAMA || cfg.learn_smooth) return false;      // smoothing gives these linears a bias
         if ((cfg.d_ffn & 31) || fused_ok(t_gate, true) || fused_ok(t_gate + 1, true)) return false;
         if (i8_route(t_gate)) return dt() == ZO_T_BF16;              // the integer GEMM has the same epilogue (bf16 output)
-        if (cfg.w_bits != 0 && !cfg.learn_clip && (cfg.w_group == 0 || cfg.w_group > 512)) return false;
         return zo_gemm_swiglu_supported(M, 2 * cfg.d_ffn, cfg.d_model, dt());
     }
     // Eq. 4, activation side of the linears whose input is smoothed by the pair carried by linear `t`:

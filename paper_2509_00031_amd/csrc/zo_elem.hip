@@ -404,31 +404,45 @@ __global__ __launch_bounds__(256) void zo_fq_weight_kernel(const TW* __restrict_
     }
 }
 
-// Groups wider than 512 elements (per-channel quantization): one workgroup per output channel,
-// two sweeps over the row (range, then codes); the stream is regenerated in the second sweep.
-template <typename TW, typename TO, bool DEBUG>
+// Groups wider than 512 elements (per-channel quantization): one workgroup per group, two sweeps over it (range, then
+// codes).  NB > 0: a thread's (at most NB) blocks of 8 weights and their perturbations stay in registers between the sweeps
+// (groups of up to 2048 NB weights), so the stream is generated once; NB = 0: any group length, stream generated twice.
+// The rows may go out interleaved for the GEMM epilogues (ilv, see interleaved_block).
+template <typename TW, typename TO, bool DEBUG, int NB>
 __global__ __launch_bounds__(256) void zo_fq_weight_row_kernel(const TW* __restrict__ W, int K, int group, zo_stream s,
                                                                float eps, int bits, TO* __restrict__ out_p, TO* __restrict__ out_m,
-                                                               uint8_t* codes, float* step, int32_t* zp)
+                                                               uint8_t* codes, float* step, int32_t* zp, zo_rowdiv kb, int ilv)
 {
     __shared__ float red[4][4];
+    constexpr int HELD = NB > 0 ? NB : 1;
     const int64_t grp = blockIdx.x;                 // group index over the whole matrix
     const int64_t b0 = grp * (group / 8);           // first Philox block of the group
     const int nb = group / 8;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    float mnp = INFINITY, mxp = -INFINITY, mnm = INFINITY, mxm = -INFINITY;
-    for (int j = threadIdx.x; j < nb; j += 256) {
-        float w[8], z[8];
+    const int sweeps = NB > 0 ? NB : (nb + 255) / 256;
+    float wv[HELD][8], zv[HELD][8];
+    auto fetch = [&](int j, float (&w)[8], float (&z)[8]) {
         zo_load8(W + 8 * (b0 + j), w);
         if (eps != 0.0f) zo_z8(s, (uint64_t)(b0 + j), z);
         else {
 #pragma unroll
             for (int i = 0; i < 8; ++i) z[i] = 0.0f;
         }
+    };
+    float mnp = INFINITY, mxp = -INFINITY, mnm = INFINITY, mxm = -INFINITY;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            float vp = __builtin_fmaf(eps, z[i], w[i]), vm = __builtin_fmaf(-eps, z[i], w[i]);
-            mnp = fminf(mnp, vp); mxp = fmaxf(mxp, vp); mnm = fminf(mnm, vm); mxm = fmaxf(mxm, vm);
+    for (int u = 0; u < sweeps; ++u) {
+        const int j = threadIdx.x + 256 * u;
+        if (j < nb) {
+            float wl[8], zl[8];
+            float (&w)[8] = NB > 0 ? wv[NB > 0 ? u : 0] : wl;
+            float (&z)[8] = NB > 0 ? zv[NB > 0 ? u : 0] : zl;
+            fetch(j, w, z);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                float vp = __builtin_fmaf(eps, z[i], w[i]), vm = __builtin_fmaf(-eps, z[i], w[i]);
+                mnp = fminf(mnp, vp); mxp = fmaxf(mxp, vp); mnm = fminf(mnm, vm); mxm = fmaxf(mxm, vm);
+            }
         }
     }
     mnp = zo_group_min<64>(mnp); mxp = zo_group_max<64>(mxp);
@@ -444,27 +458,29 @@ __global__ __launch_bounds__(256) void zo_fq_weight_row_kernel(const TW* __restr
         if (step) step[grp] = qp.step;
         if (zp) zp[grp] = (int32_t)qp.zp;
     }
-    for (int j = threadIdx.x; j < nb; j += 256) {
-        float w[8], z[8], o[8];
-        zo_load8(W + 8 * (b0 + j), w);
-        if (eps != 0.0f) zo_z8(s, (uint64_t)(b0 + j), z);
-        else {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) z[i] = 0.0f;
-        }
-        if (out_p || DEBUG) {
+    for (int u = 0; u < sweeps; ++u) {
+        const int j = threadIdx.x + 256 * u;
+        if (j < nb) {
+            float wl[8], zl[8], o[8];
+            float (&w)[8] = NB > 0 ? wv[NB > 0 ? u : 0] : wl;
+            float (&z)[8] = NB > 0 ? zv[NB > 0 ? u : 0] : zl;
+            if (NB == 0) fetch(j, w, z);
+            const int64_t ob = interleaved_block(b0 + j, kb, ilv);
+            if (out_p || DEBUG) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                float c = zo_code(qp, __builtin_fmaf(eps, z[i], w[i]));
-                o[i] = zo_dequant(qp, c);
-                if (DEBUG && codes) codes[8 * (b0 + j) + i] = (uint8_t)c;
+                for (int i = 0; i < 8; ++i) {
+                    float c = zo_code(qp, __builtin_fmaf(eps, z[i], w[i]));
+                    o[i] = zo_dequant(qp, c);
+                    if (DEBUG && codes) codes[8 * (b0 + j) + i] = (uint8_t)c;
+                }
+                if (out_p) zo_store8(out_p + 8 * ob, o);
             }
-            if (out_p) zo_store8(out_p + 8 * (b0 + j), o);
-        }
-        if (out_m) {
+            if (out_m) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) o[i] = zo_dequant(qm, zo_code(qm, __builtin_fmaf(-eps, z[i], w[i])));
-            zo_store8(out_m + 8 * (b0 + j), o);
+                for (int i = 0; i < 8; ++i) o[i] = zo_dequant(qm, zo_code(qm, __builtin_fmaf(-eps, z[i], w[i])));
+                zo_store8(out_m + 8 * ob, o);
+            }
         }
     }
 }
@@ -498,7 +514,7 @@ static hipError_t launch_fq_weight_t(const TW* W, int32_t N, int32_t K, int32_t 
                                      TO* op, TO* om, uint8_t* codes, float* step, int32_t* zp, hipStream_t st, int ilv)
 {
     const int kb = K / 8;
-    if (ilv != 0 && ((N & (ilv == 3 ? 127 : 31)) || (bits != 0 && (group ? group : K) > 512))) return hipErrorInvalidValue;
+    if (ilv != 0 && (N & (ilv == 3 ? 127 : 31))) return hipErrorInvalidValue;
     const int64_t nblk = (int64_t)N * K / 8;
     if (nblk == 0) return hipSuccess;
     if (bits == 0) return launch_fq_weight_gl<TW, TO, 1>(W, nblk, s, eps, 0, op, om, nullptr, nullptr, nullptr, st, kb, ilv);
@@ -517,11 +533,15 @@ static hipError_t launch_fq_weight_t(const TW* W, int32_t N, int32_t K, int32_t 
         }
     }
     const int64_t ngroups = (int64_t)N * (K / group);
-    if (ngroups > 0x7FFFFFFF) return hipErrorInvalidValue;
-    if (codes || step || zp)
-        zo_fq_weight_row_kernel<TW, TO, true><<<(int)ngroups, 256, 0, st>>>(W, K, group, s, eps, bits, op, om, codes, step, zp);
-    else
-        zo_fq_weight_row_kernel<TW, TO, false><<<(int)ngroups, 256, 0, st>>>(W, K, group, s, eps, bits, op, om, nullptr, nullptr, nullptr);
+    if (ngroups > 0x7FFFFFFF || (ilv != 0 && nblk >= ((int64_t)1 << 31))) return hipErrorInvalidValue;
+    const zo_rowdiv rd = make_rowdiv(kb);
+    if (codes || step || zp) {
+        zo_fq_weight_row_kernel<TW, TO, true, 0><<<(int)ngroups, 256, 0, st>>>(W, K, group, s, eps, bits, op, om, codes, step, zp, rd, ilv);
+        return hipGetLastError();
+    }
+#define ZO_ROWFQ(NB) zo_fq_weight_row_kernel<TW, TO, false, NB><<<(int)ngroups, 256, 0, st>>>(W, K, group, s, eps, bits, op, om, nullptr, nullptr, nullptr, rd, ilv)
+    if (group <= 4096) ZO_ROWFQ(2); else if (group <= 8192) ZO_ROWFQ(4); else if (group <= 12288) ZO_ROWFQ(6); else if (group <= 16384) ZO_ROWFQ(8); else ZO_ROWFQ(0);
+#undef ZO_ROWFQ
     return hipGetLastError();
 }
 

@@ -22,11 +22,11 @@ def _row_rel(a, b):
     return np.linalg.norm(a.astype(np.float64) - b, axis=1) / np.maximum(np.linalg.norm(b, axis=1), 1e-30)
 
 
-def _one_layer_step(arch, S, routes_want, lightweight=0, lr=1e-3, loss_tol=1e-3, **kw):
+def _one_layer_step(arch, S, routes_want, lightweight=0, lr=1e-3, loss_tol=1e-3, mma=0, **kw):
     torch, zo = gpu()
     base = dict(n_layers=1, max_seq=S, **kw)
-    ocfg = orc.Config(arch, act_dtype=1, lightweight=lightweight, **base)
-    cfg = zo.make_config(arch, act_dtype=1, lightweight=lightweight, **base)
+    ocfg = orc.Config(arch, act_dtype=1, lightweight=lightweight, mma=mma, **base)
+    cfg = zo.make_config(arch, act_dtype=1, lightweight=lightweight, mma=mma, **base)
     shapes = orc.param_shapes(ocfg)
     params = synth.model_params(shapes, 1234)
     ids = synth.token_ids(1, S, kw["vocab"], 5678)
@@ -82,6 +82,16 @@ def test_llama7b_widths_one_layer(w_bits, a_bits):
     torch, zo = gpu()
     _one_layer_step(1, 1024, zo.ROUTE_SWIGLU_IN_GEMM | zo.ROUTE_ROPE_IN_GEMM | zo.ROUTE_CE_IN_GEMM,
                     d_model=4096, n_heads=32, d_ffn=11008, vocab=32000, w_bits=w_bits, w_group=64, a_bits=a_bits)
+
+
+@pytest.mark.parametrize("mma", [0, 1])
+def test_llama7b_widths_one_layer_per_channel(mma):
+    """Per-channel weight steps (the weight setting of the W4A4 rows of the appendix's quantization settings) at the 7B widths:
+    through the bf16 contraction (row quantizer with interleaved outputs, all three GEMM epilogues) and through the integer
+    route (codes, integer accumulation over all of K, SwiGLU in the integer GEMM's epilogue, stand-alone rotary kernel)."""
+    torch, zo = gpu()
+    routes = zo.ROUTE_SWIGLU_IN_GEMM | zo.ROUTE_CE_IN_GEMM | (zo.ROUTE_INT8_MMA if mma else zo.ROUTE_ROPE_IN_GEMM)
+    _one_layer_step(1, 1024, routes, mma=mma, d_model=4096, n_heads=32, d_ffn=11008, vocab=32000, w_bits=4, w_group=0, a_bits=8)
 
 
 def test_opt1p3b_widths_one_layer():
